@@ -1,0 +1,183 @@
+/*
+ * pop.h -- C boundary of the population update engine (gfx950 / MI355X).
+ *
+ * The library carries out what Sec. 4.1 of "Fast Population-Based Reinforcement
+ * Learning on a Single Machine" speeds up: ONE gradient-update step applied at
+ * once to a population of P independent off-policy agents (TD3).  Every agent
+ * owns its MLP actor, twin critics, the three target copies, Adam moments,
+ * hyperparameters, seed and replay buffer; agents never exchange anything.
+ *
+ * Conventions for every call
+ *   - Return value: POP_OK (0) or a negative POP_E* code.  Nothing throws or
+ *     aborts across this boundary.  pop_last_error() gives a readable message
+ *     for the last failing call on that context (or for a failing pop_create
+ *     when passed NULL).
+ *   - Argument checks run on the host before anything is launched; a failing
+ *     call launches nothing and writes nothing.
+ *   - "device pointer" = HIP device memory of the GPU that was current at
+ *     pop_create; "host pointer" = ordinary host memory.  The caller owns every
+ *     pointer it passes, including the workspace and the stream; the library
+ *     allocates no device memory and frees nothing of the caller's.
+ *   - All work is enqueued on the stream given to pop_create.  pop_update and
+ *     calls with device pointers are asynchronous; calls that take or fill host
+ *     pointers synchronise that stream before returning.
+ *   - Shapes are row-major, the population index first (App. A of the paper:
+ *     the agents' batches are stacked on a new leading axis; App. C: weights
+ *     are [P, in, out], biases [P, 1, out]).
+ */
+#ifndef POP_H
+#define POP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pop_ctx pop_ctx; /* opaque; host memory owned by the library */
+
+enum {
+  POP_OK = 0,
+  POP_EINVAL = -1,       /* bad argument (NULL, out of range, wrong length) */
+  POP_ENOMEM = -2,       /* workspace smaller than pop_workspace_bytes() */
+  POP_EEMPTY = -3,       /* pop_update while some agent's buffer is empty */
+  POP_EHIP = -4,         /* a HIP runtime call failed; see pop_last_error() */
+  POP_EUNSUPPORTED = -5  /* shape or algorithm the kernels do not cover */
+};
+
+enum { POP_ALGO_TD3 = 0, POP_ALGO_SAC = 1 };
+
+/* Per-agent hyperparameters (Sec. 4.1: replicas differ in initial weights and
+ * hyperparameters; App. B.1 lists the ones a population tunes).  Read at
+ * pop_create and copied. */
+typedef struct {
+  uint64_t seed;        /* key of every random draw of this agent (initial
+                           weights, replay sampling, smoothing noise).  0 means
+                           "derive from the population seed and the index". */
+  float lr_actor, lr_critic;
+  float gamma;          /* discount */
+  float tau;            /* Polyak rate of the target networks */
+  float policy_noise;   /* std of the target-policy smoothing noise */
+  float noise_clip;     /* clip of that noise */
+  int32_t policy_delay; /* actor and targets are updated when step % delay == 0 */
+  float adam_b1, adam_b2, adam_eps;
+  float lr_alpha, target_entropy, init_log_alpha; /* SAC only; ignored for TD3 */
+  int32_t reserved_;    /* keeps sizeof == 64 */
+} pop_hparams;
+
+/* Population-wide shapes.  Supported now: algo TD3, n_hidden == 2 with
+ * hidden = {256, 256}, obs_dim + act_dim <= 64, act_dim <= 8, batch a
+ * multiple of 32 in [32, 1024], 1 <= capacity < 2^32.  Anything else gives
+ * POP_EUNSUPPORTED. */
+typedef struct {
+  int32_t algo;
+  int32_t P;
+  int32_t obs_dim, act_dim;
+  int32_t n_hidden;
+  int32_t hidden[4];
+  int32_t batch;
+  int64_t capacity;     /* replay rows per agent */
+} pop_config;
+
+/* Which tensor pop_get_params returns.  Networks come in the canonical flat
+ * order: layer by layer, W[in, out] row-major then b[out] (App. C layout of
+ * one population member).  Critic input is concat(obs, act). */
+enum {
+  POP_ACTOR = 0, POP_CRITIC1 = 1, POP_CRITIC2 = 2,
+  POP_T_ACTOR = 3, POP_T_CRITIC1 = 4, POP_T_CRITIC2 = 5,
+  POP_ADAM_M_ACTOR = 6, POP_ADAM_M_CRITIC1 = 7, POP_ADAM_M_CRITIC2 = 8,
+  POP_ADAM_V_ACTOR = 9, POP_ADAM_V_CRITIC1 = 10, POP_ADAM_V_CRITIC2 = 11,
+  /* gradients of the last step that updated that network; only recorded
+   * while pop_set_debug(ctx, 1) is on */
+  POP_GRAD_ACTOR = 12, POP_GRAD_CRITIC1 = 13, POP_GRAD_CRITIC2 = 14
+};
+
+/* What pop_debug_get returns (state of the most recent update step). */
+enum {
+  POP_DBG_INDICES = 0,       /* uint32 [P, batch]: replay rows sampled */
+  POP_DBG_BATCH = 1,         /* float  [P, batch, 2*obs+act+2]: rows as stored:
+                                obs, act, reward, done, next_obs */
+  POP_DBG_TARGET_ACTION = 2, /* float  [P, batch, act]: smoothed target action */
+  POP_DBG_TARGET_Y = 3,      /* float  [P, batch]: Bellman target */
+  POP_DBG_LOSSES = 4         /* float  [P, 2]: critic loss, actor loss (the
+                                actor loss of the last step that had one) */
+};
+
+/* Bytes of device workspace a population of this shape needs (replay buffers
+ * included), or a negative POP_E* code. */
+int64_t pop_workspace_bytes(const pop_config* cfg);
+
+/* Number of floats of one network in canonical order: which = POP_ACTOR or
+ * any critic code.  Negative POP_E* code on bad arguments. */
+int64_t pop_net_size(const pop_config* cfg, int32_t which);
+
+/* Create a population (Sec. 4.1: N replicas with different initial weights
+ * and hyperparameters).  Weights are Glorot-uniform from each agent's seed,
+ * biases 0, targets exact copies, Adam moments 0, step counter 0, buffers
+ * empty.  `hp` is a host array of P entries.  `workspace` is a device
+ * pointer, 256-byte aligned, of at least pop_workspace_bytes(cfg) bytes that
+ * must stay valid until pop_destroy.  `hip_stream` is a hipStream_t (NULL =
+ * the default stream).  Initialisation is enqueued on that stream. */
+int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp,
+               uint64_t seed, void* workspace, int64_t workspace_bytes,
+               void* hip_stream);
+
+/* Append n transitions to the replay buffer(s) in arrival order; once a
+ * buffer is full the oldest rows are overwritten (Sec. 1 / App. A: bounded
+ * first-in-first-out buffer, one per agent).  agent >= 0: arrays are
+ * obs[n, obs_dim], act[n, act_dim], rew[n], done[n] (0 or 1), next_obs[n,
+ * obs_dim] for that agent.  agent == -1: every array has a leading P axis
+ * ([P, n, ...]) and agent i receives slice i.  ptrs_on_device tells whether
+ * the five arrays are device or host pointers (all the same kind). */
+int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs,
+               const float* act, const float* rew, const float* done,
+               const float* next_obs, int32_t ptrs_on_device);
+
+/* Run n_steps update steps for every agent, back to back on the device with
+ * no host synchronisation in between (Sec. 4.1: many update steps chained
+ * without returning parameters to the host).  One step of one agent: sample a
+ * batch from its own buffer, TD3 critic update, and -- when step %
+ * policy_delay == 0 -- actor update and Polyak update of all three targets.
+ * POP_EEMPTY if some agent has no transitions. */
+int pop_update(pop_ctx* ctx, int32_t n_steps);
+
+/* Deterministic actions of every agent's current actor: obs[P, n, obs_dim] ->
+ * act_out[P, n, act_dim] (agent i acts on slice i). */
+int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
+            int32_t ptrs_on_device);
+
+/* Copy one tensor of one agent (see the POP_* codes) into out[out_len];
+ * out_len must be at least the tensor's length, else POP_EINVAL and nothing
+ * is written.  Returns the number of floats written (>= 0) or an error. */
+int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out,
+                       int64_t out_len, int32_t on_device);
+
+/* Record per-parameter gradients for POP_GRAD_* (costs one extra store per
+ * parameter per step).  Off by default. */
+int pop_set_debug(pop_ctx* ctx, int32_t on);
+
+/* Copy a diagnostic array of the last step (POP_DBG_*) into out; out_bytes
+ * must be at least its size.  Returns bytes written or an error. */
+int64_t pop_debug_get(pop_ctx* ctx, int32_t what, void* out, int64_t out_bytes,
+                      int32_t on_device);
+
+/* Replay indices of the last step widened to int64 [P, batch] (host pointer). */
+int pop_debug_indices(pop_ctx* ctx, int64_t* out);
+
+/* Number of update steps taken so far, and rows held by one agent's buffer. */
+int64_t pop_step_count(const pop_ctx* ctx);
+int64_t pop_buffer_count(const pop_ctx* ctx, int32_t agent);
+
+/* Block until everything enqueued by this context has finished; reports
+ * asynchronous kernel errors as POP_EHIP. */
+int pop_sync(pop_ctx* ctx);
+
+/* Free the host-side context (never the workspace). */
+int pop_destroy(pop_ctx* ctx);
+
+const char* pop_last_error(const pop_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POP_H */

@@ -1,0 +1,33 @@
+// Host-side launch wrappers implemented in the kernel source files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "pop_dev.h"
+
+namespace pop {
+
+// parameter initialisation: Glorot-uniform weights of the three online networks
+// of every agent, copied into the targets; limits are computed by the host.
+struct InitLimits { float actor[3], critic[3]; };
+hipError_t launch_init(const PopDev& d, const InitLimits& lim, hipStream_t s);
+
+// replay ring: write n rows per agent starting at cursor (agent < 0: all agents,
+// sources carry a leading population axis), then advance cursor and count.
+hipError_t launch_insert(const PopDev& d, int agent, int64_t n, const float* obs, const float* act,
+                         const float* rew, const float* done, const float* next_obs, hipStream_t s);
+
+// one update step
+hipError_t launch_sample_gather(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t launch_critic(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, hipStream_t s);
+
+// acting: obs[P][n][O] -> act[P][n][A] through the online actors
+hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, hipStream_t s);
+
+// one-time per-process kernel attribute setup (large dynamic LDS)
+hipError_t setup_kernels();
+
+int rows_per_workgroup();
+
+}  // namespace pop

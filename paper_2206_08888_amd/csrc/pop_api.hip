@@ -1,0 +1,424 @@
+// C boundary of the population update engine: argument checking, workspace
+// layout, and the per-step launch schedule.  See include/pop.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/pop.h"
+#include "launch.h"
+
+using namespace pop;
+
+namespace {
+
+constexpr int64_t kAlign = 256;
+constexpr int64_t kStagingBytes = 16ll << 20;
+
+struct Layout {
+  int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
+  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, staging, replay, total;
+  int64_t param_bytes;
+};
+
+int64_t up(int64_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+thread_local std::string g_create_error;
+
+}  // namespace
+
+struct pop_ctx {
+  pop_config cfg;
+  PopDev d;
+  Layout lay;
+  char* ws;
+  hipStream_t stream;
+  std::vector<pop_hparams> hp;
+  std::vector<HpDev> hp_dev;
+  std::vector<uint64_t> count;   // host mirror of the buffer fill levels
+  uint64_t t;                    // update steps taken
+  std::string err;
+};
+
+namespace {
+
+int fail(pop_ctx* ctx, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (ctx) ctx->err = buf; else g_create_error = buf;
+  return code;
+}
+
+#define HIP_TRY(ctx, call)                                                                     \
+  do {                                                                                         \
+    hipError_t e_ = (call);                                                                    \
+    if (e_ != hipSuccess) return fail(ctx, POP_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+int check_config(const pop_config* c, pop_ctx* ctx) {
+  if (!c) return fail(ctx, POP_EINVAL, "config is NULL");
+  if (c->P < 1 || c->obs_dim < 1 || c->act_dim < 1 || c->batch < 1 || c->capacity < 1 || c->n_hidden < 1 ||
+      c->n_hidden > 4)
+    return fail(ctx, POP_EINVAL, "config has a non-positive size");
+  if (c->algo != POP_ALGO_TD3) return fail(ctx, POP_EUNSUPPORTED, "only POP_ALGO_TD3 is implemented");
+  if (c->n_hidden != 2 || c->hidden[0] != kH || c->hidden[1] != kH)
+    return fail(ctx, POP_EUNSUPPORTED, "hidden layers must be {256, 256}");
+  if (c->obs_dim + c->act_dim > kMaxIn) return fail(ctx, POP_EUNSUPPORTED, "obs_dim + act_dim must be <= %d", kMaxIn);
+  if (c->act_dim > kMaxAct) return fail(ctx, POP_EUNSUPPORTED, "act_dim must be <= %d", kMaxAct);
+  if (c->batch % 32 != 0 || c->batch > 1024 || c->batch % rows_per_workgroup() != 0)
+    return fail(ctx, POP_EUNSUPPORTED, "batch must be a multiple of %d, at most 1024", rows_per_workgroup());
+  if (c->capacity > 0xFFFFFFFFll) return fail(ctx, POP_EUNSUPPORTED, "capacity must be below 2^32");
+  if ((int64_t)c->P * c->batch > (1ll << 24)) return fail(ctx, POP_EUNSUPPORTED, "P * batch too large");
+  return POP_OK;
+}
+
+void fill_dims(const pop_config& c, PopDev& d) {
+  std::memset(&d, 0, sizeof d);
+  d.P = c.P; d.O = c.obs_dim; d.A = c.act_dim; d.D = c.obs_dim + c.act_dim; d.B = c.batch;
+  d.row = 2 * c.obs_dim + c.act_dim + 2;
+  d.chunks = c.batch / rows_per_workgroup();
+  d.actor = make_layout(d.O, d.A);
+  d.critic = make_layout(d.D, 1);
+  d.agent_sz = d.actor.padded + 2 * d.critic.padded;
+  d.capacity = (uint64_t)c.capacity;
+}
+
+Layout make_ws_layout(const PopDev& d) {
+  Layout L;
+  int64_t o = 0;
+  auto take = [&](int64_t bytes) { int64_t at = o; o += up(bytes); return at; };
+  const int64_t P = d.P, B = d.B;
+  L.param_bytes = P * (int64_t)d.agent_sz * 4;
+  L.hp = take(P * (int64_t)sizeof(HpDev));
+  L.theta = take(L.param_bytes); L.target = take(L.param_bytes);
+  L.m = take(L.param_bytes); L.v = take(L.param_bytes); L.grad = take(L.param_bytes);
+  L.count = take(P * 4); L.cursor = take(P * 4);
+  L.idx = take(P * B * 4); L.batch = take(P * B * d.row * 4);
+  L.atilde = take(P * B * d.A * 4); L.y = take(P * B * 4);
+  const int64_t act = P * B * kH * 4;
+  L.cH1 = take(2 * act); L.cdZ2 = take(2 * act); L.cdZ1 = take(2 * act);
+  L.aH1 = take(act); L.aH2 = take(act); L.adZ2 = take(act); L.adZ1 = take(act);
+  L.cpart = take(P * 2 * (int64_t)d.chunks * kCPart * 4);
+  L.apart = take(P * (int64_t)d.chunks * kAPart * 4);
+  L.losses = take(P * 4 * 4);
+  L.staging = take(kStagingBytes);
+  L.replay = take(P * (int64_t)d.capacity * d.row * 4);
+  L.total = o;
+  return L;
+}
+
+uint64_t mix64(uint64_t seed, uint64_t i) {   // splitmix64 finaliser of seed + (i + 1) * golden ratio
+  uint64_t z = seed + (i + 1) * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return z ? z : 1;
+}
+
+float glorot_limit(int fan_in, int fan_out) { return sqrtf(6.0f / (float)(fan_in + fan_out)); }
+
+const NetLayout* net_of(const PopDev& d, int which, int* net, int64_t* base_off_bytes, const Layout& L,
+                        int64_t* region) {
+  // which in [0, 15): region = which / 3 for theta, target, m, v, grad in that order
+  static const int order[5] = {0, 1, 2, 3, 4};
+  const int reg = order[which / 3];
+  *net = which % 3;
+  const int64_t regs[5] = {L.theta, L.target, L.m, L.v, L.grad};
+  *region = regs[reg];
+  int64_t off = 0;
+  if (*net >= 1) off += d.actor.padded;
+  if (*net >= 2) off += d.critic.padded;
+  *base_off_bytes = off * 4;
+  return *net == 0 ? &d.actor : &d.critic;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t pop_workspace_bytes(const pop_config* cfg) {
+  int rc = check_config(cfg, nullptr);
+  if (rc != POP_OK) return rc;
+  PopDev d;
+  fill_dims(*cfg, d);
+  return make_ws_layout(d).total;
+}
+
+int64_t pop_net_size(const pop_config* cfg, int32_t which) {
+  int rc = check_config(cfg, nullptr);
+  if (rc != POP_OK) return rc;
+  if (which < 0 || which > POP_GRAD_CRITIC2) return fail(nullptr, POP_EINVAL, "bad tensor code %d", which);
+  PopDev d;
+  fill_dims(*cfg, d);
+  return which % 3 == 0 ? d.actor.size : d.critic.size;
+}
+
+int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint64_t seed, void* workspace,
+               int64_t workspace_bytes, void* hip_stream) {
+  if (!out) return fail(nullptr, POP_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = check_config(cfg, nullptr);
+  if (rc != POP_OK) return rc;
+  if (!hp) return fail(nullptr, POP_EINVAL, "hp is NULL");
+  if (!workspace) return fail(nullptr, POP_EINVAL, "workspace is NULL");
+  if (((uintptr_t)workspace % kAlign) != 0) return fail(nullptr, POP_EINVAL, "workspace must be 256-byte aligned");
+  for (int i = 0; i < cfg->P; ++i) {
+    const pop_hparams& h = hp[i];
+    if (h.policy_delay < 1) return fail(nullptr, POP_EINVAL, "agent %d: policy_delay must be >= 1", i);
+    if (!(h.adam_b1 >= 0.f && h.adam_b1 < 1.f && h.adam_b2 >= 0.f && h.adam_b2 < 1.f && h.adam_eps > 0.f))
+      return fail(nullptr, POP_EINVAL, "agent %d: Adam constants out of range", i);
+    if (!(h.noise_clip >= 0.f) || !(h.policy_noise >= 0.f) || !(h.tau >= 0.f && h.tau <= 1.f))
+      return fail(nullptr, POP_EINVAL, "agent %d: noise or tau out of range", i);
+  }
+  PopDev d;
+  fill_dims(*cfg, d);
+  const Layout L = make_ws_layout(d);
+  if (workspace_bytes < L.total)
+    return fail(nullptr, POP_ENOMEM, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes,
+                (long long)L.total);
+
+  pop_ctx* ctx = new pop_ctx();
+  ctx->cfg = *cfg;
+  ctx->lay = L;
+  ctx->ws = (char*)workspace;
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->t = 0;
+  ctx->hp.assign(hp, hp + cfg->P);
+  ctx->count.assign(cfg->P, 0);
+  ctx->hp_dev.resize(cfg->P);
+  for (int i = 0; i < cfg->P; ++i) {
+    pop_hparams& h = ctx->hp[i];
+    if (h.seed == 0) h.seed = mix64(seed, (uint64_t)i);
+    HpDev& g = ctx->hp_dev[i];
+    std::memset(&g, 0, sizeof g);
+    g.seed_lo = (uint32_t)h.seed; g.seed_hi = (uint32_t)(h.seed >> 32);
+    g.lr_actor = h.lr_actor; g.lr_critic = h.lr_critic; g.gamma = h.gamma; g.tau = h.tau;
+    g.policy_noise = h.policy_noise; g.noise_clip = h.noise_clip; g.policy_delay = h.policy_delay;
+    g.b1 = h.adam_b1; g.b2 = h.adam_b2; g.eps = h.adam_eps;
+  }
+  char* w = ctx->ws;
+  d.theta = (float*)(w + L.theta); d.target = (float*)(w + L.target); d.m = (float*)(w + L.m);
+  d.v = (float*)(w + L.v); d.grad = (float*)(w + L.grad); d.record_grads = 0;
+  d.hp = (const HpDev*)(w + L.hp);
+  d.replay = (float*)(w + L.replay);
+  d.count = (uint32_t*)(w + L.count); d.cursor = (uint32_t*)(w + L.cursor);
+  d.idx = (uint32_t*)(w + L.idx); d.batch = (float*)(w + L.batch);
+  d.atilde = (float*)(w + L.atilde); d.y = (float*)(w + L.y);
+  d.cH1 = (float*)(w + L.cH1); d.cdZ2 = (float*)(w + L.cdZ2); d.cdZ1 = (float*)(w + L.cdZ1);
+  d.aH1 = (float*)(w + L.aH1); d.aH2 = (float*)(w + L.aH2); d.adZ2 = (float*)(w + L.adZ2);
+  d.adZ1 = (float*)(w + L.adZ1);
+  d.cpart = (float*)(w + L.cpart); d.apart = (float*)(w + L.apart); d.losses = (float*)(w + L.losses);
+  ctx->d = d;
+
+  auto bail = [&](hipError_t e, const char* what) {
+    rc = fail(nullptr, POP_EHIP, "%s: %s", what, hipGetErrorString(e));
+    delete ctx;
+    return rc;
+  };
+  hipError_t e;
+  if ((e = setup_kernels()) != hipSuccess) return bail(e, "kernel attribute setup");
+  hipStream_t s = ctx->stream;
+  // everything between the hyperparameters and the staging area starts at zero
+  if ((e = hipMemsetAsync(w, 0, (size_t)L.staging, s)) != hipSuccess) return bail(e, "hipMemsetAsync");
+  if ((e = hipMemcpyAsync(w + L.hp, ctx->hp_dev.data(), sizeof(HpDev) * cfg->P, hipMemcpyHostToDevice, s)) != hipSuccess)
+    return bail(e, "hipMemcpyAsync(hparams)");
+  InitLimits lim;
+  lim.actor[0] = glorot_limit(d.O, kH); lim.actor[1] = glorot_limit(kH, kH); lim.actor[2] = glorot_limit(kH, d.A);
+  lim.critic[0] = glorot_limit(d.D, kH); lim.critic[1] = glorot_limit(kH, kH); lim.critic[2] = glorot_limit(kH, 1);
+  if ((e = launch_init(ctx->d, lim, s)) != hipSuccess) return bail(e, "init kernel");
+  if ((e = hipStreamSynchronize(s)) != hipSuccess) return bail(e, "hipStreamSynchronize");
+  *out = ctx;
+  return POP_OK;
+}
+
+int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs, const float* act, const float* rew,
+               const float* done, const float* next_obs, int32_t ptrs_on_device) {
+  if (!ctx) return POP_EINVAL;
+  if (agent < -1 || agent >= ctx->d.P) return fail(ctx, POP_EINVAL, "agent %d out of range", agent);
+  if (n < 0 || n > 0xFFFFFFFFll) return fail(ctx, POP_EINVAL, "n out of range");
+  if (n == 0) return POP_OK;
+  if (!obs || !act || !rew || !done || !next_obs) return fail(ctx, POP_EINVAL, "NULL transition array");
+  const PopDev& d = ctx->d;
+  hipStream_t s = ctx->stream;
+  auto bump = [&](int a, int64_t k) {
+    ctx->count[a] = std::min<uint64_t>(ctx->count[a] + (uint64_t)k, d.capacity);
+  };
+  if (ptrs_on_device) {
+    HIP_TRY(ctx, launch_insert(d, agent, n, obs, act, rew, done, next_obs, s));
+    if (agent < 0) for (int a = 0; a < d.P; ++a) bump(a, n); else bump(agent, n);
+    return POP_OK;
+  }
+  // host arrays: stage piecewise through the workspace, one agent at a time
+  float* st = (float*)(ctx->ws + ctx->lay.staging);
+  const int64_t rows_per_piece = kStagingBytes / ((int64_t)d.row * 4);
+  const int a_lo = agent < 0 ? 0 : agent, a_hi = agent < 0 ? d.P : agent + 1;
+  for (int a = a_lo; a < a_hi; ++a) {
+    const int64_t slice = agent < 0 ? (int64_t)a * n : 0;
+    for (int64_t off = 0; off < n; off += rows_per_piece) {
+      const int64_t k = std::min(rows_per_piece, n - off);
+      float* s_obs = st;
+      float* s_act = s_obs + k * d.O;
+      float* s_rew = s_act + k * d.A;
+      float* s_done = s_rew + k;
+      float* s_next = s_done + k;
+      const int64_t r = slice + off;
+      HIP_TRY(ctx, hipMemcpyAsync(s_obs, obs + r * d.O, k * d.O * 4, hipMemcpyHostToDevice, s));
+      HIP_TRY(ctx, hipMemcpyAsync(s_act, act + r * d.A, k * d.A * 4, hipMemcpyHostToDevice, s));
+      HIP_TRY(ctx, hipMemcpyAsync(s_rew, rew + r, k * 4, hipMemcpyHostToDevice, s));
+      HIP_TRY(ctx, hipMemcpyAsync(s_done, done + r, k * 4, hipMemcpyHostToDevice, s));
+      HIP_TRY(ctx, hipMemcpyAsync(s_next, next_obs + r * d.O, k * d.O * 4, hipMemcpyHostToDevice, s));
+      HIP_TRY(ctx, launch_insert(d, a, k, s_obs, s_act, s_rew, s_done, s_next, s));
+      HIP_TRY(ctx, hipStreamSynchronize(s));      // the staging area is reused by the next piece
+      bump(a, k);
+    }
+  }
+  return POP_OK;
+}
+
+int pop_update(pop_ctx* ctx, int32_t n_steps) {
+  if (!ctx) return POP_EINVAL;
+  if (n_steps < 0) return fail(ctx, POP_EINVAL, "n_steps is negative");
+  const PopDev& d = ctx->d;
+  for (int a = 0; a < d.P; ++a)
+    if (ctx->count[a] == 0) return fail(ctx, POP_EEMPTY, "agent %d has an empty replay buffer", a);
+  if (ctx->t + (uint64_t)n_steps > 0xFFFFFFFFull) return fail(ctx, POP_EINVAL, "step counter would exceed 2^32");
+  hipStream_t s = ctx->stream;
+  for (int i = 0; i < n_steps; ++i) {
+    const uint32_t t = (uint32_t)ctx->t;
+    HIP_TRY(ctx, launch_sample_gather(d, t, s));
+    HIP_TRY(ctx, launch_target(d, t, s));
+    HIP_TRY(ctx, launch_critic(d, t, s));
+    HIP_TRY(ctx, launch_wgrad_adam(d, t, 0, s));
+    bool any_actor = false;
+    for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
+    if (any_actor) {
+      HIP_TRY(ctx, launch_actor(d, t, s));
+      HIP_TRY(ctx, launch_wgrad_adam(d, t, 1, s));
+    }
+    ctx->t++;
+  }
+  return POP_OK;
+}
+
+int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t ptrs_on_device) {
+  if (!ctx) return POP_EINVAL;
+  if (n < 0) return fail(ctx, POP_EINVAL, "n is negative");
+  if (n == 0) return POP_OK;
+  if (!obs || !act_out) return fail(ctx, POP_EINVAL, "NULL array");
+  const PopDev& d = ctx->d;
+  hipStream_t s = ctx->stream;
+  if (ptrs_on_device) {
+    HIP_TRY(ctx, launch_act(d, obs, n, act_out, s));
+    return POP_OK;
+  }
+  float* st = (float*)(ctx->ws + ctx->lay.staging);
+  const int64_t per_row = (int64_t)d.P * (d.O + d.A) * 4;
+  const int64_t piece = std::max<int64_t>(1, kStagingBytes / per_row);
+  for (int64_t off = 0; off < n; off += piece) {
+    const int k = (int)std::min<int64_t>(piece, n - off);
+    float* s_obs = st;
+    float* s_act = st + (int64_t)d.P * k * d.O;
+    HIP_TRY(ctx, hipMemcpy2DAsync(s_obs, (size_t)k * d.O * 4, obs + off * d.O, (size_t)n * d.O * 4, (size_t)k * d.O * 4,
+                                  d.P, hipMemcpyHostToDevice, s));
+    HIP_TRY(ctx, launch_act(d, s_obs, k, s_act, s));
+    HIP_TRY(ctx, hipMemcpy2DAsync(act_out + off * d.A, (size_t)n * d.A * 4, s_act, (size_t)k * d.A * 4,
+                                  (size_t)k * d.A * 4, d.P, hipMemcpyDeviceToHost, s));
+    HIP_TRY(ctx, hipStreamSynchronize(s));
+  }
+  return POP_OK;
+}
+
+int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, int64_t out_len, int32_t on_device) {
+  if (!ctx) return POP_EINVAL;
+  if (agent < 0 || agent >= ctx->d.P) return fail(ctx, POP_EINVAL, "agent %d out of range", agent);
+  if (which < 0 || which > POP_GRAD_CRITIC2) return fail(ctx, POP_EINVAL, "bad tensor code %d", which);
+  if (!out) return fail(ctx, POP_EINVAL, "out is NULL");
+  int net;
+  int64_t off, region;
+  const NetLayout* L = net_of(ctx->d, which, &net, &off, ctx->lay, &region);
+  if (out_len < L->size) return fail(ctx, POP_EINVAL, "out_len %lld < %d", (long long)out_len, L->size);
+  const char* src = ctx->ws + region + (int64_t)agent * ctx->d.agent_sz * 4 + off;
+  HIP_TRY(ctx, hipMemcpyAsync(out, src, (size_t)L->size * 4, on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
+                              ctx->stream));
+  if (!on_device) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  return L->size;
+}
+
+int pop_set_debug(pop_ctx* ctx, int32_t on) {
+  if (!ctx) return POP_EINVAL;
+  ctx->d.record_grads = on ? 1 : 0;
+  return POP_OK;
+}
+
+int64_t pop_debug_get(pop_ctx* ctx, int32_t what, void* out, int64_t out_bytes, int32_t on_device) {
+  if (!ctx) return POP_EINVAL;
+  if (!out) return fail(ctx, POP_EINVAL, "out is NULL");
+  const PopDev& d = ctx->d;
+  const int64_t PB = (int64_t)d.P * d.B;
+  const char* src = nullptr;
+  int64_t bytes = 0;
+  switch (what) {
+    case POP_DBG_INDICES: src = (const char*)d.idx; bytes = PB * 4; break;
+    case POP_DBG_BATCH: src = (const char*)d.batch; bytes = PB * d.row * 4; break;
+    case POP_DBG_TARGET_ACTION: src = (const char*)d.atilde; bytes = PB * d.A * 4; break;
+    case POP_DBG_TARGET_Y: src = (const char*)d.y; bytes = PB * 4; break;
+    case POP_DBG_LOSSES: bytes = (int64_t)d.P * 2 * 4; break;
+    default: return fail(ctx, POP_EINVAL, "bad debug code %d", what);
+  }
+  if (out_bytes < bytes) return fail(ctx, POP_EINVAL, "out_bytes %lld < %lld", (long long)out_bytes, (long long)bytes);
+  if (what == POP_DBG_LOSSES) {
+    if (on_device) return fail(ctx, POP_EINVAL, "losses are returned to host memory only");
+    std::vector<float> raw((size_t)d.P * 4);
+    HIP_TRY(ctx, hipMemcpyAsync(raw.data(), d.losses, raw.size() * 4, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    float* o = (float*)out;
+    for (int a = 0; a < d.P; ++a) { o[2 * a] = raw[4 * a] + raw[4 * a + 1]; o[2 * a + 1] = raw[4 * a + 2]; }
+    return bytes;
+  }
+  HIP_TRY(ctx, hipMemcpyAsync(out, src, (size_t)bytes, on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
+                              ctx->stream));
+  if (!on_device) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  return bytes;
+}
+
+int pop_debug_indices(pop_ctx* ctx, int64_t* out) {
+  if (!ctx) return POP_EINVAL;
+  if (!out) return fail(ctx, POP_EINVAL, "out is NULL");
+  const int64_t PB = (int64_t)ctx->d.P * ctx->d.B;
+  std::vector<uint32_t> raw((size_t)PB);
+  int64_t rc = pop_debug_get(ctx, POP_DBG_INDICES, raw.data(), PB * 4, 0);
+  if (rc < 0) return (int)rc;
+  for (int64_t i = 0; i < PB; ++i) out[i] = (int64_t)raw[(size_t)i];
+  return POP_OK;
+}
+
+int64_t pop_step_count(const pop_ctx* ctx) { return ctx ? (int64_t)ctx->t : POP_EINVAL; }
+
+int64_t pop_buffer_count(const pop_ctx* ctx, int32_t agent) {
+  if (!ctx || agent < 0 || agent >= ctx->d.P) return POP_EINVAL;
+  return (int64_t)ctx->count[agent];
+}
+
+int pop_sync(pop_ctx* ctx) {
+  if (!ctx) return POP_EINVAL;
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  HIP_TRY(ctx, hipGetLastError());
+  return POP_OK;
+}
+
+int pop_destroy(pop_ctx* ctx) {
+  if (!ctx) return POP_EINVAL;
+  delete ctx;
+  return POP_OK;
+}
+
+const char* pop_last_error(const pop_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,85 @@
+// Device-side view of a population and shared constants.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pop {
+
+constexpr int kH = 256;        // hidden width the kernels are specialised for
+constexpr int kLda = kH + 4;   // LDS row stride of a 256-wide activation tile: 4*odd words, so
+                               // 8 lanes reading 16 B each from 8 consecutive rows hit all 32 banks
+constexpr int kThreads = 256;  // 4 wavefronts of 64 per workgroup in every compute kernel
+constexpr int kMaxIn = 64;     // largest first-layer fan-in (obs_dim + act_dim) held in LDS
+constexpr int kXld = kMaxIn + 4;
+constexpr int kMaxAct = 8;     // largest action dimension
+
+struct HpDev {                 // per-agent hyperparameters as the kernels read them
+  uint32_t seed_lo, seed_hi;
+  float lr_actor, lr_critic, gamma, tau, policy_noise, noise_clip;
+  int32_t policy_delay;
+  float b1, b2, eps;
+  float pad_[4];
+};
+static_assert(sizeof(HpDev) == 64, "HpDev layout");
+
+// Offsets (floats) of the tensors of one network in canonical order.
+struct NetLayout {
+  int in, out;                 // fan-in of layer 1, fan-out of the head
+  int w1, b1, w2, b2, w3, b3;  // offsets
+  int size, padded;            // true length, length rounded up to 64 floats
+};
+
+__host__ __device__ inline NetLayout make_layout(int in, int out) {
+  NetLayout L;
+  L.in = in; L.out = out;
+  L.w1 = 0;            L.b1 = in * kH;
+  L.w2 = L.b1 + kH;    L.b2 = L.w2 + kH * kH;
+  L.w3 = L.b2 + kH;    L.b3 = L.w3 + kH * out;
+  L.size = L.b3 + out; L.padded = (L.size + 63) / 64 * 64;
+  return L;
+}
+
+struct PopDev {
+  int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
+  int chunks;                  // B / rows-per-workgroup of the fused chain kernels
+  NetLayout actor, critic;
+  int agent_sz;                // actor.padded + 2 * critic.padded
+  // parameter state, each [P][agent_sz] = [actor | critic1 | critic2]
+  float *theta, *target, *m, *v, *grad;
+  int record_grads;
+  const HpDev* hp;
+  // replay
+  float* replay;               // [P][capacity][row]
+  uint64_t capacity;
+  uint32_t *count, *cursor;    // [P]
+  // state of the current step
+  uint32_t* idx;               // [P][B]
+  float* batch;                // [P][B][row]
+  float* atilde;               // [P][B][A]
+  float* y;                    // [P][B]
+  // activations handed from the chain kernels to the weight-gradient kernel
+  float *cH1, *cdZ2, *cdZ1;    // [P][2][B][256]
+  float *aH1, *aH2, *adZ2, *adZ1;  // [P][B][256]
+  // per-row-chunk partial sums of the small gradients and of the losses
+  float* cpart;                // [P][2][chunks][kCPart]
+  float* apart;                // [P][chunks][kAPart]
+  float* losses;               // [P][2]
+};
+
+// critic partial record: dW3[256] db3[1] pad[3] db2[256] db1[256] loss[1] pad[3]
+constexpr int kCP_dW3 = 0, kCP_db3 = 256, kCP_db2 = 260, kCP_db1 = 516, kCP_loss = 772, kCPart = 776;
+// actor partial record: dW3[256*kMaxAct] db3[kMaxAct] db2[256] db1[256] loss[1] pad
+constexpr int kAP_dW3 = 0, kAP_db3 = 256 * kMaxAct, kAP_db2 = kAP_db3 + kMaxAct, kAP_db1 = kAP_db2 + 256,
+              kAP_loss = kAP_db1 + 256, kAPart = kAP_loss + 8;
+
+__device__ inline const float* net_ptr(const PopDev& d, const float* base, int agent, int net) {
+  const float* p = base + (size_t)agent * d.agent_sz;
+  if (net >= 1) p += d.actor.padded;
+  if (net >= 2) p += d.critic.padded;
+  return p;
+}
+__device__ inline float* net_ptr(const PopDev& d, float* base, int agent, int net) {
+  return const_cast<float*>(net_ptr(d, (const float*)base, agent, net));
+}
+
+}  // namespace pop

@@ -1,0 +1,199 @@
+"""GPU parity: the HIP library against the CPU oracle on identical seeded inputs,
+through the C boundary.  Tolerances (fp32 path against the fp64 oracle):
+  * replay indices and gathered rows: bit-exact (integer and copy work);
+  * initial parameters: bit-exact (one fp32 rounding on both sides);
+  * gradients: relative L2 <= 1e-5 per network;
+  * parameters: relative L2 per agent and network <= 1e-4 after 1 step and
+    <= 1e-3 after 100 steps."""
+import numpy as np
+import pytest
+
+import paper_2206_08888_amd as pp
+import workloads
+from gpu_common import NETS, ensure_built, make_pair, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    ensure_built()
+
+
+def _compare_state(gpu, orc, agents, tol, label):
+    worst = 0.0
+    for j, i in enumerate(agents):
+        for which in ("actor", "critic1", "critic2", "t_actor", "t_critic1", "t_critic2"):
+            e = rel_l2(gpu.get_params(i, which), orc.get_params(j, which))
+            worst = max(worst, e)
+            assert e <= tol, "%s: agent %d %s rel-L2 %.3e > %.1e" % (label, i, which, e, tol)
+    print("%s: worst parameter rel-L2 %.3e (tol %.1e)" % (label, worst, tol))
+    return worst
+
+
+def test_initial_parameters_are_bit_exact():
+    gpu, orc, agents = make_pair(0, capacity=256, fill=256)
+    for i in agents:
+        for which in ("actor", "critic1", "critic2", "t_actor", "t_critic1", "t_critic2"):
+            a = gpu.get_params(i, which)
+            b = orc.get_params(i, which).astype(np.float32)
+            assert np.array_equal(a, b), (i, which, np.abs(a - b).max())
+        for which in ("m_actor", "v_critic2"):
+            assert not gpu.get_params(i, which).any()
+    gpu.close()
+
+
+def test_indices_and_gathered_rows_are_bit_exact_over_steps():
+    gpu, orc, agents = make_pair(0)
+    for step in range(3):
+        gpu.update(1)
+        orc.update(1)
+        idx = gpu.debug("indices")
+        rows = gpu.debug("batch")
+        for i in agents:
+            ag = orc.agents[i]
+            assert np.array_equal(idx[i].astype(np.int64), ag.last["idx"]), (step, i)
+            assert np.array_equal(rows[i], ag.buffer.rows[ag.last["idx"]]), (step, i)
+    gpu.close()
+
+
+def test_one_step_matches_oracle():
+    gpu, orc, agents = make_pair(0)
+    gpu.set_debug(1)
+    gpu.update(1)
+    orc.update(1)
+    at = gpu.debug("target_action"); y = gpu.debug("target_y"); losses = gpu.debug("losses")
+    for i in agents:
+        ag = orc.agents[i]
+        assert np.abs(at[i] - ag.last["a_tilde"]).max() <= 2e-6
+        assert rel_l2(y[i], ag.last["y"]) <= 1e-5
+        assert abs(losses[i, 0] - ag.last["critic_loss"]) <= 1e-5 * abs(ag.last["critic_loss"])
+        assert abs(losses[i, 1] - ag.last["actor_loss"]) <= 1e-5 * max(1.0, abs(ag.last["actor_loss"]))
+        for net in NETS:
+            g = gpu.get_params(i, "g_" + net); go = orc.get_params(i, "g_" + net)
+            e = rel_l2(g, go)
+            assert e <= 1e-5, "gradient agent %d %s rel-L2 %.3e" % (i, net, e)
+            # exactly-zero gradients (dead units) must be exactly zero on both sides
+            assert np.array_equal(go == 0.0, g == 0.0) or np.mean((go == 0.0) != (g == 0.0)) < 1e-4
+            for mom in ("m_", "v_"):
+                assert rel_l2(gpu.get_params(i, mom + net), orc.get_params(i, mom + net)) <= 2e-5
+    _compare_state(gpu, orc, agents, 1e-4, "config 0, 1 step")
+    gpu.close()
+
+
+def test_two_steps_cover_the_critic_only_branch():
+    gpu, orc, agents = make_pair(0)
+    gpu.update(1); orc.update(1)
+    snap = {(i, w): gpu.get_params(i, w) for i in agents for w in ("actor", "t_actor", "t_critic1", "t_critic2", "m_actor")}
+    gpu.update(1); orc.update(1)
+    for (i, w), before in snap.items():          # delayed step: actor and targets bit-unchanged
+        assert np.array_equal(before, gpu.get_params(i, w)), (i, w)
+    _compare_state(gpu, orc, agents, 1e-4, "config 0, 2 steps")
+    gpu.close()
+
+
+def test_hundred_steps_match_oracle():
+    gpu, orc, agents = make_pair(0)
+    gpu.update(100)
+    orc.update(100)
+    _compare_state(gpu, orc, agents, 1e-3, "config 0, 100 steps")
+    assert gpu.step_count() == 100
+    gpu.close()
+
+
+def test_agent_in_population_equals_agent_alone_bit_for_bit():
+    hps = workloads.hparams(2, 5)                      # per-agent lr, tau, sigma
+    full, _, _ = make_pair(2, P=5, capacity=2000, hps=hps, oracle=False)
+    full.update(4)
+    for i in (0, 3, 4):
+        cfg = pp.make_config(1, 17, 6, (256, 256), 256, 2000)
+        alone = pp.Population(cfg, [hps[i]])
+        for tr in workloads.transition_chunks(2, i, 2000):
+            alone.insert(0, **tr)
+        alone.update(4)
+        for which in pp.PARAM_CODES:
+            if which.startswith("g_"):
+                continue
+            assert np.array_equal(full.get_params(i, which), alone.get_params(0, which)), (i, which)
+        alone.close()
+    full.close()
+
+
+def test_mixed_policy_delays_and_short_buffers():
+    hps = workloads.hparams(2, 3)
+    hps[0]["policy_delay"], hps[1]["policy_delay"], hps[2]["policy_delay"] = 1, 2, 3
+    gpu, orc, agents = make_pair(2, P=3, capacity=500, fill=100, hps=hps)   # count < batch: with replacement
+    gpu.update(7); orc.update(7)
+    _compare_state(gpu, orc, agents, 2e-4, "mixed delays, 7 steps")
+    gpu.close()
+
+
+def test_ring_buffer_wraps_like_the_oracle():
+    cfgd = workloads.CONFIGS[0]
+    hps = workloads.hparams(0, 2)
+    cfg = pp.make_config(2, 17, 6, (256, 256), 256, 1000)
+    gpu = pp.Population(cfg, hps)
+    from oracle import td3
+    orc = td3.Population(hps, 17, 6, [256, 256], 256, 1000)
+    sizes = (300, 900, 1, 2500, 77)                   # wraps, and one insert larger than the ring
+    for i in range(2):
+        for c, n in enumerate(sizes):
+            tr = workloads.transitions(0, i, n, salt=10 + c)
+            gpu.insert(i, **tr); orc.insert(i, **tr)
+        assert gpu.buffer_count(i) == orc.agents[i].buffer.count == 1000
+    gpu.update(1); orc.update(1)
+    rows = gpu.debug("batch"); idx = gpu.debug("indices")
+    for i in range(2):
+        ag = orc.agents[i]
+        assert np.array_equal(idx[i].astype(np.int64), ag.last["idx"])
+        assert np.array_equal(rows[i], ag.buffer.rows[ag.last["idx"]])
+    gpu.close()
+
+
+def test_device_pointer_insert_for_all_agents_matches_host_insert():
+    import torch
+    hps = workloads.hparams(0, 2)
+    cfg = pp.make_config(2, 17, 6, (256, 256), 256, 700)
+    a = pp.Population(cfg, hps); b = pp.Population(cfg, hps)
+    n = 900
+    trs = [workloads.transitions(0, i, n) for i in range(2)]
+    for i in range(2):
+        a.insert(i, **trs[i])
+    stacked = {k: torch.from_numpy(np.stack([trs[0][k], trs[1][k]])).cuda() for k in trs[0]}
+    b.insert(-1, **stacked)
+    a.update(2); b.update(2)
+    assert np.array_equal(a.debug("batch"), b.debug("batch"))
+    for which in ("actor", "critic1", "t_critic2"):
+        assert np.array_equal(a.get_params(1, which), b.get_params(1, which))
+    a.close(); b.close()
+
+
+def test_act_matches_oracle_on_ragged_row_counts():
+    import torch
+    gpu, orc, agents = make_pair(0, capacity=512, fill=512)
+    gpu.update(3); orc.update(3)
+    rng = np.random.default_rng(5)
+    for n in (1, 31, 32, 33, 100):
+        obs = rng.standard_normal((2, n, 17)).astype(np.float32)
+        ref = orc.act(obs.astype(np.float64))
+        got = gpu.act(obs)
+        assert got.shape == (2, n, 6)
+        assert np.abs(got - ref).max() <= 5e-6
+        got_dev = gpu.act(torch.from_numpy(obs).cuda()).cpu().numpy()
+        assert np.array_equal(got, got_dev)
+    gpu.close()
+
+
+def test_errors_from_the_boundary_on_a_live_context():
+    gpu, _, _ = make_pair(0, capacity=256, fill=0, oracle=False)
+    with pytest.raises(pp.PopError) as e:
+        gpu.update(1)
+    assert e.value.code == pp.POP_EEMPTY
+    with pytest.raises(pp.PopError) as e:
+        gpu.get_params(7, "actor")
+    assert e.value.code == pp.POP_EINVAL
+    small = np.empty(10, dtype=np.float32)
+    with pytest.raises(pp.PopError) as e:
+        pp.pop_get_params(gpu.ctx, 0, 0, small)
+    assert e.value.code == pp.POP_EINVAL
+    gpu.close()

@@ -141,6 +141,25 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs,
  * POP_EEMPTY if some agent has no transitions. */
 int pop_update(pop_ctx* ctx, int32_t n_steps);
 
+/* Kernels of one update step, in launch order (indices into the arrays of
+ * pop_update_timed). */
+enum {
+  POP_K_GATHER = 0,       /* replay index draw + row gather */
+  POP_K_TARGET = 1,       /* target actor, smoothing, twin target critics, y */
+  POP_K_CRITIC = 2,       /* twin critics forward + backward to pre-activations */
+  POP_K_WGRAD_CRITIC = 3, /* critic weight gradients + Adam (+ Polyak) */
+  POP_K_ACTOR = 4,        /* actor forward, critic-1 forward/input-gradient, actor backward */
+  POP_K_WGRAD_ACTOR = 5,  /* actor weight gradients + Adam + Polyak */
+  POP_K_COUNT = 6
+};
+
+/* Measurement variant of pop_update (same work, same results): every kernel
+ * launch is bracketed by HIP events on the context's stream; ms[k] receives
+ * the summed elapsed milliseconds of kernel k and launches[k] its number of
+ * launches (host arrays of POP_K_COUNT entries, overwritten).  Synchronises
+ * the stream before returning. */
+int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launches);
+
 /* Deterministic actions of every agent's current actor: obs[P, n, obs_dim] ->
  * act_out[P, n, act_dim] (agent i acts on slice i). */
 int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,

@@ -69,6 +69,7 @@ def load_library():
         "pop_create": (C.c_int, [C.POINTER(vp), cfgp, hpp, u64, vp, i64, vp]),
         "pop_insert": (C.c_int, [vp, i32, i64, fp, fp, fp, fp, fp, i32]),
         "pop_update": (C.c_int, [vp, i32]),
+        "pop_update_timed": (C.c_int, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "pop_act": (C.c_int, [vp, fp, i32, fp, i32]),
         "pop_get_params": (i64, [vp, i32, i32, fp, i64, i32]),
         "pop_set_debug": (C.c_int, [vp, i32]),
@@ -160,6 +161,17 @@ def pop_update(ctx, n_steps):
     return _check(load_library().pop_update(ctx, n_steps), ctx)
 
 
+KERNEL_NAMES = ("gather", "target", "critic", "wgrad_critic", "actor", "wgrad_actor")
+
+
+def pop_update_timed(ctx, n_steps):
+    """Returns ({kernel: summed ms}, {kernel: launches})."""
+    ms = (C.c_double * len(KERNEL_NAMES))()
+    cnt = (C.c_int64 * len(KERNEL_NAMES))()
+    _check(load_library().pop_update_timed(ctx, n_steps, ms, cnt), ctx)
+    return dict(zip(KERNEL_NAMES, list(ms))), dict(zip(KERNEL_NAMES, list(cnt)))
+
+
 def pop_act(ctx, obs, n, act_out):
     dev = _is_device(obs)
     return _check(load_library().pop_act(ctx, _ptr(obs, dev), n, _ptr(act_out, dev), int(dev)), ctx)
@@ -225,6 +237,9 @@ class Population:
 
     def update(self, n_steps):
         return pop_update(self.ctx, n_steps)
+
+    def update_timed(self, n_steps):
+        return pop_update_timed(self.ctx, n_steps)
 
     def sync(self):
         return pop_sync(self.ctx)

@@ -2,6 +2,7 @@
 // layout, and the per-step launch schedule.  See include/pop.h for the contract.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -282,29 +283,103 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs, const f
   return POP_OK;
 }
 
-int pop_update(pop_ctx* ctx, int32_t n_steps) {
-  if (!ctx) return POP_EINVAL;
-  if (n_steps < 0) return fail(ctx, POP_EINVAL, "n_steps is negative");
+}  // extern "C"
+
+namespace {
+
+// One update step: launches in stream order.  `tick(k)` is called before and after kernel k.
+template <class Tick>
+int enqueue_step(pop_ctx* ctx, Tick tick) {
   const PopDev& d = ctx->d;
-  for (int a = 0; a < d.P; ++a)
+  hipStream_t s = ctx->stream;
+  const uint32_t t = (uint32_t)ctx->t;
+  hipError_t e;
+  auto run = [&](int k, hipError_t (*fn)(const PopDev&, uint32_t, hipStream_t)) {
+    tick(k, 0);
+    e = fn(d, t, s);
+    tick(k, 1);
+    return e == hipSuccess;
+  };
+  if (!run(POP_K_GATHER, launch_sample_gather) || !run(POP_K_TARGET, launch_target) ||
+      !run(POP_K_CRITIC, launch_critic))
+    return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+  tick(POP_K_WGRAD_CRITIC, 0);
+  e = launch_wgrad_adam(d, t, 0, s);
+  tick(POP_K_WGRAD_CRITIC, 1);
+  if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+  bool any_actor = false;
+  for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
+  if (any_actor) {
+    if (!run(POP_K_ACTOR, launch_actor)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    tick(POP_K_WGRAD_ACTOR, 0);
+    e = launch_wgrad_adam(d, t, 1, s);
+    tick(POP_K_WGRAD_ACTOR, 1);
+    if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+  }
+  ctx->t++;
+  return POP_OK;
+}
+
+int check_update(pop_ctx* ctx, int32_t n_steps) {
+  if (n_steps < 0) return fail(ctx, POP_EINVAL, "n_steps is negative");
+  for (int a = 0; a < ctx->d.P; ++a)
     if (ctx->count[a] == 0) return fail(ctx, POP_EEMPTY, "agent %d has an empty replay buffer", a);
   if (ctx->t + (uint64_t)n_steps > 0xFFFFFFFFull) return fail(ctx, POP_EINVAL, "step counter would exceed 2^32");
-  hipStream_t s = ctx->stream;
-  for (int i = 0; i < n_steps; ++i) {
-    const uint32_t t = (uint32_t)ctx->t;
-    HIP_TRY(ctx, launch_sample_gather(d, t, s));
-    HIP_TRY(ctx, launch_target(d, t, s));
-    HIP_TRY(ctx, launch_critic(d, t, s));
-    HIP_TRY(ctx, launch_wgrad_adam(d, t, 0, s));
-    bool any_actor = false;
-    for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
-    if (any_actor) {
-      HIP_TRY(ctx, launch_actor(d, t, s));
-      HIP_TRY(ctx, launch_wgrad_adam(d, t, 1, s));
-    }
-    ctx->t++;
-  }
   return POP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pop_update(pop_ctx* ctx, int32_t n_steps) {
+  if (!ctx) return POP_EINVAL;
+  int rc = check_update(ctx, n_steps);
+  if (rc != POP_OK) return rc;
+  for (int i = 0; i < n_steps; ++i)
+    if ((rc = enqueue_step(ctx, [](int, int) {})) != POP_OK) return rc;
+  return POP_OK;
+}
+
+int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launches) {
+  if (!ctx) return POP_EINVAL;
+  if (!ms || !launches) return fail(ctx, POP_EINVAL, "NULL output array");
+  int rc = check_update(ctx, n_steps);
+  if (rc != POP_OK) return rc;
+  for (int k = 0; k < POP_K_COUNT; ++k) { ms[k] = 0.0; launches[k] = 0; }
+  const int kPiece = 64;                         // steps per batch of events
+  std::vector<hipEvent_t> ev((size_t)kPiece * POP_K_COUNT * 2, nullptr);
+  for (auto& e : ev) HIP_TRY(ctx, hipEventCreate(&e));
+  std::vector<char> used((size_t)kPiece * POP_K_COUNT);
+  hipStream_t s = ctx->stream;
+  for (int done = 0; done < n_steps && rc == POP_OK; done += kPiece) {
+    const int steps = std::min(kPiece, n_steps - done);
+    std::fill(used.begin(), used.end(), 0);
+    hipError_t ee = hipSuccess;
+    for (int i = 0; i < steps && rc == POP_OK; ++i) {
+      rc = enqueue_step(ctx, [&](int k, int end) {
+        const size_t slot = (size_t)i * POP_K_COUNT + k;
+        hipError_t r = hipEventRecord(ev[2 * slot + end], s);
+        if (r != hipSuccess) ee = r;
+        used[slot] = 1;
+      });
+    }
+    hipError_t se = hipStreamSynchronize(s);
+    if (rc == POP_OK && (se != hipSuccess || ee != hipSuccess))
+      rc = fail(ctx, POP_EHIP, "timed update: %s", hipGetErrorString(se != hipSuccess ? se : ee));
+    if (rc == POP_OK) {
+      for (size_t slot = 0; slot < (size_t)steps * POP_K_COUNT; ++slot) {
+        if (!used[slot]) continue;
+        float t_ms = 0.f;
+        if (hipEventElapsedTime(&t_ms, ev[2 * slot], ev[2 * slot + 1]) == hipSuccess) {
+          ms[slot % POP_K_COUNT] += t_ms;
+          launches[slot % POP_K_COUNT] += 1;
+        }
+      }
+    }
+  }
+  for (auto& e : ev) (void)hipEventDestroy(e);
+  return rc;
 }
 
 int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t ptrs_on_device) {

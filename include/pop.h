@@ -67,7 +67,7 @@ typedef struct {
 
 /* Population-wide shapes.  Supported now: algo TD3, n_hidden == 2 with
  * hidden = {256, 256}, obs_dim + act_dim <= 64, act_dim <= 8, batch a
- * multiple of 32 in [32, 1024], 1 <= capacity < 2^32.  Anything else gives
+ * multiple of 64 in [64, 1024], 1 <= capacity < 2^32.  Anything else gives
  * POP_EUNSUPPORTED. */
 typedef struct {
   int32_t algo;

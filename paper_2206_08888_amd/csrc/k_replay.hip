@@ -8,7 +8,7 @@
 // stacked batch [P][B][row].  Consecutive lanes read consecutive floats of one
 // row, so each random row costs two or three contiguous 64-byte segments.
 #include "launch.h"
-#include "rng.h"
+#include "gather.h"
 
 namespace pop {
 
@@ -63,20 +63,11 @@ hipError_t launch_insert(const PopDev& d, int agent, int64_t n, const float* obs
 
 __global__ __launch_bounds__(256) void k_sample_gather(PopDev d, uint32_t t) {
   // grid: (ceil(B * row / 256), P); one thread per float of the stacked batch
-  const int agent = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= d.B * d.row) return;
-  const int b = e / d.row, c = e - b * d.row;
-  const HpDev hp = d.hp[agent];
-  const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, (uint32_t)(b >> 2), t, kStreamIndex, 0u);
-  const uint32_t idx = index_from_word(blk.w[b & 3], d.count[agent]);
-  const size_t dst = ((size_t)agent * d.B + b) * d.row + c;
-  d.batch[dst] = d.replay[((size_t)agent * d.capacity + idx) * d.row + c];
-  if (c == 0) d.idx[(size_t)agent * d.B + b] = idx;
+  gather_element(d, t, blockIdx.y, blockIdx.x * 256 + threadIdx.x);
 }
 
 hipError_t launch_sample_gather(const PopDev& d, uint32_t t, hipStream_t s) {
-  dim3 grid((d.B * d.row + 255) / 256, d.P);
+  dim3 grid(gather_blocks_per_agent(d), d.P);
   hipLaunchKernelGGL(k_sample_gather, grid, dim3(256), 0, s, d, t);
   return hipGetLastError();
 }

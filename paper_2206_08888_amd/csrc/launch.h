@@ -20,14 +20,13 @@ hipError_t launch_sample_gather(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_critic(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s);
-hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, hipStream_t s);
+// prefetch_next != 0: extra workgroups also gather the replay rows of step t + 1
+hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s);
 
 // acting: obs[P][n][O] -> act[P][n][A] through the online actors
 hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, hipStream_t s);
 
 // one-time per-process kernel attribute setup (large dynamic LDS)
 hipError_t setup_kernels();
-
-int rows_per_workgroup();
 
 }  // namespace pop

@@ -63,30 +63,25 @@ __device__ inline void for_each_acc(const Acc<MT>& acc, int wave, int lane, F f)
         f(32 * mt + acc_row(v, lane), 64 * wave + 32 * nt + (lane & 31), acc.t[mt][nt][v]);
 }
 
-// acc[r][c] += sum_{k<K} X[r][k] W[k][c]   (forward product x W)
-//   X: LDS, row stride ldx, rows [0, 32 MT), columns >= K up to the next
+// acc[r][c] += sum_{k<K} X[r][k] W[k][c]   (forward product x W), small K.
+//   X: LDS, row stride ldx, rows [0, 32 MT); columns >= K up to the next
 //      multiple of 8 must hold finite values (they meet zero weights);
-//   W: global, row-major [K][256].
-template <int MT, bool FULLK>
-__device__ inline void gemm_xw(const float* __restrict__ Xl, int ldx, int K, const float* __restrict__ W,
-                               int wave, int lane, Acc<MT>& acc) {
+//   W: global, row-major [K][256].  Used for the first layers (K = obs or
+//   obs + act, a few k-steps only), so it is not software-pipelined.
+template <int MT>
+__device__ inline void gemm_xw_small(const float* __restrict__ Xl, int ldx, int K, const float* __restrict__ W,
+                                     int wave, int lane, Acc<MT>& acc) {
   const int half = lane >> 5, l32 = lane & 31;
   const float* wcol = W + 64 * wave + l32;
   const int K8 = (K + 7) & ~7;
-  float bc[2][4], bn[2][4];
-  auto load_b = [&](int k0, float (&b)[2][4]) {
+  for (int k0 = 0; k0 < K8; k0 += 8) {
+    float b[2][4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int k = k0 + 4 * half + j;
-      const bool ok = FULLK || k < K;
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) b[nt][j] = ok ? wcol[(size_t)k * kH + 32 * nt] : 0.0f;
+      for (int nt = 0; nt < 2; ++nt) b[nt][j] = k < K ? wcol[(size_t)k * kH + 32 * nt] : 0.0f;
     }
-  };
-  load_b(0, bc);
-#pragma unroll 2
-  for (int k0 = 0; k0 < K8; k0 += 8) {
-    if (k0 + 8 < K8) load_b(k0 + 8, bn);
     f32x4 a[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -96,58 +91,115 @@ __device__ inline void gemm_xw(const float* __restrict__ Xl, int ldx, int K, con
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], bc[nt][j], acc.t[mt][nt]);
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) bc[nt][j] = bn[nt][j];
+        for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], b[nt][j], acc.t[mt][nt]);
   }
 }
 
-// acc[r][k] += sum_{n<256} Z[r][n] W[k][n]   (input-gradient product dz W^T)
-//   Z: LDS, row stride kLda; W: global, row-major [256][256].
-template <int MT>
-__device__ inline void gemm_zwt(const float* __restrict__ Zl, const float* __restrict__ W, int wave, int lane,
-                                Acc<MT>& acc) {
-  const int half = lane >> 5, l32 = lane & 31;
-  const float* wrow = W + (size_t)(64 * wave + l32) * kH + 4 * half;
-  f32x4 bc[2], bn[2];
+// Software-pipelined 256-deep contraction of an LDS operand with a global weight
+// operand; the contraction index is walked in 8 blocks of 32.
+//   forward  (TRANSPOSED = false): acc[r][c] += sum_k X[r][k] W[k][c], c in this wave's 64 columns
+//   backward (TRANSPOSED = true):  acc[r][k] += sum_n Z[r][n] W[k][n], k in this wave's 64 columns
+// W is row-major [256][256] in both cases.  The weight registers of block i+1
+// are requested from memory before the MFMAs of block i start (about 2000 MT
+// cycles of matrix work hide the L2 / memory latency); the LDS operand is
+// fetched half a block ahead.  __builtin_amdgcn_sched_barrier keeps the
+// compiler from sinking the loads back next to their uses.
+template <int MT, bool TRANSPOSED>
+struct WeightBlock {                       // the weights one lane needs for a 32-deep block
+  float w[2][16];                          // [column tile][4 s + j]  <->  index 32 i + 8 s + 4 half + j
+  __device__ inline void load(const float* __restrict__ W, int i, int wave, int lane) {
+    const int half = lane >> 5, l32 = lane & 31;
+    if (TRANSPOSED) {
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) bc[nt] = *reinterpret_cast<const f32x4*>(wrow + (size_t)32 * nt * kH);
-#pragma unroll 2
-  for (int n0 = 0; n0 < kH; n0 += 8) {
-    if (n0 + 8 < kH) {
+      for (int nt = 0; nt < 2; ++nt) {
+        const float* row = W + (size_t)(64 * wave + 32 * nt + l32) * kH + 32 * i + 4 * half;
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-        bn[nt] = *reinterpret_cast<const f32x4*>(wrow + (size_t)32 * nt * kH + n0 + 8);
+        for (int s = 0; s < 4; ++s) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(row + 8 * s);
+          w[nt][4 * s + 0] = v[0]; w[nt][4 * s + 1] = v[1]; w[nt][4 * s + 2] = v[2]; w[nt][4 * s + 3] = v[3];
+        }
+      }
+    } else {
+      const float* col = W + (size_t)(32 * i + 4 * half) * kH + 64 * wave + l32;
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt) w[nt][4 * s + j] = col[(size_t)(8 * s + j) * kH + 32 * nt];
     }
-    f32x4 a[MT];
+  }
+};
+
+template <int MT>
+struct LdsHalf {                           // the LDS operand of half a block (16 deep)
+  f32x4 a[MT][2];
+  __device__ inline void load(const float* __restrict__ Xl, int ldx, int k0, int lane) {
+    const int half = lane >> 5, l32 = lane & 31;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-      a[mt] = *reinterpret_cast<const f32x4*>(&Zl[(32 * mt + l32) * kLda + n0 + 4 * half]);
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+        a[mt][s] = *reinterpret_cast<const f32x4*>(&Xl[(32 * mt + l32) * ldx + k0 + 8 * s + 4 * half]);
+  }
+};
+
+template <int MT, bool TRANSPOSED>
+__device__ inline void mfma_half(const LdsHalf<MT>& x, const WeightBlock<MT, TRANSPOSED>& b, int h, Acc<MT>& acc) {
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], bc[nt][j], acc.t[mt][nt]);
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) bc[nt] = bn[nt];
+        for (int nt = 0; nt < 2; ++nt)
+          acc.t[mt][nt] = mfma32(x.a[mt][s][j], b.w[nt][4 * (2 * h + s) + j], acc.t[mt][nt]);
+}
+
+template <int MT, bool TRANSPOSED>
+__device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const float* __restrict__ W, int wave,
+                               int lane, Acc<MT>& acc) {
+  WeightBlock<MT, TRANSPOSED> b0, b1;
+  LdsHalf<MT> x0, x1;
+  b0.load(W, 0, wave, lane);
+  x0.load(Xl, ldx, 0, lane);
+#pragma unroll 1
+  for (int i = 0; i < 8; i += 2) {
+    b1.load(W, i + 1, wave, lane);
+    x1.load(Xl, ldx, 32 * i + 16, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_half<MT, TRANSPOSED>(x0, b0, 0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    x0.load(Xl, ldx, 32 * i + 32, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_half<MT, TRANSPOSED>(x1, b0, 1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (i + 2 < 8) b0.load(W, i + 2, wave, lane);
+    x1.load(Xl, ldx, 32 * i + 48, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_half<MT, TRANSPOSED>(x0, b1, 0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (i + 2 < 8) x0.load(Xl, ldx, 32 * i + 64, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_half<MT, TRANSPOSED>(x1, b1, 1, acc);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
-// One hidden layer: Y = relu(X W + b) written to LDS (row stride kLda) and,
-// when Yg != nullptr, to global memory as [rows][256].
-template <int MT, bool FULLK>
-__device__ inline void layer_relu(const float* __restrict__ Xl, int ldx, int K, const float* __restrict__ W,
-                                  const float* __restrict__ bias, float* __restrict__ Yl,
-                                  float* __restrict__ Yg, int wave, int lane) {
-  Acc<MT> acc;
-  acc.zero();
-  gemm_xw<MT, FULLK>(Xl, ldx, K, W, wave, lane, acc);
+// ReLU epilogue of a hidden layer: Y = max(acc + b, 0) goes to LDS (row stride
+// kLda) and, when Yg != nullptr, to global memory as [rows][256].  Returns the
+// activation pattern of this lane's elements, bit (2 mt + nt) 16 + v, so that
+// the backward pass can apply ReLU' without re-reading the activations: the
+// input-gradient product leaves element (row, col) in the same lane and
+// register as the forward product did.
+template <int MT>
+__device__ inline uint64_t relu_store(const Acc<MT>& acc, const float* __restrict__ bias, float* __restrict__ Yl,
+                                      float* __restrict__ Yg, int wave, int lane) {
   float bb[2];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) bb[nt] = bias[64 * wave + 32 * nt + (lane & 31)];
+  uint64_t mask = 0;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -157,9 +209,15 @@ __device__ inline void layer_relu(const float* __restrict__ Xl, int ldx, int K, 
         const int row = 32 * mt + acc_row(v, lane);
         const int col = 64 * wave + 32 * nt + (lane & 31);
         const float h = fmaxf(acc.t[mt][nt][v] + bb[nt], 0.0f);
+        if (h > 0.0f) mask |= 1ull << ((2 * mt + nt) * 16 + v);
         Yl[row * kLda + col] = h;
         if (Yg) Yg[(size_t)row * kH + col] = h;
       }
+  return mask;
+}
+
+__device__ inline bool mask_bit(uint64_t mask, int mt, int nt, int v) {
+  return (mask >> ((2 * mt + nt) * 16 + v)) & 1ull;
 }
 
 // Thin products on the vector ALU (heads with 1..8 outputs, action gradient):
@@ -208,32 +266,58 @@ __device__ inline void thin_dot(const float* __restrict__ Xl, const float* __res
 }
 
 // 32x32 tile of a weight gradient: C[m][n] = sum_{b<B} A[b*lda + m0 + m] Z[b*ldz + n0 + n],
-// both operands in global memory, rows m0 + m >= M masked to zero.  B % 16 == 0.
+// both operands in global memory, rows m0 + m >= M masked to zero.  B % 64 == 0.
+// The batch index is walked in stages of 64 rows (32 MFMAs); the operand
+// registers of stage i+1 are requested before the MFMAs of stage i start.
+// `before_last()` is called in place of the prefetch ahead of the last stage, so
+// the caller can start loads of its own (the epilogue's operands) under the
+// remaining matrix work.
+struct WgradStage {
+  float a[32], z[32];
+  __device__ inline void load(const float* __restrict__ ap, size_t lda, bool mok, const float* __restrict__ zp,
+                              size_t ldz) {
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      a[u] = mok ? *ap : 0.0f;
+      z[u] = *zp;
+      ap += 2 * lda;
+      zp += 2 * ldz;
+    }
+  }
+  __device__ inline void mfma(f32x16& acc) const {
+#pragma unroll
+    for (int u = 0; u < 32; ++u) acc = mfma32(a[u], z[u], acc);
+  }
+};
+
+template <class F>
 __device__ inline f32x16 wgrad_tile(const float* __restrict__ A, int lda, int M, int m0,
-                                    const float* __restrict__ Z, int ldz, int n0, int B, int lane) {
+                                    const float* __restrict__ Z, int ldz, int n0, int B, int lane,
+                                    F before_last) {
   const int half = lane >> 5, l32 = lane & 31;
   const bool mok = (m0 + l32) < M;
   const float* ap = A + (size_t)half * lda + m0 + l32;
   const float* zp = Z + (size_t)half * ldz + n0 + l32;
+  const size_t sa = (size_t)64 * lda, sz = (size_t)64 * ldz;     // one stage of 64 batch rows
+  const int n = B / 64;
   f32x16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-  float ac[8], zc[8], an[8], zn[8];
-  auto load = [&](int b0, float (&a)[8], float (&z)[8]) {
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      a[u] = mok ? ap[(size_t)(b0 + 2 * u) * lda] : 0.0f;
-      z[u] = zp[(size_t)(b0 + 2 * u) * ldz];
-    }
-  };
-  load(0, ac, zc);
-#pragma unroll 2
-  for (int b0 = 0; b0 < B; b0 += 16) {
-    if (b0 + 16 < B) load(b0 + 16, an, zn);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) acc = mfma32(ac[u], zc[u], acc);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) { ac[u] = an[u]; zc[u] = zn[u]; }
+  WgradStage s0, s1;
+  s0.load(ap, lda, mok, zp, ldz);
+  int st = 0;
+  while (true) {
+    if (st + 1 < n) s1.load(ap + (st + 1) * sa, lda, mok, zp + (st + 1) * sz, ldz); else before_last();
+    __builtin_amdgcn_sched_barrier(0);
+    s0.mfma(acc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (st + 1 >= n) break;
+    if (st + 2 < n) s0.load(ap + (st + 2) * sa, lda, mok, zp + (st + 2) * sz, ldz); else before_last();
+    __builtin_amdgcn_sched_barrier(0);
+    s1.mfma(acc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (st + 2 >= n) break;
+    st += 2;
   }
   return acc;
 }

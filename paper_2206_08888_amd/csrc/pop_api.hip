@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -22,7 +23,7 @@ constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
   int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
-  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, staging, replay, total;
+  int64_t cH1, cdZ2, cdZ1, aH1, adZ2, adZ1, cpart, apart, losses, staging, replay, total;
   int64_t param_bytes;
 };
 
@@ -42,6 +43,7 @@ struct pop_ctx {
   std::vector<HpDev> hp_dev;
   std::vector<uint64_t> count;   // host mirror of the buffer fill levels
   uint64_t t;                    // update steps taken
+  uint64_t gathered_t;           // step whose batch already sits in its half of the double buffer
   std::string err;
 };
 
@@ -73,8 +75,8 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
     return fail(ctx, POP_EUNSUPPORTED, "hidden layers must be {256, 256}");
   if (c->obs_dim + c->act_dim > kMaxIn) return fail(ctx, POP_EUNSUPPORTED, "obs_dim + act_dim must be <= %d", kMaxIn);
   if (c->act_dim > kMaxAct) return fail(ctx, POP_EUNSUPPORTED, "act_dim must be <= %d", kMaxAct);
-  if (c->batch % 32 != 0 || c->batch > 1024 || c->batch % rows_per_workgroup() != 0)
-    return fail(ctx, POP_EUNSUPPORTED, "batch must be a multiple of %d, at most 1024", rows_per_workgroup());
+  if (c->batch % 64 != 0 || c->batch > 1024)
+    return fail(ctx, POP_EUNSUPPORTED, "batch must be a multiple of 64, at most 1024");
   if (c->capacity > 0xFFFFFFFFll) return fail(ctx, POP_EUNSUPPORTED, "capacity must be below 2^32");
   if ((int64_t)c->P * c->batch > (1ll << 24)) return fail(ctx, POP_EUNSUPPORTED, "P * batch too large");
   return POP_OK;
@@ -84,7 +86,11 @@ void fill_dims(const pop_config& c, PopDev& d) {
   std::memset(&d, 0, sizeof d);
   d.P = c.P; d.O = c.obs_dim; d.A = c.act_dim; d.D = c.obs_dim + c.act_dim; d.B = c.batch;
   d.row = 2 * c.obs_dim + c.act_dim + 2;
-  d.chunks = c.batch / rows_per_workgroup();
+  // rows per workgroup of the chain kernels: 64 once that still gives every CU two
+  // workgroups (halves the weight traffic per row), else 32 for more parallelism
+  d.mt = ((int64_t)c.P * (c.batch / 64) >= 512) ? 2 : 1;
+  if (const char* env = getenv("POP_ROW_TILES")) { const int v = atoi(env); if (v == 1 || v == 2) d.mt = v; }
+  d.chunks = c.batch / (32 * d.mt);
   d.actor = make_layout(d.O, d.A);
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
@@ -101,11 +107,11 @@ Layout make_ws_layout(const PopDev& d) {
   L.theta = take(L.param_bytes); L.target = take(L.param_bytes);
   L.m = take(L.param_bytes); L.v = take(L.param_bytes); L.grad = take(L.param_bytes);
   L.count = take(P * 4); L.cursor = take(P * 4);
-  L.idx = take(P * B * 4); L.batch = take(P * B * d.row * 4);
+  L.idx = take(2 * P * B * 4); L.batch = take(2 * P * B * d.row * 4);
   L.atilde = take(P * B * d.A * 4); L.y = take(P * B * 4);
   const int64_t act = P * B * kH * 4;
   L.cH1 = take(2 * act); L.cdZ2 = take(2 * act); L.cdZ1 = take(2 * act);
-  L.aH1 = take(act); L.aH2 = take(act); L.adZ2 = take(act); L.adZ1 = take(act);
+  L.aH1 = take(act); L.adZ2 = take(act); L.adZ1 = take(act);
   L.cpart = take(P * 2 * (int64_t)d.chunks * kCPart * 4);
   L.apart = take(P * (int64_t)d.chunks * kAPart * 4);
   L.losses = take(P * 4 * 4);
@@ -191,6 +197,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->ws = (char*)workspace;
   ctx->stream = (hipStream_t)hip_stream;
   ctx->t = 0;
+  ctx->gathered_t = ~0ull;
   ctx->hp.assign(hp, hp + cfg->P);
   ctx->count.assign(cfg->P, 0);
   ctx->hp_dev.resize(cfg->P);
@@ -213,7 +220,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.idx = (uint32_t*)(w + L.idx); d.batch = (float*)(w + L.batch);
   d.atilde = (float*)(w + L.atilde); d.y = (float*)(w + L.y);
   d.cH1 = (float*)(w + L.cH1); d.cdZ2 = (float*)(w + L.cdZ2); d.cdZ1 = (float*)(w + L.cdZ1);
-  d.aH1 = (float*)(w + L.aH1); d.aH2 = (float*)(w + L.aH2); d.adZ2 = (float*)(w + L.adZ2);
+  d.aH1 = (float*)(w + L.aH1); d.adZ2 = (float*)(w + L.adZ2);
   d.adZ1 = (float*)(w + L.adZ1);
   d.cpart = (float*)(w + L.cpart); d.apart = (float*)(w + L.apart); d.losses = (float*)(w + L.losses);
   ctx->d = d;
@@ -246,6 +253,7 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs, const f
   if (n < 0 || n > 0xFFFFFFFFll) return fail(ctx, POP_EINVAL, "n out of range");
   if (n == 0) return POP_OK;
   if (!obs || !act || !rew || !done || !next_obs) return fail(ctx, POP_EINVAL, "NULL transition array");
+  ctx->gathered_t = ~0ull;        // a batch drawn before this insert would not see the new rows
   const PopDev& d = ctx->d;
   hipStream_t s = ctx->stream;
   auto bump = [&](int a, int64_t k) {
@@ -287,32 +295,37 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs, const f
 
 namespace {
 
-// One update step: launches in stream order.  `tick(k)` is called before and after kernel k.
+// One update step: launches in stream order.  `tick(k, end)` is called before and after
+// kernel k.  When another step follows in the same call, the critic weight-gradient
+// kernel also gathers that step's replay rows, so only the first step of a call pays
+// for a stand-alone gather.
 template <class Tick>
-int enqueue_step(pop_ctx* ctx, Tick tick) {
+int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
   const PopDev& d = ctx->d;
   hipStream_t s = ctx->stream;
   const uint32_t t = (uint32_t)ctx->t;
-  hipError_t e;
+  hipError_t e = hipSuccess;
   auto run = [&](int k, hipError_t (*fn)(const PopDev&, uint32_t, hipStream_t)) {
     tick(k, 0);
     e = fn(d, t, s);
     tick(k, 1);
     return e == hipSuccess;
   };
-  if (!run(POP_K_GATHER, launch_sample_gather) || !run(POP_K_TARGET, launch_target) ||
-      !run(POP_K_CRITIC, launch_critic))
+  if (ctx->gathered_t != ctx->t && !run(POP_K_GATHER, launch_sample_gather))
+    return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+  if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic))
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
   tick(POP_K_WGRAD_CRITIC, 0);
-  e = launch_wgrad_adam(d, t, 0, s);
+  e = launch_wgrad_adam(d, t, 0, has_next ? 1 : 0, s);
   tick(POP_K_WGRAD_CRITIC, 1);
   if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+  if (has_next) ctx->gathered_t = ctx->t + 1;
   bool any_actor = false;
   for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
   if (any_actor) {
     if (!run(POP_K_ACTOR, launch_actor)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
     tick(POP_K_WGRAD_ACTOR, 0);
-    e = launch_wgrad_adam(d, t, 1, s);
+    e = launch_wgrad_adam(d, t, 1, 0, s);
     tick(POP_K_WGRAD_ACTOR, 1);
     if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
   }
@@ -337,7 +350,7 @@ int pop_update(pop_ctx* ctx, int32_t n_steps) {
   int rc = check_update(ctx, n_steps);
   if (rc != POP_OK) return rc;
   for (int i = 0; i < n_steps; ++i)
-    if ((rc = enqueue_step(ctx, [](int, int) {})) != POP_OK) return rc;
+    if ((rc = enqueue_step(ctx, i + 1 < n_steps, [](int, int) {})) != POP_OK) return rc;
   return POP_OK;
 }
 
@@ -357,7 +370,7 @@ int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launche
     std::fill(used.begin(), used.end(), 0);
     hipError_t ee = hipSuccess;
     for (int i = 0; i < steps && rc == POP_OK; ++i) {
-      rc = enqueue_step(ctx, [&](int k, int end) {
+      rc = enqueue_step(ctx, done + i + 1 < n_steps, [&](int k, int end) {
         const size_t slot = (size_t)i * POP_K_COUNT + k;
         hipError_t r = hipEventRecord(ev[2 * slot + end], s);
         if (r != hipSuccess) ee = r;
@@ -439,9 +452,10 @@ int64_t pop_debug_get(pop_ctx* ctx, int32_t what, void* out, int64_t out_bytes, 
   const int64_t PB = (int64_t)d.P * d.B;
   const char* src = nullptr;
   int64_t bytes = 0;
+  const int64_t half = ctx->t > 0 ? (int64_t)((ctx->t - 1) & 1) : 0;   // buffer half of the last step
   switch (what) {
-    case POP_DBG_INDICES: src = (const char*)d.idx; bytes = PB * 4; break;
-    case POP_DBG_BATCH: src = (const char*)d.batch; bytes = PB * d.row * 4; break;
+    case POP_DBG_INDICES: bytes = PB * 4; src = (const char*)d.idx + half * bytes; break;
+    case POP_DBG_BATCH: bytes = PB * d.row * 4; src = (const char*)d.batch + half * bytes; break;
     case POP_DBG_TARGET_ACTION: src = (const char*)d.atilde; bytes = PB * d.A * 4; break;
     case POP_DBG_TARGET_Y: src = (const char*)d.y; bytes = PB * 4; break;
     case POP_DBG_LOSSES: bytes = (int64_t)d.P * 2 * 4; break;

@@ -41,7 +41,8 @@ __host__ __device__ inline NetLayout make_layout(int in, int out) {
 
 struct PopDev {
   int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
-  int chunks;                  // B / rows-per-workgroup of the fused chain kernels
+  int mt;                      // row tiles per workgroup of the fused chain kernels (rows = 32 mt)
+  int chunks;                  // B / (32 mt)
   NetLayout actor, critic;
   int agent_sz;                // actor.padded + 2 * critic.padded
   // parameter state, each [P][agent_sz] = [actor | critic1 | critic2]
@@ -52,14 +53,15 @@ struct PopDev {
   float* replay;               // [P][capacity][row]
   uint64_t capacity;
   uint32_t *count, *cursor;    // [P]
-  // state of the current step
-  uint32_t* idx;               // [P][B]
-  float* batch;                // [P][B][row]
+  // state of the current step; idx and batch are double-buffered by step parity so
+  // that the rows of step t + 1 can be gathered while step t is still computing
+  uint32_t* idx;               // [2][P][B]
+  float* batch;                // [2][P][B][row]
   float* atilde;               // [P][B][A]
   float* y;                    // [P][B]
   // activations handed from the chain kernels to the weight-gradient kernel
   float *cH1, *cdZ2, *cdZ1;    // [P][2][B][256]
-  float *aH1, *aH2, *adZ2, *adZ1;  // [P][B][256]
+  float *aH1, *adZ2, *adZ1;    // [P][B][256]
   // per-row-chunk partial sums of the small gradients and of the losses
   float* cpart;                // [P][2][chunks][kCPart]
   float* apart;                // [P][chunks][kAPart]
@@ -71,6 +73,21 @@ constexpr int kCP_dW3 = 0, kCP_db3 = 256, kCP_db2 = 260, kCP_db1 = 516, kCP_loss
 // actor partial record: dW3[256*kMaxAct] db3[kMaxAct] db2[256] db1[256] loss[1] pad
 constexpr int kAP_dW3 = 0, kAP_db3 = 256 * kMaxAct, kAP_db2 = kAP_db3 + kMaxAct, kAP_db1 = kAP_db2 + 256,
               kAP_loss = kAP_db1 + 256, kAPart = kAP_loss + 8;
+
+__device__ inline const float* batch_rows(const PopDev& d, uint32_t t, int agent) {
+  return d.batch + ((size_t)(t & 1u) * d.P + agent) * d.B * d.row;
+}
+
+// Workgroup ids are handed to the 8 XCDs round-robin; decode a 1-D block id so that
+// all `per_unit` workgroups of one unit (an agent or a network) land on the same
+// XCD and share its L2 (weights and activations of that unit).
+__device__ inline bool decode_block(int id, int units, int per_unit, int& unit, int& sub) {
+  const int x = id & 7, slot = id >> 3;
+  unit = (slot / per_unit) * 8 + x;
+  sub = slot % per_unit;
+  return unit < units;
+}
+__host__ inline int xcd_grid(int units, int per_unit) { return (units + 7) / 8 * 8 * per_unit; }
 
 __device__ inline const float* net_ptr(const PopDev& d, const float* base, int agent, int net) {
   const float* p = base + (size_t)agent * d.agent_sz;

@@ -16,7 +16,7 @@ __device__ inline void gather_element(const PopDev& d, uint32_t t, int agent, in
   const int b = e / d.row, c = e - b * d.row;
   const HpDev hp = d.hp[agent];
   const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, (uint32_t)(b >> 2), t, kStreamIndex, 0u);
-  const uint32_t idx = index_from_word(blk.w[b & 3], d.count[agent]);
+  const uint32_t idx = index_from_word(pick(blk, (uint32_t)b & 3u), d.count[agent]);
   const size_t slot = ((size_t)(t & 1u) * d.P + agent) * d.B + b;
   d.batch[slot * d.row + c] = d.replay[((size_t)agent * d.capacity + idx) * d.row + c];
   if (c == 0) d.idx[slot] = idx;

@@ -146,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
     const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, el >> 2, t, kStreamSmooth, 0u);
     float n4[4];
     normals4(blk, n4);
-    const float noise = fminf(fmaxf(hp.policy_noise * n4[el & 3], -hp.noise_clip), hp.noise_clip);
+    const float noise = fminf(fmaxf(hp.policy_noise * ((el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0])), -hp.noise_clip), hp.noise_clip);
     const float at = fminf(fmaxf(mu + noise, -1.0f), 1.0f);
     Xs[r * kXld + d.O + j] = at;
     d.atilde[((size_t)agent * d.B + r0 + r) * d.A + j] = at;

@@ -24,7 +24,7 @@ __global__ __launch_bounds__(256) void k_init(PopDev d, InitLimits lim) {
   if (e >= fan_in * fan_out) return;
   const HpDev hp = d.hp[agent];
   const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, (uint32_t)(e >> 2), 0u, kStreamInit, (uint32_t)(16 * net + layer));
-  const float u = (float)(blk.w[e & 3] >> 8) * 5.9604644775390625e-8f;
+  const float u = (float)(pick(blk, (uint32_t)e & 3u) >> 8) * 5.9604644775390625e-8f;
   const float centred = 2.0f * u - 1.0f;          // exact
   const float w = __fmul_rn(centred, limit);      // a single rounding, never fused
   net_ptr(d, d.theta, agent, net)[off + e] = w;

@@ -265,61 +265,4 @@ __device__ inline void thin_dot(const float* __restrict__ Xl, const float* __res
   }
 }
 
-// 32x32 tile of a weight gradient: C[m][n] = sum_{b<B} A[b*lda + m0 + m] Z[b*ldz + n0 + n],
-// both operands in global memory, rows m0 + m >= M masked to zero.  B % 64 == 0.
-// The batch index is walked in stages of 64 rows (32 MFMAs); the operand
-// registers of stage i+1 are requested before the MFMAs of stage i start.
-// `before_last()` is called in place of the prefetch ahead of the last stage, so
-// the caller can start loads of its own (the epilogue's operands) under the
-// remaining matrix work.
-struct WgradStage {
-  float a[32], z[32];
-  __device__ inline void load(const float* __restrict__ ap, size_t lda, bool mok, const float* __restrict__ zp,
-                              size_t ldz) {
-#pragma unroll
-    for (int u = 0; u < 32; ++u) {
-      a[u] = mok ? *ap : 0.0f;
-      z[u] = *zp;
-      ap += 2 * lda;
-      zp += 2 * ldz;
-    }
-  }
-  __device__ inline void mfma(f32x16& acc) const {
-#pragma unroll
-    for (int u = 0; u < 32; ++u) acc = mfma32(a[u], z[u], acc);
-  }
-};
-
-template <class F>
-__device__ inline f32x16 wgrad_tile(const float* __restrict__ A, int lda, int M, int m0,
-                                    const float* __restrict__ Z, int ldz, int n0, int B, int lane,
-                                    F before_last) {
-  const int half = lane >> 5, l32 = lane & 31;
-  const bool mok = (m0 + l32) < M;
-  const float* ap = A + (size_t)half * lda + m0 + l32;
-  const float* zp = Z + (size_t)half * ldz + n0 + l32;
-  const size_t sa = (size_t)64 * lda, sz = (size_t)64 * ldz;     // one stage of 64 batch rows
-  const int n = B / 64;
-  f32x16 acc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-  WgradStage s0, s1;
-  s0.load(ap, lda, mok, zp, ldz);
-  int st = 0;
-  while (true) {
-    if (st + 1 < n) s1.load(ap + (st + 1) * sa, lda, mok, zp + (st + 1) * sz, ldz); else before_last();
-    __builtin_amdgcn_sched_barrier(0);
-    s0.mfma(acc);
-    __builtin_amdgcn_sched_barrier(0);
-    if (st + 1 >= n) break;
-    if (st + 2 < n) s0.load(ap + (st + 2) * sa, lda, mok, zp + (st + 2) * sz, ldz); else before_last();
-    __builtin_amdgcn_sched_barrier(0);
-    s1.mfma(acc);
-    __builtin_amdgcn_sched_barrier(0);
-    if (st + 2 >= n) break;
-    st += 2;
-  }
-  return acc;
-}
-
 }  // namespace pop

@@ -28,6 +28,13 @@ __host__ __device__ inline U4 philox4x32_10(uint32_t k0, uint32_t k1, uint32_t b
   return o;
 }
 
+// Word i (0..3) of a block without indexing the register array dynamically.
+__host__ __device__ inline uint32_t pick(const U4& r, uint32_t i) {
+  const uint32_t lo = (i & 1u) ? r.w[1] : r.w[0];
+  const uint32_t hi = (i & 1u) ? r.w[3] : r.w[2];
+  return (i & 2u) ? hi : lo;
+}
+
 // Replay slot from one word: high half of word * count (integer only).
 __host__ __device__ inline uint32_t index_from_word(uint32_t w, uint32_t count) {
   return (uint32_t)(((uint64_t)w * (uint64_t)count) >> 32);

@@ -66,8 +66,8 @@ typedef struct {
 } pop_hparams;
 
 /* Population-wide shapes.  Supported now: algo TD3, n_hidden == 2 with
- * hidden = {256, 256}, obs_dim + act_dim <= 64, act_dim <= 8, batch a
- * multiple of 64 in [64, 1024], 1 <= capacity < 2^32.  Anything else gives
+ * hidden = {256, 256}, obs_dim + act_dim <= 64, act_dim <= 8, batch ==
+ * 256 (the batch of every workload of Sec. 4.1), 1 <= capacity < 2^32.  Anything else gives
  * POP_EUNSUPPORTED. */
 typedef struct {
   int32_t algo;

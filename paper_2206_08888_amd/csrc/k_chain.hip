@@ -17,10 +17,13 @@
 //   k_act    : obs -> actor (acting, no gradient)
 //
 // LDS economy: a hidden layer overwrites its own input tile (all wavefronts
-// finish reading, barrier, then write), and ReLU patterns travel from the
+// finish reading, barrier, then write) and ReLU patterns travel from the
 // forward to the backward product as bit masks in registers, so one 256-wide
-// tile per workgroup is enough (two in k_actor, which must keep the actor's
-// second hidden layer while the critic runs).
+// tile per workgroup is enough.  Latency economy: everything a layer needs
+// from memory (its first-layer weights, the first weight block of its hidden
+// layer, its biases) is requested while the previous product is still on the
+// matrix unit, and the small head vectors are staged in LDS when the kernel
+// starts.
 #include "launch.h"
 #include "mfma_tiles.h"
 #include "rng.h"
@@ -31,26 +34,60 @@ static_assert(kMaxAct == 8, "the action-gradient loops read dz3 rows as two 16-b
 
 namespace {
 
-template <int MT, int NBUF>
+// LDS map (floats): input tile [R][xld] | activation tile [R][kLda] | 3 x [R][8] scratch | vectors
+template <int MT>
 struct Lds {
   static constexpr int R = 32 * MT;
-  static constexpr int x_off = 0;                         // [R][kXld] first-layer input
-  static constexpr int a_off = x_off + R * kXld;          // [R][kLda]
-  static constexpr int b_off = a_off + R * kLda;          // [R][kLda] (NBUF == 2)
-  static constexpr int s0_off = a_off + NBUF * R * kLda;  // [R][kMaxAct] scratch
-  static constexpr int s1_off = s0_off + R * kMaxAct;
-  static constexpr int s2_off = s1_off + R * kMaxAct;
-  static constexpr int floats = s2_off + R * kMaxAct;
-  static constexpr size_t bytes = (size_t)floats * sizeof(float);
+  int xld, buf, s0, s1, s2, vec;
+  __host__ __device__ Lds(int fan_in) {
+    xld = ((fan_in + 7) & ~7) + 4;         // 4 * odd words: conflict-free 16-byte row reads
+    buf = R * xld;
+    s0 = buf + R * kLda;
+    s1 = s0 + R * kMaxAct;
+    s2 = s1 + R * kMaxAct;
+    vec = s2 + R * kMaxAct;
+  }
+  __host__ size_t bytes(int vec_floats) const { return (size_t)(vec + vec_floats) * sizeof(float); }
+};
+
+// what a two-hidden-layer network needs from memory before its products can start
+template <int MT>
+struct LayerPre {
+  SmallW w1;                       // first-layer weights
+  WeightBlock<MT, false> w2;       // block 0 of the hidden layer
+  float b1[2], b2[2];              // biases of this lane's columns
+  __device__ inline void load(const float* __restrict__ net, const NetLayout& L, int wave, int lane) {
+    w1.load(net + L.w1, L.in, wave, lane);
+    w2.load(net + L.w2, 0, wave, lane);
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      b1[nt] = net[L.b1 + 64 * wave + 32 * nt + (lane & 31)];
+      b2[nt] = net[L.b2 + 64 * wave + 32 * nt + (lane & 31)];
+    }
+  }
 };
 
 // Copy columns [c0, c0 + n) of R batch rows into the LDS input tile at columns
 // [0, n), zero the remaining columns; rows at or beyond `valid` become zero.
 template <int R>
-__device__ inline void load_input(float* Xl, const float* rows, int row_stride, int c0, int n, int valid, int tid) {
-  for (int e = tid; e < R * kXld; e += kThreads) {
-    const int r = e / kXld, c = e - r * kXld;
+__device__ inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
+                                  int tid) {
+  for (int e = tid; e < R * xld; e += kThreads) {
+    const int r = e / xld, c = e - r * xld;
     Xl[e] = (c < n && r < valid) ? rows[(size_t)r * row_stride + c0 + c] : 0.0f;
+  }
+}
+
+__device__ inline void stage_vector(float* dst, const float* __restrict__ src, int n, int tid) {
+  for (int e = tid; e < n; e += kThreads) dst[e] = src[e];
+}
+
+// Stage a head weight W3[256][J] as J rows of 256 (so that the thin products read it with
+// 16-byte LDS loads like any other row vector).
+__device__ inline void stage_head(float* dst, const float* __restrict__ src, int J, int tid) {
+  for (int e = tid; e < kH * J; e += kThreads) {
+    const int c = e / J, j = e - c * J;
+    dst[j * kH + c] = src[e];
   }
 }
 
@@ -60,36 +97,37 @@ __device__ inline float wave_sum(float v) {
   return v;
 }
 
-// First layer (small fan-in) from the input tile into `Yl` (+ optional global copy).
+// First layer from the input tile into `Yl` (+ optional global copy); returns the ReLU pattern.
 template <int MT>
-__device__ inline uint64_t first_layer(const float* Xs, int K, const float* W, const float* b, float* Yl, float* Yg,
-                                       int wave, int lane) {
+__device__ inline uint64_t first_layer(const float* Xs, int xld, const float* net, const NetLayout& L,
+                                       const LayerPre<MT>& pre, float* Yl, float* Yg, int wave, int lane) {
   Acc<MT> acc;
   acc.zero();
-  gemm_xw_small<MT>(Xs, kXld, K, W, wave, lane, acc);
-  return relu_store<MT>(acc, b, Yl, Yg, wave, lane);
+  gemm_xw_small<MT>(Xs, xld, L.in, net + L.w1, pre.w1, wave, lane, acc);
+  return relu_store<MT>(acc, pre.b1, Yl, Yg, wave, lane);
 }
 
-// Second layer: reads the tile `Xl` and writes `Yl`; Yl == Xl is allowed (the
-// barrier between product and store makes the overwrite safe).
-template <int MT>
-__device__ inline uint64_t hidden_layer(const float* Xl, const float* W, const float* b, float* Yl, float* Yg,
-                                        int wave, int lane) {
+// Hidden layer in place on `buf`; `tail` is handed to the product (see gemm256).
+template <int MT, class Tail>
+__device__ inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, LayerPre<MT>& pre,
+                                        float* Yg, int wave, int lane, Tail tail) {
   Acc<MT> acc;
   acc.zero();
-  gemm256<MT, false>(Xl, kLda, W, wave, lane, acc);
-  if (Yl == Xl) __syncthreads();
-  return relu_store<MT>(acc, b, Yl, Yg, wave, lane);
+  const float bb[2] = {pre.b2[0], pre.b2[1]};
+  gemm256<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
+  __syncthreads();                                   // every wavefront has read the input tile
+  return relu_store<MT>(acc, bb, buf, Yg, wave, lane);
 }
 
 // dX = (dZ W^T) * mask written to global [rows][256]; column sums of the result
 // (over this workgroup's rows) go to colsum_out[256].
 template <int MT>
-__device__ inline void input_grad_to_global(const float* Zl, const float* W, uint64_t mask, float* __restrict__ dXg,
-                                            float* __restrict__ colsum_out, int wave, int lane) {
+__device__ inline void input_grad_to_global(const float* Zl, const float* W, WeightBlock<MT, true>& w0, uint64_t mask,
+                                            float* __restrict__ dXg, float* __restrict__ colsum_out, int wave,
+                                            int lane) {
   Acc<MT> acc;
   acc.zero();
-  gemm256<MT, true>(Zl, kLda, W, wave, lane, acc);
+  gemm256<MT, true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
   float cs[2] = {0.0f, 0.0f};
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -98,7 +136,7 @@ __device__ inline void input_grad_to_global(const float* Zl, const float* W, uin
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const float z = mask_bit(mask, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;
-        dXg[(size_t)(32 * mt + acc_row(v, lane)) * kH + 64 * wave + 32 * nt + (lane & 31)] = z;
+        dXg[(32 * mt + acc_row(v, lane)) * kH + 64 * wave + 32 * nt + (lane & 31)] = z;
         cs[nt] += z;
       }
 #pragma unroll
@@ -116,53 +154,69 @@ __device__ inline void input_grad_to_global(const float* Zl, const float* W, uin
 //   y  = r + gamma (1 - d) min(Q1'(s', a~), Q2'(s', a~))
 template <int MT>
 __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
-  using L = Lds<MT, 1>;
-  constexpr int R = L::R;
+  constexpr int R = 32 * MT;
   extern __shared__ float lds[];
-  float* Xs = lds + L::x_off;
-  float* buf = lds + L::a_off;
-  float* head = lds + L::s0_off;
-  float* qmin = lds + L::s1_off;
+  const Lds<MT> L(d.D);
+  float* Xs = lds;
+  float* buf = lds + L.buf;
+  float* head = lds + L.s0;
+  float* qmin = lds + L.s1;
+  float* v_aw3 = lds + L.vec;                        // [A][256]
+  float* v_ab3 = v_aw3 + kH * d.A;                   // [8]
+  float* v_cw3 = v_ab3 + 8;                          // [2][256]
+  float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int agent, chunk;
   if (!decode_block(blockIdx.x, d.P, d.chunks, agent, chunk)) return;
   const int r0 = chunk * R;
+  const float* ta = net_ptr(d, d.target, agent, 0);
+  const float* tc0 = net_ptr(d, d.target, agent, 1);
+  const float* tc1 = net_ptr(d, d.target, agent, 2);
+  LayerPre<MT> pre;
+  pre.load(ta, d.actor, wave, lane);
   const HpDev hp = d.hp[agent];
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
+  stage_head(v_aw3, ta + d.actor.w3, d.A, tid);
+  stage_vector(v_ab3, ta + d.actor.b3, d.A, tid);
+  stage_vector(v_cw3, tc0 + d.critic.w3, kH, tid);
+  stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
+  if (tid < 2) v_cb3[tid] = (tid == 0 ? tc0 : tc1)[d.critic.b3];
+  load_input<R>(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
+  __syncthreads();
 
-  load_input<R>(Xs, rows, d.row, d.D + 2, d.O, R, tid);
+  first_layer<MT>(Xs, L.xld, ta, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
-  const float* ta = net_ptr(d, d.target, agent, 0);
-  first_layer<MT>(Xs, d.O, ta + d.actor.w1, ta + d.actor.b1, buf, nullptr, wave, lane);
+  hidden_layer<MT>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
-  hidden_layer<MT>(buf, ta + d.actor.w2, ta + d.actor.b2, buf, nullptr, wave, lane);
-  __syncthreads();
-  thin_dot<R, true>(buf, ta + d.actor.w3, d.A, head, tid);
+  thin_dot<R>(buf, v_aw3, d.A, head, tid);
   __syncthreads();
   for (int e = tid; e < R * d.A; e += kThreads) {
     const int r = e / d.A, j = e - r * d.A;
-    const float mu = tanhf(head[r * kMaxAct + j] + ta[d.actor.b3 + j]);
+    const float mu = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
     const uint32_t el = (uint32_t)((r0 + r) * d.A + j);
     const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, el >> 2, t, kStreamSmooth, 0u);
     float n4[4];
     normals4(blk, n4);
-    const float noise = fminf(fmaxf(hp.policy_noise * ((el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0])), -hp.noise_clip), hp.noise_clip);
+    const float n = (el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0]);
+    const float noise = fminf(fmaxf(hp.policy_noise * n, -hp.noise_clip), hp.noise_clip);
     const float at = fminf(fmaxf(mu + noise, -1.0f), 1.0f);
-    Xs[r * kXld + d.O + j] = at;
+    Xs[r * L.xld + d.O + j] = at;
     d.atilde[((size_t)agent * d.B + r0 + r) * d.A + j] = at;
   }
   __syncthreads();
 
+#pragma unroll
   for (int k = 0; k < 2; ++k) {
-    const float* tc = net_ptr(d, d.target, agent, 1 + k);
-    first_layer<MT>(Xs, d.D, tc + d.critic.w1, tc + d.critic.b1, buf, nullptr, wave, lane);
+    const float* tc = k == 0 ? tc0 : tc1;
+    first_layer<MT>(Xs, L.xld, tc, d.critic, pre, buf, nullptr, wave, lane);
     __syncthreads();
-    hidden_layer<MT>(buf, tc + d.critic.w2, tc + d.critic.b2, buf, nullptr, wave, lane);
+    hidden_layer<MT>(buf, tc, d.critic, pre, nullptr, wave, lane,
+                     [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
     __syncthreads();
-    thin_dot<R, false>(buf, tc + d.critic.w3, 1, head, tid);
+    thin_dot<R>(buf, v_cw3 + k * kH, 1, head, tid);
     __syncthreads();
     if (tid < R) {
-      const float q = head[tid * kMaxAct] + tc[d.critic.b3];
+      const float q = head[tid * kMaxAct] + v_cb3[k];
       qmin[tid] = k == 0 ? q : fminf(qmin[tid], q);
     }
     __syncthreads();
@@ -182,34 +236,46 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
 // partial sums of dW3, db3, db2, db1 and of the loss.
 template <int MT>
 __global__ __launch_bounds__(kThreads) void k_critic(PopDev d, uint32_t t) {
-  using L = Lds<MT, 1>;
-  constexpr int R = L::R;
+  constexpr int R = 32 * MT;
   extern __shared__ float lds[];
-  float* Xs = lds + L::x_off;
-  float* buf = lds + L::a_off;
-  float* head = lds + L::s0_off;
-  float* dq = lds + L::s1_off;
+  const Lds<MT> L(d.D);
+  float* Xs = lds;
+  float* buf = lds + L.buf;
+  float* head = lds + L.s0;
+  float* dq = lds + L.s1;
+  float* v_w3 = lds + L.vec;                         // [256]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int net, chunk;
   if (!decode_block(blockIdx.x, 2 * d.P, d.chunks, net, chunk)) return;
   const int agent = net >> 1, k = net & 1, r0 = chunk * R;
-  const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const float* cn = net_ptr(d, d.theta, agent, 1 + k);
+  LayerPre<MT> pre;
+  pre.load(cn, d.critic, wave, lane);
+  const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)net * d.B + r0) * kH;
   float* part = d.cpart + ((size_t)net * d.chunks + chunk) * kCPart;
+  stage_vector(v_w3, cn + d.critic.w3, kH, tid);
+  load_input<R>(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
+  float yv = 0.0f, b3 = 0.0f;
+  if (tid < R) { yv = d.y[(size_t)agent * d.B + r0 + tid]; b3 = cn[d.critic.b3]; }
+  POP_MARK(0);
+  __syncthreads();
+  POP_MARK(1);
 
-  load_input<R>(Xs, rows, d.row, 0, d.D, R, tid);
+  const uint64_t mask1 = first_layer<MT>(Xs, L.xld, cn, d.critic, pre, buf, d.cH1 + act_off, wave, lane);
   __syncthreads();
-  const uint64_t mask1 = first_layer<MT>(Xs, d.D, cn + d.critic.w1, cn + d.critic.b1, buf, d.cH1 + act_off, wave, lane);
+  POP_MARK(2);
+  WeightBlock<MT, true> wt;                          // block 0 of W2 for the input-gradient product
+  hidden_layer<MT>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
   __syncthreads();
-  hidden_layer<MT>(buf, cn + d.critic.w2, cn + d.critic.b2, buf, nullptr, wave, lane);
+  POP_MARK(3);
+  thin_dot<R>(buf, v_w3, 1, head, tid);
   __syncthreads();
-  thin_dot<R, false>(buf, cn + d.critic.w3, 1, head, tid);
-  __syncthreads();
+  POP_MARK(4);
   if (tid < 64) {                                   // R <= 64: one wavefront covers the chunk
     float err = 0.0f, g = 0.0f;
     if (tid < R) {
-      err = head[tid * kMaxAct] + cn[d.critic.b3] - d.y[(size_t)agent * d.B + r0 + tid];
+      err = head[tid * kMaxAct] + b3 - yv;
       g = 2.0f * err / (float)d.B;
       dq[tid] = g;
     }
@@ -220,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void k_critic(PopDev d, uint32_t t) {
   __syncthreads();
   {                                                 // one thread per hidden unit, 8 rows at a time
     const int c = tid;
-    const float w3 = cn[d.critic.w3 + c];
+    const float w3 = v_w3[c];
     float gw3 = 0.0f, gb2 = 0.0f;
     float* zg = d.cdZ2 + act_off + c;
 #pragma unroll 1
@@ -233,15 +299,18 @@ __global__ __launch_bounds__(kThreads) void k_critic(PopDev d, uint32_t t) {
         gw3 += h[i] * g[i];
         const float z = h[i] > 0.0f ? g[i] * w3 : 0.0f;
         buf[(rb + i) * kLda + c] = z;
-        zg[(size_t)(rb + i) * kH] = z;
+        zg[(rb + i) * kH] = z;
         gb2 += z;
       }
     }
     part[kCP_dW3 + c] = gw3;
     part[kCP_db2 + c] = gb2;
   }
+  POP_MARK(5);
   __syncthreads();
-  input_grad_to_global<MT>(buf, cn + d.critic.w2, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
+  POP_MARK(6);
+  input_grad_to_global<MT>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
+  POP_MARK(7);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -250,75 +319,94 @@ __global__ __launch_bounds__(kThreads) void k_critic(PopDev d, uint32_t t) {
 //   Critic 1: dz2c = -(1/B) W3c^T * [c2 > 0]; dz1c = (dz2c W2c^T) * [c1 > 0];
 //             da = dz1c W1c[O:O+A, :]^T
 //   Actor:    dz3 = da (1 - a_pi^2); dz2 = (dz3 W3^T) * [h2 > 0]; dz1 = (dz2 W2^T) * [h1 > 0]
+// The actor's second hidden layer has to survive the critic pass: it is parked in
+// global memory (L2) and fetched back into registers under the critic's last product.
 template <int MT>
 __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
-  using L = Lds<MT, 2>;
-  constexpr int R = L::R;
+  constexpr int R = 32 * MT;
   extern __shared__ float lds[];
-  float* Xs = lds + L::x_off;
-  float* bufA = lds + L::a_off;
-  float* bufB = lds + L::b_off;
-  float* head = lds + L::s0_off;
-  float* api = lds + L::s1_off;
-  float* dz3 = lds + L::s2_off;
+  const Lds<MT> L(d.D);
+  float* Xs = lds;
+  float* buf = lds + L.buf;
+  float* head = lds + L.s0;
+  float* api = lds + L.s1;
+  float* dz3 = lds + L.s2;
+  const int A = d.A;
+  float* v_aw3 = lds + L.vec;                        // [A][256] actor head
+  float* v_ab3 = v_aw3 + kH * A;                     // [8]
+  float* v_cw3 = v_ab3 + 8;                          // [256] critic head
+  float* v_cwa = v_cw3 + kH;                         // [A][256] critic first-layer rows of the action inputs
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int agent, chunk;
   if (!decode_block(blockIdx.x, d.P, d.chunks, agent, chunk)) return;
   const int r0 = chunk * R;
   const HpDev hp = d.hp[agent];
   if (t % (uint32_t)hp.policy_delay != 0u) return;
-  const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const float* an = net_ptr(d, d.theta, agent, 0);
   const float* cn = net_ptr(d, d.theta, agent, 1);
+  LayerPre<MT> pre;
+  pre.load(an, d.actor, wave, lane);
+  const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)agent * d.B + r0) * kH;
   float* part = d.apart + ((size_t)agent * d.chunks + chunk) * kAPart;
-  const int A = d.A;
+  stage_head(v_aw3, an + d.actor.w3, A, tid);
+  stage_vector(v_ab3, an + d.actor.b3, A, tid);
+  stage_vector(v_cw3, cn + d.critic.w3, kH, tid);
+  stage_vector(v_cwa, cn + d.critic.w1 + d.O * kH, A * kH, tid);
+  const float cb3 = cn[d.critic.b3];
+  load_input<R>(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
+  __syncthreads();
 
-  load_input<R>(Xs, rows, d.row, 0, d.O, R, tid);
+  const uint64_t mask_a1 = first_layer<MT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
   __syncthreads();
-  const uint64_t mask_a1 = first_layer<MT>(Xs, d.O, an + d.actor.w1, an + d.actor.b1, bufA, d.aH1 + act_off, wave, lane);
+  hidden_layer<MT>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane, [&]() { pre.load(cn, d.critic, wave, lane); });
   __syncthreads();
-  hidden_layer<MT>(bufA, an + d.actor.w2, an + d.actor.b2, bufB, nullptr, wave, lane);   // bufB = h2 of the actor
-  __syncthreads();
-  thin_dot<R, true>(bufB, an + d.actor.w3, A, head, tid);
+  thin_dot<R>(buf, v_aw3, A, head, tid);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
     const int r = e / A, j = e - r * A;
-    const float a = tanhf(head[r * kMaxAct + j] + an[d.actor.b3 + j]);
+    const float a = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
     api[r * kMaxAct + j] = a;
-    Xs[r * kXld + d.O + j] = a;
+    Xs[r * L.xld + d.O + j] = a;
   }
   __syncthreads();
 
   // critic 1 on [s, a_pi]
-  const uint64_t mask_c1 = first_layer<MT>(Xs, d.D, cn + d.critic.w1, cn + d.critic.b1, bufA, nullptr, wave, lane);
+  const uint64_t mask_c1 = first_layer<MT>(Xs, L.xld, cn, d.critic, pre, buf, nullptr, wave, lane);
   __syncthreads();
-  hidden_layer<MT>(bufA, cn + d.critic.w2, cn + d.critic.b2, bufA, nullptr, wave, lane);
+  WeightBlock<MT, true> wt;
+  hidden_layer<MT>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
   __syncthreads();
-  thin_dot<R, false>(bufA, cn + d.critic.w3, 1, head, tid);     // q, for the loss value only
+  thin_dot<R>(buf, v_cw3, 1, head, tid);     // q, for the loss value only
   __syncthreads();
   if (tid < 64) {
-    const float q = tid < R ? head[tid * kMaxAct] + cn[d.critic.b3] : 0.0f;
+    const float q = tid < R ? head[tid * kMaxAct] + cb3 : 0.0f;
     const float s = wave_sum(q);
     if (tid == 0) part[kAP_loss] = -s / (float)d.B;
   }
   {
     const int c = tid;
-    const float seed = -cn[d.critic.w3 + c] / (float)d.B;
+    const float seed = -v_cw3[c] / (float)d.B;
 #pragma unroll 1
     for (int rb = 0; rb < R; rb += 8) {
       float h[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) h[i] = bufA[(rb + i) * kLda + c];
+      for (int i = 0; i < 8; ++i) h[i] = buf[(rb + i) * kLda + c];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) bufA[(rb + i) * kLda + c] = h[i] > 0.0f ? seed : 0.0f;
+      for (int i = 0; i < 8; ++i) buf[(rb + i) * kLda + c] = h[i] > 0.0f ? seed : 0.0f;
     }
   }
   __syncthreads();
+  f32x4 h2r[R / 4];                                  // this thread's share of the parked h2 tile
   {
     Acc<MT> acc;
     acc.zero();
-    gemm256<MT, true>(bufA, kLda, cn + d.critic.w2, wave, lane, acc);
+    const float* h2g = d.aH2 + act_off;
+    gemm256<MT, true>(buf, kLda, cn + d.critic.w2, wt, wave, lane, acc, [&]() {
+#pragma unroll
+      for (int i = 0; i < R / 4; ++i)
+        h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
+    });
     __syncthreads();                                 // every wavefront is done reading dz2 of the critic
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -326,17 +414,21 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
       for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-          bufA[(32 * mt + acc_row(v, lane)) * kLda + 64 * wave + 32 * nt + (lane & 31)] =
+          buf[(32 * mt + acc_row(v, lane)) * kLda + 64 * wave + 32 * nt + (lane & 31)] =
               mask_bit(mask_c1, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;      // dz1 of the critic
   }
   __syncthreads();
-  thin_dot<R, false>(bufA, cn + d.critic.w1 + (size_t)d.O * kH, A, head, tid);   // da
+  thin_dot<R>(buf, v_cwa, A, head, tid);      // da
+  wt.load(an + d.actor.w2, 0, wave, lane);           // block 0 of the actor's input-gradient product
   __syncthreads();
   for (int e = tid; e < R * kMaxAct; e += kThreads) {
     const int j = e % kMaxAct;
     const float a = j < A ? api[e] : 0.0f;
     dz3[e] = j < A ? head[e] * (1.0f - a * a) : 0.0f;     // unused columns are kept at zero
   }
+#pragma unroll
+  for (int i = 0; i < R / 4; ++i)                    // h2 of the actor back into the tile
+    *reinterpret_cast<f32x4*>(&buf[(4 * i + (tid >> 6)) * kLda + 4 * (tid & 63)]) = h2r[i];
   __syncthreads();
   if (tid < A) {
     float s = 0.0f;
@@ -347,7 +439,7 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
     const int c = tid;
     float w3[kMaxAct], gw3[kMaxAct];
 #pragma unroll
-    for (int j = 0; j < kMaxAct; ++j) { w3[j] = j < A ? an[d.actor.w3 + c * A + j] : 0.0f; gw3[j] = 0.0f; }
+    for (int j = 0; j < kMaxAct; ++j) { w3[j] = j < A ? v_aw3[j * kH + c] : 0.0f; gw3[j] = 0.0f; }
     float gb2 = 0.0f;
     float* zg = d.adZ2 + act_off + c;
 #pragma unroll 1
@@ -356,7 +448,7 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
       f32x4 g[4][2];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        h[i] = bufB[(rb + i) * kLda + c];
+        h[i] = buf[(rb + i) * kLda + c];
         g[i][0] = *reinterpret_cast<const f32x4*>(&dz3[(rb + i) * kMaxAct]);      // columns >= A hold zeros
         g[i][1] = *reinterpret_cast<const f32x4*>(&dz3[(rb + i) * kMaxAct + 4]);
       }
@@ -370,8 +462,8 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
           dh += gj * w3[j];
         }
         const float z = h[i] > 0.0f ? dh : 0.0f;
-        bufB[(rb + i) * kLda + c] = z;
-        zg[(size_t)(rb + i) * kH] = z;
+        buf[(rb + i) * kLda + c] = z;
+        zg[(rb + i) * kH] = z;
         gb2 += z;
       }
     }
@@ -381,73 +473,87 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
     part[kAP_db2 + c] = gb2;
   }
   __syncthreads();
-  input_grad_to_global<MT>(bufB, an + d.actor.w2, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  input_grad_to_global<MT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Acting: act[agent][r] = pi_agent(obs[agent][r]).  grid (ceil(n / 32), P).
 __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restrict__ obs, int n,
                                                   float* __restrict__ act) {
-  using L = Lds<1, 1>;
-  constexpr int R = L::R;
+  constexpr int R = 32;
   extern __shared__ float lds[];
-  float* Xs = lds + L::x_off;
-  float* buf = lds + L::a_off;
-  float* head = lds + L::s0_off;
+  const Lds<1> L(d.O);
+  float* Xs = lds;
+  float* buf = lds + L.buf;
+  float* head = lds + L.s0;
+  float* v_aw3 = lds + L.vec;
+  float* v_ab3 = v_aw3 + kH * d.A;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int agent = blockIdx.y, r0 = blockIdx.x * R;
   const int valid = n - r0 < R ? n - r0 : R;
   const float* an = net_ptr(d, d.theta, agent, 0);
-  load_input<R>(Xs, obs + ((size_t)agent * n + r0) * d.O, d.O, 0, d.O, valid, tid);
+  LayerPre<1> pre;
+  pre.load(an, d.actor, wave, lane);
+  stage_head(v_aw3, an + d.actor.w3, d.A, tid);
+  stage_vector(v_ab3, an + d.actor.b3, d.A, tid);
+  load_input<R>(Xs, L.xld, obs + ((size_t)agent * n + r0) * d.O, d.O, 0, d.O, valid, tid);
   __syncthreads();
-  first_layer<1>(Xs, d.O, an + d.actor.w1, an + d.actor.b1, buf, nullptr, wave, lane);
+  first_layer<1>(Xs, L.xld, an, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
-  hidden_layer<1>(buf, an + d.actor.w2, an + d.actor.b2, buf, nullptr, wave, lane);
+  hidden_layer<1>(buf, an, d.actor, pre, nullptr, wave, lane, NoTail());
   __syncthreads();
-  thin_dot<R, true>(buf, an + d.actor.w3, d.A, head, tid);
+  thin_dot<R>(buf, v_aw3, d.A, head, tid);
   __syncthreads();
   for (int e = tid; e < valid * d.A; e += kThreads) {
     const int r = e / d.A, j = e - r * d.A;
-    act[((size_t)agent * n + r0 + r) * d.A + j] = tanhf(head[r * kMaxAct + j] + an[d.actor.b3 + j]);
+    act[((size_t)agent * n + r0 + r) * d.A + j] = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
   }
 }
 
 // ---------------------------------------------------------------------------------------------
+namespace {
+int vec_target(const PopDev& d) { return kH * d.A + 8 + 2 * kH + 8; }
+int vec_critic(const PopDev&) { return kH + 8; }
+int vec_actor(const PopDev& d) { return kH * d.A + 8 + kH + d.A * kH; }
+int vec_act(const PopDev& d) { return kH * d.A + 8; }
+}  // namespace
+
 hipError_t setup_kernels() {
   hipError_t e;
-#define POP_SET_LDS(fn, bytes)                                                                       \
-  if ((e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(bytes))) != hipSuccess) return e
-  POP_SET_LDS(k_target<1>, (Lds<1, 1>::bytes));
-  POP_SET_LDS(k_target<2>, (Lds<2, 1>::bytes));
-  POP_SET_LDS(k_critic<1>, (Lds<1, 1>::bytes));
-  POP_SET_LDS(k_critic<2>, (Lds<2, 1>::bytes));
-  POP_SET_LDS(k_actor<1>, (Lds<1, 2>::bytes));
-  POP_SET_LDS(k_actor<2>, (Lds<2, 2>::bytes));
-  POP_SET_LDS(k_act, (Lds<1, 1>::bytes));
+  const int most = 160 * 1024;                        // whole LDS of a CU; the launches ask for what they need
+#define POP_SET_LDS(fn)                                                                                    \
+  if ((e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, most)) != hipSuccess) return e
+  POP_SET_LDS(k_target<1>);
+  POP_SET_LDS(k_target<2>);
+  POP_SET_LDS(k_critic<1>);
+  POP_SET_LDS(k_critic<2>);
+  POP_SET_LDS(k_actor<1>);
+  POP_SET_LDS(k_actor<2>);
+  POP_SET_LDS(k_act);
 #undef POP_SET_LDS
   return hipSuccess;
 }
 
 hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.chunks));
-  if (d.mt == 2) k_target<2><<<grid, dim3(kThreads), Lds<2, 1>::bytes, s>>>(d, t);
-  else k_target<1><<<grid, dim3(kThreads), Lds<1, 1>::bytes, s>>>(d, t);
+  if (d.mt == 2) k_target<2><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_target(d)), s>>>(d, t);
+  else k_target<1><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_critic(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(2 * d.P, d.chunks));
-  if (d.mt == 2) k_critic<2><<<grid, dim3(kThreads), Lds<2, 1>::bytes, s>>>(d, t);
-  else k_critic<1><<<grid, dim3(kThreads), Lds<1, 1>::bytes, s>>>(d, t);
+  if (d.mt == 2) k_critic<2><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_critic(d)), s>>>(d, t);
+  else k_critic<1><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.chunks));
-  if (d.mt == 2) k_actor<2><<<grid, dim3(kThreads), Lds<2, 2>::bytes, s>>>(d, t);
-  else k_actor<1><<<grid, dim3(kThreads), Lds<1, 2>::bytes, s>>>(d, t);
+  if (d.mt == 2) k_actor<2><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  else k_actor<1><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, hipStream_t s) {
-  k_act<<<dim3((n + 31) / 32, d.P), dim3(kThreads), Lds<1, 1>::bytes, s>>>(d, obs, n, act);
+  k_act<<<dim3((n + 31) / 32, d.P), dim3(kThreads), Lds<1>(d.O).bytes(vec_act(d)), s>>>(d, obs, n, act);
   return hipGetLastError();
 }
 

@@ -4,30 +4,32 @@
 // hyperparametrization, i.e. Adam and soft target updates).
 //
 // The gradient of a weight matrix is dW = X^T dZ with the batch as the
-// contraction index.  A workgroup walks the batch in stages of 32 rows: the
-// slices of X and dZ it needs (written by the chain kernels) are fetched with
-// coalesced 16-byte loads into registers one stage ahead, parked in a
-// double-buffered LDS tile, and each wavefront feeds its 32x32 MFMA tile of dW
-// from there.  The wavefront then updates exactly the parameters of its tile:
+// contraction index.  A workgroup owns a slab of 32 rows of dW (all 256
+// columns): it first transposes its 32 columns of X (written by the chain
+// kernels) into an LDS tile [32][batch], and then runs the same pipelined
+// 256-deep MFMA product as a hidden layer, with dZ streamed from global memory
+// in the role of the weights.  Each wavefront then updates exactly the
+// parameters it holds in its accumulators:
 //     m <- b1 m + (1 - b1) g ;  v <- b2 v + (1 - b2) g^2
 //     theta <- theta - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
+//     theta' <- (1 - tau) theta' + tau theta        (only on delayed steps)
 // (the two bias corrections enter as reciprocals computed once per workgroup in
 // double; the final quotient uses the hardware reciprocal, 1 ulp)
-//     theta' <- (1 - tau) theta' + tau theta        (only on delayed steps)
 // so a gradient never makes a round trip through HBM.  The parameters, moments
-// and targets of the tile are requested before the product starts, so their
-// HBM latency is hidden behind the MFMA work.  The small tensors (biases, head
-// weights) arrive as per-chunk partial sums and are reduced and updated by one
-// extra workgroup per network.
+// and targets of the first half of the slab are requested under the last blocks
+// of the product, so their HBM latency is hidden behind the MFMA work.  The
+// small tensors (biases, head weights) arrive as per-chunk partial sums and are
+// reduced and updated by one extra workgroup per network.
 //
 // 1-D grid, decoded so that the roles of one network share an XCD (its L2 then
-// serves the re-reads of X and dZ).  Roles of one network:
-//   [0, 16)            64x64 blocks of W2 (4 wavefronts, one 32x32 tile each)
-//   [16, 16 + n1)      layer-1 weights: 32 rows x 128 columns per workgroup
-//   16 + n1            b1, b2, W3, b3 and the loss value
+// serves the re-reads of dZ).  Roles of one network:
+//   [0, 8)             32-row slabs of W2
+//   [8, 8 + n1)        32-row slabs of the layer-1 weights (rows >= fan-in masked)
+//   8 + n1             b1, b2, W3, b3 and the loss value
 // Blocks past the last network gather the replay rows of step t + 1 into the
 // other half of the double-buffered batch (App. A of the paper: the next
-// batches are fetched while the current update runs).
+// batches are fetched while the current update runs).  The batch size must be
+// 256 for the slab product (its contraction depth is fixed).
 #include "gather.h"
 #include "launch.h"
 #include "mfma_tiles.h"
@@ -42,9 +44,6 @@ struct Adam {
 };
 
 struct AdamRegs { float th, m, v, tg; };
-
-// one LDS stage: a slice of X (32 rows x up to 64 columns) and of dZ (32 rows x up to 128 columns)
-constexpr int kStageA = 32 * 64, kStageZ = 32 * 128, kStageFloats = kStageA + kStageZ;
 
 // b^n in double by repeated squaring (at most 64 roundings: far below fp32 resolution)
 __device__ inline double ipow(double b, uint32_t n) {
@@ -78,109 +77,63 @@ __device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uin
   if (a.record) gr[i] = g;
 }
 
-// One block of a weight matrix: WIDE = a 64x64 block of W2 (wavefront tiles 2x2), else a
-// 32x128 block of layer-1 weights (wavefront tiles 1x4, rows >= M masked).
-//   x: [B][ldx] layer input, z: [B][256] pre-activation gradient, both global;
-//   (m0w, n0w): block origin inside the weight matrix; base: offset of that matrix in the net.
-template <bool WIDE>
-__device__ inline void weight_block(const Adam& adam, const float* __restrict__ x, int ldx, int M, int m0w,
-                                    const float* __restrict__ z, int n0w, uint32_t base, int B, float* stage_lds,
-                                    float* __restrict__ th, float* __restrict__ mo, float* __restrict__ ve,
-                                    float* __restrict__ tg, float* __restrict__ gr, int tid) {
-  constexpr int as = WIDE ? 64 : 32, zs = WIDE ? 64 : 128;
-  const int wave = tid >> 6, lane = tid & 63;
-  const int ma = WIDE ? 32 * (wave >> 1) : 0;
-  const int na = WIDE ? 32 * (wave & 1) : 32 * wave;
-  const int m0 = m0w + ma, n0 = n0w + na;
-  const int half = lane >> 5, l32 = lane & 31;
-
-  // global -> register staging of one stage (32 batch rows)
-  f32x4 ra[2], rz[4];
-  float rs[4];
-  auto fetch = [&](int b0) {
-    if (WIDE) {
-      const int r = tid >> 4, c4 = tid & 15;
+// One 32-row slab of a weight matrix [M][256] (rows m0 .. m0+31, rows >= M masked):
+//   x: [256][ldx] layer input, z: [256][256] pre-activation gradient, both global;
+//   base: offset of the matrix inside the network's parameter block.
+__device__ inline void weight_slab(const Adam& adam, const float* __restrict__ x, int ldx, int M, int m0,
+                                   const float* __restrict__ z, uint32_t base, float* Xl,
+                                   float* __restrict__ th, float* __restrict__ mo, float* __restrict__ ve,
+                                   float* __restrict__ tg, float* __restrict__ gr, int tid) {
+  const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  WeightBlock<1, false> z0;
+  z0.load(z, 0, wave, lane);
+  {                                                  // X^T slice into LDS: thread b copies row b
+    const float* xr = x + (size_t)tid * ldx + m0;
+    if ((ldx & 3) == 0) {                            // 16-byte aligned rows (a hidden layer's output)
+      f32x4 v[8];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        ra[i] = *reinterpret_cast<const f32x4*>(x + (uint32_t)((b0 + r + 16 * i) * kH + m0w + 4 * c4));
-        rz[i] = *reinterpret_cast<const f32x4*>(z + (uint32_t)((b0 + r + 16 * i) * kH + n0w + 4 * c4));
+      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(xr + 4 * i);
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) Xl[(4 * i + q) * kLda + tid] = v[i][q];
+    } else {                                         // batch rows: any stride, columns >= M are zero
+      float v[32];
+#pragma unroll
+      for (int m = 0; m < 32; ++m) {
+        const int mm = (m0 + m) < M ? m : 0;
+        v[m] = xr[mm];
       }
-    } else {
-      const int r = tid >> 5, c = tid & 31;
-      const bool ok = (m0w + c) < M;
-      const int cc = ok ? m0w + c : M - 1;           // always a valid column: the load needs no branch
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float xv = x[(uint32_t)((b0 + r + 8 * i) * ldx + cc)];
-        rs[i] = ok ? xv : 0.0f;
-        rz[i] = *reinterpret_cast<const f32x4*>(z + (uint32_t)((b0 + r + 8 * i) * kH + n0w + 4 * c));
-      }
+      for (int m = 0; m < 32; ++m) Xl[m * kLda + tid] = (m0 + m) < M ? v[m] : 0.0f;
     }
-  };
-  auto park = [&](float* Al, float* Zl) {
-    if (WIDE) {
-      const int r = tid >> 4, c4 = tid & 15;
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        *reinterpret_cast<f32x4*>(&Al[(r + 16 * i) * as + 4 * c4]) = ra[i];
-        *reinterpret_cast<f32x4*>(&Zl[(r + 16 * i) * zs + 4 * c4]) = rz[i];
-      }
-    } else {
-      const int r = tid >> 5, c = tid & 31;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        Al[(r + 8 * i) * as + c] = rs[i];
-        *reinterpret_cast<f32x4*>(&Zl[(r + 8 * i) * zs + 4 * c]) = rz[i];
-      }
-    }
-  };
-  // flat offset of accumulator element 0 of this lane (row m0 + 4 half; for a layer-1 block that
-  // row may be beyond M: then no element of this lane with a valid row exists below it either)
-  const uint32_t elem0 = base + (uint32_t)((m0 + 4 * half) * kH + n0 + l32);
-  AdamRegs regs[16];
-  f32x16 acc;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-  const int stages = B / 32;
-  fetch(0);
-  park(stage_lds, stage_lds + kStageA);
-  __syncthreads();
-#pragma unroll 1
-  for (int st = 0; st < stages; ++st) {
-    const float* Al = stage_lds + (st & 1) * kStageFloats + half * as + ma + l32;
-    const float* Zl = stage_lds + (st & 1) * kStageFloats + kStageA + half * zs + na + l32;
-    if (st + 1 < stages) {
-      fetch(32 * (st + 1));
-    } else {                                       // last stage: start the epilogue's loads instead
-      uint32_t e0 = elem0;
-      asm volatile("" : "+v"(e0));                 // keeps the 64 addresses from being hoisted out of the loop
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const bool ok = WIDE || (m0 + acc_row(v, lane)) < M;
-        regs[v] = adam_load(adam, ok ? e0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH) : e0, th, mo, ve, tg);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    float fa[16], fz[16];
-#pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-      fa[ks] = Al[2 * ks * as];
-      fz[ks] = Zl[2 * ks * zs];
-    }
-#pragma unroll
-    for (int ks = 0; ks < 16; ++ks) acc = mfma32(fa[ks], fz[ks], acc);
-    __builtin_amdgcn_sched_barrier(0);
-    if (st + 1 < stages) {
-      float* An = stage_lds + ((st + 1) & 1) * kStageFloats;
-      park(An, An + kStageA);
-    }
-    __syncthreads();
   }
+  __syncthreads();
+  // flat offset of accumulator element (nt = 0, v = 0) of this lane
+  const uint32_t elem0 = base + (uint32_t)((m0 + 4 * half) * kH + 64 * wave + l32);
+  AdamRegs regs[16];
+  auto preload = [&](int nt) {
+    uint32_t e0 = elem0 + 32u * nt;
+    asm volatile("" : "+v"(e0));                     // keeps the addresses from being hoisted far ahead
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    if (WIDE || (m0 + acc_row(v, lane)) < M)
-      adam_store(adam, regs[v], acc[v], elem0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH), th, mo, ve, tg, gr);
-    if ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+    for (int v = 0; v < 16; ++v) {
+      const bool ok = (m0 + acc_row(v, lane)) < M;
+      regs[v] = adam_load(adam, ok ? e0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH) : e0, th, mo, ve, tg);
+    }
+  };
+  Acc<1> acc;
+  acc.zero();
+  gemm256<1, false>(Xl, kLda, z, z0, wave, lane, acc, [&]() { preload(0); });
+#pragma unroll
+  for (int nt = 0; nt < 2; ++nt) {
+    if (nt == 1) preload(1);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if ((m0 + acc_row(v, lane)) < M)
+        adam_store(adam, regs[v], acc.t[0][nt][v], elem0 + 32u * nt + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH),
+                   th, mo, ve, tg, gr);
+      if ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+    }
   }
 }
 
@@ -189,7 +142,7 @@ __device__ inline void weight_block(const Adam& adam, const float* __restrict__ 
 __global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
                                                           int roles, int prefetch) {
   __shared__ Adam sh_adam;
-  __shared__ __attribute__((aligned(16))) float stage_lds[2 * kStageFloats];
+  __shared__ __attribute__((aligned(16))) float xt_lds[32 * kLda];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   if ((int)blockIdx.x >= main_blocks) {              // gather role: rows of the next step
     if (prefetch) {
@@ -229,18 +182,15 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, i
   float* tg = net_ptr(d, d.target, agent, net);
   float* gr = net_ptr(d, d.grad, agent, net);
 
-  const int n1 = 2 * ((L.in + 31) / 32);
-  if (role < 16 + n1) {
+  const int n1 = (L.in + 31) / 32;
+  if (role < 8 + n1) {
     const size_t o = (size_t)unit * d.B * kH;        // unit = agent (actor) or network (critics)
-    if (role < 16) {
-      weight_block<true>(adam, (actor_phase ? d.aH1 : d.cH1) + o, kH, kH, 64 * (role >> 2),
-                         (actor_phase ? d.adZ2 : d.cdZ2) + o, 64 * (role & 3), (uint32_t)L.w2, d.B, stage_lds,
-                         th, mo, ve, tg, gr, tid);
-    } else {
-      const int q = role - 16;                       // layer-1 input = leading columns of the batch rows
-      weight_block<false>(adam, batch_rows(d, t, agent), d.row, L.in, 32 * (q >> 1),
-                          (actor_phase ? d.adZ1 : d.cdZ1) + o, 128 * (q & 1), (uint32_t)L.w1, d.B, stage_lds,
-                          th, mo, ve, tg, gr, tid);
+    if (role < 8) {
+      weight_slab(adam, (actor_phase ? d.aH1 : d.cH1) + o, kH, kH, 32 * role, (actor_phase ? d.adZ2 : d.cdZ2) + o,
+                  (uint32_t)L.w2, xt_lds, th, mo, ve, tg, gr, tid);
+    } else {                                         // layer-1 input = leading columns of the batch rows
+      weight_slab(adam, batch_rows(d, t, agent), d.row, L.in, 32 * (role - 8), (actor_phase ? d.adZ1 : d.cdZ1) + o,
+                  (uint32_t)L.w1, xt_lds, th, mo, ve, tg, gr, tid);
     }
   } else {
     // small tensors from per-chunk partial sums; thread c owns hidden unit c
@@ -286,7 +236,7 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, i
 
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s) {
   const NetLayout& L = actor_phase ? d.actor : d.critic;
-  const int roles = 16 + 2 * ((L.in + 31) / 32) + 1;
+  const int roles = 8 + (L.in + 31) / 32 + 1;
   const int main_blocks = xcd_grid(actor_phase ? d.P : 2 * d.P, roles);
   const int extra = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
   hipLaunchKernelGGL(k_wgrad_adam, dim3(main_blocks + extra), dim3(kThreads), 0, s, d, t, actor_phase, main_blocks,

@@ -63,18 +63,54 @@ __device__ inline void for_each_acc(const Acc<MT>& acc, int wave, int lane, F f)
         f(32 * mt + acc_row(v, lane), 64 * wave + 32 * nt + (lane & 31), acc.t[mt][nt][v]);
 }
 
-// acc[r][c] += sum_{k<K} X[r][k] W[k][c]   (forward product x W), small K.
+// First-layer weights of one lane for the leading 32 rows of W (k = 8 i + 4 half + j),
+// fetched ahead of time so that the product does not wait for memory.
+struct SmallW {
+  float w[4][2][4];
+  __device__ inline void load(const float* __restrict__ W, int K, int wave, int lane) {
+    const int half = lane >> 5, l32 = lane & 31;
+    const float* wcol = W + 64 * wave + l32;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = 8 * i + 4 * half + j;
+        const int kk = k < K ? k : 0;                 // always a valid row: the load needs no branch
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          const float v = wcol[kk * kH + 32 * nt];
+          w[i][nt][j] = k < K ? v : 0.0f;
+        }
+      }
+  }
+};
+
+// acc[r][c] += sum_{k<K} X[r][k] W[k][c]   (forward product x W) for a small fan-in K.
 //   X: LDS, row stride ldx, rows [0, 32 MT); columns >= K up to the next
 //      multiple of 8 must hold finite values (they meet zero weights);
-//   W: global, row-major [K][256].  Used for the first layers (K = obs or
-//   obs + act, a few k-steps only), so it is not software-pipelined.
+//   W: global, row-major [K][256]; `pre` holds its first 32 rows already.
 template <int MT>
 __device__ inline void gemm_xw_small(const float* __restrict__ Xl, int ldx, int K, const float* __restrict__ W,
-                                     int wave, int lane, Acc<MT>& acc) {
+                                     const SmallW& pre, int wave, int lane, Acc<MT>& acc) {
   const int half = lane >> 5, l32 = lane & 31;
-  const float* wcol = W + 64 * wave + l32;
   const int K8 = (K + 7) & ~7;
-  for (int k0 = 0; k0 < K8; k0 += 8) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (8 * i < K8) {
+      f32x4 a[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        a[mt] = *reinterpret_cast<const f32x4*>(&Xl[(32 * mt + l32) * ldx + 8 * i + 4 * half]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], pre.w[i][nt][j], acc.t[mt][nt]);
+    }
+  }
+  const float* wcol = W + 64 * wave + l32;
+  for (int k0 = 32; k0 < K8; k0 += 8) {              // fan-in beyond 32: plain loop
     float b[2][4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -96,43 +132,47 @@ __device__ inline void gemm_xw_small(const float* __restrict__ Xl, int ldx, int 
 }
 
 // Software-pipelined 256-deep contraction of an LDS operand with a global weight
-// operand; the contraction index is walked in 8 blocks of 32.
+// operand; the contraction index is walked in 16 blocks of 16.
 //   forward  (TRANSPOSED = false): acc[r][c] += sum_k X[r][k] W[k][c], c in this wave's 64 columns
 //   backward (TRANSPOSED = true):  acc[r][k] += sum_n Z[r][n] W[k][n], k in this wave's 64 columns
-// W is row-major [256][256] in both cases.  The weight registers of block i+1
-// are requested from memory before the MFMAs of block i start (about 2000 MT
-// cycles of matrix work hide the L2 / memory latency); the LDS operand is
-// fetched half a block ahead.  __builtin_amdgcn_sched_barrier keeps the
-// compiler from sinking the loads back next to their uses.
+// W is row-major [256][256] in both cases.  Weight registers rotate through four
+// buffers: block j+3 is requested from memory before the MFMAs of block j start,
+// so about 3000 MT cycles of matrix work cover the L2 / memory latency; the LDS
+// operand is fetched one block ahead.  Block 0 is passed in by the caller, who
+// requests it as early as it can (typically under the previous product);
+// `tail()` runs once no further weight block of this product is needed, so the
+// caller can start the loads of the next layer under the last three blocks.
+// __builtin_amdgcn_sched_barrier keeps the compiler from sinking loads back next
+// to their uses.
 template <int MT, bool TRANSPOSED>
-struct WeightBlock {                       // the weights one lane needs for a 32-deep block
-  float w[2][16];                          // [column tile][4 s + j]  <->  index 32 i + 8 s + 4 half + j
+struct WeightBlock {                       // the weights one lane needs for a 16-deep block
+  float w[2][8];                           // [column tile][4 s + j]  <->  index 16 i + 8 s + 4 half + j
   __device__ inline void load(const float* __restrict__ W, int i, int wave, int lane) {
     const int half = lane >> 5, l32 = lane & 31;
     if (TRANSPOSED) {
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt) {
-        const float* row = W + (size_t)(64 * wave + 32 * nt + l32) * kH + 32 * i + 4 * half;
+        const float* row = W + (64 * wave + 32 * nt + l32) * kH + 16 * i + 4 * half;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int s = 0; s < 2; ++s) {
           const f32x4 v = *reinterpret_cast<const f32x4*>(row + 8 * s);
           w[nt][4 * s + 0] = v[0]; w[nt][4 * s + 1] = v[1]; w[nt][4 * s + 2] = v[2]; w[nt][4 * s + 3] = v[3];
         }
       }
     } else {
-      const float* col = W + (size_t)(32 * i + 4 * half) * kH + 64 * wave + l32;
+      const float* col = W + (16 * i + 4 * half) * kH + 64 * wave + l32;
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
+      for (int s = 0; s < 2; ++s)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-          for (int nt = 0; nt < 2; ++nt) w[nt][4 * s + j] = col[(size_t)(8 * s + j) * kH + 32 * nt];
+          for (int nt = 0; nt < 2; ++nt) w[nt][4 * s + j] = col[(8 * s + j) * kH + 32 * nt];
     }
   }
 };
 
 template <int MT>
-struct LdsHalf {                           // the LDS operand of half a block (16 deep)
+struct LdsBlock {                          // the LDS operand of one block (16 deep)
   f32x4 a[MT][2];
   __device__ inline void load(const float* __restrict__ Xl, int ldx, int k0, int lane) {
     const int half = lane >> 5, l32 = lane & 31;
@@ -145,7 +185,7 @@ struct LdsHalf {                           // the LDS operand of half a block (1
 };
 
 template <int MT, bool TRANSPOSED>
-__device__ inline void mfma_half(const LdsHalf<MT>& x, const WeightBlock<MT, TRANSPOSED>& b, int h, Acc<MT>& acc) {
+__device__ inline void mfma_block(const LdsBlock<MT>& x, const WeightBlock<MT, TRANSPOSED>& b, Acc<MT>& acc) {
 #pragma unroll
   for (int s = 0; s < 2; ++s)
 #pragma unroll
@@ -154,51 +194,67 @@ __device__ inline void mfma_half(const LdsHalf<MT>& x, const WeightBlock<MT, TRA
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
-          acc.t[mt][nt] = mfma32(x.a[mt][s][j], b.w[nt][4 * (2 * h + s) + j], acc.t[mt][nt]);
+          acc.t[mt][nt] = mfma32(x.a[mt][s][j], b.w[nt][4 * s + j], acc.t[mt][nt]);
 }
 
-template <int MT, bool TRANSPOSED>
-__device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const float* __restrict__ W, int wave,
-                               int lane, Acc<MT>& acc) {
-  WeightBlock<MT, TRANSPOSED> b0, b1;
-  LdsHalf<MT> x0, x1;
-  b0.load(W, 0, wave, lane);
+struct NoTail { __device__ inline void operator()() const {} };
+
+// four blocks i .. i+3 of the product; LAST: no further weight blocks exist, run tail() instead
+template <int MT, bool TRANSPOSED, bool LAST, class Tail>
+__device__ inline void gemm256_group(const float* __restrict__ Xl, int ldx, const float* __restrict__ W, int i,
+                                     WeightBlock<MT, TRANSPOSED>& b0, WeightBlock<MT, TRANSPOSED>& b1,
+                                     WeightBlock<MT, TRANSPOSED>& b2, WeightBlock<MT, TRANSPOSED>& b3,
+                                     LdsBlock<MT>& x0, LdsBlock<MT>& x1, int wave, int lane, Acc<MT>& acc,
+                                     Tail& tail) {
+  b3.load(W, i + 3, wave, lane);
+  x1.load(Xl, ldx, 16 * (i + 1), lane);
+  __builtin_amdgcn_sched_barrier(0);
+  mfma_block<MT, TRANSPOSED>(x0, b0, acc);
+  __builtin_amdgcn_sched_barrier(0);
+  if (!LAST) b0.load(W, i + 4, wave, lane); else tail();
+  x0.load(Xl, ldx, 16 * (i + 2), lane);
+  __builtin_amdgcn_sched_barrier(0);
+  mfma_block<MT, TRANSPOSED>(x1, b1, acc);
+  __builtin_amdgcn_sched_barrier(0);
+  if (!LAST) b1.load(W, i + 5, wave, lane);
+  x1.load(Xl, ldx, 16 * (i + 3), lane);
+  __builtin_amdgcn_sched_barrier(0);
+  mfma_block<MT, TRANSPOSED>(x0, b2, acc);
+  __builtin_amdgcn_sched_barrier(0);
+  if (!LAST) { b2.load(W, i + 6, wave, lane); x0.load(Xl, ldx, 16 * (i + 4), lane); }
+  __builtin_amdgcn_sched_barrier(0);
+  mfma_block<MT, TRANSPOSED>(x1, b3, acc);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int MT, bool TRANSPOSED, class Tail>
+__device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const float* __restrict__ W,
+                               WeightBlock<MT, TRANSPOSED>& b0, int wave, int lane, Acc<MT>& acc, Tail tail) {
+  WeightBlock<MT, TRANSPOSED> b1, b2, b3;
+  LdsBlock<MT> x0, x1;
+  b1.load(W, 1, wave, lane);
+  b2.load(W, 2, wave, lane);
   x0.load(Xl, ldx, 0, lane);
+  POP_MARK(20);
 #pragma unroll 1
-  for (int i = 0; i < 8; i += 2) {
-    b1.load(W, i + 1, wave, lane);
-    x1.load(Xl, ldx, 32 * i + 16, lane);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_half<MT, TRANSPOSED>(x0, b0, 0, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    x0.load(Xl, ldx, 32 * i + 32, lane);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_half<MT, TRANSPOSED>(x1, b0, 1, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    if (i + 2 < 8) b0.load(W, i + 2, wave, lane);
-    x1.load(Xl, ldx, 32 * i + 48, lane);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_half<MT, TRANSPOSED>(x0, b1, 0, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    if (i + 2 < 8) x0.load(Xl, ldx, 32 * i + 64, lane);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_half<MT, TRANSPOSED>(x1, b1, 1, acc);
-    __builtin_amdgcn_sched_barrier(0);
+  for (int i = 0; i < 12; i += 4) {
+    gemm256_group<MT, TRANSPOSED, false>(Xl, ldx, W, i, b0, b1, b2, b3, x0, x1, wave, lane, acc, tail);
+    POP_MARK(21 + (i >> 2));
   }
+  gemm256_group<MT, TRANSPOSED, true>(Xl, ldx, W, 12, b0, b1, b2, b3, x0, x1, wave, lane, acc, tail);
+  POP_MARK(24);
 }
 
 // ReLU epilogue of a hidden layer: Y = max(acc + b, 0) goes to LDS (row stride
 // kLda) and, when Yg != nullptr, to global memory as [rows][256].  Returns the
-// activation pattern of this lane's elements, bit (2 mt + nt) 16 + v, so that
+// activation pattern of this lane's elements (bb = the two bias values of
+// this lane's columns 64 wave + 32 nt + (lane & 31), loaded by the caller ahead of the product), bit (2 mt + nt) 16 + v, so that
 // the backward pass can apply ReLU' without re-reading the activations: the
 // input-gradient product leaves element (row, col) in the same lane and
 // register as the forward product did.
 template <int MT>
-__device__ inline uint64_t relu_store(const Acc<MT>& acc, const float* __restrict__ bias, float* __restrict__ Yl,
+__device__ inline uint64_t relu_store(const Acc<MT>& acc, const float (&bb)[2], float* __restrict__ Yl,
                                       float* __restrict__ Yg, int wave, int lane) {
-  float bb[2];
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt) bb[nt] = bias[64 * wave + 32 * nt + (lane & 31)];
   uint64_t mask = 0;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -221,12 +277,10 @@ __device__ inline bool mask_bit(uint64_t mask, int mt, int nt, int v) {
 }
 
 // Thin products on the vector ALU (heads with 1..8 outputs, action gradient):
-// out[r*kMaxAct + j] = sum_{c<256} X[r][c] V_j[c],  r < R, j < J.
+// out[r*kMaxAct + j] = sum_{c<256} X[r][c] V[j*256 + c],  r < R, j < J, X and V in LDS.
 // Thread t works on rows (t >> 3) + 32 i with column groups 32 q + 4 (t & 7);
 // 8 neighbouring lanes share a row and are summed with lane shuffles.
-// STRIDED: V_j[c] = V[c * J + j] (a head weight W3[256][J]);
-// otherwise V_j[c] = V[j * 256 + c] (J rows of a [.., 256] matrix).
-template <int R, bool STRIDED>
+template <int R>
 __device__ inline void thin_dot(const float* __restrict__ Xl, const float* __restrict__ V, int J,
                                 float* __restrict__ outl, int tid) {
   const int p = tid & 7;
@@ -242,13 +296,8 @@ __device__ inline void thin_dot(const float* __restrict__ Xl, const float* __res
 #pragma unroll
       for (int j = 0; j < kMaxAct; ++j) {
         if (j < J) {
-          if (STRIDED) {
-            s[j] += x[0] * V[(c + 0) * J + j] + x[1] * V[(c + 1) * J + j] + x[2] * V[(c + 2) * J + j] +
-                    x[3] * V[(c + 3) * J + j];
-          } else {
-            const f32x4 w = *reinterpret_cast<const f32x4*>(&V[(size_t)j * kH + c]);
-            s[j] += x[0] * w[0] + x[1] * w[1] + x[2] * w[2] + x[3] * w[3];
-          }
+          const f32x4 w = *reinterpret_cast<const f32x4*>(&V[j * kH + c]);
+          s[j] += x[0] * w[0] + x[1] * w[1] + x[2] * w[2] + x[3] * w[3];
         }
       }
     }

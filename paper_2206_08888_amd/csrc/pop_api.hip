@@ -23,7 +23,7 @@ constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
   int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
-  int64_t cH1, cdZ2, cdZ1, aH1, adZ2, adZ1, cpart, apart, losses, staging, replay, total;
+  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, staging, replay, total;
   int64_t param_bytes;
 };
 
@@ -75,8 +75,7 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
     return fail(ctx, POP_EUNSUPPORTED, "hidden layers must be {256, 256}");
   if (c->obs_dim + c->act_dim > kMaxIn) return fail(ctx, POP_EUNSUPPORTED, "obs_dim + act_dim must be <= %d", kMaxIn);
   if (c->act_dim > kMaxAct) return fail(ctx, POP_EUNSUPPORTED, "act_dim must be <= %d", kMaxAct);
-  if (c->batch % 64 != 0 || c->batch > 1024)
-    return fail(ctx, POP_EUNSUPPORTED, "batch must be a multiple of 64, at most 1024");
+  if (c->batch != 256) return fail(ctx, POP_EUNSUPPORTED, "batch must be 256");
   if (c->capacity > 0xFFFFFFFFll) return fail(ctx, POP_EUNSUPPORTED, "capacity must be below 2^32");
   if ((int64_t)c->P * c->batch > (1ll << 24)) return fail(ctx, POP_EUNSUPPORTED, "P * batch too large");
   return POP_OK;
@@ -111,7 +110,7 @@ Layout make_ws_layout(const PopDev& d) {
   L.atilde = take(P * B * d.A * 4); L.y = take(P * B * 4);
   const int64_t act = P * B * kH * 4;
   L.cH1 = take(2 * act); L.cdZ2 = take(2 * act); L.cdZ1 = take(2 * act);
-  L.aH1 = take(act); L.adZ2 = take(act); L.adZ1 = take(act);
+  L.aH1 = take(act); L.aH2 = take(act); L.adZ2 = take(act); L.adZ1 = take(act);
   L.cpart = take(P * 2 * (int64_t)d.chunks * kCPart * 4);
   L.apart = take(P * (int64_t)d.chunks * kAPart * 4);
   L.losses = take(P * 4 * 4);
@@ -220,7 +219,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.idx = (uint32_t*)(w + L.idx); d.batch = (float*)(w + L.batch);
   d.atilde = (float*)(w + L.atilde); d.y = (float*)(w + L.y);
   d.cH1 = (float*)(w + L.cH1); d.cdZ2 = (float*)(w + L.cdZ2); d.cdZ1 = (float*)(w + L.cdZ1);
-  d.aH1 = (float*)(w + L.aH1); d.adZ2 = (float*)(w + L.adZ2);
+  d.aH1 = (float*)(w + L.aH1); d.aH2 = (float*)(w + L.aH2); d.adZ2 = (float*)(w + L.adZ2);
   d.adZ1 = (float*)(w + L.adZ1);
   d.cpart = (float*)(w + L.cpart); d.apart = (float*)(w + L.apart); d.losses = (float*)(w + L.losses);
   ctx->d = d;

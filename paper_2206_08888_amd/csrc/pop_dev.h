@@ -3,6 +3,18 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Phase marks for kernel tuning: compiled out unless POP_TRACE is defined by a test harness,
+// which then also defines the g_pop_trace array the marks go to.
+#ifdef POP_TRACE
+extern __device__ unsigned long long g_pop_trace[64];
+#define POP_MARK(i)                                                                 \
+  do {                                                                              \
+    if (blockIdx.x == 0 && threadIdx.x == 0) g_pop_trace[i] = wall_clock64();      \
+  } while (0)
+#else
+#define POP_MARK(i)
+#endif
+
 namespace pop {
 
 constexpr int kH = 256;        // hidden width the kernels are specialised for
@@ -61,7 +73,7 @@ struct PopDev {
   float* y;                    // [P][B]
   // activations handed from the chain kernels to the weight-gradient kernel
   float *cH1, *cdZ2, *cdZ1;    // [P][2][B][256]
-  float *aH1, *adZ2, *adZ1;    // [P][B][256]
+  float *aH1, *aH2, *adZ2, *adZ1;  // [P][B][256]
   // per-row-chunk partial sums of the small gradients and of the losses
   float* cpart;                // [P][2][chunks][kCPart]
   float* apart;                // [P][chunks][kAPart]

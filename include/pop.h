@@ -171,6 +171,16 @@ int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
 int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out,
                        int64_t out_len, int32_t on_device);
 
+/* Overwrite one tensor of one agent (POP_ACTOR .. POP_ADAM_V_CRITIC2; the
+ * gradient codes are read-only) with in[in_len] floats in canonical order;
+ * in_len must equal the tensor's length.  This is the primitive a population
+ * method needs to copy a good agent over a bad one (App. B.1 of the paper:
+ * the worst agents are replaced by copies of the best) and what tests use to
+ * start a step from a prescribed state.  Enqueued on the context's stream;
+ * synchronises when `in` is a host pointer. */
+int pop_set_params(pop_ctx* ctx, int32_t agent, int32_t which, const float* in,
+                   int64_t in_len, int32_t on_device);
+
 /* Record per-parameter gradients for POP_GRAD_* (costs one extra store per
  * parameter per step).  Off by default. */
 int pop_set_debug(pop_ctx* ctx, int32_t on);

@@ -72,6 +72,7 @@ def load_library():
         "pop_update_timed": (C.c_int, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "pop_act": (C.c_int, [vp, fp, i32, fp, i32]),
         "pop_get_params": (i64, [vp, i32, i32, fp, i64, i32]),
+        "pop_set_params": (C.c_int, [vp, i32, i32, fp, i64, i32]),
         "pop_set_debug": (C.c_int, [vp, i32]),
         "pop_debug_get": (i64, [vp, i32, vp, i64, i32]),
         "pop_debug_indices": (C.c_int, [vp, vp]),
@@ -183,6 +184,12 @@ def pop_get_params(ctx, agent, which, out):
     return _check(load_library().pop_get_params(ctx, agent, which, _ptr(out, dev), n, int(dev)), ctx)
 
 
+def pop_set_params(ctx, agent, which, data):
+    dev = _is_device(data)
+    n = data.numel() if hasattr(data, "numel") else data.size
+    return _check(load_library().pop_set_params(ctx, agent, which, _ptr(data, dev), n, int(dev)), ctx)
+
+
 def pop_set_debug(ctx, on):
     return _check(load_library().pop_set_debug(ctx, int(on)), ctx)
 
@@ -259,6 +266,12 @@ class Population:
         out = np.empty(self.actor_size if code % 3 == 0 else self.critic_size, dtype=np.float32)
         pop_get_params(self.ctx, agent, code, out)
         return out
+
+    def set_params(self, agent, which, data):
+        code = PARAM_CODES[which] if isinstance(which, str) else which
+        if not _is_device(data):
+            data = np.ascontiguousarray(data, dtype=np.float32)
+        return pop_set_params(self.ctx, agent, code, data)
 
     def set_debug(self, on):
         return pop_set_debug(self.ctx, on)

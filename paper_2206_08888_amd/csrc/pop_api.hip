@@ -438,6 +438,22 @@ int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, i
   return L->size;
 }
 
+int pop_set_params(pop_ctx* ctx, int32_t agent, int32_t which, const float* in, int64_t in_len, int32_t on_device) {
+  if (!ctx) return POP_EINVAL;
+  if (agent < 0 || agent >= ctx->d.P) return fail(ctx, POP_EINVAL, "agent %d out of range", agent);
+  if (which < 0 || which > POP_ADAM_V_CRITIC2) return fail(ctx, POP_EINVAL, "tensor code %d cannot be written", which);
+  if (!in) return fail(ctx, POP_EINVAL, "in is NULL");
+  int net;
+  int64_t off, region;
+  const NetLayout* L = net_of(ctx->d, which, &net, &off, ctx->lay, &region);
+  if (in_len != L->size) return fail(ctx, POP_EINVAL, "in_len %lld != %d", (long long)in_len, L->size);
+  char* dst = ctx->ws + region + (int64_t)agent * ctx->d.agent_sz * 4 + off;
+  HIP_TRY(ctx, hipMemcpyAsync(dst, in, (size_t)L->size * 4, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
+                              ctx->stream));
+  if (!on_device) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  return POP_OK;
+}
+
 int pop_set_debug(pop_ctx* ctx, int32_t on) {
   if (!ctx) return POP_EINVAL;
   ctx->d.record_grads = on ? 1 : 0;

@@ -10,7 +10,7 @@ import pytest
 
 import paper_2206_08888_amd as pp
 import workloads
-from gpu_common import NETS, ensure_built, make_pair, rel_l2
+from gpu_common import NETS, ForcedStepStats, ensure_built, force_state, forced_step_errors, make_pair, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -195,5 +195,44 @@ def test_errors_from_the_boundary_on_a_live_context():
     small = np.empty(10, dtype=np.float32)
     with pytest.raises(pp.PopError) as e:
         pp.pop_get_params(gpu.ctx, 0, 0, small)
+    assert e.value.code == pp.POP_EINVAL
+    gpu.close()
+
+
+def test_every_single_step_from_the_oracle_state_matches_for_100_steps():
+    """Step-by-step parity: before each of 100 steps the GPU agents are set to the oracle's
+    current state (rounded to fp32), both sides take ONE step, and all parameters, targets
+    and Adam moments must agree to the one-step tolerance (see ForcedStepStats).  Unlike a
+    free-running comparison this is not at the mercy of ReLU patterns that a rounding
+    error of 1e-7 flips (after which two correct trajectories drift apart), and it
+    exercises every Adam step count, delayed and non-delayed steps and 100 batches."""
+    hps = workloads.hparams(1, 10)[:2]                 # per-agent learning rates of the P = 10 config
+    gpu, orc, agents = make_pair(1, P=2, capacity=20000, hps=hps)
+    stats = ForcedStepStats()
+    pairs = [(i, i) for i in agents]
+    for step in range(100):
+        force_state(gpu, orc, pairs)
+        gpu.update(1)
+        orc.update(1)
+        stats.add(*forced_step_errors(gpu, orc, pairs), tag=step)
+    print(stats.finish())
+    gpu.close()
+
+
+def test_set_params_round_trips_and_rejects_bad_arguments():
+    gpu, _, _ = make_pair(0, capacity=256, fill=256, oracle=False)
+    rng = np.random.default_rng(0)
+    for which in ("actor", "t_critic2", "v_critic1"):
+        n = gpu.actor_size if which.endswith("actor") else gpu.critic_size
+        data = rng.standard_normal(n).astype(np.float32)
+        gpu.set_params(1, which, data)
+        assert np.array_equal(gpu.get_params(1, which), data)
+    other = gpu.get_params(0, "actor")
+    assert not np.array_equal(other, gpu.get_params(1, "actor"))
+    with pytest.raises(pp.PopError) as e:
+        gpu.set_params(0, "actor", np.zeros(5, dtype=np.float32))
+    assert e.value.code == pp.POP_EINVAL
+    with pytest.raises(pp.PopError) as e:
+        gpu.set_params(0, "g_actor", np.zeros(gpu.actor_size, dtype=np.float32))
     assert e.value.code == pp.POP_EINVAL
     gpu.close()

@@ -141,6 +141,8 @@ def main():
     ap.add_argument("--config", type=int, default=1, choices=(0, 1, 2, 4))
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-secondary", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: populations shard by agent with no traffic inside the step, "
@@ -153,6 +155,13 @@ def main():
     import paper_2206_08888_amd as pp
     pp.load_library()                       # fails loudly when the HIP library is missing
 
+    if args.calibrate_copy:                 # known traffic: 1 GiB read + 1 GiB written per copy
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     res, c = time_config(args.config, args.steps, args.warmup, torch)
     P, B, O, A = c["P"], c["batch"], c["obs_dim"], c["act_dim"]
     flops = kernel_flops(P, B, O, A)

@@ -172,6 +172,7 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
   const float* ta = net_ptr(d, d.target, agent, 0);
   const float* tc0 = net_ptr(d, d.target, agent, 1);
   const float* tc1 = net_ptr(d, d.target, agent, 2);
+  POP_MARK(29);
   LayerPre<MT> pre;
   pre.load(ta, d.actor, wave, lane);
   const HpDev hp = d.hp[agent];
@@ -181,15 +182,20 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
   stage_vector(v_cw3, tc0 + d.critic.w3, kH, tid);
   stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
   if (tid < 2) v_cb3[tid] = (tid == 0 ? tc0 : tc1)[d.critic.b3];
+  POP_MARK(30);
   load_input<R>(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
   __syncthreads();
+  POP_MARK(31);
 
   first_layer<MT>(Xs, L.xld, ta, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
+  POP_MARK(32);
   hidden_layer<MT>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
+  POP_MARK(33);
   thin_dot<R>(buf, v_aw3, d.A, head, tid);
   __syncthreads();
+  POP_MARK(34);
   for (int e = tid; e < R * d.A; e += kThreads) {
     const int r = e / d.A, j = e - r * d.A;
     const float mu = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
@@ -204,17 +210,21 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
     d.atilde[((size_t)agent * d.B + r0 + r) * d.A + j] = at;
   }
   __syncthreads();
+  POP_MARK(35);
 
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const float* tc = k == 0 ? tc0 : tc1;
     first_layer<MT>(Xs, L.xld, tc, d.critic, pre, buf, nullptr, wave, lane);
     __syncthreads();
+    POP_MARK(36 + 4 * k);
     hidden_layer<MT>(buf, tc, d.critic, pre, nullptr, wave, lane,
                      [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
     __syncthreads();
+    POP_MARK(37 + 4 * k);
     thin_dot<R>(buf, v_cw3 + k * kH, 1, head, tid);
     __syncthreads();
+    POP_MARK(38 + 4 * k);
     if (tid < R) {
       const float q = head[tid * kMaxAct] + v_cb3[k];
       qmin[tid] = k == 0 ? q : fminf(qmin[tid], q);
@@ -226,6 +236,7 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
     const float done = rows[(size_t)tid * d.row + d.D + 1];
     d.y[(size_t)agent * d.B + r0 + tid] = rew + hp.gamma * (1.0f - done) * qmin[tid];
   }
+  POP_MARK(45);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -108,26 +108,28 @@ __device__ inline uint64_t first_layer(const float* Xs, int xld, const float* ne
 }
 
 // Hidden layer in place on `buf`; `tail` is handed to the product (see gemm256).
-template <int MT, class Tail>
+template <int MT, bool DEEP, class Tail>
 __device__ inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, LayerPre<MT>& pre,
                                         float* Yg, int wave, int lane, Tail tail) {
   Acc<MT> acc;
   acc.zero();
   const float bb[2] = {pre.b2[0], pre.b2[1]};
-  gemm256<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
+  if (DEEP) gemm256<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
+  else gemm256_lean<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc);
   __syncthreads();                                   // every wavefront has read the input tile
   return relu_store<MT>(acc, bb, buf, Yg, wave, lane);
 }
 
 // dX = (dZ W^T) * mask written to global [rows][256]; column sums of the result
 // (over this workgroup's rows) go to colsum_out[256].
-template <int MT>
+template <int MT, bool DEEP>
 __device__ inline void input_grad_to_global(const float* Zl, const float* W, WeightBlock<MT, true>& w0, uint64_t mask,
                                             float* __restrict__ dXg, float* __restrict__ colsum_out, int wave,
                                             int lane) {
   Acc<MT> acc;
   acc.zero();
-  gemm256<MT, true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
+  if (DEEP) gemm256<MT, true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
+  else { w0.load(W, 0, wave, lane); gemm256_lean<MT, true>(Zl, kLda, W, w0, wave, lane, acc); }
   float cs[2] = {0.0f, 0.0f};
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -152,8 +154,8 @@ __device__ inline void input_grad_to_global(const float* Zl, const float* W, Wei
 // Target chain.  One workgroup per (agent, chunk).
 //   a~ = clip(pi'(s') + clip(sigma eps, -c, c), -1, 1), eps = normal e = b A + j of stream 1
 //   y  = r + gamma (1 - d) min(Q1'(s', a~), Q2'(s', a~))
-template <int MT>
-__global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
+template <int MT, bool DEEP>
+__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uint32_t t) {
   constexpr int R = 32 * MT;
   extern __shared__ float lds[];
   const Lds<MT> L(d.D);
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
   first_layer<MT>(Xs, L.xld, ta, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
   POP_MARK(32);
-  hidden_layer<MT>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
+  hidden_layer<MT, DEEP>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
   POP_MARK(33);
   thin_dot<R>(buf, v_aw3, d.A, head, tid);
@@ -215,11 +217,12 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const float* tc = k == 0 ? tc0 : tc1;
+    if (!DEEP) pre.load(tc, d.critic, wave, lane);    // lean variant: fetch right before use
     first_layer<MT>(Xs, L.xld, tc, d.critic, pre, buf, nullptr, wave, lane);
     __syncthreads();
     POP_MARK(36 + 4 * k);
-    hidden_layer<MT>(buf, tc, d.critic, pre, nullptr, wave, lane,
-                     [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
+    hidden_layer<MT, DEEP>(buf, tc, d.critic, pre, nullptr, wave, lane,
+                           [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
     __syncthreads();
     POP_MARK(37 + 4 * k);
     thin_dot<R>(buf, v_cw3 + k * kH, 1, head, tid);
@@ -245,8 +248,8 @@ __global__ __launch_bounds__(kThreads) void k_target(PopDev d, uint32_t t) {
 //   dz2 = (dq W3^T) * [h2 > 0] ;  dz1 = (dz2 W2^T) * [h1 > 0]
 // Outputs for the weight-gradient kernel: h1, dz2, dz1 (global), and the chunk's
 // partial sums of dW3, db3, db2, db1 and of the loss.
-template <int MT>
-__global__ __launch_bounds__(kThreads) void k_critic(PopDev d, uint32_t t) {
+template <int MT, bool DEEP>
+__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uint32_t t) {
   constexpr int R = 32 * MT;
   extern __shared__ float lds[];
   const Lds<MT> L(d.D);
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(kThreads) void k_critic(PopDev d, uint32_t t) {
   __syncthreads();
   POP_MARK(2);
   WeightBlock<MT, true> wt;                          // block 0 of W2 for the input-gradient product
-  hidden_layer<MT>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
+  hidden_layer<MT, DEEP>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
   __syncthreads();
   POP_MARK(3);
   thin_dot<R>(buf, v_w3, 1, head, tid);
@@ -320,7 +323,7 @@ __global__ __launch_bounds__(kThreads) void k_critic(PopDev d, uint32_t t) {
   POP_MARK(5);
   __syncthreads();
   POP_MARK(6);
-  input_grad_to_global<MT>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
+  input_grad_to_global<MT, DEEP>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
   POP_MARK(7);
 }
 
@@ -332,8 +335,8 @@ __global__ __launch_bounds__(kThreads) void k_critic(PopDev d, uint32_t t) {
 //   Actor:    dz3 = da (1 - a_pi^2); dz2 = (dz3 W3^T) * [h2 > 0]; dz1 = (dz2 W2^T) * [h1 > 0]
 // The actor's second hidden layer has to survive the critic pass: it is parked in
 // global memory (L2) and fetched back into registers under the critic's last product.
-template <int MT>
-__global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
+template <int MT, bool DEEP>
+__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_actor(PopDev d, uint32_t t) {
   constexpr int R = 32 * MT;
   extern __shared__ float lds[];
   const Lds<MT> L(d.D);
@@ -370,7 +373,7 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
 
   const uint64_t mask_a1 = first_layer<MT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
   __syncthreads();
-  hidden_layer<MT>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane, [&]() { pre.load(cn, d.critic, wave, lane); });
+  hidden_layer<MT, DEEP>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane, [&]() { pre.load(cn, d.critic, wave, lane); });
   __syncthreads();
   thin_dot<R>(buf, v_aw3, A, head, tid);
   __syncthreads();
@@ -383,10 +386,11 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
   __syncthreads();
 
   // critic 1 on [s, a_pi]
+  if (!DEEP) pre.load(cn, d.critic, wave, lane);
   const uint64_t mask_c1 = first_layer<MT>(Xs, L.xld, cn, d.critic, pre, buf, nullptr, wave, lane);
   __syncthreads();
   WeightBlock<MT, true> wt;
-  hidden_layer<MT>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
+  hidden_layer<MT, DEEP>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
   __syncthreads();
   thin_dot<R>(buf, v_cw3, 1, head, tid);     // q, for the loss value only
   __syncthreads();
@@ -413,11 +417,18 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
     Acc<MT> acc;
     acc.zero();
     const float* h2g = d.aH2 + act_off;
-    gemm256<MT, true>(buf, kLda, cn + d.critic.w2, wt, wave, lane, acc, [&]() {
+    auto fetch_h2 = [&]() {
 #pragma unroll
       for (int i = 0; i < R / 4; ++i)
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
-    });
+    };
+    if (DEEP) {
+      gemm256<MT, true>(buf, kLda, cn + d.critic.w2, wt, wave, lane, acc, fetch_h2);
+    } else {
+      wt.load(cn + d.critic.w2, 0, wave, lane);
+      gemm256_lean<MT, true>(buf, kLda, cn + d.critic.w2, wt, wave, lane, acc);
+      fetch_h2();
+    }
     __syncthreads();                                 // every wavefront is done reading dz2 of the critic
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -430,7 +441,7 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
   }
   __syncthreads();
   thin_dot<R>(buf, v_cwa, A, head, tid);      // da
-  wt.load(an + d.actor.w2, 0, wave, lane);           // block 0 of the actor's input-gradient product
+  if (DEEP) wt.load(an + d.actor.w2, 0, wave, lane); // block 0 of the actor's input-gradient product
   __syncthreads();
   for (int e = tid; e < R * kMaxAct; e += kThreads) {
     const int j = e % kMaxAct;
@@ -484,7 +495,7 @@ __global__ __launch_bounds__(kThreads) void k_actor(PopDev d, uint32_t t) {
     part[kAP_db2 + c] = gb2;
   }
   __syncthreads();
-  input_grad_to_global<MT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  input_grad_to_global<MT, DEEP>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -511,7 +522,7 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
   __syncthreads();
   first_layer<1>(Xs, L.xld, an, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
-  hidden_layer<1>(buf, an, d.actor, pre, nullptr, wave, lane, NoTail());
+  hidden_layer<1, true>(buf, an, d.actor, pre, nullptr, wave, lane, NoTail());
   __syncthreads();
   thin_dot<R>(buf, v_aw3, d.A, head, tid);
   __syncthreads();
@@ -532,35 +543,49 @@ int vec_act(const PopDev& d) { return kH * d.A + 8; }
 hipError_t setup_kernels() {
   hipError_t e;
   const int most = 160 * 1024;                        // whole LDS of a CU; the launches ask for what they need
-#define POP_SET_LDS(fn)                                                                                    \
-  if ((e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, most)) != hipSuccess) return e
-  POP_SET_LDS(k_target<1>);
-  POP_SET_LDS(k_target<2>);
-  POP_SET_LDS(k_critic<1>);
-  POP_SET_LDS(k_critic<2>);
-  POP_SET_LDS(k_actor<1>);
-  POP_SET_LDS(k_actor<2>);
+#define POP_SET_LDS(...)                                                                                   \
+  if ((e = hipFuncSetAttribute((const void*)__VA_ARGS__, hipFuncAttributeMaxDynamicSharedMemorySize, most)) != hipSuccess) return e
+  POP_SET_LDS(k_target<1, true>);
+  POP_SET_LDS(k_target<1, false>);
+  POP_SET_LDS(k_target<2, true>);
+  POP_SET_LDS(k_critic<1, true>);
+  POP_SET_LDS(k_critic<1, false>);
+  POP_SET_LDS(k_critic<2, true>);
+  POP_SET_LDS(k_actor<1, true>);
+  POP_SET_LDS(k_actor<1, false>);
+  POP_SET_LDS(k_actor<2, true>);
   POP_SET_LDS(k_act);
 #undef POP_SET_LDS
   return hipSuccess;
 }
 
+// The deep-prefetch variants win whenever a launch leaves a CU one or two workgroups
+// (the latency of a single chain is what counts).  The lean ones fit three workgroups
+// per CU; measured at P = 80 they pay off for the longest chain (actor, -9 %) and
+// marginally for the critic chain, and lose for the target chain, which stays deep.
+namespace {
+bool use_lean(const PopDev& d, int workgroups) { return d.mt == 1 && d.lean >= 0 && (d.lean > 0 || workgroups > 2 * 256); }
+}  // namespace
+
 hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.chunks));
-  if (d.mt == 2) k_target<2><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_target(d)), s>>>(d, t);
-  else k_target<1><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
+  if (d.mt == 2) k_target<2, true><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_target(d)), s>>>(d, t);
+  else if (d.lean > 0) k_target<1, false><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
+  else k_target<1, true><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_critic(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(2 * d.P, d.chunks));
-  if (d.mt == 2) k_critic<2><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_critic(d)), s>>>(d, t);
-  else k_critic<1><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
+  if (d.mt == 2) k_critic<2, true><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_critic(d)), s>>>(d, t);
+  else if (use_lean(d, 2 * d.P * d.chunks)) k_critic<1, false><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
+  else k_critic<1, true><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.chunks));
-  if (d.mt == 2) k_actor<2><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_actor(d)), s>>>(d, t);
-  else k_actor<1><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  if (d.mt == 2) k_actor<2, true><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  else if (use_lean(d, d.P * d.chunks)) k_actor<1, false><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  else k_actor<1, true><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, hipStream_t s) {

@@ -159,6 +159,7 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, i
   const uint32_t delay = (uint32_t)hp.policy_delay;
   const bool delayed_step = (t % delay) == 0u;
   if (actor_phase && !delayed_step) return;
+  if (main_blocks > 2 * 256) stagger_start(2 * 256, d.stagger_w);   // only when CUs are shared from the start
 
   if (tid == 0) {
     Adam a;

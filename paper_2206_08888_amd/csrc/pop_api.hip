@@ -90,6 +90,9 @@ void fill_dims(const pop_config& c, PopDev& d) {
   d.mt = ((int64_t)c.P * (c.batch / 64) >= 512) ? 2 : 1;
   if (const char* env = getenv("POP_ROW_TILES")) { const int v = atoi(env); if (v == 1 || v == 2) d.mt = v; }
   d.chunks = c.batch / (32 * d.mt);
+  if (const char* env = getenv("POP_LEAN")) d.lean = atoi(env) > 0 ? 1 : (atoi(env) < 0 ? -1 : 0);
+  d.stagger_w = 1000;           // 10 us: about half of a workgroup's time in the weight-gradient kernel
+  if (const char* env = getenv("POP_STAGGER_W")) d.stagger_w = atoi(env);
   d.actor = make_layout(d.O, d.A);
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;

@@ -55,6 +55,8 @@ struct PopDev {
   int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
   int mt;                      // row tiles per workgroup of the fused chain kernels (rows = 32 mt)
   int chunks;                  // B / (32 mt)
+  int lean;                    // chain-kernel variant: 0 choose by launch size, 1 always lean, -1 always deep prefetch
+  int stagger_w;               // weight-gradient kernel: start offset between co-resident workgroups, 10 ns ticks
   NetLayout actor, critic;
   int agent_sz;                // actor.padded + 2 * critic.padded
   // parameter state, each [P][agent_sz] = [actor | critic1 | critic2]
@@ -100,6 +102,22 @@ __device__ inline bool decode_block(int id, int units, int per_unit, int& unit, 
   return unit < units;
 }
 __host__ inline int xcd_grid(int units, int per_unit) { return (units + 7) / 8 * 8 * per_unit; }
+
+// Workgroups of one launch all walk through the same phases (operand staging, matrix
+// product, streaming epilogue), and the ones dispatched together onto a CU do so in
+// lockstep: they fight over the matrix pipe, then over memory.  This delays, in the
+// first `resident` workgroups of a launch only, the wavefronts that did not get the
+// first wave slot of their SIMD by slot * ticks (10 ns each), so that co-resident
+// workgroups run out of phase from then on.  The wait is bounded by the constant-rate
+// clock; a wrong guess about slots costs time, never correctness.
+__device__ inline void stagger_start(int resident, int ticks) {
+  if (ticks <= 0 || (int)blockIdx.x >= resident) return;
+  const uint32_t slot = __builtin_amdgcn_s_getreg((3 << 11) | 4) & 15u;   // HW_ID bits 3:0 = wave slot within the SIMD
+  if (slot == 0) return;
+  const uint64_t t0 = wall_clock64();
+  const uint64_t wait = (uint64_t)min(slot, 3u) * (uint64_t)ticks;
+  while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);
+}
 
 __device__ inline const float* net_ptr(const PopDev& d, const float* base, int agent, int net) {
   const float* p = base + (size_t)agent * d.agent_sz;

@@ -40,6 +40,7 @@ def kernel_flops(P, B, O, A):
         "actor": fwd_actor + 2 * B * (D * H + H * H) + 2 * B * H * H + 3 * (2 * B * A * H) + 2 * B * H * H,
         "wgrad_actor": 2 * B * H * H + 2 * B * O * H,
     }
+    per_agent["target_critic"] = per_agent["target"] + per_agent["critic"]
     return {k: v * P for k, v in per_agent.items()}
 
 
@@ -167,7 +168,7 @@ def main():
     flops = kernel_flops(P, B, O, A)
     kus = res["kernel_us"]
     per_step_us = {k: (kus[k] or 0.0) * res["kernel_launches"][k] / args.steps for k in kus}
-    dominant = max((k for k in kus if flops[k] > 0), key=lambda k: per_step_us[k])
+    dominant = max((k for k in kus if flops[k] > 0 and kus[k]), key=lambda k: per_step_us[k])
     achieved = flops[dominant] / (kus[dominant] * 1e-6) / 1e12
     roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=achieved / MFMA_FP32_PEAK_TFLOPS, traffic=read_traffic(dominant, P),

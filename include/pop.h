@@ -142,15 +142,21 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs,
 int pop_update(pop_ctx* ctx, int32_t n_steps);
 
 /* Kernels of one update step, in launch order (indices into the arrays of
- * pop_update_timed). */
+ * pop_update_timed).  By default the target and critic chains run as one
+ * launch (POP_K_TARGET_CRITIC): the critics' forward pass does not depend on
+ * the Bellman targets, so it runs beside the target networks and only the
+ * loss waits for them.  With the environment variable POP_FUSE_TC=0 at
+ * pop_create they are the two launches POP_K_TARGET and POP_K_CRITIC instead;
+ * the results are identical either way. */
 enum {
-  POP_K_GATHER = 0,       /* replay index draw + row gather */
-  POP_K_TARGET = 1,       /* target actor, smoothing, twin target critics, y */
-  POP_K_CRITIC = 2,       /* twin critics forward + backward to pre-activations */
-  POP_K_WGRAD_CRITIC = 3, /* critic weight gradients + Adam (+ Polyak) */
-  POP_K_ACTOR = 4,        /* actor forward, critic-1 forward/input-gradient, actor backward */
-  POP_K_WGRAD_ACTOR = 5,  /* actor weight gradients + Adam + Polyak */
-  POP_K_COUNT = 6
+  POP_K_GATHER = 0,        /* replay index draw + row gather */
+  POP_K_TARGET = 1,        /* target actor, smoothing, twin target critics, y */
+  POP_K_CRITIC = 2,        /* twin critics forward + backward to pre-activations */
+  POP_K_WGRAD_CRITIC = 3,  /* critic weight gradients + Adam (+ Polyak) */
+  POP_K_ACTOR = 4,         /* actor forward, critic-1 forward/input-gradient, actor backward */
+  POP_K_WGRAD_ACTOR = 5,   /* actor weight gradients + Adam + Polyak */
+  POP_K_TARGET_CRITIC = 6, /* POP_K_TARGET and POP_K_CRITIC in one launch */
+  POP_K_COUNT = 7
 };
 
 /* Measurement variant of pop_update (same work, same results): every kernel
@@ -198,7 +204,9 @@ int64_t pop_step_count(const pop_ctx* ctx);
 int64_t pop_buffer_count(const pop_ctx* ctx, int32_t agent);
 
 /* Block until everything enqueued by this context has finished; reports
- * asynchronous kernel errors as POP_EHIP. */
+ * asynchronous kernel errors as POP_EHIP, and likewise a wait between
+ * workgroups of the fused target/critic launch that ran into its time limit
+ * (about 2 s; the launch still completes, its results are invalid). */
 int pop_sync(pop_ctx* ctx);
 
 /* Free the host-side context (never the workspace). */

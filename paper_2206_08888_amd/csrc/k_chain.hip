@@ -150,14 +150,37 @@ __device__ inline void input_grad_to_global(const float* Zl, const float* W, Wei
 
 }  // namespace
 
+// Bellman targets handed from a target workgroup to critic workgroups of the same launch
+// travel as one 64-bit word per row, (t + 1) << 32 | bits of y, written and read with
+// single device-scope atomic accesses: value and "ready" tag can then never be seen apart,
+// and nothing but per-location coherence of atomics is relied on (no fences, no L2-wide
+// write-back or invalidate).  The reader polls its own row; the wait is bounded by the
+// constant-rate clock (about 2 s), after which a bit in d.fault is raised, which the host
+// reports at its next synchronisation, and the lane goes on so that the launch still drains.
+__device__ inline void publish_y(const PopDev& d, size_t row, uint32_t t, float y) {
+  const uint64_t word = ((uint64_t)(t + 1u) << 32) | (uint64_t)__float_as_uint(y);
+  __hip_atomic_store(d.y_tagged + row, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float await_y(const PopDev& d, size_t row, uint32_t t) {
+  const uint64_t t0 = wall_clock64();
+  uint64_t word;
+  while (((word = __hip_atomic_load(d.y_tagged + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != t + 1u) {
+    __builtin_amdgcn_s_sleep(4);
+    if (wall_clock64() - t0 > 200000000ull) {
+      atomicOr(d.fault, 1u);
+      break;
+    }
+  }
+  return __uint_as_float((uint32_t)word);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Target chain.  One workgroup per (agent, chunk).
 //   a~ = clip(pi'(s') + clip(sigma eps, -c, c), -1, 1), eps = normal e = b A + j of stream 1
 //   y  = r + gamma (1 - d) min(Q1'(s', a~), Q2'(s', a~))
 template <int MT, bool DEEP>
-__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uint32_t t) {
+__device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int block, float* lds) {
   constexpr int R = 32 * MT;
-  extern __shared__ float lds[];
   const Lds<MT> L(d.D);
   float* Xs = lds;
   float* buf = lds + L.buf;
@@ -169,7 +192,7 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uin
   float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int agent, chunk;
-  if (!decode_block(blockIdx.x, d.P, d.chunks, agent, chunk)) return;
+  if (!decode_block(block, d.P, d.chunks, agent, chunk)) return;
   const int r0 = chunk * R;
   const float* ta = net_ptr(d, d.target, agent, 0);
   const float* tc0 = net_ptr(d, d.target, agent, 1);
@@ -237,9 +260,17 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uin
   if (tid < R) {
     const float rew = rows[(size_t)tid * d.row + d.D];
     const float done = rows[(size_t)tid * d.row + d.D + 1];
-    d.y[(size_t)agent * d.B + r0 + tid] = rew + hp.gamma * (1.0f - done) * qmin[tid];
+    const float yv = rew + hp.gamma * (1.0f - done) * qmin[tid];
+    d.y[(size_t)agent * d.B + r0 + tid] = yv;
+    publish_y(d, (size_t)agent * d.B + r0 + tid, t, yv);   // for critic workgroups of the same launch
   }
   POP_MARK(45);
+}
+
+template <int MT, bool DEEP>
+__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uint32_t t) {
+  extern __shared__ float lds[];
+  target_chain<MT, DEEP>(d, t, blockIdx.x, lds);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -248,10 +279,11 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uin
 //   dz2 = (dq W3^T) * [h2 > 0] ;  dz1 = (dz2 W2^T) * [h1 > 0]
 // Outputs for the weight-gradient kernel: h1, dz2, dz1 (global), and the chunk's
 // partial sums of dW3, db3, db2, db1 and of the loss.
-template <int MT, bool DEEP>
-__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uint32_t t) {
+// WAIT: the targets come from target workgroups of the same launch; the lanes that need
+// them poll for their rows right before the loss.
+template <int MT, bool DEEP, bool WAIT>
+__device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int block, float* lds) {
   constexpr int R = 32 * MT;
-  extern __shared__ float lds[];
   const Lds<MT> L(d.D);
   float* Xs = lds;
   float* buf = lds + L.buf;
@@ -260,7 +292,7 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uin
   float* v_w3 = lds + L.vec;                         // [256]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int net, chunk;
-  if (!decode_block(blockIdx.x, 2 * d.P, d.chunks, net, chunk)) return;
+  if (!decode_block(block, 2 * d.P, d.chunks, net, chunk)) return;
   const int agent = net >> 1, k = net & 1, r0 = chunk * R;
   const float* cn = net_ptr(d, d.theta, agent, 1 + k);
   LayerPre<MT> pre;
@@ -271,7 +303,10 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uin
   stage_vector(v_w3, cn + d.critic.w3, kH, tid);
   load_input<R>(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
   float yv = 0.0f, b3 = 0.0f;
-  if (tid < R) { yv = d.y[(size_t)agent * d.B + r0 + tid]; b3 = cn[d.critic.b3]; }
+  if (tid < R) {
+    if (!WAIT) yv = d.y[(size_t)agent * d.B + r0 + tid];
+    b3 = cn[d.critic.b3];
+  }
   POP_MARK(0);
   __syncthreads();
   POP_MARK(1);
@@ -284,6 +319,7 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uin
   __syncthreads();
   POP_MARK(3);
   thin_dot<R>(buf, v_w3, 1, head, tid);
+  if (WAIT && tid < R) yv = await_y(d, (size_t)agent * d.B + r0 + tid, t);   // same lane uses it below
   __syncthreads();
   POP_MARK(4);
   if (tid < 64) {                                   // R <= 64: one wavefront covers the chunk
@@ -325,6 +361,24 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uin
   POP_MARK(6);
   input_grad_to_global<MT, DEEP>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
   POP_MARK(7);
+}
+
+template <int MT, bool DEEP>
+__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uint32_t t) {
+  extern __shared__ float lds[];
+  critic_chain<MT, DEEP, false>(d, t, blockIdx.x, lds);
+}
+
+// Target and critic chains of one step in a single launch.  The critic's forward pass does
+// not need the Bellman targets, so its workgroups run beside the target workgroups and
+// only wait, before the loss, for the targets of their own rows.  Target workgroups have the
+// lower block indices: workgroups are dispatched in index order, so whatever a critic
+// workgroup waits for has already been dispatched and the wait always ends.
+template <int MT>
+__global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_t t, int target_blocks) {
+  extern __shared__ float lds[];
+  if ((int)blockIdx.x < target_blocks) target_chain<MT, true>(d, t, blockIdx.x, lds);
+  else critic_chain<MT, true, true>(d, t, blockIdx.x - target_blocks, lds);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -554,6 +608,8 @@ hipError_t setup_kernels() {
   POP_SET_LDS(k_actor<1, true>);
   POP_SET_LDS(k_actor<1, false>);
   POP_SET_LDS(k_actor<2, true>);
+  POP_SET_LDS(k_target_critic<1>);
+  POP_SET_LDS(k_target_critic<2>);
   POP_SET_LDS(k_act);
 #undef POP_SET_LDS
   return hipSuccess;
@@ -579,6 +635,13 @@ hipError_t launch_critic(const PopDev& d, uint32_t t, hipStream_t s) {
   if (d.mt == 2) k_critic<2, true><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_critic(d)), s>>>(d, t);
   else if (use_lean(d, 2 * d.P * d.chunks)) k_critic<1, false><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
   else k_critic<1, true><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
+  return hipGetLastError();
+}
+hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
+  const int nt = xcd_grid(d.P, d.chunks), nc = xcd_grid(2 * d.P, d.chunks);
+  const int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
+  if (d.mt == 2) k_target_critic<2><<<dim3(nt + nc), dim3(kThreads), Lds<2>(d.D).bytes(vec), s>>>(d, t, nt);
+  else k_target_critic<1><<<dim3(nt + nc), dim3(kThreads), Lds<1>(d.D).bytes(vec), s>>>(d, t, nt);
   return hipGetLastError();
 }
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {

@@ -77,16 +77,32 @@ __device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uin
   if (a.record) gr[i] = g;
 }
 
-// One 32-row slab of a weight matrix [M][256] (rows m0 .. m0+31, rows >= M masked):
+// One 32 x 128 tile of a weight matrix [M][256]: rows m0 .. m0+31 (rows >= M masked),
+// columns n0 .. n0+127, 32 per wavefront.
 //   x: [256][ldx] layer input, z: [256][256] pre-activation gradient, both global;
 //   base: offset of the matrix inside the network's parameter block.
-__device__ inline void weight_slab(const Adam& adam, const float* __restrict__ x, int ldx, int M, int m0,
-                                   const float* __restrict__ z, uint32_t base, float* Xl,
+// The tile's parameters, moments and targets do not depend on the product, so they are
+// requested first and arrive while the operands are staged and multiplied.  `sh` is
+// written by thread 0 before the call and read after the barrier inside.
+__device__ __forceinline__ void weight_tile(const Adam* sh, bool polyak, const float* __restrict__ x, int ldx, int M, int m0,
+                                   int n0, const float* __restrict__ z, uint32_t base, float* Xl,
                                    float* __restrict__ th, float* __restrict__ mo, float* __restrict__ ve,
                                    float* __restrict__ tg, float* __restrict__ gr, int tid) {
   const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
-  WeightBlock<1, false> z0;
-  z0.load(z, 0, wave, lane);
+  POP_MARK(50);
+  // flat offset of accumulator element v = 0 of this lane
+  const uint32_t elem0 = base + (uint32_t)((m0 + 4 * half) * kH + n0 + 32 * wave + l32);
+  AdamRegs regs[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const bool ok = (m0 + acc_row(v, lane)) < M;
+    const uint32_t i = ok ? elem0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH) : elem0;
+    regs[v].th = th[i]; regs[v].m = mo[i]; regs[v].v = ve[i];
+    regs[v].tg = polyak ? tg[i] : 0.0f;
+  }
+  WeightBlock<1, false, 1> z0;
+  z0.load(z + n0, 0, wave, lane);
+  POP_MARK(51);
   {                                                  // X^T slice into LDS: thread b copies row b
     const float* xr = x + (size_t)tid * ldx + m0;
     if ((ldx & 3) == 0) {                            // 16-byte aligned rows (a hidden layer's output)
@@ -109,41 +125,31 @@ __device__ inline void weight_slab(const Adam& adam, const float* __restrict__ x
     }
   }
   __syncthreads();
-  // flat offset of accumulator element (nt = 0, v = 0) of this lane
-  const uint32_t elem0 = base + (uint32_t)((m0 + 4 * half) * kH + 64 * wave + l32);
-  AdamRegs regs[16];
-  auto preload = [&](int nt) {
-    uint32_t e0 = elem0 + 32u * nt;
-    asm volatile("" : "+v"(e0));                     // keeps the addresses from being hoisted far ahead
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const bool ok = (m0 + acc_row(v, lane)) < M;
-      regs[v] = adam_load(adam, ok ? e0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH) : e0, th, mo, ve, tg);
-    }
-  };
-  Acc<1> acc;
+  POP_MARK(52);
+  const Adam adam = *sh;
+  Acc<1, 1> acc;
   acc.zero();
-  gemm256<1, false>(Xl, kLda, z, z0, wave, lane, acc, [&]() { preload(0); });
+  gemm256<1, false, 1>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());
+  POP_MARK(53);
+  uint32_t e1 = elem0;
+  asm volatile("" : "+v"(e1));                       // recompute the addresses: keeping 64 of them alive costs more
 #pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    if (nt == 1) preload(1);
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if ((m0 + acc_row(v, lane)) < M)
-        adam_store(adam, regs[v], acc.t[0][nt][v], elem0 + 32u * nt + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH),
-                   th, mo, ve, tg, gr);
-      if ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-    }
+  for (int v = 0; v < 16; ++v) {
+    if ((m0 + acc_row(v, lane)) < M)
+      adam_store(adam, regs[v], acc.t[0][0][v], e1 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH), th, mo, ve, tg, gr);
+    if ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);
   }
+  POP_MARK(54);
 }
 
 }  // namespace
 
-__global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
+__global__ __launch_bounds__(kThreads, 3) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
                                                           int roles, int prefetch) {
   __shared__ Adam sh_adam;
   __shared__ __attribute__((aligned(16))) float xt_lds[32 * kLda];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  POP_MARK(49);
   if ((int)blockIdx.x >= main_blocks) {              // gather role: rows of the next step
     if (prefetch) {
       const int g = blockIdx.x - main_blocks, per = gather_blocks_per_agent(d);
@@ -159,9 +165,8 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, i
   const uint32_t delay = (uint32_t)hp.policy_delay;
   const bool delayed_step = (t % delay) == 0u;
   if (actor_phase && !delayed_step) return;
-  if (main_blocks > 2 * 256) stagger_start(2 * 256, d.stagger_w);   // only when CUs are shared from the start
 
-  if (tid == 0) {
+  if (tid == 0) {                                    // read by everyone after the next barrier
     Adam a;
     const uint32_t count = actor_phase ? t / delay + 1u : t + 1u;   // 1-based Adam step
     a.lr = actor_phase ? hp.lr_actor : hp.lr_critic;
@@ -173,8 +178,6 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, i
     a.record = d.record_grads;
     sh_adam = a;
   }
-  __syncthreads();
-  const Adam adam = sh_adam;
 
   const NetLayout& L = actor_phase ? d.actor : d.critic;
   float* th = net_ptr(d, d.theta, agent, net);
@@ -184,23 +187,24 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, i
   float* gr = net_ptr(d, d.grad, agent, net);
 
   const int n1 = (L.in + 31) / 32;
-  if (role < 8 + n1) {
+  if (role < 16 + 2 * n1) {
     const size_t o = (size_t)unit * d.B * kH;        // unit = agent (actor) or network (critics)
-    if (role < 8) {
-      weight_slab(adam, (actor_phase ? d.aH1 : d.cH1) + o, kH, kH, 32 * role, (actor_phase ? d.adZ2 : d.cdZ2) + o,
-                  (uint32_t)L.w2, xt_lds, th, mo, ve, tg, gr, tid);
-    } else {                                         // layer-1 input = leading columns of the batch rows
-      weight_slab(adam, batch_rows(d, t, agent), d.row, L.in, 32 * (role - 8), (actor_phase ? d.adZ1 : d.cdZ1) + o,
-                  (uint32_t)L.w1, xt_lds, th, mo, ve, tg, gr, tid);
-    }
+    const int n0 = 128 * (role & 1);
+    const bool w2 = role < 16;                       // else layer 1, whose input is the leading columns of the batch rows
+    const float* x = w2 ? (actor_phase ? d.aH1 : d.cH1) + o : batch_rows(d, t, agent);
+    const float* z = (w2 ? (actor_phase ? d.adZ2 : d.cdZ2) : (actor_phase ? d.adZ1 : d.cdZ1)) + o;
+    weight_tile(&sh_adam, delayed_step, x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
+                (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
   } else {
     // small tensors from per-chunk partial sums; thread c owns hidden unit c
+    __syncthreads();
+    const Adam adam = sh_adam;
     const int c = tid;
     const int out = L.out;
     float gb1 = 0.0f, gb2 = 0.0f, gw3[kMaxAct], gb3 = 0.0f, loss = 0.0f;
 #pragma unroll
     for (int j = 0; j < kMaxAct; ++j) gw3[j] = 0.0f;
-#pragma unroll 1
+#pragma unroll 4
     for (int ch = 0; ch < d.chunks; ++ch) {
       if (actor_phase) {
         const float* p = d.apart + ((size_t)agent * d.chunks + ch) * kAPart;
@@ -237,7 +241,7 @@ __global__ __launch_bounds__(kThreads) void k_wgrad_adam(PopDev d, uint32_t t, i
 
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s) {
   const NetLayout& L = actor_phase ? d.actor : d.critic;
-  const int roles = 8 + (L.in + 31) / 32 + 1;
+  const int roles = 16 + 2 * ((L.in + 31) / 32) + 1;
   const int main_blocks = xcd_grid(actor_phase ? d.P : 2 * d.P, roles);
   const int extra = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
   hipLaunchKernelGGL(k_wgrad_adam, dim3(main_blocks + extra), dim3(kThreads), 0, s, d, t, actor_phase, main_blocks,

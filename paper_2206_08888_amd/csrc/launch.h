@@ -19,6 +19,7 @@ hipError_t launch_insert(const PopDev& d, int agent, int64_t n, const float* obs
 hipError_t launch_sample_gather(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_critic(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s);   // both of the above in one launch
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s);
 // prefetch_next != 0: extra workgroups also gather the replay rows of step t + 1
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s);

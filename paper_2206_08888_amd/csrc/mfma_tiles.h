@@ -37,14 +37,16 @@ __device__ inline f32x16 mfma32(float a, float b, f32x16 c) {
 
 __device__ inline int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
-template <int MT>
+// NT = 32-column tiles per wavefront: 2 in the layer chains (a workgroup spans 256
+// columns), 1 in the weight-gradient tiles (128 columns per workgroup).
+template <int MT, int NT = 2>
 struct Acc {
-  f32x16 t[MT][2];
+  f32x16 t[MT][NT];
   __device__ inline void zero() {
 #pragma unroll
     for (int a = 0; a < MT; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < NT; ++b)
 #pragma unroll
         for (int v = 0; v < 16; ++v) t[a][b][v] = 0.0f;
   }
@@ -144,15 +146,15 @@ __device__ inline void gemm_xw_small(const float* __restrict__ Xl, int ldx, int 
 // caller can start the loads of the next layer under the last three blocks.
 // __builtin_amdgcn_sched_barrier keeps the compiler from sinking loads back next
 // to their uses.
-template <int MT, bool TRANSPOSED>
+template <int MT, bool TRANSPOSED, int NT = 2>
 struct WeightBlock {                       // the weights one lane needs for a 16-deep block
-  float w[2][8];                           // [column tile][4 s + j]  <->  index 16 i + 8 s + 4 half + j
+  float w[NT][8];                          // [column tile][4 s + j]  <->  index 16 i + 8 s + 4 half + j
   __device__ inline void load(const float* __restrict__ W, int i, int wave, int lane) {
     const int half = lane >> 5, l32 = lane & 31;
     if (TRANSPOSED) {
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        const float* row = W + (64 * wave + 32 * nt + l32) * kH + 16 * i + 4 * half;
+      for (int nt = 0; nt < NT; ++nt) {
+        const float* row = W + (32 * NT * wave + 32 * nt + l32) * kH + 16 * i + 4 * half;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
           const f32x4 v = *reinterpret_cast<const f32x4*>(row + 8 * s);
@@ -160,13 +162,13 @@ struct WeightBlock {                       // the weights one lane needs for a 1
         }
       }
     } else {
-      const float* col = W + (16 * i + 4 * half) * kH + 64 * wave + l32;
+      const float* col = W + (16 * i + 4 * half) * kH + 32 * NT * wave + l32;
 #pragma unroll
       for (int s = 0; s < 2; ++s)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-          for (int nt = 0; nt < 2; ++nt) w[nt][4 * s + j] = col[(8 * s + j) * kH + 32 * nt];
+          for (int nt = 0; nt < NT; ++nt) w[nt][4 * s + j] = col[(8 * s + j) * kH + 32 * nt];
     }
   }
 };
@@ -184,8 +186,8 @@ struct LdsBlock {                          // the LDS operand of one block (16 d
   }
 };
 
-template <int MT, bool TRANSPOSED>
-__device__ inline void mfma_block(const LdsBlock<MT>& x, const WeightBlock<MT, TRANSPOSED>& b, Acc<MT>& acc) {
+template <int MT, bool TRANSPOSED, int NT = 2>
+__device__ inline void mfma_block(const LdsBlock<MT>& x, const WeightBlock<MT, TRANSPOSED, NT>& b, Acc<MT, NT>& acc) {
 #pragma unroll
   for (int s = 0; s < 2; ++s)
 #pragma unroll
@@ -193,44 +195,44 @@ __device__ inline void mfma_block(const LdsBlock<MT>& x, const WeightBlock<MT, T
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < NT; ++nt)
           acc.t[mt][nt] = mfma32(x.a[mt][s][j], b.w[nt][4 * s + j], acc.t[mt][nt]);
 }
 
 struct NoTail { __device__ inline void operator()() const {} };
 
 // four blocks i .. i+3 of the product; LAST: no further weight blocks exist, run tail() instead
-template <int MT, bool TRANSPOSED, bool LAST, class Tail>
+template <int MT, bool TRANSPOSED, bool LAST, int NT, class Tail>
 __device__ inline void gemm256_group(const float* __restrict__ Xl, int ldx, const float* __restrict__ W, int i,
-                                     WeightBlock<MT, TRANSPOSED>& b0, WeightBlock<MT, TRANSPOSED>& b1,
-                                     WeightBlock<MT, TRANSPOSED>& b2, WeightBlock<MT, TRANSPOSED>& b3,
-                                     LdsBlock<MT>& x0, LdsBlock<MT>& x1, int wave, int lane, Acc<MT>& acc,
+                                     WeightBlock<MT, TRANSPOSED, NT>& b0, WeightBlock<MT, TRANSPOSED, NT>& b1,
+                                     WeightBlock<MT, TRANSPOSED, NT>& b2, WeightBlock<MT, TRANSPOSED, NT>& b3,
+                                     LdsBlock<MT>& x0, LdsBlock<MT>& x1, int wave, int lane, Acc<MT, NT>& acc,
                                      Tail& tail) {
   b3.load(W, i + 3, wave, lane);
   x1.load(Xl, ldx, 16 * (i + 1), lane);
   __builtin_amdgcn_sched_barrier(0);
-  mfma_block<MT, TRANSPOSED>(x0, b0, acc);
+  mfma_block<MT, TRANSPOSED, NT>(x0, b0, acc);
   __builtin_amdgcn_sched_barrier(0);
   if (!LAST) b0.load(W, i + 4, wave, lane); else tail();
   x0.load(Xl, ldx, 16 * (i + 2), lane);
   __builtin_amdgcn_sched_barrier(0);
-  mfma_block<MT, TRANSPOSED>(x1, b1, acc);
+  mfma_block<MT, TRANSPOSED, NT>(x1, b1, acc);
   __builtin_amdgcn_sched_barrier(0);
   if (!LAST) b1.load(W, i + 5, wave, lane);
   x1.load(Xl, ldx, 16 * (i + 3), lane);
   __builtin_amdgcn_sched_barrier(0);
-  mfma_block<MT, TRANSPOSED>(x0, b2, acc);
+  mfma_block<MT, TRANSPOSED, NT>(x0, b2, acc);
   __builtin_amdgcn_sched_barrier(0);
   if (!LAST) { b2.load(W, i + 6, wave, lane); x0.load(Xl, ldx, 16 * (i + 4), lane); }
   __builtin_amdgcn_sched_barrier(0);
-  mfma_block<MT, TRANSPOSED>(x1, b3, acc);
+  mfma_block<MT, TRANSPOSED, NT>(x1, b3, acc);
   __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int MT, bool TRANSPOSED, class Tail>
+template <int MT, bool TRANSPOSED, int NT = 2, class Tail>
 __device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const float* __restrict__ W,
-                               WeightBlock<MT, TRANSPOSED>& b0, int wave, int lane, Acc<MT>& acc, Tail tail) {
-  WeightBlock<MT, TRANSPOSED> b1, b2, b3;
+                               WeightBlock<MT, TRANSPOSED, NT>& b0, int wave, int lane, Acc<MT, NT>& acc, Tail tail) {
+  WeightBlock<MT, TRANSPOSED, NT> b1, b2, b3;
   LdsBlock<MT> x0, x1;
   b1.load(W, 1, wave, lane);
   b2.load(W, 2, wave, lane);
@@ -238,10 +240,10 @@ __device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const floa
   POP_MARK(20);
 #pragma unroll 1
   for (int i = 0; i < 12; i += 4) {
-    gemm256_group<MT, TRANSPOSED, false>(Xl, ldx, W, i, b0, b1, b2, b3, x0, x1, wave, lane, acc, tail);
+    gemm256_group<MT, TRANSPOSED, false, NT>(Xl, ldx, W, i, b0, b1, b2, b3, x0, x1, wave, lane, acc, tail);
     POP_MARK(21 + (i >> 2));
   }
-  gemm256_group<MT, TRANSPOSED, true>(Xl, ldx, W, 12, b0, b1, b2, b3, x0, x1, wave, lane, acc, tail);
+  gemm256_group<MT, TRANSPOSED, true, NT>(Xl, ldx, W, 12, b0, b1, b2, b3, x0, x1, wave, lane, acc, tail);
   POP_MARK(24);
 }
 

@@ -23,7 +23,7 @@ constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
   int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
-  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, staging, replay, total;
+  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, fault, staging, replay, total;
   int64_t param_bytes;
 };
 
@@ -44,6 +44,7 @@ struct pop_ctx {
   std::vector<uint64_t> count;   // host mirror of the buffer fill levels
   uint64_t t;                    // update steps taken
   uint64_t gathered_t;           // step whose batch already sits in its half of the double buffer
+  bool fuse_tc;                  // target and critic chains in one launch
   std::string err;
 };
 
@@ -117,6 +118,8 @@ Layout make_ws_layout(const PopDev& d) {
   L.cpart = take(P * 2 * (int64_t)d.chunks * kCPart * 4);
   L.apart = take(P * (int64_t)d.chunks * kAPart * 4);
   L.losses = take(P * 4 * 4);
+  L.y_tagged = take(P * B * 8);
+  L.fault = take(4);
   L.staging = take(kStagingBytes);
   L.replay = take(P * (int64_t)d.capacity * d.row * 4);
   L.total = o;
@@ -200,6 +203,8 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->stream = (hipStream_t)hip_stream;
   ctx->t = 0;
   ctx->gathered_t = ~0ull;
+  ctx->fuse_tc = true;
+  if (const char* env = getenv("POP_FUSE_TC")) ctx->fuse_tc = atoi(env) != 0;
   ctx->hp.assign(hp, hp + cfg->P);
   ctx->count.assign(cfg->P, 0);
   ctx->hp_dev.resize(cfg->P);
@@ -225,6 +230,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.aH1 = (float*)(w + L.aH1); d.aH2 = (float*)(w + L.aH2); d.adZ2 = (float*)(w + L.adZ2);
   d.adZ1 = (float*)(w + L.adZ1);
   d.cpart = (float*)(w + L.cpart); d.apart = (float*)(w + L.apart); d.losses = (float*)(w + L.losses);
+  d.y_tagged = (uint64_t*)(w + L.y_tagged); d.fault = (uint32_t*)(w + L.fault);
   ctx->d = d;
 
   auto bail = [&](hipError_t e, const char* what) {
@@ -315,8 +321,11 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
   };
   if (ctx->gathered_t != ctx->t && !run(POP_K_GATHER, launch_sample_gather))
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
-  if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic))
+  if (ctx->fuse_tc) {
+    if (!run(POP_K_TARGET_CRITIC, launch_target_critic)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+  } else if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic)) {
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+  }
   tick(POP_K_WGRAD_CRITIC, 0);
   e = launch_wgrad_adam(d, t, 0, has_next ? 1 : 0, s);
   tick(POP_K_WGRAD_CRITIC, 1);
@@ -515,8 +524,11 @@ int64_t pop_buffer_count(const pop_ctx* ctx, int32_t agent) {
 
 int pop_sync(pop_ctx* ctx) {
   if (!ctx) return POP_EINVAL;
+  uint32_t fault = 0;
+  HIP_TRY(ctx, hipMemcpyAsync(&fault, ctx->d.fault, sizeof fault, hipMemcpyDeviceToHost, ctx->stream));
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   HIP_TRY(ctx, hipGetLastError());
+  if (fault) return fail(ctx, POP_EHIP, "a bounded wait inside a kernel ran out (fault bits %u): results are invalid", fault);
   return POP_OK;
 }
 

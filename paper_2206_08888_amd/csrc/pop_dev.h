@@ -9,7 +9,7 @@
 extern __device__ unsigned long long g_pop_trace[64];
 #define POP_MARK(i)                                                                 \
   do {                                                                              \
-    if (blockIdx.x == 0 && threadIdx.x == 0) g_pop_trace[i] = wall_clock64();      \
+    if ((blockIdx.x == 0 || blockIdx.x + 8 == gridDim.x) && threadIdx.x == 0) g_pop_trace[i] = wall_clock64(); \
   } while (0)
 #else
 #define POP_MARK(i)
@@ -79,7 +79,10 @@ struct PopDev {
   // per-row-chunk partial sums of the small gradients and of the losses
   float* cpart;                // [P][2][chunks][kCPart]
   float* apart;                // [P][chunks][kAPart]
-  float* losses;               // [P][2]
+  float* losses;               // [P][4]: critic 1, critic 2, actor, unused
+  // cross-workgroup signalling inside a launch
+  uint64_t* y_tagged;          // [P][B]: (t + 1) << 32 | bits of y, for readers inside the launch that writes y
+  uint32_t* fault;             // [1]: bit 0 = a bounded wait ran out
 };
 
 // critic partial record: dW3[256] db3[1] pad[3] db2[256] db1[256] loss[1] pad[3]
@@ -94,14 +97,27 @@ __device__ inline const float* batch_rows(const PopDev& d, uint32_t t, int agent
 
 // Workgroup ids are handed to the 8 XCDs round-robin; decode a 1-D block id so that
 // all `per_unit` workgroups of one unit (an agent or a network) land on the same
-// XCD and share its L2 (weights and activations of that unit).
+// XCD and share its L2 (weights and activations of that unit).  That works for whole
+// groups of 8 units; the units % 8 left over are laid out plainly (their workgroups
+// spread over the XCDs), so that a grid has exactly units * per_unit blocks: blocks that
+// only exit would still take a turn in the dispatcher's walk over the CUs, and push
+// later workgroups onto CUs that are already busy while others stand empty.
+// The grouping only needs ids that are congruent mod 8 to share an XCD, so `id` may be
+// offset by any constant (a kernel that runs two kinds of workgroups).
 __device__ inline bool decode_block(int id, int units, int per_unit, int& unit, int& sub) {
-  const int x = id & 7, slot = id >> 3;
-  unit = (slot / per_unit) * 8 + x;
-  sub = slot % per_unit;
+  const int full = units & ~7, nfull = full * per_unit;
+  if (id < nfull) {
+    const int x = id & 7, slot = id >> 3;
+    unit = (slot / per_unit) * 8 + x;
+    sub = slot % per_unit;
+  } else {
+    const int j = id - nfull;
+    unit = full + j / per_unit;
+    sub = j % per_unit;
+  }
   return unit < units;
 }
-__host__ inline int xcd_grid(int units, int per_unit) { return (units + 7) / 8 * 8 * per_unit; }
+__host__ inline int xcd_grid(int units, int per_unit) { return units * per_unit; }
 
 // Workgroups of one launch all walk through the same phases (operand staging, matrix
 // product, streaming epilogue), and the ones dispatched together onto a CU do so in

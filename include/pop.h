@@ -141,22 +141,27 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs,
  * POP_EEMPTY if some agent has no transitions. */
 int pop_update(pop_ctx* ctx, int32_t n_steps);
 
-/* Kernels of one update step, in launch order (indices into the arrays of
- * pop_update_timed).  By default the target and critic chains run as one
- * launch (POP_K_TARGET_CRITIC): the critics' forward pass does not depend on
- * the Bellman targets, so it runs beside the target networks and only the
- * loss waits for them.  With the environment variable POP_FUSE_TC=0 at
- * pop_create they are the two launches POP_K_TARGET and POP_K_CRITIC instead;
- * the results are identical either way. */
+/* Kernels of an update step (indices into the arrays of pop_update_timed).
+ * For larger populations a step is ONE launch, POP_K_STEP: target chains, critic chains,
+ * critic weight-gradient tiles, actor chains, actor weight-gradient tiles and
+ * the gather of the next step's rows are parts of one grid and hand their
+ * results on per agent / per network inside the launch.  The environment
+ * variable POP_FUSE, read at pop_create, selects the launch structure:
+ *   2 one launch per step (default for populations of more than about 40 agents);
+ *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest
+ *     as separate launches (default for smaller populations);
+ *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR).
+ * The arithmetic, and so every result, is bit-identical in all three. */
 enum {
-  POP_K_GATHER = 0,        /* replay index draw + row gather */
+  POP_K_GATHER = 0,        /* replay index draw + row gather (first step of a call only) */
   POP_K_TARGET = 1,        /* target actor, smoothing, twin target critics, y */
   POP_K_CRITIC = 2,        /* twin critics forward + backward to pre-activations */
   POP_K_WGRAD_CRITIC = 3,  /* critic weight gradients + Adam (+ Polyak) */
   POP_K_ACTOR = 4,         /* actor forward, critic-1 forward/input-gradient, actor backward */
   POP_K_WGRAD_ACTOR = 5,   /* actor weight gradients + Adam + Polyak */
   POP_K_TARGET_CRITIC = 6, /* POP_K_TARGET and POP_K_CRITIC in one launch */
-  POP_K_COUNT = 7
+  POP_K_STEP = 7,          /* the whole step in one launch */
+  POP_K_COUNT = 8
 };
 
 /* Measurement variant of pop_update (same work, same results): every kernel
@@ -205,8 +210,8 @@ int64_t pop_buffer_count(const pop_ctx* ctx, int32_t agent);
 
 /* Block until everything enqueued by this context has finished; reports
  * asynchronous kernel errors as POP_EHIP, and likewise a wait between
- * workgroups of the fused target/critic launch that ran into its time limit
- * (about 2 s; the launch still completes, its results are invalid). */
+ * workgroups of a fused launch that ran into its time limit
+ * (50 ms per wait; the launch still completes, its results are invalid). */
 int pop_sync(pop_ctx* ctx);
 
 /* Free the host-side context (never the workspace). */

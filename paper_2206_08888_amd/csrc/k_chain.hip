@@ -1,271 +1,10 @@
-// Fused forward/backward chains of one TD3 update step (Sec. 4.1 of the paper:
-// every population member takes the ordinary TD3 update on its own batch).
-//
-// The batch of an agent is cut into row chunks of R = 32 MT rows.  One
-// workgroup owns one (agent or network, chunk) and walks the whole layer chain
-// for its rows with the activations resident in LDS; only what the
-// weight-gradient kernel needs later (layer inputs and pre-activation
-// gradients) is written to global memory.  Rows of a batch interact only
-// through the weight gradients, which are contracted over the full batch by a
-// separate kernel, so chunks need no communication here.
-//
-//   k_target : s' -> target actor -> smoothing noise -> twin target critics -> y
-//   k_critic : [s, a] -> critic k forward -> MSE seed gradient -> backward to
-//              the pre-activation gradients of layers 2 and 1
-//   k_actor  : s -> actor -> a_pi -> critic 1 forward -> gradient w.r.t. the
-//              action -> actor backward
-//   k_act    : obs -> actor (acting, no gradient)
-//
-// LDS economy: a hidden layer overwrites its own input tile (all wavefronts
-// finish reading, barrier, then write) and ReLU patterns travel from the
-// forward to the backward product as bit masks in registers, so one 256-wide
-// tile per workgroup is enough.  Latency economy: everything a layer needs
-// from memory (its first-layer weights, the first weight block of its hidden
-// layer, its biases) is requested while the previous product is still on the
-// matrix unit, and the small head vectors are staged in LDS when the kernel
-// starts.
-#include "launch.h"
-#include "mfma_tiles.h"
-#include "rng.h"
+// Kernels around the layer chains of chains.h, one launch per chain:
+//   k_target, k_critic, k_actor : the three chains of an update step
+//   k_target_critic             : target and critic chains in one launch
+//   k_act                       : obs -> actor (acting, no gradient)
+#include "chains.h"
 
 namespace pop {
-
-static_assert(kMaxAct == 8, "the action-gradient loops read dz3 rows as two 16-byte vectors");
-
-namespace {
-
-// LDS map (floats): input tile [R][xld] | activation tile [R][kLda] | 3 x [R][8] scratch | vectors
-template <int MT>
-struct Lds {
-  static constexpr int R = 32 * MT;
-  int xld, buf, s0, s1, s2, vec;
-  __host__ __device__ Lds(int fan_in) {
-    xld = ((fan_in + 7) & ~7) + 4;         // 4 * odd words: conflict-free 16-byte row reads
-    buf = R * xld;
-    s0 = buf + R * kLda;
-    s1 = s0 + R * kMaxAct;
-    s2 = s1 + R * kMaxAct;
-    vec = s2 + R * kMaxAct;
-  }
-  __host__ size_t bytes(int vec_floats) const { return (size_t)(vec + vec_floats) * sizeof(float); }
-};
-
-// what a two-hidden-layer network needs from memory before its products can start
-template <int MT>
-struct LayerPre {
-  SmallW w1;                       // first-layer weights
-  WeightBlock<MT, false> w2;       // block 0 of the hidden layer
-  float b1[2], b2[2];              // biases of this lane's columns
-  __device__ inline void load(const float* __restrict__ net, const NetLayout& L, int wave, int lane) {
-    w1.load(net + L.w1, L.in, wave, lane);
-    w2.load(net + L.w2, 0, wave, lane);
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-      b1[nt] = net[L.b1 + 64 * wave + 32 * nt + (lane & 31)];
-      b2[nt] = net[L.b2 + 64 * wave + 32 * nt + (lane & 31)];
-    }
-  }
-};
-
-// Copy columns [c0, c0 + n) of R batch rows into the LDS input tile at columns
-// [0, n), zero the remaining columns; rows at or beyond `valid` become zero.
-template <int R>
-__device__ inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
-                                  int tid) {
-  for (int e = tid; e < R * xld; e += kThreads) {
-    const int r = e / xld, c = e - r * xld;
-    Xl[e] = (c < n && r < valid) ? rows[(size_t)r * row_stride + c0 + c] : 0.0f;
-  }
-}
-
-__device__ inline void stage_vector(float* dst, const float* __restrict__ src, int n, int tid) {
-  for (int e = tid; e < n; e += kThreads) dst[e] = src[e];
-}
-
-// Stage a head weight W3[256][J] as J rows of 256 (so that the thin products read it with
-// 16-byte LDS loads like any other row vector).
-__device__ inline void stage_head(float* dst, const float* __restrict__ src, int J, int tid) {
-  for (int e = tid; e < kH * J; e += kThreads) {
-    const int c = e / J, j = e - c * J;
-    dst[j * kH + c] = src[e];
-  }
-}
-
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-
-// First layer from the input tile into `Yl` (+ optional global copy); returns the ReLU pattern.
-template <int MT>
-__device__ inline uint64_t first_layer(const float* Xs, int xld, const float* net, const NetLayout& L,
-                                       const LayerPre<MT>& pre, float* Yl, float* Yg, int wave, int lane) {
-  Acc<MT> acc;
-  acc.zero();
-  gemm_xw_small<MT>(Xs, xld, L.in, net + L.w1, pre.w1, wave, lane, acc);
-  return relu_store<MT>(acc, pre.b1, Yl, Yg, wave, lane);
-}
-
-// Hidden layer in place on `buf`; `tail` is handed to the product (see gemm256).
-template <int MT, bool DEEP, class Tail>
-__device__ inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, LayerPre<MT>& pre,
-                                        float* Yg, int wave, int lane, Tail tail) {
-  Acc<MT> acc;
-  acc.zero();
-  const float bb[2] = {pre.b2[0], pre.b2[1]};
-  if (DEEP) gemm256<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
-  else gemm256_lean<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc);
-  __syncthreads();                                   // every wavefront has read the input tile
-  return relu_store<MT>(acc, bb, buf, Yg, wave, lane);
-}
-
-// dX = (dZ W^T) * mask written to global [rows][256]; column sums of the result
-// (over this workgroup's rows) go to colsum_out[256].
-template <int MT, bool DEEP>
-__device__ inline void input_grad_to_global(const float* Zl, const float* W, WeightBlock<MT, true>& w0, uint64_t mask,
-                                            float* __restrict__ dXg, float* __restrict__ colsum_out, int wave,
-                                            int lane) {
-  Acc<MT> acc;
-  acc.zero();
-  if (DEEP) gemm256<MT, true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
-  else { w0.load(W, 0, wave, lane); gemm256_lean<MT, true>(Zl, kLda, W, w0, wave, lane, acc); }
-  float cs[2] = {0.0f, 0.0f};
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float z = mask_bit(mask, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;
-        dXg[(32 * mt + acc_row(v, lane)) * kH + 64 * wave + 32 * nt + (lane & 31)] = z;
-        cs[nt] += z;
-      }
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    const float tot = cs[nt] + __shfl_xor(cs[nt], 32);
-    if (lane < 32) colsum_out[64 * wave + 32 * nt + lane] = tot;
-  }
-}
-
-}  // namespace
-
-// Bellman targets handed from a target workgroup to critic workgroups of the same launch
-// travel as one 64-bit word per row, (t + 1) << 32 | bits of y, written and read with
-// single device-scope atomic accesses: value and "ready" tag can then never be seen apart,
-// and nothing but per-location coherence of atomics is relied on (no fences, no L2-wide
-// write-back or invalidate).  The reader polls its own row; the wait is bounded by the
-// constant-rate clock (about 2 s), after which a bit in d.fault is raised, which the host
-// reports at its next synchronisation, and the lane goes on so that the launch still drains.
-__device__ inline void publish_y(const PopDev& d, size_t row, uint32_t t, float y) {
-  const uint64_t word = ((uint64_t)(t + 1u) << 32) | (uint64_t)__float_as_uint(y);
-  __hip_atomic_store(d.y_tagged + row, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline float await_y(const PopDev& d, size_t row, uint32_t t) {
-  const uint64_t t0 = wall_clock64();
-  uint64_t word;
-  while (((word = __hip_atomic_load(d.y_tagged + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != t + 1u) {
-    __builtin_amdgcn_s_sleep(4);
-    if (wall_clock64() - t0 > 200000000ull) {
-      atomicOr(d.fault, 1u);
-      break;
-    }
-  }
-  return __uint_as_float((uint32_t)word);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Target chain.  One workgroup per (agent, chunk).
-//   a~ = clip(pi'(s') + clip(sigma eps, -c, c), -1, 1), eps = normal e = b A + j of stream 1
-//   y  = r + gamma (1 - d) min(Q1'(s', a~), Q2'(s', a~))
-template <int MT, bool DEEP>
-__device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int block, float* lds) {
-  constexpr int R = 32 * MT;
-  const Lds<MT> L(d.D);
-  float* Xs = lds;
-  float* buf = lds + L.buf;
-  float* head = lds + L.s0;
-  float* qmin = lds + L.s1;
-  float* v_aw3 = lds + L.vec;                        // [A][256]
-  float* v_ab3 = v_aw3 + kH * d.A;                   // [8]
-  float* v_cw3 = v_ab3 + 8;                          // [2][256]
-  float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  int agent, chunk;
-  if (!decode_block(block, d.P, d.chunks, agent, chunk)) return;
-  const int r0 = chunk * R;
-  const float* ta = net_ptr(d, d.target, agent, 0);
-  const float* tc0 = net_ptr(d, d.target, agent, 1);
-  const float* tc1 = net_ptr(d, d.target, agent, 2);
-  POP_MARK(29);
-  LayerPre<MT> pre;
-  pre.load(ta, d.actor, wave, lane);
-  const HpDev hp = d.hp[agent];
-  const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
-  stage_head(v_aw3, ta + d.actor.w3, d.A, tid);
-  stage_vector(v_ab3, ta + d.actor.b3, d.A, tid);
-  stage_vector(v_cw3, tc0 + d.critic.w3, kH, tid);
-  stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
-  if (tid < 2) v_cb3[tid] = (tid == 0 ? tc0 : tc1)[d.critic.b3];
-  POP_MARK(30);
-  load_input<R>(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
-  __syncthreads();
-  POP_MARK(31);
-
-  first_layer<MT>(Xs, L.xld, ta, d.actor, pre, buf, nullptr, wave, lane);
-  __syncthreads();
-  POP_MARK(32);
-  hidden_layer<MT, DEEP>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
-  __syncthreads();
-  POP_MARK(33);
-  thin_dot<R>(buf, v_aw3, d.A, head, tid);
-  __syncthreads();
-  POP_MARK(34);
-  for (int e = tid; e < R * d.A; e += kThreads) {
-    const int r = e / d.A, j = e - r * d.A;
-    const float mu = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
-    const uint32_t el = (uint32_t)((r0 + r) * d.A + j);
-    const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, el >> 2, t, kStreamSmooth, 0u);
-    float n4[4];
-    normals4(blk, n4);
-    const float n = (el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0]);
-    const float noise = fminf(fmaxf(hp.policy_noise * n, -hp.noise_clip), hp.noise_clip);
-    const float at = fminf(fmaxf(mu + noise, -1.0f), 1.0f);
-    Xs[r * L.xld + d.O + j] = at;
-    d.atilde[((size_t)agent * d.B + r0 + r) * d.A + j] = at;
-  }
-  __syncthreads();
-  POP_MARK(35);
-
-#pragma unroll
-  for (int k = 0; k < 2; ++k) {
-    const float* tc = k == 0 ? tc0 : tc1;
-    if (!DEEP) pre.load(tc, d.critic, wave, lane);    // lean variant: fetch right before use
-    first_layer<MT>(Xs, L.xld, tc, d.critic, pre, buf, nullptr, wave, lane);
-    __syncthreads();
-    POP_MARK(36 + 4 * k);
-    hidden_layer<MT, DEEP>(buf, tc, d.critic, pre, nullptr, wave, lane,
-                           [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
-    __syncthreads();
-    POP_MARK(37 + 4 * k);
-    thin_dot<R>(buf, v_cw3 + k * kH, 1, head, tid);
-    __syncthreads();
-    POP_MARK(38 + 4 * k);
-    if (tid < R) {
-      const float q = head[tid * kMaxAct] + v_cb3[k];
-      qmin[tid] = k == 0 ? q : fminf(qmin[tid], q);
-    }
-    __syncthreads();
-  }
-  if (tid < R) {
-    const float rew = rows[(size_t)tid * d.row + d.D];
-    const float done = rows[(size_t)tid * d.row + d.D + 1];
-    const float yv = rew + hp.gamma * (1.0f - done) * qmin[tid];
-    d.y[(size_t)agent * d.B + r0 + tid] = yv;
-    publish_y(d, (size_t)agent * d.B + r0 + tid, t, yv);   // for critic workgroups of the same launch
-  }
-  POP_MARK(45);
-}
 
 template <int MT, bool DEEP>
 __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uint32_t t) {
@@ -273,100 +12,10 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uin
   target_chain<MT, DEEP>(d, t, blockIdx.x, lds);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Critic forward + backward.  One workgroup per (critic network, chunk); network = 2 agent + k.
-//   L = (1/B) sum_b (Q_k(s_b, a_b) - y_b)^2 ;  dq = 2 (q - y) / B
-//   dz2 = (dq W3^T) * [h2 > 0] ;  dz1 = (dz2 W2^T) * [h1 > 0]
-// Outputs for the weight-gradient kernel: h1, dz2, dz1 (global), and the chunk's
-// partial sums of dW3, db3, db2, db1 and of the loss.
-// WAIT: the targets come from target workgroups of the same launch; the lanes that need
-// them poll for their rows right before the loss.
-template <int MT, bool DEEP, bool WAIT>
-__device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int block, float* lds) {
-  constexpr int R = 32 * MT;
-  const Lds<MT> L(d.D);
-  float* Xs = lds;
-  float* buf = lds + L.buf;
-  float* head = lds + L.s0;
-  float* dq = lds + L.s1;
-  float* v_w3 = lds + L.vec;                         // [256]
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  int net, chunk;
-  if (!decode_block(block, 2 * d.P, d.chunks, net, chunk)) return;
-  const int agent = net >> 1, k = net & 1, r0 = chunk * R;
-  const float* cn = net_ptr(d, d.theta, agent, 1 + k);
-  LayerPre<MT> pre;
-  pre.load(cn, d.critic, wave, lane);
-  const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
-  const size_t act_off = ((size_t)net * d.B + r0) * kH;
-  float* part = d.cpart + ((size_t)net * d.chunks + chunk) * kCPart;
-  stage_vector(v_w3, cn + d.critic.w3, kH, tid);
-  load_input<R>(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
-  float yv = 0.0f, b3 = 0.0f;
-  if (tid < R) {
-    if (!WAIT) yv = d.y[(size_t)agent * d.B + r0 + tid];
-    b3 = cn[d.critic.b3];
-  }
-  POP_MARK(0);
-  __syncthreads();
-  POP_MARK(1);
-
-  const uint64_t mask1 = first_layer<MT>(Xs, L.xld, cn, d.critic, pre, buf, d.cH1 + act_off, wave, lane);
-  __syncthreads();
-  POP_MARK(2);
-  WeightBlock<MT, true> wt;                          // block 0 of W2 for the input-gradient product
-  hidden_layer<MT, DEEP>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
-  __syncthreads();
-  POP_MARK(3);
-  thin_dot<R>(buf, v_w3, 1, head, tid);
-  if (WAIT && tid < R) yv = await_y(d, (size_t)agent * d.B + r0 + tid, t);   // same lane uses it below
-  __syncthreads();
-  POP_MARK(4);
-  if (tid < 64) {                                   // R <= 64: one wavefront covers the chunk
-    float err = 0.0f, g = 0.0f;
-    if (tid < R) {
-      err = head[tid * kMaxAct] + b3 - yv;
-      g = 2.0f * err / (float)d.B;
-      dq[tid] = g;
-    }
-    const float sq = wave_sum(err * err);
-    const float sdq = wave_sum(g);
-    if (tid == 0) { part[kCP_loss] = sq / (float)d.B; part[kCP_db3] = sdq; }
-  }
-  __syncthreads();
-  {                                                 // one thread per hidden unit, 8 rows at a time
-    const int c = tid;
-    const float w3 = v_w3[c];
-    float gw3 = 0.0f, gb2 = 0.0f;
-    float* zg = d.cdZ2 + act_off + c;
-#pragma unroll 1
-    for (int rb = 0; rb < R; rb += 8) {
-      float h[8], g[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) { h[i] = buf[(rb + i) * kLda + c]; g[i] = dq[rb + i]; }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        gw3 += h[i] * g[i];
-        const float z = h[i] > 0.0f ? g[i] * w3 : 0.0f;
-        buf[(rb + i) * kLda + c] = z;
-        zg[(rb + i) * kH] = z;
-        gb2 += z;
-      }
-    }
-    part[kCP_dW3 + c] = gw3;
-    part[kCP_db2 + c] = gb2;
-  }
-  POP_MARK(5);
-  __syncthreads();
-  POP_MARK(6);
-  input_grad_to_global<MT, DEEP>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
-  POP_MARK(7);
-}
-
 template <int MT, bool DEEP>
 __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
-  critic_chain<MT, DEEP, false>(d, t, blockIdx.x, lds);
+  critic_chain<MT, DEEP, false, false>(d, t, blockIdx.x, lds);
 }
 
 // Target and critic chains of one step in a single launch.  The critic's forward pass does
@@ -378,178 +27,13 @@ template <int MT>
 __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
   if ((int)blockIdx.x < target_blocks) target_chain<MT, true>(d, t, blockIdx.x, lds);
-  else critic_chain<MT, true, true>(d, t, blockIdx.x - target_blocks, lds);
+  else critic_chain<MT, true, true, false>(d, t, blockIdx.x - target_blocks, lds);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Actor chain (steps with t % policy_delay == 0).  One workgroup per (agent, chunk).
-//   L = -(1/B) sum_b Q1(s_b, pi(s_b)) through the critic updated earlier in this step.
-//   Critic 1: dz2c = -(1/B) W3c^T * [c2 > 0]; dz1c = (dz2c W2c^T) * [c1 > 0];
-//             da = dz1c W1c[O:O+A, :]^T
-//   Actor:    dz3 = da (1 - a_pi^2); dz2 = (dz3 W3^T) * [h2 > 0]; dz1 = (dz2 W2^T) * [h1 > 0]
-// The actor's second hidden layer has to survive the critic pass: it is parked in
-// global memory (L2) and fetched back into registers under the critic's last product.
 template <int MT, bool DEEP>
 __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_actor(PopDev d, uint32_t t) {
-  constexpr int R = 32 * MT;
   extern __shared__ float lds[];
-  const Lds<MT> L(d.D);
-  float* Xs = lds;
-  float* buf = lds + L.buf;
-  float* head = lds + L.s0;
-  float* api = lds + L.s1;
-  float* dz3 = lds + L.s2;
-  const int A = d.A;
-  float* v_aw3 = lds + L.vec;                        // [A][256] actor head
-  float* v_ab3 = v_aw3 + kH * A;                     // [8]
-  float* v_cw3 = v_ab3 + 8;                          // [256] critic head
-  float* v_cwa = v_cw3 + kH;                         // [A][256] critic first-layer rows of the action inputs
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  int agent, chunk;
-  if (!decode_block(blockIdx.x, d.P, d.chunks, agent, chunk)) return;
-  const int r0 = chunk * R;
-  const HpDev hp = d.hp[agent];
-  if (t % (uint32_t)hp.policy_delay != 0u) return;
-  const float* an = net_ptr(d, d.theta, agent, 0);
-  const float* cn = net_ptr(d, d.theta, agent, 1);
-  LayerPre<MT> pre;
-  pre.load(an, d.actor, wave, lane);
-  const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
-  const size_t act_off = ((size_t)agent * d.B + r0) * kH;
-  float* part = d.apart + ((size_t)agent * d.chunks + chunk) * kAPart;
-  stage_head(v_aw3, an + d.actor.w3, A, tid);
-  stage_vector(v_ab3, an + d.actor.b3, A, tid);
-  stage_vector(v_cw3, cn + d.critic.w3, kH, tid);
-  stage_vector(v_cwa, cn + d.critic.w1 + d.O * kH, A * kH, tid);
-  const float cb3 = cn[d.critic.b3];
-  load_input<R>(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
-  __syncthreads();
-
-  const uint64_t mask_a1 = first_layer<MT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
-  __syncthreads();
-  hidden_layer<MT, DEEP>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane, [&]() { pre.load(cn, d.critic, wave, lane); });
-  __syncthreads();
-  thin_dot<R>(buf, v_aw3, A, head, tid);
-  __syncthreads();
-  for (int e = tid; e < R * A; e += kThreads) {
-    const int r = e / A, j = e - r * A;
-    const float a = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
-    api[r * kMaxAct + j] = a;
-    Xs[r * L.xld + d.O + j] = a;
-  }
-  __syncthreads();
-
-  // critic 1 on [s, a_pi]
-  if (!DEEP) pre.load(cn, d.critic, wave, lane);
-  const uint64_t mask_c1 = first_layer<MT>(Xs, L.xld, cn, d.critic, pre, buf, nullptr, wave, lane);
-  __syncthreads();
-  WeightBlock<MT, true> wt;
-  hidden_layer<MT, DEEP>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
-  __syncthreads();
-  thin_dot<R>(buf, v_cw3, 1, head, tid);     // q, for the loss value only
-  __syncthreads();
-  if (tid < 64) {
-    const float q = tid < R ? head[tid * kMaxAct] + cb3 : 0.0f;
-    const float s = wave_sum(q);
-    if (tid == 0) part[kAP_loss] = -s / (float)d.B;
-  }
-  {
-    const int c = tid;
-    const float seed = -v_cw3[c] / (float)d.B;
-#pragma unroll 1
-    for (int rb = 0; rb < R; rb += 8) {
-      float h[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) h[i] = buf[(rb + i) * kLda + c];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) buf[(rb + i) * kLda + c] = h[i] > 0.0f ? seed : 0.0f;
-    }
-  }
-  __syncthreads();
-  f32x4 h2r[R / 4];                                  // this thread's share of the parked h2 tile
-  {
-    Acc<MT> acc;
-    acc.zero();
-    const float* h2g = d.aH2 + act_off;
-    auto fetch_h2 = [&]() {
-#pragma unroll
-      for (int i = 0; i < R / 4; ++i)
-        h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
-    };
-    if (DEEP) {
-      gemm256<MT, true>(buf, kLda, cn + d.critic.w2, wt, wave, lane, acc, fetch_h2);
-    } else {
-      wt.load(cn + d.critic.w2, 0, wave, lane);
-      gemm256_lean<MT, true>(buf, kLda, cn + d.critic.w2, wt, wave, lane, acc);
-      fetch_h2();
-    }
-    __syncthreads();                                 // every wavefront is done reading dz2 of the critic
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          buf[(32 * mt + acc_row(v, lane)) * kLda + 64 * wave + 32 * nt + (lane & 31)] =
-              mask_bit(mask_c1, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;      // dz1 of the critic
-  }
-  __syncthreads();
-  thin_dot<R>(buf, v_cwa, A, head, tid);      // da
-  if (DEEP) wt.load(an + d.actor.w2, 0, wave, lane); // block 0 of the actor's input-gradient product
-  __syncthreads();
-  for (int e = tid; e < R * kMaxAct; e += kThreads) {
-    const int j = e % kMaxAct;
-    const float a = j < A ? api[e] : 0.0f;
-    dz3[e] = j < A ? head[e] * (1.0f - a * a) : 0.0f;     // unused columns are kept at zero
-  }
-#pragma unroll
-  for (int i = 0; i < R / 4; ++i)                    // h2 of the actor back into the tile
-    *reinterpret_cast<f32x4*>(&buf[(4 * i + (tid >> 6)) * kLda + 4 * (tid & 63)]) = h2r[i];
-  __syncthreads();
-  if (tid < A) {
-    float s = 0.0f;
-    for (int r = 0; r < R; ++r) s += dz3[r * kMaxAct + tid];
-    part[kAP_db3 + tid] = s;
-  }
-  {                                                  // actor head backward, one thread per hidden unit
-    const int c = tid;
-    float w3[kMaxAct], gw3[kMaxAct];
-#pragma unroll
-    for (int j = 0; j < kMaxAct; ++j) { w3[j] = j < A ? v_aw3[j * kH + c] : 0.0f; gw3[j] = 0.0f; }
-    float gb2 = 0.0f;
-    float* zg = d.adZ2 + act_off + c;
-#pragma unroll 1
-    for (int rb = 0; rb < R; rb += 4) {
-      float h[4];
-      f32x4 g[4][2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        h[i] = buf[(rb + i) * kLda + c];
-        g[i][0] = *reinterpret_cast<const f32x4*>(&dz3[(rb + i) * kMaxAct]);      // columns >= A hold zeros
-        g[i][1] = *reinterpret_cast<const f32x4*>(&dz3[(rb + i) * kMaxAct + 4]);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float dh = 0.0f;
-#pragma unroll
-        for (int j = 0; j < kMaxAct; ++j) {
-          const float gj = g[i][j >> 2][j & 3];
-          gw3[j] += h[i] * gj;
-          dh += gj * w3[j];
-        }
-        const float z = h[i] > 0.0f ? dh : 0.0f;
-        buf[(rb + i) * kLda + c] = z;
-        zg[(rb + i) * kH] = z;
-        gb2 += z;
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < kMaxAct; ++j)
-      if (j < A) part[kAP_dW3 + c * A + j] = gw3[j];
-    part[kAP_db2 + c] = gb2;
-  }
-  __syncthreads();
-  input_grad_to_global<MT, DEEP>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  actor_chain<MT, DEEP, false>(d, t, blockIdx.x, lds, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -585,14 +69,6 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
     act[((size_t)agent * n + r0 + r) * d.A + j] = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
   }
 }
-
-// ---------------------------------------------------------------------------------------------
-namespace {
-int vec_target(const PopDev& d) { return kH * d.A + 8 + 2 * kH + 8; }
-int vec_critic(const PopDev&) { return kH + 8; }
-int vec_actor(const PopDev& d) { return kH * d.A + 8 + kH + d.A * kH; }
-int vec_act(const PopDev& d) { return kH * d.A + 8; }
-}  // namespace
 
 hipError_t setup_kernels() {
   hipError_t e;

@@ -1,0 +1,85 @@
+// One update step of the whole population as a single launch (Sec. 4.1 of the paper: the
+// update steps of all population members are issued together and chained on the device).
+//
+// Blocks, in index order:
+//   target chains | critic chains | critic weight-gradient tiles | actor chains |
+//   actor weight-gradient tiles | gather of the next step's replay rows
+// Each part depends on the one before it only per agent or per network, never globally:
+// a critic chunk needs the Bellman targets of its own rows, a weight-gradient tile the 8
+// chunks of its own network, an actor chunk the updated critic 1 of its own agent.  Those
+// hand-overs happen inside the launch (tagged words and release/acquire counters, see
+// chains.h), so nothing waits for the slowest workgroup of a whole phase, memory-bound
+// Adam tiles run beside matrix-bound chains of other agents, and work that has no
+// dependency yet (the critics' forward pass, the actor's forward pass, the Adam operand
+// loads) starts at once.  Workgroups are dispatched in block order, so a workgroup only
+// ever waits for workgroups that were dispatched before it.
+#include "gather.h"
+#include "wgrad.h"
+
+namespace pop {
+
+struct StepGrid {
+  int t, c, wc, a, wa, g;          // blocks of each part
+  int roles_c, roles_a;            // weight-gradient roles per critic / actor network
+};
+
+template <int MT>
+__global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, StepGrid g) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  int b = blockIdx.x;
+  if (b == 0) {                                      // zero the counters the next step will count in
+    const int other = (int)((t + 1u) & 1u);
+    for (int i = threadIdx.x; i < 2 * d.P; i += kThreads) {
+      d.done_c[other * 2 * d.P + i] = 0u;
+      d.done_wc[other * 2 * d.P + i] = 0u;
+      if (i < d.P) d.done_a[other * d.P + i] = 0u;
+    }
+  }
+  if (b < g.t) { target_chain<MT, true>(d, t, b, lds); return; }
+  b -= g.t;
+  if (b < g.c) { critic_chain<MT, true, true, true>(d, t, b, lds); return; }
+  b -= g.c;
+  Adam* sh_adam = reinterpret_cast<Adam*>(lds + 32 * kLda);
+  if (b < g.wc) { wgrad_roles<true>(d, t, 0, b, g.roles_c, lds, sh_adam); return; }
+  b -= g.wc;
+  if (b < g.a) { actor_chain<MT, true, true>(d, t, b, lds, g.roles_c); return; }
+  b -= g.a;
+  if (b < g.wa) { wgrad_roles<true>(d, t, 1, b, g.roles_a, lds, sh_adam); return; }
+  b -= g.wa;
+  if (b < g.g) {
+    const int per = gather_blocks_per_agent(d);
+    gather_element(d, t + 1u, b / per, (b % per) * 256 + threadIdx.x);
+  }
+}
+
+hipError_t setup_step_kernel() {
+  hipError_t e = hipFuncSetAttribute((const void*)k_step<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)k_step<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+hipError_t launch_step(const PopDev& d, uint32_t t, int with_actor, int prefetch_next, hipStream_t s) {
+  StepGrid g;
+  g.roles_c = wgrad_role_count(d, 0);
+  g.roles_a = wgrad_role_count(d, 1);
+  g.t = xcd_grid(d.P, d.chunks);
+  g.c = xcd_grid(2 * d.P, d.chunks);
+  g.wc = xcd_grid(2 * d.P, g.roles_c);
+  g.a = with_actor ? xcd_grid(d.P, d.chunks) : 0;
+  g.wa = with_actor ? xcd_grid(d.P, g.roles_a) : 0;
+  g.g = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
+  int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
+  if (vec_actor(d) > vec) vec = vec_actor(d);
+  const size_t tiles = (size_t)(32 * kLda) * sizeof(float) + sizeof(Adam);
+  const dim3 grid(g.t + g.c + g.wc + g.a + g.wa + g.g);
+  if (d.mt == 2) {
+    size_t bytes = Lds<2>(d.D).bytes(vec);
+    k_step<2><<<grid, dim3(kThreads), bytes > tiles ? bytes : tiles, s>>>(d, t, g);
+  } else {
+    size_t bytes = Lds<1>(d.D).bytes(vec);
+    k_step<1><<<grid, dim3(kThreads), bytes > tiles ? bytes : tiles, s>>>(d, t, g);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace pop

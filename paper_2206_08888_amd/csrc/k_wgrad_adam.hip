@@ -1,247 +1,34 @@
-// Weight gradients contracted over the full batch, with the Adam update and the
-// Polyak target update applied in the epilogue (Sec. 1 of the paper: compute a
-// loss, differentiate it, apply a variant of SGD; Sec. 4.1: standard TD3
-// hyperparametrization, i.e. Adam and soft target updates).
-//
-// The gradient of a weight matrix is dW = X^T dZ with the batch as the
-// contraction index.  A workgroup owns a slab of 32 rows of dW (all 256
-// columns): it first transposes its 32 columns of X (written by the chain
-// kernels) into an LDS tile [32][batch], and then runs the same pipelined
-// 256-deep MFMA product as a hidden layer, with dZ streamed from global memory
-// in the role of the weights.  Each wavefront then updates exactly the
-// parameters it holds in its accumulators:
-//     m <- b1 m + (1 - b1) g ;  v <- b2 v + (1 - b2) g^2
-//     theta <- theta - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
-//     theta' <- (1 - tau) theta' + tau theta        (only on delayed steps)
-// (the two bias corrections enter as reciprocals computed once per workgroup in
-// double; the final quotient uses the hardware reciprocal, 1 ulp)
-// so a gradient never makes a round trip through HBM.  The parameters, moments
-// and targets of the first half of the slab are requested under the last blocks
-// of the product, so their HBM latency is hidden behind the MFMA work.  The
-// small tensors (biases, head weights) arrive as per-chunk partial sums and are
-// reduced and updated by one extra workgroup per network.
-//
-// 1-D grid, decoded so that the roles of one network share an XCD (its L2 then
-// serves the re-reads of dZ).  Roles of one network:
-//   [0, 8)             32-row slabs of W2
-//   [8, 8 + n1)        32-row slabs of the layer-1 weights (rows >= fan-in masked)
-//   8 + n1             b1, b2, W3, b3 and the loss value
-// Blocks past the last network gather the replay rows of step t + 1 into the
-// other half of the double-buffered batch (App. A of the paper: the next
-// batches are fetched while the current update runs).  The batch size must be
-// 256 for the slab product (its contraction depth is fixed).
+// Weight gradients + Adam + Polyak as a launch of its own (wgrad.h has the work); extra
+// blocks past the last network gather the replay rows of step t + 1 into the other half of
+// the double-buffered batch (App. A of the paper: the next batches are fetched while the
+// current update runs).
 #include "gather.h"
-#include "launch.h"
-#include "mfma_tiles.h"
+#include "wgrad.h"
 
 namespace pop {
-
-namespace {
-
-struct Adam {
-  float lr, b1, b2, eps, inv_c1, inv_c2, tau;
-  int polyak, record;
-};
-
-struct AdamRegs { float th, m, v, tg; };
-
-// b^n in double by repeated squaring (at most 64 roundings: far below fp32 resolution)
-__device__ inline double ipow(double b, uint32_t n) {
-  double r = 1.0;
-  for (; n; n >>= 1) {
-    if (n & 1u) r *= b;
-    b *= b;
-  }
-  return r;
-}
-
-__device__ inline AdamRegs adam_load(const Adam& a, uint32_t i, const float* __restrict__ th, const float* __restrict__ m,
-                                     const float* __restrict__ v, const float* __restrict__ tg) {
-  AdamRegs r;
-  r.th = th[i]; r.m = m[i]; r.v = v[i];
-  r.tg = a.polyak ? tg[i] : 0.0f;
-  return r;
-}
-
-__device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uint32_t i, float* __restrict__ th,
-                                  float* __restrict__ m, float* __restrict__ v, float* __restrict__ tg,
-                                  float* __restrict__ gr) {
-  const float mm = a.b1 * r.m + (1.0f - a.b1) * g;
-  const float vv = a.b2 * r.v + (1.0f - a.b2) * (g * g);
-  m[i] = mm;
-  v[i] = vv;
-  const float denom = __builtin_amdgcn_sqrtf(vv * a.inv_c2) + a.eps;
-  const float tn = r.th - a.lr * (mm * a.inv_c1) * __builtin_amdgcn_rcpf(denom);
-  th[i] = tn;
-  if (a.polyak) tg[i] = (1.0f - a.tau) * r.tg + a.tau * tn;
-  if (a.record) gr[i] = g;
-}
-
-// One 32 x 128 tile of a weight matrix [M][256]: rows m0 .. m0+31 (rows >= M masked),
-// columns n0 .. n0+127, 32 per wavefront.
-//   x: [256][ldx] layer input, z: [256][256] pre-activation gradient, both global;
-//   base: offset of the matrix inside the network's parameter block.
-// The tile's parameters, moments and targets do not depend on the product, so they are
-// requested first and arrive while the operands are staged and multiplied.  `sh` is
-// written by thread 0 before the call and read after the barrier inside.
-__device__ __forceinline__ void weight_tile(const Adam* sh, bool polyak, const float* __restrict__ x, int ldx, int M, int m0,
-                                   int n0, const float* __restrict__ z, uint32_t base, float* Xl,
-                                   float* __restrict__ th, float* __restrict__ mo, float* __restrict__ ve,
-                                   float* __restrict__ tg, float* __restrict__ gr, int tid) {
-  const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
-  POP_MARK(50);
-  // flat offset of accumulator element v = 0 of this lane
-  const uint32_t elem0 = base + (uint32_t)((m0 + 4 * half) * kH + n0 + 32 * wave + l32);
-  AdamRegs regs[16];
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const bool ok = (m0 + acc_row(v, lane)) < M;
-    const uint32_t i = ok ? elem0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH) : elem0;
-    regs[v].th = th[i]; regs[v].m = mo[i]; regs[v].v = ve[i];
-    regs[v].tg = polyak ? tg[i] : 0.0f;
-  }
-  WeightBlock<1, false, 1> z0;
-  z0.load(z + n0, 0, wave, lane);
-  POP_MARK(51);
-  {                                                  // X^T slice into LDS: thread b copies row b
-    const float* xr = x + (size_t)tid * ldx + m0;
-    if ((ldx & 3) == 0) {                            // 16-byte aligned rows (a hidden layer's output)
-      f32x4 v[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(xr + 4 * i);
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) Xl[(4 * i + q) * kLda + tid] = v[i][q];
-    } else {                                         // batch rows: any stride, columns >= M are zero
-      float v[32];
-#pragma unroll
-      for (int m = 0; m < 32; ++m) {
-        const int mm = (m0 + m) < M ? m : 0;
-        v[m] = xr[mm];
-      }
-#pragma unroll
-      for (int m = 0; m < 32; ++m) Xl[m * kLda + tid] = (m0 + m) < M ? v[m] : 0.0f;
-    }
-  }
-  __syncthreads();
-  POP_MARK(52);
-  const Adam adam = *sh;
-  Acc<1, 1> acc;
-  acc.zero();
-  gemm256<1, false, 1>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());
-  POP_MARK(53);
-  uint32_t e1 = elem0;
-  asm volatile("" : "+v"(e1));                       // recompute the addresses: keeping 64 of them alive costs more
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    if ((m0 + acc_row(v, lane)) < M)
-      adam_store(adam, regs[v], acc.t[0][0][v], e1 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH), th, mo, ve, tg, gr);
-    if ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-  }
-  POP_MARK(54);
-}
-
-}  // namespace
 
 __global__ __launch_bounds__(kThreads, 3) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
                                                           int roles, int prefetch) {
   __shared__ Adam sh_adam;
   __shared__ __attribute__((aligned(16))) float xt_lds[32 * kLda];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   POP_MARK(49);
   if ((int)blockIdx.x >= main_blocks) {              // gather role: rows of the next step
     if (prefetch) {
       const int g = blockIdx.x - main_blocks, per = gather_blocks_per_agent(d);
-      gather_element(d, t + 1u, g / per, (g % per) * 256 + tid);
+      gather_element(d, t + 1u, g / per, (g % per) * 256 + threadIdx.x);
     }
     return;
   }
-  int unit, role;
-  if (!decode_block(blockIdx.x, actor_phase ? d.P : 2 * d.P, roles, unit, role)) return;
-  const int agent = actor_phase ? unit : unit >> 1;
-  const int net = actor_phase ? 0 : 1 + (unit & 1);
-  const HpDev hp = d.hp[agent];
-  const uint32_t delay = (uint32_t)hp.policy_delay;
-  const bool delayed_step = (t % delay) == 0u;
-  if (actor_phase && !delayed_step) return;
+  wgrad_roles<false>(d, t, actor_phase, blockIdx.x, roles, xt_lds, &sh_adam);
+}
 
-  if (tid == 0) {                                    // read by everyone after the next barrier
-    Adam a;
-    const uint32_t count = actor_phase ? t / delay + 1u : t + 1u;   // 1-based Adam step
-    a.lr = actor_phase ? hp.lr_actor : hp.lr_critic;
-    a.b1 = hp.b1; a.b2 = hp.b2; a.eps = hp.eps;
-    a.inv_c1 = (float)(1.0 / (1.0 - ipow((double)hp.b1, count)));
-    a.inv_c2 = (float)(1.0 / (1.0 - ipow((double)hp.b2, count)));
-    a.tau = hp.tau;
-    a.polyak = delayed_step ? 1 : 0;
-    a.record = d.record_grads;
-    sh_adam = a;
-  }
-
+int wgrad_role_count(const PopDev& d, int actor_phase) {
   const NetLayout& L = actor_phase ? d.actor : d.critic;
-  float* th = net_ptr(d, d.theta, agent, net);
-  float* mo = net_ptr(d, d.m, agent, net);
-  float* ve = net_ptr(d, d.v, agent, net);
-  float* tg = net_ptr(d, d.target, agent, net);
-  float* gr = net_ptr(d, d.grad, agent, net);
-
-  const int n1 = (L.in + 31) / 32;
-  if (role < 16 + 2 * n1) {
-    const size_t o = (size_t)unit * d.B * kH;        // unit = agent (actor) or network (critics)
-    const int n0 = 128 * (role & 1);
-    const bool w2 = role < 16;                       // else layer 1, whose input is the leading columns of the batch rows
-    const float* x = w2 ? (actor_phase ? d.aH1 : d.cH1) + o : batch_rows(d, t, agent);
-    const float* z = (w2 ? (actor_phase ? d.adZ2 : d.cdZ2) : (actor_phase ? d.adZ1 : d.cdZ1)) + o;
-    weight_tile(&sh_adam, delayed_step, x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
-                (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
-  } else {
-    // small tensors from per-chunk partial sums; thread c owns hidden unit c
-    __syncthreads();
-    const Adam adam = sh_adam;
-    const int c = tid;
-    const int out = L.out;
-    float gb1 = 0.0f, gb2 = 0.0f, gw3[kMaxAct], gb3 = 0.0f, loss = 0.0f;
-#pragma unroll
-    for (int j = 0; j < kMaxAct; ++j) gw3[j] = 0.0f;
-#pragma unroll 4
-    for (int ch = 0; ch < d.chunks; ++ch) {
-      if (actor_phase) {
-        const float* p = d.apart + ((size_t)agent * d.chunks + ch) * kAPart;
-        gb1 += p[kAP_db1 + c];
-        gb2 += p[kAP_db2 + c];
-#pragma unroll
-        for (int j = 0; j < kMaxAct; ++j)
-          if (j < out) gw3[j] += p[kAP_dW3 + c * out + j];
-        if (c < out) gb3 += p[kAP_db3 + c];
-        if (c == 0) loss += p[kAP_loss];
-      } else {
-        const float* p = d.cpart + ((size_t)unit * d.chunks + ch) * kCPart;
-        gb1 += p[kCP_db1 + c];
-        gb2 += p[kCP_db2 + c];
-        gw3[0] += p[kCP_dW3 + c];
-        if (c == 0) { gb3 += p[kCP_db3]; loss += p[kCP_loss]; }
-      }
-    }
-    auto upd = [&](float g, uint32_t i) { adam_store(adam, adam_load(adam, i, th, mo, ve, tg), g, i, th, mo, ve, tg, gr); };
-    upd(gb1, (uint32_t)(L.b1 + c));
-    upd(gb2, (uint32_t)(L.b2 + c));
-#pragma unroll
-    for (int j = 0; j < kMaxAct; ++j)
-      if (j < out) upd(gw3[j], (uint32_t)(L.w3 + c * out + j));
-    if (c < out) upd(gb3, (uint32_t)(L.b3 + c));
-    if (c == 0) {
-      // critic loss = sum over the twins; the two critic workgroups of an agent write
-      // their halves to separate slots and the reader adds them
-      if (actor_phase) d.losses[(size_t)agent * 4 + 2] = loss;
-      else d.losses[(size_t)agent * 4 + (net - 1)] = loss;
-    }
-  }
+  return 16 + 2 * ((L.in + 31) / 32) + 1;
 }
 
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s) {
-  const NetLayout& L = actor_phase ? d.actor : d.critic;
-  const int roles = 16 + 2 * ((L.in + 31) / 32) + 1;
+  const int roles = wgrad_role_count(d, actor_phase);
   const int main_blocks = xcd_grid(actor_phase ? d.P : 2 * d.P, roles);
   const int extra = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
   hipLaunchKernelGGL(k_wgrad_adam, dim3(main_blocks + extra), dim3(kThreads), 0, s, d, t, actor_phase, main_blocks,

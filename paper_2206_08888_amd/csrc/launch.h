@@ -24,6 +24,11 @@ hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s);
 // prefetch_next != 0: extra workgroups also gather the replay rows of step t + 1
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s);
 
+// the whole step as one launch (k_step.hip); with_actor: some agent has its delayed actor step at t
+hipError_t launch_step(const PopDev& d, uint32_t t, int with_actor, int prefetch_next, hipStream_t s);
+hipError_t setup_step_kernel();
+int wgrad_role_count(const PopDev& d, int actor_phase);
+
 // acting: obs[P][n][O] -> act[P][n][A] through the online actors
 hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, hipStream_t s);
 

@@ -35,6 +35,16 @@ __device__ inline f32x16 mfma32(float a, float b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
+// Global store of a result that another workgroup of the SAME launch reads (THROUGH): a
+// device-scope atomic store, which is written through the XCD's L2 to memory instead of
+// waiting there as a dirty line, so that the producer only has to see its own stores
+// acknowledged before it signals, not have the whole L2 written back.
+template <bool THROUGH>
+__device__ inline void put(float* p, float v) {
+  if (THROUGH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+
 __device__ inline int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 
 // NT = 32-column tiles per wavefront: 2 in the layer chains (a workgroup spans 256
@@ -284,7 +294,7 @@ __device__ inline void gemm256_lean(const float* __restrict__ Xl, int ldx, const
 // the backward pass can apply ReLU' without re-reading the activations: the
 // input-gradient product leaves element (row, col) in the same lane and
 // register as the forward product did.
-template <int MT>
+template <int MT, bool THROUGH = false>
 __device__ inline uint64_t relu_store(const Acc<MT>& acc, const float (&bb)[2], float* __restrict__ Yl,
                                       float* __restrict__ Yg, int wave, int lane) {
   uint64_t mask = 0;
@@ -299,7 +309,7 @@ __device__ inline uint64_t relu_store(const Acc<MT>& acc, const float (&bb)[2], 
         const float h = fmaxf(acc.t[mt][nt][v] + bb[nt], 0.0f);
         if (h > 0.0f) mask |= 1ull << ((2 * mt + nt) * 16 + v);
         Yl[row * kLda + col] = h;
-        if (Yg) Yg[(size_t)row * kH + col] = h;
+        if (Yg) put<THROUGH>(Yg + (size_t)row * kH + col, h);
       }
   return mask;
 }

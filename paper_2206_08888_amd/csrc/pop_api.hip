@@ -23,7 +23,7 @@ constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
   int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
-  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, fault, staging, replay, total;
+  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, fault, staging, replay, total;
   int64_t param_bytes;
 };
 
@@ -44,7 +44,7 @@ struct pop_ctx {
   std::vector<uint64_t> count;   // host mirror of the buffer fill levels
   uint64_t t;                    // update steps taken
   uint64_t gathered_t;           // step whose batch already sits in its half of the double buffer
-  bool fuse_tc;                  // target and critic chains in one launch
+  int fuse;                      // 0: one launch per chain, 1: target + critic chains fused, 2: one launch per step
   std::string err;
 };
 
@@ -119,6 +119,7 @@ Layout make_ws_layout(const PopDev& d) {
   L.apart = take(P * (int64_t)d.chunks * kAPart * 4);
   L.losses = take(P * 4 * 4);
   L.y_tagged = take(P * B * 8);
+  L.done_c = take(4 * P * 4); L.done_wc = take(4 * P * 4); L.done_a = take(2 * P * 4);
   L.fault = take(4);
   L.staging = take(kStagingBytes);
   L.replay = take(P * (int64_t)d.capacity * d.row * 4);
@@ -203,8 +204,16 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->stream = (hipStream_t)hip_stream;
   ctx->t = 0;
   ctx->gathered_t = ~0ull;
-  ctx->fuse_tc = true;
-  if (const char* env = getenv("POP_FUSE_TC")) ctx->fuse_tc = atoi(env) != 0;
+  // One launch per step pays once the parts of a step are each several times larger than
+  // the 512 workgroups the chip holds at once (tails of one part overlap the next part);
+  // for small populations everything is resident at once anyway, the chains of a step are
+  // latency-bound, and waiting weight-gradient workgroups would only take the slots the
+  // actor chains could start in, so there the parts stay separate launches apart from
+  // the target/critic pair.
+  // (The 64-row chains of very large populations do not fit the register budget of the
+  // single kernel without spilling and stay separate as well.)
+  ctx->fuse = (d.mt == 1 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512) ? 2 : 1;
+  if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 2) ctx->fuse = v; }
   ctx->hp.assign(hp, hp + cfg->P);
   ctx->count.assign(cfg->P, 0);
   ctx->hp_dev.resize(cfg->P);
@@ -230,7 +239,8 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.aH1 = (float*)(w + L.aH1); d.aH2 = (float*)(w + L.aH2); d.adZ2 = (float*)(w + L.adZ2);
   d.adZ1 = (float*)(w + L.adZ1);
   d.cpart = (float*)(w + L.cpart); d.apart = (float*)(w + L.apart); d.losses = (float*)(w + L.losses);
-  d.y_tagged = (uint64_t*)(w + L.y_tagged); d.fault = (uint32_t*)(w + L.fault);
+  d.y_tagged = (uint64_t*)(w + L.y_tagged); d.done_c = (uint32_t*)(w + L.done_c); d.done_wc = (uint32_t*)(w + L.done_wc); d.done_a = (uint32_t*)(w + L.done_a);
+  d.fault = (uint32_t*)(w + L.fault);
   ctx->d = d;
 
   auto bail = [&](hipError_t e, const char* what) {
@@ -239,7 +249,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
     return rc;
   };
   hipError_t e;
-  if ((e = setup_kernels()) != hipSuccess) return bail(e, "kernel attribute setup");
+  if ((e = setup_kernels()) != hipSuccess || (e = setup_step_kernel()) != hipSuccess) return bail(e, "kernel attribute setup");
   hipStream_t s = ctx->stream;
   // everything between the hyperparameters and the staging area starts at zero
   if ((e = hipMemsetAsync(w, 0, (size_t)L.staging, s)) != hipSuccess) return bail(e, "hipMemsetAsync");
@@ -321,7 +331,18 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
   };
   if (ctx->gathered_t != ctx->t && !run(POP_K_GATHER, launch_sample_gather))
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
-  if (ctx->fuse_tc) {
+  bool any_actor = false;
+  for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
+  if (ctx->fuse == 2) {
+    tick(POP_K_STEP, 0);
+    e = launch_step(d, t, any_actor ? 1 : 0, has_next ? 1 : 0, s);
+    tick(POP_K_STEP, 1);
+    if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    if (has_next) ctx->gathered_t = ctx->t + 1;
+    ctx->t++;
+    return POP_OK;
+  }
+  if (ctx->fuse == 1) {
     if (!run(POP_K_TARGET_CRITIC, launch_target_critic)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
   } else if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic)) {
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
@@ -331,8 +352,6 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
   tick(POP_K_WGRAD_CRITIC, 1);
   if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
   if (has_next) ctx->gathered_t = ctx->t + 1;
-  bool any_actor = false;
-  for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
   if (any_actor) {
     if (!run(POP_K_ACTOR, launch_actor)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
     tick(POP_K_WGRAD_ACTOR, 0);

@@ -82,7 +82,10 @@ struct PopDev {
   float* losses;               // [P][4]: critic 1, critic 2, actor, unused
   // cross-workgroup signalling inside a launch
   uint64_t* y_tagged;          // [P][B]: (t + 1) << 32 | bits of y, for readers inside the launch that writes y
-  uint32_t* fault;             // [1]: bit 0 = a bounded wait ran out
+  uint32_t* done_c;            // [2][2P] critic chunks finished per network, by step parity
+  uint32_t* done_wc;           // [2][2P] critic weight-gradient roles finished per network
+  uint32_t* done_a;            // [2][P]  actor chunks finished per agent
+  uint32_t* fault;             // [1]: bit 0 = a wait for y ran out, bit 1 = a wait for a count
 };
 
 // critic partial record: dW3[256] db3[1] pad[3] db2[256] db1[256] loss[1] pad[3]

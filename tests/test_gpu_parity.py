@@ -238,24 +238,35 @@ def test_set_params_round_trips_and_rejects_bad_arguments():
     gpu.close()
 
 
-def test_fused_and_separate_target_critic_launches_agree_bit_for_bit(monkeypatch):
-    """The target and critic chains as one launch (critic workgroups wait inside the
-    kernel for the targets of their rows) against the same chains as two launches:
-    identical arithmetic, so every parameter and moment must be bit-identical, also
-    for a population size that is not a multiple of 8 (uneven XCD groups)."""
+def test_launch_structures_agree_bit_for_bit(monkeypatch):
+    """One launch per step (parts hand results on inside the launch: tagged words for the
+    Bellman targets, release/acquire counters for activation tiles and updated critics),
+    target + critic chains fused, and one launch per part: identical arithmetic, so every
+    parameter and moment must be bit-identical, also for a population size that is not a
+    multiple of 8 (uneven XCD groups) and with mixed policy delays (agents whose actor
+    parts leave early)."""
+    hps = workloads.hparams(2, 11)
+    for i, hp in enumerate(hps):
+        hp["policy_delay"] = (2, 1, 3)[i % 3]
     states = []
-    for fuse in ("1", "0"):
-        monkeypatch.setenv("POP_FUSE_TC", fuse)
-        gpu, _, _ = make_pair(2, P=11, capacity=3000, oracle=False)
+    for fuse in ("2", "1", "0"):
+        monkeypatch.setenv("POP_FUSE", fuse)
+        gpu, _, _ = make_pair(2, P=11, capacity=3000, hps=hps, oracle=False)
         gpu.update(7)
         ms, cnt = gpu.update_timed(6)
-        assert cnt["gather"] == 1 and cnt["wgrad_critic"] == 6 and cnt["actor"] == cnt["wgrad_actor"] == 3
-        if fuse == "1":
-            assert cnt["target_critic"] == 6 and cnt["target"] == cnt["critic"] == 0
+        assert cnt["gather"] == 1
+        if fuse == "2":
+            assert cnt["step"] == 6 and sum(cnt.values()) == 7
         else:
-            assert cnt["target_critic"] == 0 and cnt["target"] == cnt["critic"] == 6
+            assert cnt["step"] == 0 and cnt["wgrad_critic"] == 6 and cnt["actor"] == cnt["wgrad_actor"] == 6
+            if fuse == "1":
+                assert cnt["target_critic"] == 6 and cnt["target"] == cnt["critic"] == 0
+            else:
+                assert cnt["target_critic"] == 0 and cnt["target"] == cnt["critic"] == 6
         assert all(ms[k] > 0.0 for k in ms if cnt[k]) and gpu.step_count() == 13
+        gpu.sync()
         states.append({(i, w): gpu.get_params(i, w) for i in range(11) for w in pp.PARAM_CODES if not w.startswith("g_")})
         gpu.close()
-    for key in states[0]:
-        assert np.array_equal(states[0][key], states[1][key]), key
+    for other in states[1:]:
+        for key in states[0]:
+            assert np.array_equal(states[0][key], other[key]), key

@@ -19,7 +19,7 @@ import numpy as np
 import pytest
 
 import workloads
-from gpu_common import (PARAMS6, ForcedStepStats, ensure_built, force_state, forced_step_errors,
+from gpu_common import (PARAMS6, STATE12, ForcedStepStats, ensure_built, force_state, forced_step_errors,
                         make_full_size_pair, rel_l2)
 
 pytestmark = pytest.mark.gpu
@@ -74,3 +74,22 @@ def test_sampled_agents_match_oracle_at_full_size(config_id):
     assert ec <= 1e-2, (config_id, ec)
     assert gpu.step_count() == 100
     gpu.close()
+
+
+def test_single_launch_step_equals_separate_launches_bit_for_bit_at_p80(monkeypatch):
+    """Config 2 at full size: the update step as ONE launch (results passed between
+    workgroups inside the launch) against one launch per part, 60 steps.  The arithmetic
+    is the same, so a single stale or early read anywhere in the hand-overs would show as a
+    bit difference in some parameter or moment of some agent."""
+    agents = (0, 7, 33, 64, 79)
+    states = []
+    for fuse in ("2", "0"):
+        monkeypatch.setenv("POP_FUSE", fuse)
+        gpu, _ = make_full_size_pair(2, [])
+        gpu.update(60)
+        gpu.sync()
+        assert gpu.step_count() == 60
+        states.append({(i, w): gpu.get_params(i, w) for i in agents for w in STATE12})
+        gpu.close()
+    for key in states[0]:
+        assert np.array_equal(states[0][key], states[1][key]), key

@@ -42,6 +42,7 @@ def kernel_flops(P, B, O, A):
     }
     per_agent["target_critic"] = per_agent["target"] + per_agent["critic"]
     # the whole step as one launch: average over launches with and without the delayed actor part (delay 2)
+    per_agent["step_tail"] = per_agent["wgrad_critic"] + per_agent["actor"] + per_agent["wgrad_actor"]
     per_agent["step"] = (per_agent["target_critic"] + per_agent["wgrad_critic"]
                          + (per_agent["actor"] + per_agent["wgrad_actor"]) / 2)
     return {k: v * P for k, v in per_agent.items()}

@@ -148,8 +148,10 @@ int pop_update(pop_ctx* ctx, int32_t n_steps);
  * results on per agent / per network inside the launch.  The environment
  * variable POP_FUSE, read at pop_create, selects the launch structure:
  *   2 one launch per step (default for populations of more than about 40 agents);
- *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest
- *     as separate launches (default for smaller populations);
+ *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC); on steps
+ *     with an actor update the rest of the step in a second launch
+ *     (POP_K_STEP_TAIL), else POP_K_WGRAD_CRITIC (default for smaller
+ *     populations);
  *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR).
  * The arithmetic, and so every result, is bit-identical in all three. */
 enum {
@@ -161,7 +163,8 @@ enum {
   POP_K_WGRAD_ACTOR = 5,   /* actor weight gradients + Adam + Polyak */
   POP_K_TARGET_CRITIC = 6, /* POP_K_TARGET and POP_K_CRITIC in one launch */
   POP_K_STEP = 7,          /* the whole step in one launch */
-  POP_K_COUNT = 8
+  POP_K_STEP_TAIL = 8,     /* critic weight gradients, actor chain, actor weight gradients in one launch */
+  POP_K_COUNT = 9
 };
 
 /* Measurement variant of pop_update (same work, same results): every kernel

@@ -162,7 +162,7 @@ def pop_update(ctx, n_steps):
     return _check(load_library().pop_update(ctx, n_steps), ctx)
 
 
-KERNEL_NAMES = ("gather", "target", "critic", "wgrad_critic", "actor", "wgrad_actor", "target_critic", "step")
+KERNEL_NAMES = ("gather", "target", "critic", "wgrad_critic", "actor", "wgrad_actor", "target_critic", "step", "step_tail")
 
 
 def pop_update_timed(ctx, n_steps):

@@ -191,11 +191,12 @@ __device__ inline float await_y(const PopDev& d, size_t row, uint32_t t) {
 // A device-scope release fence in the producer would give the same ordering by the book,
 // but it writes back every dirty line of the XCD's L2 -- all the Adam state other
 // workgroups are streaming out -- and was measured at +40 % step time at P = 80.
-// Counts start at zero in every launch: the counters are double-buffered by step parity
-// and a launch clears the other half for its successor.  Consumers always have higher
+// Counts start at zero in every launch: there are two sets of counters, a launch counts in
+// one (d.sync_half, alternated by the host from launch to launch) and clears the other for
+// its successor.  Consumers always have higher
 // block indices than their producers, and workgroups are dispatched in index order, so a
 // wait only ever concerns workgroups already dispatched.
-__device__ inline int parity_base(const PopDev& d, uint32_t t, int n) { return (int)(t & 1u) * n; }
+__device__ inline int parity_base(const PopDev& d, uint32_t, int n) { return d.sync_half * n; }
 __device__ inline void signal_count(uint32_t* count, int tid) {
   __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): this wavefront's stores are acknowledged
   __syncthreads();
@@ -435,6 +436,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
   if (t % (uint32_t)hp.policy_delay != 0u) return;
   const float* an = net_ptr(d, d.theta, agent, 0);
   const float* cn = net_ptr(d, d.theta, agent, 1);
+  POP_MARK(8);
   LayerPre<MT> pre;
   pre.load(an, d.actor, wave, lane);
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
@@ -468,6 +470,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
   __syncthreads();
 
   // critic 1 on [s, a_pi]
+  POP_MARK(9);
   if (WAIT) {
     if (tid == 0) wait_count(d, d.done_wc + parity_base(d, t, 2 * d.P) + 2 * agent, (uint32_t)critic_roles);
     __syncthreads();
@@ -477,11 +480,13 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
   } else if (!DEEP) {
     pre.load(cn, d.critic, wave, lane);
   }
+  POP_MARK(10);
   const uint64_t mask_c1 = first_layer<MT>(Xs, L.xld, cn, d.critic, pre, buf, nullptr, wave, lane);
   __syncthreads();
   WeightBlock<MT, true> wt;
   hidden_layer<MT, DEEP>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
   __syncthreads();
+  POP_MARK(11);
   thin_dot<R>(buf, v_cw3, 1, head, tid);     // q, for the loss value only
   __syncthreads();
   if (tid < 64) {
@@ -530,6 +535,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
               mask_bit(mask_c1, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;      // dz1 of the critic
   }
   __syncthreads();
+  POP_MARK(12);
   thin_dot<R>(buf, v_cwa, A, head, tid);      // da
   if (DEEP) wt.load(an + d.actor.w2, 0, wave, lane); // block 0 of the actor's input-gradient product
   __syncthreads();
@@ -585,7 +591,9 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
     put<WAIT>(part + kAP_db2 + c, gb2);
   }
   __syncthreads();
+  POP_MARK(13);
   input_grad_to_global<MT, DEEP, WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  POP_MARK(14);
   if (WAIT) signal_count(d.done_a + parity_base(d, t, d.P) + agent, tid);
 }
 

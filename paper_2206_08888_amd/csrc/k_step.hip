@@ -1,7 +1,8 @@
 // One update step of the whole population as a single launch (Sec. 4.1 of the paper: the
 // update steps of all population members are issued together and chained on the device).
 //
-// Blocks, in index order:
+// (Smaller populations run the target and critic chains as a launch of their own and only
+// the rest of the step here: with_chains = 0.)  Blocks, in index order:
 //   target chains | critic chains | critic weight-gradient tiles | actor chains |
 //   actor weight-gradient tiles | gather of the next step's replay rows
 // Each part depends on the one before it only per agent or per network, never globally:
@@ -19,7 +20,7 @@
 namespace pop {
 
 struct StepGrid {
-  int t, c, wc, a, wa, g;          // blocks of each part
+  int t, c, wc, a, wa, g;          // blocks of each part (0: the part is not in this launch)
   int roles_c, roles_a;            // weight-gradient roles per critic / actor network
 };
 
@@ -27,8 +28,10 @@ template <int MT>
 __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, StepGrid g) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   int b = blockIdx.x;
+  POP_MARK(63);
   if (b == 0) {                                      // zero the counters the next step will count in
-    const int other = (int)((t + 1u) & 1u);
+                                                     // (whichever part block 0 belongs to)
+    const int other = d.sync_half ^ 1;
     for (int i = threadIdx.x; i < 2 * d.P; i += kThreads) {
       d.done_c[other * 2 * d.P + i] = 0u;
       d.done_wc[other * 2 * d.P + i] = 0u;
@@ -40,7 +43,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
   if (b < g.c) { critic_chain<MT, true, true, true>(d, t, b, lds); return; }
   b -= g.c;
   Adam* sh_adam = reinterpret_cast<Adam*>(lds + 32 * kLda);
-  if (b < g.wc) { wgrad_roles<true>(d, t, 0, b, g.roles_c, lds, sh_adam); return; }
+  if (b < g.wc) { wgrad_roles<true>(d, t, 0, b, g.roles_c, lds, sh_adam, g.c != 0); return; }
   b -= g.wc;
   if (b < g.a) { actor_chain<MT, true, true>(d, t, b, lds, g.roles_c); return; }
   b -= g.a;
@@ -58,12 +61,15 @@ hipError_t setup_step_kernel() {
   return hipFuncSetAttribute((const void*)k_step<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 
-hipError_t launch_step(const PopDev& d, uint32_t t, int with_actor, int prefetch_next, hipStream_t s) {
+hipError_t launch_step(const PopDev& dev, uint32_t t, uint32_t launch_seq, int with_chains, int with_actor,
+                       int prefetch_next, hipStream_t s) {
+  PopDev d = dev;
+  d.sync_half = (int)(launch_seq & 1u);              // the previous launch of this kernel cleared this half
   StepGrid g;
   g.roles_c = wgrad_role_count(d, 0);
   g.roles_a = wgrad_role_count(d, 1);
-  g.t = xcd_grid(d.P, d.chunks);
-  g.c = xcd_grid(2 * d.P, d.chunks);
+  g.t = with_chains ? xcd_grid(d.P, d.chunks) : 0;       // else: target and critic chains ran in an earlier launch
+  g.c = with_chains ? xcd_grid(2 * d.P, d.chunks) : 0;
   g.wc = xcd_grid(2 * d.P, g.roles_c);
   g.a = with_actor ? xcd_grid(d.P, d.chunks) : 0;
   g.wa = with_actor ? xcd_grid(d.P, g.roles_a) : 0;

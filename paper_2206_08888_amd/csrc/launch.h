@@ -24,8 +24,11 @@ hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s);
 // prefetch_next != 0: extra workgroups also gather the replay rows of step t + 1
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s);
 
-// the whole step as one launch (k_step.hip); with_actor: some agent has its delayed actor step at t
-hipError_t launch_step(const PopDev& d, uint32_t t, int with_actor, int prefetch_next, hipStream_t s);
+// the step as one launch (k_step.hip); with_chains = 0: without the target and critic chains (launched
+// before); with_actor: some agent has its delayed actor step at t; launch_seq: 0, 1, 2, ... over the
+// launches of this kernel on this population (alternates the two sets of hand-over counters)
+hipError_t launch_step(const PopDev& d, uint32_t t, uint32_t launch_seq, int with_chains, int with_actor,
+                       int prefetch_next, hipStream_t s);
 hipError_t setup_step_kernel();
 int wgrad_role_count(const PopDev& d, int actor_phase);
 

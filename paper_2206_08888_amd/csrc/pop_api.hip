@@ -44,6 +44,7 @@ struct pop_ctx {
   std::vector<uint64_t> count;   // host mirror of the buffer fill levels
   uint64_t t;                    // update steps taken
   uint64_t gathered_t;           // step whose batch already sits in its half of the double buffer
+  uint32_t step_launches;        // launches of the step kernel so far (alternates its hand-over counters)
   int fuse;                      // 0: one launch per chain, 1: target + critic chains fused, 2: one launch per step
   std::string err;
 };
@@ -92,8 +93,6 @@ void fill_dims(const pop_config& c, PopDev& d) {
   if (const char* env = getenv("POP_ROW_TILES")) { const int v = atoi(env); if (v == 1 || v == 2) d.mt = v; }
   d.chunks = c.batch / (32 * d.mt);
   if (const char* env = getenv("POP_LEAN")) d.lean = atoi(env) > 0 ? 1 : (atoi(env) < 0 ? -1 : 0);
-  d.stagger_w = 1000;           // 10 us: about half of a workgroup's time in the weight-gradient kernel
-  if (const char* env = getenv("POP_STAGGER_W")) d.stagger_w = atoi(env);
   d.actor = make_layout(d.O, d.A);
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
@@ -204,6 +203,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->stream = (hipStream_t)hip_stream;
   ctx->t = 0;
   ctx->gathered_t = ~0ull;
+  ctx->step_launches = 0;
   // One launch per step pays once the parts of a step are each several times larger than
   // the 512 workgroups the chip holds at once (tails of one part overlap the next part);
   // for small populations everything is resident at once anyway, the chains of a step are
@@ -335,7 +335,7 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
   for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
   if (ctx->fuse == 2) {
     tick(POP_K_STEP, 0);
-    e = launch_step(d, t, any_actor ? 1 : 0, has_next ? 1 : 0, s);
+    e = launch_step(d, t, ctx->step_launches++, 1, any_actor ? 1 : 0, has_next ? 1 : 0, s);
     tick(POP_K_STEP, 1);
     if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
     if (has_next) ctx->gathered_t = ctx->t + 1;
@@ -344,6 +344,15 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
   }
   if (ctx->fuse == 1) {
     if (!run(POP_K_TARGET_CRITIC, launch_target_critic)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    if (any_actor) {                                 // the rest of the step in one launch: the actor's own forward pass
+      tick(POP_K_STEP_TAIL, 0);                      // runs beside the critic weight gradients
+      e = launch_step(d, t, ctx->step_launches++, 0, 1, has_next ? 1 : 0, s);
+      tick(POP_K_STEP_TAIL, 1);
+      if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+      if (has_next) ctx->gathered_t = ctx->t + 1;
+      ctx->t++;
+      return POP_OK;
+    }
   } else if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic)) {
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
   }

@@ -7,9 +7,11 @@
 // which then also defines the g_pop_trace array the marks go to.
 #ifdef POP_TRACE
 extern __device__ unsigned long long g_pop_trace[64];
+extern __device__ int g_pop_trace_block;            // the block whose marks are recorded
 #define POP_MARK(i)                                                                 \
   do {                                                                              \
-    if ((blockIdx.x == 0 || blockIdx.x + 8 == gridDim.x) && threadIdx.x == 0) g_pop_trace[i] = wall_clock64(); \
+    if ((int)blockIdx.x == g_pop_trace_block && threadIdx.x == 0) g_pop_trace[i] = wall_clock64(); \
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (i) == 63) g_pop_trace[63] = wall_clock64();       \
   } while (0)
 #else
 #define POP_MARK(i)
@@ -56,7 +58,6 @@ struct PopDev {
   int mt;                      // row tiles per workgroup of the fused chain kernels (rows = 32 mt)
   int chunks;                  // B / (32 mt)
   int lean;                    // chain-kernel variant: 0 choose by launch size, 1 always lean, -1 always deep prefetch
-  int stagger_w;               // weight-gradient kernel: start offset between co-resident workgroups, 10 ns ticks
   NetLayout actor, critic;
   int agent_sz;                // actor.padded + 2 * critic.padded
   // parameter state, each [P][agent_sz] = [actor | critic1 | critic2]
@@ -82,7 +83,8 @@ struct PopDev {
   float* losses;               // [P][4]: critic 1, critic 2, actor, unused
   // cross-workgroup signalling inside a launch
   uint64_t* y_tagged;          // [P][B]: (t + 1) << 32 | bits of y, for readers inside the launch that writes y
-  uint32_t* done_c;            // [2][2P] critic chunks finished per network, by step parity
+  int sync_half;               // which half of the counters below this launch counts in (set per launch)
+  uint32_t* done_c;            // [2][2P] critic chunks finished per network
   uint32_t* done_wc;           // [2][2P] critic weight-gradient roles finished per network
   uint32_t* done_a;            // [2][P]  actor chunks finished per agent
   uint32_t* fault;             // [1]: bit 0 = a wait for y ran out, bit 1 = a wait for a count
@@ -121,22 +123,6 @@ __device__ inline bool decode_block(int id, int units, int per_unit, int& unit, 
   return unit < units;
 }
 __host__ inline int xcd_grid(int units, int per_unit) { return units * per_unit; }
-
-// Workgroups of one launch all walk through the same phases (operand staging, matrix
-// product, streaming epilogue), and the ones dispatched together onto a CU do so in
-// lockstep: they fight over the matrix pipe, then over memory.  This delays, in the
-// first `resident` workgroups of a launch only, the wavefronts that did not get the
-// first wave slot of their SIMD by slot * ticks (10 ns each), so that co-resident
-// workgroups run out of phase from then on.  The wait is bounded by the constant-rate
-// clock; a wrong guess about slots costs time, never correctness.
-__device__ inline void stagger_start(int resident, int ticks) {
-  if (ticks <= 0 || (int)blockIdx.x >= resident) return;
-  const uint32_t slot = __builtin_amdgcn_s_getreg((3 << 11) | 4) & 15u;   // HW_ID bits 3:0 = wave slot within the SIMD
-  if (slot == 0) return;
-  const uint64_t t0 = wall_clock64();
-  const uint64_t wait = (uint64_t)min(slot, 3u) * (uint64_t)ticks;
-  while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(16);
-}
 
 __device__ inline const float* net_ptr(const PopDev& d, const float* base, int agent, int net) {
   const float* p = base + (size_t)agent * d.agent_sz;

@@ -101,7 +101,7 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
     regs[v].th = th[i]; regs[v].m = mo[i]; regs[v].v = ve[i];
     regs[v].tg = polyak ? tg[i] : 0.0f;
   }
-  if (WAIT) {                                        // x and z come from a chain of this launch
+  if (WAIT && wait_on) {                             // x and z come from a chain of this launch
     if (tid == 0) wait_count(d, wait_on, want);
     __syncthreads();
   }
@@ -148,11 +148,12 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
 }
 
 // All roles of the weight-gradient step of one network; `block` indexes (network, role).
-// WAIT: producers (the chain of this network) and consumers (the actor chain, for critic 1)
-// run in the same launch -- hold before the first read of chain output, count in at the end.
+// WAIT: consumers (the actor chain, for critic 1) and, if producer_in_launch, producers (the
+// chain of this network) run in the same launch -- hold before the first read of chain
+// output, count in at the end.
 template <bool WAIT>
 __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int actor_phase, int block, int roles,
-                                            float* xt_lds, Adam* sh_adam) {
+                                            float* xt_lds, Adam* sh_adam, bool producer_in_launch = true) {
   const int tid = threadIdx.x;
   int unit, role;
   if (!decode_block(block, actor_phase ? d.P : 2 * d.P, roles, unit, role)) return;
@@ -184,8 +185,9 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
   float* gr = net_ptr(d, d.grad, agent, net);
 
   // WAIT: the chain that produces this network's activations runs in the same launch
-  const uint32_t* wait_on = actor_phase ? d.done_a + parity_base(d, t, d.P) + agent
-                                        : d.done_c + parity_base(d, t, 2 * d.P) + unit;
+  const uint32_t* wait_on = !producer_in_launch ? nullptr
+                            : actor_phase       ? d.done_a + parity_base(d, t, d.P) + agent
+                                                : d.done_c + parity_base(d, t, 2 * d.P) + unit;
   const int n1 = (L.in + 31) / 32;
   if (role < 16 + 2 * n1) {
     const size_t o = (size_t)unit * d.B * kH;        // unit = agent (actor) or network (critics)
@@ -197,7 +199,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
                 (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
   } else {
     // small tensors from per-chunk partial sums; thread c owns hidden unit c
-    if (WAIT && tid == 0) wait_count(d, wait_on, (uint32_t)d.chunks);
+    if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)d.chunks);
     __syncthreads();
     const Adam adam = *sh_adam;
     const int c = tid;

@@ -258,11 +258,12 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
         if fuse == "2":
             assert cnt["step"] == 6 and sum(cnt.values()) == 7
         else:
-            assert cnt["step"] == 0 and cnt["wgrad_critic"] == 6 and cnt["actor"] == cnt["wgrad_actor"] == 6
+            assert cnt["step"] == 0
             if fuse == "1":
-                assert cnt["target_critic"] == 6 and cnt["target"] == cnt["critic"] == 0
+                assert cnt["target_critic"] == 6 and cnt["step_tail"] == 6 and sum(cnt.values()) == 13
             else:
-                assert cnt["target_critic"] == 0 and cnt["target"] == cnt["critic"] == 6
+                assert cnt["target"] == cnt["critic"] == cnt["wgrad_critic"] == cnt["actor"] == cnt["wgrad_actor"] == 6
+                assert sum(cnt.values()) == 31
         assert all(ms[k] > 0.0 for k in ms if cnt[k]) and gpu.step_count() == 13
         gpu.sync()
         states.append({(i, w): gpu.get_params(i, w) for i in range(11) for w in pp.PARAM_CODES if not w.startswith("g_")})

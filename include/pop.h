@@ -148,12 +148,13 @@ int pop_update(pop_ctx* ctx, int32_t n_steps);
  * results on per agent / per network inside the launch.  The environment
  * variable POP_FUSE, read at pop_create, selects the launch structure:
  *   2 one launch per step (default for populations of more than about 40 agents);
- *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC); on steps
- *     with an actor update the rest of the step in a second launch
- *     (POP_K_STEP_TAIL), else POP_K_WGRAD_CRITIC (default for smaller
+ *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest
+ *     one launch per part (default for smaller and for very large
  *     populations);
+ *   3 as 1, but on steps with an actor update the rest of the step is one
+ *     launch (POP_K_STEP_TAIL);
  *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR).
- * The arithmetic, and so every result, is bit-identical in all three. */
+ * The arithmetic, and so every result, is bit-identical in all of them. */
 enum {
   POP_K_GATHER = 0,        /* replay index draw + row gather (first step of a call only) */
   POP_K_TARGET = 1,        /* target actor, smoothing, twin target critics, y */

@@ -28,7 +28,7 @@
 // k_step.hip runs all of them, with the weight-gradient tiles, inside one launch per step.
 #pragma once
 #include "launch.h"
-#include "mfma_tiles.h"
+#include "mfma_tiles16.h"
 #include "rng.h"
 
 namespace pop {
@@ -37,13 +37,14 @@ static_assert(kMaxAct == 8, "the action-gradient loops read dz3 rows as two 16-b
 
 namespace {
 
-// LDS map (floats): input tile [R][xld] | activation tile [R][kLda] | 3 x [R][8] scratch | vectors
-template <int MT>
-struct Lds {
-  static constexpr int R = 32 * MT;
+// LDS map (floats): input tile [R][xld] | activation tile [R][kLda] | 3 x [R][8] scratch | vectors.
+// KPAD: the first-layer product reads the input tile in blocks of KPAD columns.
+template <int R_, int KPAD>
+struct LdsMap {
+  static constexpr int R = R_;
   int xld, buf, s0, s1, s2, vec;
-  __host__ __device__ Lds(int fan_in) {
-    xld = ((fan_in + 7) & ~7) + 4;         // 4 * odd words: conflict-free 16-byte row reads
+  __host__ __device__ LdsMap(int fan_in) {
+    xld = ((fan_in + KPAD - 1) / KPAD) * KPAD + 4;   // 4 * odd words: conflict-free 16-byte row reads
     buf = R * xld;
     s0 = buf + R * kLda;
     s1 = s0 + R * kMaxAct;
@@ -52,6 +53,8 @@ struct Lds {
   }
   __host__ size_t bytes(int vec_floats) const { return (size_t)(vec + vec_floats) * sizeof(float); }
 };
+template <int MT>
+using Lds = LdsMap<32 * MT, 8>;
 
 // what a two-hidden-layer network needs from memory before its products can start
 template <int MT>
@@ -151,6 +154,138 @@ __device__ inline void input_grad_to_global(const float* Zl, const float* W, Wei
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Tile geometries of a chain: what the chains below need from a geometry G is
+//   G::R, G::kPad, G::Pre (prefetch record with load()), G::WtBlock + G::load_wt (block 0 of a
+//   transposed weight operand), first_layer, hidden_layer, input_grad_to_global,
+//   input_grad_to_lds, thin (thin products on the vector ALU).
+template <int MT>
+struct Rows32 {                                      // 32 MT rows on v_mfma_f32_32x32x2_f32 (mfma_tiles.h)
+  static constexpr int R = 32 * MT, kPad = 8;
+  using Pre = LayerPre<MT>;
+  using WtBlock = WeightBlock<MT, true>;
+  __device__ static inline void load_wt(WtBlock& wt, const float* W, int wave, int lane) { wt.load(W, 0, wave, lane); }
+  template <bool THROUGH>
+  __device__ static inline uint64_t first_layer(const float* Xs, int xld, const float* net, const NetLayout& L,
+                                                const Pre& pre, float* Yl, float* Yg, int wave, int lane) {
+    return pop::first_layer<MT, THROUGH>(Xs, xld, net, L, pre, Yl, Yg, wave, lane);
+  }
+  template <bool DEEP, bool THROUGH, class Tail>
+  __device__ static inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, Pre& pre, float* Yg,
+                                                 int wave, int lane, Tail tail) {
+    return pop::hidden_layer<MT, DEEP, THROUGH>(buf, net, L, pre, Yg, wave, lane, tail);
+  }
+  template <bool DEEP, bool THROUGH>
+  __device__ static inline void input_grad_to_global(const float* Zl, const float* W, WtBlock& w0, uint64_t mask,
+                                                     float* dXg, float* colsum_out, int wave, int lane) {
+    pop::input_grad_to_global<MT, DEEP, THROUGH>(Zl, W, w0, mask, dXg, colsum_out, wave, lane);
+  }
+  // buf <- (buf W^T) * mask in place; tail() as in gemm256
+  template <bool DEEP, class Tail>
+  __device__ static inline void input_grad_to_lds(float* buf, const float* W, WtBlock& wt, uint64_t mask, int wave,
+                                                  int lane, Tail tail) {
+    Acc<MT> acc;
+    acc.zero();
+    if (DEEP) {
+      gemm256<MT, true>(buf, kLda, W, wt, wave, lane, acc, tail);
+    } else {
+      wt.load(W, 0, wave, lane);
+      gemm256_lean<MT, true>(buf, kLda, W, wt, wave, lane, acc);
+      tail();
+    }
+    __syncthreads();                                 // every wavefront is done reading the operand
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          buf[(32 * mt + acc_row(v, lane)) * kLda + 64 * wave + 32 * nt + (lane & 31)] =
+              mask_bit(mask, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;
+  }
+  __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid) {
+    thin_dot<R>(Xl, V, J, outl, tid);
+  }
+};
+
+struct Rows16 {                                      // 16 rows on v_mfma_f32_16x16x4_f32 (mfma_tiles16.h)
+  static constexpr int R = 16, kPad = 16;
+  struct Pre {
+    SmallW16 w1;
+    WeightBlock16<false> w2;
+    f32x4 b1, b2;                                    // biases of this lane's 4 columns
+    __device__ inline void load(const float* __restrict__ net, const NetLayout& L, int wave, int lane) {
+      w1.load(net + L.w1, L.in, wave, lane);
+      w2.load(net + L.w2, 0, wave, lane);
+      b1 = *reinterpret_cast<const f32x4*>(net + L.b1 + 64 * wave + 4 * (lane & 15));
+      b2 = *reinterpret_cast<const f32x4*>(net + L.b2 + 64 * wave + 4 * (lane & 15));
+    }
+  };
+  using WtBlock = WeightBlock16<true>;
+  __device__ static inline void load_wt(WtBlock& wt, const float* W, int wave, int lane) { wt.load(W, 0, wave, lane); }
+  template <bool THROUGH>
+  __device__ static inline uint64_t first_layer(const float* Xs, int xld, const float* net, const NetLayout& L,
+                                                const Pre& pre, float* Yl, float* Yg, int wave, int lane) {
+    Acc16 acc;
+    acc.zero();
+    gemm_xw_small16(Xs, xld, L.in, net + L.w1, pre.w1, wave, lane, acc);
+    return relu_store16<THROUGH>(acc, pre.b1, Yl, Yg, wave, lane);
+  }
+  template <bool DEEP, bool THROUGH, class Tail>
+  __device__ static inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, Pre& pre, float* Yg,
+                                                 int wave, int lane, Tail tail) {
+    Acc16 acc;
+    acc.zero();
+    const f32x4 bb = pre.b2;
+    gemm256_16<false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
+    __syncthreads();                                 // every wavefront has read the input tile
+    return relu_store16<THROUGH>(acc, bb, buf, Yg, wave, lane);
+  }
+  template <bool DEEP, bool THROUGH>
+  __device__ static inline void input_grad_to_global(const float* Zl, const float* W, WtBlock& w0, uint64_t mask,
+                                                     float* __restrict__ dXg, float* __restrict__ colsum_out, int wave,
+                                                     int lane) {
+    Acc16 acc;
+    acc.zero();
+    gemm256_16<true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
+    const int c = lane & 15, kq = lane >> 4;
+    float cs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        const float z = mask_bit16(mask, nt, v) ? acc.t[nt][v] : 0.0f;
+        put<THROUGH>(dXg + (4 * kq + v) * kH + 64 * wave + 4 * c + nt, z);
+        cs[nt] += z;
+      }
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      float tot = cs[nt] + __shfl_xor(cs[nt], 16);
+      tot += __shfl_xor(tot, 32);
+      if (lane < 16) put<THROUGH>(colsum_out + 64 * wave + 4 * c + nt, tot);
+    }
+  }
+  template <bool DEEP, class Tail>
+  __device__ static inline void input_grad_to_lds(float* buf, const float* W, WtBlock& wt, uint64_t mask, int wave,
+                                                  int lane, Tail tail) {
+    Acc16 acc;
+    acc.zero();
+    gemm256_16<true>(buf, kLda, W, wt, wave, lane, acc, tail);
+    __syncthreads();
+    const int c = lane & 15, kq = lane >> 4;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      f32x4 o;
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) o[nt] = mask_bit16(mask, nt, v) ? acc.t[nt][v] : 0.0f;
+      *reinterpret_cast<f32x4*>(&buf[(4 * kq + v) * kLda + 64 * wave + 4 * c]) = o;
+    }
+  }
+  __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid) {
+    thin_dot16(Xl, V, J, outl, tid);
+  }
+};
+
 }  // namespace
 
 // Longest time a workgroup waits for another one of the same launch, in 10 ns ticks of the
@@ -218,10 +353,10 @@ __device__ inline void wait_count(const PopDev& d, const uint32_t* count, uint32
 // Target chain.  One workgroup per (agent, chunk).
 //   a~ = clip(pi'(s') + clip(sigma eps, -c, c), -1, 1), eps = normal e = b A + j of stream 1
 //   y  = r + gamma (1 - d) min(Q1'(s', a~), Q2'(s', a~))
-template <int MT, bool DEEP>
+template <class G, bool DEEP>
 __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int block, float* lds) {
-  constexpr int R = 32 * MT;
-  const Lds<MT> L(d.D);
+  constexpr int R = G::R;
+  const LdsMap<G::R, G::kPad> L(d.D);
   float* Xs = lds;
   float* buf = lds + L.buf;
   float* head = lds + L.s0;
@@ -232,13 +367,13 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int bl
   float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int agent, chunk;
-  if (!decode_block(block, d.P, d.chunks, agent, chunk)) return;
+  if (!decode_block(block, d.P, d.B / R, agent, chunk)) return;
   const int r0 = chunk * R;
   const float* ta = net_ptr(d, d.target, agent, 0);
   const float* tc0 = net_ptr(d, d.target, agent, 1);
   const float* tc1 = net_ptr(d, d.target, agent, 2);
   POP_MARK(29);
-  LayerPre<MT> pre;
+  typename G::Pre pre;
   pre.load(ta, d.actor, wave, lane);
   const HpDev hp = d.hp[agent];
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
@@ -252,13 +387,13 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int bl
   __syncthreads();
   POP_MARK(31);
 
-  first_layer<MT>(Xs, L.xld, ta, d.actor, pre, buf, nullptr, wave, lane);
+  G::template first_layer<false>(Xs, L.xld, ta, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
   POP_MARK(32);
-  hidden_layer<MT, DEEP>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
+  G::template hidden_layer<DEEP, false>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
   POP_MARK(33);
-  thin_dot<R>(buf, v_aw3, d.A, head, tid);
+  G::thin(buf, v_aw3, d.A, head, tid);
   __syncthreads();
   POP_MARK(34);
   for (int e = tid; e < R * d.A; e += kThreads) {
@@ -281,14 +416,14 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int bl
   for (int k = 0; k < 2; ++k) {
     const float* tc = k == 0 ? tc0 : tc1;
     if (!DEEP) pre.load(tc, d.critic, wave, lane);    // lean variant: fetch right before use
-    first_layer<MT>(Xs, L.xld, tc, d.critic, pre, buf, nullptr, wave, lane);
+    G::template first_layer<false>(Xs, L.xld, tc, d.critic, pre, buf, nullptr, wave, lane);
     __syncthreads();
     POP_MARK(36 + 4 * k);
-    hidden_layer<MT, DEEP>(buf, tc, d.critic, pre, nullptr, wave, lane,
+    G::template hidden_layer<DEEP, false>(buf, tc, d.critic, pre, nullptr, wave, lane,
                            [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
     __syncthreads();
     POP_MARK(37 + 4 * k);
-    thin_dot<R>(buf, v_cw3 + k * kH, 1, head, tid);
+    G::thin(buf, v_cw3 + k * kH, 1, head, tid);
     __syncthreads();
     POP_MARK(38 + 4 * k);
     if (tid < R) {
@@ -317,10 +452,10 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int bl
 // WAIT: the targets come from target workgroups of the same launch; the lanes that need
 // them poll for their rows right before the loss.  SIGNAL: count this chunk as finished
 // for the weight-gradient workgroups of the same launch.
-template <int MT, bool DEEP, bool WAIT, bool SIGNAL>
+template <class G, bool DEEP, bool WAIT, bool SIGNAL>
 __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int block, float* lds) {
-  constexpr int R = 32 * MT;
-  const Lds<MT> L(d.D);
+  constexpr int R = G::R;
+  const LdsMap<G::R, G::kPad> L(d.D);
   float* Xs = lds;
   float* buf = lds + L.buf;
   float* head = lds + L.s0;
@@ -328,14 +463,14 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int bl
   float* v_w3 = lds + L.vec;                         // [256]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int net, chunk;
-  if (!decode_block(block, 2 * d.P, d.chunks, net, chunk)) return;
+  if (!decode_block(block, 2 * d.P, d.B / R, net, chunk)) return;
   const int agent = net >> 1, k = net & 1, r0 = chunk * R;
   const float* cn = net_ptr(d, d.theta, agent, 1 + k);
-  LayerPre<MT> pre;
+  typename G::Pre pre;
   pre.load(cn, d.critic, wave, lane);
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)net * d.B + r0) * kH;
-  float* part = d.cpart + ((size_t)net * d.chunks + chunk) * kCPart;
+  float* part = d.cpart + ((size_t)net * (d.B / R) + chunk) * kCPart;
   stage_vector(v_w3, cn + d.critic.w3, kH, tid);
   load_input<R>(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
   float yv = 0.0f, b3 = 0.0f;
@@ -347,14 +482,14 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int bl
   __syncthreads();
   POP_MARK(1);
 
-  const uint64_t mask1 = first_layer<MT, SIGNAL>(Xs, L.xld, cn, d.critic, pre, buf, d.cH1 + act_off, wave, lane);
+  const uint64_t mask1 = G::template first_layer<SIGNAL>(Xs, L.xld, cn, d.critic, pre, buf, d.cH1 + act_off, wave, lane);
   __syncthreads();
   POP_MARK(2);
-  WeightBlock<MT, true> wt;                          // block 0 of W2 for the input-gradient product
-  hidden_layer<MT, DEEP>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
+  typename G::WtBlock wt;                          // block 0 of W2 for the input-gradient product
+  G::template hidden_layer<DEEP, false>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { G::load_wt(wt, cn + d.critic.w2, wave, lane); });
   __syncthreads();
   POP_MARK(3);
-  thin_dot<R>(buf, v_w3, 1, head, tid);
+  G::thin(buf, v_w3, 1, head, tid);
   if (WAIT && tid < R) yv = await_y(d, (size_t)agent * d.B + r0 + tid, t);   // same lane uses it below
   __syncthreads();
   POP_MARK(4);
@@ -395,7 +530,7 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int bl
   POP_MARK(5);
   __syncthreads();
   POP_MARK(6);
-  input_grad_to_global<MT, DEEP, SIGNAL>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
+  G::template input_grad_to_global<DEEP, SIGNAL>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
   POP_MARK(7);
   if (SIGNAL) signal_count(d.done_c + parity_base(d, t, 2 * d.P) + net, tid);
 }
@@ -414,10 +549,10 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int bl
 // pass goes ahead, everything that reads critic 1 waits until all of its weight-gradient
 // workgroups are done.  SIGNAL: count this chunk as finished for the actor's weight-gradient
 // workgroups.
-template <int MT, bool DEEP, bool WAIT>
+template <class G, bool DEEP, bool WAIT>
 __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int block, float* lds, int critic_roles) {
-  constexpr int R = 32 * MT;
-  const Lds<MT> L(d.D);
+  constexpr int R = G::R;
+  const LdsMap<G::R, G::kPad> L(d.D);
   float* Xs = lds;
   float* buf = lds + L.buf;
   float* head = lds + L.s0;
@@ -430,18 +565,18 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
   float* v_cwa = v_cw3 + kH;                         // [A][256] critic first-layer rows of the action inputs
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   int agent, chunk;
-  if (!decode_block(block, d.P, d.chunks, agent, chunk)) return;
+  if (!decode_block(block, d.P, d.B / R, agent, chunk)) return;
   const int r0 = chunk * R;
   const HpDev hp = d.hp[agent];
   if (t % (uint32_t)hp.policy_delay != 0u) return;
   const float* an = net_ptr(d, d.theta, agent, 0);
   const float* cn = net_ptr(d, d.theta, agent, 1);
   POP_MARK(8);
-  LayerPre<MT> pre;
+  typename G::Pre pre;
   pre.load(an, d.actor, wave, lane);
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)agent * d.B + r0) * kH;
-  float* part = d.apart + ((size_t)agent * d.chunks + chunk) * kAPart;
+  float* part = d.apart + ((size_t)agent * (d.B / R) + chunk) * kAPart;
   stage_head(v_aw3, an + d.actor.w3, A, tid);
   stage_vector(v_ab3, an + d.actor.b3, A, tid);
   float cb3 = 0.0f;
@@ -454,12 +589,12 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
   load_input<R>(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
   __syncthreads();
 
-  const uint64_t mask_a1 = first_layer<MT, WAIT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
+  const uint64_t mask_a1 = G::template first_layer<WAIT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
   __syncthreads();
-  hidden_layer<MT, DEEP>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
+  G::template hidden_layer<DEEP, false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
                          [&]() { if (!WAIT) pre.load(cn, d.critic, wave, lane); });
   __syncthreads();
-  thin_dot<R>(buf, v_aw3, A, head, tid);
+  G::thin(buf, v_aw3, A, head, tid);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
     const int r = e / A, j = e - r * A;
@@ -481,13 +616,13 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
     pre.load(cn, d.critic, wave, lane);
   }
   POP_MARK(10);
-  const uint64_t mask_c1 = first_layer<MT>(Xs, L.xld, cn, d.critic, pre, buf, nullptr, wave, lane);
+  const uint64_t mask_c1 = G::template first_layer<false>(Xs, L.xld, cn, d.critic, pre, buf, nullptr, wave, lane);
   __syncthreads();
-  WeightBlock<MT, true> wt;
-  hidden_layer<MT, DEEP>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { wt.load(cn + d.critic.w2, 0, wave, lane); });
+  typename G::WtBlock wt;
+  G::template hidden_layer<DEEP, false>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { G::load_wt(wt, cn + d.critic.w2, wave, lane); });
   __syncthreads();
   POP_MARK(11);
-  thin_dot<R>(buf, v_cw3, 1, head, tid);     // q, for the loss value only
+  G::thin(buf, v_cw3, 1, head, tid);     // q, for the loss value only
   __syncthreads();
   if (tid < 64) {
     const float q = tid < R ? head[tid * kMaxAct] + cb3 : 0.0f;
@@ -509,35 +644,17 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
   __syncthreads();
   f32x4 h2r[R / 4];                                  // this thread's share of the parked h2 tile
   {
-    Acc<MT> acc;
-    acc.zero();
     const float* h2g = d.aH2 + act_off;
-    auto fetch_h2 = [&]() {
+    G::template input_grad_to_lds<DEEP>(buf, cn + d.critic.w2, wt, mask_c1, wave, lane, [&]() {
 #pragma unroll
       for (int i = 0; i < R / 4; ++i)
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
-    };
-    if (DEEP) {
-      gemm256<MT, true>(buf, kLda, cn + d.critic.w2, wt, wave, lane, acc, fetch_h2);
-    } else {
-      wt.load(cn + d.critic.w2, 0, wave, lane);
-      gemm256_lean<MT, true>(buf, kLda, cn + d.critic.w2, wt, wave, lane, acc);
-      fetch_h2();
-    }
-    __syncthreads();                                 // every wavefront is done reading dz2 of the critic
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          buf[(32 * mt + acc_row(v, lane)) * kLda + 64 * wave + 32 * nt + (lane & 31)] =
-              mask_bit(mask_c1, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;      // dz1 of the critic
+    });                                              // buf = dz1 of the critic
   }
   __syncthreads();
   POP_MARK(12);
-  thin_dot<R>(buf, v_cwa, A, head, tid);      // da
-  if (DEEP) wt.load(an + d.actor.w2, 0, wave, lane); // block 0 of the actor's input-gradient product
+  G::thin(buf, v_cwa, A, head, tid);      // da
+  if (DEEP) G::load_wt(wt, an + d.actor.w2, wave, lane); // block 0 of the actor's input-gradient product
   __syncthreads();
   for (int e = tid; e < R * kMaxAct; e += kThreads) {
     const int j = e % kMaxAct;
@@ -592,7 +709,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
   }
   __syncthreads();
   POP_MARK(13);
-  input_grad_to_global<MT, DEEP, WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  G::template input_grad_to_global<DEEP, WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
   POP_MARK(14);
   if (WAIT) signal_count(d.done_a + parity_base(d, t, d.P) + agent, tid);
 }

@@ -6,16 +6,16 @@
 
 namespace pop {
 
-template <int MT, bool DEEP>
-__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_target(PopDev d, uint32_t t) {
+template <class G>
+__global__ __launch_bounds__(kThreads, 1) void k_target(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
-  target_chain<MT, DEEP>(d, t, blockIdx.x, lds);
+  target_chain<G, true>(d, t, blockIdx.x, lds);
 }
 
-template <int MT, bool DEEP>
-__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uint32_t t) {
+template <class G>
+__global__ __launch_bounds__(kThreads, 1) void k_critic(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
-  critic_chain<MT, DEEP, false, false>(d, t, blockIdx.x, lds);
+  critic_chain<G, true, false, false>(d, t, blockIdx.x, lds);
 }
 
 // Target and critic chains of one step in a single launch.  The critic's forward pass does
@@ -23,17 +23,18 @@ __global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_critic(PopDev d, uin
 // only wait, before the loss, for the targets of their own rows.  Target workgroups have the
 // lower block indices: workgroups are dispatched in index order, so whatever a critic
 // workgroup waits for has already been dispatched and the wait always ends.
-template <int MT>
+// GT, GC: tile geometries of the two chains.
+template <class GT, class GC>
 __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
-  if ((int)blockIdx.x < target_blocks) target_chain<MT, true>(d, t, blockIdx.x, lds);
-  else critic_chain<MT, true, true, false>(d, t, blockIdx.x - target_blocks, lds);
+  if ((int)blockIdx.x < target_blocks) target_chain<GT, true>(d, t, blockIdx.x, lds);
+  else critic_chain<GC, true, true, false>(d, t, blockIdx.x - target_blocks, lds);
 }
 
-template <int MT, bool DEEP>
-__global__ __launch_bounds__(kThreads, DEEP ? 1 : 3) void k_actor(PopDev d, uint32_t t) {
+template <class G>
+__global__ __launch_bounds__(kThreads, 1) void k_actor(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
-  actor_chain<MT, DEEP, false>(d, t, blockIdx.x, lds, 0);
+  actor_chain<G, true, false>(d, t, blockIdx.x, lds, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -75,56 +76,56 @@ hipError_t setup_kernels() {
   const int most = 160 * 1024;                        // whole LDS of a CU; the launches ask for what they need
 #define POP_SET_LDS(...)                                                                                   \
   if ((e = hipFuncSetAttribute((const void*)__VA_ARGS__, hipFuncAttributeMaxDynamicSharedMemorySize, most)) != hipSuccess) return e
-  POP_SET_LDS(k_target<1, true>);
-  POP_SET_LDS(k_target<1, false>);
-  POP_SET_LDS(k_target<2, true>);
-  POP_SET_LDS(k_critic<1, true>);
-  POP_SET_LDS(k_critic<1, false>);
-  POP_SET_LDS(k_critic<2, true>);
-  POP_SET_LDS(k_actor<1, true>);
-  POP_SET_LDS(k_actor<1, false>);
-  POP_SET_LDS(k_actor<2, true>);
-  POP_SET_LDS(k_target_critic<1>);
-  POP_SET_LDS(k_target_critic<2>);
+  POP_SET_LDS(k_target<Rows16>);
+  POP_SET_LDS(k_target<Rows32<1>>);
+  POP_SET_LDS(k_target<Rows32<2>>);
+  POP_SET_LDS(k_critic<Rows32<1>>);
+  POP_SET_LDS(k_critic<Rows32<2>>);
+  POP_SET_LDS(k_actor<Rows16>);
+  POP_SET_LDS(k_actor<Rows32<1>>);
+  POP_SET_LDS(k_actor<Rows32<2>>);
+  POP_SET_LDS(k_target_critic<Rows16, Rows32<2>>);
+  POP_SET_LDS(k_target_critic<Rows32<1>, Rows32<1>>);
+  POP_SET_LDS(k_target_critic<Rows32<2>, Rows32<2>>);
   POP_SET_LDS(k_act);
 #undef POP_SET_LDS
   return hipSuccess;
 }
 
-// The deep-prefetch variants win whenever a launch leaves a CU one or two workgroups
-// (the latency of a single chain is what counts).  The lean ones fit three workgroups
-// per CU; measured at P = 80 they pay off for the longest chain (actor, -9 %) and
-// marginally for the critic chain, and lose for the target chain, which stays deep.
-namespace {
-bool use_lean(const PopDev& d, int workgroups) { return d.mt == 1 && d.lean >= 0 && (d.lean > 0 || workgroups > 2 * 256); }
-}  // namespace
-
+// Rows per workgroup come in three classes (pop_dev.h): (target, critic, actor) = (16, 64, 16)
+// for small populations, (32, 32, 32), and (64, 64, 64) for large ones.
 hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s) {
-  const dim3 grid(xcd_grid(d.P, d.chunks));
-  if (d.mt == 2) k_target<2, true><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_target(d)), s>>>(d, t);
-  else if (d.lean > 0) k_target<1, false><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
-  else k_target<1, true><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
+  const dim3 grid(xcd_grid(d.P, d.B / d.rows_t)), block(kThreads);
+  if (d.rows_t == 16) k_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_target(d)), s>>>(d, t);
+  else if (d.rows_t == 32) k_target<Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
+  else k_target<Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec_target(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_critic(const PopDev& d, uint32_t t, hipStream_t s) {
-  const dim3 grid(xcd_grid(2 * d.P, d.chunks));
-  if (d.mt == 2) k_critic<2, true><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_critic(d)), s>>>(d, t);
-  else if (use_lean(d, 2 * d.P * d.chunks)) k_critic<1, false><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
-  else k_critic<1, true><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
+  const dim3 grid(xcd_grid(2 * d.P, d.B / d.rows_c)), block(kThreads);
+  if (d.rows_c == 32) k_critic<Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
+  else k_critic<Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec_critic(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
-  const int nt = xcd_grid(d.P, d.chunks), nc = xcd_grid(2 * d.P, d.chunks);
+  const int nt = xcd_grid(d.P, d.B / d.rows_t), nc = xcd_grid(2 * d.P, d.B / d.rows_c);
   const int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
-  if (d.mt == 2) k_target_critic<2><<<dim3(nt + nc), dim3(kThreads), Lds<2>(d.D).bytes(vec), s>>>(d, t, nt);
-  else k_target_critic<1><<<dim3(nt + nc), dim3(kThreads), Lds<1>(d.D).bytes(vec), s>>>(d, t, nt);
+  const dim3 grid(nt + nc), block(kThreads);
+  if (d.rows_t == 16) {
+    const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = Lds<2>(d.D).bytes(vec);
+    k_target_critic<Rows16, Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
+  } else if (d.rows_t == 32) {
+    k_target_critic<Rows32<1>, Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec), s>>>(d, t, nt);
+  } else {
+    k_target_critic<Rows32<2>, Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec), s>>>(d, t, nt);
+  }
   return hipGetLastError();
 }
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {
-  const dim3 grid(xcd_grid(d.P, d.chunks));
-  if (d.mt == 2) k_actor<2, true><<<grid, dim3(kThreads), Lds<2>(d.D).bytes(vec_actor(d)), s>>>(d, t);
-  else if (use_lean(d, d.P * d.chunks)) k_actor<1, false><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
-  else k_actor<1, true><<<grid, dim3(kThreads), Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  const dim3 grid(xcd_grid(d.P, d.B / d.rows_a)), block(kThreads);
+  if (d.rows_a == 16) k_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  else if (d.rows_a == 32) k_actor<Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  else k_actor<Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   return hipGetLastError();
 }
 hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, hipStream_t s) {

@@ -24,11 +24,13 @@ struct StepGrid {
   int roles_c, roles_a;            // weight-gradient roles per critic / actor network
 };
 
-template <int MT>
+// GT, GC, GA: tile geometries of the target, critic and actor chains.
+template <class GT, class GC, class GA>
 __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, StepGrid g) {
   extern __shared__ __attribute__((aligned(16))) float lds[];
   int b = blockIdx.x;
   POP_MARK(63);
+  POP_BLOCK_TIME(0);
   if (b == 0) {                                      // zero the counters the next step will count in
                                                      // (whichever part block 0 belongs to)
     const int other = d.sync_half ^ 1;
@@ -38,16 +40,16 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
       if (i < d.P) d.done_a[other * d.P + i] = 0u;
     }
   }
-  if (b < g.t) { target_chain<MT, true>(d, t, b, lds); return; }
+  if (b < g.t) { target_chain<GT, true>(d, t, b, lds); POP_BLOCK_TIME(1); return; }
   b -= g.t;
-  if (b < g.c) { critic_chain<MT, true, true, true>(d, t, b, lds); return; }
+  if (b < g.c) { critic_chain<GC, true, true, true>(d, t, b, lds); POP_BLOCK_TIME(1); return; }
   b -= g.c;
   Adam* sh_adam = reinterpret_cast<Adam*>(lds + 32 * kLda);
-  if (b < g.wc) { wgrad_roles<true>(d, t, 0, b, g.roles_c, lds, sh_adam, g.c != 0); return; }
+  if (b < g.wc) { wgrad_roles<true>(d, t, 0, b, g.roles_c, lds, sh_adam, g.c != 0); POP_BLOCK_TIME(1); return; }
   b -= g.wc;
-  if (b < g.a) { actor_chain<MT, true, true>(d, t, b, lds, g.roles_c); return; }
+  if (b < g.a) { actor_chain<GA, true, true>(d, t, b, lds, g.roles_c); POP_BLOCK_TIME(1); return; }
   b -= g.a;
-  if (b < g.wa) { wgrad_roles<true>(d, t, 1, b, g.roles_a, lds, sh_adam); return; }
+  if (b < g.wa) { wgrad_roles<true>(d, t, 1, b, g.roles_a, lds, sh_adam); POP_BLOCK_TIME(1); return; }
   b -= g.wa;
   if (b < g.g) {
     const int per = gather_blocks_per_agent(d);
@@ -55,10 +57,15 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
   }
 }
 
+#define POP_STEP_SMALL k_step<Rows16, Rows32<2>, Rows16>
+#define POP_STEP_MID k_step<Rows32<1>, Rows32<1>, Rows32<1>>
+#define POP_STEP_LARGE k_step<Rows32<2>, Rows32<2>, Rows32<2>>
+
 hipError_t setup_step_kernel() {
-  hipError_t e = hipFuncSetAttribute((const void*)k_step<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute((const void*)k_step<2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  hipError_t e;
+  if ((e = hipFuncSetAttribute((const void*)POP_STEP_SMALL, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute((const void*)POP_STEP_MID, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)) != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)POP_STEP_LARGE, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 
 hipError_t launch_step(const PopDev& dev, uint32_t t, uint32_t launch_seq, int with_chains, int with_actor,
@@ -68,22 +75,28 @@ hipError_t launch_step(const PopDev& dev, uint32_t t, uint32_t launch_seq, int w
   StepGrid g;
   g.roles_c = wgrad_role_count(d, 0);
   g.roles_a = wgrad_role_count(d, 1);
-  g.t = with_chains ? xcd_grid(d.P, d.chunks) : 0;       // else: target and critic chains ran in an earlier launch
-  g.c = with_chains ? xcd_grid(2 * d.P, d.chunks) : 0;
+  g.t = with_chains ? xcd_grid(d.P, d.B / d.rows_t) : 0;       // else: target and critic chains ran in an earlier launch
+  g.c = with_chains ? xcd_grid(2 * d.P, d.B / d.rows_c) : 0;
   g.wc = xcd_grid(2 * d.P, g.roles_c);
-  g.a = with_actor ? xcd_grid(d.P, d.chunks) : 0;
+  g.a = with_actor ? xcd_grid(d.P, d.B / d.rows_a) : 0;
   g.wa = with_actor ? xcd_grid(d.P, g.roles_a) : 0;
   g.g = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
   int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
   if (vec_actor(d) > vec) vec = vec_actor(d);
   const size_t tiles = (size_t)(32 * kLda) * sizeof(float) + sizeof(Adam);
-  const dim3 grid(g.t + g.c + g.wc + g.a + g.wa + g.g);
-  if (d.mt == 2) {
-    size_t bytes = Lds<2>(d.D).bytes(vec);
-    k_step<2><<<grid, dim3(kThreads), bytes > tiles ? bytes : tiles, s>>>(d, t, g);
+  const dim3 grid(g.t + g.c + g.wc + g.a + g.wa + g.g), block(kThreads);
+  size_t bytes = tiles;
+  auto need = [&](size_t b) { if (b > bytes) bytes = b; };
+  if (d.rows_a == 16) {
+    need(LdsMap<16, 16>(d.D).bytes(vec));
+    need(Lds<2>(d.D).bytes(vec));
+    POP_STEP_SMALL<<<grid, block, bytes, s>>>(d, t, g);
+  } else if (d.rows_a == 32) {
+    need(Lds<1>(d.D).bytes(vec));
+    POP_STEP_MID<<<grid, block, bytes, s>>>(d, t, g);
   } else {
-    size_t bytes = Lds<1>(d.D).bytes(vec);
-    k_step<1><<<grid, dim3(kThreads), bytes > tiles ? bytes : tiles, s>>>(d, t, g);
+    need(Lds<2>(d.D).bytes(vec));
+    POP_STEP_LARGE<<<grid, block, bytes, s>>>(d, t, g);
   }
   return hipGetLastError();
 }

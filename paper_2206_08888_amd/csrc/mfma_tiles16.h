@@ -1,0 +1,218 @@
+// 16-row flavour of the MFMA building blocks, for small populations.
+//
+// With few agents a launch has fewer workgroups than the chip has CUs, and a layer chain
+// is as slow as the matrix pipe of ONE CU lets it be.  Halving the rows per workgroup
+// halves the MFMA time of every product and uses twice as many CUs (weights are re-read
+// from L2 twice as often, which is free at these sizes).  32x32 tiles would waste half of
+// every instruction on 16 rows, so these products run on v_mfma_f32_16x16x4_f32: one
+// instruction multiplies a 16x4 slice of A by a 4x16 slice of B into a 16x16 fp32 tile
+// held as 4 registers per lane (32 cycles).
+//
+// Operand layout of that instruction on a 64-lane wavefront (checked against a CPU product):
+//   A: lane l supplies A[row = l & 15][k = l >> 4]
+//   B: lane l supplies B[k = l >> 4][col = l & 15]
+//   D: register v of lane l is D[row = 4 (l >> 4) + v][col = l & 15]
+//
+// A workgroup is 4 wavefronts; for a [16 x 256] output each wavefront owns the 64 columns
+// [64 wave, 64 wave + 64) as 4 tiles, INTERLEAVED: tile nt holds the columns
+// 64 wave + 4 c + nt (c = l & 15).  A lane's 4 tiles then sit on 4 consecutive columns, so
+//   * the right operand is fetched with 16-byte loads (forward: 4 consecutive columns of
+//     one weight row = the 4 tiles' values for one k; backward: 4 consecutive k of one
+//     weight row per tile),
+//   * results go to LDS / global as 16-byte vectors.
+// As in the 32-row flavour the contraction index is visited in the order the loads like:
+// within a 16-deep block, MFMA j of a lane group kq = l >> 4 uses k = 16 i + 4 kq + j.
+#pragma once
+#include "mfma_tiles.h"
+
+namespace pop {
+
+struct Acc16 {
+  f32x4 t[4];                                        // [tile nt][v]
+  __device__ inline void zero() {
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) t[nt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  }
+};
+
+__device__ inline f32x4 mfma16(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+
+// the weights one lane needs for a 16-deep block
+//   forward  (TRANSPOSED = false): w[j][nt] = W[16 i + 4 kq + j][64 wave + 4 c + nt]
+//   backward (TRANSPOSED = true):  w[nt][j] = W[64 wave + 4 c + nt][16 i + 4 kq + j]
+template <bool TRANSPOSED>
+struct WeightBlock16 {
+  f32x4 w[4];
+  __device__ inline void load(const float* __restrict__ W, int i, int wave, int lane) {
+    const int c = lane & 15, kq = lane >> 4;
+    if (TRANSPOSED) {
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+        w[nt] = *reinterpret_cast<const f32x4*>(W + (64 * wave + 4 * c + nt) * kH + 16 * i + 4 * kq);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        w[j] = *reinterpret_cast<const f32x4*>(W + (16 * i + 4 * kq + j) * kH + 64 * wave + 4 * c);
+    }
+  }
+};
+
+struct LdsBlock16 {                                  // the LDS operand of one block: 4 consecutive k of this lane's row
+  f32x4 a;
+  __device__ inline void load(const float* __restrict__ Xl, int ldx, int k0, int lane) {
+    a = *reinterpret_cast<const f32x4*>(&Xl[(lane & 15) * ldx + k0 + 4 * (lane >> 4)]);
+  }
+};
+
+template <bool TRANSPOSED>
+__device__ inline void mfma_block16(const LdsBlock16& x, const WeightBlock16<TRANSPOSED>& b, Acc16& acc) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+      acc.t[nt] = mfma16(x.a[j], TRANSPOSED ? b.w[nt][j] : b.w[j][nt], acc.t[nt]);
+}
+
+// 256-deep product of a 16-row LDS operand with a global weight operand, 16 blocks of 16,
+// fully unrolled; weight registers rotate through four buffers (block i+3 is requested
+// before the MFMAs of block i, about 1500 cycles of matrix work ahead), the LDS operand one
+// block ahead.  Block 0 comes from the caller; `tail()` runs once the last weight block has
+// been requested, so the caller can start the next layer's loads under the last blocks.
+template <bool TRANSPOSED, class Tail>
+__device__ inline void gemm256_16(const float* __restrict__ Xl, int ldx, const float* __restrict__ W,
+                                  WeightBlock16<TRANSPOSED>& b0, int wave, int lane, Acc16& acc, Tail tail) {
+  WeightBlock16<TRANSPOSED> wb[4];
+  LdsBlock16 xb[2];
+  wb[0] = b0;
+  wb[1].load(W, 1, wave, lane);
+  wb[2].load(W, 2, wave, lane);
+  xb[0].load(Xl, ldx, 0, lane);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    if (i + 3 < 16) wb[(i + 3) & 3].load(W, i + 3, wave, lane);
+    if (i == 13) tail();
+    if (i + 1 < 16) xb[(i + 1) & 1].load(Xl, ldx, 16 * (i + 1), lane);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_block16<TRANSPOSED>(xb[i & 1], wb[i & 3], acc);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// First-layer weights for the leading 32 rows of W (two blocks), fetched ahead of time;
+// rows at or beyond the fan-in K read as zero.
+struct SmallW16 {
+  f32x4 w[2][4];
+  __device__ inline void load(const float* __restrict__ W, int K, int wave, int lane) {
+    const int c = lane & 15, kq = lane >> 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = 16 * i + 4 * kq + j;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(W + (k < K ? k : 0) * kH + 64 * wave + 4 * c);
+        w[i][j] = k < K ? v : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+      }
+  }
+};
+
+// acc[r][c] += sum_{k<K} X[r][k] W[k][c] for a small fan-in K <= 64.
+//   X: LDS, row stride ldx, 16 rows; columns K .. roundup16(K)-1 must hold finite values
+//      (they meet zero weights);  W: global, row-major [K][256]; `pre` holds rows 0..31.
+__device__ inline void gemm_xw_small16(const float* __restrict__ Xl, int ldx, int K, const float* __restrict__ W,
+                                       const SmallW16& pre, int wave, int lane, Acc16& acc) {
+  const int c = lane & 15, kq = lane >> 4;
+  const int K16 = (K + 15) & ~15;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    if (16 * i < K16) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[c * ldx + 16 * i + 4 * kq]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc.t[nt] = mfma16(a[j], pre.w[i][j][nt], acc.t[nt]);
+    }
+  }
+  for (int k0 = 32; k0 < K16; k0 += 16) {            // fan-in beyond 32: plain loop
+    f32x4 b[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = k0 + 4 * kq + j;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(W + (size_t)(k < K ? k : 0) * kH + 64 * wave + 4 * c);
+      b[j] = k < K ? v : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+    const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[c * ldx + k0 + 4 * kq]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) acc.t[nt] = mfma16(a[j], b[j][nt], acc.t[nt]);
+  }
+}
+
+// ReLU epilogue: Y = max(acc + b, 0) to LDS (row stride kLda) and, when Yg != nullptr, to
+// global memory as [rows][256]; bb = biases of this lane's 4 columns.  Returns the
+// activation pattern, bit 4 nt + v; the backward product leaves element (row, col) in the
+// same lane and register.
+template <bool THROUGH = false>
+__device__ inline uint64_t relu_store16(const Acc16& acc, const f32x4& bb, float* __restrict__ Yl, float* __restrict__ Yg,
+                                        int wave, int lane) {
+  const int c = lane & 15, kq = lane >> 4;
+  uint64_t mask = 0;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    f32x4 o;
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+      o[nt] = fmaxf(acc.t[nt][v] + bb[nt], 0.0f);
+      if (o[nt] > 0.0f) mask |= 1ull << (4 * nt + v);
+    }
+    const int row = 4 * kq + v, col = 64 * wave + 4 * c;
+    *reinterpret_cast<f32x4*>(&Yl[row * kLda + col]) = o;
+    if (Yg) {
+      if (THROUGH) {
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) put<true>(Yg + (size_t)row * kH + col + nt, o[nt]);
+      } else {
+        *reinterpret_cast<f32x4*>(Yg + (size_t)row * kH + col) = o;
+      }
+    }
+  }
+  return mask;
+}
+
+__device__ inline bool mask_bit16(uint64_t mask, int nt, int v) { return (mask >> (4 * nt + v)) & 1ull; }
+
+// Thin products for 16 rows: out[r*kMaxAct + j] = sum_{c<256} X[r][c] V[j*256 + c], r < 16, j < J.
+// Thread t works on row t >> 4 with the column groups 64 q + 4 (t & 15); the 16 lanes of a
+// row are summed with lane shuffles.
+__device__ inline void thin_dot16(const float* __restrict__ Xl, const float* __restrict__ V, int J,
+                                  float* __restrict__ outl, int tid) {
+  const int p = tid & 15, r = tid >> 4;
+  float s[kMaxAct];
+#pragma unroll
+  for (int j = 0; j < kMaxAct; ++j) s[j] = 0.0f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int c = 64 * q + 4 * p;
+    const f32x4 x = *reinterpret_cast<const f32x4*>(&Xl[r * kLda + c]);
+#pragma unroll
+    for (int j = 0; j < kMaxAct; ++j) {
+      if (j < J) {
+        const f32x4 w = *reinterpret_cast<const f32x4*>(&V[j * kH + c]);
+        s[j] += x[0] * w[0] + x[1] * w[1] + x[2] * w[2] + x[3] * w[3];
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < kMaxAct; ++j) {
+    if (j < J) {
+      float v = s[j];
+      v += __shfl_xor(v, 1);
+      v += __shfl_xor(v, 2);
+      v += __shfl_xor(v, 4);
+      v += __shfl_xor(v, 8);
+      if (p == 0) outl[r * kMaxAct + j] = v;
+    }
+  }
+}
+
+}  // namespace pop

@@ -45,7 +45,9 @@ struct pop_ctx {
   uint64_t t;                    // update steps taken
   uint64_t gathered_t;           // step whose batch already sits in its half of the double buffer
   uint32_t step_launches;        // launches of the step kernel so far (alternates its hand-over counters)
-  int fuse;                      // 0: one launch per chain, 1: target + critic chains fused, 2: one launch per step
+  int fuse;                      // launch structure of a step, see POP_K_* in pop.h: 0 one launch per part, 1 target and
+                                 // critic chains in one launch, 2 one launch per step, 3 as 1 plus the rest of a
+                                 // delayed step in one launch
   std::string err;
 };
 
@@ -87,12 +89,21 @@ void fill_dims(const pop_config& c, PopDev& d) {
   std::memset(&d, 0, sizeof d);
   d.P = c.P; d.O = c.obs_dim; d.A = c.act_dim; d.D = c.obs_dim + c.act_dim; d.B = c.batch;
   d.row = 2 * c.obs_dim + c.act_dim + 2;
-  // rows per workgroup of the chain kernels: 64 once that still gives every CU two
-  // workgroups (halves the weight traffic per row), else 32 for more parallelism
-  d.mt = ((int64_t)c.P * (c.batch / 64) >= 512) ? 2 : 1;
-  if (const char* env = getenv("POP_ROW_TILES")) { const int v = atoi(env); if (v == 1 || v == 2) d.mt = v; }
-  d.chunks = c.batch / (32 * d.mt);
-  if (const char* env = getenv("POP_LEAN")) d.lean = atoi(env) > 0 ? 1 : (atoi(env) < 0 ? -1 : 0);
+  // Rows per workgroup of the layer chains.  64 once that still gives every CU two workgroups
+  // (halves the weight traffic per row).  16 for the target and actor chains of small
+  // populations: those parts have only 8 P workgroups at 32 rows, well under the 256 CUs, and
+  // their latency is what a step waits for; 16-row tiles halve the matrix time of every
+  // product by spreading it over twice the CUs.  Else 32.
+  const int cls = ((int64_t)c.P * (c.batch / 64) >= 512) ? 2 : ((int64_t)c.P * (c.batch / 16) <= 256 ? 0 : 1);
+  d.rows_t = d.rows_a = cls == 2 ? 64 : (cls == 0 ? 16 : 32);
+  // Beside 16 P target workgroups of 16 rows, 64-row critic chains (8 P workgroups) keep the fused
+  // target/critic launch of a small population within one workgroup per CU.
+  d.rows_c = cls == 1 ? 32 : 64;
+  if (const char* env = getenv("POP_ROWS")) {       // 16, 32 or 64: override (measurements, tests)
+    const int v = atoi(env);
+    if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; }
+    if (v == 32 || v == 64) d.rows_t = d.rows_c = d.rows_a = v;
+  }
   d.actor = make_layout(d.O, d.A);
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
@@ -114,8 +125,8 @@ Layout make_ws_layout(const PopDev& d) {
   const int64_t act = P * B * kH * 4;
   L.cH1 = take(2 * act); L.cdZ2 = take(2 * act); L.cdZ1 = take(2 * act);
   L.aH1 = take(act); L.aH2 = take(act); L.adZ2 = take(act); L.adZ1 = take(act);
-  L.cpart = take(P * 2 * (int64_t)d.chunks * kCPart * 4);
-  L.apart = take(P * (int64_t)d.chunks * kAPart * 4);
+  L.cpart = take(P * 2 * (int64_t)(d.B / d.rows_c) * kCPart * 4);
+  L.apart = take(P * (int64_t)(d.B / d.rows_a) * kAPart * 4);
   L.losses = take(P * 4 * 4);
   L.y_tagged = take(P * B * 8);
   L.done_c = take(4 * P * 4); L.done_wc = take(4 * P * 4); L.done_a = take(2 * P * 4);
@@ -212,8 +223,8 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   // the target/critic pair.
   // (The 64-row chains of very large populations do not fit the register budget of the
   // single kernel without spilling and stay separate as well.)
-  ctx->fuse = (d.mt == 1 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512) ? 2 : 1;
-  if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 2) ctx->fuse = v; }
+  ctx->fuse = (d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512) ? 2 : 1;
+  if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
   ctx->hp.assign(hp, hp + cfg->P);
   ctx->count.assign(cfg->P, 0);
   ctx->hp_dev.resize(cfg->P);
@@ -342,9 +353,9 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
     ctx->t++;
     return POP_OK;
   }
-  if (ctx->fuse == 1) {
+  if (ctx->fuse == 1 || ctx->fuse == 3) {
     if (!run(POP_K_TARGET_CRITIC, launch_target_critic)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
-    if (any_actor) {                                 // the rest of the step in one launch: the actor's own forward pass
+    if (any_actor && ctx->fuse == 3) {               // the rest of the step in one launch: the actor's own forward pass
       tick(POP_K_STEP_TAIL, 0);                      // runs beside the critic weight gradients
       e = launch_step(d, t, ctx->step_launches++, 0, 1, has_next ? 1 : 0, s);
       tick(POP_K_STEP_TAIL, 1);

@@ -13,8 +13,11 @@ extern __device__ int g_pop_trace_block;            // the block whose marks are
     if ((int)blockIdx.x == g_pop_trace_block && threadIdx.x == 0) g_pop_trace[i] = wall_clock64(); \
     if (blockIdx.x == 0 && threadIdx.x == 0 && (i) == 63) g_pop_trace[63] = wall_clock64();       \
   } while (0)
+extern __device__ unsigned long long g_pop_block_time[2][8192];   // start / end of every block of the traced launch
+#define POP_BLOCK_TIME(w) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_pop_block_time[w][blockIdx.x] = wall_clock64(); } while (0)
 #else
 #define POP_MARK(i)
+#define POP_BLOCK_TIME(w)
 #endif
 
 namespace pop {
@@ -55,9 +58,8 @@ __host__ __device__ inline NetLayout make_layout(int in, int out) {
 
 struct PopDev {
   int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
-  int mt;                      // row tiles per workgroup of the fused chain kernels (rows = 32 mt)
-  int chunks;                  // B / (32 mt)
-  int lean;                    // chain-kernel variant: 0 choose by launch size, 1 always lean, -1 always deep prefetch
+  int rows_t, rows_c, rows_a;  // batch rows per workgroup of the target / critic / actor chain: (16, 32, 16) for small
+                               // populations, (32, 32, 32), or (64, 64, 64) for large ones
   NetLayout actor, critic;
   int agent_sz;                // actor.padded + 2 * critic.padded
   // parameter state, each [P][agent_sz] = [actor | critic1 | critic2]

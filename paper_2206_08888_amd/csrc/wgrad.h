@@ -188,6 +188,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
   const uint32_t* wait_on = !producer_in_launch ? nullptr
                             : actor_phase       ? d.done_a + parity_base(d, t, d.P) + agent
                                                 : d.done_c + parity_base(d, t, 2 * d.P) + unit;
+  const int chunks = d.B / (actor_phase ? d.rows_a : d.rows_c);   // row chunks of the chain that feeds this network
   const int n1 = (L.in + 31) / 32;
   if (role < 16 + 2 * n1) {
     const size_t o = (size_t)unit * d.B * kH;        // unit = agent (actor) or network (critics)
@@ -195,11 +196,11 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     const bool w2 = role < 16;                       // else layer 1, whose input is the leading columns of the batch rows
     const float* x = w2 ? (actor_phase ? d.aH1 : d.cH1) + o : batch_rows(d, t, agent);
     const float* z = (w2 ? (actor_phase ? d.adZ2 : d.cdZ2) : (actor_phase ? d.adZ1 : d.cdZ1)) + o;
-    weight_tile<WAIT>(d, wait_on, (uint32_t)d.chunks, sh_adam, delayed_step, x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
+    weight_tile<WAIT>(d, wait_on, (uint32_t)chunks, sh_adam, delayed_step, x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
                 (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
   } else {
     // small tensors from per-chunk partial sums; thread c owns hidden unit c
-    if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)d.chunks);
+    if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
     __syncthreads();
     const Adam adam = *sh_adam;
     const int c = tid;
@@ -208,9 +209,9 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
 #pragma unroll
     for (int j = 0; j < kMaxAct; ++j) gw3[j] = 0.0f;
 #pragma unroll 4
-    for (int ch = 0; ch < d.chunks; ++ch) {
+    for (int ch = 0; ch < chunks; ++ch) {
       if (actor_phase) {
-        const float* p = d.apart + ((size_t)agent * d.chunks + ch) * kAPart;
+        const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart;
         gb1 += p[kAP_db1 + c];
         gb2 += p[kAP_db2 + c];
 #pragma unroll
@@ -219,7 +220,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
         if (c < out) gb3 += p[kAP_db3 + c];
         if (c == 0) loss += p[kAP_loss];
       } else {
-        const float* p = d.cpart + ((size_t)unit * d.chunks + ch) * kCPart;
+        const float* p = d.cpart + ((size_t)unit * chunks + ch) * kCPart;
         gb1 += p[kCP_db1 + c];
         gb2 += p[kCP_db2 + c];
         gw3[0] += p[kCP_dW3 + c];

@@ -240,8 +240,8 @@ def test_set_params_round_trips_and_rejects_bad_arguments():
 
 def test_launch_structures_agree_bit_for_bit(monkeypatch):
     """One launch per step (parts hand results on inside the launch: tagged words for the
-    Bellman targets, release/acquire counters for activation tiles and updated critics),
-    target + critic chains fused, and one launch per part: identical arithmetic, so every
+    Bellman targets, counters for activation tiles and updated critics), target + critic
+    chains fused with and without the rest of the step fused, and one launch per part: identical arithmetic, so every
     parameter and moment must be bit-identical, also for a population size that is not a
     multiple of 8 (uneven XCD groups) and with mixed policy delays (agents whose actor
     parts leave early)."""
@@ -249,7 +249,7 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
     for i, hp in enumerate(hps):
         hp["policy_delay"] = (2, 1, 3)[i % 3]
     states = []
-    for fuse in ("2", "1", "0"):
+    for fuse in ("2", "3", "1", "0"):
         monkeypatch.setenv("POP_FUSE", fuse)
         gpu, _, _ = make_pair(2, P=11, capacity=3000, hps=hps, oracle=False)
         gpu.update(7)
@@ -259,8 +259,11 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
             assert cnt["step"] == 6 and sum(cnt.values()) == 7
         else:
             assert cnt["step"] == 0
-            if fuse == "1":
+            if fuse == "3":
                 assert cnt["target_critic"] == 6 and cnt["step_tail"] == 6 and sum(cnt.values()) == 13
+            elif fuse == "1":
+                assert cnt["target_critic"] == cnt["wgrad_critic"] == cnt["actor"] == cnt["wgrad_actor"] == 6
+                assert sum(cnt.values()) == 25
             else:
                 assert cnt["target"] == cnt["critic"] == cnt["wgrad_critic"] == cnt["actor"] == cnt["wgrad_actor"] == 6
                 assert sum(cnt.values()) == 31

@@ -7,7 +7,7 @@
 
 namespace pop {
 
-__global__ __launch_bounds__(kThreads, 3) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
+__global__ __launch_bounds__(kThreads, 2) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
                                                           int roles, int prefetch) {
   __shared__ Adam sh_adam;
   __shared__ __attribute__((aligned(16))) float xt_lds[32 * kLda];

@@ -257,6 +257,31 @@ __device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const floa
   POP_MARK(24);
 }
 
+// The same product fully unrolled with NB rotating weight buffers (block i + NB - 1 is requested
+// before the MFMAs of block i): for operands that come from memory rather than L2 and for
+// narrow tiles (NT = 1), where a block is only 512 cycles of matrix work and four buffers
+// cover too little latency.
+template <int MT, bool TRANSPOSED, int NT, int NB, class Tail>
+__device__ inline void gemm256_unrolled(const float* __restrict__ Xl, int ldx, const float* __restrict__ W,
+                                        WeightBlock<MT, TRANSPOSED, NT>& b0, int wave, int lane, Acc<MT, NT>& acc,
+                                        Tail tail) {
+  WeightBlock<MT, TRANSPOSED, NT> wb[NB];
+  LdsBlock<MT> xb[2];
+  wb[0] = b0;
+#pragma unroll
+  for (int i = 1; i < NB - 1; ++i) wb[i].load(W, i, wave, lane);
+  xb[0].load(Xl, ldx, 0, lane);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    if (i + NB - 1 < 16) wb[(i + NB - 1) % NB].load(W, i + NB - 1, wave, lane);
+    if (i == 16 - NB + 1) tail();
+    if (i + 1 < 16) xb[(i + 1) & 1].load(Xl, ldx, 16 * (i + 1), lane);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_block<MT, TRANSPOSED, NT>(xb[i & 1], wb[i % NB], acc);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // The same product with two weight buffers only (block j+1 requested before block j's
 // MFMAs): a third fewer live registers, for launches with several workgroups per CU,
 // where other workgroups' MFMAs cover the exposed latency instead of deep prefetching.

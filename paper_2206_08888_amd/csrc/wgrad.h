@@ -52,14 +52,6 @@ __device__ inline double ipow(double b, uint32_t n) {
   return r;
 }
 
-__device__ inline AdamRegs adam_load(const Adam& a, uint32_t i, const float* __restrict__ th, const float* __restrict__ m,
-                                     const float* __restrict__ v, const float* __restrict__ tg) {
-  AdamRegs r;
-  r.th = th[i]; r.m = m[i]; r.v = v[i];
-  r.tg = a.polyak ? tg[i] : 0.0f;
-  return r;
-}
-
 // THROUGH: the updated parameter is read by the actor chain of the same launch
 template <bool THROUGH = false>
 __device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uint32_t i, float* __restrict__ th,
@@ -81,11 +73,12 @@ __device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uin
 //   x: [256][ldx] layer input, z: [256][256] pre-activation gradient, both global;
 //   base: offset of the matrix inside the network's parameter block.
 // The tile's parameters, moments and targets do not depend on the product, so they are
-// requested first and arrive while the operands are staged and multiplied.  `sh` is
-// written by thread 0 before the call and read after the barrier inside.
-template <bool WAIT>
+// requested first and arrive while the operands are staged and multiplied.  `setup()` fills
+// `sh` (thread 0 only; a few hundred cycles of double arithmetic): it runs once the loads are
+// on their way, and `sh` is read after the barrier that follows.
+template <bool WAIT, class Setup>
 __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wait_on, uint32_t want, const Adam* sh,
-                                            bool polyak, const float* __restrict__ x, int ldx, int M, int m0,
+                                            Setup setup, bool polyak, const float* __restrict__ x, int ldx, int M, int m0,
                                    int n0, const float* __restrict__ z, uint32_t base, float* Xl,
                                    float* __restrict__ th, float* __restrict__ mo, float* __restrict__ ve,
                                    float* __restrict__ tg, float* __restrict__ gr, int tid) {
@@ -94,47 +87,57 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   // flat offset of accumulator element v = 0 of this lane
   const uint32_t elem0 = base + (uint32_t)((m0 + 4 * half) * kH + n0 + 32 * wave + l32);
   AdamRegs regs[16];
+  auto load_adam = [&]() {
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const bool ok = (m0 + acc_row(v, lane)) < M;
-    const uint32_t i = ok ? elem0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH) : elem0;
-    regs[v].th = th[i]; regs[v].m = mo[i]; regs[v].v = ve[i];
-    regs[v].tg = polyak ? tg[i] : 0.0f;
-  }
-  if (WAIT && wait_on) {                             // x and z come from a chain of this launch
+    for (int v = 0; v < 16; ++v) {
+      const bool ok = (m0 + acc_row(v, lane)) < M;
+      const uint32_t i = ok ? elem0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH) : elem0;
+      regs[v].th = th[i]; regs[v].m = mo[i]; regs[v].v = ve[i];
+      regs[v].tg = polyak ? tg[i] : 0.0f;
+    }
+  };
+  // this thread's row of the X slice (thread b holds batch row b, 32 columns of it)
+  const bool aligned = (ldx & 3) == 0;               // a hidden layer's output; else batch rows of any stride
+  const float* xr = x + (size_t)tid * ldx + m0;
+  float xs[32];
+  auto load_x = [&]() {
+    if (aligned) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(xr + 4 * i);
+        xs[4 * i] = v[0]; xs[4 * i + 1] = v[1]; xs[4 * i + 2] = v[2]; xs[4 * i + 3] = v[3];
+      }
+    } else {
+#pragma unroll
+      for (int m = 0; m < 32; ++m) xs[m] = xr[(m0 + m) < M ? m : 0];
+    }
+  };
+  WeightBlock<1, false, 1> z0;
+  if (WAIT && wait_on) {                             // x and z come from a chain of this launch:
+    load_adam();                                     // the Adam operands can be on their way meanwhile
+    setup();
     if (tid == 0) wait_count(d, wait_on, want);
     __syncthreads();
+    load_x();
+    z0.load(z + n0, 0, wave, lane);
+  } else {                                           // what the product needs first goes out first
+    load_x();
+    z0.load(z + n0, 0, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+    load_adam();
+    __builtin_amdgcn_sched_barrier(0);
+    setup();
   }
-  WeightBlock<1, false, 1> z0;
-  z0.load(z + n0, 0, wave, lane);
+  __builtin_amdgcn_sched_barrier(0);
   POP_MARK(51);
-  {                                                  // X^T slice into LDS: thread b copies row b
-    const float* xr = x + (size_t)tid * ldx + m0;
-    if ((ldx & 3) == 0) {                            // 16-byte aligned rows (a hidden layer's output)
-      f32x4 v[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = *reinterpret_cast<const f32x4*>(xr + 4 * i);
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) Xl[(4 * i + q) * kLda + tid] = v[i][q];
-    } else {                                         // batch rows: any stride, columns >= M are zero
-      float v[32];
-#pragma unroll
-      for (int m = 0; m < 32; ++m) {
-        const int mm = (m0 + m) < M ? m : 0;
-        v[m] = xr[mm];
-      }
-#pragma unroll
-      for (int m = 0; m < 32; ++m) Xl[m * kLda + tid] = (m0 + m) < M ? v[m] : 0.0f;
-    }
-  }
+  for (int m = 0; m < 32; ++m) Xl[m * kLda + tid] = (aligned || (m0 + m) < M) ? xs[m] : 0.0f;   // X^T slice into LDS
   __syncthreads();
   POP_MARK(52);
   const Adam adam = *sh;
   Acc<1, 1> acc;
   acc.zero();
-  gemm256<1, false, 1>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());
+  gemm256_unrolled<1, false, 1, 8>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());
   POP_MARK(53);
   uint32_t e1 = elem0;
   asm volatile("" : "+v"(e1));                       // recompute the addresses: keeping 64 of them alive costs more
@@ -164,7 +167,8 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
   const bool delayed_step = (t % delay) == 0u;
   if (actor_phase && !delayed_step) return;
 
-  if (tid == 0) {                                    // read by everyone after the next barrier
+  auto setup = [&]() {
+    if (tid != 0) return;                            // read by everyone after the next barrier
     Adam a;
     const uint32_t count = actor_phase ? t / delay + 1u : t + 1u;   // 1-based Adam step
     a.lr = actor_phase ? hp.lr_actor : hp.lr_critic;
@@ -175,7 +179,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     a.polyak = delayed_step ? 1 : 0;
     a.record = d.record_grads;
     *sh_adam = a;
-  }
+  };
 
   const NetLayout& L = actor_phase ? d.actor : d.critic;
   float* th = net_ptr(d, d.theta, agent, net);
@@ -196,15 +200,30 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     const bool w2 = role < 16;                       // else layer 1, whose input is the leading columns of the batch rows
     const float* x = w2 ? (actor_phase ? d.aH1 : d.cH1) + o : batch_rows(d, t, agent);
     const float* z = (w2 ? (actor_phase ? d.adZ2 : d.cdZ2) : (actor_phase ? d.adZ1 : d.cdZ1)) + o;
-    weight_tile<WAIT>(d, wait_on, (uint32_t)chunks, sh_adam, delayed_step, x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
+    weight_tile<WAIT>(d, wait_on, (uint32_t)chunks, sh_adam, setup, delayed_step, x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
                 (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
   } else {
-    // small tensors from per-chunk partial sums; thread c owns hidden unit c
+    // small tensors from per-chunk partial sums; thread c owns hidden unit c.  The Adam operands
+    // are requested first: they depend on nothing and arrive while the partial sums are read.
+    const int c = tid;
+    const int out = L.out;
+    const uint32_t i_b1 = (uint32_t)(L.b1 + c), i_b2 = (uint32_t)(L.b2 + c), i_w3 = (uint32_t)(L.w3 + c * out),
+                   i_b3 = (uint32_t)(L.b3 + (c < out ? c : 0));
+    const bool polyak = delayed_step;
+    auto ld = [&](uint32_t i) {
+      AdamRegs r;
+      r.th = th[i]; r.m = mo[i]; r.v = ve[i];
+      r.tg = polyak ? tg[i] : 0.0f;
+      return r;
+    };
+    const AdamRegs r_b1 = ld(i_b1), r_b2 = ld(i_b2), r_b3 = ld(i_b3);
+    AdamRegs r_w3[kMaxAct];
+#pragma unroll
+    for (int j = 0; j < kMaxAct; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j < out ? j : 0));
+    setup();
     if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
     __syncthreads();
     const Adam adam = *sh_adam;
-    const int c = tid;
-    const int out = L.out;
     float gb1 = 0.0f, gb2 = 0.0f, gw3[kMaxAct], gb3 = 0.0f, loss = 0.0f;
 #pragma unroll
     for (int j = 0; j < kMaxAct; ++j) gw3[j] = 0.0f;
@@ -227,13 +246,12 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
         if (c == 0) { gb3 += p[kCP_db3]; loss += p[kCP_loss]; }
       }
     }
-    auto upd = [&](float g, uint32_t i) { adam_store<WAIT>(adam, adam_load(adam, i, th, mo, ve, tg), g, i, th, mo, ve, tg, gr); };
-    upd(gb1, (uint32_t)(L.b1 + c));
-    upd(gb2, (uint32_t)(L.b2 + c));
+    adam_store<WAIT>(adam, r_b1, gb1, i_b1, th, mo, ve, tg, gr);
+    adam_store<WAIT>(adam, r_b2, gb2, i_b2, th, mo, ve, tg, gr);
 #pragma unroll
     for (int j = 0; j < kMaxAct; ++j)
-      if (j < out) upd(gw3[j], (uint32_t)(L.w3 + c * out + j));
-    if (c < out) upd(gb3, (uint32_t)(L.b3 + c));
+      if (j < out) adam_store<WAIT>(adam, r_w3[j], gw3[j], i_w3 + (uint32_t)j, th, mo, ve, tg, gr);
+    if (c < out) adam_store<WAIT>(adam, r_b3, gb3, i_b3, th, mo, ve, tg, gr);
     if (c == 0) {
       // critic loss = sum over the twins; the two critic workgroups of an agent write
       // their halves to separate slots and the reader adds them

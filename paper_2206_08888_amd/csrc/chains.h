@@ -354,7 +354,7 @@ __device__ inline void wait_count(const PopDev& d, const uint32_t* count, uint32
 //   a~ = clip(pi'(s') + clip(sigma eps, -c, c), -1, 1), eps = normal e = b A + j of stream 1
 //   y  = r + gamma (1 - d) min(Q1'(s', a~), Q2'(s', a~))
 template <class G, bool DEEP>
-__device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int block, float* lds) {
+__device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int agent, int chunk, float* lds) {
   constexpr int R = G::R;
   const LdsMap<G::R, G::kPad> L(d.D);
   float* Xs = lds;
@@ -366,8 +366,6 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int bl
   float* v_cw3 = v_ab3 + 8;                          // [2][256]
   float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  int agent, chunk;
-  if (!decode_block(block, d.P, d.B / R, agent, chunk)) return;
   const int r0 = chunk * R;
   const float* ta = net_ptr(d, d.target, agent, 0);
   const float* tc0 = net_ptr(d, d.target, agent, 1);
@@ -453,7 +451,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int bl
 // them poll for their rows right before the loss.  SIGNAL: count this chunk as finished
 // for the weight-gradient workgroups of the same launch.
 template <class G, bool DEEP, bool WAIT, bool SIGNAL>
-__device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int block, float* lds) {
+__device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int net, int chunk, float* lds) {
   constexpr int R = G::R;
   const LdsMap<G::R, G::kPad> L(d.D);
   float* Xs = lds;
@@ -462,8 +460,6 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int bl
   float* dq = lds + L.s1;
   float* v_w3 = lds + L.vec;                         // [256]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  int net, chunk;
-  if (!decode_block(block, 2 * d.P, d.B / R, net, chunk)) return;
   const int agent = net >> 1, k = net & 1, r0 = chunk * R;
   const float* cn = net_ptr(d, d.theta, agent, 1 + k);
   typename G::Pre pre;
@@ -550,7 +546,7 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int bl
 // workgroups are done.  SIGNAL: count this chunk as finished for the actor's weight-gradient
 // workgroups.
 template <class G, bool DEEP, bool WAIT>
-__device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int block, float* lds, int critic_roles) {
+__device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int agent, int chunk, float* lds, int critic_roles) {
   constexpr int R = G::R;
   const LdsMap<G::R, G::kPad> L(d.D);
   float* Xs = lds;
@@ -564,8 +560,6 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int blo
   float* v_cw3 = v_ab3 + 8;                          // [256] critic head
   float* v_cwa = v_cw3 + kH;                         // [A][256] critic first-layer rows of the action inputs
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  int agent, chunk;
-  if (!decode_block(block, d.P, d.B / R, agent, chunk)) return;
   const int r0 = chunk * R;
   const HpDev hp = d.hp[agent];
   if (t % (uint32_t)hp.policy_delay != 0u) return;

@@ -9,13 +9,15 @@ namespace pop {
 template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_target(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
-  target_chain<G, true>(d, t, blockIdx.x, lds);
+  int agent, chunk;
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) target_chain<G, true>(d, t, agent, chunk, lds);
 }
 
 template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_critic(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
-  critic_chain<G, true, false, false>(d, t, blockIdx.x, lds);
+  int net, chunk;
+  if (decode_block(blockIdx.x, 2 * d.P, d.B / G::R, net, chunk)) critic_chain<G, true, false, false>(d, t, net, chunk, lds);
 }
 
 // Target and critic chains of one step in a single launch.  The critic's forward pass does
@@ -27,14 +29,19 @@ __global__ __launch_bounds__(kThreads, 1) void k_critic(PopDev d, uint32_t t) {
 template <class GT, class GC>
 __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
-  if ((int)blockIdx.x < target_blocks) target_chain<GT, true>(d, t, blockIdx.x, lds);
-  else critic_chain<GC, true, true, false>(d, t, blockIdx.x - target_blocks, lds);
+  int unit, chunk;
+  if ((int)blockIdx.x < target_blocks) {
+    if (decode_block(blockIdx.x, d.P, d.B / GT::R, unit, chunk)) target_chain<GT, true>(d, t, unit, chunk, lds);
+  } else if (decode_block(blockIdx.x - target_blocks, 2 * d.P, d.B / GC::R, unit, chunk)) {
+    critic_chain<GC, true, true, false>(d, t, unit, chunk, lds);
+  }
 }
 
 template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_actor(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
-  actor_chain<G, true, false>(d, t, blockIdx.x, lds, 0);
+  int agent, chunk;
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, true, false>(d, t, agent, chunk, lds, 0);
 }
 
 // ---------------------------------------------------------------------------------------------

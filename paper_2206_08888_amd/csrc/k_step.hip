@@ -40,16 +40,37 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
       if (i < d.P) d.done_a[other * d.P + i] = 0u;
     }
   }
-  if (b < g.t) { target_chain<GT, true>(d, t, b, lds); POP_BLOCK_TIME(1); return; }
+  int unit, sub;
+  if (b < g.t) {
+    if (decode_block(b, d.P, d.B / GT::R, unit, sub)) target_chain<GT, true>(d, t, unit, sub, lds);
+    POP_BLOCK_TIME(1);
+    return;
+  }
   b -= g.t;
-  if (b < g.c) { critic_chain<GC, true, true, true>(d, t, b, lds); POP_BLOCK_TIME(1); return; }
+  if (b < g.c) {
+    if (decode_block(b, 2 * d.P, d.B / GC::R, unit, sub)) critic_chain<GC, true, true, true>(d, t, unit, sub, lds);
+    POP_BLOCK_TIME(1);
+    return;
+  }
   b -= g.c;
   Adam* sh_adam = reinterpret_cast<Adam*>(lds + 32 * kLda);
-  if (b < g.wc) { wgrad_roles<true>(d, t, 0, b, g.roles_c, lds, sh_adam, g.c != 0); POP_BLOCK_TIME(1); return; }
+  if (b < g.wc) {
+    if (decode_block(b, 2 * d.P, g.roles_c, unit, sub)) wgrad_roles<true>(d, t, 0, unit, sub, lds, sh_adam, g.c != 0);
+    POP_BLOCK_TIME(1);
+    return;
+  }
   b -= g.wc;
-  if (b < g.a) { actor_chain<GA, true, true>(d, t, b, lds, g.roles_c); POP_BLOCK_TIME(1); return; }
+  if (b < g.a) {
+    if (decode_block(b, d.P, d.B / GA::R, unit, sub)) actor_chain<GA, true, true>(d, t, unit, sub, lds, g.roles_c);
+    POP_BLOCK_TIME(1);
+    return;
+  }
   b -= g.a;
-  if (b < g.wa) { wgrad_roles<true>(d, t, 1, b, g.roles_a, lds, sh_adam); POP_BLOCK_TIME(1); return; }
+  if (b < g.wa) {
+    if (decode_block(b, d.P, g.roles_a, unit, sub)) wgrad_roles<true>(d, t, 1, unit, sub, lds, sh_adam);
+    POP_BLOCK_TIME(1);
+    return;
+  }
   b -= g.wa;
   if (b < g.g) {
     const int per = gather_blocks_per_agent(d);

@@ -19,7 +19,9 @@ __global__ __launch_bounds__(kThreads, 2) void k_wgrad_adam(PopDev d, uint32_t t
     }
     return;
   }
-  wgrad_roles<false>(d, t, actor_phase, blockIdx.x, roles, xt_lds, &sh_adam);
+  int unit, role;
+  if (decode_block(blockIdx.x, actor_phase ? d.P : 2 * d.P, roles, unit, role))
+    wgrad_roles<false>(d, t, actor_phase, unit, role, xt_lds, &sh_adam);
 }
 
 int wgrad_role_count(const PopDev& d, int actor_phase) {

@@ -150,16 +150,14 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   POP_MARK(54);
 }
 
-// All roles of the weight-gradient step of one network; `block` indexes (network, role).
+// One role of the weight-gradient step of one network (unit = agent in the actor phase, else network).
 // WAIT: consumers (the actor chain, for critic 1) and, if producer_in_launch, producers (the
 // chain of this network) run in the same launch -- hold before the first read of chain
 // output, count in at the end.
 template <bool WAIT>
-__device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int actor_phase, int block, int roles,
+__device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int actor_phase, int unit, int role,
                                             float* xt_lds, Adam* sh_adam, bool producer_in_launch = true) {
   const int tid = threadIdx.x;
-  int unit, role;
-  if (!decode_block(block, actor_phase ? d.P : 2 * d.P, roles, unit, role)) return;
   const int agent = actor_phase ? unit : unit >> 1;
   const int net = actor_phase ? 0 : 1 + (unit & 1);
   const HpDev hp = d.hp[agent];

@@ -16,16 +16,27 @@ One step t (0-based) of one agent, in order:
      hand-derived backprop; Adam on both critics with step count t + 1;
   5. if t mod d == 0: actor loss -(1/B) sum_b Q1(s, pi(s)) through the critic
      just updated in 4 (critic weights get no gradient from it); Adam on the
-     actor with its own step count t/d + 1; then Polyak-average all three
-     target networks towards the online ones.
+     actor with its own step count (the number of actor updates taken so far,
+     this one included; t/d + 1 while d stays fixed); then Polyak-average all
+     three target networks towards the online ones.
 Readings taken where the sources the paper cites differ: the actor sees the
 critic after its update; all targets move only on delayed steps; step 0 is a
 delayed step; sampling is with replacement; ReLU'(0) = 0; `done` is a float
 that multiplies the bootstrap term.
 
+Population-method primitives (Sec. 4.2 / App. B.1 of the paper: at the end of an
+iteration the worst agents are replaced by copies of good ones and get new
+hyperparameters): Population.copy_agent and Population.set_hparams, written as
+what the words say -- the copy takes networks, targets, optimiser state and
+optionally the buffer; the copy keeps its own seed and hyperparameters until
+set_hparams changes them.
+
 Pins: tests/test_oracle_td3.py (finite differences of both losses through the
 whole step, torch.autograd float64 cross-check of one full step, hand cases of
-the target, step-ordering properties, population independence).
+the target, step-ordering properties, population independence; a copied agent
+given the parent's seed and hyperparameters stays bit-identical to the parent;
+hyperparameter changes act from the next step on and leave the Adam counts
+continuous).
 """
 import numpy as np
 
@@ -55,6 +66,7 @@ class Agent:
         self.opt_critic = [optim.AdamState(c) for c in self.critic]
         self.buffer = replay.ReplayBuffer(capacity, obs_dim, act_dim)
         self.t = 0
+        self.actor_updates = 0                  # Adam step count of the actor so far
         self.last = {}                          # diagnostics of the last step
 
     # -- pieces of the step, exposed so tests can pin them one by one ---------
@@ -113,8 +125,9 @@ class Agent:
         delay = int(hp["policy_delay"])
         if t % delay == 0:
             a_loss, a_grads = self.actor_loss_and_grads(s)
+            self.actor_updates += 1
             optim.adam_step(self.actor, a_grads, self.opt_actor, hp["lr_actor"],
-                            t // delay + 1, hp["adam_b1"], hp["adam_b2"], hp["adam_eps"])
+                            self.actor_updates, hp["adam_b1"], hp["adam_b2"], hp["adam_eps"])
             optim.polyak(self.t_actor, self.actor, hp["tau"])
             for k in range(2):
                 optim.polyak(self.t_critic[k], self.critic[k], hp["tau"])
@@ -153,6 +166,27 @@ class Population:
 
     def act(self, obs):
         return np.stack([ag.act(obs[i]) for i, ag in enumerate(self.agents)])
+
+    def copy_agent(self, dst, src, with_buffer):
+        """Agent dst becomes a copy of agent src: online and target networks, Adam moments
+        and the actor's Adam count; with_buffer: also the replay buffer (contents, cursor,
+        fill level).  dst keeps its own seed and hyperparameters."""
+        import copy
+        a, b = self.agents[src], self.agents[dst]
+        b.actor, b.critic = copy.deepcopy(a.actor), copy.deepcopy(a.critic)
+        b.t_actor, b.t_critic = copy.deepcopy(a.t_actor), copy.deepcopy(a.t_critic)
+        b.opt_actor, b.opt_critic = copy.deepcopy(a.opt_actor), copy.deepcopy(a.opt_critic)
+        b.actor_updates = a.actor_updates
+        if with_buffer:
+            b.buffer = copy.deepcopy(a.buffer)
+
+    def set_hparams(self, agent, hp):
+        """New hyperparameters (and seed) for one agent from its next step on."""
+        ag = self.agents[agent]
+        ag.hp = dict(hp)
+        for k in HP_FLOAT_FIELDS:
+            ag.hp[k] = float(np.float32(ag.hp[k]))
+        ag.seed = int(hp["seed"])
 
     def get_params(self, agent, which):
         ag = self.agents[agent]

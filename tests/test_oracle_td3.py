@@ -220,3 +220,62 @@ def test_seed_zero_is_derived_from_population_seed_and_index():
     pop = td3.Population([hp, hp], 3, 2, [4, 4], 4, 8, seed=99)
     assert pop.agents[0].seed == philox.mix64(99, 0) and pop.agents[1].seed == philox.mix64(99, 1)
     assert not np.array_equal(pop.get_params(0, "actor"), pop.get_params(1, "actor"))
+
+
+# ---- population-method primitives (App. B.1: worst agents replaced by copies of good ones, new hyperparameters) ----
+def _small_population(P=3, steps=5):
+    hps = workloads.hparams(2, P=P)
+    pop = td3.Population(hps, 3, 2, [8, 8], 16, 64)
+    for i in range(P):
+        pop.insert(i, **workloads.transitions(2, i, 50, obs_dim=3, act_dim=2))
+    pop.update(steps)
+    return pop, hps
+
+
+def test_copied_agent_with_the_parents_seed_and_hparams_stays_identical_to_the_parent():
+    pop, hps = _small_population()
+    before = {w: pop.get_params(2, w).copy() for w in td3.WHICH[:12]}
+    pop.copy_agent(0, 2, with_buffer=True)
+    for w in td3.WHICH[:12]:
+        assert np.array_equal(pop.get_params(0, w), pop.get_params(2, w)), w          # all of the state arrived
+        assert np.array_equal(pop.get_params(2, w), before[w]), w                     # the parent is untouched
+    assert pop.agents[0].seed == hps[0]["seed"] and pop.agents[0].hp["lr_critic"] == np.float32(hps[0]["lr_critic"])
+    pop.set_hparams(0, hps[2])
+    pop.update(6)
+    for w in td3.WHICH[:12]:
+        assert np.array_equal(pop.get_params(0, w), pop.get_params(2, w)), w
+    # a deep copy: the child goes its own way once it has its own hyperparameters again
+    pop.set_hparams(0, hps[0])
+    pop.update(1)
+    assert not np.array_equal(pop.get_params(0, "critic1"), pop.get_params(2, "critic1"))
+
+
+def test_copy_without_buffer_keeps_the_childs_own_transitions():
+    pop, _ = _small_population()
+    rows = pop.agents[0].buffer.rows.copy()
+    pop.copy_agent(0, 1, with_buffer=False)
+    assert np.array_equal(pop.agents[0].buffer.rows, rows)
+    assert np.array_equal(pop.get_params(0, "v_actor"), pop.get_params(1, "v_actor"))
+
+
+def test_new_hparams_act_from_the_next_step_and_keep_the_adam_counts_continuous():
+    pop, hps = _small_population(P=2, steps=4)          # delay 2: actor updates at t = 0, 2
+    ag = pop.agents[0]
+    assert ag.actor_updates == 2
+    frozen = dict(hps[0], lr_critic=0.0, policy_delay=3)
+    pop.set_hparams(0, frozen)
+    c_before, a_before = pop.get_params(0, "critic1").copy(), pop.get_params(0, "actor").copy()
+    pop.update(2)                                       # t = 4, 5: no multiple of 3
+    assert np.array_equal(pop.get_params(0, "critic1"), c_before)      # lr 0: moments move, parameters do not
+    assert np.array_equal(pop.get_params(0, "actor"), a_before) and ag.actor_updates == 2
+    assert not np.array_equal(pop.get_params(1, "critic1"), pop.get_params(0, "critic1"))
+    # t = 6 is an actor step under delay 3; its Adam step is the 3rd, whatever t // delay says.
+    # Check against the closed form of one Adam step from the moments before it.
+    m0, v0 = pop.get_params(0, "m_actor").copy(), pop.get_params(0, "v_actor").copy()
+    pop.update(1)
+    assert ag.actor_updates == 3
+    g = mlp.flatten(ag.last["actor_grads"])
+    b1, b2, eps, lr = ag.hp["adam_b1"], ag.hp["adam_b2"], ag.hp["adam_eps"], ag.hp["lr_actor"]
+    m1, v1 = b1 * m0 + (1 - b1) * g, b2 * v0 + (1 - b2) * g * g
+    want = a_before - lr * (m1 / (1 - b1 ** 3)) / (np.sqrt(v1 / (1 - b2 ** 3)) + eps)
+    np.testing.assert_allclose(pop.get_params(0, "actor"), want, rtol=1e-12, atol=1e-15)

@@ -196,6 +196,26 @@ int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out,
 int pop_set_params(pop_ctx* ctx, int32_t agent, int32_t which, const float* in,
                    int64_t in_len, int32_t on_device);
 
+/* Agent dst becomes a copy of agent src: online and target networks, Adam
+ * moments and the actor's Adam step count (device-to-device copies on the
+ * context's stream); with_buffer != 0: also the replay buffer with its fill
+ * level and write position.  dst keeps its own seed and hyperparameters.
+ * This is the "exploit" half of the population step of App. B.1 of the paper
+ * (the worst agents are replaced by copies of randomly chosen good ones);
+ * which agents are good is the caller's business.  Synchronises the stream.
+ * POP_EINVAL for an agent index out of range; dst == src is a no-op. */
+int pop_copy_agent(pop_ctx* ctx, int32_t dst, int32_t src, int32_t with_buffer);
+
+/* New hyperparameters (and seed) for one agent, in force from its next update
+ * step on: the "explore" half of the same population step (App. B.1: the
+ * copies have their hyperparameters re-sampled -- learning rates, update
+ * frequency of the policy, noise parameters, discount).  Checked like the
+ * hyperparameters given to pop_create; seed 0 is rejected here.  Adam's step
+ * counts stay continuous: the critics count every step, the actor the actor
+ * updates actually taken, whatever policy_delay was at the time.
+ * Synchronises the stream. */
+int pop_set_hparams(pop_ctx* ctx, int32_t agent, const pop_hparams* hp);
+
 /* Record per-parameter gradients for POP_GRAD_* (costs one extra store per
  * parameter per step).  Off by default. */
 int pop_set_debug(pop_ctx* ctx, int32_t on);

@@ -73,6 +73,8 @@ def load_library():
         "pop_act": (C.c_int, [vp, fp, i32, fp, i32]),
         "pop_get_params": (i64, [vp, i32, i32, fp, i64, i32]),
         "pop_set_params": (C.c_int, [vp, i32, i32, fp, i64, i32]),
+        "pop_copy_agent": (C.c_int, [vp, i32, i32, i32]),
+        "pop_set_hparams": (C.c_int, [vp, i32, hpp]),
         "pop_set_debug": (C.c_int, [vp, i32]),
         "pop_debug_get": (i64, [vp, i32, vp, i64, i32]),
         "pop_debug_indices": (C.c_int, [vp, vp]),
@@ -190,6 +192,17 @@ def pop_set_params(ctx, agent, which, data):
     return _check(load_library().pop_set_params(ctx, agent, which, _ptr(data, dev), n, int(dev)), ctx)
 
 
+def pop_copy_agent(ctx, dst, src, with_buffer):
+    return _check(load_library().pop_copy_agent(ctx, dst, src, int(bool(with_buffer))), ctx)
+
+
+def pop_set_hparams(ctx, agent, hp):
+    """hp: a plain dict (see workloads.hparams) or a pop_hparams."""
+    if isinstance(hp, dict):
+        hp = make_hparams([hp])[0]
+    return _check(load_library().pop_set_hparams(ctx, agent, C.byref(hp)), ctx)
+
+
 def pop_set_debug(ctx, on):
     return _check(load_library().pop_set_debug(ctx, int(on)), ctx)
 
@@ -272,6 +285,12 @@ class Population:
         if not _is_device(data):
             data = np.ascontiguousarray(data, dtype=np.float32)
         return pop_set_params(self.ctx, agent, code, data)
+
+    def copy_agent(self, dst, src, with_buffer):
+        return pop_copy_agent(self.ctx, dst, src, with_buffer)
+
+    def set_hparams(self, agent, hp):
+        return pop_set_hparams(self.ctx, agent, hp)
 
     def set_debug(self, on):
         return pop_set_debug(self.ctx, on)

@@ -114,28 +114,26 @@ __device__ inline uint64_t first_layer(const float* Xs, int xld, const float* ne
 }
 
 // Hidden layer in place on `buf`; `tail` is handed to the product (see gemm256).
-template <int MT, bool DEEP, bool THROUGH = false, class Tail>
+template <int MT, bool THROUGH = false, class Tail>
 __device__ inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, LayerPre<MT>& pre,
                                         float* Yg, int wave, int lane, Tail tail) {
   Acc<MT> acc;
   acc.zero();
   const float bb[2] = {pre.b2[0], pre.b2[1]};
-  if (DEEP) gemm256<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
-  else gemm256_lean<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc);
+  gemm256<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
   __syncthreads();                                   // every wavefront has read the input tile
   return relu_store<MT, THROUGH>(acc, bb, buf, Yg, wave, lane);
 }
 
 // dX = (dZ W^T) * mask written to global [rows][256]; column sums of the result
 // (over this workgroup's rows) go to colsum_out[256].
-template <int MT, bool DEEP, bool THROUGH = false>
+template <int MT, bool THROUGH = false>
 __device__ inline void input_grad_to_global(const float* Zl, const float* W, WeightBlock<MT, true>& w0, uint64_t mask,
                                             float* __restrict__ dXg, float* __restrict__ colsum_out, int wave,
                                             int lane) {
   Acc<MT> acc;
   acc.zero();
-  if (DEEP) gemm256<MT, true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
-  else { w0.load(W, 0, wave, lane); gemm256_lean<MT, true>(Zl, kLda, W, w0, wave, lane, acc); }
+  gemm256<MT, true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
   float cs[2] = {0.0f, 0.0f};
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -170,29 +168,23 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
                                                 const Pre& pre, float* Yl, float* Yg, int wave, int lane) {
     return pop::first_layer<MT, THROUGH>(Xs, xld, net, L, pre, Yl, Yg, wave, lane);
   }
-  template <bool DEEP, bool THROUGH, class Tail>
+  template <bool THROUGH, class Tail>
   __device__ static inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, Pre& pre, float* Yg,
                                                  int wave, int lane, Tail tail) {
-    return pop::hidden_layer<MT, DEEP, THROUGH>(buf, net, L, pre, Yg, wave, lane, tail);
+    return pop::hidden_layer<MT, THROUGH>(buf, net, L, pre, Yg, wave, lane, tail);
   }
-  template <bool DEEP, bool THROUGH>
+  template <bool THROUGH>
   __device__ static inline void input_grad_to_global(const float* Zl, const float* W, WtBlock& w0, uint64_t mask,
                                                      float* dXg, float* colsum_out, int wave, int lane) {
-    pop::input_grad_to_global<MT, DEEP, THROUGH>(Zl, W, w0, mask, dXg, colsum_out, wave, lane);
+    pop::input_grad_to_global<MT, THROUGH>(Zl, W, w0, mask, dXg, colsum_out, wave, lane);
   }
   // buf <- (buf W^T) * mask in place; tail() as in gemm256
-  template <bool DEEP, class Tail>
+  template <class Tail>
   __device__ static inline void input_grad_to_lds(float* buf, const float* W, WtBlock& wt, uint64_t mask, int wave,
                                                   int lane, Tail tail) {
     Acc<MT> acc;
     acc.zero();
-    if (DEEP) {
-      gemm256<MT, true>(buf, kLda, W, wt, wave, lane, acc, tail);
-    } else {
-      wt.load(W, 0, wave, lane);
-      gemm256_lean<MT, true>(buf, kLda, W, wt, wave, lane, acc);
-      tail();
-    }
+    gemm256<MT, true>(buf, kLda, W, wt, wave, lane, acc, tail);
     __syncthreads();                                 // every wavefront is done reading the operand
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -231,7 +223,7 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
     gemm_xw_small16(Xs, xld, L.in, net + L.w1, pre.w1, wave, lane, acc);
     return relu_store16<THROUGH>(acc, pre.b1, Yl, Yg, wave, lane);
   }
-  template <bool DEEP, bool THROUGH, class Tail>
+  template <bool THROUGH, class Tail>
   __device__ static inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, Pre& pre, float* Yg,
                                                  int wave, int lane, Tail tail) {
     Acc16 acc;
@@ -241,7 +233,7 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
     __syncthreads();                                 // every wavefront has read the input tile
     return relu_store16<THROUGH>(acc, bb, buf, Yg, wave, lane);
   }
-  template <bool DEEP, bool THROUGH>
+  template <bool THROUGH>
   __device__ static inline void input_grad_to_global(const float* Zl, const float* W, WtBlock& w0, uint64_t mask,
                                                      float* __restrict__ dXg, float* __restrict__ colsum_out, int wave,
                                                      int lane) {
@@ -265,7 +257,7 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
       if (lane < 16) put<THROUGH>(colsum_out + 64 * wave + 4 * c + nt, tot);
     }
   }
-  template <bool DEEP, class Tail>
+  template <class Tail>
   __device__ static inline void input_grad_to_lds(float* buf, const float* W, WtBlock& wt, uint64_t mask, int wave,
                                                   int lane, Tail tail) {
     Acc16 acc;
@@ -353,7 +345,7 @@ __device__ inline void wait_count(const PopDev& d, const uint32_t* count, uint32
 // Target chain.  One workgroup per (agent, chunk).
 //   a~ = clip(pi'(s') + clip(sigma eps, -c, c), -1, 1), eps = normal e = b A + j of stream 1
 //   y  = r + gamma (1 - d) min(Q1'(s', a~), Q2'(s', a~))
-template <class G, bool DEEP>
+template <class G>
 __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int agent, int chunk, float* lds) {
   constexpr int R = G::R;
   const LdsMap<G::R, G::kPad> L(d.D);
@@ -388,7 +380,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   G::template first_layer<false>(Xs, L.xld, ta, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
   POP_MARK(32);
-  G::template hidden_layer<DEEP, false>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
+  G::template hidden_layer<false>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
   POP_MARK(33);
   G::thin(buf, v_aw3, d.A, head, tid);
@@ -413,11 +405,10 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const float* tc = k == 0 ? tc0 : tc1;
-    if (!DEEP) pre.load(tc, d.critic, wave, lane);    // lean variant: fetch right before use
     G::template first_layer<false>(Xs, L.xld, tc, d.critic, pre, buf, nullptr, wave, lane);
     __syncthreads();
     POP_MARK(36 + 4 * k);
-    G::template hidden_layer<DEEP, false>(buf, tc, d.critic, pre, nullptr, wave, lane,
+    G::template hidden_layer<false>(buf, tc, d.critic, pre, nullptr, wave, lane,
                            [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
     __syncthreads();
     POP_MARK(37 + 4 * k);
@@ -450,7 +441,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
 // WAIT: the targets come from target workgroups of the same launch; the lanes that need
 // them poll for their rows right before the loss.  SIGNAL: count this chunk as finished
 // for the weight-gradient workgroups of the same launch.
-template <class G, bool DEEP, bool WAIT, bool SIGNAL>
+template <class G, bool WAIT, bool SIGNAL>
 __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int net, int chunk, float* lds) {
   constexpr int R = G::R;
   const LdsMap<G::R, G::kPad> L(d.D);
@@ -482,7 +473,7 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
   __syncthreads();
   POP_MARK(2);
   typename G::WtBlock wt;                          // block 0 of W2 for the input-gradient product
-  G::template hidden_layer<DEEP, false>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { G::load_wt(wt, cn + d.critic.w2, wave, lane); });
+  G::template hidden_layer<false>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { G::load_wt(wt, cn + d.critic.w2, wave, lane); });
   __syncthreads();
   POP_MARK(3);
   G::thin(buf, v_w3, 1, head, tid);
@@ -526,7 +517,7 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
   POP_MARK(5);
   __syncthreads();
   POP_MARK(6);
-  G::template input_grad_to_global<DEEP, SIGNAL>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
+  G::template input_grad_to_global<SIGNAL>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
   POP_MARK(7);
   if (SIGNAL) signal_count(d.done_c + parity_base(d, t, 2 * d.P) + net, tid);
 }
@@ -545,7 +536,7 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
 // pass goes ahead, everything that reads critic 1 waits until all of its weight-gradient
 // workgroups are done.  SIGNAL: count this chunk as finished for the actor's weight-gradient
 // workgroups.
-template <class G, bool DEEP, bool WAIT>
+template <class G, bool WAIT>
 __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int agent, int chunk, float* lds, int critic_roles) {
   constexpr int R = G::R;
   const LdsMap<G::R, G::kPad> L(d.D);
@@ -585,7 +576,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
 
   const uint64_t mask_a1 = G::template first_layer<WAIT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
   __syncthreads();
-  G::template hidden_layer<DEEP, false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
+  G::template hidden_layer<false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
                          [&]() { if (!WAIT) pre.load(cn, d.critic, wave, lane); });
   __syncthreads();
   G::thin(buf, v_aw3, A, head, tid);
@@ -606,14 +597,12 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
     stage_critic();
     pre.load(cn, d.critic, wave, lane);
     __syncthreads();
-  } else if (!DEEP) {
-    pre.load(cn, d.critic, wave, lane);
   }
   POP_MARK(10);
   const uint64_t mask_c1 = G::template first_layer<false>(Xs, L.xld, cn, d.critic, pre, buf, nullptr, wave, lane);
   __syncthreads();
   typename G::WtBlock wt;
-  G::template hidden_layer<DEEP, false>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { G::load_wt(wt, cn + d.critic.w2, wave, lane); });
+  G::template hidden_layer<false>(buf, cn, d.critic, pre, nullptr, wave, lane, [&]() { G::load_wt(wt, cn + d.critic.w2, wave, lane); });
   __syncthreads();
   POP_MARK(11);
   G::thin(buf, v_cw3, 1, head, tid);     // q, for the loss value only
@@ -639,7 +628,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   f32x4 h2r[R / 4];                                  // this thread's share of the parked h2 tile
   {
     const float* h2g = d.aH2 + act_off;
-    G::template input_grad_to_lds<DEEP>(buf, cn + d.critic.w2, wt, mask_c1, wave, lane, [&]() {
+    G::input_grad_to_lds(buf, cn + d.critic.w2, wt, mask_c1, wave, lane, [&]() {
 #pragma unroll
       for (int i = 0; i < R / 4; ++i)
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
@@ -648,7 +637,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   __syncthreads();
   POP_MARK(12);
   G::thin(buf, v_cwa, A, head, tid);      // da
-  if (DEEP) G::load_wt(wt, an + d.actor.w2, wave, lane); // block 0 of the actor's input-gradient product
+  G::load_wt(wt, an + d.actor.w2, wave, lane);       // block 0 of the actor's input-gradient product
   __syncthreads();
   for (int e = tid; e < R * kMaxAct; e += kThreads) {
     const int j = e % kMaxAct;
@@ -703,7 +692,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   }
   __syncthreads();
   POP_MARK(13);
-  G::template input_grad_to_global<DEEP, WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  G::template input_grad_to_global<WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
   POP_MARK(14);
   if (WAIT) signal_count(d.done_a + parity_base(d, t, d.P) + agent, tid);
 }

@@ -10,14 +10,14 @@ template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_target(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
-  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) target_chain<G, true>(d, t, agent, chunk, lds);
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) target_chain<G>(d, t, agent, chunk, lds);
 }
 
 template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_critic(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int net, chunk;
-  if (decode_block(blockIdx.x, 2 * d.P, d.B / G::R, net, chunk)) critic_chain<G, true, false, false>(d, t, net, chunk, lds);
+  if (decode_block(blockIdx.x, 2 * d.P, d.B / G::R, net, chunk)) critic_chain<G, false, false>(d, t, net, chunk, lds);
 }
 
 // Target and critic chains of one step in a single launch.  The critic's forward pass does
@@ -31,9 +31,9 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_
   extern __shared__ float lds[];
   int unit, chunk;
   if ((int)blockIdx.x < target_blocks) {
-    if (decode_block(blockIdx.x, d.P, d.B / GT::R, unit, chunk)) target_chain<GT, true>(d, t, unit, chunk, lds);
+    if (decode_block(blockIdx.x, d.P, d.B / GT::R, unit, chunk)) target_chain<GT>(d, t, unit, chunk, lds);
   } else if (decode_block(blockIdx.x - target_blocks, 2 * d.P, d.B / GC::R, unit, chunk)) {
-    critic_chain<GC, true, true, false>(d, t, unit, chunk, lds);
+    critic_chain<GC, true, false>(d, t, unit, chunk, lds);
   }
 }
 
@@ -41,7 +41,7 @@ template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_actor(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
-  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, true, false>(d, t, agent, chunk, lds, 0);
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, false>(d, t, agent, chunk, lds, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
   __syncthreads();
   first_layer<1>(Xs, L.xld, an, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
-  hidden_layer<1, true>(buf, an, d.actor, pre, nullptr, wave, lane, NoTail());
+  hidden_layer<1>(buf, an, d.actor, pre, nullptr, wave, lane, NoTail());
   __syncthreads();
   thin_dot<R>(buf, v_aw3, d.A, head, tid);
   __syncthreads();

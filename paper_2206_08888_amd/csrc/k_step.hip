@@ -42,13 +42,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
   }
   int unit, sub;
   if (b < g.t) {
-    if (decode_block(b, d.P, d.B / GT::R, unit, sub)) target_chain<GT, true>(d, t, unit, sub, lds);
+    if (decode_block(b, d.P, d.B / GT::R, unit, sub)) target_chain<GT>(d, t, unit, sub, lds);
     POP_BLOCK_TIME(1);
     return;
   }
   b -= g.t;
   if (b < g.c) {
-    if (decode_block(b, 2 * d.P, d.B / GC::R, unit, sub)) critic_chain<GC, true, true, true>(d, t, unit, sub, lds);
+    if (decode_block(b, 2 * d.P, d.B / GC::R, unit, sub)) critic_chain<GC, true, true>(d, t, unit, sub, lds);
     POP_BLOCK_TIME(1);
     return;
   }
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
   }
   b -= g.wc;
   if (b < g.a) {
-    if (decode_block(b, d.P, d.B / GA::R, unit, sub)) actor_chain<GA, true, true>(d, t, unit, sub, lds, g.roles_c);
+    if (decode_block(b, d.P, d.B / GA::R, unit, sub)) actor_chain<GA, true>(d, t, unit, sub, lds, g.roles_c);
     POP_BLOCK_TIME(1);
     return;
   }

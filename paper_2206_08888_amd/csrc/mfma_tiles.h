@@ -282,36 +282,6 @@ __device__ inline void gemm256_unrolled(const float* __restrict__ Xl, int ldx, c
   }
 }
 
-// The same product with two weight buffers only (block j+1 requested before block j's
-// MFMAs): a third fewer live registers, for launches with several workgroups per CU,
-// where other workgroups' MFMAs cover the exposed latency instead of deep prefetching.
-template <int MT, bool TRANSPOSED>
-__device__ inline void gemm256_lean(const float* __restrict__ Xl, int ldx, const float* __restrict__ W,
-                                    WeightBlock<MT, TRANSPOSED>& b0, int wave, int lane, Acc<MT>& acc) {
-  WeightBlock<MT, TRANSPOSED> b1;
-  LdsBlock<MT> x0, x1;
-  x0.load(Xl, ldx, 0, lane);
-#pragma unroll 1
-  for (int i = 0; i < 14; i += 2) {
-    b1.load(W, i + 1, wave, lane);
-    x1.load(Xl, ldx, 16 * (i + 1), lane);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_block<MT, TRANSPOSED>(x0, b0, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    b0.load(W, i + 2, wave, lane);
-    x0.load(Xl, ldx, 16 * (i + 2), lane);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_block<MT, TRANSPOSED>(x1, b1, acc);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  b1.load(W, 15, wave, lane);
-  x1.load(Xl, ldx, 16 * 15, lane);
-  __builtin_amdgcn_sched_barrier(0);
-  mfma_block<MT, TRANSPOSED>(x0, b0, acc);
-  __builtin_amdgcn_sched_barrier(0);
-  mfma_block<MT, TRANSPOSED>(x1, b1, acc);
-}
-
 // ReLU epilogue of a hidden layer: Y = max(acc + b, 0) goes to LDS (row stride
 // kLda) and, when Yg != nullptr, to global memory as [rows][256].  Returns the
 // activation pattern of this lane's elements (bb = the two bias values of

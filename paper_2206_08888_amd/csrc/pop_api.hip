@@ -183,6 +183,28 @@ int64_t pop_net_size(const pop_config* cfg, int32_t which) {
   return which % 3 == 0 ? d.actor.size : d.critic.size;
 }
 
+namespace {
+int check_hparams(pop_ctx* ctx, const pop_hparams& h, int i) {
+  if (h.policy_delay < 1) return fail(ctx, POP_EINVAL, "agent %d: policy_delay must be >= 1", i);
+  if (!(h.adam_b1 >= 0.f && h.adam_b1 < 1.f && h.adam_b2 >= 0.f && h.adam_b2 < 1.f && h.adam_eps > 0.f))
+    return fail(ctx, POP_EINVAL, "agent %d: Adam constants out of range", i);
+  if (!(h.noise_clip >= 0.f) || !(h.policy_noise >= 0.f) || !(h.tau >= 0.f && h.tau <= 1.f))
+    return fail(ctx, POP_EINVAL, "agent %d: noise or tau out of range", i);
+  return POP_OK;
+}
+
+// device copy of one agent's hyperparameters; actor_base / t_base are left to the caller
+void to_device_hp(const pop_hparams& h, HpDev& g) {
+  g.seed_lo = (uint32_t)h.seed; g.seed_hi = (uint32_t)(h.seed >> 32);
+  g.lr_actor = h.lr_actor; g.lr_critic = h.lr_critic; g.gamma = h.gamma; g.tau = h.tau;
+  g.policy_noise = h.policy_noise; g.noise_clip = h.noise_clip; g.policy_delay = h.policy_delay;
+  g.b1 = h.adam_b1; g.b2 = h.adam_b2; g.eps = h.adam_eps;
+}
+
+// actor updates of agent a taken in steps [0, t_now): those before t_base plus the multiples of its delay since
+uint32_t actor_updates_before(const pop_ctx* ctx, int a, uint64_t t_now);
+}  // namespace
+
 int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint64_t seed, void* workspace,
                int64_t workspace_bytes, void* hip_stream) {
   if (!out) return fail(nullptr, POP_EINVAL, "out is NULL");
@@ -192,14 +214,8 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   if (!hp) return fail(nullptr, POP_EINVAL, "hp is NULL");
   if (!workspace) return fail(nullptr, POP_EINVAL, "workspace is NULL");
   if (((uintptr_t)workspace % kAlign) != 0) return fail(nullptr, POP_EINVAL, "workspace must be 256-byte aligned");
-  for (int i = 0; i < cfg->P; ++i) {
-    const pop_hparams& h = hp[i];
-    if (h.policy_delay < 1) return fail(nullptr, POP_EINVAL, "agent %d: policy_delay must be >= 1", i);
-    if (!(h.adam_b1 >= 0.f && h.adam_b1 < 1.f && h.adam_b2 >= 0.f && h.adam_b2 < 1.f && h.adam_eps > 0.f))
-      return fail(nullptr, POP_EINVAL, "agent %d: Adam constants out of range", i);
-    if (!(h.noise_clip >= 0.f) || !(h.policy_noise >= 0.f) || !(h.tau >= 0.f && h.tau <= 1.f))
-      return fail(nullptr, POP_EINVAL, "agent %d: noise or tau out of range", i);
-  }
+  for (int i = 0; i < cfg->P; ++i)
+    if ((rc = check_hparams(nullptr, hp[i], i)) != POP_OK) return rc;
   PopDev d;
   fill_dims(*cfg, d);
   const Layout L = make_ws_layout(d);
@@ -232,11 +248,8 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
     pop_hparams& h = ctx->hp[i];
     if (h.seed == 0) h.seed = mix64(seed, (uint64_t)i);
     HpDev& g = ctx->hp_dev[i];
-    std::memset(&g, 0, sizeof g);
-    g.seed_lo = (uint32_t)h.seed; g.seed_hi = (uint32_t)(h.seed >> 32);
-    g.lr_actor = h.lr_actor; g.lr_critic = h.lr_critic; g.gamma = h.gamma; g.tau = h.tau;
-    g.policy_noise = h.policy_noise; g.noise_clip = h.noise_clip; g.policy_delay = h.policy_delay;
-    g.b1 = h.adam_b1; g.b2 = h.adam_b2; g.eps = h.adam_eps;
+    std::memset(&g, 0, sizeof g);                    // actor_base = t_base = 0
+    to_device_hp(h, g);
   }
   char* w = ctx->ws;
   d.theta = (float*)(w + L.theta); d.target = (float*)(w + L.target); d.m = (float*)(w + L.m);
@@ -559,6 +572,62 @@ int64_t pop_step_count(const pop_ctx* ctx) { return ctx ? (int64_t)ctx->t : POP_
 int64_t pop_buffer_count(const pop_ctx* ctx, int32_t agent) {
   if (!ctx || agent < 0 || agent >= ctx->d.P) return POP_EINVAL;
   return (int64_t)ctx->count[agent];
+}
+
+namespace {
+uint32_t actor_updates_before(const pop_ctx* ctx, int a, uint64_t t_now) {
+  const HpDev& g = ctx->hp_dev[a];
+  const uint64_t d = (uint64_t)g.policy_delay, lo = g.t_base;
+  if (t_now <= lo) return g.actor_base;
+  const uint64_t hi = t_now - 1;                     // multiples of d in [lo, hi]
+  return g.actor_base + (uint32_t)(hi / d - (lo + d - 1) / d + 1);
+}
+}  // namespace
+
+int pop_set_hparams(pop_ctx* ctx, int32_t agent, const pop_hparams* hp) {
+  if (!ctx) return POP_EINVAL;
+  if (!hp) return fail(ctx, POP_EINVAL, "hp is NULL");
+  if (agent < 0 || agent >= ctx->d.P) return fail(ctx, POP_EINVAL, "agent %d out of range", agent);
+  const int rc = check_hparams(ctx, *hp, agent);
+  if (rc != POP_OK) return rc;
+  if (hp->seed == 0) return fail(ctx, POP_EINVAL, "seed 0 (derive from the population seed) is only meaningful at pop_create");
+  HpDev& g = ctx->hp_dev[agent];
+  g.actor_base = actor_updates_before(ctx, agent, ctx->t);   // under the old delay, up to now
+  g.t_base = (uint32_t)ctx->t;
+  ctx->hp[agent] = *hp;
+  to_device_hp(*hp, g);
+  // hp_dev lives as long as the context and is only changed here, after a synchronisation
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.hp + sizeof(HpDev) * agent, &g, sizeof(HpDev), hipMemcpyHostToDevice, ctx->stream));
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  return POP_OK;
+}
+
+int pop_copy_agent(pop_ctx* ctx, int32_t dst, int32_t src, int32_t with_buffer) {
+  if (!ctx) return POP_EINVAL;
+  const PopDev& d = ctx->d;
+  if (dst < 0 || dst >= d.P || src < 0 || src >= d.P) return fail(ctx, POP_EINVAL, "agent out of range (dst %d, src %d)", dst, src);
+  if (dst == src) return POP_OK;
+  hipStream_t s = ctx->stream;
+  const size_t state = (size_t)d.agent_sz * sizeof(float);
+  for (float* region : {d.theta, d.target, d.m, d.v})
+    HIP_TRY(ctx, hipMemcpyAsync(region + (size_t)dst * d.agent_sz, region + (size_t)src * d.agent_sz, state, hipMemcpyDeviceToDevice, s));
+  if (with_buffer) {
+    const size_t rows = (size_t)d.capacity * d.row;
+    HIP_TRY(ctx, hipMemcpyAsync(d.replay + (size_t)dst * rows, d.replay + (size_t)src * rows, rows * sizeof(float), hipMemcpyDeviceToDevice, s));
+    HIP_TRY(ctx, hipMemcpyAsync(d.count + dst, d.count + src, sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
+    HIP_TRY(ctx, hipMemcpyAsync(d.cursor + dst, d.cursor + src, sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
+    ctx->count[dst] = ctx->count[src];
+    if (ctx->gathered_t == ctx->t) ctx->gathered_t = ~0ull;   // rows already gathered for the next step are stale for dst
+  }
+  // the Adam state came along, so the count of actor updates does too; dst keeps its own delay from here on
+  HpDev& g = ctx->hp_dev[dst];
+  g.actor_base = actor_updates_before(ctx, src, ctx->t);
+  g.t_base = (uint32_t)ctx->t;
+  HIP_TRY(ctx, hipStreamSynchronize(s));
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.hp + sizeof(HpDev) * dst, &g, sizeof(HpDev), hipMemcpyHostToDevice, s));
+  HIP_TRY(ctx, hipStreamSynchronize(s));
+  return POP_OK;
 }
 
 int pop_sync(pop_ctx* ctx) {

@@ -35,7 +35,10 @@ struct HpDev {                 // per-agent hyperparameters as the kernels read 
   float lr_actor, lr_critic, gamma, tau, policy_noise, noise_clip;
   int32_t policy_delay;
   float b1, b2, eps;
-  float pad_[4];
+  // Adam step count of the actor: actor_base updates were taken before step t_base; since then one at every
+  // step that is a multiple of policy_delay (both change only when the host resets hyperparameters or copies an agent)
+  uint32_t actor_base, t_base;
+  float pad_[2];
 };
 static_assert(sizeof(HpDev) == 64, "HpDev layout");
 

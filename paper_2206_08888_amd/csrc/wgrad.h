@@ -168,7 +168,9 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
   auto setup = [&]() {
     if (tid != 0) return;                            // read by everyone after the next barrier
     Adam a;
-    const uint32_t count = actor_phase ? t / delay + 1u : t + 1u;   // 1-based Adam step
+    // 1-based Adam step: critics count every step; the actor its own updates, i.e. the multiples of
+    // its delay in [t_base, t] on top of those taken before t_base (t is one of them here)
+    const uint32_t count = actor_phase ? hp.actor_base + (t / delay - (hp.t_base + delay - 1u) / delay + 1u) : t + 1u;
     a.lr = actor_phase ? hp.lr_actor : hp.lr_critic;
     a.b1 = hp.b1; a.b2 = hp.b2; a.eps = hp.eps;
     a.inv_c1 = (float)(1.0 / (1.0 - ipow((double)hp.b1, count)));

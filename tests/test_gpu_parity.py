@@ -10,7 +10,8 @@ import pytest
 
 import paper_2206_08888_amd as pp
 import workloads
-from gpu_common import NETS, ForcedStepStats, ensure_built, force_state, forced_step_errors, make_pair, rel_l2
+from gpu_common import (MOM_M, MOM_V, NETS, STATE12, ForcedStepStats, ensure_built, force_state, forced_step_errors,
+                        make_pair, rel_l2)
 
 pytestmark = pytest.mark.gpu
 
@@ -274,3 +275,46 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
     for other in states[1:]:
         for key in states[0]:
             assert np.array_equal(states[0][key], other[key]), key
+
+
+def test_copy_agent_and_set_hparams_follow_the_oracle():
+    """The population step of App. B.1 on both sides: train, replace agent 0 by a copy of
+    agent 2 (with its buffer) and agent 1 by a copy of agent 3 (keeping its own buffer), give
+    the copies new hyperparameters (learning rates, discount, noise, a different policy
+    delay), train on.  Parameters, targets and moments are compared after the copy (bit for
+    bit against the parent on the GPU), one step later (1e-4) and a few steps later."""
+    P = 4
+    hps = workloads.hparams(2, P)
+    gpu, orc, _ = make_pair(2, P=P, capacity=3000, hps=hps)
+    for side in (gpu, orc):
+        side.update(5)
+        side.copy_agent(0, 2, True)
+        side.copy_agent(1, 3, False)
+    for w in STATE12:
+        assert np.array_equal(gpu.get_params(0, w), gpu.get_params(2, w)), w
+        assert np.array_equal(gpu.get_params(1, w), gpu.get_params(3, w)), w
+    assert gpu.buffer_count(0) == gpu.buffer_count(2) == 3000
+    new0 = dict(hps[0], lr_actor=1e-3, lr_critic=2e-4, gamma=0.95, policy_noise=0.4, noise_clip=0.3, policy_delay=3)
+    new1 = dict(hps[1], lr_actor=5e-5, lr_critic=1e-3, tau=0.01, policy_delay=1, seed=987654321)
+    for side in (gpu, orc):
+        side.set_hparams(0, new0)
+        side.set_hparams(1, new1)
+    force_state(gpu, orc, [(i, i) for i in range(P)])          # remove the drift of the first 5 steps
+    gpu.update(1); orc.update(1)                               # t = 5: actor step only for agent 1 (delay 1)
+    _compare_state(gpu, orc, range(P), 1e-4, "first step after copy + new hyperparameters")
+    for w in MOM_M + MOM_V:
+        for i in range(P):
+            assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 1e-3, (i, w)
+    force_state(gpu, orc, [(i, i) for i in range(P)])
+    gpu.update(1); orc.update(1)                               # t = 6: actor step for agents 0 (delay 3), 1, 2, 3
+    _compare_state(gpu, orc, range(P), 1e-4, "second step (actor step under the new delay; Adam count continues)")
+    assert orc.agents[0].actor_updates == 4 and orc.agents[1].actor_updates == 5
+    gpu.update(6); orc.update(6)
+    _compare_state(gpu, orc, range(P), 1e-3, "six more free steps")
+    with pytest.raises(pp.PopError):
+        gpu.copy_agent(0, P, True)
+    with pytest.raises(pp.PopError):
+        gpu.set_hparams(0, dict(new0, policy_delay=0))
+    with pytest.raises(pp.PopError):
+        gpu.set_hparams(0, dict(new0, seed=0))
+    gpu.close()

@@ -134,8 +134,15 @@ class Agent:
             self.last.update(actor_grads=a_grads, actor_loss=a_loss)
         self.t = t + 1
 
-    def act(self, obs):
-        y, _ = mlp.forward(self.actor, np.asarray(obs, dtype=np.float64), 'tanh')
+    def act(self, obs, sigma=0.0, step=0):
+        """Actions of the online actor; sigma > 0: with Gaussian exploration noise,
+        a = clip(pi(obs) + sigma * eps, -1, 1), eps = unit normal number r*A + j of the
+        agent's exploration stream at counter `step` (r = row of obs)."""
+        obs = np.asarray(obs, dtype=np.float64)
+        y, _ = mlp.forward(self.actor, obs, 'tanh')
+        if sigma > 0.0:
+            eps = philox.normals(self.seed, obs.shape[0] * self.A, step, philox.STREAM_EXPLORE)
+            y = np.clip(y + float(np.float32(sigma)) * eps.reshape(obs.shape[0], self.A), -1.0, 1.0)
         return y
 
 
@@ -164,8 +171,9 @@ class Population:
             for _ in range(n_steps):
                 ag.step()
 
-    def act(self, obs):
-        return np.stack([ag.act(obs[i]) for i, ag in enumerate(self.agents)])
+    def act(self, obs, sigma=None, step=0):
+        return np.stack([ag.act(obs[i], 0.0 if sigma is None else sigma[i], step)
+                         for i, ag in enumerate(self.agents)])
 
     def copy_agent(self, dst, src, with_buffer):
         """Agent dst becomes a copy of agent src: online and target networks, Adam moments

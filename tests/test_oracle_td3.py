@@ -279,3 +279,28 @@ def test_new_hparams_act_from_the_next_step_and_keep_the_adam_counts_continuous(
     m1, v1 = b1 * m0 + (1 - b1) * g, b2 * v0 + (1 - b2) * g * g
     want = a_before - lr * (m1 / (1 - b1 ** 3)) / (np.sqrt(v1 / (1 - b2 ** 3)) + eps)
     np.testing.assert_allclose(pop.get_params(0, "actor"), want, rtol=1e-12, atol=1e-15)
+
+
+# ---- acting with exploration noise -------------------------------------------------------
+def test_exploration_noise_hand_cases():
+    ag = _agent()
+    obs = np.random.default_rng(3).standard_normal((4000, 3))
+    mu = ag.act(obs)
+    assert np.array_equal(ag.act(obs, sigma=0.0, step=7), mu)                  # no noise asked for
+    a = ag.act(obs, sigma=0.05, step=7)
+    assert np.all(np.abs(a) <= 1.0)
+    inner = np.abs(mu) < 0.5                                                   # far from the clip: a - mu is the noise itself
+    z = (a - mu)[inner] / np.float32(0.05)
+    assert abs(z.mean()) < 0.05 and abs(z.std() - 1.0) < 0.03                  # unit normals scaled by sigma
+    assert abs(np.mean(z ** 3)) < 0.15 and abs(np.mean(z ** 4) - 3.0) < 0.3    # symmetric, Gaussian kurtosis
+    assert np.array_equal(ag.act(obs, sigma=0.05, step=7), a)                  # a function of (seed, step, row, column)
+    assert not np.array_equal(ag.act(obs, sigma=0.05, step=8), a)
+    assert np.array_equal(ag.act(obs[:100], sigma=0.05, step=7), a[:100])      # row r always gets the same numbers
+    big = ag.act(obs, sigma=50.0, step=1)                                      # saturating noise ends on the bounds
+    assert np.mean(np.abs(big) == 1.0) > 0.95
+    other = _agent(hp=dict(HP, seed=12))
+    other.actor = ag.actor
+    assert not np.array_equal(other.act(obs, sigma=0.05, step=7), a)           # keyed by the agent's seed
+    # independent of the smoothing-noise stream of the update step
+    smooth = philox.normals(ag.seed, 4000 * 2, 7, philox.STREAM_SMOOTH).reshape(4000, 2)
+    assert abs(np.corrcoef(smooth[inner[:, 0], 0], ((a - mu)[:, 0])[inner[:, 0]])[0, 1]) < 0.06

@@ -180,6 +180,17 @@ int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launche
 int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
             int32_t ptrs_on_device);
 
+/* The same with Gaussian exploration noise, as the data-collecting actors of
+ * a TD3 agent use it: a = clip(pi(obs) + sigma[i] * eps, -1, 1) for agent i,
+ * sigma = host array of P non-negative values (0: no noise for that agent).
+ * eps is unit normal number r * act_dim + j (r = row of the agent's slice, j =
+ * action component) of the agent's exploration stream at counter `step`, so a
+ * call is reproducible and independent of how it is split into pieces; callers
+ * pass a fresh `step` per call (e.g. their environment-step counter).
+ * Synchronises the stream (sigma is staged on the device). */
+int pop_act_explore(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
+                    int32_t ptrs_on_device, const float* sigma, uint32_t step);
+
 /* Copy one tensor of one agent (see the POP_* codes) into out[out_len];
  * out_len must be at least the tensor's length, else POP_EINVAL and nothing
  * is written.  Returns the number of floats written (>= 0) or an error. */

@@ -71,6 +71,7 @@ def load_library():
         "pop_update": (C.c_int, [vp, i32]),
         "pop_update_timed": (C.c_int, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "pop_act": (C.c_int, [vp, fp, i32, fp, i32]),
+        "pop_act_explore": (C.c_int, [vp, fp, i32, fp, i32, fp, C.c_uint32]),
         "pop_get_params": (i64, [vp, i32, i32, fp, i64, i32]),
         "pop_set_params": (C.c_int, [vp, i32, i32, fp, i64, i32]),
         "pop_copy_agent": (C.c_int, [vp, i32, i32, i32]),
@@ -180,6 +181,13 @@ def pop_act(ctx, obs, n, act_out):
     return _check(load_library().pop_act(ctx, _ptr(obs, dev), n, _ptr(act_out, dev), int(dev)), ctx)
 
 
+def pop_act_explore(ctx, obs, n, act_out, sigma, step):
+    dev = _is_device(obs)
+    sigma = np.ascontiguousarray(sigma, dtype=np.float32)
+    return _check(load_library().pop_act_explore(ctx, _ptr(obs, dev), n, _ptr(act_out, dev), int(dev),
+                                                 C.c_void_p(sigma.ctypes.data), int(step)), ctx)
+
+
 def pop_get_params(ctx, agent, which, out):
     dev = _is_device(out)
     n = out.numel() if hasattr(out, "numel") else out.size
@@ -264,14 +272,18 @@ class Population:
     def sync(self):
         return pop_sync(self.ctx)
 
-    def act(self, obs):
+    def act(self, obs, sigma=None, step=0):
         import torch
         n = obs.shape[1]
         if _is_device(obs):
             out = torch.empty((self.cfg.P, n, self.cfg.act_dim), dtype=torch.float32, device=obs.device)
         else:
             out = np.empty((self.cfg.P, n, self.cfg.act_dim), dtype=np.float32)
-        pop_act(self.ctx, obs, n, out)
+        if sigma is None:
+            pop_act(self.ctx, obs, n, out)
+        else:
+            assert len(sigma) == self.cfg.P
+            pop_act_explore(self.ctx, obs, n, out, sigma, step)
         return out
 
     def get_params(self, agent, which):

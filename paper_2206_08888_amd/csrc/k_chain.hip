@@ -46,8 +46,12 @@ __global__ __launch_bounds__(kThreads, 1) void k_actor(PopDev d, uint32_t t) {
 
 // ---------------------------------------------------------------------------------------------
 // Acting: act[agent][r] = pi_agent(obs[agent][r]).  grid (ceil(n / 32), P).
+// sigma != nullptr: Gaussian exploration noise, a = clip(pi + sigma[agent] eps, -1, 1) with eps =
+// unit normal number (row_base + r) A + j of the agent's exploration stream at counter `step`
+// (row_base: index of row 0 of this call within the caller's whole request).
 __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restrict__ obs, int n,
-                                                  float* __restrict__ act) {
+                                                  float* __restrict__ act, const float* __restrict__ sigma,
+                                                  uint32_t step, uint32_t row_base) {
   constexpr int R = 32;
   extern __shared__ float lds[];
   const Lds<1> L(d.O);
@@ -72,9 +76,20 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
   __syncthreads();
   thin_dot<R>(buf, v_aw3, d.A, head, tid);
   __syncthreads();
+  const float sg = sigma ? sigma[agent] : 0.0f;
+  const HpDev hp = d.hp[agent];
   for (int e = tid; e < valid * d.A; e += kThreads) {
     const int r = e / d.A, j = e - r * d.A;
-    act[((size_t)agent * n + r0 + r) * d.A + j] = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
+    float a = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
+    if (sg > 0.0f) {
+      const uint32_t el = (row_base + (uint32_t)(r0 + r)) * (uint32_t)d.A + (uint32_t)j;
+      const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, el >> 2, step, kStreamExplore, 0u);
+      float n4[4];
+      normals4(blk, n4);
+      const float nz = (el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0]);
+      a = fminf(fmaxf(a + sg * nz, -1.0f), 1.0f);
+    }
+    act[((size_t)agent * n + r0 + r) * d.A + j] = a;
   }
 }
 
@@ -135,8 +150,10 @@ hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {
   else k_actor<Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   return hipGetLastError();
 }
-hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, hipStream_t s) {
-  k_act<<<dim3((n + 31) / 32, d.P), dim3(kThreads), Lds<1>(d.O).bytes(vec_act(d)), s>>>(d, obs, n, act);
+hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, const float* sigma, uint32_t step,
+                      uint32_t row_base, hipStream_t s) {
+  k_act<<<dim3((n + 31) / 32, d.P), dim3(kThreads), Lds<1>(d.O).bytes(vec_act(d)), s>>>(d, obs, n, act, sigma, step,
+                                                                                        row_base);
   return hipGetLastError();
 }
 

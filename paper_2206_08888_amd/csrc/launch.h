@@ -32,8 +32,10 @@ hipError_t launch_step(const PopDev& d, uint32_t t, uint32_t launch_seq, int wit
 hipError_t setup_step_kernel();
 int wgrad_role_count(const PopDev& d, int actor_phase);
 
-// acting: obs[P][n][O] -> act[P][n][A] through the online actors
-hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, hipStream_t s);
+// acting: obs[P][n][O] -> act[P][n][A] through the online actors; sigma (device, [P]) != nullptr adds
+// exploration noise drawn at counter `step`, rows numbered from row_base
+hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, const float* sigma, uint32_t step,
+                      uint32_t row_base, hipStream_t s);
 
 // one-time per-process kernel attribute setup (large dynamic LDS)
 hipError_t setup_kernels();

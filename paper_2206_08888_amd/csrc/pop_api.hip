@@ -23,7 +23,7 @@ constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
   int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
-  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, fault, staging, replay, total;
+  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, fault, sigma, staging, replay, total;
   int64_t param_bytes;
 };
 
@@ -131,6 +131,7 @@ Layout make_ws_layout(const PopDev& d) {
   L.y_tagged = take(P * B * 8);
   L.done_c = take(4 * P * 4); L.done_wc = take(4 * P * 4); L.done_a = take(2 * P * 4);
   L.fault = take(4);
+  L.sigma = take(P * 4);
   L.staging = take(kStagingBytes);
   L.replay = take(P * (int64_t)d.capacity * d.row * 4);
   L.total = o;
@@ -458,15 +459,17 @@ int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launche
   return rc;
 }
 
-int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t ptrs_on_device) {
-  if (!ctx) return POP_EINVAL;
+namespace {
+int act_impl(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t ptrs_on_device, const float* sigma_dev,
+             uint32_t step) {
   if (n < 0) return fail(ctx, POP_EINVAL, "n is negative");
   if (n == 0) return POP_OK;
   if (!obs || !act_out) return fail(ctx, POP_EINVAL, "NULL array");
   const PopDev& d = ctx->d;
+  if ((int64_t)n * d.A > 0xFFFFFFFFll) return fail(ctx, POP_EINVAL, "n * act_dim exceeds 2^32");
   hipStream_t s = ctx->stream;
   if (ptrs_on_device) {
-    HIP_TRY(ctx, launch_act(d, obs, n, act_out, s));
+    HIP_TRY(ctx, launch_act(d, obs, n, act_out, sigma_dev, step, 0u, s));
     return POP_OK;
   }
   float* st = (float*)(ctx->ws + ctx->lay.staging);
@@ -478,12 +481,32 @@ int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t p
     float* s_act = st + (int64_t)d.P * k * d.O;
     HIP_TRY(ctx, hipMemcpy2DAsync(s_obs, (size_t)k * d.O * 4, obs + off * d.O, (size_t)n * d.O * 4, (size_t)k * d.O * 4,
                                   d.P, hipMemcpyHostToDevice, s));
-    HIP_TRY(ctx, launch_act(d, s_obs, k, s_act, s));
+    HIP_TRY(ctx, launch_act(d, s_obs, k, s_act, sigma_dev, step, (uint32_t)off, s));
     HIP_TRY(ctx, hipMemcpy2DAsync(act_out + off * d.A, (size_t)n * d.A * 4, s_act, (size_t)k * d.A * 4,
                                   (size_t)k * d.A * 4, d.P, hipMemcpyDeviceToHost, s));
     HIP_TRY(ctx, hipStreamSynchronize(s));
   }
   return POP_OK;
+}
+}  // namespace
+
+int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t ptrs_on_device) {
+  if (!ctx) return POP_EINVAL;
+  return act_impl(ctx, obs, n, act_out, ptrs_on_device, nullptr, 0u);
+}
+
+int pop_act_explore(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t ptrs_on_device,
+                    const float* sigma, uint32_t step) {
+  if (!ctx) return POP_EINVAL;
+  if (!sigma) return fail(ctx, POP_EINVAL, "sigma is NULL");
+  for (int a = 0; a < ctx->d.P; ++a)
+    if (!(sigma[a] >= 0.0f)) return fail(ctx, POP_EINVAL, "agent %d: sigma must be >= 0", a);
+  float* sigma_dev = (float*)(ctx->ws + ctx->lay.sigma);
+  // the staged values must not change under an earlier call still in flight
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  HIP_TRY(ctx, hipMemcpyAsync(sigma_dev, sigma, sizeof(float) * ctx->d.P, hipMemcpyHostToDevice, ctx->stream));
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  return act_impl(ctx, obs, n, act_out, ptrs_on_device, sigma_dev, step);
 }
 
 int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, int64_t out_len, int32_t on_device) {

@@ -185,6 +185,30 @@ def test_act_matches_oracle_on_ragged_row_counts():
     gpu.close()
 
 
+def test_act_with_exploration_noise_matches_oracle():
+    """a = clip(pi(obs) + sigma_i eps, -1, 1): the noise numbers are the same words on both
+    sides (element r*A + j of stream 5 at the given counter), so the comparison is
+    elementwise: 2e-6 for the Box-Muller float arithmetic times sigma, plus the actor's 5e-6."""
+    import torch
+    gpu, orc, agents = make_pair(0, capacity=512, fill=512)
+    gpu.update(2); orc.update(2)
+    rng = np.random.default_rng(6)
+    sigma = [0.1, 0.0]                                      # agent 1 acts without noise
+    for n, step in ((1, 0), (33, 5), (700, 123456789)):
+        obs = rng.standard_normal((2, n, 17)).astype(np.float32)
+        ref = orc.act(obs.astype(np.float64), sigma=sigma, step=step)
+        got = gpu.act(obs, sigma=sigma, step=step)
+        assert np.abs(got - ref).max() <= 1e-5, (n, step, np.abs(got - ref).max())
+        assert np.array_equal(got[1], gpu.act(obs)[1])      # sigma 0: exactly the noiseless path
+        assert not np.array_equal(got[0], gpu.act(obs)[0])
+        got_dev = gpu.act(torch.from_numpy(obs).cuda(), sigma=sigma, step=step).cpu().numpy()
+        assert np.array_equal(got, got_dev)                 # device pointers and staged host pieces agree
+        assert np.all(np.abs(got) <= 1.0)
+    with pytest.raises(pp.PopError):
+        gpu.act(obs, sigma=[0.1, -1.0], step=0)
+    gpu.close()
+
+
 def test_errors_from_the_boundary_on_a_live_context():
     gpu, _, _ = make_pair(0, capacity=256, fill=0, oracle=False)
     with pytest.raises(pp.PopError) as e:

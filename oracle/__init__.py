@@ -1,4 +1,4 @@
-"""CPU oracle for the population TD3 update step.
+"""CPU oracle for the population TD3 (td3.py) and SAC (sac.py) update steps.
 
 TEST INFRASTRUCTURE ONLY.  This package is the slow, plain, fp64 definition of
 what the HIP path computes: every agent of the population is stepped on its
@@ -10,12 +10,13 @@ Paper passages followed (Flajolet et al., "Fast Population-Based Reinforcement
 Learning on a Single Machine"):
   * Sec. 4.1 "Training Independent Replicas of the Same Agent": N replicas,
     different initial weights and hyperparameters, updated independently; MLP
-    actor and critics; TD3 with the standard hyperparametrization.
+    actor and critics; TD3 and SAC with the standard hyperparametrization.
   * App. C: a population layer is y[p] = x[p] W[p] + b[p] with W of shape
     [P, in, out] and b of shape [P, 1, out].
   * App. A: one bounded first-in-first-out replay buffer per agent, batches of
     all agents stacked on a new leading axis.
-The paper does not print the TD3 equations (it cites Fujimoto et al. 2018);
+The paper does not print the TD3 or SAC equations (it cites Fujimoto et al. 2018
+and Haarnoja et al. 2018);
 the reading taken for every point it leaves open is listed in the design notes
 of the repository and restated in the docstrings below.
 

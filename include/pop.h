@@ -61,11 +61,13 @@ typedef struct {
   float noise_clip;     /* clip of that noise */
   int32_t policy_delay; /* actor and targets are updated when step % delay == 0 */
   float adam_b1, adam_b2, adam_eps;
-  float lr_alpha, target_entropy, init_log_alpha; /* SAC only; ignored for TD3 */
+  float lr_alpha, target_entropy, init_log_alpha; /* SAC only (learning rate of log alpha, the entropy the
+                           temperature steers to, log alpha at step 0); ignored for TD3.  SAC in turn ignores
+                           policy_noise, noise_clip and policy_delay: it updates everything every step */
   int32_t reserved_;    /* keeps sizeof == 64 */
 } pop_hparams;
 
-/* Population-wide shapes.  Supported now: algo TD3, n_hidden == 2 with
+/* Population-wide shapes.  Supported now: algo TD3 or SAC, n_hidden == 2 with
  * hidden = {256, 256}, obs_dim + act_dim <= 64, act_dim <= 8, batch ==
  * 256 (the batch of every workload of Sec. 4.1), 1 <= capacity < 2^32.  Anything else gives
  * POP_EUNSUPPORTED. */
@@ -89,7 +91,12 @@ enum {
   POP_ADAM_V_ACTOR = 9, POP_ADAM_V_CRITIC1 = 10, POP_ADAM_V_CRITIC2 = 11,
   /* gradients of the last step that updated that network; only recorded
    * while pop_set_debug(ctx, 1) is on */
-  POP_GRAD_ACTOR = 12, POP_GRAD_CRITIC1 = 13, POP_GRAD_CRITIC2 = 14
+  POP_GRAD_ACTOR = 12, POP_GRAD_CRITIC1 = 13, POP_GRAD_CRITIC2 = 14,
+  /* SAC only, one float each: the log of the temperature alpha and its Adam
+   * moments.  (For SAC the POP_T_ACTOR slot exists but is unused: there is no
+   * target actor; the actor network has 2 * act_dim outputs, the means of the
+   * actions followed by their log standard deviations.) */
+  POP_LOG_ALPHA = 15, POP_ADAM_M_LOG_ALPHA = 16, POP_ADAM_V_LOG_ALPHA = 17
 };
 
 /* What pop_debug_get returns (state of the most recent update step). */
@@ -175,8 +182,9 @@ enum {
  * the stream before returning. */
 int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launches);
 
-/* Deterministic actions of every agent's current actor: obs[P, n, obs_dim] ->
- * act_out[P, n, act_dim] (agent i acts on slice i). */
+/* Deterministic actions of every agent's current actor (for SAC: the tanh of
+ * the mean): obs[P, n, obs_dim] -> act_out[P, n, act_dim] (agent i acts on
+ * slice i). */
 int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
             int32_t ptrs_on_device);
 
@@ -187,6 +195,8 @@ int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
  * action component) of the agent's exploration stream at counter `step`, so a
  * call is reproducible and independent of how it is split into pieces; callers
  * pass a fresh `step` per call (e.g. their environment-step counter).
+ * For SAC the policy itself is sampled instead: a = tanh(mu + sigma[i] *
+ * std * eps) with the policy's own std (sigma[i] = 1 is the policy).
  * Synchronises the stream (sigma is staged on the device). */
 int pop_act_explore(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
                     int32_t ptrs_on_device, const float* sigma, uint32_t step);

@@ -16,6 +16,7 @@ PARAM_CODES = {
     "actor": 0, "critic1": 1, "critic2": 2, "t_actor": 3, "t_critic1": 4, "t_critic2": 5,
     "m_actor": 6, "m_critic1": 7, "m_critic2": 8, "v_actor": 9, "v_critic1": 10, "v_critic2": 11,
     "g_actor": 12, "g_critic1": 13, "g_critic2": 14,
+    "log_alpha": 15, "m_log_alpha": 16, "v_log_alpha": 17,        # SAC only, one float each
 }
 DEBUG_CODES = {"indices": 0, "batch": 1, "target_action": 2, "target_y": 3, "losses": 4}
 
@@ -288,7 +289,8 @@ class Population:
 
     def get_params(self, agent, which):
         code = PARAM_CODES[which] if isinstance(which, str) else which
-        out = np.empty(self.actor_size if code % 3 == 0 else self.critic_size, dtype=np.float32)
+        size = 1 if code >= 15 else (self.actor_size if code % 3 == 0 else self.critic_size)
+        out = np.empty(size, dtype=np.float32)
         pop_get_params(self.ctx, agent, code, out)
         return out
 

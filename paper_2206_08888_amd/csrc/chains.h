@@ -37,20 +37,22 @@ static_assert(kMaxAct == 8, "the action-gradient loops read dz3 rows as two 16-b
 
 namespace {
 
-// LDS map (floats): input tile [R][xld] | activation tile [R][kLda] | 3 x [R][8] scratch | vectors.
+// LDS map (floats): input tile [R][xld] | activation tile [R][kLda] | NS x [R][8] scratch | vectors.
 // KPAD: the first-layer product reads the input tile in blocks of KPAD columns.
 template <int R_, int KPAD>
 struct LdsMap {
   static constexpr int R = R_;
   int xld, buf, s0, s1, s2, vec;
-  __host__ __device__ LdsMap(int fan_in) {
+  // NS: number of [R][8] scratch regions (s0, s1, s2, and for the SAC chains six more after them)
+  __host__ __device__ LdsMap(int fan_in, int NS = 3) {
     xld = ((fan_in + KPAD - 1) / KPAD) * KPAD + 4;   // 4 * odd words: conflict-free 16-byte row reads
     buf = R * xld;
     s0 = buf + R * kLda;
     s1 = s0 + R * kMaxAct;
     s2 = s1 + R * kMaxAct;
-    vec = s2 + R * kMaxAct;
+    vec = s0 + NS * R * kMaxAct;
   }
+  __host__ __device__ int s(int i) const { return s0 + i * R * kMaxAct; }
   __host__ size_t bytes(int vec_floats) const { return (size_t)(vec + vec_floats) * sizeof(float); }
 };
 template <int MT>
@@ -198,6 +200,22 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
   __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid) {
     thin_dot<R>(Xl, V, J, outl, tid);
   }
+  // buf[row][col] = mask ? rowvec[row] * colvec[col] : 0  (mask as returned by hidden_layer)
+  __device__ static inline void store_outer_masked(float* buf, uint64_t mask, const float* rowvec, const float* colvec,
+                                                   int wave, int lane) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const int col = 64 * wave + 32 * nt + (lane & 31);
+        const float cv = colvec[col];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 32 * mt + acc_row(v, lane);
+          buf[row * kLda + col] = mask_bit(mask, mt, nt, v) ? rowvec[row] * cv : 0.0f;
+        }
+      }
+  }
 };
 
 struct Rows16 {                                      // 16 rows on v_mfma_f32_16x16x4_f32 (mfma_tiles16.h)
@@ -275,6 +293,20 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
   }
   __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid) {
     thin_dot16(Xl, V, J, outl, tid);
+  }
+  __device__ static inline void store_outer_masked(float* buf, uint64_t mask, const float* rowvec, const float* colvec,
+                                                   int wave, int lane) {
+    const int c = lane & 15, kq = lane >> 4;
+    const f32x4 cv = *reinterpret_cast<const f32x4*>(&colvec[64 * wave + 4 * c]);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int row = 4 * kq + v;
+      const float rv = rowvec[row];
+      f32x4 o;
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) o[nt] = mask_bit16(mask, nt, v) ? rv * cv[nt] : 0.0f;
+      *reinterpret_cast<f32x4*>(&buf[row * kLda + 64 * wave + 4 * c]) = o;
+    }
   }
 };
 
@@ -701,6 +733,6 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
 inline int vec_target(const PopDev& d) { return kH * d.A + 8 + 2 * kH + 8; }
 inline int vec_critic(const PopDev&) { return kH + 8; }
 inline int vec_actor(const PopDev& d) { return kH * d.A + 8 + kH + d.A * kH; }
-inline int vec_act(const PopDev& d) { return kH * d.A + 8; }
+inline int vec_act(const PopDev& d) { return kH * d.actor.out + kMaxHead; }
 
 }  // namespace pop

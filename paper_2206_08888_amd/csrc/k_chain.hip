@@ -58,16 +58,17 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
   float* Xs = lds;
   float* buf = lds + L.buf;
   float* head = lds + L.s0;
+  float* head_ls = lds + L.s1;                       // SAC: log-std head
   float* v_aw3 = lds + L.vec;
-  float* v_ab3 = v_aw3 + kH * d.A;
+  float* v_ab3 = v_aw3 + kH * d.actor.out;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int agent = blockIdx.y, r0 = blockIdx.x * R;
   const int valid = n - r0 < R ? n - r0 : R;
   const float* an = net_ptr(d, d.theta, agent, 0);
   LayerPre<1> pre;
   pre.load(an, d.actor, wave, lane);
-  stage_head(v_aw3, an + d.actor.w3, d.A, tid);
-  stage_vector(v_ab3, an + d.actor.b3, d.A, tid);
+  stage_head(v_aw3, an + d.actor.w3, d.actor.out, tid);      // SAC: 2A outputs, the means come first
+  stage_vector(v_ab3, an + d.actor.b3, d.actor.out, tid);
   load_input<R>(Xs, L.xld, obs + ((size_t)agent * n + r0) * d.O, d.O, 0, d.O, valid, tid);
   __syncthreads();
   first_layer<1>(Xs, L.xld, an, d.actor, pre, buf, nullptr, wave, lane);
@@ -75,19 +76,27 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
   hidden_layer<1>(buf, an, d.actor, pre, nullptr, wave, lane, NoTail());
   __syncthreads();
   thin_dot<R>(buf, v_aw3, d.A, head, tid);
-  __syncthreads();
   const float sg = sigma ? sigma[agent] : 0.0f;
+  const bool sac = d.algo == 1;
+  if (sac && sg > 0.0f) thin_dot<R>(buf, v_aw3 + d.A * kH, d.A, head_ls, tid);
+  __syncthreads();
   const HpDev hp = d.hp[agent];
   for (int e = tid; e < valid * d.A; e += kThreads) {
     const int r = e / d.A, j = e - r * d.A;
-    float a = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
+    const float pre_act = head[r * kMaxAct + j] + v_ab3[j];
+    float a = tanhf(pre_act);
     if (sg > 0.0f) {
       const uint32_t el = (row_base + (uint32_t)(r0 + r)) * (uint32_t)d.A + (uint32_t)j;
       const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, el >> 2, step, kStreamExplore, 0u);
       float n4[4];
       normals4(blk, n4);
       const float nz = (el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0]);
-      a = fminf(fmaxf(a + sg * nz, -1.0f), 1.0f);
+      if (sac) {                                     // a sample of the policy itself, its std scaled by sigma
+        const float ls = fminf(fmaxf(head_ls[r * kMaxAct + j] + v_ab3[d.A + j], -20.0f), 2.0f);
+        a = tanhf(pre_act + sg * expf(ls) * nz);
+      } else {
+        a = fminf(fmaxf(a + sg * nz, -1.0f), 1.0f);
+      }
     }
     act[((size_t)agent * n + r0 + r) * d.A + j] = a;
   }

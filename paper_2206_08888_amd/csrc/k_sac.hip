@@ -1,0 +1,54 @@
+// Kernels around the SAC chains of chains_sac.h (one launch per chain; the critic chain and
+// the weight-gradient tiles are the TD3 ones).
+#include "chains_sac.h"
+
+namespace pop {
+
+template <class G>
+__global__ __launch_bounds__(kThreads, 1) void k_sac_target(PopDev d, uint32_t t) {
+  extern __shared__ float lds[];
+  int agent, chunk;
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) sac_target_chain<G>(d, t, agent, chunk, lds);
+}
+
+template <class G>
+__global__ __launch_bounds__(kThreads, 1) void k_sac_actor(PopDev d, uint32_t t) {
+  extern __shared__ float lds[];
+  int agent, chunk;
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) sac_actor_chain<G>(d, t, agent, chunk, lds);
+}
+
+hipError_t setup_sac_kernels() {
+  hipError_t e;
+  const int most = 160 * 1024;
+#define POP_SET_LDS(...)                                                                                   \
+  if ((e = hipFuncSetAttribute((const void*)__VA_ARGS__, hipFuncAttributeMaxDynamicSharedMemorySize, most)) != hipSuccess) return e
+  POP_SET_LDS(k_sac_target<Rows16>);
+  POP_SET_LDS(k_sac_target<Rows32<1>>);
+  POP_SET_LDS(k_sac_target<Rows32<2>>);
+  POP_SET_LDS(k_sac_actor<Rows16>);
+  POP_SET_LDS(k_sac_actor<Rows32<1>>);
+  POP_SET_LDS(k_sac_actor<Rows32<2>>);
+#undef POP_SET_LDS
+  return hipSuccess;
+}
+
+hipError_t launch_sac_target(const PopDev& d, uint32_t t, hipStream_t s) {
+  const dim3 grid(xcd_grid(d.P, d.B / d.rows_t)), block(kThreads);
+  const int vec = vec_sac_target(d);
+  if (d.rows_t == 16) k_sac_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  else if (d.rows_t == 32) k_sac_target<Rows32<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  else k_sac_target<Rows32<2>><<<grid, block, LdsMap<64, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  return hipGetLastError();
+}
+
+hipError_t launch_sac_actor(const PopDev& d, uint32_t t, hipStream_t s) {
+  const dim3 grid(xcd_grid(d.P, d.B / d.rows_a)), block(kThreads);
+  const int vec = vec_sac_actor(d);
+  if (d.rows_a == 16) k_sac_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  else if (d.rows_a == 32) k_sac_actor<Rows32<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  else k_sac_actor<Rows32<2>><<<grid, block, LdsMap<64, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  return hipGetLastError();
+}
+
+}  // namespace pop

@@ -24,6 +24,12 @@ hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s);
 // prefetch_next != 0: extra workgroups also gather the replay rows of step t + 1
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s);
 
+// SAC: target chain (online actor, soft clipped double-Q target) and actor chain (k_sac.hip); the critic chain
+// and the weight-gradient launches are shared with TD3
+hipError_t launch_sac_target(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t launch_sac_actor(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t setup_sac_kernels();
+
 // the step as one launch (k_step.hip); with_chains = 0: without the target and critic chains (launched
 // before); with_actor: some agent has its delayed actor step at t; launch_seq: 0, 1, 2, ... over the
 // launches of this kernel on this population (alternates the two sets of hand-over counters)

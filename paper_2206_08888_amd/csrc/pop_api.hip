@@ -23,7 +23,7 @@ constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
   int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
-  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, fault, sigma, staging, replay, total;
+  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, fault, sigma, log_alpha, staging, replay, total;
   int64_t param_bytes;
 };
 
@@ -74,7 +74,7 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
   if (c->P < 1 || c->obs_dim < 1 || c->act_dim < 1 || c->batch < 1 || c->capacity < 1 || c->n_hidden < 1 ||
       c->n_hidden > 4)
     return fail(ctx, POP_EINVAL, "config has a non-positive size");
-  if (c->algo != POP_ALGO_TD3) return fail(ctx, POP_EUNSUPPORTED, "only POP_ALGO_TD3 is implemented");
+  if (c->algo != POP_ALGO_TD3 && c->algo != POP_ALGO_SAC) return fail(ctx, POP_EINVAL, "unknown algorithm %d", c->algo);
   if (c->n_hidden != 2 || c->hidden[0] != kH || c->hidden[1] != kH)
     return fail(ctx, POP_EUNSUPPORTED, "hidden layers must be {256, 256}");
   if (c->obs_dim + c->act_dim > kMaxIn) return fail(ctx, POP_EUNSUPPORTED, "obs_dim + act_dim must be <= %d", kMaxIn);
@@ -87,6 +87,7 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
 
 void fill_dims(const pop_config& c, PopDev& d) {
   std::memset(&d, 0, sizeof d);
+  d.algo = c.algo;
   d.P = c.P; d.O = c.obs_dim; d.A = c.act_dim; d.D = c.obs_dim + c.act_dim; d.B = c.batch;
   d.row = 2 * c.obs_dim + c.act_dim + 2;
   // Rows per workgroup of the layer chains.  64 once that still gives every CU two workgroups
@@ -94,7 +95,8 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // populations: those parts have only 8 P workgroups at 32 rows, well under the 256 CUs, and
   // their latency is what a step waits for; 16-row tiles halve the matrix time of every
   // product by spreading it over twice the CUs.  Else 32.
-  const int cls = ((int64_t)c.P * (c.batch / 64) >= 512) ? 2 : ((int64_t)c.P * (c.batch / 16) <= 256 ? 0 : 1);
+  int cls = ((int64_t)c.P * (c.batch / 64) >= 512) ? 2 : ((int64_t)c.P * (c.batch / 16) <= 256 ? 0 : 1);
+  if (c.algo == POP_ALGO_SAC && cls == 2) cls = 1;   // the SAC actor chain (six products) spills at 64 rows
   d.rows_t = d.rows_a = cls == 2 ? 64 : (cls == 0 ? 16 : 32);
   // Beside 16 P target workgroups of 16 rows, 64-row critic chains (8 P workgroups) keep the fused
   // target/critic launch of a small population within one workgroup per CU.
@@ -104,7 +106,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
     if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; }
     if (v == 32 || v == 64) d.rows_t = d.rows_c = d.rows_a = v;
   }
-  d.actor = make_layout(d.O, d.A);
+  d.actor = make_layout(d.O, c.algo == POP_ALGO_SAC ? 2 * d.A : d.A);   // SAC: mean and log-std per action
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
   d.capacity = (uint64_t)c.capacity;
@@ -132,6 +134,7 @@ Layout make_ws_layout(const PopDev& d) {
   L.done_c = take(4 * P * 4); L.done_wc = take(4 * P * 4); L.done_a = take(2 * P * 4);
   L.fault = take(4);
   L.sigma = take(P * 4);
+  L.log_alpha = take(3 * P * 4);
   L.staging = take(kStagingBytes);
   L.replay = take(P * (int64_t)d.capacity * d.row * 4);
   L.total = o;
@@ -178,6 +181,7 @@ int64_t pop_workspace_bytes(const pop_config* cfg) {
 int64_t pop_net_size(const pop_config* cfg, int32_t which) {
   int rc = check_config(cfg, nullptr);
   if (rc != POP_OK) return rc;
+  if (which >= POP_LOG_ALPHA && which <= POP_ADAM_V_LOG_ALPHA) return 1;
   if (which < 0 || which > POP_GRAD_CRITIC2) return fail(nullptr, POP_EINVAL, "bad tensor code %d", which);
   PopDev d;
   fill_dims(*cfg, d);
@@ -200,6 +204,7 @@ void to_device_hp(const pop_hparams& h, HpDev& g) {
   g.lr_actor = h.lr_actor; g.lr_critic = h.lr_critic; g.gamma = h.gamma; g.tau = h.tau;
   g.policy_noise = h.policy_noise; g.noise_clip = h.noise_clip; g.policy_delay = h.policy_delay;
   g.b1 = h.adam_b1; g.b2 = h.adam_b2; g.eps = h.adam_eps;
+  g.lr_alpha = h.lr_alpha; g.target_entropy = h.target_entropy;
 }
 
 // actor updates of agent a taken in steps [0, t_now): those before t_base plus the multiples of its delay since
@@ -243,6 +248,8 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->fuse = (d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512) ? 2 : 1;
   if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
   ctx->hp.assign(hp, hp + cfg->P);
+  if (cfg->algo == POP_ALGO_SAC)
+    for (auto& h : ctx->hp) h.policy_delay = 1;
   ctx->count.assign(cfg->P, 0);
   ctx->hp_dev.resize(cfg->P);
   for (int i = 0; i < cfg->P; ++i) {
@@ -251,6 +258,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
     HpDev& g = ctx->hp_dev[i];
     std::memset(&g, 0, sizeof g);                    // actor_base = t_base = 0
     to_device_hp(h, g);
+    if (cfg->algo == POP_ALGO_SAC) g.policy_delay = 1;   // SAC updates everything every step
   }
   char* w = ctx->ws;
   d.theta = (float*)(w + L.theta); d.target = (float*)(w + L.target); d.m = (float*)(w + L.m);
@@ -266,6 +274,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.cpart = (float*)(w + L.cpart); d.apart = (float*)(w + L.apart); d.losses = (float*)(w + L.losses);
   d.y_tagged = (uint64_t*)(w + L.y_tagged); d.done_c = (uint32_t*)(w + L.done_c); d.done_wc = (uint32_t*)(w + L.done_wc); d.done_a = (uint32_t*)(w + L.done_a);
   d.fault = (uint32_t*)(w + L.fault);
+  d.log_alpha = (float*)(w + L.log_alpha);
   ctx->d = d;
 
   auto bail = [&](hipError_t e, const char* what) {
@@ -274,16 +283,24 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
     return rc;
   };
   hipError_t e;
-  if ((e = setup_kernels()) != hipSuccess || (e = setup_step_kernel()) != hipSuccess) return bail(e, "kernel attribute setup");
+  if ((e = setup_kernels()) != hipSuccess || (e = setup_step_kernel()) != hipSuccess || (e = setup_sac_kernels()) != hipSuccess)
+    return bail(e, "kernel attribute setup");
   hipStream_t s = ctx->stream;
   // everything between the hyperparameters and the staging area starts at zero
   if ((e = hipMemsetAsync(w, 0, (size_t)L.staging, s)) != hipSuccess) return bail(e, "hipMemsetAsync");
   if ((e = hipMemcpyAsync(w + L.hp, ctx->hp_dev.data(), sizeof(HpDev) * cfg->P, hipMemcpyHostToDevice, s)) != hipSuccess)
     return bail(e, "hipMemcpyAsync(hparams)");
   InitLimits lim;
-  lim.actor[0] = glorot_limit(d.O, kH); lim.actor[1] = glorot_limit(kH, kH); lim.actor[2] = glorot_limit(kH, d.A);
+  lim.actor[0] = glorot_limit(d.O, kH); lim.actor[1] = glorot_limit(kH, kH); lim.actor[2] = glorot_limit(kH, d.actor.out);
   lim.critic[0] = glorot_limit(d.D, kH); lim.critic[1] = glorot_limit(kH, kH); lim.critic[2] = glorot_limit(kH, 1);
   if ((e = launch_init(ctx->d, lim, s)) != hipSuccess) return bail(e, "init kernel");
+  if (cfg->algo == POP_ALGO_SAC) {                 // log temperature; its Adam moments stay zero
+    std::vector<float> la(cfg->P);
+    for (int i = 0; i < cfg->P; ++i) la[i] = ctx->hp[i].init_log_alpha;
+    if ((e = hipMemcpyAsync(d.log_alpha, la.data(), sizeof(float) * cfg->P, hipMemcpyHostToDevice, s)) != hipSuccess ||
+        (e = hipStreamSynchronize(s)) != hipSuccess)
+      return bail(e, "hipMemcpyAsync(log_alpha)");
+  }
   if ((e = hipStreamSynchronize(s)) != hipSuccess) return bail(e, "hipStreamSynchronize");
   *out = ctx;
   return POP_OK;
@@ -358,6 +375,22 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
   bool any_actor = false;
   for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
+  if (d.algo == POP_ALGO_SAC) {                       // one launch per part; critic chain and tiles are the TD3 ones
+    if (!run(POP_K_TARGET, launch_sac_target) || !run(POP_K_CRITIC, launch_critic))
+      return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    tick(POP_K_WGRAD_CRITIC, 0);
+    e = launch_wgrad_adam(d, t, 0, has_next ? 1 : 0, s);
+    tick(POP_K_WGRAD_CRITIC, 1);
+    if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    if (has_next) ctx->gathered_t = ctx->t + 1;
+    if (!run(POP_K_ACTOR, launch_sac_actor)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    tick(POP_K_WGRAD_ACTOR, 0);
+    e = launch_wgrad_adam(d, t, 1, 0, s);
+    tick(POP_K_WGRAD_ACTOR, 1);
+    if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    ctx->t++;
+    return POP_OK;
+  }
   if (ctx->fuse == 2) {
     tick(POP_K_STEP, 0);
     e = launch_step(d, t, ctx->step_launches++, 1, any_actor ? 1 : 0, has_next ? 1 : 0, s);
@@ -512,6 +545,14 @@ int pop_act_explore(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, i
 int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, int64_t out_len, int32_t on_device) {
   if (!ctx) return POP_EINVAL;
   if (agent < 0 || agent >= ctx->d.P) return fail(ctx, POP_EINVAL, "agent %d out of range", agent);
+  if (which >= POP_LOG_ALPHA && which <= POP_ADAM_V_LOG_ALPHA) {       // SAC temperature: one float
+    if (ctx->d.algo != POP_ALGO_SAC) return fail(ctx, POP_EINVAL, "tensor code %d exists for SAC only", which);
+    if (!out || out_len < 1) return fail(ctx, POP_EINVAL, "out is NULL or too short");
+    const float* src = ctx->d.log_alpha + (size_t)(which - POP_LOG_ALPHA) * ctx->d.P + agent;
+    HIP_TRY(ctx, hipMemcpyAsync(out, src, 4, on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, ctx->stream));
+    if (!on_device) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return 1;
+  }
   if (which < 0 || which > POP_GRAD_CRITIC2) return fail(ctx, POP_EINVAL, "bad tensor code %d", which);
   if (!out) return fail(ctx, POP_EINVAL, "out is NULL");
   int net;
@@ -528,6 +569,14 @@ int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, i
 int pop_set_params(pop_ctx* ctx, int32_t agent, int32_t which, const float* in, int64_t in_len, int32_t on_device) {
   if (!ctx) return POP_EINVAL;
   if (agent < 0 || agent >= ctx->d.P) return fail(ctx, POP_EINVAL, "agent %d out of range", agent);
+  if (which >= POP_LOG_ALPHA && which <= POP_ADAM_V_LOG_ALPHA) {
+    if (ctx->d.algo != POP_ALGO_SAC) return fail(ctx, POP_EINVAL, "tensor code %d exists for SAC only", which);
+    if (!in || in_len != 1) return fail(ctx, POP_EINVAL, "in is NULL or in_len != 1");
+    float* dst = ctx->d.log_alpha + (size_t)(which - POP_LOG_ALPHA) * ctx->d.P + agent;
+    HIP_TRY(ctx, hipMemcpyAsync(dst, in, 4, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, ctx->stream));
+    if (!on_device) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return POP_OK;
+  }
   if (which < 0 || which > POP_ADAM_V_CRITIC2) return fail(ctx, POP_EINVAL, "tensor code %d cannot be written", which);
   if (!in) return fail(ctx, POP_EINVAL, "in is NULL");
   int net;
@@ -619,6 +668,7 @@ int pop_set_hparams(pop_ctx* ctx, int32_t agent, const pop_hparams* hp) {
   g.t_base = (uint32_t)ctx->t;
   ctx->hp[agent] = *hp;
   to_device_hp(*hp, g);
+  if (ctx->d.algo == POP_ALGO_SAC) { ctx->hp[agent].policy_delay = 1; g.policy_delay = 1; }
   // hp_dev lives as long as the context and is only changed here, after a synchronisation
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   HIP_TRY(ctx, hipMemcpyAsync(ctx->ws + ctx->lay.hp + sizeof(HpDev) * agent, &g, sizeof(HpDev), hipMemcpyHostToDevice, ctx->stream));
@@ -635,6 +685,9 @@ int pop_copy_agent(pop_ctx* ctx, int32_t dst, int32_t src, int32_t with_buffer) 
   const size_t state = (size_t)d.agent_sz * sizeof(float);
   for (float* region : {d.theta, d.target, d.m, d.v})
     HIP_TRY(ctx, hipMemcpyAsync(region + (size_t)dst * d.agent_sz, region + (size_t)src * d.agent_sz, state, hipMemcpyDeviceToDevice, s));
+  if (d.algo == POP_ALGO_SAC)
+    for (int k = 0; k < 3; ++k)
+      HIP_TRY(ctx, hipMemcpyAsync(d.log_alpha + (size_t)k * d.P + dst, d.log_alpha + (size_t)k * d.P + src, sizeof(float), hipMemcpyDeviceToDevice, s));
   if (with_buffer) {
     const size_t rows = (size_t)d.capacity * d.row;
     HIP_TRY(ctx, hipMemcpyAsync(d.replay + (size_t)dst * rows, d.replay + (size_t)src * rows, rows * sizeof(float), hipMemcpyDeviceToDevice, s));

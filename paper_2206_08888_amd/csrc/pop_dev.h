@@ -29,6 +29,7 @@ constexpr int kThreads = 256;  // 4 wavefronts of 64 per workgroup in every comp
 constexpr int kMaxIn = 64;     // largest first-layer fan-in (obs_dim + act_dim) held in LDS
 constexpr int kXld = kMaxIn + 4;
 constexpr int kMaxAct = 8;     // largest action dimension
+constexpr int kMaxHead = 16;   // largest actor head: 2 * kMaxAct outputs (mean and log-std of the SAC policy)
 
 struct HpDev {                 // per-agent hyperparameters as the kernels read them
   uint32_t seed_lo, seed_hi;
@@ -38,7 +39,7 @@ struct HpDev {                 // per-agent hyperparameters as the kernels read 
   // Adam step count of the actor: actor_base updates were taken before step t_base; since then one at every
   // step that is a multiple of policy_delay (both change only when the host resets hyperparameters or copies an agent)
   uint32_t actor_base, t_base;
-  float pad_[2];
+  float lr_alpha, target_entropy;   // SAC
 };
 static_assert(sizeof(HpDev) == 64, "HpDev layout");
 
@@ -60,6 +61,7 @@ __host__ __device__ inline NetLayout make_layout(int in, int out) {
 }
 
 struct PopDev {
+  int algo;                    // POP_ALGO_TD3 (0) or POP_ALGO_SAC (1); the SAC actor has 2 A outputs
   int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
   int rows_t, rows_c, rows_a;  // batch rows per workgroup of the target / critic / actor chain: (16, 32, 16) for small
                                // populations, (32, 32, 32), or (64, 64, 64) for large ones
@@ -86,6 +88,7 @@ struct PopDev {
   float* cpart;                // [P][2][chunks][kCPart]
   float* apart;                // [P][chunks][kAPart]
   float* losses;               // [P][4]: critic 1, critic 2, actor, unused
+  float* log_alpha;            // SAC: [3][P] log temperature, its Adam m, its Adam v
   // cross-workgroup signalling inside a launch
   uint64_t* y_tagged;          // [P][B]: (t + 1) << 32 | bits of y, for readers inside the launch that writes y
   int sync_half;               // which half of the counters below this launch counts in (set per launch)
@@ -97,9 +100,9 @@ struct PopDev {
 
 // critic partial record: dW3[256] db3[1] pad[3] db2[256] db1[256] loss[1] pad[3]
 constexpr int kCP_dW3 = 0, kCP_db3 = 256, kCP_db2 = 260, kCP_db1 = 516, kCP_loss = 772, kCPart = 776;
-// actor partial record: dW3[256*kMaxAct] db3[kMaxAct] db2[256] db1[256] loss[1] pad
-constexpr int kAP_dW3 = 0, kAP_db3 = 256 * kMaxAct, kAP_db2 = kAP_db3 + kMaxAct, kAP_db1 = kAP_db2 + 256,
-              kAP_loss = kAP_db1 + 256, kAPart = kAP_loss + 8;
+// actor partial record: dW3[256*kMaxHead] db3[kMaxHead] db2[256] db1[256] loss[1] logp[1] pad
+constexpr int kAP_dW3 = 0, kAP_db3 = 256 * kMaxHead, kAP_db2 = kAP_db3 + kMaxHead, kAP_db1 = kAP_db2 + 256,
+              kAP_loss = kAP_db1 + 256, kAP_logp = kAP_loss + 1 /* SAC: sum of log pi over the chunk */, kAPart = kAP_loss + 8;
 
 __device__ inline const float* batch_rows(const PopDev& d, uint32_t t, int agent) {
   return d.batch + ((size_t)(t & 1u) * d.P + agent) * d.B * d.row;

@@ -8,7 +8,7 @@
 
 namespace pop {
 
-enum : uint32_t { kStreamIndex = 0, kStreamSmooth = 1, kStreamInit = 4, kStreamExplore = 5 };
+enum : uint32_t { kStreamIndex = 0, kStreamSmooth = 1, kStreamSacS = 2, kStreamSacS2 = 3, kStreamInit = 4, kStreamExplore = 5 };
 
 struct U4 { uint32_t w[4]; };
 

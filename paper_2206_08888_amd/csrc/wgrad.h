@@ -176,7 +176,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     a.inv_c1 = (float)(1.0 / (1.0 - ipow((double)hp.b1, count)));
     a.inv_c2 = (float)(1.0 / (1.0 - ipow((double)hp.b2, count)));
     a.tau = hp.tau;
-    a.polyak = delayed_step ? 1 : 0;
+    a.polyak = (delayed_step && !(actor_phase && d.algo == 1)) ? 1 : 0;   // SAC has no target actor
     a.record = d.record_grads;
     *sh_adam = a;
   };
@@ -200,7 +200,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     const bool w2 = role < 16;                       // else layer 1, whose input is the leading columns of the batch rows
     const float* x = w2 ? (actor_phase ? d.aH1 : d.cH1) + o : batch_rows(d, t, agent);
     const float* z = (w2 ? (actor_phase ? d.adZ2 : d.cdZ2) : (actor_phase ? d.adZ1 : d.cdZ1)) + o;
-    weight_tile<WAIT>(d, wait_on, (uint32_t)chunks, sh_adam, setup, delayed_step, x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
+    weight_tile<WAIT>(d, wait_on, (uint32_t)chunks, sh_adam, setup, delayed_step && !(actor_phase && d.algo == 1), x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
                 (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
   } else {
     // small tensors from per-chunk partial sums; thread c owns hidden unit c.  The Adam operands
@@ -209,7 +209,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     const int out = L.out;
     const uint32_t i_b1 = (uint32_t)(L.b1 + c), i_b2 = (uint32_t)(L.b2 + c), i_w3 = (uint32_t)(L.w3 + c * out),
                    i_b3 = (uint32_t)(L.b3 + (c < out ? c : 0));
-    const bool polyak = delayed_step;
+    const bool polyak = delayed_step && !(actor_phase && d.algo == 1);
     auto ld = [&](uint32_t i) {
       AdamRegs r;
       r.th = th[i]; r.m = mo[i]; r.v = ve[i];
@@ -217,16 +217,16 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
       return r;
     };
     const AdamRegs r_b1 = ld(i_b1), r_b2 = ld(i_b2), r_b3 = ld(i_b3);
-    AdamRegs r_w3[kMaxAct];
+    AdamRegs r_w3[kMaxHead];
 #pragma unroll
-    for (int j = 0; j < kMaxAct; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j < out ? j : 0));
+    for (int j = 0; j < kMaxHead; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j < out ? j : 0));
     setup();
     if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
     __syncthreads();
     const Adam adam = *sh_adam;
-    float gb1 = 0.0f, gb2 = 0.0f, gw3[kMaxAct], gb3 = 0.0f, loss = 0.0f;
+    float gb1 = 0.0f, gb2 = 0.0f, gw3[kMaxHead], gb3 = 0.0f, loss = 0.0f, logp = 0.0f;
 #pragma unroll
-    for (int j = 0; j < kMaxAct; ++j) gw3[j] = 0.0f;
+    for (int j = 0; j < kMaxHead; ++j) gw3[j] = 0.0f;
 #pragma unroll 4
     for (int ch = 0; ch < chunks; ++ch) {
       if (actor_phase) {
@@ -234,10 +234,10 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
         gb1 += p[kAP_db1 + c];
         gb2 += p[kAP_db2 + c];
 #pragma unroll
-        for (int j = 0; j < kMaxAct; ++j)
+        for (int j = 0; j < kMaxHead; ++j)
           if (j < out) gw3[j] += p[kAP_dW3 + c * out + j];
         if (c < out) gb3 += p[kAP_db3 + c];
-        if (c == 0) loss += p[kAP_loss];
+        if (c == 0) { loss += p[kAP_loss]; logp += p[kAP_logp]; }
       } else {
         const float* p = d.cpart + ((size_t)unit * chunks + ch) * kCPart;
         gb1 += p[kCP_db1 + c];
@@ -249,9 +249,21 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     adam_store<WAIT>(adam, r_b1, gb1, i_b1, th, mo, ve, tg, gr);
     adam_store<WAIT>(adam, r_b2, gb2, i_b2, th, mo, ve, tg, gr);
 #pragma unroll
-    for (int j = 0; j < kMaxAct; ++j)
+    for (int j = 0; j < kMaxHead; ++j)
       if (j < out) adam_store<WAIT>(adam, r_w3[j], gw3[j], i_w3 + (uint32_t)j, th, mo, ve, tg, gr);
     if (c < out) adam_store<WAIT>(adam, r_b3, gb3, i_b3, th, mo, ve, tg, gr);
+    if (actor_phase && d.algo == 1 && c == 0) {
+      // SAC temperature: gradient of -alpha mean(log pi + target entropy) with respect to log_alpha, log pi
+      // from this step's actor pass held constant; one Adam step with lr_alpha, no target
+      float* la = d.log_alpha + agent;
+      const float cur = la[0], m0 = la[d.P], v0 = la[2 * d.P];
+      const float g = -expf(cur) * (logp / (float)d.B + hp.target_entropy);
+      const float mm = adam.b1 * m0 + (1.0f - adam.b1) * g;
+      const float vv = adam.b2 * v0 + (1.0f - adam.b2) * (g * g);
+      la[d.P] = mm;
+      la[2 * d.P] = vv;
+      la[0] = cur - hp.lr_alpha * (mm * adam.inv_c1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vv * adam.inv_c2) + adam.eps);
+    }
     if (c == 0) {
       // critic loss = sum over the twins; the two critic workgroups of an agent write
       // their halves to separate slots and the reader adds them

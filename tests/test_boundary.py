@@ -57,7 +57,8 @@ def test_workspace_size_and_net_sizes(lib):
     (dict(obs_dim=100), pp.POP_EUNSUPPORTED),
     (dict(act_dim=9), pp.POP_EUNSUPPORTED),
     (dict(capacity=1 << 33), pp.POP_EUNSUPPORTED),
-    (dict(algo=pp.POP_ALGO_SAC), pp.POP_EUNSUPPORTED),
+    (dict(algo=7), pp.POP_EINVAL),
+    (dict(algo=pp.POP_ALGO_SAC, obs_dim=376, act_dim=17), pp.POP_EUNSUPPORTED),   # the Humanoid shapes are not covered
 ])
 def test_bad_configs_are_rejected(lib, kwargs, code):
     base = dict(P=2, obs_dim=17, act_dim=6, hidden=(256, 256), batch=256, capacity=1000)

@@ -113,7 +113,7 @@ def test_agent_in_population_equals_agent_alone_bit_for_bit():
             alone.insert(0, **tr)
         alone.update(4)
         for which in pp.PARAM_CODES:
-            if which.startswith("g_"):
+            if which.startswith("g_") or which.endswith("log_alpha"):
                 continue
             assert np.array_equal(full.get_params(i, which), alone.get_params(0, which)), (i, which)
         alone.close()
@@ -294,7 +294,7 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
                 assert sum(cnt.values()) == 31
         assert all(ms[k] > 0.0 for k in ms if cnt[k]) and gpu.step_count() == 13
         gpu.sync()
-        states.append({(i, w): gpu.get_params(i, w) for i in range(11) for w in pp.PARAM_CODES if not w.startswith("g_")})
+        states.append({(i, w): gpu.get_params(i, w) for i in range(11) for w in STATE12})
         gpu.close()
     for other in states[1:]:
         for key in states[0]:

@@ -27,9 +27,11 @@ MFMA_FP32_PEAK_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 H = 256
 
 
-def kernel_flops(P, B, O, A):
+def kernel_flops(P, B, O, A, algo="td3"):
     """Algorithmic FLOPs of one launch of each kernel (2 per multiply-add), whole population."""
     D = O + A
+    if algo == "sac":
+        return sac_kernel_flops(P, B, O, A)
     fwd_actor = 2 * B * (O * H + H * H + H * A)
     fwd_critic = 2 * B * (D * H + H * H + H)
     per_agent = {
@@ -48,8 +50,30 @@ def kernel_flops(P, B, O, A):
     return {k: v * P for k, v in per_agent.items()}
 
 
-def step_flops_per_agent(B, O, A, delay=2):
-    f = kernel_flops(1, B, O, A)
+def sac_kernel_flops(P, B, O, A):
+    """SAC: the actor head has 2A outputs, the actor step runs both critics forward and backward."""
+    D = O + A
+    fwd_actor = 2 * B * (O * H + H * H + H * 2 * A)
+    fwd_critic = 2 * B * (D * H + H * H + H)
+    critic_to_action = 2 * B * H + 2 * B * H * H + 2 * B * A * H          # dz2, dz1, da
+    per_agent = {
+        "gather": 0,
+        "target": fwd_actor + 2 * fwd_critic,
+        "critic": 2 * (fwd_critic + 2 * B * H * H + 2 * B * H),
+        "wgrad_critic": 2 * (2 * B * H * H + 2 * B * D * H),
+        "actor": fwd_actor + 2 * fwd_critic + 2 * critic_to_action + 2 * (2 * B * 2 * A * H) + 2 * B * H * H,
+        "wgrad_actor": 2 * B * H * H + 2 * B * O * H,
+    }
+    per_agent["target_critic"] = per_agent["target"] + per_agent["critic"]
+    for k in ("step", "step_tail"):
+        per_agent[k] = 0
+    return {k: v * P for k, v in per_agent.items()}
+
+
+def step_flops_per_agent(B, O, A, delay=2, algo="td3"):
+    f = kernel_flops(1, B, O, A, algo)
+    if algo == "sac":
+        delay = 1
     return f["target"] + f["critic"] + f["wgrad_critic"] + (f["actor"] + f["wgrad_actor"]) / delay
 
 
@@ -57,7 +81,8 @@ def build_population(config_id, torch, fill=None):
     import paper_2206_08888_amd as pp
     c = workloads.CONFIGS[config_id]
     P, O, A, cap = c["P"], c["obs_dim"], c["act_dim"], c["capacity"]
-    cfg = pp.make_config(P, O, A, c["hidden"], c["batch"], cap)
+    cfg = pp.make_config(P, O, A, c["hidden"], c["batch"], cap,
+                         algo=pp.POP_ALGO_SAC if c["algo"] == "sac" else pp.POP_ALGO_TD3)
     pop = pp.Population(cfg, workloads.hparams(config_id))
     gen = torch.Generator(device="cuda")
     gen.manual_seed(workloads.DATA_SEED + config_id)
@@ -101,11 +126,11 @@ def time_config(config_id, steps, warmup, torch, with_kernels=True):
 
 def cpu_baseline(config_id, budget_s=12.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
-    from oracle import td3
+    from oracle import sac, td3
     c = workloads.CONFIGS[config_id]
     n_agents, rows = 2, 50_000
     hps = workloads.hparams(config_id)[:n_agents]
-    orc = td3.Population(hps, c["obs_dim"], c["act_dim"], list(c["hidden"]), c["batch"], rows)
+    orc = (sac if c["algo"] == "sac" else td3).Population(hps, c["obs_dim"], c["act_dim"], list(c["hidden"]), c["batch"], rows)
     for i in range(n_agents):
         orc.insert(i, **workloads.transitions(config_id, i, rows))
     orc.update(1)
@@ -143,7 +168,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=1, choices=(0, 1, 2, 4))
+    ap.add_argument("--config", type=int, default=1, choices=(0, 1, 2, 4, 5))
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-secondary", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -169,7 +194,7 @@ def main():
         del src, dst
     res, c = time_config(args.config, args.steps, args.warmup, torch)
     P, B, O, A = c["P"], c["batch"], c["obs_dim"], c["act_dim"]
-    flops = kernel_flops(P, B, O, A)
+    flops = kernel_flops(P, B, O, A, c["algo"])
     kus = res["kernel_us"]
     per_step_us = {k: (kus[k] or 0.0) * res["kernel_launches"][k] / args.steps for k in kus}
     dominant = max((k for k in kus if flops[k] > 0 and kus[k]), key=lambda k: per_step_us[k])
@@ -177,15 +202,15 @@ def main():
     roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=achieved / MFMA_FP32_PEAK_TFLOPS, traffic=read_traffic(dominant, P),
                     avg_launch_us=kus[dominant], flops_per_launch=flops[dominant])
-    step_frac = res["value"] * step_flops_per_agent(B, O, A) / (MFMA_FP32_PEAK_TFLOPS * 1e12)
+    step_frac = res["value"] * step_flops_per_agent(B, O, A, algo=c["algo"]) / (MFMA_FP32_PEAK_TFLOPS * 1e12)
     line = {
-        "metric": "agent-updates/sec (P x SGD steps/s), TD3 population",
+        "metric": "agent-updates/sec (P x SGD steps/s), %s population" % c["algo"].upper(),
         "value": res["value"], "unit": "agent-updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config %d: TD3 population P=%d, obs %d, act %d, MLP 256x256, batch %d, "
+        "config": {"workload": "config %d: %s population P=%d, obs %d, act %d, MLP 256x256, batch %d, "
                                "%d-row replay buffer per agent, per-agent hyperparameters"
-                               % (args.config, P, O, A, B, c["capacity"]),
+                               % (args.config, c["algo"].upper(), P, O, A, B, c["capacity"]),
                    "P": P, "batch": B, "obs_dim": O, "act_dim": A, "capacity": c["capacity"]},
         "roofline": roofline,
         "step_frac_of_fp32_mfma_peak": step_frac,

@@ -18,6 +18,19 @@ __global__ __launch_bounds__(kThreads, 1) void k_sac_actor(PopDev d, uint32_t t)
   if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) sac_actor_chain<G>(d, t, agent, chunk, lds);
 }
 
+// Target and critic chains in one launch, as for TD3 (k_chain.hip): the critics' forward pass runs beside
+// the target workgroups and only the loss waits for the targets of its own rows.
+template <class GT, class GC>
+__global__ __launch_bounds__(kThreads, 1) void k_sac_target_critic(PopDev d, uint32_t t, int target_blocks) {
+  extern __shared__ float lds[];
+  int unit, chunk;
+  if ((int)blockIdx.x < target_blocks) {
+    if (decode_block(blockIdx.x, d.P, d.B / GT::R, unit, chunk)) sac_target_chain<GT>(d, t, unit, chunk, lds);
+  } else if (decode_block(blockIdx.x - target_blocks, 2 * d.P, d.B / GC::R, unit, chunk)) {
+    critic_chain<GC, true, false>(d, t, unit, chunk, lds);
+  }
+}
+
 hipError_t setup_sac_kernels() {
   hipError_t e;
   const int most = 160 * 1024;
@@ -29,6 +42,8 @@ hipError_t setup_sac_kernels() {
   POP_SET_LDS(k_sac_actor<Rows16>);
   POP_SET_LDS(k_sac_actor<Rows32<1>>);
   POP_SET_LDS(k_sac_actor<Rows32<2>>);
+  POP_SET_LDS(k_sac_target_critic<Rows16, Rows32<2>>);
+  POP_SET_LDS(k_sac_target_critic<Rows32<1>, Rows32<1>>);
 #undef POP_SET_LDS
   return hipSuccess;
 }
@@ -39,6 +54,22 @@ hipError_t launch_sac_target(const PopDev& d, uint32_t t, hipStream_t s) {
   if (d.rows_t == 16) k_sac_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   else if (d.rows_t == 32) k_sac_target<Rows32<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   else k_sac_target<Rows32<2>><<<grid, block, LdsMap<64, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  return hipGetLastError();
+}
+
+hipError_t launch_sac_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
+  const int nt = xcd_grid(d.P, d.B / d.rows_t), nc = xcd_grid(2 * d.P, d.B / d.rows_c);
+  const dim3 grid(nt + nc), block(kThreads);
+  const int vec = vec_sac_target(d);                 // larger than the critic chain's
+  if (d.rows_t == 16 && d.rows_c == 64) {
+    const size_t a = LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), b = Lds<2>(d.D).bytes(vec_critic(d));
+    k_sac_target_critic<Rows16, Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
+  } else if (d.rows_t == 32 && d.rows_c == 32) {
+    const size_t a = LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), b = Lds<1>(d.D).bytes(vec_critic(d));
+    k_sac_target_critic<Rows32<1>, Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
+  } else {
+    return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

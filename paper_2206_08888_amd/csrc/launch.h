@@ -28,6 +28,7 @@ hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int p
 // and the weight-gradient launches are shared with TD3
 hipError_t launch_sac_target(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_sac_actor(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t launch_sac_target_critic(const PopDev& d, uint32_t t, hipStream_t s);   // target + critic chains in one launch
 hipError_t setup_sac_kernels();
 
 // the step as one launch (k_step.hip); with_chains = 0: without the target and critic chains (launched

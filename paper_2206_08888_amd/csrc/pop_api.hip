@@ -246,6 +246,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   // (The 64-row chains of very large populations do not fit the register budget of the
   // single kernel without spilling and stay separate as well.)
   ctx->fuse = (d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512) ? 2 : 1;
+  if (cfg->algo == POP_ALGO_SAC) ctx->fuse = 0;     // measured at P = 32: fusing target and critic chains loses 4 %
   if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
   ctx->hp.assign(hp, hp + cfg->P);
   if (cfg->algo == POP_ALGO_SAC)
@@ -375,9 +376,13 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
   bool any_actor = false;
   for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
-  if (d.algo == POP_ALGO_SAC) {                       // one launch per part; critic chain and tiles are the TD3 ones
-    if (!run(POP_K_TARGET, launch_sac_target) || !run(POP_K_CRITIC, launch_critic))
+  if (d.algo == POP_ALGO_SAC) {                       // critic chain and tiles are the TD3 ones; POP_FUSE = 0: one launch
+                                                      // per part, else target and critic chains in one launch
+    if (ctx->fuse != 0) {
+      if (!run(POP_K_TARGET_CRITIC, launch_sac_target_critic)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    } else if (!run(POP_K_TARGET, launch_sac_target) || !run(POP_K_CRITIC, launch_critic)) {
       return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    }
     tick(POP_K_WGRAD_CRITIC, 0);
     e = launch_wgrad_adam(d, t, 0, has_next ? 1 : 0, s);
     tick(POP_K_WGRAD_CRITIC, 1);

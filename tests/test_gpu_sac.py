@@ -162,6 +162,21 @@ def test_act_mean_and_sampled_actions_match_oracle():
     gpu.close()
 
 
+def test_fused_and_separate_target_critic_launches_agree_bit_for_bit(monkeypatch):
+    states = []
+    for fuse in ("1", "0"):
+        monkeypatch.setenv("POP_FUSE", fuse)
+        gpu, _, _ = make_sac_pair(P=11, capacity=800, oracle=False, hps=sac_hparams(11))
+        gpu.update(5)
+        ms, cnt = gpu.update_timed(3)
+        assert (cnt["target_critic"], cnt["target"], cnt["critic"]) == ((3, 0, 0) if fuse == "1" else (0, 3, 3))
+        assert cnt["wgrad_critic"] == cnt["actor"] == cnt["wgrad_actor"] == 3
+        states.append({(i, w): gpu.get_params(i, w) for i in range(11) for w in NETS5 + MOMS + ALPHA3})
+        gpu.close()
+    for key in states[0]:
+        assert np.array_equal(states[0][key], states[1][key]), key
+
+
 def test_copy_agent_carries_the_temperature():
     gpu, _, _ = make_sac_pair(P=3, capacity=600, oracle=False)
     gpu.update(3)

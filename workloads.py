@@ -29,6 +29,9 @@ CONFIGS = {
     # 3: SAC variant
     3: dict(algo="sac", P=32, hidden=(256, 256), batch=256, capacity=500_000, steps=500,
             sweep=(), **HUMANOID),
+    # 5: SAC at the shapes the paper itself measures SAC on (Sec. 4.1: HalfCheetah-v2), population of config 3
+    5: dict(algo="sac", P=32, hidden=(256, 256), batch=256, capacity=200_000, steps=500,
+            sweep=("lr", "tau"), **HALFCHEETAH),
     # 4: saturation case, P up to 256
     4: dict(algo="td3", P=256, hidden=(256, 256), batch=256, capacity=50_000, steps=200,
             sweep=("lr", "tau", "policy_noise"), **HALFCHEETAH),

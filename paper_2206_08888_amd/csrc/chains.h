@@ -1,7 +1,8 @@
 // Fused forward/backward chains of one TD3 update step (Sec. 4.1 of the paper:
 // every population member takes the ordinary TD3 update on its own batch).
 //
-// The batch of an agent is cut into row chunks of R = 32 MT rows.  One
+// The batch of an agent is cut into row chunks of R = 16, 32 or 64 rows (the tile
+// geometries below).  One
 // workgroup owns one (agent or network, chunk) and walks the whole layer chain
 // for its rows with the activations resident in LDS; only what the
 // weight-gradient kernel needs later (layer inputs and pre-activation

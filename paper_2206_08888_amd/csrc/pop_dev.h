@@ -63,7 +63,7 @@ __host__ __device__ inline NetLayout make_layout(int in, int out) {
 struct PopDev {
   int algo;                    // POP_ALGO_TD3 (0) or POP_ALGO_SAC (1); the SAC actor has 2 A outputs
   int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
-  int rows_t, rows_c, rows_a;  // batch rows per workgroup of the target / critic / actor chain: (16, 32, 16) for small
+  int rows_t, rows_c, rows_a;  // batch rows per workgroup of the target / critic / actor chain: (16, 64, 16) for small
                                // populations, (32, 32, 32), or (64, 64, 64) for large ones
   NetLayout actor, critic;
   int agent_sz;                // actor.padded + 2 * critic.padded

@@ -4,32 +4,31 @@
 // hyperparametrization, i.e. Adam and soft target updates).
 //
 // The gradient of a weight matrix is dW = X^T dZ with the batch as the
-// contraction index.  A workgroup owns a slab of 32 rows of dW (all 256
-// columns): it first transposes its 32 columns of X (written by the chain
-// kernels) into an LDS tile [32][batch], and then runs the same pipelined
-// 256-deep MFMA product as a hidden layer, with dZ streamed from global memory
-// in the role of the weights.  Each wavefront then updates exactly the
-// parameters it holds in its accumulators:
+// contraction index.  A workgroup owns a tile of 32 rows x 128 columns of dW
+// (one 32-column accumulator tile per wavefront): it transposes its 32 columns
+// of X (written by the chains) into an LDS tile [32][batch] and runs a
+// pipelined 256-deep MFMA product with dZ streamed from global memory in the
+// role of the weights.  Each wavefront then updates exactly the parameters it
+// holds in its accumulators:
 //     m <- b1 m + (1 - b1) g ;  v <- b2 v + (1 - b2) g^2
 //     theta <- theta - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
 //     theta' <- (1 - tau) theta' + tau theta        (only on delayed steps)
 // (the two bias corrections enter as reciprocals computed once per workgroup in
 // double; the final quotient uses the hardware reciprocal, 1 ulp)
-// so a gradient never makes a round trip through HBM.  The parameters, moments
-// and targets of the first half of the slab are requested under the last blocks
-// of the product, so their HBM latency is hidden behind the MFMA work.  The
-// small tensors (biases, head weights) arrive as per-chunk partial sums and are
-// reduced and updated by one extra workgroup per network.
+// so a gradient never makes a round trip through HBM.  Parameters, moments and
+// targets of the tile do not depend on the product: they are requested right
+// after the product's own first operands and arrive under it.  The small
+// tensors (biases, head weights) arrive as per-chunk partial sums and are
+// reduced and updated by one extra workgroup per network, which for SAC also
+// takes the Adam step of the temperature.
 //
-// 1-D block index, decoded so that the roles of one network share an XCD (its L2 then
-// serves the re-reads of dZ).  Roles of one network:
-//   [0, 8)             32-row slabs of W2
-//   [8, 8 + n1)        32-row slabs of the layer-1 weights (rows >= fan-in masked)
-//   8 + n1             b1, b2, W3, b3 and the loss value
-// Blocks past the last network gather the replay rows of step t + 1 into the
-// other half of the double-buffered batch (App. A of the paper: the next
-// batches are fetched while the current update runs).  The batch size must be
-// 256 for the slab product (its contraction depth is fixed).
+// Roles of one network (n1 = ceil(fan-in of layer 1 / 32)):
+//   [0, 16)              tiles of W2: 32-row slab role / 2, column half role % 2
+//   [16, 16 + 2 n1)      tiles of the layer-1 weights (rows >= fan-in masked)
+//   16 + 2 n1            b1, b2, W3, b3, the loss value (and log alpha)
+// The kernels decode block indices so that the roles of one network share an
+// XCD (its L2 then serves the re-reads of dZ).  The batch size must be 256 for
+// the tile product (its contraction depth is fixed).
 #pragma once
 #include "chains.h"
 

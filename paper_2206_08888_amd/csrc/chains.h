@@ -198,8 +198,8 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
           buf[(32 * mt + acc_row(v, lane)) * kLda + 64 * wave + 32 * nt + (lane & 31)] =
               mask_bit(mask, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;
   }
-  __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid) {
-    thin_dot<R>(Xl, V, J, outl, tid);
+  __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid, int stride = kMaxAct) {
+    thin_dot<R>(Xl, V, J, outl, tid, stride);
   }
   // buf[row][col] = mask ? rowvec[row] * colvec[col] : 0  (mask as returned by hidden_layer)
   __device__ static inline void store_outer_masked(float* buf, uint64_t mask, const float* rowvec, const float* colvec,
@@ -292,8 +292,8 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
       *reinterpret_cast<f32x4*>(&buf[(4 * kq + v) * kLda + 64 * wave + 4 * c]) = o;
     }
   }
-  __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid) {
-    thin_dot16(Xl, V, J, outl, tid);
+  __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid, int stride = kMaxAct) {
+    thin_dot16(Xl, V, J, outl, tid, stride);
   }
   __device__ static inline void store_outer_masked(float* buf, uint64_t mask, const float* rowvec, const float* colvec,
                                                    int wave, int lane) {
@@ -312,6 +312,12 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
 };
 
 }  // namespace
+
+// Thin product with any number of outputs, eight at a time (the register budget of one pass).
+template <class G>
+__device__ inline void thin_wide(const float* Xl, const float* V, int J, float* outl, int stride, int tid) {
+  for (int j0 = 0; j0 < J; j0 += kMaxAct) G::thin(Xl, V + j0 * kH, J - j0 < kMaxAct ? J - j0 : kMaxAct, outl + j0, tid, stride);
+}
 
 // Longest time a workgroup waits for another one of the same launch, in 10 ns ticks of the
 // constant-rate clock (50 ms; a healthy wait is a fraction of a millisecond).
@@ -735,5 +741,6 @@ inline int vec_target(const PopDev& d) { return kH * d.A + 8 + 2 * kH + 8; }
 inline int vec_critic(const PopDev&) { return kH + 8; }
 inline int vec_actor(const PopDev& d) { return kH * d.A + 8 + kH + d.A * kH; }
 inline int vec_act(const PopDev& d) { return kH * d.actor.out + kMaxHead; }
+constexpr int kActScratch = 2 * (kSacMaxAct / kMaxAct);   // acting: two head blocks of [32][kSacMaxAct]
 
 }  // namespace pop

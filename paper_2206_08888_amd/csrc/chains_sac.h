@@ -38,8 +38,12 @@ __device__ inline float normal_at(const HpDev& hp, uint32_t el, uint32_t t, uint
 
 }  // namespace
 
-// LDS scratch regions of the SAC chains: nine [R][8] blocks
-constexpr int kSacScratch = 9;
+// LDS scratch of the SAC chains: nine blocks of [R][kSs] floats (a block = kSacRegion of the
+// map's [R][8] regions); the action dimension goes up to kSacMaxAct here.
+constexpr int kSs = kSacMaxAct;
+constexpr int kSacRegion = kSs / kMaxAct;
+constexpr int kSacScratch = 9 * kSacRegion;
+static_assert(kSs % kMaxAct == 0 && 2 * kSs >= kMaxHead, "dz3 rows of kMaxHead floats fit two scratch blocks");
 
 inline int vec_sac_target(const PopDev& d) { return kH * 2 * d.A + kMaxHead + 2 * kH + 8; }
 inline int vec_sac_actor(const PopDev& d) { return kH * 2 * d.A + kMaxHead + 2 * kH + 2 * d.A * kH + 8; }
@@ -54,10 +58,10 @@ __device__ __forceinline__ void sac_target_chain(const PopDev& d, uint32_t t, in
   float* Xs = lds;
   float* buf = lds + L.buf;
   float* hm = lds + L.s(0);                          // mean head, later thin-product scratch
-  float* hl = lds + L.s(1);                          // log-std head, later the terms of log pi
-  float* qmin = lds + L.s(2);                        // [R] min of the target critics, [R..2R) log pi
+  float* hl = lds + L.s(kSacRegion);                 // log-std head, later the terms of log pi
+  float* qmin = lds + L.s(2 * kSacRegion);           // [R] min of the target critics, [R..2R) log pi
   float* v_aw3 = lds + L.vec;                        // [2A][256]
-  float* v_ab3 = v_aw3 + kH * 2 * A;                 // [16]
+  float* v_ab3 = v_aw3 + kH * 2 * A;                 // [kMaxHead]
   float* v_cw3 = v_ab3 + kMaxHead;                   // [2][256]
   float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -82,22 +86,22 @@ __device__ __forceinline__ void sac_target_chain(const PopDev& d, uint32_t t, in
   __syncthreads();
   G::template hidden_layer<false>(buf, an, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
-  G::thin(buf, v_aw3, A, hm, tid);
-  G::thin(buf, v_aw3 + A * kH, A, hl, tid);
+  thin_wide<G>(buf, v_aw3, A, hm, kSs, tid);
+  thin_wide<G>(buf, v_aw3 + A * kH, A, hl, kSs, tid);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
     const int r = e / A, j = e - r * A;
-    const float mu = hm[r * kMaxAct + j] + v_ab3[j];
-    const float ls = fminf(fmaxf(hl[r * kMaxAct + j] + v_ab3[A + j], kLogStdMin), kLogStdMax);
+    const float mu = hm[r * kSs + j] + v_ab3[j];
+    const float ls = fminf(fmaxf(hl[r * kSs + j] + v_ab3[A + j], kLogStdMin), kLogStdMax);
     const float eps = normal_at(hp, (uint32_t)((r0 + r) * A + j), t, kStreamSacS2);
     const float u = mu + expf(ls) * eps;
     Xs[r * L.xld + d.O + j] = tanhf(u);
-    hl[r * kMaxAct + j] = -0.5f * eps * eps - ls - kHalfLog2Pi - 2.0f * (kLn2 - u - softplusf(-2.0f * u));
+    hl[r * kSs + j] = -0.5f * eps * eps - ls - kHalfLog2Pi - 2.0f * (kLn2 - u - softplusf(-2.0f * u));
   }
   __syncthreads();
   if (tid < R) {
     float lp = 0.0f;
-    for (int j = 0; j < A; ++j) lp += hl[tid * kMaxAct + j];
+    for (int j = 0; j < A; ++j) lp += hl[tid * kSs + j];
     qmin[R + tid] = lp;
   }
 
@@ -109,10 +113,10 @@ __device__ __forceinline__ void sac_target_chain(const PopDev& d, uint32_t t, in
     G::template hidden_layer<false>(buf, tc, d.critic, pre, nullptr, wave, lane,
                                     [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
     __syncthreads();
-    G::thin(buf, v_cw3 + k * kH, 1, hm, tid);
+    G::thin(buf, v_cw3 + k * kH, 1, hm, tid, kSs);
     __syncthreads();
     if (tid < R) {
-      const float q = hm[tid * kMaxAct] + v_cb3[k];
+      const float q = hm[tid * kSs] + v_cb3[k];
       qmin[tid] = k == 0 ? q : fminf(qmin[tid], q);
     }
     __syncthreads();
@@ -124,6 +128,42 @@ __device__ __forceinline__ void sac_target_chain(const PopDev& d, uint32_t t, in
     d.y[(size_t)agent * d.B + r0 + tid] = yv;
     publish_y(d, (size_t)agent * d.B + r0 + tid, t, yv);
   }
+}
+
+// Backward through the actor's head for one chunk, thread c = hidden unit c:
+//   gW3[c][j] = sum_r h2[r][c] dz3[r][j];  dz2[r][c] = [h2[r][c] > 0] sum_j dz3[r][j] W3[c][j]
+// buf: h2 in, dz2 out (LDS tile, row stride kLda); dz3: [R][kMaxHead], columns >= H2 hold zeros;
+// NC: head columns handled (a multiple of 4, >= H2).
+template <int R, int NC>
+__device__ __forceinline__ void sac_head_backward(float* buf, const float* dz3, const float* v_aw3, int H2, float* zg,
+                                                  float* part, int c) {
+  float w3[NC], gw3[NC];
+#pragma unroll
+  for (int j = 0; j < NC; ++j) { w3[j] = j < H2 ? v_aw3[j * kH + c] : 0.0f; gw3[j] = 0.0f; }
+  float gb2 = 0.0f;
+  zg += c;
+#pragma unroll 1
+  for (int r = 0; r < R; ++r) {
+    const float h = buf[r * kLda + c];
+    float dh = 0.0f;
+#pragma unroll
+    for (int q = 0; q < NC / 4; ++q) {
+      const f32x4 g = *reinterpret_cast<const f32x4*>(&dz3[r * kMaxHead + 4 * q]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        gw3[4 * q + i] += h * g[i];
+        dh += g[i] * w3[4 * q + i];
+      }
+    }
+    const float z = h > 0.0f ? dh : 0.0f;
+    buf[r * kLda + c] = z;
+    zg[r * kH] = z;
+    gb2 += z;
+  }
+#pragma unroll
+  for (int j = 0; j < NC; ++j)
+    if (j < H2) part[kAP_dW3 + c * H2 + j] = gw3[j];
+  part[kAP_db2 + c] = gb2;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -141,15 +181,15 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
   float* Xs = lds;
   float* buf = lds + L.buf;
   float* hm = lds + L.s(0);                          // mean head -> terms of log pi -> thin-product scratch
-  float* hl = lds + L.s(1);                          // log-std head -> std * eps
-  float* ap = lds + L.s(2);                          // a = tanh(u)
-  float* ins = lds + L.s(3);                         // 1 where the log-std was inside its range
-  float* qv = lds + L.s(4);                          // [R] q1 | q2 | seed1 | seed2 | log pi
-  float* da1 = lds + L.s(5);
-  float* da2 = lds + L.s(6);
-  float* dz3 = lds + L.s(7);                         // [R][16] (two regions)
+  float* hl = lds + L.s(kSacRegion);                 // log-std head -> std * eps
+  float* ap = lds + L.s(2 * kSacRegion);             // a = tanh(u)
+  float* ins = lds + L.s(3 * kSacRegion);            // 1 where the log-std was inside its range
+  float* qv = lds + L.s(4 * kSacRegion);             // [R] q1 | q2 | seed1 | seed2 | log pi
+  float* da1 = lds + L.s(5 * kSacRegion);
+  float* da2 = lds + L.s(6 * kSacRegion);
+  float* dz3 = lds + L.s(7 * kSacRegion);            // [R][kMaxHead] (two blocks)
   float* v_aw3 = lds + L.vec;                        // [2A][256] actor head
-  float* v_ab3 = v_aw3 + kH * H2;                    // [16]
+  float* v_ab3 = v_aw3 + kH * H2;                    // [kMaxHead]
   float* v_cw3 = v_ab3 + kMaxHead;                   // [2][256] critic heads
   float* v_cwa = v_cw3 + 2 * kH;                     // [2][A][256] critic first-layer rows of the action inputs
   float* v_cb3 = v_cwa + 2 * A * kH;                 // [2]
@@ -180,11 +220,11 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
   G::template hidden_layer<false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
                                   [&]() { pre.load(cn[0], d.critic, wave, lane); });
   __syncthreads();
-  G::thin(buf, v_aw3, A, hm, tid);
-  G::thin(buf, v_aw3 + A * kH, A, hl, tid);
+  thin_wide<G>(buf, v_aw3, A, hm, kSs, tid);
+  thin_wide<G>(buf, v_aw3 + A * kH, A, hl, kSs, tid);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
-    const int r = e / A, j = e - r * A, o = r * kMaxAct + j;
+    const int r = e / A, j = e - r * A, o = r * kSs + j;
     const float mu = hm[o] + v_ab3[j];
     const float ls_raw = hl[o] + v_ab3[A + j];
     const float ls = fminf(fmaxf(ls_raw, kLogStdMin), kLogStdMax);
@@ -201,7 +241,7 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
   __syncthreads();
   if (tid < R) {
     float lp = 0.0f;
-    for (int j = 0; j < A; ++j) lp += hm[tid * kMaxAct + j];
+    for (int j = 0; j < A; ++j) lp += hm[tid * kSs + j];
     qv[4 * R + tid] = lp;
   }
 
@@ -217,9 +257,9 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
       else G::load_wt(wt, cn[0] + d.critic.w2, wave, lane);
     });
     __syncthreads();
-    G::thin(buf, v_cw3 + k * kH, 1, hm, tid);
+    G::thin(buf, v_cw3 + k * kH, 1, hm, tid, kSs);
     __syncthreads();
-    if (tid < R) qv[k * R + tid] = hm[tid * kMaxAct] + v_cb3[k];
+    if (tid < R) qv[k * R + tid] = hm[tid * kSs] + v_cb3[k];
     __syncthreads();
   }
   if (tid < 64) {                                    // R <= 64: one wavefront covers the chunk
@@ -251,7 +291,7 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
     });                                              // buf = dz1 of critic k
     __syncthreads();
-    G::thin(buf, v_cwa + k * A * kH, A, k == 0 ? da1 : da2, tid);
+    thin_wide<G>(buf, v_cwa + k * A * kH, A, k == 0 ? da1 : da2, kSs, tid);
     if (k == 0) G::load_wt(wt, cn[1] + d.critic.w2, wave, lane);
     else G::load_wt(wt, an + d.actor.w2, wave, lane);
     __syncthreads();
@@ -263,7 +303,7 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
     const int r = e / kMaxHead, c = e - r * kMaxHead;
     float g = 0.0f;
     if (c < H2) {
-      const int j = c < A ? c : c - A, o = r * kMaxAct + j;
+      const int j = c < A ? c : c - A, o = r * kSs + j;
       const float a = ap[o];
       const float du = (da1[o] + da2[o]) * (1.0f - a * a) + ab * 2.0f * a;
       g = c < A ? du : (du * hl[o] - ab) * ins[o];
@@ -279,36 +319,9 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
     for (int r = 0; r < R; ++r) s += dz3[r * kMaxHead + tid];
     part[kAP_db3 + tid] = s;
   }
-  {                                                  // actor head backward, one thread per hidden unit
-    const int c = tid;
-    float w3[kMaxHead], gw3[kMaxHead];
-#pragma unroll
-    for (int j = 0; j < kMaxHead; ++j) { w3[j] = j < H2 ? v_aw3[j * kH + c] : 0.0f; gw3[j] = 0.0f; }
-    float gb2 = 0.0f;
-    float* zg = d.adZ2 + act_off + c;
-#pragma unroll 1
-    for (int r = 0; r < R; ++r) {
-      const float h = buf[r * kLda + c];
-      float dh = 0.0f;
-#pragma unroll
-      for (int q = 0; q < kMaxHead / 4; ++q) {
-        const f32x4 g = *reinterpret_cast<const f32x4*>(&dz3[r * kMaxHead + 4 * q]);   // columns >= 2A hold zeros
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          gw3[4 * q + i] += h * g[i];
-          dh += g[i] * w3[4 * q + i];
-        }
-      }
-      const float z = h > 0.0f ? dh : 0.0f;
-      buf[r * kLda + c] = z;
-      zg[r * kH] = z;
-      gb2 += z;
-    }
-#pragma unroll
-    for (int j = 0; j < kMaxHead; ++j)
-      if (j < H2) part[kAP_dW3 + c * H2 + j] = gw3[j];
-    part[kAP_db2 + c] = gb2;
-  }
+  // actor head backward, one thread per hidden unit; the common small heads stay in 16 registers
+  if (H2 <= 16) sac_head_backward<R, 16>(buf, dz3, v_aw3, H2, d.adZ2 + act_off, part, tid);
+  else sac_head_backward<R, kMaxHead>(buf, dz3, v_aw3, H2, d.adZ2 + act_off, part, tid);
   __syncthreads();
   G::template input_grad_to_global<false>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
 }

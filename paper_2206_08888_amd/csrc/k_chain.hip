@@ -54,11 +54,12 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
                                                   uint32_t step, uint32_t row_base) {
   constexpr int R = 32;
   extern __shared__ float lds[];
-  const Lds<1> L(d.O);
+  constexpr int kHs = kSacMaxAct;                    // row stride of the head blocks: three [R][8] regions each
+  const Lds<1> L(d.O, kActScratch);
   float* Xs = lds;
   float* buf = lds + L.buf;
-  float* head = lds + L.s0;
-  float* head_ls = lds + L.s1;                       // SAC: log-std head
+  float* head = lds + L.s(0);
+  float* head_ls = lds + L.s(kHs / kMaxAct);         // SAC: log-std head
   float* v_aw3 = lds + L.vec;
   float* v_ab3 = v_aw3 + kH * d.actor.out;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -75,15 +76,15 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
   __syncthreads();
   hidden_layer<1>(buf, an, d.actor, pre, nullptr, wave, lane, NoTail());
   __syncthreads();
-  thin_dot<R>(buf, v_aw3, d.A, head, tid);
+  thin_wide<Rows32<1>>(buf, v_aw3, d.A, head, kHs, tid);
   const float sg = sigma ? sigma[agent] : 0.0f;
   const bool sac = d.algo == 1;
-  if (sac && sg > 0.0f) thin_dot<R>(buf, v_aw3 + d.A * kH, d.A, head_ls, tid);
+  if (sac && sg > 0.0f) thin_wide<Rows32<1>>(buf, v_aw3 + d.A * kH, d.A, head_ls, kHs, tid);
   __syncthreads();
   const HpDev hp = d.hp[agent];
   for (int e = tid; e < valid * d.A; e += kThreads) {
     const int r = e / d.A, j = e - r * d.A;
-    const float pre_act = head[r * kMaxAct + j] + v_ab3[j];
+    const float pre_act = head[r * kHs + j] + v_ab3[j];
     float a = tanhf(pre_act);
     if (sg > 0.0f) {
       const uint32_t el = (row_base + (uint32_t)(r0 + r)) * (uint32_t)d.A + (uint32_t)j;
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(kThreads) void k_act(PopDev d, const float* __restr
       normals4(blk, n4);
       const float nz = (el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0]);
       if (sac) {                                     // a sample of the policy itself, its std scaled by sigma
-        const float ls = fminf(fmaxf(head_ls[r * kMaxAct + j] + v_ab3[d.A + j], -20.0f), 2.0f);
+        const float ls = fminf(fmaxf(head_ls[r * kHs + j] + v_ab3[d.A + j], -20.0f), 2.0f);
         a = tanhf(pre_act + sg * expf(ls) * nz);
       } else {
         a = fminf(fmaxf(a + sg * nz, -1.0f), 1.0f);
@@ -161,7 +162,7 @@ hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {
 }
 hipError_t launch_act(const PopDev& d, const float* obs, int n, float* act, const float* sigma, uint32_t step,
                       uint32_t row_base, hipStream_t s) {
-  k_act<<<dim3((n + 31) / 32, d.P), dim3(kThreads), Lds<1>(d.O).bytes(vec_act(d)), s>>>(d, obs, n, act, sigma, step,
+  k_act<<<dim3((n + 31) / 32, d.P), dim3(kThreads), Lds<1>(d.O, kActScratch).bytes(vec_act(d)), s>>>(d, obs, n, act, sigma, step,
                                                                                         row_base);
   return hipGetLastError();
 }

@@ -6,6 +6,7 @@
 // so the values are reproducible bit for bit on any IEEE machine.  Biases,
 // Adam moments and padding are zeroed by the host before this kernel runs;
 // targets receive the same values as the online networks.
+#include <algorithm>
 #include "launch.h"
 #include "rng.h"
 
@@ -32,7 +33,7 @@ __global__ __launch_bounds__(256) void k_init(PopDev d, InitLimits lim) {
 }
 
 hipError_t launch_init(const PopDev& d, const InitLimits& lim, hipStream_t s) {
-  const int biggest = kH * kH;
+  const int biggest = kH * std::max(kH, std::max(d.D, d.actor.out));   // largest weight matrix of the three networks
   dim3 grid((biggest + 255) / 256, 9, d.P);
   hipLaunchKernelGGL(k_init, grid, dim3(256), 0, s, d, lim);
   return hipGetLastError();

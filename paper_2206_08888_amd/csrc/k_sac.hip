@@ -1,5 +1,6 @@
 // Kernels around the SAC chains of chains_sac.h (one launch per chain; the critic chain and
 // the weight-gradient tiles are the TD3 ones).
+#include <algorithm>
 #include "chains_sac.h"
 
 namespace pop {
@@ -46,6 +47,22 @@ hipError_t setup_sac_kernels() {
   POP_SET_LDS(k_sac_target_critic<Rows32<1>, Rows32<1>>);
 #undef POP_SET_LDS
   return hipSuccess;
+}
+
+namespace {
+size_t chain_lds(const PopDev& d, int rows, int regions, int vec) {
+  return rows == 16 ? LdsMap<16, 16>(d.D, regions).bytes(vec)
+         : rows == 32 ? LdsMap<32, 8>(d.D, regions).bytes(vec)
+                      : LdsMap<64, 8>(d.D, regions).bytes(vec);
+}
+}  // namespace
+
+size_t sac_lds_bytes(const PopDev& d) {
+  size_t m = chain_lds(d, d.rows_t, kSacScratch, vec_sac_target(d));
+  m = std::max(m, chain_lds(d, d.rows_a, kSacScratch, vec_sac_actor(d)));
+  m = std::max(m, chain_lds(d, d.rows_c, 3, vec_critic(d)));
+  m = std::max(m, Lds<1>(d.O, kActScratch).bytes(vec_act(d)));
+  return m;
 }
 
 hipError_t launch_sac_target(const PopDev& d, uint32_t t, hipStream_t s) {

@@ -30,6 +30,7 @@ hipError_t launch_sac_target(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_sac_actor(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_sac_target_critic(const PopDev& d, uint32_t t, hipStream_t s);   // target + critic chains in one launch
 hipError_t setup_sac_kernels();
+size_t sac_lds_bytes(const PopDev& d);   // largest dynamic LDS request of the SAC step's and the acting kernels
 
 // the step as one launch (k_step.hip); with_chains = 0: without the target and critic chains (launched
 // before); with_actor: some agent has its delayed actor step at t; launch_seq: 0, 1, 2, ... over the

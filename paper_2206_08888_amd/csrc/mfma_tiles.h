@@ -314,12 +314,13 @@ __device__ inline bool mask_bit(uint64_t mask, int mt, int nt, int v) {
 }
 
 // Thin products on the vector ALU (heads with 1..8 outputs, action gradient):
-// out[r*kMaxAct + j] = sum_{c<256} X[r][c] V[j*256 + c],  r < R, j < J, X and V in LDS.
+// out[r*stride + j] = sum_{c<256} X[r][c] V[j*256 + c],  r < R, j < J <= 8, X and V in LDS.
 // Thread t works on rows (t >> 3) + 32 i with column groups 32 q + 4 (t & 7);
 // 8 neighbouring lanes share a row and are summed with lane shuffles.
+// `stride`: row stride of `outl` (kMaxAct unless the caller keeps wider rows).
 template <int R>
 __device__ inline void thin_dot(const float* __restrict__ Xl, const float* __restrict__ V, int J,
-                                float* __restrict__ outl, int tid) {
+                                float* __restrict__ outl, int tid, int stride = kMaxAct) {
   const int p = tid & 7;
   for (int i = 0; i < R / 32; ++i) {
     const int r = (tid >> 3) + 32 * i;
@@ -345,7 +346,7 @@ __device__ inline void thin_dot(const float* __restrict__ Xl, const float* __res
         v += __shfl_xor(v, 1);
         v += __shfl_xor(v, 2);
         v += __shfl_xor(v, 4);
-        if (p == 0) outl[r * kMaxAct + j] = v;
+        if (p == 0) outl[r * stride + j] = v;
       }
     }
   }

@@ -181,11 +181,11 @@ __device__ inline uint64_t relu_store16(const Acc16& acc, const f32x4& bb, float
 
 __device__ inline bool mask_bit16(uint64_t mask, int nt, int v) { return (mask >> (4 * nt + v)) & 1ull; }
 
-// Thin products for 16 rows: out[r*kMaxAct + j] = sum_{c<256} X[r][c] V[j*256 + c], r < 16, j < J.
+// Thin products for 16 rows: out[r*stride + j] = sum_{c<256} X[r][c] V[j*256 + c], r < 16, j < J <= 8.
 // Thread t works on row t >> 4 with the column groups 64 q + 4 (t & 15); the 16 lanes of a
 // row are summed with lane shuffles.
 __device__ inline void thin_dot16(const float* __restrict__ Xl, const float* __restrict__ V, int J,
-                                  float* __restrict__ outl, int tid) {
+                                  float* __restrict__ outl, int tid, int stride = kMaxAct) {
   const int p = tid & 15, r = tid >> 4;
   float s[kMaxAct];
 #pragma unroll
@@ -210,7 +210,7 @@ __device__ inline void thin_dot16(const float* __restrict__ Xl, const float* __r
       v += __shfl_xor(v, 2);
       v += __shfl_xor(v, 4);
       v += __shfl_xor(v, 8);
-      if (p == 0) outl[r * kMaxAct + j] = v;
+      if (p == 0) outl[r * stride + j] = v;
     }
   }
 }

@@ -77,8 +77,9 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
   if (c->algo != POP_ALGO_TD3 && c->algo != POP_ALGO_SAC) return fail(ctx, POP_EINVAL, "unknown algorithm %d", c->algo);
   if (c->n_hidden != 2 || c->hidden[0] != kH || c->hidden[1] != kH)
     return fail(ctx, POP_EUNSUPPORTED, "hidden layers must be {256, 256}");
-  if (c->obs_dim + c->act_dim > kMaxIn) return fail(ctx, POP_EUNSUPPORTED, "obs_dim + act_dim must be <= %d", kMaxIn);
-  if (c->act_dim > kMaxAct) return fail(ctx, POP_EUNSUPPORTED, "act_dim must be <= %d", kMaxAct);
+  const int max_in = c->algo == POP_ALGO_SAC ? kSacMaxIn : kMaxIn, max_act = c->algo == POP_ALGO_SAC ? kSacMaxAct : kMaxAct;
+  if (c->obs_dim + c->act_dim > max_in) return fail(ctx, POP_EUNSUPPORTED, "obs_dim + act_dim must be <= %d", max_in);
+  if (c->act_dim > max_act) return fail(ctx, POP_EUNSUPPORTED, "act_dim must be <= %d", max_act);
   if (c->batch != 256) return fail(ctx, POP_EUNSUPPORTED, "batch must be 256");
   if (c->capacity > 0xFFFFFFFFll) return fail(ctx, POP_EUNSUPPORTED, "capacity must be below 2^32");
   if ((int64_t)c->P * c->batch > (1ll << 24)) return fail(ctx, POP_EUNSUPPORTED, "P * batch too large");
@@ -101,6 +102,9 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // Beside 16 P target workgroups of 16 rows, 64-row critic chains (8 P workgroups) keep the fused
   // target/critic launch of a small population within one workgroup per CU.
   d.rows_c = cls == 1 ? 32 : 64;
+  // Wide inputs (SAC only): the input tile grows with the fan-in, so the chains that also hold the
+  // actor's and the critics' head rows in LDS take 16 rows, the critic chain 32.
+  if (d.D > kMaxIn) { d.rows_t = d.rows_a = 16; d.rows_c = 32; }
   if (const char* env = getenv("POP_ROWS")) {       // 16, 32 or 64: override (measurements, tests)
     const int v = atoi(env);
     if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; }
@@ -110,6 +114,16 @@ void fill_dims(const pop_config& c, PopDev& d) {
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
   d.capacity = (uint64_t)c.capacity;
+}
+
+// The SAC chains size their LDS from the shapes: refuse what one CU cannot hold.
+int check_fit(const PopDev& d, pop_ctx* ctx) {
+  if (d.algo != POP_ALGO_SAC) return POP_OK;
+  const size_t need = sac_lds_bytes(d);
+  if (need > kLdsPerCU)
+    return fail(ctx, POP_EUNSUPPORTED, "obs_dim %d, act_dim %d need %zu bytes of LDS per workgroup, %d available", d.O, d.A,
+                need, kLdsPerCU);
+  return POP_OK;
 }
 
 Layout make_ws_layout(const PopDev& d) {
@@ -175,6 +189,7 @@ int64_t pop_workspace_bytes(const pop_config* cfg) {
   if (rc != POP_OK) return rc;
   PopDev d;
   fill_dims(*cfg, d);
+  if ((rc = check_fit(d, nullptr)) != POP_OK) return rc;
   return make_ws_layout(d).total;
 }
 
@@ -224,6 +239,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
     if ((rc = check_hparams(nullptr, hp[i], i)) != POP_OK) return rc;
   PopDev d;
   fill_dims(*cfg, d);
+  if ((rc = check_fit(d, nullptr)) != POP_OK) return rc;
   const Layout L = make_ws_layout(d);
   if (workspace_bytes < L.total)
     return fail(nullptr, POP_ENOMEM, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes,
@@ -512,7 +528,8 @@ int act_impl(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t 
   }
   float* st = (float*)(ctx->ws + ctx->lay.staging);
   const int64_t per_row = (int64_t)d.P * (d.O + d.A) * 4;
-  const int64_t piece = std::max<int64_t>(1, kStagingBytes / per_row);
+  if (per_row > kStagingBytes) return fail(ctx, POP_EUNSUPPORTED, "host arrays: one row of all agents exceeds the staging area; pass device pointers");
+  const int64_t piece = kStagingBytes / per_row;
   for (int64_t off = 0; off < n; off += piece) {
     const int k = (int)std::min<int64_t>(piece, n - off);
     float* s_obs = st;

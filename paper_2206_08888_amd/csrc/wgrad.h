@@ -149,6 +149,8 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   POP_MARK(54);
 }
 
+constexpr int kHeadBlock = 16;   // head columns whose Adam operands the small-tensor role holds in registers at once
+
 // One role of the weight-gradient step of one network (unit = agent in the actor phase, else network).
 // WAIT: consumers (the actor chain, for critic 1) and, if producer_in_launch, producers (the
 // chain of this network) run in the same launch -- hold before the first read of chain
@@ -216,16 +218,16 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
       return r;
     };
     const AdamRegs r_b1 = ld(i_b1), r_b2 = ld(i_b2), r_b3 = ld(i_b3);
-    AdamRegs r_w3[kMaxHead];
+    AdamRegs r_w3[kHeadBlock];                       // head columns go in blocks of kHeadBlock; the first is requested here
 #pragma unroll
-    for (int j = 0; j < kMaxHead; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j < out ? j : 0));
+    for (int j = 0; j < kHeadBlock; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j < out ? j : 0));
     setup();
     if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
     __syncthreads();
     const Adam adam = *sh_adam;
-    float gb1 = 0.0f, gb2 = 0.0f, gw3[kMaxHead], gb3 = 0.0f, loss = 0.0f, logp = 0.0f;
+    float gb1 = 0.0f, gb2 = 0.0f, gw3[kHeadBlock], gb3 = 0.0f, loss = 0.0f, logp = 0.0f;
 #pragma unroll
-    for (int j = 0; j < kMaxHead; ++j) gw3[j] = 0.0f;
+    for (int j = 0; j < kHeadBlock; ++j) gw3[j] = 0.0f;
 #pragma unroll 4
     for (int ch = 0; ch < chunks; ++ch) {
       if (actor_phase) {
@@ -233,7 +235,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
         gb1 += p[kAP_db1 + c];
         gb2 += p[kAP_db2 + c];
 #pragma unroll
-        for (int j = 0; j < kMaxHead; ++j)
+        for (int j = 0; j < kHeadBlock; ++j)
           if (j < out) gw3[j] += p[kAP_dW3 + c * out + j];
         if (c < out) gb3 += p[kAP_db3 + c];
         if (c == 0) { loss += p[kAP_loss]; logp += p[kAP_logp]; }
@@ -248,9 +250,26 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     adam_store<WAIT>(adam, r_b1, gb1, i_b1, th, mo, ve, tg, gr);
     adam_store<WAIT>(adam, r_b2, gb2, i_b2, th, mo, ve, tg, gr);
 #pragma unroll
-    for (int j = 0; j < kMaxHead; ++j)
+    for (int j = 0; j < kHeadBlock; ++j)
       if (j < out) adam_store<WAIT>(adam, r_w3[j], gw3[j], i_w3 + (uint32_t)j, th, mo, ve, tg, gr);
     if (c < out) adam_store<WAIT>(adam, r_b3, gb3, i_b3, th, mo, ve, tg, gr);
+#pragma unroll 1
+    for (int j0 = kHeadBlock; j0 < out; j0 += kHeadBlock) {   // wider heads (SAC with more than 8 actions; actor only)
+#pragma unroll
+      for (int j = 0; j < kHeadBlock; ++j) {
+        r_w3[j] = ld(i_w3 + (uint32_t)(j0 + j < out ? j0 + j : 0));
+        gw3[j] = 0.0f;
+      }
+      for (int ch = 0; ch < chunks; ++ch) {
+        const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart + kAP_dW3 + c * out + j0;
+#pragma unroll
+        for (int j = 0; j < kHeadBlock; ++j)
+          if (j0 + j < out) gw3[j] += p[j];
+      }
+#pragma unroll
+      for (int j = 0; j < kHeadBlock; ++j)
+        if (j0 + j < out) adam_store<WAIT>(adam, r_w3[j], gw3[j], i_w3 + (uint32_t)(j0 + j), th, mo, ve, tg, gr);
+    }
     if (actor_phase && d.algo == 1 && c == 0) {
       // SAC temperature: gradient of -alpha mean(log pi + target entropy) with respect to log_alpha, log pi
       // from this step's actor pass held constant; one Adam step with lr_alpha, no target

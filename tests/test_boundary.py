@@ -58,7 +58,8 @@ def test_workspace_size_and_net_sizes(lib):
     (dict(act_dim=9), pp.POP_EUNSUPPORTED),
     (dict(capacity=1 << 33), pp.POP_EUNSUPPORTED),
     (dict(algo=7), pp.POP_EINVAL),
-    (dict(algo=pp.POP_ALGO_SAC, obs_dim=376, act_dim=17), pp.POP_EUNSUPPORTED),   # the Humanoid shapes are not covered
+    (dict(algo=pp.POP_ALGO_SAC, obs_dim=100, act_dim=25), pp.POP_EUNSUPPORTED),
+    (dict(algo=pp.POP_ALGO_SAC, obs_dim=440, act_dim=17), pp.POP_EUNSUPPORTED),
 ])
 def test_bad_configs_are_rejected(lib, kwargs, code):
     base = dict(P=2, obs_dim=17, act_dim=6, hidden=(256, 256), batch=256, capacity=1000)
@@ -67,6 +68,13 @@ def test_bad_configs_are_rejected(lib, kwargs, code):
         pp.pop_workspace_bytes(pp.make_config(**base))
     assert e.value.code == code
     assert pp.pop_last_error() != ""
+
+
+def test_sac_takes_the_humanoid_shapes(lib):
+    cfg = pp.make_config(2, 376, 17, (256, 256), 256, 1000, algo=pp.POP_ALGO_SAC)
+    assert pp.pop_net_size(cfg, pp.PARAM_CODES["actor"]) == 376 * 256 + 256 + 256 * 256 + 256 + 256 * 34 + 34
+    assert pp.pop_net_size(cfg, pp.PARAM_CODES["critic1"]) == 393 * 256 + 256 + 256 * 256 + 256 + 256 + 1
+    assert pp.pop_workspace_bytes(cfg) > 2 * 1000 * (2 * 376 + 17 + 2) * 4
 
 
 def test_create_checks_arguments_before_any_gpu_work(lib):

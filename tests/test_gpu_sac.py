@@ -8,7 +8,7 @@ import pytest
 import paper_2206_08888_amd as pp
 import workloads
 from gpu_common import ensure_built, rel_l2
-from oracle import sac as oracle_sac
+from oracle import sac as oracle_sac, mlp as oracle_mlp, philox as oracle_philox
 
 pytestmark = pytest.mark.gpu
 
@@ -22,24 +22,32 @@ def _lib():
     ensure_built()
 
 
-def sac_hparams(P, config_id=2):
+def sac_hparams(P, config_id=2, act_dim=6):
     hps = workloads.hparams(config_id, P)                 # per-agent seed, lr, tau
     rng = np.random.default_rng(4242)
     for hp in hps:
-        hp["target_entropy"] = -6.0
+        hp["target_entropy"] = -float(act_dim)
         hp["lr_alpha"] = float(np.float32(np.exp(rng.uniform(np.log(1e-4), np.log(1e-3)))))
         hp["init_log_alpha"] = float(np.float32(rng.uniform(-1.0, 0.5)))
     return hps
 
 
-def make_sac_pair(P=2, capacity=2000, oracle=True, hps=None, agents=None):
-    hps = sac_hparams(P) if hps is None else hps
-    cfg = pp.make_config(P, 17, 6, (256, 256), 256, capacity, algo=pp.POP_ALGO_SAC)
+def make_sac_pair(P=2, capacity=2000, oracle=True, hps=None, agents=None, obs_dim=17, act_dim=6):
+    """Buffers hold the synthetic transitions of config 2 (HalfCheetah shapes), of config 3 for the Humanoid
+    shapes, else of config 2's stream drawn at the given shapes."""
+    hps = sac_hparams(P, act_dim=act_dim) if hps is None else hps
+    cfg = pp.make_config(P, obs_dim, act_dim, (256, 256), 256, capacity, algo=pp.POP_ALGO_SAC)
     gpu = pp.Population(cfg, hps)
     agents = list(range(P)) if agents is None else list(agents)
-    orc = oracle_sac.Population([hps[i] for i in agents], 17, 6, [256, 256], 256, capacity) if oracle else None
+    orc = oracle_sac.Population([hps[i] for i in agents], obs_dim, act_dim, [256, 256], 256, capacity) if oracle else None
     for i in range(P):
-        for tr in workloads.transition_chunks(2, i, capacity):
+        if (obs_dim, act_dim) == (17, 6):
+            chunks = workloads.transition_chunks(2, i, capacity)
+        elif (obs_dim, act_dim) == (376, 17):
+            chunks = workloads.transition_chunks(3, i, capacity)
+        else:
+            chunks = [workloads.transitions(2, i, capacity, obs_dim=obs_dim, act_dim=act_dim, salt=1)]
+        for tr in chunks:
             gpu.insert(i, **tr)
             if oracle and i in agents:
                 orc.insert(agents.index(i), **tr)
@@ -190,4 +198,116 @@ def test_copy_agent_carries_the_temperature():
             td3.get_params(0, "log_alpha")
         finally:
             td3.close()
+    gpu.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# Wider shapes: Humanoid-v2 (obs 376, act 17: the SAC configuration of the workload list; the actor
+# head has 34 outputs, the critics' first layer a fan-in of 393) and one in between (obs 40, act 10:
+# a head of 20 columns on the ordinary row classes).
+WIDE = [(376, 17), (40, 10)]
+
+
+def relu_margin(net, x):
+    """Smallest |pre-activation| of the hidden layers of `net` on the rows of x."""
+    _, cache = oracle_mlp.forward(net, x, 'linear')
+    return min(float(np.abs(z).min()) for z in cache[1][:-1])
+
+
+# fp32 products with a fan-in of a few hundred carry absolute errors of a few 1e-6 at these scales; a hidden unit
+# whose fp64 pre-activation is closer to zero than this may switch sides in fp32, which changes the gradient by
+# about 1/B of one sample's share (1e-3 relative): only such a network may miss the sharp tolerance
+KINK = 8e-6
+
+
+@pytest.mark.parametrize("obs_dim,act_dim", WIDE)
+def test_wide_shapes_one_step_matches_oracle(obs_dim, act_dim):
+    gpu, orc, agents = make_sac_pair(capacity=700, obs_dim=obs_dim, act_dim=act_dim)
+    for i in agents:
+        for w in NETS5:
+            assert np.array_equal(gpu.get_params(i, w), orc.get_params(i, w).astype(np.float32)), (i, w)
+    # how close the oracle's ReLUs come to their kinks in this step, per agent and network
+    margin = {}
+    actors = [oracle_mlp.copy_net(ag.actor) for ag in orc.agents]
+    for i, ag in enumerate(orc.agents):
+        idx = oracle_philox.sample_indices(ag.seed, 0, ag.B, ag.buffer.count)
+        s, a = (x.astype(np.float64) for x in ag.buffer.gather(idx)[:2])
+        for k in range(2):
+            margin[i, "critic%d" % (k + 1)] = relu_margin(ag.critic[k], np.concatenate([s, a], axis=1))
+    gpu.set_debug(True)
+    gpu.update(1); orc.update(1)
+    for i, ag in enumerate(orc.agents):                 # the actor pass runs through the updated critics
+        idx = ag.last["idx"]
+        s = ag.buffer.gather(idx)[0].astype(np.float64)
+        a_pi = oracle_sac.sample_policy(actors[i], s, ag.last["eps1"])[0]
+        x = np.concatenate([s, a_pi], axis=1)
+        margin[i, "actor"] = min(relu_margin(actors[i], s), relu_margin(ag.critic[0], x), relu_margin(ag.critic[1], x))
+    loose = []
+    for i in agents:
+        for w in ("critic1", "critic2", "actor"):
+            e = rel_l2(gpu.get_params(i, "g_" + w), orc.get_params(i, "g_" + w))
+            sharp = e <= 1e-5
+            if not sharp:                                 # only a ReLU on its kink explains more
+                assert margin[i, w] <= KINK and e <= 2e-2, (i, w, e, margin[i, w])
+                loose.append((i, w, e, margin[i, w]))
+            for mom, mtol in (("m_", 2e-5), ("v_", 4e-5)):
+                e = rel_l2(gpu.get_params(i, mom + w), orc.get_params(i, mom + w))
+                assert e <= (mtol if sharp else 4e-2), (i, mom + w, e)
+    print("networks compared at the loose tolerance (agent, network, error, ReLU margin): %s" % loose)
+    assert len(loose) <= 2, loose                         # the sharp comparison must cover most networks
+    # Adam's first step moves every weight by about lr * sign(g): where the kink flipped the signs of the smallest
+    # gradient entries the parameters differ by 2 lr there
+    kinked = {(i, w) for i, w, _, _ in loose}
+    for i in agents:
+        for w in NETS5:
+            tol = 2e-3 if (i, w.replace("t_", "")) in kinked else 1e-4
+            e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
+            assert e <= tol, (i, w, e, tol)
+        assert abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(i, "log_alpha")[0])) <= 2e-6
+    gpu.close()
+
+
+@pytest.mark.parametrize("obs_dim,act_dim", WIDE)
+def test_wide_shapes_forced_single_steps_match_oracle(obs_dim, act_dim):
+    """Step 0 is judged by its gradients in the one-step test: Adam's first update is lr * sign(g), which turns a
+    ReLU resolved differently in fp32 (it happens at these fan-ins) into 2 lr on the smallest gradient entries."""
+    gpu, orc, agents = make_sac_pair(capacity=700, obs_dim=obs_dim, act_dim=act_dim)
+    worst = 0.0
+    for step in range(12):
+        force(gpu, orc, agents)
+        gpu.update(1); orc.update(1)
+        for j, i in enumerate(agents):
+            for w in NETS5:
+                e = rel_l2(gpu.get_params(i, w), orc.get_params(j, w))
+                if step > 0:
+                    worst = max(worst, e)
+                assert e <= (2e-3 if step == 0 else 1e-4), (step, i, w, e)
+            assert abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(j, "log_alpha")[0])) <= 2e-6
+    print("forced SAC steps at obs %d, act %d: worst parameter rel-L2 %.3e" % (obs_dim, act_dim, worst))
+    gpu.close()
+
+
+@pytest.mark.parametrize("obs_dim,act_dim", WIDE)
+def test_wide_shapes_in_a_mid_size_population(obs_dim, act_dim):
+    """P = 20: the 32-row class for the narrower shape; agents 0 and 19 against the oracle over two free steps."""
+    hps = sac_hparams(20, act_dim=act_dim)
+    gpu, orc, agents = make_sac_pair(P=20, capacity=400, hps=hps, agents=[0, 19], obs_dim=obs_dim, act_dim=act_dim)
+    gpu.update(2); orc.update(2)
+    compare(gpu, orc, agents, 1e-4, "two SAC steps at P = 20, obs %d, act %d" % (obs_dim, act_dim))
+    gpu.close()
+
+
+@pytest.mark.parametrize("obs_dim,act_dim", WIDE)
+def test_wide_shapes_act_matches_oracle(obs_dim, act_dim):
+    gpu, orc, agents = make_sac_pair(capacity=400, obs_dim=obs_dim, act_dim=act_dim)
+    gpu.update(2); orc.update(2)
+    rng = np.random.default_rng(9)
+    obs = rng.standard_normal((2, 45, obs_dim)).astype(np.float32)
+    wide = obs_dim > 64                                   # fp32 rounding of the first layer grows with its fan-in
+    err = float(np.abs(gpu.act(obs) - orc.act(obs.astype(np.float64))).max())
+    assert err <= (2e-5 if wide else 5e-6), err
+    got = gpu.act(obs, sigma=[1.0, 0.0], step=7)
+    want0 = orc.agents[0].act(obs[0].astype(np.float64), deterministic=False, step=7)
+    err = float(np.abs(got[0] - want0).max())
+    assert err <= (5e-5 if wide else 2e-5), err
     gpu.close()

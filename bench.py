@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the population TD3 update step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1|2|4] [--no-cpu] [--no-secondary]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..5] [--no-cpu] [--no-secondary]
 
 A "step" is one update step of the whole population (every kernel of the hot
 path: replay sample + gather, target chain, critic chain, critic weight
@@ -168,7 +168,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=1, choices=(0, 1, 2, 4, 5))
+    ap.add_argument("--config", type=int, default=1, choices=(0, 1, 2, 3, 4, 5))
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-secondary", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",

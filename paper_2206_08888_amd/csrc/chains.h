@@ -87,16 +87,52 @@ __device__ inline void load_input(float* Xl, int xld, const float* rows, int row
   }
 }
 
+// The same for wide rows: wavefront w takes the rows w, w + 4, ..., its lanes consecutive columns
+// (coalesced, no index division, every load independent of the others).
+template <int R>
+__device__ inline void load_input_wide(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
+                                       int tid) {
+  const int wave = tid >> 6, lane = tid & 63;
+  for (int r = wave; r < R; r += kThreads / 64) {
+    const float* src = rows + (size_t)r * row_stride + c0;
+    const bool live = r < valid;
+#pragma unroll 4
+    for (int c = lane; c < xld; c += 64) Xl[r * xld + c] = (live && c < n) ? src[c] : 0.0f;
+  }
+}
+
+// Copies into LDS ahead of a chain.  The loads of a thread are requested eight at a time before the
+// first of them is used: as a plain loop every element would wait out its own trip to memory.
 __device__ inline void stage_vector(float* dst, const float* __restrict__ src, int n, int tid) {
-  for (int e = tid; e < n; e += kThreads) dst[e] = src[e];
+  constexpr int U = 8;
+  for (int e0 = tid; e0 < n; e0 += U * kThreads) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int e = e0 + u * kThreads;
+      v[u] = src[e < n ? e : n - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int e = e0 + u * kThreads;
+      if (e < n) dst[e] = v[u];
+    }
+  }
 }
 
 // Stage a head weight W3[256][J] as J rows of 256 (so that the thin products read it with
-// 16-byte LDS loads like any other row vector).
+// 16-byte LDS loads like any other row vector); thread c moves the J weights of hidden unit c.
+static_assert(kThreads == kH, "stage_head: one thread per hidden unit");
 __device__ inline void stage_head(float* dst, const float* __restrict__ src, int J, int tid) {
-  for (int e = tid; e < kH * J; e += kThreads) {
-    const int c = e / J, j = e - c * J;
-    dst[j * kH + c] = src[e];
+  constexpr int U = 8;
+  const float* row = src + tid * J;
+  for (int j0 = 0; j0 < J; j0 += U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = row[j0 + u < J ? j0 + u : J - 1];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (j0 + u < J) dst[(j0 + u) * kH + tid] = v[u];
   }
 }
 
@@ -166,6 +202,10 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
   using Pre = LayerPre<MT>;
   using WtBlock = WeightBlock<MT, true>;
   __device__ static inline void load_wt(WtBlock& wt, const float* W, int wave, int lane) { wt.load(W, 0, wave, lane); }
+  __device__ static inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
+                                           int tid) {
+    pop::load_input<R>(Xl, xld, rows, row_stride, c0, n, valid, tid);
+  }
   template <bool THROUGH>
   __device__ static inline uint64_t first_layer(const float* Xs, int xld, const float* net, const NetLayout& L,
                                                 const Pre& pre, float* Yl, float* Yg, int wave, int lane) {
@@ -234,6 +274,10 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
   };
   using WtBlock = WeightBlock16<true>;
   __device__ static inline void load_wt(WtBlock& wt, const float* W, int wave, int lane) { wt.load(W, 0, wave, lane); }
+  __device__ static inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
+                                           int tid) {
+    pop::load_input<R>(Xl, xld, rows, row_stride, c0, n, valid, tid);
+  }
   template <bool THROUGH>
   __device__ static inline uint64_t first_layer(const float* Xs, int xld, const float* net, const NetLayout& L,
                                                 const Pre& pre, float* Yl, float* Yg, int wave, int lane) {
@@ -308,6 +352,40 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
       for (int nt = 0; nt < 4; ++nt) o[nt] = mask_bit16(mask, nt, v) ? rv * cv[nt] : 0.0f;
       *reinterpret_cast<f32x4*>(&buf[row * kLda + 64 * wave + 4 * c]) = o;
     }
+  }
+};
+
+// The same tiles for first layers with a fan-in of several hundred (the SAC Humanoid shapes): only the
+// first-layer product differs (software-pipelined beyond the prefetched rows).
+template <int MT>
+struct Rows32Deep : Rows32<MT> {
+  using Pre = typename Rows32<MT>::Pre;
+  __device__ static inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
+                                           int tid) {
+    load_input_wide<32 * MT>(Xl, xld, rows, row_stride, c0, n, valid, tid);
+  }
+  template <bool THROUGH>
+  __device__ static inline uint64_t first_layer(const float* Xs, int xld, const float* net, const NetLayout& L,
+                                                const Pre& pre, float* Yl, float* Yg, int wave, int lane) {
+    Acc<MT> acc;
+    acc.zero();
+    gemm_xw_deep<MT>(Xs, xld, L.in, net + L.w1, pre.w1, wave, lane, acc);
+    return relu_store<MT, THROUGH>(acc, pre.b1, Yl, Yg, wave, lane);
+  }
+};
+
+struct Rows16Deep : Rows16 {
+  __device__ static inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
+                                           int tid) {
+    load_input_wide<16>(Xl, xld, rows, row_stride, c0, n, valid, tid);
+  }
+  template <bool THROUGH>
+  __device__ static inline uint64_t first_layer(const float* Xs, int xld, const float* net, const NetLayout& L,
+                                                const Pre& pre, float* Yl, float* Yg, int wave, int lane) {
+    Acc16 acc;
+    acc.zero();
+    gemm_xw_deep16(Xs, xld, L.in, net + L.w1, pre.w1, wave, lane, acc);
+    return relu_store16<THROUGH>(acc, pre.b1, Yl, Yg, wave, lane);
   }
 };
 
@@ -412,7 +490,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
   if (tid < 2) v_cb3[tid] = (tid == 0 ? tc0 : tc1)[d.critic.b3];
   POP_MARK(30);
-  load_input<R>(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
+  G::load_input(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
   __syncthreads();
   POP_MARK(31);
 
@@ -498,7 +576,7 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
   const size_t act_off = ((size_t)net * d.B + r0) * kH;
   float* part = d.cpart + ((size_t)net * (d.B / R) + chunk) * kCPart;
   stage_vector(v_w3, cn + d.critic.w3, kH, tid);
-  load_input<R>(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
+  G::load_input(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
   float yv = 0.0f, b3 = 0.0f;
   if (tid < R) {
     if (!WAIT) yv = d.y[(size_t)agent * d.B + r0 + tid];
@@ -610,7 +688,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
     cb3 = cn[d.critic.b3];
   };
   if (!WAIT) stage_critic();
-  load_input<R>(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
+  G::load_input(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
   __syncthreads();
 
   const uint64_t mask_a1 = G::template first_layer<WAIT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
@@ -726,7 +804,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
     }
 #pragma unroll
     for (int j = 0; j < kMaxAct; ++j)
-      if (j < A) put<WAIT>(part + kAP_dW3 + c * A + j, gw3[j]);
+      if (j < A) put<WAIT>(part + kAP_dW3 + j * kH + c, gw3[j]);
     put<WAIT>(part + kAP_db2 + c, gb2);
   }
   __syncthreads();

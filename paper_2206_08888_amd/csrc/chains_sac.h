@@ -45,8 +45,11 @@ constexpr int kSacRegion = kSs / kMaxAct;
 constexpr int kSacScratch = 9 * kSacRegion;
 static_assert(kSs % kMaxAct == 0 && 2 * kSs >= kMaxHead, "dz3 rows of kMaxHead floats fit two scratch blocks");
 
-inline int vec_sac_target(const PopDev& d) { return kH * 2 * d.A + kMaxHead + 2 * kH + 8; }
-inline int vec_sac_actor(const PopDev& d) { return kH * 2 * d.A + kMaxHead + 2 * kH + 2 * d.A * kH + 8; }
+// vectors the chains keep in LDS: the actor's head bias, the two critic heads and their biases (the wide
+// operands -- the actor's head, the critics' first-layer rows of the action -- go through the matrix pipe
+// straight from global memory)
+inline int vec_sac_target(const PopDev&) { return kMaxHead + 2 * kH + 8; }
+inline int vec_sac_actor(const PopDev&) { return kMaxHead + 2 * kH + 8; }
 
 // ---------------------------------------------------------------------------------------------
 // Target chain.  One workgroup per (agent, chunk).
@@ -57,11 +60,9 @@ __device__ __forceinline__ void sac_target_chain(const PopDev& d, uint32_t t, in
   const int A = d.A;
   float* Xs = lds;
   float* buf = lds + L.buf;
-  float* hm = lds + L.s(0);                          // mean head, later thin-product scratch
-  float* hl = lds + L.s(kSacRegion);                 // log-std head, later the terms of log pi
+  float* hd = lds + L.s(0);                          // [R][kMaxHead]: means | log-stds (later the terms of log pi)
   float* qmin = lds + L.s(2 * kSacRegion);           // [R] min of the target critics, [R..2R) log pi
-  float* v_aw3 = lds + L.vec;                        // [2A][256]
-  float* v_ab3 = v_aw3 + kH * 2 * A;                 // [kMaxHead]
+  float* v_ab3 = lds + L.vec;                        // [kMaxHead]
   float* v_cw3 = v_ab3 + kMaxHead;                   // [2][256]
   float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -74,52 +75,59 @@ __device__ __forceinline__ void sac_target_chain(const PopDev& d, uint32_t t, in
   const HpDev hp = d.hp[agent];
   const float alpha = expf(d.log_alpha[agent]);
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
-  stage_head(v_aw3, an + d.actor.w3, 2 * A, tid);
+  POP_MARK(0);
   stage_vector(v_ab3, an + d.actor.b3, 2 * A, tid);
   stage_vector(v_cw3, tc0 + d.critic.w3, kH, tid);
   stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
   if (tid < 2) v_cb3[tid] = (tid == 0 ? tc0 : tc1)[d.critic.b3];
-  load_input<R>(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
+  G::load_input(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
   __syncthreads();
+  POP_MARK(1);
 
   G::template first_layer<false>(Xs, L.xld, an, d.actor, pre, buf, nullptr, wave, lane);
   __syncthreads();
+  POP_MARK(2);
   G::template hidden_layer<false>(buf, an, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
-  thin_wide<G>(buf, v_aw3, A, hm, kSs, tid);
-  thin_wide<G>(buf, v_aw3 + A * kH, A, hl, kSs, tid);
+  POP_MARK(3);
+  head_mfma<R>(buf, an + d.actor.w3, 2 * A, hd, kMaxHead, wave, lane);
   __syncthreads();
+  POP_MARK(4);
   for (int e = tid; e < R * A; e += kThreads) {
     const int r = e / A, j = e - r * A;
-    const float mu = hm[r * kSs + j] + v_ab3[j];
-    const float ls = fminf(fmaxf(hl[r * kSs + j] + v_ab3[A + j], kLogStdMin), kLogStdMax);
+    const float mu = hd[r * kMaxHead + j] + v_ab3[j];
+    const float ls = fminf(fmaxf(hd[r * kMaxHead + A + j] + v_ab3[A + j], kLogStdMin), kLogStdMax);
     const float eps = normal_at(hp, (uint32_t)((r0 + r) * A + j), t, kStreamSacS2);
     const float u = mu + expf(ls) * eps;
     Xs[r * L.xld + d.O + j] = tanhf(u);
-    hl[r * kSs + j] = -0.5f * eps * eps - ls - kHalfLog2Pi - 2.0f * (kLn2 - u - softplusf(-2.0f * u));
+    hd[r * kMaxHead + A + j] = -0.5f * eps * eps - ls - kHalfLog2Pi - 2.0f * (kLn2 - u - softplusf(-2.0f * u));
   }
   __syncthreads();
   if (tid < R) {
     float lp = 0.0f;
-    for (int j = 0; j < A; ++j) lp += hl[tid * kSs + j];
+    for (int j = 0; j < A; ++j) lp += hd[tid * kMaxHead + A + j];
     qmin[R + tid] = lp;
   }
+  POP_MARK(5);
 
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const float* tc = k == 0 ? tc0 : tc1;
     G::template first_layer<false>(Xs, L.xld, tc, d.critic, pre, buf, nullptr, wave, lane);
     __syncthreads();
+    POP_MARK(6 + 3 * k);
     G::template hidden_layer<false>(buf, tc, d.critic, pre, nullptr, wave, lane,
                                     [&]() { if (k == 0) pre.load(tc1, d.critic, wave, lane); });
     __syncthreads();
-    G::thin(buf, v_cw3 + k * kH, 1, hm, tid, kSs);
+    POP_MARK(7 + 3 * k);
+    G::thin(buf, v_cw3 + k * kH, 1, hd, tid, kMaxHead);
     __syncthreads();
     if (tid < R) {
-      const float q = hm[tid * kSs] + v_cb3[k];
+      const float q = hd[tid * kMaxHead] + v_cb3[k];
       qmin[tid] = k == 0 ? q : fminf(qmin[tid], q);
     }
     __syncthreads();
+    POP_MARK(8 + 3 * k);
   }
   if (tid < R) {
     const float rew = rows[(size_t)tid * d.row + d.D];
@@ -128,18 +136,22 @@ __device__ __forceinline__ void sac_target_chain(const PopDev& d, uint32_t t, in
     d.y[(size_t)agent * d.B + r0 + tid] = yv;
     publish_y(d, (size_t)agent * d.B + r0 + tid, t, yv);
   }
+  POP_MARK(12);
 }
 
 // Backward through the actor's head for one chunk, thread c = hidden unit c:
 //   gW3[c][j] = sum_r h2[r][c] dz3[r][j];  dz2[r][c] = [h2[r][c] > 0] sum_j dz3[r][j] W3[c][j]
-// buf: h2 in, dz2 out (LDS tile, row stride kLda); dz3: [R][kMaxHead], columns >= H2 hold zeros;
+// buf: h2 in, dz2 out (LDS tile, row stride kLda); dz3: [R][kMaxHead], columns >= H2 hold zeros; W3: the
+// head's weights [256][H2] in global memory;
 // NC: head columns handled (a multiple of 4, >= H2).
 template <int R, int NC>
-__device__ __forceinline__ void sac_head_backward(float* buf, const float* dz3, const float* v_aw3, int H2, float* zg,
-                                                  float* part, int c) {
+__device__ __forceinline__ void sac_head_backward(float* buf, const float* dz3, const float* __restrict__ W3, int H2,
+                                                  float* zg, float* part, int c) {
   float w3[NC], gw3[NC];
 #pragma unroll
-  for (int j = 0; j < NC; ++j) { w3[j] = j < H2 ? v_aw3[j * kH + c] : 0.0f; gw3[j] = 0.0f; }
+  for (int j = 0; j < NC; ++j) { w3[j] = W3[c * H2 + (j < H2 ? j : 0)]; gw3[j] = 0.0f; }
+#pragma unroll
+  for (int j = 0; j < NC; ++j) w3[j] = j < H2 ? w3[j] : 0.0f;
   float gb2 = 0.0f;
   zg += c;
 #pragma unroll 1
@@ -162,7 +174,7 @@ __device__ __forceinline__ void sac_head_backward(float* buf, const float* dz3, 
   }
 #pragma unroll
   for (int j = 0; j < NC; ++j)
-    if (j < H2) part[kAP_dW3 + c * H2 + j] = gw3[j];
+    if (j < H2) part[kAP_dW3 + j * kH + c] = gw3[j];
   part[kAP_db2 + c] = gb2;
 }
 
@@ -180,19 +192,17 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
   const int A = d.A, H2 = 2 * d.A;
   float* Xs = lds;
   float* buf = lds + L.buf;
-  float* hm = lds + L.s(0);                          // mean head -> terms of log pi -> thin-product scratch
-  float* hl = lds + L.s(kSacRegion);                 // log-std head -> std * eps
+  float* hd = lds + L.s(0);                          // [R][kMaxHead]: means -> terms of log pi -> thin-product scratch
+                                                     //                | log-stds -> std * eps
   float* ap = lds + L.s(2 * kSacRegion);             // a = tanh(u)
   float* ins = lds + L.s(3 * kSacRegion);            // 1 where the log-std was inside its range
   float* qv = lds + L.s(4 * kSacRegion);             // [R] q1 | q2 | seed1 | seed2 | log pi
   float* da1 = lds + L.s(5 * kSacRegion);
   float* da2 = lds + L.s(6 * kSacRegion);
   float* dz3 = lds + L.s(7 * kSacRegion);            // [R][kMaxHead] (two blocks)
-  float* v_aw3 = lds + L.vec;                        // [2A][256] actor head
-  float* v_ab3 = v_aw3 + kH * H2;                    // [kMaxHead]
+  float* v_ab3 = lds + L.vec;                        // [kMaxHead]
   float* v_cw3 = v_ab3 + kMaxHead;                   // [2][256] critic heads
-  float* v_cwa = v_cw3 + 2 * kH;                     // [2][A][256] critic first-layer rows of the action inputs
-  float* v_cb3 = v_cwa + 2 * A * kH;                 // [2]
+  float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r0 = chunk * R;
   const HpDev hp = d.hp[agent];
@@ -205,28 +215,26 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)agent * d.B + r0) * kH;
   float* part = d.apart + ((size_t)agent * (d.B / R) + chunk) * kAPart;
-  stage_head(v_aw3, an + d.actor.w3, H2, tid);
+  POP_MARK(20);
   stage_vector(v_ab3, an + d.actor.b3, H2, tid);
-  for (int k = 0; k < 2; ++k) {
-    stage_vector(v_cw3 + k * kH, cn[k] + d.critic.w3, kH, tid);
-    stage_vector(v_cwa + k * A * kH, cn[k] + d.critic.w1 + d.O * kH, A * kH, tid);
-  }
+  for (int k = 0; k < 2; ++k) stage_vector(v_cw3 + k * kH, cn[k] + d.critic.w3, kH, tid);
   if (tid < 2) v_cb3[tid] = cn[tid][d.critic.b3];
-  load_input<R>(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
+  G::load_input(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
   __syncthreads();
+  POP_MARK(21);
 
   const uint64_t mask_a1 = G::template first_layer<false>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
   __syncthreads();
   G::template hidden_layer<false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
                                   [&]() { pre.load(cn[0], d.critic, wave, lane); });
   __syncthreads();
-  thin_wide<G>(buf, v_aw3, A, hm, kSs, tid);
-  thin_wide<G>(buf, v_aw3 + A * kH, A, hl, kSs, tid);
+  POP_MARK(22);
+  head_mfma<R>(buf, an + d.actor.w3, H2, hd, kMaxHead, wave, lane);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
-    const int r = e / A, j = e - r * A, o = r * kSs + j;
-    const float mu = hm[o] + v_ab3[j];
-    const float ls_raw = hl[o] + v_ab3[A + j];
+    const int r = e / A, j = e - r * A, o = r * kSs + j, om = r * kMaxHead + j, ol = om + A;
+    const float mu = hd[om] + v_ab3[j];
+    const float ls_raw = hd[ol] + v_ab3[A + j];
     const float ls = fminf(fmaxf(ls_raw, kLogStdMin), kLogStdMax);
     const float eps = normal_at(hp, (uint32_t)((r0 + r) * A + j), t, kStreamSacS);
     const float se = expf(ls) * eps;
@@ -234,16 +242,17 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
     const float a = tanhf(u);
     ap[o] = a;
     Xs[r * L.xld + d.O + j] = a;
-    hl[o] = se;
+    hd[ol] = se;
     ins[o] = (ls_raw >= kLogStdMin && ls_raw <= kLogStdMax) ? 1.0f : 0.0f;
-    hm[o] = -0.5f * eps * eps - ls - kHalfLog2Pi - 2.0f * (kLn2 - u - softplusf(-2.0f * u));
+    hd[om] = -0.5f * eps * eps - ls - kHalfLog2Pi - 2.0f * (kLn2 - u - softplusf(-2.0f * u));
   }
   __syncthreads();
   if (tid < R) {
     float lp = 0.0f;
-    for (int j = 0; j < A; ++j) lp += hm[tid * kSs + j];
+    for (int j = 0; j < A; ++j) lp += hd[tid * kMaxHead + j];
     qv[4 * R + tid] = lp;
   }
+  POP_MARK(23);
 
   // both critics forward on [s, a]; the ReLU patterns of both layers stay in registers
   uint64_t mask1[2], mask2[2];
@@ -257,10 +266,11 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
       else G::load_wt(wt, cn[0] + d.critic.w2, wave, lane);
     });
     __syncthreads();
-    G::thin(buf, v_cw3 + k * kH, 1, hm, tid, kSs);
+    G::thin(buf, v_cw3 + k * kH, 1, hd, tid, kMaxHead);
     __syncthreads();
-    if (tid < R) qv[k * R + tid] = hm[tid * kSs] + v_cb3[k];
+    if (tid < R) qv[k * R + tid] = hd[tid * kMaxHead] + v_cb3[k];
     __syncthreads();
+    POP_MARK(24 + k);
   }
   if (tid < 64) {                                    // R <= 64: one wavefront covers the chunk
     float term = 0.0f, lp = 0.0f;
@@ -291,10 +301,11 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
     });                                              // buf = dz1 of critic k
     __syncthreads();
-    thin_wide<G>(buf, v_cwa + k * A * kH, A, k == 0 ? da1 : da2, kSs, tid);
+    head_mfma_t<R>(buf, cn[k] + d.critic.w1 + d.O * kH, A, k == 0 ? da1 : da2, kSs, wave, lane);
     if (k == 0) G::load_wt(wt, cn[1] + d.critic.w2, wave, lane);
     else G::load_wt(wt, an + d.actor.w2, wave, lane);
     __syncthreads();
+    POP_MARK(26 + k);
   }
 
   // through the sampling into the actor's head
@@ -306,7 +317,7 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
       const int j = c < A ? c : c - A, o = r * kSs + j;
       const float a = ap[o];
       const float du = (da1[o] + da2[o]) * (1.0f - a * a) + ab * 2.0f * a;
-      g = c < A ? du : (du * hl[o] - ab) * ins[o];
+      g = c < A ? du : (du * hd[r * kMaxHead + A + j] - ab) * ins[o];
     }
     dz3[e] = g;                                      // unused columns are kept at zero
   }
@@ -319,11 +330,14 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
     for (int r = 0; r < R; ++r) s += dz3[r * kMaxHead + tid];
     part[kAP_db3 + tid] = s;
   }
+  POP_MARK(28);
   // actor head backward, one thread per hidden unit; the common small heads stay in 16 registers
-  if (H2 <= 16) sac_head_backward<R, 16>(buf, dz3, v_aw3, H2, d.adZ2 + act_off, part, tid);
-  else sac_head_backward<R, kMaxHead>(buf, dz3, v_aw3, H2, d.adZ2 + act_off, part, tid);
+  if (H2 <= 16) sac_head_backward<R, 16>(buf, dz3, an + d.actor.w3, H2, d.adZ2 + act_off, part, tid);
+  else sac_head_backward<R, kMaxHead>(buf, dz3, an + d.actor.w3, H2, d.adZ2 + act_off, part, tid);
   __syncthreads();
+  POP_MARK(29);
   G::template input_grad_to_global<false>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  POP_MARK(30);
 }
 
 }  // namespace pop

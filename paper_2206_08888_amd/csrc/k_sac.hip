@@ -40,9 +40,13 @@ hipError_t setup_sac_kernels() {
   POP_SET_LDS(k_sac_target<Rows16>);
   POP_SET_LDS(k_sac_target<Rows32<1>>);
   POP_SET_LDS(k_sac_target<Rows32<2>>);
+  POP_SET_LDS(k_sac_target<Rows16Deep>);
+  POP_SET_LDS(k_sac_target<Rows32Deep<1>>);
   POP_SET_LDS(k_sac_actor<Rows16>);
   POP_SET_LDS(k_sac_actor<Rows32<1>>);
   POP_SET_LDS(k_sac_actor<Rows32<2>>);
+  POP_SET_LDS(k_sac_actor<Rows16Deep>);
+  POP_SET_LDS(k_sac_actor<Rows32Deep<1>>);
   POP_SET_LDS(k_sac_target_critic<Rows16, Rows32<2>>);
   POP_SET_LDS(k_sac_target_critic<Rows32<1>, Rows32<1>>);
 #undef POP_SET_LDS
@@ -68,7 +72,11 @@ size_t sac_lds_bytes(const PopDev& d) {
 hipError_t launch_sac_target(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_t)), block(kThreads);
   const int vec = vec_sac_target(d);
-  if (d.rows_t == 16) k_sac_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  if (d.D > kMaxIn) {                                // wide inputs: 16 rows, pipelined first layers
+    if (d.rows_t == 16) k_sac_target<Rows16Deep><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+    else if (d.rows_t == 32) k_sac_target<Rows32Deep<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+    else return hipErrorInvalidValue;
+  } else if (d.rows_t == 16) k_sac_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   else if (d.rows_t == 32) k_sac_target<Rows32<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   else k_sac_target<Rows32<2>><<<grid, block, LdsMap<64, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   return hipGetLastError();
@@ -78,6 +86,7 @@ hipError_t launch_sac_target_critic(const PopDev& d, uint32_t t, hipStream_t s) 
   const int nt = xcd_grid(d.P, d.B / d.rows_t), nc = xcd_grid(2 * d.P, d.B / d.rows_c);
   const dim3 grid(nt + nc), block(kThreads);
   const int vec = vec_sac_target(d);                 // larger than the critic chain's
+  if (d.D > kMaxIn) return hipErrorInvalidValue;     // wide inputs run the two chains as separate launches
   if (d.rows_t == 16 && d.rows_c == 64) {
     const size_t a = LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), b = Lds<2>(d.D).bytes(vec_critic(d));
     k_sac_target_critic<Rows16, Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
@@ -93,7 +102,11 @@ hipError_t launch_sac_target_critic(const PopDev& d, uint32_t t, hipStream_t s) 
 hipError_t launch_sac_actor(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_a)), block(kThreads);
   const int vec = vec_sac_actor(d);
-  if (d.rows_a == 16) k_sac_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  if (d.D > kMaxIn) {
+    if (d.rows_a == 16) k_sac_actor<Rows16Deep><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+    else if (d.rows_a == 32) k_sac_actor<Rows32Deep<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+    else return hipErrorInvalidValue;
+  } else if (d.rows_a == 16) k_sac_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   else if (d.rows_a == 32) k_sac_actor<Rows32<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   else k_sac_actor<Rows32<2>><<<grid, block, LdsMap<64, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   return hipGetLastError();

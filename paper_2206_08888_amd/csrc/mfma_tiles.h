@@ -143,6 +143,73 @@ __device__ inline void gemm_xw_small(const float* __restrict__ Xl, int ldx, int 
   }
 }
 
+// The same product for a fan-in of several hundred: the 8-deep blocks beyond the prefetched 32
+// rows are software-pipelined, four weight blocks in flight ahead of the matrix pipe.
+template <int MT>
+__device__ inline void gemm_xw_deep(const float* __restrict__ Xl, int ldx, int K, const float* __restrict__ W,
+                                    const SmallW& pre, int wave, int lane, Acc<MT>& acc) {
+  constexpr int PF = 4;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int nb = (K + 7) >> 3;                       // 8-deep blocks in all; 0 .. 3 come from `pre`
+  const float* wcol = W + 64 * wave + l32;
+  float b[PF][2][4];
+  auto request = [&](float (&dst)[2][4], int blk) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = 8 * blk + 4 * half + j;
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const float v = wcol[(size_t)(k < K ? k : 0) * kH + 32 * nt];
+        dst[nt][j] = k < K ? v : 0.0f;
+      }
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < PF; ++s)
+    if (4 + s < nb) request(b[s], 4 + s);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (i < nb) {
+      f32x4 a[MT];
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        a[mt] = *reinterpret_cast<const f32x4*>(&Xl[(32 * mt + l32) * ldx + 8 * i + 4 * half]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], pre.w[i][nt][j], acc.t[mt][nt]);
+    }
+  }
+  for (int blk = 4; blk < nb; blk += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+      const int i = blk + s;
+      if (i < nb) {
+        f32x4 a[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          a[mt] = *reinterpret_cast<const f32x4*>(&Xl[(32 * mt + l32) * ldx + 8 * i + 4 * half]);
+        float w[2][4];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) w[nt][j] = b[s][nt][j];
+        if (i + PF < nb) request(b[s], i + PF);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], w[nt][j], acc.t[mt][nt]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+}
+
 // Software-pipelined 256-deep contraction of an LDS operand with a global weight
 // operand; the contraction index is walked in 16 blocks of 16.
 //   forward  (TRANSPOSED = false): acc[r][c] += sum_k X[r][k] W[k][c], c in this wave's 64 columns

@@ -148,6 +148,57 @@ __device__ inline void gemm_xw_small16(const float* __restrict__ Xl, int ldx, in
   }
 }
 
+// The same product for a fan-in of several hundred: the blocks beyond the prefetched 32 rows are
+// software-pipelined, four weight blocks (64 rows of W) in flight ahead of the matrix pipe.
+__device__ inline void gemm_xw_deep16(const float* __restrict__ Xl, int ldx, int K, const float* __restrict__ W,
+                                      const SmallW16& pre, int wave, int lane, Acc16& acc) {
+  constexpr int PF = 4;
+  const int c = lane & 15, kq = lane >> 4;
+  const int nb = (K + 15) >> 4;                      // 16-deep blocks in all; 0 and 1 come from `pre`
+  const float* wcol = W + 64 * wave + 4 * c;
+  f32x4 b[PF][4];
+  auto request = [&](f32x4 (&dst)[4], int blk) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = 16 * blk + 4 * kq + j;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(wcol + (size_t)(k < K ? k : 0) * kH);
+      dst[j] = k < K ? v : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < PF; ++s)
+    if (2 + s < nb) request(b[s], 2 + s);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    if (i < nb) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[c * ldx + 16 * i + 4 * kq]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc.t[nt] = mfma16(a[j], pre.w[i][j][nt], acc.t[nt]);
+    }
+  }
+  for (int blk = 2; blk < nb; blk += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+      const int i = blk + s;
+      if (i < nb) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[c * ldx + 16 * i + 4 * kq]);
+        f32x4 w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = b[s][j];
+        if (i + PF < nb) request(b[s], i + PF);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int nt = 0; nt < 4; ++nt) acc.t[nt] = mfma16(a[j], w[j][nt], acc.t[nt]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+}
+
 // ReLU epilogue: Y = max(acc + b, 0) to LDS (row stride kLda) and, when Yg != nullptr, to
 // global memory as [rows][256]; bb = biases of this lane's 4 columns.  Returns the
 // activation pattern, bit 4 nt + v; the backward product leaves element (row, col) in the
@@ -177,6 +228,71 @@ __device__ inline uint64_t relu_store16(const Acc16& acc, const f32x4& bb, float
     }
   }
   return mask;
+}
+
+// Narrow products on the matrix pipe, weights straight from global memory (no LDS staging):
+//   head_mfma:   out[r*stride + j] = sum_{c<256} X[r][c] W[c*J + j]      (W: [256][J], a network's head)
+//   head_mfma_t: out[r*stride + j] = sum_{c<256} X[r][c] W[j*256 + c]    (W: J rows of 256)
+// r < R (a multiple of 16), j < J; X in LDS with row stride kLda.  The output is cut into 16x16 tiles,
+// dealt round-robin to the 4 wavefronts; a tile's 256-deep product is 64 v_mfma_f32_16x16x4_f32, its
+// weights requested in one go before the first of them.  Columns at or beyond J are neither read nor
+// written.  The tile loop is controlled by a scalar (readfirstlane of the wavefront index): written on
+// the per-lane value, the compiler wraps the matrix instructions in an EXEC-masked loop, and one build of
+// that form produced wrong sums.
+template <int R>
+__device__ inline void head_mfma(const float* __restrict__ Xl, const float* __restrict__ W, int J, float* __restrict__ outl,
+                                 int stride, int wave, int lane) {
+  constexpr int RT = R / 16;
+  const int c = lane & 15, kq = lane >> 4;
+  const int tiles = RT * ((J + 15) >> 4);
+  for (int tile = __builtin_amdgcn_readfirstlane(wave); tile < tiles; tile += kThreads / 64) {
+    const int rt = tile % RT, col = 16 * (tile / RT) + c;
+    const bool ok = col < J;
+    const float* wp = W + (ok ? col : 0) + (size_t)(4 * kq) * J;
+    float b[16][4];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[i][j] = wp[(size_t)(16 * i + j) * J];
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[(16 * rt + c) * kLda + 16 * i + 4 * kq]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc = mfma16(a[j], ok ? b[i][j] : 0.0f, acc);
+    }
+    if (ok) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) outl[(16 * rt + 4 * kq + v) * stride + col] = acc[v];
+    }
+  }
+}
+
+template <int R>
+__device__ inline void head_mfma_t(const float* __restrict__ Xl, const float* __restrict__ W, int J, float* __restrict__ outl,
+                                   int stride, int wave, int lane) {
+  constexpr int RT = R / 16;
+  const int c = lane & 15, kq = lane >> 4;
+  const int tiles = RT * ((J + 15) >> 4);
+  for (int tile = __builtin_amdgcn_readfirstlane(wave); tile < tiles; tile += kThreads / 64) {
+    const int rt = tile % RT, col = 16 * (tile / RT) + c;
+    const bool ok = col < J;
+    const float* wp = W + (size_t)(ok ? col : 0) * kH + 4 * kq;
+    f32x4 b[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) b[i] = *reinterpret_cast<const f32x4*>(wp + 16 * i);
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[(16 * rt + c) * kLda + 16 * i + 4 * kq]);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc = mfma16(a[j], ok ? b[i][j] : 0.0f, acc);
+    }
+    if (ok) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) outl[(16 * rt + 4 * kq + v) * stride + col] = acc[v];
+    }
+  }
 }
 
 __device__ inline bool mask_bit16(uint64_t mask, int nt, int v) { return (mask >> (4 * nt + v)) & 1ull; }

@@ -102,14 +102,15 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // Beside 16 P target workgroups of 16 rows, 64-row critic chains (8 P workgroups) keep the fused
   // target/critic launch of a small population within one workgroup per CU.
   d.rows_c = cls == 1 ? 32 : 64;
-  // Wide inputs (SAC only): the input tile grows with the fan-in, so the chains that also hold the
-  // actor's and the critics' head rows in LDS take 16 rows, the critic chain 32.
-  if (d.D > kMaxIn) { d.rows_t = d.rows_a = 16; d.rows_c = 32; }
   if (const char* env = getenv("POP_ROWS")) {       // 16, 32 or 64: override (measurements, tests)
     const int v = atoi(env);
     if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; }
     if (v == 32 || v == 64) d.rows_t = d.rows_c = d.rows_a = v;
   }
+  // Wide inputs (SAC only; kernels with a pipelined first layer): 32-row chains -- with weights of
+  // 2 MB per agent, 16-row workgroups re-read them from L2 often enough to be bound by that -- except
+  // for populations too small to fill the chip with them.
+  if (d.D > kMaxIn) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; }
   d.actor = make_layout(d.O, c.algo == POP_ALGO_SAC ? 2 * d.A : d.A);   // SAC: mean and log-std per action
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
@@ -264,6 +265,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->fuse = (d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512) ? 2 : 1;
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = 0;     // measured at P = 32: fusing target and critic chains loses 4 %
   if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
+  if (d.D > kMaxIn) ctx->fuse = 0;                  // wide inputs: the chains exist as separate launches only
   ctx->hp.assign(hp, hp + cfg->P);
   if (cfg->algo == POP_ALGO_SAC)
     for (auto& h : ctx->hp) h.policy_delay = 1;

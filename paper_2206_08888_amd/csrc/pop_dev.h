@@ -102,7 +102,7 @@ struct PopDev {
 
 // critic partial record: dW3[256] db3[1] pad[3] db2[256] db1[256] loss[1] pad[3]
 constexpr int kCP_dW3 = 0, kCP_db3 = 256, kCP_db2 = 260, kCP_db1 = 516, kCP_loss = 772, kCPart = 776;
-// actor partial record: dW3[256*kMaxHead] db3[kMaxHead] db2[256] db1[256] loss[1] logp[1] pad
+// actor partial record: dW3[kMaxHead][256] (head column j of hidden unit c at j*256 + c) db3[kMaxHead] db2[256] db1[256] loss[1] logp[1] pad
 constexpr int kAP_dW3 = 0, kAP_db3 = 256 * kMaxHead, kAP_db2 = kAP_db3 + kMaxHead, kAP_db1 = kAP_db2 + 256,
               kAP_loss = kAP_db1 + 256, kAP_logp = kAP_loss + 1 /* SAC: sum of log pi over the chunk */, kAPart = kAP_loss + 8;
 

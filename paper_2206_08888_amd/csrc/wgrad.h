@@ -208,6 +208,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     // are requested first: they depend on nothing and arrive while the partial sums are read.
     const int c = tid;
     const int out = L.out;
+    POP_MARK(55);
     const uint32_t i_b1 = (uint32_t)(L.b1 + c), i_b2 = (uint32_t)(L.b2 + c), i_w3 = (uint32_t)(L.w3 + c * out),
                    i_b3 = (uint32_t)(L.b3 + (c < out ? c : 0));
     const bool polyak = delayed_step && !(actor_phase && d.algo == 1);
@@ -225,28 +226,34 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
     __syncthreads();
     const Adam adam = *sh_adam;
+    POP_MARK(56);
     float gb1 = 0.0f, gb2 = 0.0f, gw3[kHeadBlock], gb3 = 0.0f, loss = 0.0f, logp = 0.0f;
 #pragma unroll
     for (int j = 0; j < kHeadBlock; ++j) gw3[j] = 0.0f;
+    // Every load of a chunk's record goes out unconditionally (head columns beyond `out` re-read column 0
+    // and are dropped at the store), so that the loads of several chunks are in flight together.
+    if (actor_phase) {
 #pragma unroll 4
-    for (int ch = 0; ch < chunks; ++ch) {
-      if (actor_phase) {
+      for (int ch = 0; ch < chunks; ++ch) {
         const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart;
-        gb1 += p[kAP_db1 + c];
-        gb2 += p[kAP_db2 + c];
+        const float t1 = p[kAP_db1 + c], t2 = p[kAP_db2 + c], t3 = p[kAP_db3 + (c < out ? c : 0)];
+        const float tl = p[kAP_loss], tp = p[kAP_logp];
+        float tw[kHeadBlock];
 #pragma unroll
-        for (int j = 0; j < kHeadBlock; ++j)
-          if (j < out) gw3[j] += p[kAP_dW3 + c * out + j];
-        if (c < out) gb3 += p[kAP_db3 + c];
-        if (c == 0) { loss += p[kAP_loss]; logp += p[kAP_logp]; }
-      } else {
+        for (int j = 0; j < kHeadBlock; ++j) tw[j] = p[kAP_dW3 + (j < out ? j : 0) * kH + c];
+        gb1 += t1; gb2 += t2; gb3 += t3; loss += tl; logp += tp;
+#pragma unroll
+        for (int j = 0; j < kHeadBlock; ++j) gw3[j] += tw[j];
+      }
+    } else {
+#pragma unroll 4
+      for (int ch = 0; ch < chunks; ++ch) {
         const float* p = d.cpart + ((size_t)unit * chunks + ch) * kCPart;
-        gb1 += p[kCP_db1 + c];
-        gb2 += p[kCP_db2 + c];
-        gw3[0] += p[kCP_dW3 + c];
-        if (c == 0) { gb3 += p[kCP_db3]; loss += p[kCP_loss]; }
+        const float t1 = p[kCP_db1 + c], t2 = p[kCP_db2 + c], tw = p[kCP_dW3 + c], t3 = p[kCP_db3], tl = p[kCP_loss];
+        gb1 += t1; gb2 += t2; gw3[0] += tw; gb3 += t3; loss += tl;
       }
     }
+    POP_MARK(57);
     adam_store<WAIT>(adam, r_b1, gb1, i_b1, th, mo, ve, tg, gr);
     adam_store<WAIT>(adam, r_b2, gb2, i_b2, th, mo, ve, tg, gr);
 #pragma unroll
@@ -260,11 +267,14 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
         r_w3[j] = ld(i_w3 + (uint32_t)(j0 + j < out ? j0 + j : 0));
         gw3[j] = 0.0f;
       }
+#pragma unroll 4
       for (int ch = 0; ch < chunks; ++ch) {
-        const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart + kAP_dW3 + c * out + j0;
+        const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart + kAP_dW3 + c;
+        float tw[kHeadBlock];
 #pragma unroll
-        for (int j = 0; j < kHeadBlock; ++j)
-          if (j0 + j < out) gw3[j] += p[j];
+        for (int j = 0; j < kHeadBlock; ++j) tw[j] = p[(j0 + j < out ? j0 + j : 0) * kH];
+#pragma unroll
+        for (int j = 0; j < kHeadBlock; ++j) gw3[j] += tw[j];
       }
 #pragma unroll
       for (int j = 0; j < kHeadBlock; ++j)
@@ -282,6 +292,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
       la[2 * d.P] = vv;
       la[0] = cur - hp.lr_alpha * (mm * adam.inv_c1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(vv * adam.inv_c2) + adam.eps);
     }
+    POP_MARK(58);
     if (c == 0) {
       // critic loss = sum over the twins; the two critic workgroups of an agent write
       // their halves to separate slots and the reader adds them

@@ -92,12 +92,21 @@ __device__ inline void load_input(float* Xl, int xld, const float* rows, int row
 template <int R>
 __device__ inline void load_input_wide(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
                                        int tid) {
+  constexpr int RW = R / (kThreads / 64);            // rows per wavefront
   const int wave = tid >> 6, lane = tid & 63;
-  for (int r = wave; r < R; r += kThreads / 64) {
-    const float* src = rows + (size_t)r * row_stride + c0;
-    const bool live = r < valid;
-#pragma unroll 4
-    for (int c = lane; c < xld; c += 64) Xl[r * xld + c] = (live && c < n) ? src[c] : 0.0f;
+#pragma unroll 2
+  for (int c = lane; c < xld; c += 64) {             // RW (x2) loads in flight per lane
+    float v[RW];
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+      const int r = wave + (kThreads / 64) * i;
+      v[i] = rows[(size_t)(r < valid ? r : 0) * row_stride + c0 + (c < n ? c : 0)];
+    }
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+      const int r = wave + (kThreads / 64) * i;
+      Xl[r * xld + c] = (r < valid && c < n) ? v[i] : 0.0f;
+    }
   }
 }
 
@@ -357,7 +366,8 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
 
 // The same tiles for first layers with a fan-in of several hundred (the SAC Humanoid shapes): only the
 // first-layer product differs (software-pipelined beyond the prefetched rows).
-template <int MT>
+// PF: weight blocks of 8 rows in flight; 8 where the registers allow it (the critic chain), else 4.
+template <int MT, int PF = 4>
 struct Rows32Deep : Rows32<MT> {
   using Pre = typename Rows32<MT>::Pre;
   __device__ static inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
@@ -369,7 +379,7 @@ struct Rows32Deep : Rows32<MT> {
                                                 const Pre& pre, float* Yl, float* Yg, int wave, int lane) {
     Acc<MT> acc;
     acc.zero();
-    gemm_xw_deep<MT>(Xs, xld, L.in, net + L.w1, pre.w1, wave, lane, acc);
+    gemm_xw_deep<MT, PF>(Xs, xld, L.in, net + L.w1, pre.w1, wave, lane, acc);
     return relu_store<MT, THROUGH>(acc, pre.b1, Yl, Yg, wave, lane);
   }
 };

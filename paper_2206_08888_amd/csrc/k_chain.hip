@@ -113,7 +113,7 @@ hipError_t setup_kernels() {
   POP_SET_LDS(k_target<Rows32<2>>);
   POP_SET_LDS(k_critic<Rows32<1>>);
   POP_SET_LDS(k_critic<Rows32<2>>);
-  POP_SET_LDS(k_critic<Rows32Deep<1>>);
+  POP_SET_LDS(k_critic<Rows32Deep<1, 8>>);
   POP_SET_LDS(k_actor<Rows16>);
   POP_SET_LDS(k_actor<Rows32<1>>);
   POP_SET_LDS(k_actor<Rows32<2>>);
@@ -138,7 +138,7 @@ hipError_t launch_critic(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(2 * d.P, d.B / d.rows_c)), block(kThreads);
   if (d.D > kMaxIn) {                                // wide inputs (SAC): 32 rows, pipelined first layer
     if (d.rows_c != 32) return hipErrorInvalidValue;
-    k_critic<Rows32Deep<1>><<<grid, block, Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
+    k_critic<Rows32Deep<1, 8>><<<grid, block, Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
   } else if (d.rows_c == 32) k_critic<Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec_critic(d)), s>>>(d, t);
   else k_critic<Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec_critic(d)), s>>>(d, t);
   return hipGetLastError();

@@ -144,11 +144,10 @@ __device__ inline void gemm_xw_small(const float* __restrict__ Xl, int ldx, int 
 }
 
 // The same product for a fan-in of several hundred: the 8-deep blocks beyond the prefetched 32
-// rows are software-pipelined, four weight blocks in flight ahead of the matrix pipe.
-template <int MT>
+// rows are software-pipelined, PF weight blocks (8 PF rows of W) in flight ahead of the matrix pipe.
+template <int MT, int PF>
 __device__ inline void gemm_xw_deep(const float* __restrict__ Xl, int ldx, int K, const float* __restrict__ W,
                                     const SmallW& pre, int wave, int lane, Acc<MT>& acc) {
-  constexpr int PF = 4;
   const int half = lane >> 5, l32 = lane & 31;
   const int nb = (K + 7) >> 3;                       // 8-deep blocks in all; 0 .. 3 come from `pre`
   const float* wcol = W + 64 * wave + l32;

@@ -95,20 +95,40 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
       regs[v].tg = polyak ? tg[i] : 0.0f;
     }
   };
-  // this thread's row of the X slice (thread b holds batch row b, 32 columns of it)
-  const bool aligned = (ldx & 3) == 0;               // a hidden layer's output; else batch rows of any stride
-  const float* xr = x + (size_t)tid * ldx + m0;
+  // The X slice [256 batch rows][32 columns], read so that one load instruction covers whole 128-byte
+  // row pieces (a lane-per-row pattern touches 64 cache lines per instruction and lives off the L1):
+  //   16-byte path (row stride a multiple of 4: a hidden layer's output): instruction i, lane l takes
+  //     4 columns 4 (l & 7) .. of row 64 wave + 8 i + (l >> 3);
+  //   else (batch rows of any stride): instruction i, lane l takes column l & 31 of row 64 wave + 2 i + (l >> 5),
+  //     columns at or beyond M read column 0 and are zeroed on the way into LDS.
+  const bool aligned = (ldx & 3) == 0;
   float xs[32];
   auto load_x = [&]() {
     if (aligned) {
+      const uint32_t o0 = (uint32_t)((64 * wave + (lane >> 3)) * ldx + m0 + 4 * (lane & 7)), step = (uint32_t)(8 * ldx);
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(xr + 4 * i);
+        const f32x4 v = *reinterpret_cast<const f32x4*>(x + (o0 + (uint32_t)i * step));
         xs[4 * i] = v[0]; xs[4 * i + 1] = v[1]; xs[4 * i + 2] = v[2]; xs[4 * i + 3] = v[3];
       }
     } else {
+      const int col = lane & 31;
+      const uint32_t o0 = (uint32_t)((64 * wave + (lane >> 5)) * ldx + m0 + ((m0 + col) < M ? col : 0)), step = (uint32_t)(2 * ldx);
 #pragma unroll
-      for (int m = 0; m < 32; ++m) xs[m] = xr[(m0 + m) < M ? m : 0];
+      for (int i = 0; i < 32; ++i) xs[i] = x[o0 + (uint32_t)i * step];
+    }
+  };
+  auto store_x = [&]() {                             // transposed into LDS: Xl[column][batch row]
+    if (aligned) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Xl[(4 * (lane & 7) + e) * kLda + 64 * wave + 8 * i + (lane >> 3)] = xs[4 * i + e];
+    } else {
+      const int col = lane & 31;
+      const bool live = (m0 + col) < M;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) Xl[col * kLda + 64 * wave + 2 * i + (lane >> 5)] = live ? xs[i] : 0.0f;
     }
   };
   WeightBlock<1, false, 1> z0;
@@ -129,8 +149,7 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   }
   __builtin_amdgcn_sched_barrier(0);
   POP_MARK(51);
-#pragma unroll
-  for (int m = 0; m < 32; ++m) Xl[m * kLda + tid] = (aligned || (m0 + m) < M) ? xs[m] : 0.0f;   // X^T slice into LDS
+  store_x();
   __syncthreads();
   POP_MARK(52);
   const Adam adam = *sh;

@@ -68,9 +68,10 @@ typedef struct {
 } pop_hparams;
 
 /* Population-wide shapes.  Supported now: algo TD3 or SAC, n_hidden == 2 with
- * hidden = {256, 256}, obs_dim + act_dim <= 64, act_dim <= 8, batch ==
- * 256 (the batch of every workload of Sec. 4.1), 1 <= capacity < 2^32.  Anything else gives
- * POP_EUNSUPPORTED. */
+ * hidden = {256, 256}, batch == 256 (the batch of every workload of Sec. 4.1),
+ * 1 <= capacity < 2^32; TD3: obs_dim + act_dim <= 64, act_dim <= 8 (HalfCheetah-v2 of
+ * Sec. 4.1 is 17 / 6); SAC: obs_dim + act_dim <= 448, act_dim <= 24 (up to the
+ * Humanoid-v2 shapes 376 / 17).  Anything else gives POP_EUNSUPPORTED. */
 typedef struct {
   int32_t algo;
   int32_t P;

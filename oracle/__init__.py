@@ -1,4 +1,4 @@
-"""CPU oracle for the population TD3 (td3.py) and SAC (sac.py) update steps.
+"""CPU oracle for the population TD3 (td3.py), SAC (sac.py) and shared-critic TD3 (td3_shared.py) update steps.
 
 TEST INFRASTRUCTURE ONLY.  This package is the slow, plain, fp64 definition of
 what the HIP path computes: every agent of the population is stepped on its
@@ -11,6 +11,9 @@ Learning on a Single Machine"):
   * Sec. 4.1 "Training Independent Replicas of the Same Agent": N replicas,
     different initial weights and hyperparameters, updated independently; MLP
     actor and critics; TD3 and SAC with the standard hyperparametrization.
+  * Sec. 4.2 "Training Agents Sharing Parameters": one critic pair for the
+    whole population, every batch through the policy networks in parallel,
+    the critic loss averaged over the population (td3_shared.py).
   * App. C: a population layer is y[p] = x[p] W[p] + b[p] with W of shape
     [P, in, out] and b of shape [P, 1, out].
   * App. A: one bounded first-in-first-out replay buffer per agent, batches of

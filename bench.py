@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the population TD3 update step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..5] [--no-cpu] [--no-secondary]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..6] [--no-cpu] [--no-secondary]
 
 A "step" is one update step of the whole population (every kernel of the hot
 path: replay sample + gather, target chain, critic chain, critic weight
@@ -81,8 +81,8 @@ def build_population(config_id, torch, fill=None):
     import paper_2206_08888_amd as pp
     c = workloads.CONFIGS[config_id]
     P, O, A, cap = c["P"], c["obs_dim"], c["act_dim"], c["capacity"]
-    cfg = pp.make_config(P, O, A, c["hidden"], c["batch"], cap,
-                         algo=pp.POP_ALGO_SAC if c["algo"] == "sac" else pp.POP_ALGO_TD3)
+    algo = {"sac": pp.POP_ALGO_SAC, "td3": pp.POP_ALGO_TD3, "td3_shared": pp.POP_ALGO_TD3_SHARED}[c["algo"]]
+    cfg = pp.make_config(P, O, A, c["hidden"], c["batch"], cap, algo=algo)
     pop = pp.Population(cfg, workloads.hparams(config_id))
     gen = torch.Generator(device="cuda")
     gen.manual_seed(workloads.DATA_SEED + config_id)
@@ -126,11 +126,11 @@ def time_config(config_id, steps, warmup, torch, with_kernels=True):
 
 def cpu_baseline(config_id, budget_s=12.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
-    from oracle import sac, td3
+    from oracle import sac, td3, td3_shared
     c = workloads.CONFIGS[config_id]
     n_agents, rows = 2, 50_000
     hps = workloads.hparams(config_id)[:n_agents]
-    orc = (sac if c["algo"] == "sac" else td3).Population(hps, c["obs_dim"], c["act_dim"], list(c["hidden"]), c["batch"], rows)
+    orc = {"sac": sac, "td3": td3, "td3_shared": td3_shared}[c["algo"]].Population(hps, c["obs_dim"], c["act_dim"], list(c["hidden"]), c["batch"], rows)
     for i in range(n_agents):
         orc.insert(i, **workloads.transitions(config_id, i, rows))
     orc.update(1)
@@ -168,7 +168,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", type=int, default=1, choices=(0, 1, 2, 3, 4, 5))
+    ap.add_argument("--config", type=int, default=1, choices=(0, 1, 2, 3, 4, 5, 6))
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-secondary", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",

@@ -45,7 +45,7 @@ enum {
   POP_EUNSUPPORTED = -5  /* shape or algorithm the kernels do not cover */
 };
 
-enum { POP_ALGO_TD3 = 0, POP_ALGO_SAC = 1 };
+enum { POP_ALGO_TD3 = 0, POP_ALGO_SAC = 1, POP_ALGO_TD3_SHARED = 2 };
 
 /* Per-agent hyperparameters (Sec. 4.1: replicas differ in initial weights and
  * hyperparameters; App. B.1 lists the ones a population tunes).  Read at
@@ -67,7 +67,16 @@ typedef struct {
   int32_t reserved_;    /* keeps sizeof == 64 */
 } pop_hparams;
 
-/* Population-wide shapes.  Supported now: algo TD3 or SAC, n_hidden == 2 with
+/* POP_ALGO_TD3_SHARED (Sec. 4.2 of the paper, "Training Agents Sharing Parameters"): TD3 with ONE pair of critics
+ * (and target critics) for the whole population; every agent keeps its own policy, target policy, buffer, seed,
+ * discount and smoothing noise.  A step runs every agent's batch through that agent's policy networks, takes one
+ * Adam step on the critics for the critic loss averaged over the population, then (on delayed steps) the ordinary
+ * TD3 policy step of every agent through the updated critic.  The critics take their initial weights (seed),
+ * learning rate, Adam constants and tau from agent 0's hyperparameters; policy_delay must be the same for all
+ * agents (POP_EINVAL otherwise).  The tensor codes of the critics name the shared tensors whatever `agent` is;
+ * pop_copy_agent copies the policy side only.  Shapes as for TD3.
+ *
+ * Population-wide shapes.  Supported now: algo TD3, TD3_SHARED or SAC, n_hidden == 2 with
  * hidden = {256, 256}, batch == 256 (the batch of every workload of Sec. 4.1),
  * 1 <= capacity < 2^32; TD3: obs_dim + act_dim <= 64, act_dim <= 8 (HalfCheetah-v2 of
  * Sec. 4.1 is 17 / 6); SAC: obs_dim + act_dim <= 448, act_dim <= 24 (up to the

@@ -10,7 +10,7 @@ import os
 import numpy as np
 
 POP_OK, POP_EINVAL, POP_ENOMEM, POP_EEMPTY, POP_EHIP, POP_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
-POP_ALGO_TD3, POP_ALGO_SAC = 0, 1
+POP_ALGO_TD3, POP_ALGO_SAC, POP_ALGO_TD3_SHARED = 0, 1, 2
 
 PARAM_CODES = {
     "actor": 0, "critic1": 1, "critic2": 2, "t_actor": 3, "t_critic1": 4, "t_critic2": 5,

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpop.so")
-SOURCES = ["pop_api.hip", "k_replay.hip", "k_init.hip", "k_chain.hip", "k_wgrad_adam.hip", "k_step.hip", "k_sac.hip"]
+SOURCES = ["pop_api.hip", "k_replay.hip", "k_init.hip", "k_chain.hip", "k_wgrad_adam.hip", "k_step.hip", "k_sac.hip", "k_wgrad_shared.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wno-unused-command-line-argument", "-Wno-pass-failed",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -611,12 +611,12 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
     float err = 0.0f, g = 0.0f;
     if (tid < R) {
       err = head[tid * kMaxAct] + b3 - yv;
-      g = 2.0f * err / (float)d.B;
+      g = 2.0f * err / (float)(d.B * d.share);         // share > 1: the critic loss is the mean over the population
       dq[tid] = g;
     }
     const float sq = wave_sum(err * err);
     const float sdq = wave_sum(g);
-    if (tid == 0) { put<SIGNAL>(part + kCP_loss, sq / (float)d.B); put<SIGNAL>(part + kCP_db3, sdq); }
+    if (tid == 0) { put<SIGNAL>(part + kCP_loss, sq / (float)(d.B * d.share)); put<SIGNAL>(part + kCP_db3, sdq); }
   }
   __syncthreads();
   {                                                 // one thread per hidden unit, 8 rows at a time

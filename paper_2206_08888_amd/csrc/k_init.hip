@@ -16,6 +16,7 @@ __global__ __launch_bounds__(256) void k_init(PopDev d, InitLimits lim) {
   // grid: (ceil(max tensor / 256), 9 tensors, P)
   const int agent = blockIdx.z;
   const int net = blockIdx.y / 3, layer = blockIdx.y % 3;
+  if (d.share > 1 && net >= 1 && agent != 0) return;  // shared critics: the one pair is agent 0's
   const NetLayout& L = net == 0 ? d.actor : d.critic;
   const int fan_in = layer == 0 ? L.in : kH;
   const int fan_out = layer == 2 ? L.out : kH;

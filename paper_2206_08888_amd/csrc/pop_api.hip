@@ -23,7 +23,7 @@ constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
   int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
-  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, fault, sigma, log_alpha, staging, replay, total;
+  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, fault, spart, sloss, sigma, log_alpha, staging, replay, total;
   int64_t param_bytes;
 };
 
@@ -74,7 +74,8 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
   if (c->P < 1 || c->obs_dim < 1 || c->act_dim < 1 || c->batch < 1 || c->capacity < 1 || c->n_hidden < 1 ||
       c->n_hidden > 4)
     return fail(ctx, POP_EINVAL, "config has a non-positive size");
-  if (c->algo != POP_ALGO_TD3 && c->algo != POP_ALGO_SAC) return fail(ctx, POP_EINVAL, "unknown algorithm %d", c->algo);
+  if (c->algo != POP_ALGO_TD3 && c->algo != POP_ALGO_SAC && c->algo != POP_ALGO_TD3_SHARED)
+    return fail(ctx, POP_EINVAL, "unknown algorithm %d", c->algo);
   if (c->n_hidden != 2 || c->hidden[0] != kH || c->hidden[1] != kH)
     return fail(ctx, POP_EUNSUPPORTED, "hidden layers must be {256, 256}");
   const int max_in = c->algo == POP_ALGO_SAC ? kSacMaxIn : kMaxIn, max_act = c->algo == POP_ALGO_SAC ? kSacMaxAct : kMaxAct;
@@ -115,6 +116,14 @@ void fill_dims(const pop_config& c, PopDev& d) {
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
   d.capacity = (uint64_t)c.capacity;
+  d.share = 1;
+  if (c.algo == POP_ALGO_TD3_SHARED) {
+    // groups of agents whose critic gradients are summed by separate workgroups: as many as keep the partial
+    // launch (2 networks x groups x roles workgroups) within the 512 the chip holds at once
+    const int roles = 16 + 2 * ((d.critic.in + 31) / 32) + 1;
+    d.share = c.P;
+    d.groups = std::max(1, std::min(c.P, 512 / (2 * roles)));
+  }
 }
 
 // The SAC chains size their LDS from the shapes: refuse what one CU cannot hold.
@@ -148,6 +157,8 @@ Layout make_ws_layout(const PopDev& d) {
   L.y_tagged = take(P * B * 8);
   L.done_c = take(4 * P * 4); L.done_wc = take(4 * P * 4); L.done_a = take(2 * P * 4);
   L.fault = take(4);
+  L.spart = take(2 * (int64_t)d.groups * d.critic.padded * 4);
+  L.sloss = take(2 * (int64_t)d.groups * 4);
   L.sigma = take(P * 4);
   L.log_alpha = take(3 * P * 4);
   L.staging = take(kStagingBytes);
@@ -238,6 +249,10 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   if (((uintptr_t)workspace % kAlign) != 0) return fail(nullptr, POP_EINVAL, "workspace must be 256-byte aligned");
   for (int i = 0; i < cfg->P; ++i)
     if ((rc = check_hparams(nullptr, hp[i], i)) != POP_OK) return rc;
+  if (cfg->algo == POP_ALGO_TD3_SHARED)
+    for (int i = 1; i < cfg->P; ++i)
+      if (hp[i].policy_delay != hp[0].policy_delay)
+        return fail(nullptr, POP_EINVAL, "shared critics: agent %d has policy_delay %d, agent 0 has %d", i, hp[i].policy_delay, hp[0].policy_delay);
   PopDev d;
   fill_dims(*cfg, d);
   if ((rc = check_fit(d, nullptr)) != POP_OK) return rc;
@@ -264,8 +279,9 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   // single kernel without spilling and stay separate as well.)
   ctx->fuse = (d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512) ? 2 : 1;
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = 0;     // measured at P = 32: fusing target and critic chains loses 4 %
+  if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 0;   // one launch per part (the critic's weight step is a reduction)
   if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
-  if (d.D > kMaxIn) ctx->fuse = 0;                  // wide inputs: the chains exist as separate launches only
+  if (d.D > kMaxIn || cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 0;                  // wide inputs: the chains exist as separate launches only
   ctx->hp.assign(hp, hp + cfg->P);
   if (cfg->algo == POP_ALGO_SAC)
     for (auto& h : ctx->hp) h.policy_delay = 1;
@@ -294,6 +310,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.y_tagged = (uint64_t*)(w + L.y_tagged); d.done_c = (uint32_t*)(w + L.done_c); d.done_wc = (uint32_t*)(w + L.done_wc); d.done_a = (uint32_t*)(w + L.done_a);
   d.fault = (uint32_t*)(w + L.fault);
   d.log_alpha = (float*)(w + L.log_alpha);
+  d.spart = (float*)(w + L.spart); d.sloss = (float*)(w + L.sloss);
   ctx->d = d;
 
   auto bail = [&](hipError_t e, const char* what) {
@@ -411,6 +428,20 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
     e = launch_wgrad_adam(d, t, 1, 0, s);
     tick(POP_K_WGRAD_ACTOR, 1);
     if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    ctx->t++;
+    return POP_OK;
+  }
+  if (d.algo == POP_ALGO_TD3_SHARED) {                // the TD3 chains on the shared critic blocks; the critics' weight
+                                                      // step sums over the population (k_wgrad_shared.hip)
+    if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic) || !run(POP_K_WGRAD_CRITIC, launch_wgrad_shared))
+      return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    if (any_actor) {
+      if (!run(POP_K_ACTOR, launch_actor)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+      tick(POP_K_WGRAD_ACTOR, 0);
+      e = launch_wgrad_adam(d, t, 1, 0, s);
+      tick(POP_K_WGRAD_ACTOR, 1);
+      if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    }
     ctx->t++;
     return POP_OK;
   }
@@ -583,6 +614,7 @@ int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, i
   int64_t off, region;
   const NetLayout* L = net_of(ctx->d, which, &net, &off, ctx->lay, &region);
   if (out_len < L->size) return fail(ctx, POP_EINVAL, "out_len %lld < %d", (long long)out_len, L->size);
+  if (ctx->d.share > 1 && net >= 1) agent = 0;         // the shared critics live in agent 0's blocks
   const char* src = ctx->ws + region + (int64_t)agent * ctx->d.agent_sz * 4 + off;
   HIP_TRY(ctx, hipMemcpyAsync(out, src, (size_t)L->size * 4, on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
                               ctx->stream));
@@ -607,6 +639,7 @@ int pop_set_params(pop_ctx* ctx, int32_t agent, int32_t which, const float* in, 
   int64_t off, region;
   const NetLayout* L = net_of(ctx->d, which, &net, &off, ctx->lay, &region);
   if (in_len != L->size) return fail(ctx, POP_EINVAL, "in_len %lld != %d", (long long)in_len, L->size);
+  if (ctx->d.share > 1 && net >= 1) agent = 0;
   char* dst = ctx->ws + region + (int64_t)agent * ctx->d.agent_sz * 4 + off;
   HIP_TRY(ctx, hipMemcpyAsync(dst, in, (size_t)L->size * 4, on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice,
                               ctx->stream));
@@ -687,6 +720,8 @@ int pop_set_hparams(pop_ctx* ctx, int32_t agent, const pop_hparams* hp) {
   const int rc = check_hparams(ctx, *hp, agent);
   if (rc != POP_OK) return rc;
   if (hp->seed == 0) return fail(ctx, POP_EINVAL, "seed 0 (derive from the population seed) is only meaningful at pop_create");
+  if (ctx->d.algo == POP_ALGO_TD3_SHARED && ctx->d.P > 1 && hp->policy_delay != ctx->hp[agent == 0 ? 1 : 0].policy_delay)
+    return fail(ctx, POP_EINVAL, "shared critics: policy_delay is common to the population (%d)", ctx->hp[agent == 0 ? 1 : 0].policy_delay);
   HpDev& g = ctx->hp_dev[agent];
   g.actor_base = actor_updates_before(ctx, agent, ctx->t);   // under the old delay, up to now
   g.t_base = (uint32_t)ctx->t;
@@ -706,7 +741,8 @@ int pop_copy_agent(pop_ctx* ctx, int32_t dst, int32_t src, int32_t with_buffer) 
   if (dst < 0 || dst >= d.P || src < 0 || src >= d.P) return fail(ctx, POP_EINVAL, "agent out of range (dst %d, src %d)", dst, src);
   if (dst == src) return POP_OK;
   hipStream_t s = ctx->stream;
-  const size_t state = (size_t)d.agent_sz * sizeof(float);
+  // the actor block comes first in an agent's state; with shared critics that is all an agent owns
+  const size_t state = (size_t)(d.share > 1 ? d.actor.padded : d.agent_sz) * sizeof(float);
   for (float* region : {d.theta, d.target, d.m, d.v})
     HIP_TRY(ctx, hipMemcpyAsync(region + (size_t)dst * d.agent_sz, region + (size_t)src * d.agent_sz, state, hipMemcpyDeviceToDevice, s));
   if (d.algo == POP_ALGO_SAC)

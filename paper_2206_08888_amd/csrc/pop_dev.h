@@ -63,7 +63,12 @@ __host__ __device__ inline NetLayout make_layout(int in, int out) {
 }
 
 struct PopDev {
-  int algo;                    // POP_ALGO_TD3 (0) or POP_ALGO_SAC (1); the SAC actor has 2 A outputs
+  int algo;                    // POP_ALGO_TD3 (0), POP_ALGO_SAC (1; its actor has 2 A outputs) or POP_ALGO_TD3_SHARED (2)
+  int share;                   // 1; shared critics (Sec. 4.2 of the paper): P -- every agent's critic blocks are agent
+                               // 0's and the critic loss is the mean over the population
+  int groups;                  // shared critics: agent groups whose gradients are summed separately (spart)
+  float* spart;                // shared critics: [2][groups][critic.padded] partial gradients, laid out like the network
+  float* sloss;                // shared critics: [2][groups] partial losses
   int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
   int rows_t, rows_c, rows_a;  // batch rows per workgroup of the target / critic / actor chain: (16, 64, 16) for small
                                // populations, (32, 32, 32), or (64, 64, 64) for large ones
@@ -135,6 +140,7 @@ __device__ inline bool decode_block(int id, int units, int per_unit, int& unit, 
 __host__ inline int xcd_grid(int units, int per_unit) { return units * per_unit; }
 
 __device__ inline const float* net_ptr(const PopDev& d, const float* base, int agent, int net) {
+  if (d.share > 1 && net >= 1) agent = 0;            // the one critic pair lives in agent 0's blocks
   const float* p = base + (size_t)agent * d.agent_sz;
   if (net >= 1) p += d.actor.padded;
   if (net >= 2) p += d.critic.padded;

@@ -67,6 +67,45 @@ __device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uin
   if (a.record) gr[i] = g;
 }
 
+// The X slice [256 batch rows][32 columns] of a weight-gradient tile, read so that one load instruction
+// covers whole 128-byte row pieces (a lane-per-row pattern touches 64 cache lines per instruction and lives
+// off the L1), then written transposed into LDS as Xl[column][batch row]:
+//   16-byte path (row stride a multiple of 4: a hidden layer's output): instruction i, lane l takes
+//     4 columns 4 (l & 7) .. of row 64 wave + 8 i + (l >> 3);
+//   else (batch rows of any stride): instruction i, lane l takes column l & 31 of row 64 wave + 2 i + (l >> 5),
+//     columns at or beyond M read column 0 and are zeroed on the way into LDS.
+struct XSlice {
+  float xs[32];
+  __device__ __forceinline__ void load(const float* __restrict__ x, int ldx, int M, int m0, int wave, int lane) {
+    if ((ldx & 3) == 0) {
+      const uint32_t o0 = (uint32_t)((64 * wave + (lane >> 3)) * ldx + m0 + 4 * (lane & 7)), step = (uint32_t)(8 * ldx);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(x + (o0 + (uint32_t)i * step));
+        xs[4 * i] = v[0]; xs[4 * i + 1] = v[1]; xs[4 * i + 2] = v[2]; xs[4 * i + 3] = v[3];
+      }
+    } else {
+      const int col = lane & 31;
+      const uint32_t o0 = (uint32_t)((64 * wave + (lane >> 5)) * ldx + m0 + ((m0 + col) < M ? col : 0)), step = (uint32_t)(2 * ldx);
+#pragma unroll
+      for (int i = 0; i < 32; ++i) xs[i] = x[o0 + (uint32_t)i * step];
+    }
+  }
+  __device__ __forceinline__ void store(float* Xl, int ldx, int M, int m0, int wave, int lane) const {
+    if ((ldx & 3) == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Xl[(4 * (lane & 7) + e) * kLda + 64 * wave + 8 * i + (lane >> 3)] = xs[4 * i + e];
+    } else {
+      const int col = lane & 31;
+      const bool live = (m0 + col) < M;
+#pragma unroll
+      for (int i = 0; i < 32; ++i) Xl[col * kLda + 64 * wave + 2 * i + (lane >> 5)] = live ? xs[i] : 0.0f;
+    }
+  }
+};
+
 // One 32 x 128 tile of a weight matrix [M][256]: rows m0 .. m0+31 (rows >= M masked),
 // columns n0 .. n0+127, 32 per wavefront.
 //   x: [256][ldx] layer input, z: [256][256] pre-activation gradient, both global;
@@ -95,42 +134,9 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
       regs[v].tg = polyak ? tg[i] : 0.0f;
     }
   };
-  // The X slice [256 batch rows][32 columns], read so that one load instruction covers whole 128-byte
-  // row pieces (a lane-per-row pattern touches 64 cache lines per instruction and lives off the L1):
-  //   16-byte path (row stride a multiple of 4: a hidden layer's output): instruction i, lane l takes
-  //     4 columns 4 (l & 7) .. of row 64 wave + 8 i + (l >> 3);
-  //   else (batch rows of any stride): instruction i, lane l takes column l & 31 of row 64 wave + 2 i + (l >> 5),
-  //     columns at or beyond M read column 0 and are zeroed on the way into LDS.
-  const bool aligned = (ldx & 3) == 0;
-  float xs[32];
-  auto load_x = [&]() {
-    if (aligned) {
-      const uint32_t o0 = (uint32_t)((64 * wave + (lane >> 3)) * ldx + m0 + 4 * (lane & 7)), step = (uint32_t)(8 * ldx);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const f32x4 v = *reinterpret_cast<const f32x4*>(x + (o0 + (uint32_t)i * step));
-        xs[4 * i] = v[0]; xs[4 * i + 1] = v[1]; xs[4 * i + 2] = v[2]; xs[4 * i + 3] = v[3];
-      }
-    } else {
-      const int col = lane & 31;
-      const uint32_t o0 = (uint32_t)((64 * wave + (lane >> 5)) * ldx + m0 + ((m0 + col) < M ? col : 0)), step = (uint32_t)(2 * ldx);
-#pragma unroll
-      for (int i = 0; i < 32; ++i) xs[i] = x[o0 + (uint32_t)i * step];
-    }
-  };
-  auto store_x = [&]() {                             // transposed into LDS: Xl[column][batch row]
-    if (aligned) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) Xl[(4 * (lane & 7) + e) * kLda + 64 * wave + 8 * i + (lane >> 3)] = xs[4 * i + e];
-    } else {
-      const int col = lane & 31;
-      const bool live = (m0 + col) < M;
-#pragma unroll
-      for (int i = 0; i < 32; ++i) Xl[col * kLda + 64 * wave + 2 * i + (lane >> 5)] = live ? xs[i] : 0.0f;
-    }
-  };
+  XSlice xsl;
+  auto load_x = [&]() { xsl.load(x, ldx, M, m0, wave, lane); };
+  auto store_x = [&]() { xsl.store(Xl, ldx, M, m0, wave, lane); };
   WeightBlock<1, false, 1> z0;
   if (WAIT && wait_on) {                             // x and z come from a chain of this launch:
     load_adam();                                     // the Adam operands can be on their way meanwhile

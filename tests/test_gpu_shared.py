@@ -1,0 +1,197 @@
+"""GPU parity of TD3 with shared critics (Sec. 4.2 of the paper) against oracle/td3_shared.py, through the
+C boundary.  Tolerances as for TD3: initial parameters bit-exact; gradients rel-L2 <= 1e-5, parameters and
+targets <= 1e-4 after one step and <= 1e-3 after 100 steps, per network."""
+import numpy as np
+import pytest
+
+import paper_2206_08888_amd as pp
+import workloads
+from gpu_common import ensure_built, rel_l2
+from oracle import mlp as oracle_mlp, philox as oracle_philox, td3_shared as oracle_shared
+
+pytestmark = pytest.mark.gpu
+
+ACTOR_SIDE = ("actor", "t_actor")
+CRITIC_SIDE = ("critic1", "critic2", "t_critic1", "t_critic2")
+MOMS_A = ("m_actor", "v_actor")
+MOMS_C = ("m_critic1", "m_critic2", "v_critic1", "v_critic2")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    ensure_built()
+
+
+def make_shared_pair(P=3, capacity=1500, hps=None, oracle=True, config_id=2):
+    hps = workloads.hparams(config_id, P) if hps is None else hps      # per-agent lr, tau, noise; one policy delay
+    cfg = pp.make_config(P, 17, 6, (256, 256), 256, capacity, algo=pp.POP_ALGO_TD3_SHARED)
+    gpu = pp.Population(cfg, hps)
+    orc = oracle_shared.Population(hps, 17, 6, [256, 256], 256, capacity) if oracle else None
+    for i in range(P):
+        for tr in workloads.transition_chunks(2, i, capacity):
+            gpu.insert(i, **tr)
+            if oracle:
+                orc.insert(i, **tr)
+    return gpu, orc
+
+
+def compare(gpu, orc, tol, label):
+    P = len(orc.agents)
+    worst = 0.0
+    for w in CRITIC_SIDE:
+        e = rel_l2(gpu.get_params(0, w), orc.get_params(0, w))
+        worst = max(worst, e)
+        assert e <= tol, "%s: %s rel-L2 %.3e > %.1e" % (label, w, e, tol)
+    for i in range(P):
+        for w in ACTOR_SIDE:
+            e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
+            worst = max(worst, e)
+            assert e <= tol, "%s: agent %d %s rel-L2 %.3e > %.1e" % (label, i, w, e, tol)
+    print("%s: worst parameter rel-L2 %.3e (tol %.1e)" % (label, worst, tol))
+
+
+def force(gpu, orc):
+    for w in CRITIC_SIDE + MOMS_C:
+        gpu.set_params(0, w, orc.get_params(0, w))
+    for i in range(len(orc.agents)):
+        for w in ACTOR_SIDE + MOMS_A:
+            gpu.set_params(i, w, orc.get_params(i, w))
+
+
+def test_initial_state_one_critic_pair_from_agent_zero():
+    gpu, orc = make_shared_pair()
+    for i in range(3):
+        for w in ACTOR_SIDE + CRITIC_SIDE:
+            assert np.array_equal(gpu.get_params(i, w), orc.get_params(i, w).astype(np.float32)), (i, w)
+    assert np.array_equal(gpu.get_params(0, "critic2"), gpu.get_params(2, "critic2"))
+    assert not np.array_equal(gpu.get_params(0, "actor"), gpu.get_params(1, "actor"))
+    gpu.close()
+
+
+def test_one_step_matches_oracle():
+    gpu, orc = make_shared_pair()
+    gpu.set_debug(True)
+    gpu.update(1); orc.update(1)
+    for w in ("g_critic1", "g_critic2"):
+        e = rel_l2(gpu.get_params(1, w), orc.get_params(1, w))
+        assert e <= 1e-5, (w, e)
+    for i in range(3):
+        e = rel_l2(gpu.get_params(i, "g_actor"), orc.get_params(i, "g_actor"))
+        assert e <= 1e-5, (i, e)
+    compare(gpu, orc, 1e-4, "one step, shared critics")
+    for w in MOMS_C:
+        assert rel_l2(gpu.get_params(0, w), orc.get_params(0, w)) <= 2e-5, w
+    for i in range(3):
+        for w in MOMS_A:
+            assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 2e-5, (i, w)
+    losses = gpu.debug("losses")
+    assert abs(losses[0, 0] - orc.last["critic_loss"]) <= 1e-5 * abs(orc.last["critic_loss"])
+    assert np.all(losses[:, 0] == losses[0, 0])             # the population's critic loss, reported for every agent
+    for i, ag in enumerate(orc.agents):
+        assert abs(losses[i, 1] - ag.last["actor_loss"]) <= 1e-5 * max(1.0, abs(ag.last["actor_loss"]))
+    assert gpu.step_count() == 1
+    gpu.close()
+
+
+def test_thirty_forced_single_steps_match_oracle():
+    gpu, orc = make_shared_pair()
+    worst = 0.0
+    for step in range(30):
+        force(gpu, orc)
+        gpu.update(1); orc.update(1)
+        for w in CRITIC_SIDE:
+            e = rel_l2(gpu.get_params(0, w), orc.get_params(0, w))
+            worst = max(worst, e)
+            assert e <= 1e-4, (step, w, e)
+        for i in range(3):
+            for w in ACTOR_SIDE:
+                e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
+                worst = max(worst, e)
+                assert e <= 1e-4, (step, i, w, e)
+    print("forced steps, shared critics: worst parameter rel-L2 %.3e" % worst)
+    gpu.close()
+
+
+def test_hundred_steps_match_oracle():
+    gpu, orc = make_shared_pair(P=2, hps=workloads.hparams(0, 2), capacity=2000)
+    gpu.update(100); orc.update(100)
+    compare(gpu, orc, 1e-3, "100 steps, shared critics")
+    assert gpu.step_count() == 100
+    gpu.close()
+
+
+def test_population_of_one_equals_plain_td3():
+    """Same chains, same inputs; the critic's weight step goes through the partial sums and a separate Adam kernel,
+    so the last bit may differ (fused multiply-adds are formed per kernel): fp32 rounding level, not bit identity."""
+    hps = workloads.hparams(2, 1)
+    shared, _ = make_shared_pair(P=1, capacity=1200, hps=hps, oracle=False)
+    plain = pp.Population(pp.make_config(1, 17, 6, (256, 256), 256, 1200), hps)
+    for tr in workloads.transition_chunks(2, 0, 1200):
+        plain.insert(0, **tr)
+    shared.update(6); plain.update(6)
+    for w in ACTOR_SIDE + CRITIC_SIDE + MOMS_A + MOMS_C:
+        e = rel_l2(shared.get_params(0, w), plain.get_params(0, w))
+        assert e <= 5e-6, (w, e)
+    shared.close(); plain.close()
+
+
+def critic_relu_margin(orc, k, t):
+    """Smallest |hidden pre-activation| of shared critic k over every agent's batch of step t (before the step)."""
+    m = np.inf
+    for ag in orc.agents:
+        idx = oracle_philox.sample_indices(ag.seed, t, ag.B, ag.buffer.count)
+        s, a = (x.astype(np.float64) for x in ag.buffer.gather(idx)[:2])
+        _, cache = oracle_mlp.forward(orc.critic[k], np.concatenate([s, a], axis=1), 'linear')
+        m = min(m, min(float(np.abs(z).min()) for z in cache[1][:-1]))
+    return m
+
+
+def test_twenty_agents_in_uneven_groups_match_oracle():
+    """P = 20: the critic gradient is summed in 13 groups of one or two agents.  With 2.6 million hidden
+    pre-activations per critic and step, one of them usually lies within fp32 rounding of zero (here 2.3e-8 in
+    critic 1 at step 0) and is resolved differently by the two precisions: that network's gradient may then differ
+    by one sample's share, and Adam's first, sign-like step turns it into 2 lr on the smallest entries."""
+    gpu, orc = make_shared_pair(P=20, capacity=500)
+    margin = [critic_relu_margin(orc, k, 0) for k in range(2)]
+    gpu.set_debug(True)
+    gpu.update(1); orc.update(1)
+    kinked = []
+    for k in range(2):
+        w = "critic%d" % (k + 1)
+        e = rel_l2(gpu.get_params(0, "g_" + w), orc.get_params(0, "g_" + w))
+        if e > 1e-5:                                        # only a ReLU on its kink explains more
+            assert margin[k] <= 1e-6 and e <= 2e-2, (w, e, margin[k])
+            kinked.append(w)
+        for name in (w, "t_" + w):
+            e = rel_l2(gpu.get_params(0, name), orc.get_params(0, name))
+            assert e <= (2e-3 if w in kinked else 1e-4), (name, e)
+    print("critics compared at the loose tolerance at step 0: %s (ReLU margins %s)" % (kinked, margin))
+    for i in range(20):                                     # the policies went through critic 1: same allowance
+        for w in ACTOR_SIDE:
+            e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
+            assert e <= 2e-3, (i, w, e)
+    force(gpu, orc)                                         # later steps are not sign-like: judged at the sharp tolerance
+    gpu.update(2); orc.update(2)
+    compare(gpu, orc, 1e-4, "two steps from a common state at P = 20, shared critics")
+    gpu.close()
+
+
+def test_copy_agent_copies_the_policy_side_only_and_delays_stay_common():
+    gpu, _ = make_shared_pair(oracle=False)
+    gpu.update(3)
+    critic = {w: gpu.get_params(0, w) for w in CRITIC_SIDE + MOMS_C}
+    gpu.copy_agent(2, 0, False)
+    for w in ACTOR_SIDE + MOMS_A:
+        assert np.array_equal(gpu.get_params(2, w), gpu.get_params(0, w)), w
+    for w, v in critic.items():
+        assert np.array_equal(gpu.get_params(1, w), v), w
+    hp = dict(workloads.hparams(2, 3)[1], policy_delay=3)
+    with pytest.raises(pp.PopError) as e:
+        gpu.set_hparams(1, hp)
+    assert e.value.code == pp.POP_EINVAL
+    gpu.close()
+    mixed = workloads.hparams(2, 3)
+    mixed[2]["policy_delay"] = 1
+    with pytest.raises(pp.PopError) as e:
+        pp.Population(pp.make_config(3, 17, 6, (256, 256), 256, 500, algo=pp.POP_ALGO_TD3_SHARED), mixed)
+    assert e.value.code == pp.POP_EINVAL

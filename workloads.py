@@ -32,6 +32,10 @@ CONFIGS = {
     # 5: SAC at the shapes the paper itself measures SAC on (Sec. 4.1: HalfCheetah-v2), population of config 3
     5: dict(algo="sac", P=32, hidden=(256, 256), batch=256, capacity=200_000, steps=500,
             sweep=("lr", "tau"), **HALFCHEETAH),
+    # 6: TD3 with shared critics (Sec. 4.2 of the paper; its runtime figure varies the population size), at the
+    #    population and shapes of config 2; one policy delay for all agents
+    6: dict(algo="td3_shared", P=80, hidden=(256, 256), batch=256, capacity=200_000, steps=1000,
+            sweep=("lr", "tau", "policy_noise"), **HALFCHEETAH),
     # 4: saturation case, P up to 256
     4: dict(algo="td3", P=256, hidden=(256, 256), batch=256, capacity=50_000, steps=200,
             sweep=("lr", "tau", "policy_noise"), **HALFCHEETAH),

@@ -1,0 +1,134 @@
+"""GPU parity of the variants at full size, in the launch configuration bench.py times:
+SAC at the population, shapes and buffer sizes of workloads 5 (HalfCheetah shapes) and 3 (Humanoid shapes, 500,000-row
+buffers: 49 GB of replay on the device), and TD3 with shared critics at P = 80 (workload 6's population; its oracle
+needs every agent, so the buffers are cut to 20,000 rows).
+
+SAC, sampled agents (first and last; population independence makes them the same computation alone):
+  A. one free step from the common initial state: indices bit-exact; parameters <= 1e-4, or <= 2e-3 at the Humanoid
+     shapes (Adam's first update is lr * sign(g): with first layers of fan-in 393 some ReLU pre-activation usually
+     lies within fp32 rounding of zero, and the few gradient entries that change sign move by 2 lr);
+  B. forced single steps (the sampled GPU agents start every step from the oracle's state): indices bit-exact,
+     parameters and targets <= 1e-4, log alpha <= 2e-6 after every step.
+Shared critics: the same two phases with all 80 agents in the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2206_08888_amd as pp
+import workloads
+from gpu_common import ensure_built, rel_l2
+from oracle import sac as oracle_sac, td3_shared as oracle_shared
+
+pytestmark = pytest.mark.gpu
+
+NETS5 = ("actor", "critic1", "critic2", "t_critic1", "t_critic2")
+SAC_STATE = NETS5 + ("m_actor", "m_critic1", "m_critic2", "v_actor", "v_critic1", "v_critic2",
+                     "log_alpha", "m_log_alpha", "v_log_alpha")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    ensure_built()
+
+
+def _fill_on_device(gpu, P, O, A, cap, seed):
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    piece = max(1, min(cap, (48 << 20) // (P * (2 * O + A + 2))))
+    done = 0
+    while done < cap:
+        n = min(piece, cap - done)
+        gpu.insert(-1, obs=torch.randn((P, n, O), generator=gen, device="cuda"),
+                   act=torch.rand((P, n, A), generator=gen, device="cuda") * 2 - 1,
+                   rew=torch.randn((P, n), generator=gen, device="cuda"),
+                   done=(torch.rand((P, n), generator=gen, device="cuda") < 0.01).float(),
+                   next_obs=torch.randn((P, n, O), generator=gen, device="cuda"))
+        done += n
+
+
+@pytest.mark.parametrize("config_id,forced_steps", [(5, 12), (3, 6)])
+def test_sac_sampled_agents_match_oracle_at_full_size(config_id, forced_steps):
+    c = workloads.CONFIGS[config_id]
+    P, O, A, cap, B = c["P"], c["obs_dim"], c["act_dim"], c["capacity"], c["batch"]
+    agents = [0, P - 1]
+    hps = workloads.hparams(config_id)
+    gpu = pp.Population(pp.make_config(P, O, A, c["hidden"], B, cap, algo=pp.POP_ALGO_SAC), hps)
+    _fill_on_device(gpu, P, O, A, cap, workloads.DATA_SEED + 77 * config_id)
+    orc = oracle_sac.Population([hps[i] for i in agents], O, A, list(c["hidden"]), B, cap)
+    for j, i in enumerate(agents):                      # a full ring of host rows overwrites the device-made ones
+        for tr in workloads.transition_chunks(config_id, i, cap):
+            gpu.insert(i, **tr)
+            orc.insert(j, **tr)
+
+    def check_indices(tag):
+        idx = gpu.debug("indices")
+        for j, i in enumerate(agents):
+            assert np.array_equal(idx[i].astype(np.int64), orc.agents[j].last["idx"]), (tag, i)
+
+    def worst():
+        w = 0.0
+        for j, i in enumerate(agents):
+            for name in NETS5:
+                w = max(w, rel_l2(gpu.get_params(i, name), orc.get_params(j, name)))
+            da = abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(j, "log_alpha")[0]))
+            assert da <= 2e-6, (i, da)
+        return w
+
+    gpu.update(1); orc.update(1)                        # A
+    check_indices("A")
+    e1 = worst()
+    assert e1 <= (2e-3 if O + A > 64 else 1e-4), (config_id, e1)
+    eb = 0.0
+    for step in range(forced_steps):                    # B
+        for j, i in enumerate(agents):
+            for name in SAC_STATE:
+                gpu.set_params(i, name, orc.get_params(j, name))
+        gpu.update(1); orc.update(1)
+        check_indices("B%d" % step)
+        e = worst()
+        eb = max(eb, e)
+        assert e <= 1e-4, (config_id, step, e)
+    print("config %d (SAC, P=%d, obs %d, act %d, %d-row buffers): rel-L2 after 1 free step %.2e; %d forced steps, worst %.2e"
+          % (config_id, P, O, A, cap, e1, forced_steps, eb))
+    assert gpu.step_count() == 1 + forced_steps
+    gpu.close()
+
+
+def test_shared_critics_match_oracle_at_p80():
+    c = workloads.CONFIGS[6]
+    P, O, A, B, cap = c["P"], c["obs_dim"], c["act_dim"], c["batch"], 20_000
+    hps = workloads.hparams(6)
+    gpu = pp.Population(pp.make_config(P, O, A, c["hidden"], B, cap, algo=pp.POP_ALGO_TD3_SHARED), hps)
+    orc = oracle_shared.Population(hps, O, A, list(c["hidden"]), B, cap)
+    for i in range(P):
+        tr = workloads.transitions(6, i, cap, salt=1)
+        gpu.insert(i, **tr)
+        orc.insert(i, **tr)
+    critic_side = ("critic1", "critic2", "t_critic1", "t_critic2")
+    actor_side = ("actor", "t_actor")
+
+    def worst(sample):
+        w = max(rel_l2(gpu.get_params(0, n), orc.get_params(0, n)) for n in critic_side)
+        for i in sample:
+            w = max(w, max(rel_l2(gpu.get_params(i, n), orc.get_params(i, n)) for n in actor_side))
+        return w
+
+    gpu.update(1); orc.update(1)                        # A: the first Adam step is sign-like (see the SAC note above)
+    idx = gpu.debug("indices")
+    for i in range(P):
+        assert np.array_equal(idx[i].astype(np.int64), orc.agents[i].last["idx"]), i
+    e1 = worst(range(P))
+    assert e1 <= 2e-3, e1
+    eb = 0.0
+    for step in range(5):                               # B: forced single steps
+        for n in critic_side + ("m_critic1", "m_critic2", "v_critic1", "v_critic2"):
+            gpu.set_params(0, n, orc.get_params(0, n))
+        for i in range(P):
+            for n in actor_side + ("m_actor", "v_actor"):
+                gpu.set_params(i, n, orc.get_params(i, n))
+        gpu.update(1); orc.update(1)
+        e = worst(range(P))
+        eb = max(eb, e)
+        assert e <= 1e-4, (step, e)
+    print("shared critics, P=80: rel-L2 after 1 free step %.2e; 5 forced steps, worst %.2e" % (e1, eb))
+    gpu.close()

@@ -279,9 +279,10 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   // single kernel without spilling and stay separate as well.)
   ctx->fuse = (d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512) ? 2 : 1;
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = 0;     // measured at P = 32: fusing target and critic chains loses 4 %
-  if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 0;   // one launch per part (the critic's weight step is a reduction)
+  if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 1;   // target and critic chains together; the critic's weight step is a reduction of its own
   if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
-  if (d.D > kMaxIn || cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 0;                  // wide inputs: the chains exist as separate launches only
+  if (d.D > kMaxIn) ctx->fuse = 0;
+  if (cfg->algo == POP_ALGO_TD3_SHARED && ctx->fuse > 1) ctx->fuse = 1;                  // wide inputs: the chains exist as separate launches only
   ctx->hp.assign(hp, hp + cfg->P);
   if (cfg->algo == POP_ALGO_SAC)
     for (auto& h : ctx->hp) h.policy_delay = 1;
@@ -433,8 +434,12 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
   }
   if (d.algo == POP_ALGO_TD3_SHARED) {                // the TD3 chains on the shared critic blocks; the critics' weight
                                                       // step sums over the population (k_wgrad_shared.hip)
-    if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic) || !run(POP_K_WGRAD_CRITIC, launch_wgrad_shared))
+    if (ctx->fuse != 0) {                             // target and critic chains in one launch (y handed over inside it)
+      if (!run(POP_K_TARGET_CRITIC, launch_target_critic)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    } else if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic)) {
       return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    }
+    if (!run(POP_K_WGRAD_CRITIC, launch_wgrad_shared)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
     if (any_actor) {
       if (!run(POP_K_ACTOR, launch_actor)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
       tick(POP_K_WGRAD_ACTOR, 0);

@@ -480,8 +480,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   float* buf = lds + L.buf;
   float* head = lds + L.s0;
   float* qmin = lds + L.s1;
-  float* v_aw3 = lds + L.vec;                        // [A][256]
-  float* v_ab3 = v_aw3 + kH * d.A;                   // [8]
+  float* v_ab3 = lds + L.vec;                        // [8]
   float* v_cw3 = v_ab3 + 8;                          // [2][256]
   float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -494,7 +493,6 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   pre.load(ta, d.actor, wave, lane);
   const HpDev hp = d.hp[agent];
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
-  stage_head(v_aw3, ta + d.actor.w3, d.A, tid);
   stage_vector(v_ab3, ta + d.actor.b3, d.A, tid);
   stage_vector(v_cw3, tc0 + d.critic.w3, kH, tid);
   stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
@@ -510,7 +508,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   G::template hidden_layer<false>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
   POP_MARK(33);
-  G::thin(buf, v_aw3, d.A, head, tid);
+  head_mfma<R>(buf, ta + d.actor.w3, d.A, head, kMaxAct, wave, lane);   // the head's weights straight from global memory
   __syncthreads();
   POP_MARK(34);
   for (int e = tid; e < R * d.A; e += kThreads) {
@@ -673,10 +671,10 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   float* api = lds + L.s1;
   float* dz3 = lds + L.s2;
   const int A = d.A;
-  float* v_aw3 = lds + L.vec;                        // [A][256] actor head
-  float* v_ab3 = v_aw3 + kH * A;                     // [8]
+  float* v_ab3 = lds + L.vec;                        // [8] actor head bias
   float* v_cw3 = v_ab3 + 8;                          // [256] critic head
-  float* v_cwa = v_cw3 + kH;                         // [A][256] critic first-layer rows of the action inputs
+  // the actor's head and the critic's first-layer rows of the action inputs are matrix-pipe operands read
+  // straight from global memory (head_mfma, head_mfma_t)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r0 = chunk * R;
   const HpDev hp = d.hp[agent];
@@ -689,12 +687,10 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)agent * d.B + r0) * kH;
   float* part = d.apart + ((size_t)agent * (d.B / R) + chunk) * kAPart;
-  stage_head(v_aw3, an + d.actor.w3, A, tid);
   stage_vector(v_ab3, an + d.actor.b3, A, tid);
   float cb3 = 0.0f;
   auto stage_critic = [&]() {
     stage_vector(v_cw3, cn + d.critic.w3, kH, tid);
-    stage_vector(v_cwa, cn + d.critic.w1 + d.O * kH, A * kH, tid);
     cb3 = cn[d.critic.b3];
   };
   if (!WAIT) stage_critic();
@@ -706,7 +702,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   G::template hidden_layer<false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
                          [&]() { if (!WAIT) pre.load(cn, d.critic, wave, lane); });
   __syncthreads();
-  G::thin(buf, v_aw3, A, head, tid);
+  head_mfma<R>(buf, an + d.actor.w3, A, head, kMaxAct, wave, lane);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
     const int r = e / A, j = e - r * A;
@@ -763,7 +759,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   }
   __syncthreads();
   POP_MARK(12);
-  G::thin(buf, v_cwa, A, head, tid);      // da
+  head_mfma_t<R>(buf, cn + d.critic.w1 + d.O * kH, A, head, kMaxAct, wave, lane);   // da
   G::load_wt(wt, an + d.actor.w2, wave, lane);       // block 0 of the actor's input-gradient product
   __syncthreads();
   for (int e = tid; e < R * kMaxAct; e += kThreads) {
@@ -784,7 +780,9 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
     const int c = tid;
     float w3[kMaxAct], gw3[kMaxAct];
 #pragma unroll
-    for (int j = 0; j < kMaxAct; ++j) { w3[j] = j < A ? v_aw3[j * kH + c] : 0.0f; gw3[j] = 0.0f; }
+    for (int j = 0; j < kMaxAct; ++j) { w3[j] = (an + d.actor.w3)[c * A + (j < A ? j : 0)]; gw3[j] = 0.0f; }
+#pragma unroll
+    for (int j = 0; j < kMaxAct; ++j) w3[j] = j < A ? w3[j] : 0.0f;
     float gb2 = 0.0f;
     float* zg = d.adZ2 + act_off + c;
 #pragma unroll 1
@@ -825,9 +823,9 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
 }
 
 // floats of staged vectors behind the LDS map of each chain
-inline int vec_target(const PopDev& d) { return kH * d.A + 8 + 2 * kH + 8; }
+inline int vec_target(const PopDev&) { return 8 + 2 * kH + 8; }
 inline int vec_critic(const PopDev&) { return kH + 8; }
-inline int vec_actor(const PopDev& d) { return kH * d.A + 8 + kH + d.A * kH; }
+inline int vec_actor(const PopDev&) { return 8 + kH; }
 inline int vec_act(const PopDev& d) { return kH * d.actor.out + kMaxHead; }
 constexpr int kActScratch = 2 * (kSacMaxAct / kMaxAct);   // acting: two head blocks of [32][kSacMaxAct]
 

@@ -57,6 +57,13 @@ def load_library():
     global _LIB
     if _LIB is not None:
         return _LIB
+    # PyTorch ships its own HIP runtime; callers allocate the workspace and the stream with it, so it has to be the
+    # runtime libpop.so binds to as well: loaded first, its libamdhip64 satisfies the library's dependency.  (Loaded
+    # the other way round the process holds two runtimes and the library's one finds no device.)
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     path = lib_path()
     if not os.path.exists(path):
         raise ImportError("%s is missing: build it with `python -m paper_2206_08888_amd.build` "

@@ -235,7 +235,7 @@ __device__ inline uint64_t relu_store16(const Acc16& acc, const f32x4& bb, float
 //   head_mfma_t: out[r*stride + j] = sum_{c<256} X[r][c] W[j*256 + c]    (W: J rows of 256)
 // r < R (a multiple of 16), j < J; X in LDS with row stride kLda.  The output is cut into 16x16 tiles,
 // dealt round-robin to the 4 wavefronts; a tile's 256-deep product is 64 v_mfma_f32_16x16x4_f32, its
-// weights requested in one go before the first of them.  Columns at or beyond J are neither read nor
+// weights requested in one go (head_mfma: in two halves) ahead of the products.  Columns at or beyond J are neither read nor
 // written.  The tile loop is controlled by a scalar (readfirstlane of the wavefront index): written on
 // the per-lane value, the compiler wraps the matrix instructions in an EXEC-masked loop, and one build of
 // that form produced wrong sums.
@@ -249,17 +249,20 @@ __device__ inline void head_mfma(const float* __restrict__ Xl, const float* __re
     const int rt = tile % RT, col = 16 * (tile / RT) + c;
     const bool ok = col < J;
     const float* wp = W + (ok ? col : 0) + (size_t)(4 * kq) * J;
-    float b[16][4];
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) b[i][j] = wp[(size_t)(16 * i + j) * J];
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[(16 * rt + c) * kLda + 16 * i + 4 * kq]);
+    for (int h = 0; h < 2; ++h) {                    // two halves of 128 rows: 32 weight registers at a time
+      float b[8][4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc = mfma16(a[j], ok ? b[i][j] : 0.0f, acc);
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[i][j] = wp[(size_t)(16 * (8 * h + i) + j) * J];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[(16 * rt + c) * kLda + 16 * (8 * h + i) + 4 * kq]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = mfma16(a[j], ok ? b[i][j] : 0.0f, acc);
+      }
     }
     if (ok) {
 #pragma unroll

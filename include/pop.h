@@ -159,18 +159,17 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs,
 int pop_update(pop_ctx* ctx, int32_t n_steps);
 
 /* Kernels of an update step (indices into the arrays of pop_update_timed).
- * For larger populations a step is ONE launch, POP_K_STEP: target chains, critic chains,
+ * For most populations a step is ONE launch, POP_K_STEP: target chains, critic chains,
  * critic weight-gradient tiles, actor chains, actor weight-gradient tiles and
  * the gather of the next step's rows are parts of one grid and hand their
  * results on per agent / per network inside the launch.  The environment
  * variable POP_FUSE, read at pop_create, selects the launch structure:
- *   2 one launch per step (default for populations of more than about 40 agents);
+ *   2 one launch per step (TD3 default for up to 16 and for 43 .. 127 agents);
  *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest
- *     one launch per part (default for smaller and for very large
- *     populations);
+ *     one launch per part (TD3 default for 17 .. 42 and from 128 agents; shared critics);
  *   3 as 1, but on steps with an actor update the rest of the step is one
  *     launch (POP_K_STEP_TAIL);
- *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR).
+ *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR; SAC).
  * The arithmetic, and so every result, is bit-identical in all of them. */
 enum {
   POP_K_GATHER = 0,        /* replay index draw + row gather (first step of a call only) */

@@ -1,0 +1,118 @@
+"""GPU parity at the edges of the supported shapes: the largest and the smallest observation / action sizes of
+each algorithm, buffers shorter than a batch, zero-step calls.  Tolerances as elsewhere: gradients are not compared
+here; parameters and targets per network rel-L2 <= 1e-4 on forced single steps, and <= 2e-3 on the very first step
+from the initial state at large fan-ins (Adam's first update is lr * sign(g): a ReLU pre-activation within fp32
+rounding of zero flips the sign of the smallest gradient entries, see test_gpu_sac.py)."""
+import numpy as np
+import pytest
+
+import paper_2206_08888_amd as pp
+import workloads
+from gpu_common import STATE12, PARAMS6, ensure_built, rel_l2
+from oracle import sac as oracle_sac, td3 as oracle_td3, td3_shared as oracle_shared
+
+pytestmark = pytest.mark.gpu
+
+SAC_NETS = ("actor", "critic1", "critic2", "t_critic1", "t_critic2")
+SAC_STATE = SAC_NETS + ("m_actor", "m_critic1", "m_critic2", "v_actor", "v_critic1", "v_critic2",
+                        "log_alpha", "m_log_alpha", "v_log_alpha")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    ensure_built()
+
+
+def _pair(algo, P, O, A, capacity, fill=None, hps=None):
+    fill = capacity if fill is None else fill
+    hps = workloads.hparams(2, P) if hps is None else hps
+    if algo == "sac":
+        for hp in hps:
+            hp["target_entropy"] = -float(A)
+    code = {"td3": pp.POP_ALGO_TD3, "sac": pp.POP_ALGO_SAC, "shared": pp.POP_ALGO_TD3_SHARED}[algo]
+    gpu = pp.Population(pp.make_config(P, O, A, (256, 256), 256, capacity, algo=code), hps)
+    mod = {"td3": oracle_td3, "sac": oracle_sac, "shared": oracle_shared}[algo]
+    orc = mod.Population(hps, O, A, [256, 256], 256, capacity)
+    for i in range(P):
+        tr = workloads.transitions(2, i, fill, obs_dim=O, act_dim=A, salt=3)
+        gpu.insert(i, **tr)
+        orc.insert(i, **tr)
+    return gpu, orc
+
+
+def _worst(gpu, orc, P, names):
+    return max(rel_l2(gpu.get_params(i, n), orc.get_params(i, n)) for i in range(P) for n in names)
+
+
+def _first_then_forced(gpu, orc, P, nets, state, first_tol, steps=3):
+    gpu.update(1); orc.update(1)
+    e1 = _worst(gpu, orc, P, nets)
+    assert e1 <= first_tol, e1
+    eb = 0.0
+    for _ in range(steps):
+        for i in range(P):
+            for n in state:
+                gpu.set_params(i, n, orc.get_params(i, n))
+        gpu.update(1); orc.update(1)
+        e = _worst(gpu, orc, P, nets)
+        eb = max(eb, e)
+        assert e <= 1e-4, e
+    return e1, eb
+
+
+@pytest.mark.parametrize("O,A", [(56, 8), (1, 1), (63, 1)])
+def test_td3_at_the_ends_of_its_shape_range(O, A):
+    gpu, orc = _pair("td3", 3, O, A, 600)
+    for i in range(3):
+        for n in PARAMS6:
+            assert np.array_equal(gpu.get_params(i, n), orc.get_params(i, n).astype(np.float32)), (i, n)
+    e1, eb = _first_then_forced(gpu, orc, 3, PARAMS6, STATE12, 1e-4)
+    obs = np.random.default_rng(2).standard_normal((3, 37, O)).astype(np.float32)
+    assert np.abs(gpu.act(obs) - orc.act(obs.astype(np.float64))).max() <= 1e-5
+    print("TD3 obs %d act %d: first step %.2e, forced steps %.2e" % (O, A, e1, eb))
+    gpu.close()
+
+
+@pytest.mark.parametrize("O,A,P", [(424, 24, 2), (424, 24, 20), (1, 1, 2), (60, 4, 2), (61, 4, 2)])
+def test_sac_at_the_ends_of_its_shape_range(O, A, P):
+    """(424, 24) is the largest input and head the SAC kernels take (16-row chains at P = 2, 32-row ones at P = 20);
+    (60, 4) / (61, 4) sit on either side of the switch to the pipelined first layers."""
+    gpu, orc = _pair("sac", P, O, A, 400)
+    for i in range(P):
+        for n in SAC_NETS:
+            assert np.array_equal(gpu.get_params(i, n), orc.get_params(i, n).astype(np.float32)), (i, n)
+    e1, eb = _first_then_forced(gpu, orc, P, SAC_NETS, SAC_STATE, 2e-3 if O + A > 64 else 1e-4)
+    for i in range(P):
+        assert abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(i, "log_alpha")[0])) <= 2e-6
+    obs = np.random.default_rng(2).standard_normal((P, 19, O)).astype(np.float32)
+    assert np.abs(gpu.act(obs) - orc.act(obs.astype(np.float64))).max() <= (2e-5 if O > 64 else 5e-6)
+    print("SAC obs %d act %d P %d: first step %.2e, forced steps %.2e" % (O, A, P, e1, eb))
+    gpu.close()
+
+
+@pytest.mark.parametrize("algo", ["td3", "sac", "shared"])
+def test_buffers_shorter_than_a_batch_and_zero_step_calls(algo):
+    """100 transitions for a batch of 256: sampling is with replacement over the filled part; update(0) is a no-op."""
+    P = 3
+    gpu, orc = _pair(algo, P, 17, 6, 500, fill=100)
+    nets = SAC_NETS if algo == "sac" else PARAMS6
+    before = {(i, n): gpu.get_params(i, n) for i in range(P) for n in nets}
+    gpu.update(0)
+    assert gpu.step_count() == 0
+    for (i, n), v in before.items():
+        assert np.array_equal(gpu.get_params(i, n), v)
+    gpu.update(2); orc.update(2)
+    idx = gpu.debug("indices")
+    for i in range(P):
+        assert idx[i].max() < 100
+        assert np.array_equal(idx[i].astype(np.int64), orc.agents[i].last["idx"]), i
+    assert _worst(gpu, orc, P, nets) <= 1e-4
+    gpu.close()
+
+
+def test_unsupported_shapes_are_refused_with_a_message():
+    for algo, O, A in ((pp.POP_ALGO_TD3, 57, 8), (pp.POP_ALGO_TD3, 17, 9), (pp.POP_ALGO_TD3_SHARED, 60, 6),
+                       (pp.POP_ALGO_SAC, 425, 24), (pp.POP_ALGO_SAC, 100, 25)):
+        with pytest.raises(pp.PopError) as e:
+            pp.Population(pp.make_config(2, O, A, (256, 256), 256, 100, algo=algo), workloads.hparams(2, 2))
+        assert e.value.code == pp.POP_EUNSUPPORTED and "must be <=" in str(e.value)

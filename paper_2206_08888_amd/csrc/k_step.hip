@@ -102,15 +102,19 @@ hipError_t launch_step(const PopDev& dev, uint32_t t, uint32_t launch_seq, int w
   g.a = with_actor ? xcd_grid(d.P, d.B / d.rows_a) : 0;
   g.wa = with_actor ? xcd_grid(d.P, g.roles_a) : 0;
   g.g = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
-  int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
-  if (vec_actor(d) > vec) vec = vec_actor(d);
+  const int vec_ta = vec_target(d) > vec_actor(d) ? vec_target(d) : vec_actor(d);
+  const int vec = vec_ta > vec_critic(d) ? vec_ta : vec_critic(d);
   const size_t tiles = (size_t)(32 * kLda) * sizeof(float) + sizeof(Adam);
   const dim3 grid(g.t + g.c + g.wc + g.a + g.wa + g.g), block(kThreads);
   size_t bytes = tiles;
   auto need = [&](size_t b) { if (b > bytes) bytes = b; };
   if (d.rows_a == 16) {
-    need(LdsMap<16, 16>(d.D).bytes(vec));
-    need(Lds<2>(d.D).bytes(vec));
+    need(LdsMap<16, 16>(d.D).bytes(vec_ta));
+    need(Lds<2>(d.D).bytes(vec_critic(d)));
+    // One workgroup per CU for small populations: the request is kept above half of a CU's LDS (the 64-row
+    // critic chain alone needs 80,928 of the 81,920 bytes that would let two share).  With two per CU the actor
+    // chains start earlier but every chain then shares its matrix pipe: 118 against 100 us/step at P = 10.
+    need((size_t)kLdsPerCU / 2 + 64);
     POP_STEP_SMALL<<<grid, block, bytes, s>>>(d, t, g);
   } else if (d.rows_a == 32) {
     need(Lds<1>(d.D).bytes(vec));

@@ -181,30 +181,57 @@ __device__ inline void gemm_xw_deep(const float* __restrict__ Xl, int ldx, int K
           for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], pre.w[i][nt][j], acc.t[mt][nt]);
     }
   }
-  for (int blk = 4; blk < nb; blk += PF) {
+  auto lds_block = [&](f32x4 (&a)[MT], int i) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      a[mt] = *reinterpret_cast<const f32x4*>(&Xl[(32 * mt + l32) * ldx + 8 * i + 4 * half]);
+  };
+  f32x4 an[MT];                                      // the LDS operand runs one block ahead of the matrix pipe
+  if (4 < nb) lds_block(an, 4);
+  // FAST: block i + PF lies wholly inside the K rows: its eight loads are one running pointer plus constants
+  // (no per-load address arithmetic or row guard, which would sit in front of every group of MFMAs)
+  const float* wrun = wcol + (size_t)(8 * (4 + PF) + 4 * half) * kH;     // rows of block 4 + PF for this lane
+  auto step = [&](int s, int i, bool next_x, bool next_w, bool fast) {
+    f32x4 a[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) a[mt] = an[mt];
+    if (next_x) lds_block(an, i + 1);
+    float w[2][4];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[nt][j] = b[s][nt][j];
+    if (fast) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) b[s][nt][j] = wrun[j * kH + 32 * nt];
+    } else if (next_w) {
+      request(b[s], i + PF);
+    }
+    wrun += 8 * kH;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], w[nt][j], acc.t[mt][nt]);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  int blk = 4;
+  // steady state, free of branches (a branch inside the loop makes the compiler drain every outstanding load at
+  // the join): every block of the group exists and every block requested from it is a full one
+  const int nfull = K >> 3;
+  for (; blk + 2 * PF <= nfull; blk += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) step(s, blk + s, true, true, true);
+  }
+  for (; blk < nb; blk += PF) {                      // the last groups: guarded requests
 #pragma unroll
     for (int s = 0; s < PF; ++s) {
       const int i = blk + s;
-      if (i < nb) {
-        f32x4 a[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          a[mt] = *reinterpret_cast<const f32x4*>(&Xl[(32 * mt + l32) * ldx + 8 * i + 4 * half]);
-        float w[2][4];
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) w[nt][j] = b[s][nt][j];
-        if (i + PF < nb) request(b[s], i + PF);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], w[nt][j], acc.t[mt][nt]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      if (i < nb) step(s, i, i + 1 < nb, i + PF < nb, false);
     }
   }
 }

@@ -178,23 +178,43 @@ __device__ inline void gemm_xw_deep16(const float* __restrict__ Xl, int ldx, int
         for (int nt = 0; nt < 4; ++nt) acc.t[nt] = mfma16(a[j], pre.w[i][j][nt], acc.t[nt]);
     }
   }
-  for (int blk = 2; blk < nb; blk += PF) {
+  f32x4 an = {0.0f, 0.0f, 0.0f, 0.0f};               // the LDS operand runs one block ahead of the matrix pipe
+  if (2 < nb) an = *reinterpret_cast<const f32x4*>(&Xl[c * ldx + 16 * 2 + 4 * kq]);
+  // FAST: block i + PF lies wholly inside the K rows: its four loads are one running pointer plus constants
+  const float* wrun = wcol + (size_t)(16 * (2 + PF) + 4 * kq) * kH;      // rows of block 2 + PF for this lane
+  auto step = [&](int s, int i, bool next_x, bool next_w, bool fast) {
+    const f32x4 a = an;
+    if (next_x) an = *reinterpret_cast<const f32x4*>(&Xl[c * ldx + 16 * (i + 1) + 4 * kq]);
+    f32x4 w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = b[s][j];
+    if (fast) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[s][j] = *reinterpret_cast<const f32x4*>(wrun + j * kH);
+    } else if (next_w) {
+      request(b[s], i + PF);
+    }
+    wrun += 16 * kH;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) acc.t[nt] = mfma16(a[j], w[j][nt], acc.t[nt]);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  int blk = 2;
+  // steady state, free of branches (a branch inside the loop makes the compiler drain every outstanding load at
+  // the join): every block of the group exists and every block requested from it is a full one
+  const int nfull = K >> 4;
+  for (; blk + 2 * PF <= nfull; blk += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) step(s, blk + s, true, true, true);
+  }
+  for (; blk < nb; blk += PF) {                      // the last groups: guarded requests
 #pragma unroll
     for (int s = 0; s < PF; ++s) {
       const int i = blk + s;
-      if (i < nb) {
-        const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[c * ldx + 16 * i + 4 * kq]);
-        f32x4 w[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = b[s][j];
-        if (i + PF < nb) request(b[s], i + PF);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-          for (int nt = 0; nt < 4; ++nt) acc.t[nt] = mfma16(a[j], w[j][nt], acc.t[nt]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      if (i < nb) step(s, i, i + 1 < nb, i + PF < nb, false);
     }
   }
 }

@@ -1,4 +1,4 @@
-// Replay sample + gather of one float of the stacked batch of step t.
+// Replay sample + gather of the stacked batch of step t.
 // Slot b of agent i takes word b & 3 of block b >> 2 of the agent's stream 0 at
 // step t and maps it to a row of the agent's buffer; element e = b * row + c of
 // the batch copies column c of that row.  Shared by the stand-alone gather
@@ -9,17 +9,40 @@
 
 namespace pop {
 
-__host__ __device__ inline int gather_blocks_per_agent(const PopDev& d) { return (d.B * d.row + 255) / 256; }
+// Floats of the stacked batch one thread copies: 1 for narrow rows; for wide rows (SAC at the Humanoid shapes:
+// 771 floats) one per 64 floats of a row, so that the gather of a step stays a few dozen workgroups per agent
+// (as the tail of the weight-gradient launch, tens of thousands of one-float workgroups cost more in dispatch
+// than the rows cost to fetch).
+__host__ __device__ inline int gather_floats_per_thread(const PopDev& d) {
+  const int e = (d.row + 63) / 64;
+  return e < 1 ? 1 : (e > 16 ? 16 : e);
+}
+__host__ __device__ inline int gather_blocks_per_agent(const PopDev& d) {
+  const int per = 256 * gather_floats_per_thread(d);
+  return (d.B * d.row + per - 1) / per;
+}
 
-__device__ inline void gather_element(const PopDev& d, uint32_t t, int agent, int e) {
-  if (e >= d.B * d.row) return;
-  const int b = e / d.row, c = e - b * d.row;
+// Workgroup `block` (of gather_blocks_per_agent) of one agent: thread `tid` copies the floats
+// (block * E + k) * 256 + tid, k < E, of the agent's stacked batch.
+__device__ inline void gather_block(const PopDev& d, uint32_t t, int agent, int block, int tid) {
+  const int E = gather_floats_per_thread(d);
   const HpDev hp = d.hp[agent];
-  const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, (uint32_t)(b >> 2), t, kStreamIndex, 0u);
-  const uint32_t idx = index_from_word(pick(blk, (uint32_t)b & 3u), d.count[agent]);
-  const size_t slot = ((size_t)(t & 1u) * d.P + agent) * d.B + b;
-  d.batch[slot * d.row + c] = d.replay[((size_t)agent * d.capacity + idx) * d.row + c];
-  if (c == 0) d.idx[slot] = idx;
+  const uint32_t count = d.count[agent];
+  int drawn = -1;                                    // batch slot whose index is held in idx
+  uint32_t idx = 0;
+  for (int k = 0; k < E; ++k) {
+    const int e = (block * E + k) * 256 + tid;
+    if (e >= d.B * d.row) return;
+    const int b = e / d.row, c = e - b * d.row;
+    if (b != drawn) {
+      const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, (uint32_t)(b >> 2), t, kStreamIndex, 0u);
+      idx = index_from_word(pick(blk, (uint32_t)b & 3u), count);
+      drawn = b;
+    }
+    const size_t slot = ((size_t)(t & 1u) * d.P + agent) * d.B + b;
+    d.batch[slot * d.row + c] = d.replay[((size_t)agent * d.capacity + idx) * d.row + c];
+    if (c == 0) d.idx[slot] = idx;
+  }
 }
 
 }  // namespace pop

@@ -62,8 +62,8 @@ hipError_t launch_insert(const PopDev& d, int agent, int64_t n, const float* obs
 }
 
 __global__ __launch_bounds__(256) void k_sample_gather(PopDev d, uint32_t t) {
-  // grid: (ceil(B * row / 256), P); one thread per float of the stacked batch
-  gather_element(d, t, blockIdx.y, blockIdx.x * 256 + threadIdx.x);
+  // grid: (gather_blocks_per_agent, P); a thread copies one float of the stacked batch (several for wide rows)
+  gather_block(d, t, blockIdx.y, blockIdx.x, threadIdx.x);
 }
 
 hipError_t launch_sample_gather(const PopDev& d, uint32_t t, hipStream_t s) {

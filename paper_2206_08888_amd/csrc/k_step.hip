@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
   b -= g.wa;
   if (b < g.g) {
     const int per = gather_blocks_per_agent(d);
-    gather_element(d, t + 1u, b / per, (b % per) * 256 + threadIdx.x);
+    gather_block(d, t + 1u, b / per, b % per, threadIdx.x);
   }
 }
 

@@ -15,7 +15,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_wgrad_adam(PopDev d, uint32_t t
   if ((int)blockIdx.x >= main_blocks) {              // gather role: rows of the next step
     if (prefetch) {
       const int g = blockIdx.x - main_blocks, per = gather_blocks_per_agent(d);
-      gather_element(d, t + 1u, g / per, (g % per) * 256 + threadIdx.x);
+      gather_block(d, t + 1u, g / per, g % per, threadIdx.x);
     }
     return;
   }

@@ -25,23 +25,37 @@ __host__ __device__ inline int gather_blocks_per_agent(const PopDev& d) {
 // Workgroup `block` (of gather_blocks_per_agent) of one agent: thread `tid` copies the floats
 // (block * E + k) * 256 + tid, k < E, of the agent's stacked batch.
 __device__ inline void gather_block(const PopDev& d, uint32_t t, int agent, int block, int tid) {
+  constexpr int kMaxE = 16;
   const int E = gather_floats_per_thread(d);
   const HpDev hp = d.hp[agent];
   const uint32_t count = d.count[agent];
+  const int total = d.B * d.row;
+  const float* src = d.replay + (size_t)agent * d.capacity * d.row;
+  float* dst = d.batch + ((size_t)(t & 1u) * d.P + agent) * d.B * d.row;
+  uint32_t* idx_out = d.idx + ((size_t)(t & 1u) * d.P + agent) * d.B;
   int drawn = -1;                                    // batch slot whose index is held in idx
   uint32_t idx = 0;
-  for (int k = 0; k < E; ++k) {
+  float v[kMaxE];
+  // all loads of a thread go out before the first store: the rows are random, every load a trip to HBM
+#pragma unroll
+  for (int k = 0; k < kMaxE; ++k) {
     const int e = (block * E + k) * 256 + tid;
-    if (e >= d.B * d.row) return;
-    const int b = e / d.row, c = e - b * d.row;
-    if (b != drawn) {
-      const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, (uint32_t)(b >> 2), t, kStreamIndex, 0u);
-      idx = index_from_word(pick(blk, (uint32_t)b & 3u), count);
-      drawn = b;
+    v[k] = 0.0f;
+    if (k < E && e < total) {
+      const int b = e / d.row, c = e - b * d.row;
+      if (b != drawn) {
+        const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, (uint32_t)(b >> 2), t, kStreamIndex, 0u);
+        idx = index_from_word(pick(blk, (uint32_t)b & 3u), count);
+        drawn = b;
+        if (c == 0) idx_out[b] = idx;
+      }
+      v[k] = src[(size_t)idx * d.row + c];
     }
-    const size_t slot = ((size_t)(t & 1u) * d.P + agent) * d.B + b;
-    d.batch[slot * d.row + c] = d.replay[((size_t)agent * d.capacity + idx) * d.row + c];
-    if (c == 0) d.idx[slot] = idx;
+  }
+#pragma unroll
+  for (int k = 0; k < kMaxE; ++k) {
+    const int e = (block * E + k) * 256 + tid;
+    if (k < E && e < total) dst[e] = v[k];
   }
 }
 

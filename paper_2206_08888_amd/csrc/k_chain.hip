@@ -147,6 +147,8 @@ hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
   const int nt = xcd_grid(d.P, d.B / d.rows_t), nc = xcd_grid(2 * d.P, d.B / d.rows_c);
   const int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
   const dim3 grid(nt + nc), block(kThreads);
+  if (!(d.rows_t == 16 && d.rows_c == 64) && !(d.rows_t == d.rows_c && (d.rows_t == 32 || d.rows_t == 64)))
+    return hipErrorInvalidValue;                     // the kernel exists for these row classes only
   if (d.rows_t == 16) {
     const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = Lds<2>(d.D).bytes(vec);
     k_target_critic<Rows16, Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);

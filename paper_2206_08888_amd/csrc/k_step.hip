@@ -105,6 +105,9 @@ hipError_t setup_step_kernel() {
 hipError_t launch_step(const PopDev& dev, uint32_t t, uint32_t launch_seq, int with_chains, int with_actor,
                        int prefetch_next, hipStream_t s) {
   PopDev d = dev;
+  const bool small = d.rows_t == 16 && d.rows_c == 64 && d.rows_a == 16;
+  if (!small && !(d.rows_t == d.rows_c && d.rows_c == d.rows_a && (d.rows_a == 32 || d.rows_a == 64)))
+    return hipErrorInvalidValue;                     // the kernel exists for these three row classes only
   d.sync_half = (int)(launch_seq & 1u);              // the previous launch of this kernel cleared this half
   StepGrid g;
   g.roles_c = wgrad_role_count(d, 0);

@@ -103,10 +103,20 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // Beside 16 P target workgroups of 16 rows, 64-row critic chains (8 P workgroups) keep the fused
   // target/critic launch of a small population within one workgroup per CU.
   d.rows_c = cls == 1 ? 32 : 64;
-  if (const char* env = getenv("POP_ROWS")) {       // 16, 32 or 64: override (measurements, tests)
+  if (c.algo == POP_ALGO_SAC && cls == 1) {           // one launch per chain, so each takes the rows that suit it:
+    // 64-row critic chains while they still fit one round of one workgroup per CU (51 against 59 us at P = 32),
+    // 16-row target chains while they fit one round of two per CU (44 against 46 us); the actor chain stays at 32
+    if ((int64_t)c.P * (c.batch / 64) * 2 <= 256) d.rows_c = 64;
+    if ((int64_t)c.P * (c.batch / 16) <= 512) d.rows_t = 16;
+  }
+  if (const char* env = getenv("POP_ROWS")) {       // 16, 32 or 64, or "target,critic,actor": override (measurements, tests)
     const int v = atoi(env);
-    if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; }
-    if (v == 32 || v == 64) d.rows_t = d.rows_c = d.rows_a = v;
+    int rt = 0, rc = 0, ra = 0;
+    auto ok = [](int r, bool chain16) { return r == 32 || r == 64 || (chain16 && r == 16); };
+    if (sscanf(env, "%d,%d,%d", &rt, &rc, &ra) == 3) {   // "target,critic,actor"
+      if (ok(rt, true) && ok(rc, false) && ok(ra, true)) { d.rows_t = rt; d.rows_c = rc; d.rows_a = ra; }
+    } else if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; }
+    else if (v == 32 || v == 64) d.rows_t = d.rows_c = d.rows_a = v;
   }
   // Wide inputs (SAC only; kernels with a pipelined first layer): 32-row chains -- with weights of
   // 2 MB per agent, 16-row workgroups re-read them from L2 often enough to be bound by that -- except

@@ -147,12 +147,15 @@ def test_agent_in_population_equals_agent_alone_bit_for_bit():
     full.close()
 
 
-def test_a_mid_size_population_uses_the_32_row_chains_and_still_matches():
-    """P = 20 is past the 16-row class: agents 0 and 19 against the oracle, one forced-free step each way."""
-    hps = sac_hparams(20)
-    gpu, orc, agents = make_sac_pair(P=20, capacity=600, hps=hps, agents=[0, 19])
+@pytest.mark.parametrize("P", [20, 36])
+def test_mid_size_populations_use_the_wider_chains_and_still_match(P):
+    """Past the 16-row class every chain has its own rows per workgroup: P = 20 runs 16-row target, 64-row critic
+    and 32-row actor chains, P = 36 32-row chains throughout.  First and last agent against the oracle, two free
+    steps."""
+    hps = sac_hparams(P)
+    gpu, orc, agents = make_sac_pair(P=P, capacity=600, hps=hps, agents=[0, P - 1])
     gpu.update(2); orc.update(2)
-    compare(gpu, orc, agents, 1e-4, "two SAC steps at P = 20")
+    compare(gpu, orc, agents, 1e-4, "two SAC steps at P = %d" % P)
     gpu.close()
 
 

@@ -162,26 +162,26 @@ __device__ inline uint64_t first_layer(const float* Xs, int xld, const float* ne
 }
 
 // Hidden layer in place on `buf`; `tail` is handed to the product (see gemm256).
-template <int MT, bool THROUGH = false, class Tail>
+template <int MT, bool THROUGH = false, bool FED = false, class Tail>
 __device__ inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, LayerPre<MT>& pre,
                                         float* Yg, int wave, int lane, Tail tail) {
   Acc<MT> acc;
   acc.zero();
   const float bb[2] = {pre.b2[0], pre.b2[1]};
-  gemm256<MT, false>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
+  gemm256<MT, false, 2, FED>(buf, kLda, net + L.w2, pre.w2, wave, lane, acc, tail);
   __syncthreads();                                   // every wavefront has read the input tile
   return relu_store<MT, THROUGH>(acc, bb, buf, Yg, wave, lane);
 }
 
 // dX = (dZ W^T) * mask written to global [rows][256]; column sums of the result
 // (over this workgroup's rows) go to colsum_out[256].
-template <int MT, bool THROUGH = false>
+template <int MT, bool THROUGH = false, bool FED = false>
 __device__ inline void input_grad_to_global(const float* Zl, const float* W, WeightBlock<MT, true>& w0, uint64_t mask,
                                             float* __restrict__ dXg, float* __restrict__ colsum_out, int wave,
                                             int lane) {
   Acc<MT> acc;
   acc.zero();
-  gemm256<MT, true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
+  gemm256<MT, true, 2, FED>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
   float cs[2] = {0.0f, 0.0f};
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
@@ -205,7 +205,9 @@ __device__ inline void input_grad_to_global(const float* Zl, const float* W, Wei
 //   G::R, G::kPad, G::Pre (prefetch record with load()), G::WtBlock + G::load_wt (block 0 of a
 //   transposed weight operand), first_layer, hidden_layer, input_grad_to_global,
 //   input_grad_to_lds, thin (thin products on the vector ALU).
-template <int MT>
+// FED: the 256-deep products issue their loads between the MFMAs (mfma_tiles.h) -- for kernels that run two
+// workgroups per CU.
+template <int MT, bool FED = false>
 struct Rows32 {                                      // 32 MT rows on v_mfma_f32_32x32x2_f32 (mfma_tiles.h)
   static constexpr int R = 32 * MT, kPad = 8;
   using Pre = LayerPre<MT>;
@@ -223,12 +225,12 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
   template <bool THROUGH, class Tail>
   __device__ static inline uint64_t hidden_layer(float* buf, const float* net, const NetLayout& L, Pre& pre, float* Yg,
                                                  int wave, int lane, Tail tail) {
-    return pop::hidden_layer<MT, THROUGH>(buf, net, L, pre, Yg, wave, lane, tail);
+    return pop::hidden_layer<MT, THROUGH, FED>(buf, net, L, pre, Yg, wave, lane, tail);
   }
   template <bool THROUGH>
   __device__ static inline void input_grad_to_global(const float* Zl, const float* W, WtBlock& w0, uint64_t mask,
                                                      float* dXg, float* colsum_out, int wave, int lane) {
-    pop::input_grad_to_global<MT, THROUGH>(Zl, W, w0, mask, dXg, colsum_out, wave, lane);
+    pop::input_grad_to_global<MT, THROUGH, FED>(Zl, W, w0, mask, dXg, colsum_out, wave, lane);
   }
   // buf <- (buf W^T) * mask in place; tail() as in gemm256
   template <class Tail>
@@ -236,7 +238,7 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
                                                   int lane, Tail tail) {
     Acc<MT> acc;
     acc.zero();
-    gemm256<MT, true>(buf, kLda, W, wt, wave, lane, acc, tail);
+    gemm256<MT, true, 2, FED>(buf, kLda, W, wt, wave, lane, acc, tail);
     __syncthreads();                                 // every wavefront is done reading the operand
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)

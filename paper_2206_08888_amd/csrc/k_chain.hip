@@ -37,8 +37,9 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_
   }
 }
 
-template <class G>
-__global__ __launch_bounds__(kThreads, 1) void k_actor(PopDev d, uint32_t t) {
+// PER_CU: workgroups per CU the register budget is set for
+template <class G, int PER_CU = 1>
+__global__ __launch_bounds__(kThreads, PER_CU) void k_actor(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
   if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, false>(d, t, agent, chunk, lds, 0);
@@ -116,6 +117,8 @@ hipError_t setup_kernels() {
   POP_SET_LDS(k_critic<Rows32Deep<1, 8>>);
   POP_SET_LDS(k_actor<Rows16>);
   POP_SET_LDS(k_actor<Rows32<1>>);
+  POP_SET_LDS(k_actor<Rows32<1, true>, 2>);
+  POP_SET_LDS(k_target_critic<Rows32<1, true>, Rows32<1, true>>);
   POP_SET_LDS(k_actor<Rows32<2>>);
   POP_SET_LDS(k_target_critic<Rows16, Rows32<2>>);
   POP_SET_LDS(k_target_critic<Rows32<1>, Rows32<1>>);
@@ -153,7 +156,9 @@ hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
     const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = Lds<2>(d.D).bytes(vec);
     k_target_critic<Rows16, Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
   } else if (d.rows_t == 32) {
-    k_target_critic<Rows32<1>, Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec), s>>>(d, t, nt);
+    // more workgroups than CUs: two share a CU, and the products that issue their loads between the MFMAs pay
+    if (nt + nc > kCUs) k_target_critic<Rows32<1, true>, Rows32<1, true>><<<grid, block, Lds<1>(d.D).bytes(vec), s>>>(d, t, nt);
+    else k_target_critic<Rows32<1>, Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec), s>>>(d, t, nt);
   } else {
     k_target_critic<Rows32<2>, Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec), s>>>(d, t, nt);
   }
@@ -162,6 +167,7 @@ hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_a)), block(kThreads);
   if (d.rows_a == 16) k_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  else if (d.rows_a == 32 && (int)grid.x > kCUs) k_actor<Rows32<1, true>, 2><<<grid, block, Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   else if (d.rows_a == 32) k_actor<Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   else k_actor<Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   return hipGetLastError();

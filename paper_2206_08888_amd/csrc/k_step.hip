@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
 }
 
 #define POP_STEP_SMALL k_step<Rows16, Rows32<2>, Rows16>
-#define POP_STEP_MID k_step<Rows32<1>, Rows32<1>, Rows32<1>>
+#define POP_STEP_MID k_step<Rows32<1, true>, Rows32<1, true>, Rows32<1, true>>
 #define POP_STEP_LARGE k_step<Rows32<2>, Rows32<2>, Rows32<2>>
 
 hipError_t setup_step_kernel() {

@@ -274,6 +274,23 @@ struct WeightBlock {                       // the weights one lane needs for a 1
           for (int nt = 0; nt < NT; ++nt) w[nt][4 * s + j] = col[(8 * s + j) * kH + 32 * nt];
     }
   }
+  // The same block as kPieces separate load instructions, in the order of use, from this lane's pointer into W
+  // (lane_base) moved on to block i by the caller: blk = lane_base(W) + 16 i kH (forward) or + 16 i (transposed).
+  static constexpr int kPieces = TRANSPOSED ? 2 * NT : 8 * NT;
+  __device__ static inline const float* lane_base(const float* __restrict__ W, int wave, int lane) {
+    const int half = lane >> 5, l32 = lane & 31;
+    return TRANSPOSED ? W + (32 * NT * wave + l32) * kH + 4 * half : W + 4 * half * kH + 32 * NT * wave + l32;
+  }
+  __device__ inline void load_piece(const float* __restrict__ blk, int p) {
+    if (TRANSPOSED) {
+      const int s = p / NT, nt = p % NT;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(blk + 32 * nt * kH + 8 * s);
+      w[nt][4 * s + 0] = v[0]; w[nt][4 * s + 1] = v[1]; w[nt][4 * s + 2] = v[2]; w[nt][4 * s + 3] = v[3];
+    } else {
+      const int s = p / (4 * NT), j = (p / NT) & 3, nt = p % NT;
+      w[nt][4 * s + j] = blk[(8 * s + j) * kH + 32 * nt];
+    }
+  }
 };
 
 template <int MT>
@@ -286,6 +303,10 @@ struct LdsBlock {                          // the LDS operand of one block (16 d
 #pragma unroll
       for (int s = 0; s < 2; ++s)
         a[mt][s] = *reinterpret_cast<const f32x4*>(&Xl[(32 * mt + l32) * ldx + k0 + 8 * s + 4 * half]);
+  }
+  __device__ inline void load_piece(const float* __restrict__ Xl, int ldx, int k0, int lane, int p) {   // p < 2 MT
+    const int half = lane >> 5, l32 = lane & 31, mt = p >> 1, s = p & 1;
+    a[mt][s] = *reinterpret_cast<const f32x4*>(&Xl[(32 * mt + l32) * ldx + k0 + 8 * s + 4 * half]);
   }
 };
 
@@ -300,6 +321,35 @@ __device__ inline void mfma_block(const LdsBlock<MT>& x, const WeightBlock<MT, T
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
           acc.t[mt][nt] = mfma32(x.a[mt][s][j], b.w[nt][4 * s + j], acc.t[mt][nt]);
+}
+
+// The MFMAs of one block with the loads of a later block (weights `nb` <- the block at `blk` when FEED, LDS operand
+// `nx` <- columns nk0.. when FEEDX) dealt out between them, one piece behind an MFMA until they are used up.  A
+// matrix instruction keeps its pipe busy for 64 cycles after it issues; address arithmetic and load instructions
+// issued in that shadow cost nothing, while a whole block's worth of them between two blocks leaves the pipe
+// idle for as long as they take to issue -- which shows where two workgroups share a CU and the other wavefront of
+// the SIMD is no further along (the scheduling barriers pin the order).  With one workgroup per CU the plain
+// order is the faster one: 8.7 against 10.2 us per 32-row product, but 25.7 against 20.7 us with two per CU.
+template <int MT, bool TRANSPOSED, int NT, bool FEED, bool FEEDX>
+__device__ inline void mfma_block_fed(const LdsBlock<MT>& x, const WeightBlock<MT, TRANSPOSED, NT>& b, Acc<MT, NT>& acc,
+                                      WeightBlock<MT, TRANSPOSED, NT>& nb, const float* __restrict__ blk, LdsBlock<MT>& nx,
+                                      const float* __restrict__ Xl, int ldx, int nk0, int lane) {
+  constexpr int M = 8 * MT * NT, L = WeightBlock<MT, TRANSPOSED, NT>::kPieces, LX = 2 * MT;
+  constexpr int every = M / L > 0 ? M / L : 1;      // one MFMA in `every` is followed by a weight piece
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+          const int m = ((s * 4 + j) * MT + mt) * NT + nt;
+          acc.t[mt][nt] = mfma32(x.a[mt][s][j], b.w[nt][4 * s + j], acc.t[mt][nt]);
+          if (FEEDX && m < LX) nx.load_piece(Xl, ldx, nk0, lane, m);
+          if (FEED && m % every == 0 && m / every < L) nb.load_piece(blk, m / every);
+          __builtin_amdgcn_sched_barrier(0);
+        }
 }
 
 struct NoTail { __device__ inline void operator()() const {} };
@@ -332,7 +382,22 @@ __device__ inline void gemm256_group(const float* __restrict__ Xl, int ldx, cons
   __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int MT, bool TRANSPOSED, int NT = 2, class Tail>
+// the same four blocks with the loads dealt out between the MFMAs; wg: this lane's pointer at block i
+template <int MT, bool TRANSPOSED, bool LAST, int NT, class Tail>
+__device__ inline void gemm256_group_fed(const float* __restrict__ Xl, int ldx, const float* __restrict__ wg, int i,
+                                         WeightBlock<MT, TRANSPOSED, NT>& b0, WeightBlock<MT, TRANSPOSED, NT>& b1,
+                                         WeightBlock<MT, TRANSPOSED, NT>& b2, WeightBlock<MT, TRANSPOSED, NT>& b3,
+                                         LdsBlock<MT>& x0, LdsBlock<MT>& x1, int lane, Acc<MT, NT>& acc, Tail& tail) {
+  constexpr int step = TRANSPOSED ? 16 : 16 * kH;    // floats from one block to the next
+  mfma_block_fed<MT, TRANSPOSED, NT, true, true>(x0, b0, acc, b3, wg + 3 * step, x1, Xl, ldx, 16 * (i + 1), lane);
+  if (LAST) tail();
+  mfma_block_fed<MT, TRANSPOSED, NT, !LAST, true>(x1, b1, acc, b0, wg + 4 * step, x0, Xl, ldx, 16 * (i + 2), lane);
+  mfma_block_fed<MT, TRANSPOSED, NT, !LAST, true>(x0, b2, acc, b1, wg + 5 * step, x1, Xl, ldx, 16 * (i + 3), lane);
+  mfma_block_fed<MT, TRANSPOSED, NT, !LAST, !LAST>(x1, b3, acc, b2, wg + 6 * step, x0, Xl, ldx, 16 * (i + 4), lane);
+}
+
+// FED: the loads of a block are issued between the MFMAs of an earlier one (mfma_block_fed) instead of ahead of them.
+template <int MT, bool TRANSPOSED, int NT = 2, bool FED = false, class Tail>
 __device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const float* __restrict__ W,
                                WeightBlock<MT, TRANSPOSED, NT>& b0, int wave, int lane, Acc<MT, NT>& acc, Tail tail) {
   WeightBlock<MT, TRANSPOSED, NT> b1, b2, b3;
@@ -341,6 +406,17 @@ __device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const floa
   b2.load(W, 2, wave, lane);
   x0.load(Xl, ldx, 0, lane);
   POP_MARK(20);
+  if (FED) {
+    const float* wg = WeightBlock<MT, TRANSPOSED, NT>::lane_base(W, wave, lane);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll 1
+    for (int i = 0; i < 12; i += 4) {
+      gemm256_group_fed<MT, TRANSPOSED, false, NT>(Xl, ldx, wg, i, b0, b1, b2, b3, x0, x1, lane, acc, tail);
+      wg += 4 * (TRANSPOSED ? 16 : 16 * kH);
+    }
+    gemm256_group_fed<MT, TRANSPOSED, true, NT>(Xl, ldx, wg, 12, b0, b1, b2, b3, x0, x1, lane, acc, tail);
+    return;
+  }
 #pragma unroll 1
   for (int i = 0; i < 12; i += 4) {
     gemm256_group<MT, TRANSPOSED, false, NT>(Xl, ldx, W, i, b0, b1, b2, b3, x0, x1, wave, lane, acc, tail);

@@ -280,15 +280,15 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->gathered_t = ~0ull;
   ctx->step_launches = 0;
   // One launch per step (parts handing over between workgroups) or one launch per part, by measurement over
-  // P = 2 .. 64 (us/step, single launch vs target+critic fused and the rest separate): 80 / 88 at P = 2,
-  // 99 / 101 at P = 10, 137 / 137 at P = 16, 177 / 163 at P = 20, 203 / 202 at P = 32, 246 / 282 at P = 42,
-  // 345 / 372 at P = 64.  Small populations (16-row class) fit the chip at once and save the launch
-  // boundaries; from P = 43 the parts are each several times larger than the 512 workgroups the chip holds and
-  // the tails of one part overlap the next; in between, waiting weight-gradient workgroups take the slots the
-  // actor chains could start in.  (The 64-row chains of very large populations do not fit the register budget
-  // of the single kernel without spilling and stay separate as well.)
+  // P = 2 .. 128 (us/step, single launch vs target+critic fused and the rest separate): 80 / 88 at P = 2,
+  // 99 / 101 at P = 10, 137 / 137 at P = 16, 171 / 154 at P = 20, 197 / 187 at P = 32, 214 / 238 at P = 36,
+  // 241 / 265 at P = 42, 340 / 352 at P = 64, 792 / 661 at P = 128.  Small populations (16-row class) fit the chip
+  // at once and save the launch boundaries; from P = 34 the parts are each several times larger than the 512
+  // workgroups the chip holds and the tails of one part overlap the next; in between, waiting weight-gradient
+  // workgroups take the slots the actor chains could start in.  (The 64-row chains of very large populations do
+  // not fit the register budget of the single kernel without spilling and stay separate as well.)
   const bool small = d.rows_t == 16 && d.rows_c == 64;
-  const bool large = d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 2 * 512;
+  const bool large = d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 800;
   ctx->fuse = (small || large) ? 2 : 1;
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = 0;     // measured at P = 32: fusing target and critic chains loses 4 %
   if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 1;   // target and critic chains together; the critic's weight step is a reduction of its own

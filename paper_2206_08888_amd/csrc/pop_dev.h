@@ -30,6 +30,7 @@ constexpr int kMaxIn = 64;     // TD3: largest first-layer fan-in (obs_dim + act
 constexpr int kMaxAct = 8;     // TD3: largest action dimension; also the row stride of the small LDS scratch blocks
 constexpr int kSacMaxIn = 448; // SAC: largest first-layer fan-in (the Humanoid shapes need 393)
 constexpr int kSacMaxAct = 24; // SAC: largest action dimension (Humanoid: 17) and row stride of its scratch blocks
+constexpr int kCUs = 256;       // compute units of the chip
 constexpr int kLdsPerCU = 160 * 1024;   // bytes of LDS one workgroup can ask for
 constexpr int kMaxHead = 48;   // largest actor head: 2 * kSacMaxAct outputs (mean and log-std of the SAC policy)
 

@@ -324,18 +324,27 @@ __device__ inline void mfma_block(const LdsBlock<MT>& x, const WeightBlock<MT, T
 }
 
 // The MFMAs of one block with the loads of a later block (weights `nb` <- the block at `blk` when FEED, LDS operand
-// `nx` <- columns nk0.. when FEEDX) dealt out between them, one piece behind an MFMA until they are used up.  A
-// matrix instruction keeps its pipe busy for 64 cycles after it issues; address arithmetic and load instructions
-// issued in that shadow cost nothing, while a whole block's worth of them between two blocks leaves the pipe
-// idle for as long as they take to issue -- which shows where two workgroups share a CU and the other wavefront of
-// the SIMD is no further along (the scheduling barriers pin the order).  With one workgroup per CU the plain
-// order is the faster one: 8.7 against 10.2 us per 32-row product, but 25.7 against 20.7 us with two per CU.
+// `nx` <- columns nk0.. when FEEDX) dealt out between them, one piece behind an MFMA until they are used up
+// (scheduling groups tell the compiler that order).  A matrix instruction keeps its pipe busy for 64 cycles after
+// it issues; load instructions issued in that shadow cost nothing, while a whole block's worth of them between
+// two blocks -- some 16 cycles each -- leaves the pipe idle for as long as they take to issue.  That shows where
+// two workgroups share a CU and the other wavefront of the SIMD is no further along: 25.6 us per 32-row product
+// for such a pair, 19.9 us in this form.  With one workgroup per CU the plain order is the faster one (8.7
+// against 9.4 us).
 template <int MT, bool TRANSPOSED, int NT, bool FEED, bool FEEDX>
 __device__ inline void mfma_block_fed(const LdsBlock<MT>& x, const WeightBlock<MT, TRANSPOSED, NT>& b, Acc<MT, NT>& acc,
                                       WeightBlock<MT, TRANSPOSED, NT>& nb, const float* __restrict__ blk, LdsBlock<MT>& nx,
                                       const float* __restrict__ Xl, int ldx, int nk0, int lane) {
   constexpr int M = 8 * MT * NT, L = WeightBlock<MT, TRANSPOSED, NT>::kPieces, LX = 2 * MT;
   constexpr int every = M / L > 0 ? M / L : 1;      // one MFMA in `every` is followed by a weight piece
+  if (FEEDX) {
+#pragma unroll
+    for (int p = 0; p < LX; ++p) nx.load_piece(Xl, ldx, nk0, lane, p);
+  }
+  if (FEED) {
+#pragma unroll
+    for (int p = 0; p < L; ++p) nb.load_piece(blk, p);
+  }
 #pragma unroll
   for (int s = 0; s < 2; ++s)
 #pragma unroll
@@ -343,13 +352,15 @@ __device__ inline void mfma_block_fed(const LdsBlock<MT>& x, const WeightBlock<M
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          const int m = ((s * 4 + j) * MT + mt) * NT + nt;
+        for (int nt = 0; nt < NT; ++nt)
           acc.t[mt][nt] = mfma32(x.a[mt][s][j], b.w[nt][4 * s + j], acc.t[mt][nt]);
-          if (FEEDX && m < LX) nx.load_piece(Xl, ldx, nk0, lane, m);
-          if (FEED && m % every == 0 && m / every < L) nb.load_piece(blk, m / every);
-          __builtin_amdgcn_sched_barrier(0);
-        }
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if (FEEDX && m < LX) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    if (FEED && m % every == 0 && m / every < L) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 struct NoTail { __device__ inline void operator()() const {} };

@@ -161,7 +161,8 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   const Adam adam = *sh;
   Acc<1, 1> acc;
   acc.zero();
-  gemm256_unrolled<1, false, 1, 8>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());
+  gemm256_unrolled<1, false, 1, 8, true>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());   // loads between the MFMAs: a
+                                                     // block is 8 MFMAs and 8 load instructions, and these kernels run two workgroups per CU
   POP_MARK(53);
   uint32_t e1 = elem0;
   asm volatile("" : "+v"(e1));                       // recompute the addresses: keeping 64 of them alive costs more

@@ -129,7 +129,7 @@ hipError_t setup_kernels() {
 }
 
 // Rows per workgroup come in three classes (pop_dev.h): (target, critic, actor) = (16, 64, 16)
-// for small populations, (32, 32, 32), and (64, 64, 64) for large ones.
+// for small populations, else (32, 32, 32); (64, 64, 64) on request.
 hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_t)), block(kThreads);
   if (d.rows_t == 16) k_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_target(d)), s>>>(d, t);

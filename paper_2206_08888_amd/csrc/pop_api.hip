@@ -92,14 +92,14 @@ void fill_dims(const pop_config& c, PopDev& d) {
   d.algo = c.algo;
   d.P = c.P; d.O = c.obs_dim; d.A = c.act_dim; d.D = c.obs_dim + c.act_dim; d.B = c.batch;
   d.row = 2 * c.obs_dim + c.act_dim + 2;
-  // Rows per workgroup of the layer chains.  64 once that still gives every CU two workgroups
-  // (halves the weight traffic per row).  16 for the target and actor chains of small
+  // Rows per workgroup of the layer chains.  16 for the target and actor chains of small
   // populations: those parts have only 8 P workgroups at 32 rows, well under the 256 CUs, and
   // their latency is what a step waits for; 16-row tiles halve the matrix time of every
-  // product by spreading it over twice the CUs.  Else 32.
-  int cls = ((int64_t)c.P * (c.batch / 64) >= 512) ? 2 : ((int64_t)c.P * (c.batch / 16) <= 256 ? 0 : 1);
-  if (c.algo == POP_ALGO_SAC && cls == 2) cls = 1;   // the SAC actor chain (six products) spills at 64 rows
-  d.rows_t = d.rows_a = cls == 2 ? 64 : (cls == 0 ? 16 : 32);
+  // product by spreading it over twice the CUs.  Else 32.  (64-row chains for all three parts, half the weight
+  // traffic per row, exist as well -- POP_ROWS=64 -- and were the choice from 128 agents on until the 32-row
+  // products learnt to issue their loads between the MFMAs: 1297 against 1278 us/step at P = 256, equal at 128.)
+  const int cls = (int64_t)c.P * (c.batch / 16) <= 256 ? 0 : 1;
+  d.rows_t = d.rows_a = cls == 0 ? 16 : 32;
   // Beside 16 P target workgroups of 16 rows, 64-row critic chains (8 P workgroups) keep the fused
   // target/critic launch of a small population within one workgroup per CU.
   d.rows_c = cls == 1 ? 32 : 64;
@@ -282,13 +282,14 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   // One launch per step (parts handing over between workgroups) or one launch per part, by measurement over
   // P = 2 .. 128 (us/step, single launch vs target+critic fused and the rest separate): 80 / 88 at P = 2,
   // 99 / 101 at P = 10, 137 / 137 at P = 16, 171 / 154 at P = 20, 197 / 187 at P = 32, 214 / 238 at P = 36,
-  // 241 / 265 at P = 42, 340 / 352 at P = 64, 792 / 661 at P = 128.  Small populations (16-row class) fit the chip
+  // 241 / 265 at P = 42, 340 / 352 at P = 64.  Small populations (16-row class) fit the chip
   // at once and save the launch boundaries; from P = 34 the parts are each several times larger than the 512
   // workgroups the chip holds and the tails of one part overlap the next; in between, waiting weight-gradient
-  // workgroups take the slots the actor chains could start in.  (The 64-row chains of very large populations do
-  // not fit the register budget of the single kernel without spilling and stay separate as well.)
+  // workgroups take the slots the actor chains could start in; from about a hundred agents the separate launches
+  // are ahead again by a per cent or two (657 / 665 at P = 128, 1278 / 1319 at P = 256, 32-row chains).
   const bool small = d.rows_t == 16 && d.rows_c == 64;
-  const bool large = d.rows_c == 32 && (int64_t)cfg->P * (cfg->batch / 32) * 3 > 800;
+  const int64_t chain_blocks = (int64_t)cfg->P * (cfg->batch / 32) * 3;
+  const bool large = d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2400;
   ctx->fuse = (small || large) ? 2 : 1;
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = 0;     // measured at P = 32: fusing target and critic chains loses 4 %
   if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 1;   // target and critic chains together; the critic's weight step is a reduction of its own

@@ -301,6 +301,32 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
             assert np.array_equal(states[0][key], other[key]), key
 
 
+def test_sixty_four_row_chains_match_oracle_and_each_other(monkeypatch):
+    """No population gets 64-row target and actor chains by default any more (the 32-row ones overtook them);
+    POP_ROWS=64 still selects them.  P = 5 with mixed delays, 5 steps: against the oracle, and one launch per step
+    against one launch per part bit for bit."""
+    hps = workloads.hparams(2, 5)
+    for i, hp in enumerate(hps):
+        hp["policy_delay"] = (2, 1, 3)[i % 3]
+    monkeypatch.setenv("POP_ROWS", "64")
+    states = []
+    for fuse in ("1", "2", "0"):
+        monkeypatch.setenv("POP_FUSE", fuse)
+        gpu, orc, _ = make_pair(2, P=5, capacity=2000, hps=hps, oracle=(fuse == "1"))
+        gpu.update(5)
+        if orc is not None:
+            orc.update(5)
+            for i in range(5):
+                for w in NETS:
+                    assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 1e-4, (i, w)
+        gpu.sync()
+        states.append({(i, w): gpu.get_params(i, w) for i in range(5) for w in STATE12})
+        gpu.close()
+    for other in states[1:]:
+        for key in states[0]:
+            assert np.array_equal(states[0][key], other[key]), key
+
+
 def test_copy_agent_and_set_hparams_follow_the_oracle():
     """The population step of App. B.1 on both sides: train, replace agent 0 by a copy of
     agent 2 (with its buffer) and agent 1 by a copy of agent 3 (keeping its own buffer), give

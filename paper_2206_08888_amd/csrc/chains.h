@@ -510,7 +510,8 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   G::template hidden_layer<false>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
   POP_MARK(33);
-  head_mfma<R>(buf, ta + d.actor.w3, d.A, head, kMaxAct, wave, lane);   // the head's weights straight from global memory
+  if (R <= 32) head_mfma_split<R <= 32 ? R : 16, false>(buf, ta + d.actor.w3, d.A, head, kMaxAct, wave, lane, v_cb3 + 8);
+  else head_mfma<R>(buf, ta + d.actor.w3, d.A, head, kMaxAct, wave, lane);   // the head's weights straight from global memory
   __syncthreads();
   POP_MARK(34);
   for (int e = tid; e < R * d.A; e += kThreads) {
@@ -704,7 +705,8 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   G::template hidden_layer<false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
                          [&]() { if (!WAIT) pre.load(cn, d.critic, wave, lane); });
   __syncthreads();
-  head_mfma<R>(buf, an + d.actor.w3, A, head, kMaxAct, wave, lane);
+  if (R <= 32) head_mfma_split<R <= 32 ? R : 16, false>(buf, an + d.actor.w3, A, head, kMaxAct, wave, lane, v_cw3 + kH);
+  else head_mfma<R>(buf, an + d.actor.w3, A, head, kMaxAct, wave, lane);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
     const int r = e / A, j = e - r * A;
@@ -761,7 +763,8 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   }
   __syncthreads();
   POP_MARK(12);
-  head_mfma_t<R>(buf, cn + d.critic.w1 + d.O * kH, A, head, kMaxAct, wave, lane);   // da
+  if (R <= 32) head_mfma_split<R <= 32 ? R : 16, true>(buf, cn + d.critic.w1 + d.O * kH, A, head, kMaxAct, wave, lane, v_cw3 + kH);   // da
+  else head_mfma_t<R>(buf, cn + d.critic.w1 + d.O * kH, A, head, kMaxAct, wave, lane);
   G::load_wt(wt, an + d.actor.w2, wave, lane);       // block 0 of the actor's input-gradient product
   __syncthreads();
   for (int e = tid; e < R * kMaxAct; e += kThreads) {
@@ -825,9 +828,9 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
 }
 
 // floats of staged vectors behind the LDS map of each chain
-inline int vec_target(const PopDev&) { return 8 + 2 * kH + 8; }
+inline int vec_target(const PopDev&) { return 8 + 2 * kH + 8 + kHeadRed; }
 inline int vec_critic(const PopDev&) { return kH + 8; }
-inline int vec_actor(const PopDev&) { return 8 + kH; }
+inline int vec_actor(const PopDev&) { return 8 + kH + kHeadRed; }
 inline int vec_act(const PopDev& d) { return kH * d.actor.out + kMaxHead; }
 constexpr int kActScratch = 2 * (kSacMaxAct / kMaxAct);   // acting: two head blocks of [32][kSacMaxAct]
 

@@ -318,6 +318,56 @@ __device__ inline void head_mfma_t(const float* __restrict__ Xl, const float* __
   }
 }
 
+// The same two products with the contraction split over the four wavefronts (64 deep each), for heads of at most
+// 16 columns on 16 or 32 rows: dealt out as whole tiles only one or two wavefronts would work, each through 64
+// MFMAs that wait for one another (2 us; 0.7 this way).  BY_ROWS: W as for head_mfma_t, else as for head_mfma.
+// The partial tiles meet in LDS (red: [R / 16][4][16][16] floats) and are added in wavefront order.  Contains a
+// workgroup barrier; the caller still places one before `outl` is read.
+constexpr int kHeadRed = 2 * 4 * 256;                // floats of `red` for R <= 32
+template <int R, bool BY_ROWS>
+__device__ inline void head_mfma_split(const float* __restrict__ Xl, const float* __restrict__ W, int J,
+                                       float* __restrict__ outl, int stride, int wave, int lane, float* __restrict__ red) {
+  static_assert(R == 16 || R == 32, "wider tiles keep every wavefront busy as whole tiles");
+  constexpr int RT = R / 16;
+  const int c = lane & 15, kq = lane >> 4;
+  const bool ok = c < J;
+  const int k0 = 64 * wave + 4 * kq;                 // MFMA j of block i contracts k = k0 + 16 i + j
+  f32x4 b[4];
+  if (BY_ROWS) {
+    const float* wp = W + (size_t)(ok ? c : 0) * kH + k0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = *reinterpret_cast<const f32x4*>(wp + 16 * i);
+  } else {
+    const float* wp = W + (ok ? c : 0) + (size_t)k0 * J;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[i][j] = wp[(size_t)(16 * i + j) * J];
+  }
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    f32x4 acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x4 a = *reinterpret_cast<const f32x4*>(&Xl[(16 * rt + c) * kLda + k0 + 16 * i]);
+      acc0 = mfma16(a[0], ok ? b[i][0] : 0.0f, acc0);
+      acc1 = mfma16(a[1], ok ? b[i][1] : 0.0f, acc1);
+      acc0 = mfma16(a[2], ok ? b[i][2] : 0.0f, acc0);
+      acc1 = mfma16(a[3], ok ? b[i][3] : 0.0f, acc1);
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[((rt * 4 + wave) * 16 + 4 * kq + v) * 16 + c] = acc0[v] + acc1[v];
+  }
+  __syncthreads();
+  const int row = (64 * wave + lane) >> 4;           // 256 threads: one element of each row tile
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const float* p = red + (rt * 4 * 16 + row) * 16 + c;
+    const float sum = ((p[0] + p[256]) + p[512]) + p[768];
+    if (ok) outl[(16 * rt + row) * stride + c] = sum;
+  }
+}
+
 __device__ inline bool mask_bit16(uint64_t mask, int nt, int v) { return (mask >> (4 * nt + v)) & 1ull; }
 
 // Thin products for 16 rows: out[r*stride + j] = sum_{c<256} X[r][c] V[j*256 + c], r < 16, j < J <= 8.

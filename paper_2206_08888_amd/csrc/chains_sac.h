@@ -48,8 +48,8 @@ static_assert(kSs % kMaxAct == 0 && 2 * kSs >= kMaxHead, "dz3 rows of kMaxHead f
 // vectors the chains keep in LDS: the actor's head bias, the two critic heads and their biases (the wide
 // operands -- the actor's head, the critics' first-layer rows of the action -- go through the matrix pipe
 // straight from global memory)
-inline int vec_sac_target(const PopDev&) { return kMaxHead + 2 * kH + 8; }
-inline int vec_sac_actor(const PopDev&) { return kMaxHead + 2 * kH + 8; }
+inline int vec_sac_target(const PopDev&) { return kMaxHead + 2 * kH + 8 + kHeadRed; }
+inline int vec_sac_actor(const PopDev&) { return kMaxHead + 2 * kH + 8 + kHeadRed; }
 
 // ---------------------------------------------------------------------------------------------
 // Target chain.  One workgroup per (agent, chunk).
@@ -90,7 +90,8 @@ __device__ __forceinline__ void sac_target_chain(const PopDev& d, uint32_t t, in
   G::template hidden_layer<false>(buf, an, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
   POP_MARK(3);
-  head_mfma<R>(buf, an + d.actor.w3, 2 * A, hd, kMaxHead, wave, lane);
+  if (R <= 32 && 2 * A <= 16) head_mfma_split<R <= 32 ? R : 16, false>(buf, an + d.actor.w3, 2 * A, hd, kMaxHead, wave, lane, v_cb3 + 8);
+  else head_mfma<R>(buf, an + d.actor.w3, 2 * A, hd, kMaxHead, wave, lane);
   __syncthreads();
   POP_MARK(4);
   for (int e = tid; e < R * A; e += kThreads) {
@@ -229,7 +230,8 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
                                   [&]() { pre.load(cn[0], d.critic, wave, lane); });
   __syncthreads();
   POP_MARK(22);
-  head_mfma<R>(buf, an + d.actor.w3, H2, hd, kMaxHead, wave, lane);
+  if (R <= 32 && H2 <= 16) head_mfma_split<R <= 32 ? R : 16, false>(buf, an + d.actor.w3, H2, hd, kMaxHead, wave, lane, v_cb3 + 8);
+  else head_mfma<R>(buf, an + d.actor.w3, H2, hd, kMaxHead, wave, lane);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
     const int r = e / A, j = e - r * A, o = r * kSs + j, om = r * kMaxHead + j, ol = om + A;
@@ -301,7 +303,8 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
     });                                              // buf = dz1 of critic k
     __syncthreads();
-    head_mfma_t<R>(buf, cn[k] + d.critic.w1 + d.O * kH, A, k == 0 ? da1 : da2, kSs, wave, lane);
+    if (R <= 32 && A <= 16) head_mfma_split<R <= 32 ? R : 16, true>(buf, cn[k] + d.critic.w1 + d.O * kH, A, k == 0 ? da1 : da2, kSs, wave, lane, v_cb3 + 8);
+    else head_mfma_t<R>(buf, cn[k] + d.critic.w1 + d.O * kH, A, k == 0 ? da1 : da2, kSs, wave, lane);
     if (k == 0) G::load_wt(wt, cn[1] + d.critic.w2, wave, lane);
     else G::load_wt(wt, an + d.actor.w2, wave, lane);
     __syncthreads();

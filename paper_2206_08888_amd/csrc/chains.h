@@ -70,8 +70,8 @@ struct LayerPre {
     w2.load(net + L.w2, 0, wave, lane);
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
-      b1[nt] = net[L.b1 + 64 * wave + 32 * nt + (lane & 31)];
-      b2[nt] = net[L.b2 + 64 * wave + 32 * nt + (lane & 31)];
+      b1[nt] = net[L.b1 + tile_col(wave, nt, lane)];
+      b2[nt] = net[L.b2 + tile_col(wave, nt, lane)];
     }
   }
 };
@@ -183,21 +183,19 @@ __device__ inline void input_grad_to_global(const float* Zl, const float* W, Wei
   acc.zero();
   gemm256<MT, true, 2, FED>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
   float cs[2] = {0.0f, 0.0f};
+  const int col = tile_col(wave, 0, lane);
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float z = mask_bit(mask, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;
-        put<THROUGH>(dXg + (32 * mt + acc_row(v, lane)) * kH + 64 * wave + 32 * nt + (lane & 31), z);
-        cs[nt] += z;
-      }
-#pragma unroll
-  for (int nt = 0; nt < 2; ++nt) {
-    const float tot = cs[nt] + __shfl_xor(cs[nt], 32);
-    if (lane < 32) put<THROUGH>(colsum_out + 64 * wave + 32 * nt + lane, tot);
-  }
+    for (int v = 0; v < 16; ++v) {
+      const float z0 = mask_bit(mask, mt, 0, v) ? acc.t[mt][0][v] : 0.0f;
+      const float z1 = mask_bit(mask, mt, 1, v) ? acc.t[mt][1][v] : 0.0f;
+      put2<THROUGH>(dXg + (32 * mt + acc_row(v, lane)) * kH + col, z0, z1);
+      cs[0] += z0;
+      cs[1] += z1;
+    }
+  const float t0 = cs[0] + __shfl_xor(cs[0], 32), t1 = cs[1] + __shfl_xor(cs[1], 32);
+  if (lane < 32) put2<THROUGH>(colsum_out + col, t0, t1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -240,14 +238,13 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
     acc.zero();
     gemm256<MT, true, 2, FED>(buf, kLda, W, wt, wave, lane, acc, tail);
     __syncthreads();                                 // every wavefront is done reading the operand
+    const int col = tile_col(wave, 0, lane);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          buf[(32 * mt + acc_row(v, lane)) * kLda + 64 * wave + 32 * nt + (lane & 31)] =
-              mask_bit(mask, mt, nt, v) ? acc.t[mt][nt][v] : 0.0f;
+      for (int v = 0; v < 16; ++v)
+        *reinterpret_cast<f32x2*>(&buf[(32 * mt + acc_row(v, lane)) * kLda + col]) =
+            f32x2{mask_bit(mask, mt, 0, v) ? acc.t[mt][0][v] : 0.0f, mask_bit(mask, mt, 1, v) ? acc.t[mt][1][v] : 0.0f};
   }
   __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid, int stride = kMaxAct) {
     thin_dot<R>(Xl, V, J, outl, tid, stride);
@@ -255,17 +252,16 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
   // buf[row][col] = mask ? rowvec[row] * colvec[col] : 0  (mask as returned by hidden_layer)
   __device__ static inline void store_outer_masked(float* buf, uint64_t mask, const float* rowvec, const float* colvec,
                                                    int wave, int lane) {
+    const int col = tile_col(wave, 0, lane);
+    const f32x2 cv = *reinterpret_cast<const f32x2*>(&colvec[col]);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        const int col = 64 * wave + 32 * nt + (lane & 31);
-        const float cv = colvec[col];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = 32 * mt + acc_row(v, lane);
-          buf[row * kLda + col] = mask_bit(mask, mt, nt, v) ? rowvec[row] * cv : 0.0f;
-        }
+      for (int v = 0; v < 16; ++v) {
+        const int row = 32 * mt + acc_row(v, lane);
+        const float rv = rowvec[row];
+        *reinterpret_cast<f32x2*>(&buf[row * kLda + col]) =
+            f32x2{mask_bit(mask, mt, 0, v) ? rv * cv[0] : 0.0f, mask_bit(mask, mt, 1, v) ? rv * cv[1] : 0.0f};
       }
   }
 };

@@ -30,6 +30,7 @@ namespace pop {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 __device__ inline f32x16 mfma32(float a, float b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
@@ -44,8 +45,22 @@ __device__ inline void put(float* p, float v) {
   if (THROUGH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   else *p = v;
 }
+// the same for two neighbouring floats at an 8-byte aligned address (a lane's two columns, tile_col)
+template <bool THROUGH>
+__device__ inline void put2(float* p, float a, float b) {
+  if (THROUGH) {
+    const unsigned long long word = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else {
+    *reinterpret_cast<f32x2*>(p) = f32x2{a, b};
+  }
+}
 
 __device__ inline int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+// Column (of 256) that a lane holds of tile nt of its wavefront's two accumulator tiles: the lane's two columns
+// are neighbours, so that a forward product fetches both weights of a row with one 8-byte load (half the load
+// instructions, which is what the forward products were short of).
+__device__ inline int tile_col(int wave, int nt, int lane) { return 64 * wave + 2 * (lane & 31) + nt; }
 
 // NT = 32-column tiles per wavefront: 2 in the layer chains (a workgroup spans 256
 // columns), 1 in the weight-gradient tiles (128 columns per workgroup).
@@ -72,7 +87,7 @@ __device__ inline void for_each_acc(const Acc<MT>& acc, int wave, int lane, F f)
     for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        f(32 * mt + acc_row(v, lane), 64 * wave + 32 * nt + (lane & 31), acc.t[mt][nt][v]);
+        f(32 * mt + acc_row(v, lane), tile_col(wave, nt, lane), acc.t[mt][nt][v]);
 }
 
 // First-layer weights of one lane for the leading 32 rows of W (k = 8 i + 4 half + j),
@@ -81,18 +96,16 @@ struct SmallW {
   float w[4][2][4];
   __device__ inline void load(const float* __restrict__ W, int K, int wave, int lane) {
     const int half = lane >> 5, l32 = lane & 31;
-    const float* wcol = W + 64 * wave + l32;
+    const float* wcol = W + tile_col(wave, 0, l32);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int k = 8 * i + 4 * half + j;
         const int kk = k < K ? k : 0;                 // always a valid row: the load needs no branch
+        const f32x2 v = *reinterpret_cast<const f32x2*>(wcol + kk * kH);
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-          const float v = wcol[kk * kH + 32 * nt];
-          w[i][nt][j] = k < K ? v : 0.0f;
-        }
+        for (int nt = 0; nt < 2; ++nt) w[i][nt][j] = k < K ? v[nt] : 0.0f;
       }
   }
 };
@@ -121,14 +134,15 @@ __device__ inline void gemm_xw_small(const float* __restrict__ Xl, int ldx, int 
           for (int nt = 0; nt < 2; ++nt) acc.t[mt][nt] = mfma32(a[mt][j], pre.w[i][nt][j], acc.t[mt][nt]);
     }
   }
-  const float* wcol = W + 64 * wave + l32;
+  const float* wcol = W + tile_col(wave, 0, l32);
   for (int k0 = 32; k0 < K8; k0 += 8) {              // fan-in beyond 32: plain loop
     float b[2][4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int k = k0 + 4 * half + j;
+      const f32x2 v = *reinterpret_cast<const f32x2*>(wcol + (size_t)(k < K ? k : 0) * kH);
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) b[nt][j] = k < K ? wcol[(size_t)k * kH + 32 * nt] : 0.0f;
+      for (int nt = 0; nt < 2; ++nt) b[nt][j] = k < K ? v[nt] : 0.0f;
     }
     f32x4 a[MT];
 #pragma unroll
@@ -150,17 +164,15 @@ __device__ inline void gemm_xw_deep(const float* __restrict__ Xl, int ldx, int K
                                     const SmallW& pre, int wave, int lane, Acc<MT>& acc) {
   const int half = lane >> 5, l32 = lane & 31;
   const int nb = (K + 7) >> 3;                       // 8-deep blocks in all; 0 .. 3 come from `pre`
-  const float* wcol = W + 64 * wave + l32;
+  const float* wcol = W + tile_col(wave, 0, l32);
   float b[PF][2][4];
   auto request = [&](float (&dst)[2][4], int blk) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int k = 8 * blk + 4 * half + j;
+      const f32x2 v = *reinterpret_cast<const f32x2*>(wcol + (size_t)(k < K ? k : 0) * kH);
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        const float v = wcol[(size_t)(k < K ? k : 0) * kH + 32 * nt];
-        dst[nt][j] = k < K ? v : 0.0f;
-      }
+      for (int nt = 0; nt < 2; ++nt) dst[nt][j] = k < K ? v[nt] : 0.0f;
     }
   };
 #pragma unroll
@@ -203,9 +215,11 @@ __device__ inline void gemm_xw_deep(const float* __restrict__ Xl, int ldx, int K
       for (int j = 0; j < 4; ++j) w[nt][j] = b[s][nt][j];
     if (fast) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) b[s][nt][j] = wrun[j * kH + 32 * nt];
+      for (int j = 0; j < 4; ++j) {
+        const f32x2 v = *reinterpret_cast<const f32x2*>(wrun + j * kH);
+        b[s][0][j] = v[0];
+        b[s][1][j] = v[1];
+      }
     } else if (next_w) {
       request(b[s], i + PF);
     }
@@ -252,18 +266,33 @@ __device__ inline void gemm_xw_deep(const float* __restrict__ Xl, int ldx, int K
 template <int MT, bool TRANSPOSED, int NT = 2>
 struct WeightBlock {                       // the weights one lane needs for a 16-deep block
   float w[NT][8];                          // [column tile][4 s + j]  <->  index 16 i + 8 s + 4 half + j
+  // column of W (forward) or row of W (transposed) that lane l32 holds of tile nt: with two tiles per wavefront
+  // the lane's two columns are neighbours, so that the forward product fetches both with one load
+  __device__ static constexpr int col_of(int wave, int nt, int l32) {
+    return NT == 2 ? tile_col(wave, nt, l32) : 32 * wave + l32;
+  }
   __device__ inline void load(const float* __restrict__ W, int i, int wave, int lane) {
     const int half = lane >> 5, l32 = lane & 31;
     if (TRANSPOSED) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
-        const float* row = W + (32 * NT * wave + 32 * nt + l32) * kH + 16 * i + 4 * half;
+        const float* row = W + col_of(wave, nt, l32) * kH + 16 * i + 4 * half;
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
           const f32x4 v = *reinterpret_cast<const f32x4*>(row + 8 * s);
           w[nt][4 * s + 0] = v[0]; w[nt][4 * s + 1] = v[1]; w[nt][4 * s + 2] = v[2]; w[nt][4 * s + 3] = v[3];
         }
       }
+    } else if (NT == 2) {                            // the lane's two columns are neighbours: one 8-byte load per row
+      const float* col = W + (16 * i + 4 * half) * kH + 64 * wave + 2 * l32;
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const f32x2 v = *reinterpret_cast<const f32x2*>(col + (8 * s + j) * kH);
+          w[0][4 * s + j] = v[0];
+          w[NT - 1][4 * s + j] = v[1];
+        }
     } else {
       const float* col = W + (16 * i + 4 * half) * kH + 32 * NT * wave + l32;
 #pragma unroll
@@ -276,19 +305,24 @@ struct WeightBlock {                       // the weights one lane needs for a 1
   }
   // The same block as kPieces separate load instructions, in the order of use, from this lane's pointer into W
   // (lane_base) moved on to block i by the caller: blk = lane_base(W) + 16 i kH (forward) or + 16 i (transposed).
-  static constexpr int kPieces = TRANSPOSED ? 2 * NT : 8 * NT;
+  static constexpr int kPieces = TRANSPOSED ? 2 * NT : 8;
   __device__ static inline const float* lane_base(const float* __restrict__ W, int wave, int lane) {
     const int half = lane >> 5, l32 = lane & 31;
-    return TRANSPOSED ? W + (32 * NT * wave + l32) * kH + 4 * half : W + 4 * half * kH + 32 * NT * wave + l32;
+    return TRANSPOSED ? W + col_of(wave, 0, l32) * kH + 4 * half : W + 4 * half * kH + col_of(wave, 0, l32);
   }
   __device__ inline void load_piece(const float* __restrict__ blk, int p) {
     if (TRANSPOSED) {
       const int s = p / NT, nt = p % NT;
-      const f32x4 v = *reinterpret_cast<const f32x4*>(blk + 32 * nt * kH + 8 * s);
+      const f32x4 v = *reinterpret_cast<const f32x4*>(blk + (col_of(0, nt, 0) - col_of(0, 0, 0)) * kH + 8 * s);
       w[nt][4 * s + 0] = v[0]; w[nt][4 * s + 1] = v[1]; w[nt][4 * s + 2] = v[2]; w[nt][4 * s + 3] = v[3];
+    } else if (NT == 2) {
+      const int s = p >> 2, j = p & 3;
+      const f32x2 v = *reinterpret_cast<const f32x2*>(blk + (8 * s + j) * kH);
+      w[0][4 * s + j] = v[0];
+      w[NT - 1][4 * s + j] = v[1];
     } else {
-      const int s = p / (4 * NT), j = (p / NT) & 3, nt = p % NT;
-      w[nt][4 * s + j] = blk[(8 * s + j) * kH + 32 * nt];
+      const int s = p >> 2, j = p & 3;
+      w[0][4 * s + j] = blk[(8 * s + j) * kH];
     }
   }
 };
@@ -487,19 +521,18 @@ template <int MT, bool THROUGH = false>
 __device__ inline uint64_t relu_store(const Acc<MT>& acc, const float (&bb)[2], float* __restrict__ Yl,
                                       float* __restrict__ Yg, int wave, int lane) {
   uint64_t mask = 0;
+  const int col = tile_col(wave, 0, lane);           // the lane's two columns go out as one 8-byte store
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = 32 * mt + acc_row(v, lane);
-        const int col = 64 * wave + 32 * nt + (lane & 31);
-        const float h = fmaxf(acc.t[mt][nt][v] + bb[nt], 0.0f);
-        if (h > 0.0f) mask |= 1ull << ((2 * mt + nt) * 16 + v);
-        Yl[row * kLda + col] = h;
-        if (Yg) put<THROUGH>(Yg + (size_t)row * kH + col, h);
-      }
+    for (int v = 0; v < 16; ++v) {
+      const int row = 32 * mt + acc_row(v, lane);
+      const float h0 = fmaxf(acc.t[mt][0][v] + bb[0], 0.0f), h1 = fmaxf(acc.t[mt][1][v] + bb[1], 0.0f);
+      if (h0 > 0.0f) mask |= 1ull << ((2 * mt + 0) * 16 + v);
+      if (h1 > 0.0f) mask |= 1ull << ((2 * mt + 1) * 16 + v);
+      *reinterpret_cast<f32x2*>(&Yl[row * kLda + col]) = f32x2{h0, h1};
+      if (Yg) put2<THROUGH>(Yg + (size_t)row * kH + col, h0, h1);
+    }
   return mask;
 }
 

@@ -67,6 +67,34 @@ __device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uin
   if (a.record) gr[i] = g;
 }
 
+// Four neighbouring parameters at once (16-byte operands; the updated parameters, when another workgroup of the
+// launch reads them, as two 8-byte write-through stores).
+struct AdamRegs4 { f32x4 th, m, v, tg; };
+template <bool THROUGH = false>
+__device__ inline void adam_store4(const Adam& a, const AdamRegs4& r, const f32x4& g, uint32_t i, float* __restrict__ th,
+                                   float* __restrict__ m, float* __restrict__ v, float* __restrict__ tg,
+                                   float* __restrict__ gr) {
+  f32x4 mm, vv, tn, tt;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    mm[e] = a.b1 * r.m[e] + (1.0f - a.b1) * g[e];
+    vv[e] = a.b2 * r.v[e] + (1.0f - a.b2) * (g[e] * g[e]);
+    const float denom = __builtin_amdgcn_sqrtf(vv[e] * a.inv_c2) + a.eps;
+    tn[e] = r.th[e] - a.lr * (mm[e] * a.inv_c1) * __builtin_amdgcn_rcpf(denom);
+    tt[e] = (1.0f - a.tau) * r.tg[e] + a.tau * tn[e];
+  }
+  *reinterpret_cast<f32x4*>(m + i) = mm;
+  *reinterpret_cast<f32x4*>(v + i) = vv;
+  if (THROUGH) {
+    put2<true>(th + i, tn[0], tn[1]);
+    put2<true>(th + i + 2, tn[2], tn[3]);
+  } else {
+    *reinterpret_cast<f32x4*>(th + i) = tn;
+  }
+  if (a.polyak) *reinterpret_cast<f32x4*>(tg + i) = tt;
+  if (a.record) *reinterpret_cast<f32x4*>(gr + i) = g;
+}
+
 // The X slice [256 batch rows][32 columns] of a weight-gradient tile, read so that one load instruction
 // covers whole 128-byte row pieces (a lane-per-row pattern touches 64 cache lines per instruction and lives
 // off the L1), then written transposed into LDS as Xl[column][batch row]:
@@ -122,16 +150,22 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
                                    float* __restrict__ tg, float* __restrict__ gr, int tid) {
   const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
   POP_MARK(50);
-  // flat offset of accumulator element v = 0 of this lane
-  const uint32_t elem0 = base + (uint32_t)((m0 + 4 * half) * kH + n0 + 32 * wave + l32);
-  AdamRegs regs[16];
+  // The Adam step works on whole row pieces: thread `tid` owns, for q = 0 .. 3, the four parameters of row
+  // (tid >> 5) + 8 q at columns 4 (tid & 31) .. of the tile -- 16-byte operands, a quarter of the load and store
+  // instructions of a one-float-per-lane layout (the CU's one load path is what the tile launches queue for).
+  // The product leaves the gradients in the MFMA layout; they change over through LDS (the X slice is done with).
+  const int arow = tid >> 5, acol = 4 * (tid & 31);
+  const uint32_t elem0 = base + (uint32_t)((m0 + arow) * kH + n0 + acol);      // q = 0; q adds 8 rows
+  AdamRegs4 regs[4];
   auto load_adam = [&]() {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const bool ok = (m0 + acc_row(v, lane)) < M;
-      const uint32_t i = ok ? elem0 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH) : elem0;
-      regs[v].th = th[i]; regs[v].m = mo[i]; regs[v].v = ve[i];
-      regs[v].tg = polyak ? tg[i] : 0.0f;
+    for (int q = 0; q < 4; ++q) {
+      const bool ok = (m0 + arow + 8 * q) < M;
+      const uint32_t i = ok ? elem0 + (uint32_t)(8 * q * kH) : elem0 - (uint32_t)(arow * kH);   // else: row m0, always valid
+      regs[q].th = *reinterpret_cast<const f32x4*>(th + i);
+      regs[q].m = *reinterpret_cast<const f32x4*>(mo + i);
+      regs[q].v = *reinterpret_cast<const f32x4*>(ve + i);
+      regs[q].tg = polyak ? *reinterpret_cast<const f32x4*>(tg + i) : f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
   };
   XSlice xsl;
@@ -164,13 +198,16 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   gemm256_unrolled<1, false, 1, 8, true>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());   // loads between the MFMAs: a
                                                      // block is 8 MFMAs and 8 load instructions, and these kernels run two workgroups per CU
   POP_MARK(53);
-  uint32_t e1 = elem0;
-  asm volatile("" : "+v"(e1));                       // recompute the addresses: keeping 64 of them alive costs more
+  __syncthreads();                                   // every wavefront is done with the X slice
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    if ((m0 + acc_row(v, lane)) < M)
-      adam_store<WAIT>(adam, regs[v], acc.t[0][0][v], e1 + (uint32_t)((8 * (v >> 2) + (v & 3)) * kH), th, mo, ve, tg, gr);
-    if ((v & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+  for (int v = 0; v < 16; ++v) Xl[acc_row(v, lane) * kLda + 32 * wave + l32] = acc.t[0][0][v];
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if ((m0 + arow + 8 * q) < M) {
+      const f32x4 g = *reinterpret_cast<const f32x4*>(&Xl[(arow + 8 * q) * kLda + acol]);
+      adam_store4<WAIT>(adam, regs[q], g, elem0 + (uint32_t)(8 * q * kH), th, mo, ve, tg, gr);
+    }
   }
   POP_MARK(54);
 }

@@ -12,6 +12,8 @@
 //
 // A workgroup is 4 wavefronts; for a [R x 256] output each wavefront owns the
 // 64 columns [64 wave, 64 wave + 64) for all R = 32 MT rows, i.e. MT x 2 tiles.
+// Tile nt holds the columns of parity nt: lane l has columns 64 wave + 2 (l & 31) + nt
+// (tile_col), two neighbours, which it loads and stores as one 8-byte access.
 // The left operand (activations) lives in LDS and is shared by the 4
 // wavefronts; the right operand (weights) is read by each wavefront straight
 // from global memory/L2 into registers, because every weight element is used

@@ -148,7 +148,7 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
                                    int n0, const float* __restrict__ z, uint32_t base, float* Xl,
                                    float* __restrict__ th, float* __restrict__ mo, float* __restrict__ ve,
                                    float* __restrict__ tg, float* __restrict__ gr, int tid) {
-  const int wave = tid >> 6, lane = tid & 63, half = lane >> 5, l32 = lane & 31;
+  const int wave = tid >> 6, lane = tid & 63, l32 = lane & 31;
   POP_MARK(50);
   // The Adam step works on whole row pieces: thread `tid` owns, for q = 0 .. 3, the four parameters of row
   // (tid >> 5) + 8 q at columns 4 (tid & 31) .. of the tile -- 16-byte operands, a quarter of the load and store

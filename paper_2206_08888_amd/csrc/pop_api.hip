@@ -281,13 +281,14 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->step_launches = 0;
   // One launch per step (parts handing over between workgroups) or one launch per part, by measurement over
   // P = 2 .. 128 (us/step, single launch vs target+critic fused and the rest separate): 80 / 88 at P = 2,
-  // 99 / 101 at P = 10, 137 / 137 at P = 16, 171 / 154 at P = 20, 197 / 187 at P = 32, 214 / 238 at P = 36,
-  // 241 / 265 at P = 42, 340 / 352 at P = 64.  Small populations (16-row class) fit the chip
-  // at once and save the launch boundaries; from P = 34 the parts are each several times larger than the 512
-  // workgroups the chip holds and the tails of one part overlap the next; in between, waiting weight-gradient
-  // workgroups take the slots the actor chains could start in; from about a hundred agents the separate launches
-  // are ahead again by a per cent or two (657 / 665 at P = 128, 1278 / 1319 at P = 256, 32-row chains).
-  const bool small = d.rows_t == 16 && d.rows_c == 64;
+  // 95 / 96 at P = 10, 113 / 118 at P = 12, 132 / 120 at P = 13, 138 / 130 at P = 16, 157 / 137 at P = 20,
+  // 184 / 171 at P = 32, 197 / 216 at P = 36, 215 / 227 at P = 40, 321 / 326 at P = 64, 485 / 480 at P = 96,
+  // 649 / 633 at P = 128.  Up to 12 agents the target and critic chains still fit the chip at once, one workgroup
+  // per CU, and the single launch saves the launch boundaries; from P = 34 the parts are each several times
+  // larger than the 512 workgroups the chip holds and the tails of one part overlap the next; in between, waiting
+  // weight-gradient workgroups take the slots the actor chains could start in; from about a hundred agents the
+  // separate launches are ahead again by a per cent or two.
+  const bool small = d.rows_t == 16 && d.rows_c == 64 && (int64_t)cfg->P * (cfg->batch / 16) <= 192;   // P <= 12
   const int64_t chain_blocks = (int64_t)cfg->P * (cfg->batch / 32) * 3;
   const bool large = d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2400;
   ctx->fuse = (small || large) ? 2 : 1;

@@ -116,3 +116,21 @@ def test_unsupported_shapes_are_refused_with_a_message():
         with pytest.raises(pp.PopError) as e:
             pp.Population(pp.make_config(2, O, A, (256, 256), 256, 100, algo=algo), workloads.hparams(2, 2))
         assert e.value.code == pp.POP_EUNSUPPORTED and "must be <=" in str(e.value)
+
+
+def test_row_classes_without_a_kernel_are_refused_at_launch(monkeypatch):
+    """POP_ROWS can ask for (target, critic, actor) rows per workgroup that the fused launches have no kernel for:
+    the launch is refused with an error, nothing runs; as separate launches the same rows work and match."""
+    monkeypatch.setenv("POP_ROWS", "16,32,16")
+    monkeypatch.setenv("POP_FUSE", "2")
+    gpu, orc = _pair("td3", 3, 17, 6, 600)
+    with pytest.raises(pp.PopError) as e:
+        gpu.update(1)
+    assert e.value.code == pp.POP_EHIP
+    gpu.close()
+    monkeypatch.setenv("POP_FUSE", "0")
+    gpu, orc = _pair("td3", 3, 17, 6, 600)
+    gpu.update(2); orc.update(2)
+    assert _worst(gpu, orc, 3, PARAMS6) <= 1e-4
+    gpu.close()
+

@@ -313,18 +313,26 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
     const int c = lane & 15, kq = lane >> 4;
     float cs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-    for (int v = 0; v < 4; ++v)
+    for (int v = 0; v < 4; ++v) {                    // the lane's four columns are neighbours: two 8-byte stores per row
+      float z[4];
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt) {
-        const float z = mask_bit16(mask, nt, v) ? acc.t[nt][v] : 0.0f;
-        put<THROUGH>(dXg + (4 * kq + v) * kH + 64 * wave + 4 * c + nt, z);
-        cs[nt] += z;
+        z[nt] = mask_bit16(mask, nt, v) ? acc.t[nt][v] : 0.0f;
+        cs[nt] += z[nt];
       }
+      float* p = dXg + (4 * kq + v) * kH + 64 * wave + 4 * c;
+      put2<THROUGH>(p, z[0], z[1]);
+      put2<THROUGH>(p + 2, z[2], z[3]);
+    }
+    float tot[4];
 #pragma unroll
     for (int nt = 0; nt < 4; ++nt) {
-      float tot = cs[nt] + __shfl_xor(cs[nt], 16);
-      tot += __shfl_xor(tot, 32);
-      if (lane < 16) put<THROUGH>(colsum_out + 64 * wave + 4 * c + nt, tot);
+      tot[nt] = cs[nt] + __shfl_xor(cs[nt], 16);
+      tot[nt] += __shfl_xor(tot[nt], 32);
+    }
+    if (lane < 16) {
+      put2<THROUGH>(colsum_out + 64 * wave + 4 * c, tot[0], tot[1]);
+      put2<THROUGH>(colsum_out + 64 * wave + 4 * c + 2, tot[2], tot[3]);
     }
   }
   template <class Tail>

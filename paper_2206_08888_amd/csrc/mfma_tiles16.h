@@ -240,8 +240,8 @@ __device__ inline uint64_t relu_store16(const Acc16& acc, const f32x4& bb, float
     *reinterpret_cast<f32x4*>(&Yl[row * kLda + col]) = o;
     if (Yg) {
       if (THROUGH) {
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) put<true>(Yg + (size_t)row * kH + col + nt, o[nt]);
+        put2<true>(Yg + (size_t)row * kH + col, o[0], o[1]);
+        put2<true>(Yg + (size_t)row * kH + col + 2, o[2], o[3]);
       } else {
         *reinterpret_cast<f32x4*>(Yg + (size_t)row * kH + col) = o;
       }

@@ -1,8 +1,8 @@
 // One update step of the whole population as a single launch (Sec. 4.1 of the paper: the
 // update steps of all population members are issued together and chained on the device).
 //
-// (Smaller populations run the target and critic chains as a launch of their own and only
-// the rest of the step here: with_chains = 0.)  Blocks, in index order:
+// (with_chains = 0: the target and critic chains ran as a launch of their own and only the
+// rest of the step is here.)  Blocks, in index order:
 //   target chains | critic chains | critic weight-gradient tiles | actor chains |
 //   actor weight-gradient tiles | gather of the next step's replay rows
 // Each part depends on the one before it only per agent or per network, never globally:

@@ -164,9 +164,9 @@ int pop_update(pop_ctx* ctx, int32_t n_steps);
  * the gather of the next step's rows are parts of one grid and hand their
  * results on per agent / per network inside the launch.  The environment
  * variable POP_FUSE, read at pop_create, selects the launch structure:
- *   2 one launch per step (TD3 default for up to 12 and for 34 .. 100 agents);
+ *   2 one launch per step (TD3 default for up to 12 and for 34 .. 83 agents);
  *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest
- *     one launch per part (TD3 default for 13 .. 33 and from 101 agents; shared critics);
+ *     one launch per part (TD3 default for 13 .. 33 and from 84 agents; shared critics);
  *   3 as 1, but on steps with an actor update the rest of the step is one
  *     launch (POP_K_STEP_TAIL);
  *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR; SAC).

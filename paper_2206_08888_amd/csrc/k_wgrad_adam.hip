@@ -7,7 +7,7 @@
 
 namespace pop {
 
-__global__ __launch_bounds__(kThreads, 2) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
+__global__ __launch_bounds__(kThreads, 3) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
                                                           int roles, int prefetch) {
   __shared__ Adam sh_adam;
   __shared__ __attribute__((aligned(16))) float xt_lds[32 * kLda];
@@ -21,7 +21,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_wgrad_adam(PopDev d, uint32_t t
   }
   int unit, role;
   if (decode_block(blockIdx.x, actor_phase ? d.P : 2 * d.P, roles, unit, role))
-    wgrad_roles<false>(d, t, actor_phase, unit, role, xt_lds, &sh_adam);
+    wgrad_roles<false, true>(d, t, actor_phase, unit, role, xt_lds, &sh_adam);
 }
 
 int wgrad_role_count(const PopDev& d, int actor_phase) {

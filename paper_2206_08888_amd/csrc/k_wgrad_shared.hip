@@ -13,7 +13,7 @@
 
 namespace pop {
 
-__global__ __launch_bounds__(kThreads, 2) void k_shared_partial(PopDev d, uint32_t t, int roles) {
+__global__ __launch_bounds__(kThreads, 3) void k_shared_partial(PopDev d, uint32_t t, int roles) {
   __shared__ __attribute__((aligned(16))) float xt_lds[32 * kLda];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   // block -> (network, group, role): the roles of one (network, group) are neighbours
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_shared_partial(PopDev d, uint32
       __syncthreads();                               // the previous agent's product has read the slice
       xsl.store(xt_lds, ldx, M, m0, wave, lane);
       __syncthreads();
-      gemm256_unrolled<1, false, 1, 8, true>(xt_lds, kLda, z, z0, wave, lane, acc, NoTail());
+      gemm256_unrolled<1, false, 1, 4, true>(xt_lds, kLda, z, z0, wave, lane, acc, NoTail());
     }
     const int half = lane >> 5, l32 = lane & 31;
     const uint32_t elem0 = (uint32_t)((w2 ? L.w2 : L.w1) + (m0 + 4 * half) * kH + n0 + 32 * wave + l32);

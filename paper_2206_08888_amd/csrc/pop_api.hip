@@ -129,10 +129,10 @@ void fill_dims(const pop_config& c, PopDev& d) {
   d.share = 1;
   if (c.algo == POP_ALGO_TD3_SHARED) {
     // groups of agents whose critic gradients are summed by separate workgroups: as many as keep the partial
-    // launch (2 networks x groups x roles workgroups) within the 512 the chip holds at once
+    // launch (2 networks x groups x roles workgroups) within the 768 the chip holds at once (three per CU)
     const int roles = 16 + 2 * ((d.critic.in + 31) / 32) + 1;
     d.share = c.P;
-    d.groups = std::max(1, std::min(c.P, 512 / (2 * roles)));
+    d.groups = std::max(1, std::min(c.P, 768 / (2 * roles)));
   }
 }
 
@@ -281,16 +281,17 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->step_launches = 0;
   // One launch per step (parts handing over between workgroups) or one launch per part, by measurement over
   // P = 2 .. 128 (us/step, single launch vs target+critic fused and the rest separate): 80 / 88 at P = 2,
-  // 95 / 96 at P = 10, 113 / 118 at P = 12, 132 / 120 at P = 13, 138 / 130 at P = 16, 157 / 137 at P = 20,
-  // 184 / 171 at P = 32, 197 / 216 at P = 36, 215 / 227 at P = 40, 321 / 326 at P = 64, 485 / 480 at P = 96,
-  // 649 / 633 at P = 128.  Up to 12 agents the target and critic chains still fit the chip at once, one workgroup
-  // per CU, and the single launch saves the launch boundaries; from P = 34 the parts are each several times
-  // larger than the 512 workgroups the chip holds and the tails of one part overlap the next; in between, waiting
-  // weight-gradient workgroups take the slots the actor chains could start in; from about a hundred agents the
-  // separate launches are ahead again by a per cent or two.
+  // 95 / 96 at P = 10, 113 / 118 at P = 12, 132 / 120 at P = 13, 138 / 130 at P = 16, 159 / 134 at P = 20,
+  // 185 / 166 at P = 32, 197 / 210 at P = 36, 251 / 257 at P = 48, 323 / 315 at P = 64, 402 / 403 at P = 80,
+  // 486 / 464 at P = 96, 650 / 616 at P = 128.  Up to 12 agents the target and critic chains still fit the chip
+  // at once, one workgroup per CU, and the single launch saves the launch boundaries; from P = 34 the parts are
+  // each several times larger than the 512 workgroups the chip holds and the tails of one part overlap the next;
+  // in between, waiting weight-gradient workgroups take the slots the actor chains could start in; towards a
+  // hundred agents the separate launches are ahead again (their tile kernel runs three workgroups per CU, the
+  // tiles inside the single launch two).
   const bool small = d.rows_t == 16 && d.rows_c == 64 && (int64_t)cfg->P * (cfg->batch / 16) <= 192;   // P <= 12
   const int64_t chain_blocks = (int64_t)cfg->P * (cfg->batch / 32) * 3;
-  const bool large = d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2400;
+  const bool large = d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2000;   // 34 <= P <= 83
   ctx->fuse = (small || large) ? 2 : 1;
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = 0;     // measured at P = 32: fusing target and critic chains loses 4 %
   if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 1;   // target and critic chains together; the critic's weight step is a reduction of its own

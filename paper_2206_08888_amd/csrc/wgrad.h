@@ -142,7 +142,7 @@ struct XSlice {
 // requested first and arrive while the operands are staged and multiplied.  `setup()` fills
 // `sh` (thread 0 only; a few hundred cycles of double arithmetic): it runs once the loads are
 // on their way, and `sh` is read after the barrier that follows.
-template <bool WAIT, class Setup>
+template <bool WAIT, bool SLIM, class Setup>
 __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wait_on, uint32_t want, const Adam* sh,
                                             Setup setup, bool polyak, const float* __restrict__ x, int ldx, int M, int m0,
                                    int n0, const float* __restrict__ z, uint32_t base, float* Xl,
@@ -195,7 +195,7 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   const Adam adam = *sh;
   Acc<1, 1> acc;
   acc.zero();
-  gemm256_unrolled<1, false, 1, 8, true>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());   // loads between the MFMAs: a
+  gemm256_unrolled<1, false, 1, SLIM ? 4 : 8, true>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());   // loads between the MFMAs: a
                                                      // block is 8 MFMAs and 8 load instructions, and these kernels run two workgroups per CU
   POP_MARK(53);
   __syncthreads();                                   // every wavefront is done with the X slice
@@ -218,7 +218,8 @@ constexpr int kHeadBlock = 16;   // head columns whose Adam operands the small-t
 // WAIT: consumers (the actor chain, for critic 1) and, if producer_in_launch, producers (the
 // chain of this network) run in the same launch -- hold before the first read of chain
 // output, count in at the end.
-template <bool WAIT>
+// SLIM: the register budget of three workgroups per CU (four dZ buffers, head columns eight at a time).
+template <bool WAIT, bool SLIM = false>
 __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int actor_phase, int unit, int role,
                                             float* xt_lds, Adam* sh_adam, bool producer_in_launch = true) {
   const int tid = threadIdx.x;
@@ -264,11 +265,12 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     const bool w2 = role < 16;                       // else layer 1, whose input is the leading columns of the batch rows
     const float* x = w2 ? (actor_phase ? d.aH1 : d.cH1) + o : batch_rows(d, t, agent);
     const float* z = (w2 ? (actor_phase ? d.adZ2 : d.cdZ2) : (actor_phase ? d.adZ1 : d.cdZ1)) + o;
-    weight_tile<WAIT>(d, wait_on, (uint32_t)chunks, sh_adam, setup, delayed_step && !(actor_phase && d.algo == 1), x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
+    weight_tile<WAIT, SLIM>(d, wait_on, (uint32_t)chunks, sh_adam, setup, delayed_step && !(actor_phase && d.algo == 1), x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
                 (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
   } else {
     // small tensors from per-chunk partial sums; thread c owns hidden unit c.  The Adam operands
     // are requested first: they depend on nothing and arrive while the partial sums are read.
+    constexpr int HB = SLIM ? 8 : kHeadBlock;         // head columns held in registers at once
     const int c = tid;
     const int out = L.out;
     POP_MARK(55);
@@ -282,31 +284,31 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
       return r;
     };
     const AdamRegs r_b1 = ld(i_b1), r_b2 = ld(i_b2), r_b3 = ld(i_b3);
-    AdamRegs r_w3[kHeadBlock];                       // head columns go in blocks of kHeadBlock; the first is requested here
+    AdamRegs r_w3[HB];                       // head columns go in blocks of HB; the first is requested here
 #pragma unroll
-    for (int j = 0; j < kHeadBlock; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j < out ? j : 0));
+    for (int j = 0; j < HB; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j < out ? j : 0));
     setup();
     if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
     __syncthreads();
     const Adam adam = *sh_adam;
     POP_MARK(56);
-    float gb1 = 0.0f, gb2 = 0.0f, gw3[kHeadBlock], gb3 = 0.0f, loss = 0.0f, logp = 0.0f;
+    float gb1 = 0.0f, gb2 = 0.0f, gw3[HB], gb3 = 0.0f, loss = 0.0f, logp = 0.0f;
 #pragma unroll
-    for (int j = 0; j < kHeadBlock; ++j) gw3[j] = 0.0f;
+    for (int j = 0; j < HB; ++j) gw3[j] = 0.0f;
     // Every load of a chunk's record goes out unconditionally (head columns beyond `out` re-read column 0
     // and are dropped at the store), so that the loads of several chunks are in flight together.
     if (actor_phase) {
-#pragma unroll 4
+#pragma unroll (SLIM ? 2 : 4)
       for (int ch = 0; ch < chunks; ++ch) {
         const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart;
         const float t1 = p[kAP_db1 + c], t2 = p[kAP_db2 + c], t3 = p[kAP_db3 + (c < out ? c : 0)];
         const float tl = p[kAP_loss], tp = p[kAP_logp];
-        float tw[kHeadBlock];
+        float tw[HB];
 #pragma unroll
-        for (int j = 0; j < kHeadBlock; ++j) tw[j] = p[kAP_dW3 + (j < out ? j : 0) * kH + c];
+        for (int j = 0; j < HB; ++j) tw[j] = p[kAP_dW3 + (j < out ? j : 0) * kH + c];
         gb1 += t1; gb2 += t2; gb3 += t3; loss += tl; logp += tp;
 #pragma unroll
-        for (int j = 0; j < kHeadBlock; ++j) gw3[j] += tw[j];
+        for (int j = 0; j < HB; ++j) gw3[j] += tw[j];
       }
     } else {
 #pragma unroll 4
@@ -320,27 +322,27 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     adam_store<WAIT>(adam, r_b1, gb1, i_b1, th, mo, ve, tg, gr);
     adam_store<WAIT>(adam, r_b2, gb2, i_b2, th, mo, ve, tg, gr);
 #pragma unroll
-    for (int j = 0; j < kHeadBlock; ++j)
+    for (int j = 0; j < HB; ++j)
       if (j < out) adam_store<WAIT>(adam, r_w3[j], gw3[j], i_w3 + (uint32_t)j, th, mo, ve, tg, gr);
     if (c < out) adam_store<WAIT>(adam, r_b3, gb3, i_b3, th, mo, ve, tg, gr);
 #pragma unroll 1
-    for (int j0 = kHeadBlock; j0 < out; j0 += kHeadBlock) {   // wider heads (SAC with more than 8 actions; actor only)
+    for (int j0 = HB; j0 < out; j0 += HB) {   // wider heads (SAC with more than 8 actions; actor only)
 #pragma unroll
-      for (int j = 0; j < kHeadBlock; ++j) {
+      for (int j = 0; j < HB; ++j) {
         r_w3[j] = ld(i_w3 + (uint32_t)(j0 + j < out ? j0 + j : 0));
         gw3[j] = 0.0f;
       }
 #pragma unroll 4
       for (int ch = 0; ch < chunks; ++ch) {
         const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart + kAP_dW3 + c;
-        float tw[kHeadBlock];
+        float tw[HB];
 #pragma unroll
-        for (int j = 0; j < kHeadBlock; ++j) tw[j] = p[(j0 + j < out ? j0 + j : 0) * kH];
+        for (int j = 0; j < HB; ++j) tw[j] = p[(j0 + j < out ? j0 + j : 0) * kH];
 #pragma unroll
-        for (int j = 0; j < kHeadBlock; ++j) gw3[j] += tw[j];
+        for (int j = 0; j < HB; ++j) gw3[j] += tw[j];
       }
 #pragma unroll
-      for (int j = 0; j < kHeadBlock; ++j)
+      for (int j = 0; j < HB; ++j)
         if (j0 + j < out) adam_store<WAIT>(adam, r_w3[j], gw3[j], i_w3 + (uint32_t)(j0 + j), th, mo, ve, tg, gr);
     }
     if (actor_phase && d.algo == 1 && c == 0) {

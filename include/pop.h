@@ -159,14 +159,14 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs,
 int pop_update(pop_ctx* ctx, int32_t n_steps);
 
 /* Kernels of an update step (indices into the arrays of pop_update_timed).
- * For most populations a step is ONE launch, POP_K_STEP: target chains, critic chains,
+ * A step can be ONE launch, POP_K_STEP: target chains, critic chains,
  * critic weight-gradient tiles, actor chains, actor weight-gradient tiles and
  * the gather of the next step's rows are parts of one grid and hand their
  * results on per agent / per network inside the launch.  The environment
  * variable POP_FUSE, read at pop_create, selects the launch structure:
- *   2 one launch per step (TD3 default for up to 12 and for 34 .. 83 agents);
+ *   2 one launch per step (TD3 default for up to 5, for 11 and 12, and for 34 .. 83 agents);
  *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest
- *     one launch per part (TD3 default for 13 .. 33 and from 84 agents; shared critics);
+ *     one launch per part (TD3 default for 6 .. 10, 13 .. 33 and from 84 agents; shared critics);
  *   3 as 1, but on steps with an actor update the rest of the step is one
  *     launch (POP_K_STEP_TAIL);
  *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR; SAC).

@@ -280,16 +280,21 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->gathered_t = ~0ull;
   ctx->step_launches = 0;
   // One launch per step (parts handing over between workgroups) or one launch per part, by measurement over
-  // P = 2 .. 128 (us/step, single launch vs target+critic fused and the rest separate): 80 / 88 at P = 2,
-  // 95 / 96 at P = 10, 113 / 118 at P = 12, 132 / 120 at P = 13, 138 / 130 at P = 16, 159 / 134 at P = 20,
-  // 185 / 166 at P = 32, 197 / 210 at P = 36, 251 / 257 at P = 48, 323 / 315 at P = 64, 402 / 403 at P = 80,
-  // 486 / 464 at P = 96, 650 / 616 at P = 128.  Up to 12 agents the target and critic chains still fit the chip
-  // at once, one workgroup per CU, and the single launch saves the launch boundaries; from P = 34 the parts are
-  // each several times larger than the 512 workgroups the chip holds and the tails of one part overlap the next;
-  // in between, waiting weight-gradient workgroups take the slots the actor chains could start in; towards a
-  // hundred agents the separate launches are ahead again (their tile kernel runs three workgroups per CU, the
-  // tiles inside the single launch two).
-  const bool small = d.rows_t == 16 && d.rows_c == 64 && (int64_t)cfg->P * (cfg->batch / 16) <= 192;   // P <= 12
+  // P = 2 .. 128 (us/step, single launch vs target+critic fused and the rest separate): 78 / 83 at P = 2,
+  // 84 / 85 at P = 5, 89 / 85 at P = 6, 92 / 91 at P = 8, 94.5 / 92.6 at P = 10, 103 / 115 at P = 11, 111 / 115 at
+  // P = 12, 132 / 120 at P = 13, 138 / 130 at P = 16, 159 / 134 at P = 20, 185 / 166 at P = 32, 197 / 210 at P = 36,
+  // 251 / 257 at P = 48, 323 / 315 at P = 64, 402 / 403 at P = 80, 486 / 464 at P = 96, 650 / 616 at P = 128.
+  // A handful of agents: the launch boundaries are what the single launch saves.  6 .. 10 agents: target and critic
+  // chains fit the chip at once (24 P workgroups, one per CU) either way, and the stand-alone tile kernel holds all
+  // the tiles at three per CU where the single launch, one workgroup per CU, needs a second round for them.  11
+  // and 12: the chains no longer fit at once and the single launch overlaps what is left over.  13 .. 33: waiting
+  // weight-gradient workgroups take the slots the actor chains could start in.  From P = 34 the parts are each
+  // several times larger than the 512 workgroups the chip holds and the tails of one part overlap the next;
+  // towards a hundred agents the separate launches are ahead again (their tile kernel runs three workgroups per
+  // CU, the tiles inside the single launch two).
+  const int64_t tc_blocks = (int64_t)cfg->P * (cfg->batch / 16) + 2 * (int64_t)cfg->P * (cfg->batch / 64);   // small class
+  const bool small = d.rows_t == 16 && d.rows_c == 64 && (int64_t)cfg->P * (cfg->batch / 16) <= 192 &&       // P <= 12 and
+                     (tc_blocks > kCUs || (int64_t)cfg->P * (cfg->batch / 16) <= 80);                       // P <= 5 or P >= 11
   const int64_t chain_blocks = (int64_t)cfg->P * (cfg->batch / 32) * 3;
   const bool large = d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2000;   // 34 <= P <= 83
   ctx->fuse = (small || large) ? 2 : 1;

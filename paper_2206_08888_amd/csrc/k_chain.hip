@@ -121,6 +121,7 @@ hipError_t setup_kernels() {
   POP_SET_LDS(k_target_critic<Rows32<1, true>, Rows32<1, true>>);
   POP_SET_LDS(k_actor<Rows32<2>>);
   POP_SET_LDS(k_target_critic<Rows16, Rows32<2>>);
+  POP_SET_LDS(k_target_critic<Rows16, Rows32<1>>);
   POP_SET_LDS(k_target_critic<Rows32<1>, Rows32<1>>);
   POP_SET_LDS(k_target_critic<Rows32<2>, Rows32<2>>);
   POP_SET_LDS(k_act);
@@ -128,8 +129,8 @@ hipError_t setup_kernels() {
   return hipSuccess;
 }
 
-// Rows per workgroup come in three classes (pop_dev.h): (target, critic, actor) = (16, 64, 16)
-// for small populations, else (32, 32, 32); (64, 64, 64) on request.
+// Rows per workgroup (pop_dev.h): (target, critic, actor) = (16, 32 or 64, 16) for small
+// populations, else (32, 32, 32); (64, 64, 64) on request.
 hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_t)), block(kThreads);
   if (d.rows_t == 16) k_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_target(d)), s>>>(d, t);
@@ -150,9 +151,12 @@ hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
   const int nt = xcd_grid(d.P, d.B / d.rows_t), nc = xcd_grid(2 * d.P, d.B / d.rows_c);
   const int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
   const dim3 grid(nt + nc), block(kThreads);
-  if (!(d.rows_t == 16 && d.rows_c == 64) && !(d.rows_t == d.rows_c && (d.rows_t == 32 || d.rows_t == 64)))
+  if (!(d.rows_t == 16 && (d.rows_c == 64 || d.rows_c == 32)) && !(d.rows_t == d.rows_c && (d.rows_t == 32 || d.rows_t == 64)))
     return hipErrorInvalidValue;                     // the kernel exists for these row classes only
-  if (d.rows_t == 16) {
+  if (d.rows_t == 16 && d.rows_c == 32) {
+    const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = Lds<1>(d.D).bytes(vec);
+    k_target_critic<Rows16, Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
+  } else if (d.rows_t == 16) {
     const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = Lds<2>(d.D).bytes(vec);
     k_target_critic<Rows16, Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
   } else if (d.rows_t == 32) {

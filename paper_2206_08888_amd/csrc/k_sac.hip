@@ -48,6 +48,7 @@ hipError_t setup_sac_kernels() {
   POP_SET_LDS(k_sac_actor<Rows16Deep>);
   POP_SET_LDS(k_sac_actor<Rows32Deep<1>>);
   POP_SET_LDS(k_sac_target_critic<Rows16, Rows32<2>>);
+  POP_SET_LDS(k_sac_target_critic<Rows16, Rows32<1>>);
   POP_SET_LDS(k_sac_target_critic<Rows32<1>, Rows32<1>>);
 #undef POP_SET_LDS
   return hipSuccess;
@@ -90,6 +91,9 @@ hipError_t launch_sac_target_critic(const PopDev& d, uint32_t t, hipStream_t s) 
   if (d.rows_t == 16 && d.rows_c == 64) {
     const size_t a = LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), b = Lds<2>(d.D).bytes(vec_critic(d));
     k_sac_target_critic<Rows16, Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
+  } else if (d.rows_t == 16 && d.rows_c == 32) {
+    const size_t a = LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), b = Lds<1>(d.D).bytes(vec_critic(d));
+    k_sac_target_critic<Rows16, Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
   } else if (d.rows_t == 32 && d.rows_c == 32) {
     const size_t a = LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), b = Lds<1>(d.D).bytes(vec_critic(d));
     k_sac_target_critic<Rows32<1>, Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);

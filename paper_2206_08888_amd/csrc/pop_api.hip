@@ -103,6 +103,15 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // Beside 16 P target workgroups of 16 rows, 64-row critic chains (8 P workgroups) keep the fused
   // target/critic launch of a small population within one workgroup per CU.
   d.rows_c = cls == 1 ? 32 : 64;
+  // Small class: 32-row critic chains (16 P workgroups) where they still fit one round of one workgroup
+  // per CU beside the target chains (P <= 8) -- the critics' backward pass, which starts when the targets arrive, is
+  // the tail of that launch and halves: 81 against 91 us/step at P = 8 -- and from 11 agents on, where neither class
+  // fits one round beside the targets and the two chains are launches of their own (98 against 111 us/step at
+  // P = 12, 108 against 126 at P = 16).  In between (P = 9, 10: 24 P <= 256 < 32 P) the 64-row class stays.  Shared
+  // critics measure alike (98 -> 89 us/step at P = 8, 122 -> 109 at P = 12); SAC, whose steps are longer, gains
+  // from the 32-row critic chains throughout (177 -> 157 us/step at P = 10 as launches of their own).
+  const int64_t b16 = (int64_t)c.P * (c.batch / 16);
+  if (cls == 0 && (c.algo == POP_ALGO_SAC || 2 * b16 <= 256 || b16 + b16 / 2 > 256)) d.rows_c = 32;
   if (c.algo == POP_ALGO_SAC && cls == 1) {           // one launch per chain, so each takes the rows that suit it:
     // 64-row critic chains while they still fit one round of one workgroup per CU (51 against 59 us at P = 32),
     // 16-row target chains while they fit one round of two per CU (44 against 46 us); the actor chain stays at 32
@@ -279,30 +288,38 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->t = 0;
   ctx->gathered_t = ~0ull;
   ctx->step_launches = 0;
-  // One launch per step (parts handing over between workgroups) or one launch per part, by measurement over
-  // P = 2 .. 128 (us/step, single launch vs target+critic fused and the rest separate): 78 / 83 at P = 2,
-  // 84 / 85 at P = 5, 89 / 85 at P = 6, 92 / 91 at P = 8, 94.5 / 92.6 at P = 10, 103 / 115 at P = 11, 111 / 115 at
-  // P = 12, 132 / 120 at P = 13, 138 / 130 at P = 16, 159 / 134 at P = 20, 185 / 166 at P = 32, 197 / 210 at P = 36,
-  // 251 / 257 at P = 48, 323 / 315 at P = 64, 402 / 403 at P = 80, 486 / 464 at P = 96, 650 / 616 at P = 128.
-  // A handful of agents: the launch boundaries are what the single launch saves.  6 .. 10 agents: target and critic
-  // chains fit the chip at once (24 P workgroups, one per CU) either way, and the stand-alone tile kernel holds all
-  // the tiles at three per CU where the single launch, one workgroup per CU, needs a second round for them.  11
-  // and 12: the chains no longer fit at once and the single launch overlaps what is left over.  13 .. 33: waiting
-  // weight-gradient workgroups take the slots the actor chains could start in.  From P = 34 the parts are each
-  // several times larger than the 512 workgroups the chip holds and the tails of one part overlap the next;
-  // towards a hundred agents the separate launches are ahead again (their tile kernel runs three workgroups per
-  // CU, the tiles inside the single launch two).
-  const int64_t tc_blocks = (int64_t)cfg->P * (cfg->batch / 16) + 2 * (int64_t)cfg->P * (cfg->batch / 64);   // small class
-  const bool small = d.rows_t == 16 && d.rows_c == 64 && (int64_t)cfg->P * (cfg->batch / 16) <= 192 &&       // P <= 12 and
-                     (tc_blocks > kCUs || (int64_t)cfg->P * (cfg->batch / 16) <= 80);                       // P <= 5 or P >= 11
+  // One launch per step (parts handing over between workgroups), target and critic chains in one launch and the
+  // rest in launches of their own, or one launch per part -- by measurement over P = 2 .. 128 (us/step, 64-row
+  // critic chains up to P = 16; single launch / target+critic fused / per part): 78 / 83 / - at P = 2, 84 / 85 / -
+  // at P = 5, 92 / 91 / - at P = 8, 94.5 / 92.6 / - at P = 10, 111 / 115 / 116 at P = 12, 138 / 126 / 127 at P = 16,
+  // 159 / 134 / 158 at P = 20, 185 / 166 / 177 at P = 32, 197 / 210 / 259 at P = 36, 251 / 257 / - at P = 48,
+  // 323 / 315 / - at P = 64, 402 / 403 / - at P = 80, 486 / 464 / - at P = 96, 650 / 616 / - at P = 128; with 32-row
+  // critic chains beside 16-row target chains, target+critic fused / per part: 73 / 88 at P = 2, 75 / 90 at P = 6,
+  // 81 / 96 at P = 8, 101 / 97 at P = 10, - / 98 at P = 12, - / 108 at P = 16, - / 161 at P = 18.
+  // Up to 10 agents: target and critic chains fit the chip at once, one workgroup per CU, and the stand-alone
+  // tile kernel holds all the tiles at three per CU where the single launch, one workgroup per CU, needs a second
+  // round for them.  11 .. 16: the chains no longer fit at once; each as a launch of its own fills the chip with
+  // one round of 16-row (target, actor) or 32-row (critic) workgroups.  17 .. 33: target and critic chains share a
+  // launch, two workgroups per CU; waiting weight-gradient workgroups would take the slots the actor chains could
+  // start in.  From P = 34 the parts are each several times larger than the 512 workgroups the chip holds and the
+  // tails of one part overlap the next inside a single launch; towards a hundred agents the separate launches are
+  // ahead again (their tile kernel runs three workgroups per CU, the tiles inside the single launch two).
+  const int64_t tc_blocks = (int64_t)cfg->P * (cfg->batch / d.rows_t) + 2 * (int64_t)cfg->P * (cfg->batch / d.rows_c);
   const int64_t chain_blocks = (int64_t)cfg->P * (cfg->batch / 32) * 3;
-  const bool large = d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2000;   // 34 <= P <= 83
-  ctx->fuse = (small || large) ? 2 : 1;
-  if (cfg->algo == POP_ALGO_SAC) ctx->fuse = 0;     // measured at P = 32: fusing target and critic chains loses 4 %
+  const bool large = d.rows_t == 32 && d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2000;   // 34 <= P <= 83
+  ctx->fuse = large ? 2 : 1;
+  if (d.rows_t == 16 && d.rows_c == 32 && tc_blocks > kCUs) ctx->fuse = 0;   // 11 <= P <= 16
+  // SAC: the target and critic chains share a launch where all their workgroups get a CU each (16-row target and
+  // 32-row critic chains up to P = 8: 142 against 157 us/step there); measured at P = 32, fusing them loses 4 %
+  if (cfg->algo == POP_ALGO_SAC) ctx->fuse = (d.rows_t == 16 && d.rows_c == 32 && tc_blocks <= kCUs) ? 1 : 0;
   if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 1;   // target and critic chains together; the critic's weight step is a reduction of its own
   if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
   if (d.D > kMaxIn) ctx->fuse = 0;                  // wide inputs: the chains exist as separate launches only
   if (cfg->algo == POP_ALGO_TD3_SHARED && ctx->fuse > 1) ctx->fuse = 1;
+  if (ctx->fuse >= 2 && d.rows_t == 16 && d.rows_c != 64) {   // the single launch exists for the (16, 64, 16) small class only
+    delete ctx;
+    return fail(nullptr, POP_EINVAL, "POP_FUSE=2 and 3 need POP_ROWS=16 (64-row critic chains) for a population this small");
+  }
   ctx->hp.assign(hp, hp + cfg->P);
   if (cfg->algo == POP_ALGO_SAC)
     for (auto& h : ctx->hp) h.policy_delay = 1;

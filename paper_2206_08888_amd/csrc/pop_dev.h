@@ -71,8 +71,8 @@ struct PopDev {
   float* spart;                // shared critics: [2][groups][critic.padded] partial gradients, laid out like the network
   float* sloss;                // shared critics: [2][groups] partial losses
   int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
-  int rows_t, rows_c, rows_a;  // batch rows per workgroup of the target / critic / actor chain: (16, 64, 16) for small
-                               // populations, else (32, 32, 32); (64, 64, 64) on request
+  int rows_t, rows_c, rows_a;  // batch rows per workgroup of the target / critic / actor chain: (16, 32 or 64, 16) for
+                               // small populations, else (32, 32, 32); (64, 64, 64) on request
   NetLayout actor, critic;
   int agent_sz;                // actor.padded + 2 * critic.padded
   // parameter state, each [P][agent_sz] = [actor | critic1 | critic2]

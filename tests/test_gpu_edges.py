@@ -121,7 +121,7 @@ def test_unsupported_shapes_are_refused_with_a_message():
 def test_row_classes_without_a_kernel_are_refused_at_launch(monkeypatch):
     """POP_ROWS can ask for (target, critic, actor) rows per workgroup that the fused launches have no kernel for:
     the launch is refused with an error, nothing runs; as separate launches the same rows work and match."""
-    monkeypatch.setenv("POP_ROWS", "16,32,16")
+    monkeypatch.setenv("POP_ROWS", "32,64,32")
     monkeypatch.setenv("POP_FUSE", "2")
     gpu, orc = _pair("td3", 3, 17, 6, 600)
     with pytest.raises(pp.PopError) as e:

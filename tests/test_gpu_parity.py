@@ -274,6 +274,7 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
     for i, hp in enumerate(hps):
         hp["policy_delay"] = (2, 1, 3)[i % 3]
     states = []
+    monkeypatch.setenv("POP_ROWS", "16")                # the row class all four structures exist for (16, 64, 16)
     for fuse in ("2", "3", "1", "0"):
         monkeypatch.setenv("POP_FUSE", fuse)
         gpu, _, _ = make_pair(2, P=11, capacity=3000, hps=hps, oracle=False)
@@ -299,6 +300,33 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
     for other in states[1:]:
         for key in states[0]:
             assert np.array_equal(states[0][key], other[key]), key
+
+
+@pytest.mark.parametrize("P,launches", [(8, {"target_critic": 3, "wgrad_critic": 3}), (12, {"target": 3, "critic": 3, "wgrad_critic": 3})])
+def test_small_populations_with_32_row_critic_chains_match_oracle(P, launches, monkeypatch):
+    """Up to 8 agents the critic chains take 32 rows beside the 16-row target chains of the same launch; from 11
+    to 16 agents the two chains are launches of their own.  Both against the oracle over three steps with mixed
+    policy delays, in the launch structure the library picks by itself; a single launch per step is refused for
+    these row classes."""
+    monkeypatch.delenv("POP_FUSE", raising=False)
+    monkeypatch.delenv("POP_ROWS", raising=False)
+    hps = workloads.hparams(2, P)
+    for i, hp in enumerate(hps):
+        hp["policy_delay"] = (2, 1, 3)[i % 3]
+    gpu, orc, _ = make_pair(2, P=P, capacity=1500, hps=hps)
+    _, cnt = gpu.update_timed(3)
+    for k, v in launches.items():
+        assert cnt[k] == v, (k, cnt)
+    assert cnt["step"] == 0
+    orc.update(3)
+    for i in range(P):
+        for w in NETS:
+            assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 1e-4, (i, w)
+    gpu.close()
+    monkeypatch.setenv("POP_FUSE", "2")
+    with pytest.raises(pp.PopError) as e:
+        make_pair(2, P=P, capacity=1500, hps=hps, oracle=False)
+    assert e.value.code == pp.POP_EINVAL
 
 
 def test_sixty_four_row_chains_match_oracle_and_each_other(monkeypatch):

@@ -589,7 +589,7 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
   pre.load(cn, d.critic, wave, lane);
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)net * d.B + r0) * kH;
-  float* part = d.cpart + ((size_t)net * (d.B / R) + chunk) * kCPart;
+  float* part = d.cpart + ((size_t)net * d.cstride + chunk) * kCPart;
   stage_vector(v_w3, cn + d.critic.w3, kH, tid);
   G::load_input(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
   float yv = 0.0f, b3 = 0.0f;

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_shared_partial(PopDev d, uint32
     for (int agent = g; agent < d.P; agent += d.groups) {
 #pragma unroll 4
       for (int ch = 0; ch < chunks; ++ch) {
-        const float* p = d.cpart + ((size_t)(2 * agent + net) * chunks + ch) * kCPart;
+        const float* p = d.cpart + ((size_t)(2 * agent + net) * d.cstride + ch) * kCPart;
         const float t1 = p[kCP_db1 + c], t2 = p[kCP_db2 + c], tw = p[kCP_dW3 + c], t3 = p[kCP_db3], tl = p[kCP_loss];
         gb1 += t1; gb2 += t2; gw3 += tw; gb3 += t3; loss += tl;
       }

@@ -112,6 +112,13 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // from the 32-row critic chains throughout (177 -> 157 us/step at P = 10 as launches of their own).
   const int64_t b16 = (int64_t)c.P * (c.batch / 16);
   if (cls == 0 && (c.algo == POP_ALGO_SAC || 2 * b16 <= 256 || b16 + b16 / 2 > 256)) d.rows_c = 32;
+  // 9 and 10 agents (24 P <= 256 < 32 P), TD3 proper, target and critic chains in one launch: the 16-row target
+  // workgroups go on into critic 1 for their own rows (no hand-over, nothing waits), and only critic 2 has
+  // workgroups of its own, 32 rows each: 16 P + 8 P workgroups as before, but the tail after the targets is a
+  // 16-row critic chain or a 32-row backward pass instead of a 64-row backward pass.
+  d.rows_c1 = 0;
+  const char* fuse_env = getenv("POP_FUSE");
+  if (c.algo == POP_ALGO_TD3 && cls == 0 && d.rows_c == 64 && (!fuse_env || atoi(fuse_env) == 1)) { d.rows_c = 32; d.rows_c1 = 16; }
   if (c.algo == POP_ALGO_SAC && cls == 1) {           // one launch per chain, so each takes the rows that suit it:
     // 64-row critic chains while they still fit one round of one workgroup per CU (51 against 59 us at P = 32),
     // 16-row target chains while they fit one round of two per CU (44 against 46 us); the actor chain stays at 32
@@ -123,14 +130,18 @@ void fill_dims(const pop_config& c, PopDev& d) {
     int rt = 0, rc = 0, ra = 0;
     auto ok = [](int r, bool chain16) { return r == 32 || r == 64 || (chain16 && r == 16); };
     if (sscanf(env, "%d,%d,%d", &rt, &rc, &ra) == 3) {   // "target,critic,actor"
-      if (ok(rt, true) && ok(rc, false) && ok(ra, true)) { d.rows_t = rt; d.rows_c = rc; d.rows_a = ra; }
-    } else if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; }
-    else if (v == 32 || v == 64) d.rows_t = d.rows_c = d.rows_a = v;
+      if (ok(rt, true) && ok(rc, false) && ok(ra, true)) { d.rows_t = rt; d.rows_c = rc; d.rows_a = ra; d.rows_c1 = 0; }
+    } else if (!strcmp(env, "16+")) {                  // the class of 9 and 10 agents, whatever the population
+      if (c.algo == POP_ALGO_TD3) { d.rows_t = d.rows_a = d.rows_c1 = 16; d.rows_c = 32; }
+    } else if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; d.rows_c1 = 0; }
+    else if (v == 32 || v == 64) { d.rows_t = d.rows_c = d.rows_a = v; d.rows_c1 = 0; }
   }
   // Wide inputs (SAC only; kernels with a pipelined first layer): 32-row chains -- with weights of
   // 2 MB per agent, 16-row workgroups re-read them from L2 often enough to be bound by that -- except
   // for populations too small to fill the chip with them.
   if (d.D > kMaxIn) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; }
+  if (d.rows_c1 == 0) d.rows_c1 = d.rows_c;
+  d.cstride = d.B / (d.rows_c1 < d.rows_c ? d.rows_c1 : d.rows_c);
   d.actor = make_layout(d.O, c.algo == POP_ALGO_SAC ? 2 * d.A : d.A);   // SAC: mean and log-std per action
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
@@ -170,7 +181,7 @@ Layout make_ws_layout(const PopDev& d) {
   const int64_t act = P * B * kH * 4;
   L.cH1 = take(2 * act); L.cdZ2 = take(2 * act); L.cdZ1 = take(2 * act);
   L.aH1 = take(act); L.aH2 = take(act); L.adZ2 = take(act); L.adZ1 = take(act);
-  L.cpart = take(P * 2 * (int64_t)(d.B / d.rows_c) * kCPart * 4);
+  L.cpart = take(P * 2 * (int64_t)d.cstride * kCPart * 4);
   L.apart = take(P * (int64_t)(d.B / d.rows_a) * kAPart * 4);
   L.losses = take(P * 4 * 4);
   L.y_tagged = take(P * B * 8);
@@ -304,7 +315,8 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   // start in.  From P = 34 the parts are each several times larger than the 512 workgroups the chip holds and the
   // tails of one part overlap the next inside a single launch; towards a hundred agents the separate launches are
   // ahead again (their tile kernel runs three workgroups per CU, the tiles inside the single launch two).
-  const int64_t tc_blocks = (int64_t)cfg->P * (cfg->batch / d.rows_t) + 2 * (int64_t)cfg->P * (cfg->batch / d.rows_c);
+  const int64_t tc_blocks = (int64_t)cfg->P * (cfg->batch / d.rows_t) + (int64_t)cfg->P * (cfg->batch / d.rows_c) +
+                            (d.rows_c1 == d.rows_c ? (int64_t)cfg->P * (cfg->batch / d.rows_c) : 0);
   const int64_t chain_blocks = (int64_t)cfg->P * (cfg->batch / 32) * 3;
   const bool large = d.rows_t == 32 && d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2000;   // 34 <= P <= 83
   ctx->fuse = large ? 2 : 1;
@@ -316,6 +328,10 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
   if (d.D > kMaxIn) ctx->fuse = 0;                  // wide inputs: the chains exist as separate launches only
   if (cfg->algo == POP_ALGO_TD3_SHARED && ctx->fuse > 1) ctx->fuse = 1;
+  if (d.rows_c1 != d.rows_c && ctx->fuse != 1) {
+    delete ctx;
+    return fail(nullptr, POP_EINVAL, "POP_ROWS=16+ needs POP_FUSE=1 (target and critic chains in one launch)");
+  }
   if (ctx->fuse >= 2 && d.rows_t == 16 && d.rows_c != 64) {   // the single launch exists for the (16, 64, 16) small class only
     delete ctx;
     return fail(nullptr, POP_EINVAL, "POP_FUSE=2 and 3 need POP_ROWS=16 (64-row critic chains) for a population this small");

@@ -73,6 +73,8 @@ struct PopDev {
   int P, O, A, D, B, row;      // D = O + A; row = 2 O + A + 2 floats
   int rows_t, rows_c, rows_a;  // batch rows per workgroup of the target / critic / actor chain: (16, 32 or 64, 16) for
                                // small populations, else (32, 32, 32); (64, 64, 64) on request
+  int rows_c1;                 // rows per workgroup of critic 1's chain: rows_c, or 16 where the target workgroups run it (k_chain.hip)
+  int cstride;                 // chunk slots per network in cpart: B / min(rows_c1, rows_c)
   NetLayout actor, critic;
   int agent_sz;                // actor.padded + 2 * critic.padded
   // parameter state, each [P][agent_sz] = [actor | critic1 | critic2]
@@ -93,7 +95,7 @@ struct PopDev {
   float *cH1, *cdZ2, *cdZ1;    // [P][2][B][256]
   float *aH1, *aH2, *adZ2, *adZ1;  // [P][B][256]
   // per-row-chunk partial sums of the small gradients and of the losses
-  float* cpart;                // [P][2][chunks][kCPart]
+  float* cpart;                // [P][2][cstride][kCPart]
   float* apart;                // [P][chunks][kAPart]
   float* losses;               // [P][4]: critic 1, critic 2, actor, unused
   float* log_alpha;            // SAC: [3][P] log temperature, its Adam m, its Adam v

@@ -257,7 +257,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
   const uint32_t* wait_on = !producer_in_launch ? nullptr
                             : actor_phase       ? d.done_a + parity_base(d, t, d.P) + agent
                                                 : d.done_c + parity_base(d, t, 2 * d.P) + unit;
-  const int chunks = d.B / (actor_phase ? d.rows_a : d.rows_c);   // row chunks of the chain that feeds this network
+  const int chunks = d.B / (actor_phase ? d.rows_a : (unit & 1) ? d.rows_c : d.rows_c1);   // row chunks of the chain that feeds this network
   const int n1 = (L.in + 31) / 32;
   if (role < 16 + 2 * n1) {
     const size_t o = (size_t)unit * d.B * kH;        // unit = agent (actor) or network (critics)
@@ -313,7 +313,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     } else {
 #pragma unroll 4
       for (int ch = 0; ch < chunks; ++ch) {
-        const float* p = d.cpart + ((size_t)unit * chunks + ch) * kCPart;
+        const float* p = d.cpart + ((size_t)unit * d.cstride + ch) * kCPart;
         const float t1 = p[kCP_db1 + c], t2 = p[kCP_db2 + c], tw = p[kCP_dW3 + c], t3 = p[kCP_db3], tl = p[kCP_loss];
         gb1 += t1; gb2 += t2; gw3[0] += tw; gb3 += t3; loss += tl;
       }

@@ -166,15 +166,15 @@ int pop_update(pop_ctx* ctx, int32_t n_steps);
  * variable POP_FUSE, read at pop_create, selects the launch structure:
  *   2 one launch per step (TD3 default for 34 .. 83 agents);
  *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest
- *     one launch per part (TD3 default up to 10, for 17 .. 33 and from 84 agents; shared critics;
+ *     one launch per part (TD3 default up to 12, for 17 .. 33 and from 84 agents; shared critics;
  *     SAC up to 8 agents);
  *   3 as 1, but on steps with an actor update the rest of the step is one
  *     launch (POP_K_STEP_TAIL);
- *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR; TD3 default for 11 .. 16 agents; SAC).
+ *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR; TD3 default for 13 .. 16 agents; SAC).
  * 2 and 3 exist for populations whose chains all take 32 or 64 batch rows per workgroup, and for the
  * small class with 64-row critic chains (POP_ROWS=16); pop_create refuses them with POP_EINVAL otherwise.
- * POP_ROWS (16, 32, 64, "16+" -- 16-row target workgroups that go on into critic 1, 32-row workgroups for critic 2,
- * TD3 with POP_FUSE=1 only -- or "target,critic,actor" with 16 allowed for the target and actor chains only), read
+ * POP_ROWS (16, 32, 64, "16+" / "16++" -- 16-row target workgroups that go on into critic 1, 32- / 64-row workgroups
+ * for critic 2, TD3 with POP_FUSE=1 only -- or "target,critic,actor" with 16 allowed for the target and actor chains only), read
  * wherever a configuration is sized, overrides the batch rows per workgroup of the chains; a launch
  * that has no kernel for the rows asked for fails with POP_EHIP and runs nothing.
  * The arithmetic, and so every result, is bit-identical in all of them. */

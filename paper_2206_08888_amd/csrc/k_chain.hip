@@ -40,6 +40,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_
 // The same for populations whose 16-row target workgroups and 32-row critic workgroups do not all get a CU at
 // once: a target workgroup goes on into critic 1 for its own 16 rows (its targets are its own, nothing waits),
 // and only critic 2 has workgroups of its own.
+template <class GC>
 __global__ __launch_bounds__(kThreads, 1) void k_target_critic1(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
   int agent, chunk;
@@ -49,8 +50,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic1(PopDev d, uint32
       __syncthreads();                               // the chain is done with its LDS; a lane reads back the targets it wrote
       critic_chain<Rows16, false, false>(d, t, 2 * agent, chunk, lds);
     }
-  } else if (decode_block(blockIdx.x - target_blocks, d.P, d.B / 32, agent, chunk)) {
-    critic_chain<Rows32<1>, true, false>(d, t, 2 * agent + 1, chunk, lds);
+  } else if (decode_block(blockIdx.x - target_blocks, d.P, d.B / GC::R, agent, chunk)) {
+    critic_chain<GC, true, false>(d, t, 2 * agent + 1, chunk, lds);
   }
 }
 
@@ -139,7 +140,8 @@ hipError_t setup_kernels() {
   POP_SET_LDS(k_actor<Rows32<2>>);
   POP_SET_LDS(k_target_critic<Rows16, Rows32<2>>);
   POP_SET_LDS(k_target_critic<Rows16, Rows32<1>>);
-  POP_SET_LDS(k_target_critic1);
+  POP_SET_LDS(k_target_critic1<Rows32<1>>);
+  POP_SET_LDS(k_target_critic1<Rows32<2>>);
   POP_SET_LDS(k_target_critic<Rows32<1>, Rows32<1>>);
   POP_SET_LDS(k_target_critic<Rows32<2>, Rows32<2>>);
   POP_SET_LDS(k_act);
@@ -169,9 +171,11 @@ hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
   const int nt = xcd_grid(d.P, d.B / d.rows_t), nc = xcd_grid(2 * d.P, d.B / d.rows_c);
   const int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
   if (d.rows_c1 != d.rows_c) {                       // critic 1 inside the target workgroups
-    if (d.rows_t != 16 || d.rows_c1 != 16 || d.rows_c != 32) return hipErrorInvalidValue;
-    const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = Lds<1>(d.D).bytes(vec);
-    k_target_critic1<<<dim3(nt + xcd_grid(d.P, d.B / 32)), dim3(kThreads), a > b ? a : b, s>>>(d, t, nt);
+    if (d.rows_t != 16 || d.rows_c1 != 16 || (d.rows_c != 32 && d.rows_c != 64)) return hipErrorInvalidValue;
+    const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = d.rows_c == 32 ? Lds<1>(d.D).bytes(vec) : Lds<2>(d.D).bytes(vec);
+    const dim3 grid(nt + xcd_grid(d.P, d.B / d.rows_c)), block(kThreads);
+    if (d.rows_c == 32) k_target_critic1<Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
+    else k_target_critic1<Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
     return hipGetLastError();
   }
   const dim3 grid(nt + nc), block(kThreads);

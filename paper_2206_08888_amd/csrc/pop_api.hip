@@ -115,10 +115,14 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // 9 and 10 agents (24 P <= 256 < 32 P), TD3 proper, target and critic chains in one launch: the 16-row target
   // workgroups go on into critic 1 for their own rows (no hand-over, nothing waits), and only critic 2 has
   // workgroups of its own, 32 rows each: 16 P + 8 P workgroups as before, but the tail after the targets is a
-  // 16-row critic chain or a 32-row backward pass instead of a 64-row backward pass.
+  // 16-row critic chain or a 32-row backward pass instead of a 64-row backward pass (88 against 92 us/step at P = 10).
   d.rows_c1 = 0;
   const char* fuse_env = getenv("POP_FUSE");
-  if (c.algo == POP_ALGO_TD3 && cls == 0 && d.rows_c == 64 && (!fuse_env || atoi(fuse_env) == 1)) { d.rows_c = 32; d.rows_c1 = 16; }
+  if (c.algo == POP_ALGO_TD3 && cls == 0 && (!fuse_env || atoi(fuse_env) == 1)) {
+    if (d.rows_c == 64) { d.rows_c = 32; d.rows_c1 = 16; }
+    // 11 and 12 agents (20 P <= 256 < 24 P): the same with 64-row workgroups for critic 2 -- 93 against 98 us/step
+    else if (b16 + b16 / 2 > 256 && b16 + b16 / 4 <= 256) { d.rows_c = 64; d.rows_c1 = 16; }
+  }
   if (c.algo == POP_ALGO_SAC && cls == 1) {           // one launch per chain, so each takes the rows that suit it:
     // 64-row critic chains while they still fit one round of one workgroup per CU (51 against 59 us at P = 32),
     // 16-row target chains while they fit one round of two per CU (44 against 46 us); the actor chain stays at 32
@@ -131,8 +135,8 @@ void fill_dims(const pop_config& c, PopDev& d) {
     auto ok = [](int r, bool chain16) { return r == 32 || r == 64 || (chain16 && r == 16); };
     if (sscanf(env, "%d,%d,%d", &rt, &rc, &ra) == 3) {   // "target,critic,actor"
       if (ok(rt, true) && ok(rc, false) && ok(ra, true)) { d.rows_t = rt; d.rows_c = rc; d.rows_a = ra; d.rows_c1 = 0; }
-    } else if (!strcmp(env, "16+")) {                  // the class of 9 and 10 agents, whatever the population
-      if (c.algo == POP_ALGO_TD3) { d.rows_t = d.rows_a = d.rows_c1 = 16; d.rows_c = 32; }
+    } else if (!strcmp(env, "16+") || !strcmp(env, "16++")) {   // the classes of 9 .. 12 agents, whatever the population
+      if (c.algo == POP_ALGO_TD3) { d.rows_t = d.rows_a = d.rows_c1 = 16; d.rows_c = env[3] ? 64 : 32; }
     } else if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; d.rows_c1 = 0; }
     else if (v == 32 || v == 64) { d.rows_t = d.rows_c = d.rows_a = v; d.rows_c1 = 0; }
   }
@@ -307,10 +311,11 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   // 323 / 315 / - at P = 64, 402 / 403 / - at P = 80, 486 / 464 / - at P = 96, 650 / 616 / - at P = 128; with 32-row
   // critic chains beside 16-row target chains, target+critic fused / per part: 73 / 88 at P = 2, 75 / 90 at P = 6,
   // 81 / 96 at P = 8, 101 / 97 at P = 10, - / 98 at P = 12, - / 108 at P = 16, - / 161 at P = 18.
-  // Up to 10 agents: target and critic chains fit the chip at once, one workgroup per CU, and the stand-alone
-  // tile kernel holds all the tiles at three per CU where the single launch, one workgroup per CU, needs a second
-  // round for them.  11 .. 16: the chains no longer fit at once; each as a launch of its own fills the chip with
-  // one round of 16-row (target, actor) or 32-row (critic) workgroups.  17 .. 33: target and critic chains share a
+  // Up to 12 agents: target and critic chains fit the chip at once, one workgroup per CU (from 9 agents on with
+  // critic 1 inside the target workgroups: fill_dims), and the stand-alone tile kernel holds all the tiles at three
+  // per CU where the single launch, one workgroup per CU, needs a second round for them.  13 .. 16: the chains no
+  // longer fit at once; each as a launch of its own fills the chip with one round of 16-row (target, actor) or
+  // 32-row (critic) workgroups.  17 .. 33: target and critic chains share a
   // launch, two workgroups per CU; waiting weight-gradient workgroups would take the slots the actor chains could
   // start in.  From P = 34 the parts are each several times larger than the 512 workgroups the chip holds and the
   // tails of one part overlap the next inside a single launch; towards a hundred agents the separate launches are
@@ -320,7 +325,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   const int64_t chain_blocks = (int64_t)cfg->P * (cfg->batch / 32) * 3;
   const bool large = d.rows_t == 32 && d.rows_c == 32 && chain_blocks > 800 && chain_blocks <= 2000;   // 34 <= P <= 83
   ctx->fuse = large ? 2 : 1;
-  if (d.rows_t == 16 && d.rows_c == 32 && tc_blocks > kCUs) ctx->fuse = 0;   // 11 <= P <= 16
+  if (d.rows_t == 16 && d.rows_c == 32 && tc_blocks > kCUs) ctx->fuse = 0;   // 13 <= P <= 16
   // SAC: the target and critic chains share a launch where all their workgroups get a CU each (16-row target and
   // 32-row critic chains up to P = 8: 142 against 157 us/step there); measured at P = 32, fusing them loses 4 %
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = (d.rows_t == 16 && d.rows_c == 32 && tc_blocks <= kCUs) ? 1 : 0;
@@ -330,7 +335,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   if (cfg->algo == POP_ALGO_TD3_SHARED && ctx->fuse > 1) ctx->fuse = 1;
   if (d.rows_c1 != d.rows_c && ctx->fuse != 1) {
     delete ctx;
-    return fail(nullptr, POP_EINVAL, "POP_ROWS=16+ needs POP_FUSE=1 (target and critic chains in one launch)");
+    return fail(nullptr, POP_EINVAL, "POP_ROWS=16+ and 16++ need POP_FUSE=1 (target and critic chains in one launch)");
   }
   if (ctx->fuse >= 2 && d.rows_t == 16 && d.rows_c != 64) {   // the single launch exists for the (16, 64, 16) small class only
     delete ctx;

@@ -303,11 +303,11 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
 
 
 @pytest.mark.parametrize("P,launches", [(8, {"target_critic": 3, "wgrad_critic": 3}), (9, {"target_critic": 3, "wgrad_critic": 3}),
-                                        (12, {"target": 3, "critic": 3, "wgrad_critic": 3})])
+                                        (12, {"target_critic": 3, "wgrad_critic": 3}), (14, {"target": 3, "critic": 3, "wgrad_critic": 3})])
 def test_small_populations_with_32_row_critic_chains_match_oracle(P, launches, monkeypatch):
     """Up to 8 agents the critic chains take 32 rows beside the 16-row target chains of the same launch; with 9
-    and 10 the target workgroups run critic 1 for their own rows and only critic 2 has 32-row workgroups; from 11
-    to 16 agents the two chains are launches of their own.  Both against the oracle over three steps with mixed
+    and 10 the target workgroups run critic 1 for their own rows and only critic 2 has 32-row workgroups (64-row
+    ones with 11 and 12 agents); from 13 to 16 agents the two chains are launches of their own.  Both against the oracle over three steps with mixed
     policy delays, in the launch structure the library picks by itself; a single launch per step is refused for
     these row classes."""
     monkeypatch.delenv("POP_FUSE", raising=False)

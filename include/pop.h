@@ -177,6 +177,9 @@ int pop_update(pop_ctx* ctx, int32_t n_steps);
  * for critic 2, TD3 with POP_FUSE=1 only -- or "target,critic,actor" with 16 allowed for the target and actor chains only), read
  * wherever a configuration is sized, overrides the batch rows per workgroup of the chains; a launch
  * that has no kernel for the rows asked for fails with POP_EHIP and runs nothing.
+ * POP_HALF_TILES=0/1 switches the half-width weight-gradient tiles of the stand-alone launches off / on
+ * (default: on up to 10 agents; always off while POP_FUSE is set, so that the launch structures compare
+ * bit for bit).
  * The arithmetic, and so every result, is bit-identical in all of them. */
 enum {
   POP_K_GATHER = 0,        /* replay index draw + row gather (first step of a call only) */

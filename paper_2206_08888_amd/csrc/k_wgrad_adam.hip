@@ -7,6 +7,8 @@
 
 namespace pop {
 
+// HALF: tiles of half the width, for populations whose full tiles would leave CUs with one or two of them.
+template <bool HALF>
 __global__ __launch_bounds__(kThreads, 3) void k_wgrad_adam(PopDev d, uint32_t t, int actor_phase, int main_blocks,
                                                           int roles, int prefetch) {
   __shared__ Adam sh_adam;
@@ -21,7 +23,7 @@ __global__ __launch_bounds__(kThreads, 3) void k_wgrad_adam(PopDev d, uint32_t t
   }
   int unit, role;
   if (decode_block(blockIdx.x, actor_phase ? d.P : 2 * d.P, roles, unit, role))
-    wgrad_roles<false, true>(d, t, actor_phase, unit, role, xt_lds, &sh_adam);
+    wgrad_roles<false, true, HALF>(d, t, actor_phase, unit, role, xt_lds, &sh_adam);
 }
 
 int wgrad_role_count(const PopDev& d, int actor_phase) {
@@ -30,11 +32,13 @@ int wgrad_role_count(const PopDev& d, int actor_phase) {
 }
 
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s) {
-  const int roles = wgrad_role_count(d, actor_phase);
+  const int full = wgrad_role_count(d, actor_phase);
+  const int roles = d.half_tiles ? 2 * (full - 1) + 1 : full;   // every tile role twice; one small-tensor role
   const int main_blocks = xcd_grid(actor_phase ? d.P : 2 * d.P, roles);
   const int extra = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
-  hipLaunchKernelGGL(k_wgrad_adam, dim3(main_blocks + extra), dim3(kThreads), 0, s, d, t, actor_phase, main_blocks,
-                     roles, prefetch_next);
+  const dim3 grid(main_blocks + extra), block(kThreads);
+  if (d.half_tiles) k_wgrad_adam<true><<<grid, block, 0, s>>>(d, t, actor_phase, main_blocks, roles, prefetch_next);
+  else k_wgrad_adam<false><<<grid, block, 0, s>>>(d, t, actor_phase, main_blocks, roles, prefetch_next);
   return hipGetLastError();
 }
 

@@ -476,8 +476,8 @@ __device__ inline void gemm256(const float* __restrict__ Xl, int ldx, const floa
 // The same product fully unrolled with NB rotating weight buffers (block i + NB - 1 is requested
 // before the MFMAs of block i): for operands that come from memory rather than L2 and for
 // narrow tiles (NT = 1), where a block is only 512 cycles of matrix work and four buffers
-// cover too little latency.
-template <int MT, bool TRANSPOSED, int NT, int NB, bool FED = false, class Tail>
+// cover too little latency.  KB: blocks of 16 to contract over (16: all 256; 8: the half that Xl and W point at).
+template <int MT, bool TRANSPOSED, int NT, int NB, bool FED = false, int KB = 16, class Tail>
 __device__ inline void gemm256_unrolled(const float* __restrict__ Xl, int ldx, const float* __restrict__ W,
                                         WeightBlock<MT, TRANSPOSED, NT>& b0, int wave, int lane, Acc<MT, NT>& acc,
                                         Tail tail) {
@@ -492,20 +492,20 @@ __device__ inline void gemm256_unrolled(const float* __restrict__ Xl, int ldx, c
     constexpr int step = TRANSPOSED ? 16 : 16 * kH;
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
+    for (int i = 0; i < KB; ++i) {
       const int n = i + NB - 1;
-      if (i == 16 - NB + 1) tail();
-      if (n < 16) mfma_block_fed<MT, TRANSPOSED, NT, true, true>(xb[i & 1], wb[i % NB], acc, wb[n % NB], wl + n * step, xb[(i + 1) & 1], Xl, ldx, 16 * (i + 1), lane);
-      else if (i + 1 < 16) mfma_block_fed<MT, TRANSPOSED, NT, false, true>(xb[i & 1], wb[i % NB], acc, wb[n % NB], wl, xb[(i + 1) & 1], Xl, ldx, 16 * (i + 1), lane);
+      if (i == KB - NB + 1) tail();
+      if (n < KB) mfma_block_fed<MT, TRANSPOSED, NT, true, true>(xb[i & 1], wb[i % NB], acc, wb[n % NB], wl + n * step, xb[(i + 1) & 1], Xl, ldx, 16 * (i + 1), lane);
+      else if (i + 1 < KB) mfma_block_fed<MT, TRANSPOSED, NT, false, true>(xb[i & 1], wb[i % NB], acc, wb[n % NB], wl, xb[(i + 1) & 1], Xl, ldx, 16 * (i + 1), lane);
       else mfma_block_fed<MT, TRANSPOSED, NT, false, false>(xb[i & 1], wb[i % NB], acc, wb[n % NB], wl, xb[(i + 1) & 1], Xl, ldx, 0, lane);
     }
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    if (i + NB - 1 < 16) wb[(i + NB - 1) % NB].load(W, i + NB - 1, wave, lane);
-    if (i == 16 - NB + 1) tail();
-    if (i + 1 < 16) xb[(i + 1) & 1].load(Xl, ldx, 16 * (i + 1), lane);
+  for (int i = 0; i < KB; ++i) {
+    if (i + NB - 1 < KB) wb[(i + NB - 1) % NB].load(W, i + NB - 1, wave, lane);
+    if (i == KB - NB + 1) tail();
+    if (i + 1 < KB) xb[(i + 1) & 1].load(Xl, ldx, 16 * (i + 1), lane);
     __builtin_amdgcn_sched_barrier(0);
     mfma_block<MT, TRANSPOSED, NT>(xb[i & 1], wb[i % NB], acc);
     __builtin_amdgcn_sched_barrier(0);

@@ -146,6 +146,13 @@ void fill_dims(const pop_config& c, PopDev& d) {
   if (d.D > kMaxIn) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; }
   if (d.rows_c1 == 0) d.rows_c1 = d.rows_c;
   d.cstride = d.B / (d.rows_c1 < d.rows_c ? d.rows_c1 : d.rows_c);
+  // Stand-alone weight-gradient launches: with fewer than two 32 x 128 tiles per CU (19 workgroups per network at
+  // these shapes) some CUs hold two tiles and others one, and the launch lasts as long as the former; tiles of
+  // half the width (37 workgroups per network) spread evenly while all of them are resident at three per CU, i.e.
+  // up to 10 agents: 73 -> 69 us/step at P = 2, 81 -> 79 at P = 8, 87.8 -> 85.6 at P = 10 (93.5 -> 94.3 at P = 12).
+  // The sums over the batch then come in two halves, so the launch structures that POP_FUSE selects for
+  // comparisons bit for bit keep the full tiles.  POP_HALF_TILES=0/1 overrides (measurements).
+  d.half_tiles = (getenv("POP_HALF_TILES") ? atoi(getenv("POP_HALF_TILES")) != 0 : 2 * (int64_t)c.P * 37 <= 3 * 256) && !getenv("POP_FUSE");
   d.actor = make_layout(d.O, c.algo == POP_ALGO_SAC ? 2 * d.A : d.A);   // SAC: mean and log-std per action
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;

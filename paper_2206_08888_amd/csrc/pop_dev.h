@@ -75,6 +75,7 @@ struct PopDev {
                                // small populations, else (32, 32, 32); (64, 64, 64) on request
   int rows_c1;                 // rows per workgroup of critic 1's chain: rows_c, or 16 where the target workgroups run it (k_chain.hip)
   int cstride;                 // chunk slots per network in cpart: B / min(rows_c1, rows_c)
+  int half_tiles;              // the stand-alone weight-gradient launch runs tiles of half the width (k_wgrad_adam.hip)
   NetLayout actor, critic;
   int agent_sz;                // actor.padded + 2 * critic.padded
   // parameter state, each [P][agent_sz] = [actor | critic1 | critic2]

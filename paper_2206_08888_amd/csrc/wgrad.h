@@ -142,7 +142,7 @@ struct XSlice {
 // requested first and arrive while the operands are staged and multiplied.  `setup()` fills
 // `sh` (thread 0 only; a few hundred cycles of double arithmetic): it runs once the loads are
 // on their way, and `sh` is read after the barrier that follows.
-template <bool WAIT, bool SLIM, class Setup>
+template <bool WAIT, bool SLIM, bool HALF, class Setup>
 __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wait_on, uint32_t want, const Adam* sh,
                                             Setup setup, bool polyak, const float* __restrict__ x, int ldx, int M, int m0,
                                    int n0, const float* __restrict__ z, uint32_t base, float* Xl,
@@ -154,14 +154,18 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   // (tid >> 5) + 8 q at columns 4 (tid & 31) .. of the tile -- 16-byte operands, a quarter of the load and store
   // instructions of a one-float-per-lane layout (the CU's one load path is what the tile launches queue for).
   // The product leaves the gradients in the MFMA layout; they change over through LDS (the X slice is done with).
-  const int arow = tid >> 5, acol = 4 * (tid & 31);
-  const uint32_t elem0 = base + (uint32_t)((m0 + arow) * kH + n0 + acol);      // q = 0; q adds 8 rows
-  AdamRegs4 regs[4];
+  // HALF: the tile is 64 columns wide; wavefront pairs take the two column groups for one half of the batch each
+  // (kh), the halves are summed where the gradients change layout, and a thread owns two row pieces, 16 rows apart.
+  constexpr int Q = HALF ? 2 : 4, QR = HALF ? 16 : 8;
+  const int cw = HALF ? (wave & 1) : wave, kh = HALF ? (wave >> 1) : 0;
+  const int arow = HALF ? tid >> 4 : tid >> 5, acol = 4 * (tid & (HALF ? 15 : 31));
+  const uint32_t elem0 = base + (uint32_t)((m0 + arow) * kH + n0 + acol);      // q = 0; q adds QR rows
+  AdamRegs4 regs[Q];
   auto load_adam = [&]() {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const bool ok = (m0 + arow + 8 * q) < M;
-      const uint32_t i = ok ? elem0 + (uint32_t)(8 * q * kH) : elem0 - (uint32_t)(arow * kH);   // else: row m0, always valid
+    for (int q = 0; q < Q; ++q) {
+      const bool ok = (m0 + arow + QR * q) < M;
+      const uint32_t i = ok ? elem0 + (uint32_t)(QR * q * kH) : elem0 - (uint32_t)(arow * kH);   // else: row m0, always valid
       regs[q].th = *reinterpret_cast<const f32x4*>(th + i);
       regs[q].m = *reinterpret_cast<const f32x4*>(mo + i);
       regs[q].v = *reinterpret_cast<const f32x4*>(ve + i);
@@ -172,16 +176,17 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   auto load_x = [&]() { xsl.load(x, ldx, M, m0, wave, lane); };
   auto store_x = [&]() { xsl.store(Xl, ldx, M, m0, wave, lane); };
   WeightBlock<1, false, 1> z0;
+  const float* zk = z + n0 + (size_t)kh * 128 * kH;   // this wavefront's rows of dZ
   if (WAIT && wait_on) {                             // x and z come from a chain of this launch:
     load_adam();                                     // the Adam operands can be on their way meanwhile
     setup();
     if (tid == 0) wait_count(d, wait_on, want);
     __syncthreads();
     load_x();
-    z0.load(z + n0, 0, wave, lane);
+    z0.load(zk, 0, cw, lane);
   } else {                                           // what the product needs first goes out first
     load_x();
-    z0.load(z + n0, 0, wave, lane);
+    z0.load(zk, 0, cw, lane);
     __builtin_amdgcn_sched_barrier(0);
     load_adam();
     __builtin_amdgcn_sched_barrier(0);
@@ -195,7 +200,7 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   const Adam adam = *sh;
   Acc<1, 1> acc;
   acc.zero();
-  gemm256_unrolled<1, false, 1, SLIM ? 4 : 8, true>(Xl, kLda, z + n0, z0, wave, lane, acc, NoTail());   // loads between the MFMAs: a
+  gemm256_unrolled<1, false, 1, SLIM ? 4 : 8, true, HALF ? 8 : 16>(Xl + 128 * kh, kLda, zk, z0, cw, lane, acc, NoTail());   // loads between the MFMAs: a
                                                      // block is 8 MFMAs and 8 load instructions, and these kernels run two workgroups per CU
   POP_MARK(53);
   __syncthreads();                                   // every wavefront is done with the X slice
@@ -203,10 +208,11 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   for (int v = 0; v < 16; ++v) Xl[acc_row(v, lane) * kLda + 32 * wave + l32] = acc.t[0][0][v];
   __syncthreads();
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    if ((m0 + arow + 8 * q) < M) {
-      const f32x4 g = *reinterpret_cast<const f32x4*>(&Xl[(arow + 8 * q) * kLda + acol]);
-      adam_store4<WAIT>(adam, regs[q], g, elem0 + (uint32_t)(8 * q * kH), th, mo, ve, tg, gr);
+  for (int q = 0; q < Q; ++q) {
+    if ((m0 + arow + QR * q) < M) {
+      f32x4 g = *reinterpret_cast<const f32x4*>(&Xl[(arow + QR * q) * kLda + acol]);
+      if (HALF) g += *reinterpret_cast<const f32x4*>(&Xl[(arow + QR * q) * kLda + 64 + acol]);
+      adam_store4<WAIT>(adam, regs[q], g, elem0 + (uint32_t)(QR * q * kH), th, mo, ve, tg, gr);
     }
   }
   POP_MARK(54);
@@ -219,7 +225,7 @@ constexpr int kHeadBlock = 16;   // head columns whose Adam operands the small-t
 // chain of this network) run in the same launch -- hold before the first read of chain
 // output, count in at the end.
 // SLIM: the register budget of three workgroups per CU (four dZ buffers, head columns eight at a time).
-template <bool WAIT, bool SLIM = false>
+template <bool WAIT, bool SLIM = false, bool HALF = false>
 __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int actor_phase, int unit, int role,
                                             float* xt_lds, Adam* sh_adam, bool producer_in_launch = true) {
   const int tid = threadIdx.x;
@@ -259,13 +265,16 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
                                                 : d.done_c + parity_base(d, t, 2 * d.P) + unit;
   const int chunks = d.B / (actor_phase ? d.rows_a : (unit & 1) ? d.rows_c : d.rows_c1);   // row chunks of the chain that feeds this network
   const int n1 = (L.in + 31) / 32;
-  if (role < 16 + 2 * n1) {
+  const int tiles = 16 + 2 * n1;                      // 32 x 128 tiles; HALF: each as two roles, 64 columns wide
+  if (role < (HALF ? 2 * tiles : tiles)) {
     const size_t o = (size_t)unit * d.B * kH;        // unit = agent (actor) or network (critics)
-    const int n0 = 128 * (role & 1);
+    const int half = HALF ? (role & 1) : 0;
+    if (HALF) role >>= 1;
+    const int n0 = 128 * (role & 1) + 64 * half;
     const bool w2 = role < 16;                       // else layer 1, whose input is the leading columns of the batch rows
     const float* x = w2 ? (actor_phase ? d.aH1 : d.cH1) + o : batch_rows(d, t, agent);
     const float* z = (w2 ? (actor_phase ? d.adZ2 : d.cdZ2) : (actor_phase ? d.adZ1 : d.cdZ1)) + o;
-    weight_tile<WAIT, SLIM>(d, wait_on, (uint32_t)chunks, sh_adam, setup, delayed_step && !(actor_phase && d.algo == 1), x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
+    weight_tile<WAIT, SLIM, HALF>(d, wait_on, (uint32_t)chunks, sh_adam, setup, delayed_step && !(actor_phase && d.algo == 1), x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
                 (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
   } else {
     // small tensors from per-chunk partial sums; thread c owns hidden unit c.  The Adam operands

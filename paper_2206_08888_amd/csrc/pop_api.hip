@@ -143,7 +143,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // Wide inputs (SAC only; kernels with a pipelined first layer): 32-row chains -- with weights of
   // 2 MB per agent, 16-row workgroups re-read them from L2 often enough to be bound by that -- except
   // for populations too small to fill the chip with them.
-  if (d.D > kMaxIn) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; }
+  if (d.D > kMaxIn) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; d.rows_c1 = 0; }
   if (d.rows_c1 == 0) d.rows_c1 = d.rows_c;
   d.cstride = d.B / (d.rows_c1 < d.rows_c ? d.rows_c1 : d.rows_c);
   // Stand-alone weight-gradient launches: with fewer than two 32 x 128 tiles per CU (19 workgroups per network at

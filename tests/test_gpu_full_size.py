@@ -1,42 +1,30 @@
 """GPU parity at the full sizes of the benchmark configs, in the launch configuration
 bench.py times (whole population resident, real buffer sizes).  The oracle cannot
-step 80 or 256 agents with million-row buffers in seconds, so it steps three sampled
-agents (first, middle, last) alone; population independence (pinned on both sides)
-makes that the same computation.
+step 80 or 256 agents with million-row buffers in seconds, so it steps five sampled
+agents alone; population independence (pinned on both sides) makes that the same computation.
 
-Three phases per config:
-  A. one free step from the common initial state: indices bit-exact, parameters <= 1e-4;
-  B. 30 forced single steps (the sampled GPU agents are set to the oracle's state before
-     each step): tolerances of gpu_common.ForcedStepStats after every step;
-  C. free running from the state after B up to step 100: indices stay bit-exact; the
-     parameter difference is reported and bounded by 1e-2.  The 1e-3 bound of the small
-     free-running test (test_gpu_parity.py) is not asserted here: a free-running fp32
-     trajectory follows the fp64 one to ~3e-7 until some ReLU pre-activation lands within
-     rounding error of zero on one side only; from there the two (both correct)
-     trajectories separate, typically to 1e-4..3e-3 by step 100 for the larger learning
-     rates of these configs."""
+Two phases per config:
+  A. 100 free steps from the common initial state, one step at a time, indices bit-exact at every step.  The first
+     step is compared element by element.  Until an agent meets a ReLU tie its two trajectories must agree to 1e-5
+     (every gradient, every parameter tensor, every step); the step at which they part must be a demonstrated tie:
+     the device's gradient is the oracle's with a hidden unit of relative margin < 1e-6 resolved the other way,
+     reproduced to 1e-5 (gpu_common.free_run_tie_aware).  After it the two are different, equally valid TD3
+     trajectories: bounded by 1e-2 at step 100, median over the sampled agents reported.  An agent that meets no
+     tie ends within 1e-5, far inside the 1e-3 asked for after 100 steps.
+  B. 30 forced single steps (the sampled GPU agents are set to the oracle's state before each step): every
+     tensor element by element (gpu_common.check_step_elementwise), ties demonstrated in the same way and rare."""
 import numpy as np
 import pytest
 
 import workloads
-from gpu_common import (PARAMS6, STATE12, ForcedStepStats, ensure_built, force_state, forced_step_errors,
-                        make_full_size_pair, rel_l2)
+from gpu_common import (PARAMS6, STATE12, check_step_elementwise, describe_free_run, ensure_built, force_state,
+                        free_run_tie_aware, make_full_size_pair, rel_l2, snapshot)
 
 pytestmark = pytest.mark.gpu
 
 @pytest.fixture(scope="module", autouse=True)
 def _lib():
     ensure_built()
-
-
-def _worst(gpu, orc, agents, names):
-    worst = 0.0
-    for j, i in enumerate(agents):
-        for which in names:
-            ref = orc.get_params(j, which)
-            if ref.any():
-                worst = max(worst, rel_l2(gpu.get_params(i, which), ref))
-    return worst
 
 
 def _check_indices(gpu, orc, agents, tag):
@@ -48,31 +36,36 @@ def _check_indices(gpu, orc, agents, tag):
 @pytest.mark.parametrize("config_id", [1, 2, 4])
 def test_sampled_agents_match_oracle_at_full_size(config_id):
     P = workloads.CONFIGS[config_id]["P"]
-    agents = [0, P // 2, P - 1]
+    agents = sorted({0, P // 4, P // 2, (3 * P) // 4, P - 1})
     gpu, orc = make_full_size_pair(config_id, agents)
     pairs = [(i, j) for j, i in enumerate(agents)]
-    # A: one free step
-    gpu.update(1); orc.update(1)
-    _check_indices(gpu, orc, agents, "A")
-    e1 = _worst(gpu, orc, agents, PARAMS6)
-    assert e1 <= 1e-4, (config_id, e1)
+    # A: 100 free steps
+    before = snapshot(orc, range(len(agents)))
+    first = {}
+
+    def each_step(t):
+        _check_indices(gpu, orc, agents, "A%d" % t)
+        if t == 0:
+            first["ties"] = []
+            first["rep"] = check_step_elementwise(gpu, orc, pairs, before, "config %d, first step" % config_id, ties=first["ties"])
+
+    res = free_run_tie_aware(gpu, orc, pairs, 100, "config %d" % config_id, each_step=each_step)
+    print("config %d (P=%d), first step: %s; ties %s" % (config_id, P, first["rep"], first["ties"]))
+    print("config %d (P=%d), 100 free steps: %s" % (config_id, P, describe_free_run(res)))
+    for i, r in res.items():
+        assert r["error"] <= (1e-5 if r["departed"] is None else 1e-2), (config_id, i, r)
+    assert gpu.step_count() == 100
     # B: forced single steps
-    stats = ForcedStepStats()
+    gpu.set_debug(1)
+    ties, rep = [], None
     for step in range(30):
         force_state(gpu, orc, pairs)
+        before = snapshot(orc, range(len(agents)))
         gpu.update(1); orc.update(1)
         _check_indices(gpu, orc, agents, "B%d" % step)
-        stats.add(*forced_step_errors(gpu, orc, pairs), tag=(config_id, step))
-    summary = stats.finish()
-    # C: free running to step 100
-    force_state(gpu, orc, pairs)
-    n = 100 - 31
-    gpu.update(n); orc.update(n)
-    _check_indices(gpu, orc, agents, "C")
-    ec = _worst(gpu, orc, agents, PARAMS6)
-    print("config %d (P=%d): rel-L2 after 1 free step %.2e; %s; after %d free steps %.2e" % (config_id, P, e1, summary, n, ec))
-    assert ec <= 1e-2, (config_id, ec)
-    assert gpu.step_count() == 100
+        rep = check_step_elementwise(gpu, orc, pairs, before, "config %d, forced step %d" % (config_id, step), ties=ties, report=rep)
+    print("config %d (P=%d), 30 forced steps: %s; %d network updates behind a ReLU tie: %s" % (config_id, P, rep, len(ties), ties))
+    assert len(ties) <= 15                               # rare: 30 steps x 5 agents x up to 3 networks were compared
     gpu.close()
 
 

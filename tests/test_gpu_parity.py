@@ -2,16 +2,22 @@
 through the C boundary.  Tolerances (fp32 path against the fp64 oracle):
   * replay indices and gathered rows: bit-exact (integer and copy work);
   * initial parameters: bit-exact (one fp32 rounding on both sides);
-  * gradients: relative L2 <= 1e-5 per network;
-  * parameters: relative L2 per agent and network <= 1e-4 after 1 step and
-    <= 1e-3 after 100 steps."""
+  * single steps from a common state: every tensor (W1, b1, W2, b2, W3, b3) of every network element by
+    element -- gradients within 1e-6 of the tensor's largest entry and 1e-5 relative L2, parameters, targets and
+    Adam moments within the tolerance parity_checks.py derives from the Adam update (1e-4 of max(|theta|, lr) on
+    well-determined entries), entries with an exactly zero gradient unchanged bit for bit;
+  * several free steps: per tensor, relative L2 <= 1e-4 after a few steps and <= 1e-3 after 100 steps (the
+    relative L2 of the whole network is asserted as well);
+  * a hidden unit within fp32 rounding of its ReLU kink may be resolved differently by the two precisions: such a
+    step is accepted only when the device's gradient is reproduced by the oracle's with exactly those units
+    flipped (relu_ties.py), and is then compared as strictly as any other."""
 import numpy as np
 import pytest
 
 import paper_2206_08888_amd as pp
 import workloads
-from gpu_common import (MOM_M, MOM_V, NETS, STATE12, ForcedStepStats, ensure_built, force_state, forced_step_errors,
-                        make_pair, rel_l2)
+from gpu_common import (MOM_M, MOM_V, NETS, PARAMS6, STATE12, check_step_elementwise, check_tensors_all, describe_free_run,
+                        ensure_built, force_state, free_run_tie_aware, make_pair, rel_l2, snapshot)
 
 pytestmark = pytest.mark.gpu
 
@@ -21,14 +27,13 @@ def _lib():
     ensure_built()
 
 
-def _compare_state(gpu, orc, agents, tol, label):
-    worst = 0.0
-    for j, i in enumerate(agents):
-        for which in ("actor", "critic1", "critic2", "t_actor", "t_critic1", "t_critic2"):
-            e = rel_l2(gpu.get_params(i, which), orc.get_params(j, which))
-            worst = max(worst, e)
-            assert e <= tol, "%s: agent %d %s rel-L2 %.3e > %.1e" % (label, i, which, e, tol)
-    print("%s: worst parameter rel-L2 %.3e (tol %.1e)" % (label, worst, tol))
+def _compare_state(gpu, orc, agents, tol, label, steps=1):
+    """Parameters and targets of every network after `steps` free steps: relative L2 of the whole network and of
+    each of its tensors."""
+    pairs = [(i, j) for j, i in enumerate(agents)]
+    worst = check_tensors_all(gpu, orc, pairs, PARAMS6, tol, label, steps=steps)
+    assert worst <= tol, "%s: worst network rel-L2 %.3e > %.1e" % (label, worst, tol)
+    print("%s: worst parameter rel-L2 %.3e (tol %.1e), every tensor within the same tolerance" % (label, worst, tol))
     return worst
 
 
@@ -61,23 +66,24 @@ def test_indices_and_gathered_rows_are_bit_exact_over_steps():
 def test_one_step_matches_oracle():
     gpu, orc, agents = make_pair(0)
     gpu.set_debug(1)
+    before = snapshot(orc, agents)
     gpu.update(1)
     orc.update(1)
     at = gpu.debug("target_action"); y = gpu.debug("target_y"); losses = gpu.debug("losses")
     for i in agents:
         ag = orc.agents[i]
         assert np.abs(at[i] - ag.last["a_tilde"]).max() <= 2e-6
-        assert rel_l2(y[i], ag.last["y"]) <= 1e-5
+        assert np.abs(y[i] - ag.last["y"]).max() <= 1e-5 * np.abs(ag.last["y"]).max()
         assert abs(losses[i, 0] - ag.last["critic_loss"]) <= 1e-5 * abs(ag.last["critic_loss"])
         assert abs(losses[i, 1] - ag.last["actor_loss"]) <= 1e-5 * max(1.0, abs(ag.last["actor_loss"]))
-        for net in NETS:
-            g = gpu.get_params(i, "g_" + net); go = orc.get_params(i, "g_" + net)
-            e = rel_l2(g, go)
-            assert e <= 1e-5, "gradient agent %d %s rel-L2 %.3e" % (i, net, e)
-            # exactly-zero gradients (dead units) must be exactly zero on both sides
-            assert np.array_equal(go == 0.0, g == 0.0) or np.mean((go == 0.0) != (g == 0.0)) < 1e-4
+        for net in NETS:                                  # network-level figures as before, now beside the element-wise ones
+            assert rel_l2(gpu.get_params(i, "g_" + net), orc.get_params(i, "g_" + net)) <= 1e-5
             for mom in ("m_", "v_"):
                 assert rel_l2(gpu.get_params(i, mom + net), orc.get_params(i, mom + net)) <= 2e-5
+    ties = []
+    rep = check_step_elementwise(gpu, orc, [(i, i) for i in agents], before, "config 0, 1 step", ties=ties)
+    print("config 0, 1 step: %s; ties %s" % (rep, ties))
+    assert rep.masked <= 0.01 * rep.entries
     _compare_state(gpu, orc, agents, 1e-4, "config 0, 1 step")
     gpu.close()
 
@@ -89,16 +95,26 @@ def test_two_steps_cover_the_critic_only_branch():
     gpu.update(1); orc.update(1)
     for (i, w), before in snap.items():          # delayed step: actor and targets bit-unchanged
         assert np.array_equal(before, gpu.get_params(i, w)), (i, w)
-    _compare_state(gpu, orc, agents, 1e-4, "config 0, 2 steps")
+    _compare_state(gpu, orc, agents, 1e-4, "config 0, 2 steps", steps=2)
     gpu.close()
 
 
 def test_hundred_steps_match_oracle():
+    """100 free steps in one call: relative L2 <= 1e-3 per network.  The same run taken one step at a time shows
+    where the two precisions part: tight agreement (1e-5, per tensor) until a ReLU tie, which is demonstrated."""
     gpu, orc, agents = make_pair(0)
     gpu.update(100)
     orc.update(100)
-    _compare_state(gpu, orc, agents, 1e-3, "config 0, 100 steps")
+    worst = max(rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) for i in agents for w in PARAMS6)
+    print("config 0, 100 steps in one call: worst network rel-L2 %.3e" % worst)
+    assert worst <= 1e-3
     assert gpu.step_count() == 100
+    gpu.close()
+    gpu, orc, agents = make_pair(0)
+    res = free_run_tie_aware(gpu, orc, [(i, i) for i in agents], 100, "config 0")
+    print("config 0, 100 steps one at a time: " + describe_free_run(res))
+    for i, r in res.items():
+        assert r["error"] <= (1e-5 if r["departed"] is None else 1e-3), (i, r)
     gpu.close()
 
 
@@ -125,7 +141,7 @@ def test_mixed_policy_delays_and_short_buffers():
     hps[0]["policy_delay"], hps[1]["policy_delay"], hps[2]["policy_delay"] = 1, 2, 3
     gpu, orc, agents = make_pair(2, P=3, capacity=500, fill=100, hps=hps)   # count < batch: with replacement
     gpu.update(7); orc.update(7)
-    _compare_state(gpu, orc, agents, 2e-4, "mixed delays, 7 steps")
+    _compare_state(gpu, orc, agents, 2e-4, "mixed delays, 7 steps", steps=7)
     gpu.close()
 
 
@@ -227,20 +243,23 @@ def test_errors_from_the_boundary_on_a_live_context():
 def test_every_single_step_from_the_oracle_state_matches_for_100_steps():
     """Step-by-step parity: before each of 100 steps the GPU agents are set to the oracle's
     current state (rounded to fp32), both sides take ONE step, and all parameters, targets
-    and Adam moments must agree to the one-step tolerance (see ForcedStepStats).  Unlike a
+    and Adam moments must agree element by element (gpu_common.check_step_elementwise).  Unlike a
     free-running comparison this is not at the mercy of ReLU patterns that a rounding
     error of 1e-7 flips (after which two correct trajectories drift apart), and it
     exercises every Adam step count, delayed and non-delayed steps and 100 batches."""
     hps = workloads.hparams(1, 10)[:2]                 # per-agent learning rates of the P = 10 config
     gpu, orc, agents = make_pair(1, P=2, capacity=20000, hps=hps)
-    stats = ForcedStepStats()
+    gpu.set_debug(1)
     pairs = [(i, i) for i in agents]
+    ties, rep = [], None
     for step in range(100):
         force_state(gpu, orc, pairs)
+        before = snapshot(orc, agents)
         gpu.update(1)
         orc.update(1)
-        stats.add(*forced_step_errors(gpu, orc, pairs), tag=step)
-    print(stats.finish())
+        rep = check_step_elementwise(gpu, orc, pairs, before, "forced step %d" % step, ties=ties, report=rep)
+    print("100 forced steps: %s; %d network updates behind a ReLU tie: %s" % (rep, len(ties), ties))
+    assert len(ties) <= 20                               # rare: 600 network updates were compared
     gpu.close()
 
 
@@ -321,9 +340,7 @@ def test_small_populations_with_32_row_critic_chains_match_oracle(P, launches, m
         assert cnt[k] == v, (k, cnt)
     assert cnt["step"] == 0
     orc.update(3)
-    for i in range(P):
-        for w in NETS:
-            assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 1e-4, (i, w)
+    _compare_state(gpu, orc, range(P), 1e-4, "P = %d, 3 steps" % P, steps=3)
     gpu.close()
     monkeypatch.setenv("POP_FUSE", "2")
     if P == 9:                                          # falls back to 64-row critic chains, which the single launch has
@@ -349,9 +366,7 @@ def test_sixty_four_row_chains_match_oracle_and_each_other(monkeypatch):
         gpu.update(5)
         if orc is not None:
             orc.update(5)
-            for i in range(5):
-                for w in NETS:
-                    assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 1e-4, (i, w)
+            _compare_state(gpu, orc, range(5), 1e-4, "64-row chains, 5 steps", steps=5)
         gpu.sync()
         states.append({(i, w): gpu.get_params(i, w) for i in range(5) for w in STATE12})
         gpu.close()
@@ -382,18 +397,21 @@ def test_copy_agent_and_set_hparams_follow_the_oracle():
     for side in (gpu, orc):
         side.set_hparams(0, new0)
         side.set_hparams(1, new1)
-    force_state(gpu, orc, [(i, i) for i in range(P)])          # remove the drift of the first 5 steps
+    pairs = [(i, i) for i in range(P)]
+    gpu.set_debug(1)
+    ties = []
+    force_state(gpu, orc, pairs)                               # remove the drift of the first 5 steps
+    before = snapshot(orc, range(P))
     gpu.update(1); orc.update(1)                               # t = 5: actor step only for agent 1 (delay 1)
-    _compare_state(gpu, orc, range(P), 1e-4, "first step after copy + new hyperparameters")
-    for w in MOM_M + MOM_V:
-        for i in range(P):
-            assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 1e-3, (i, w)
-    force_state(gpu, orc, [(i, i) for i in range(P)])
+    check_step_elementwise(gpu, orc, pairs, before, "first step after copy + new hyperparameters", ties=ties)
+    force_state(gpu, orc, pairs)
+    before = snapshot(orc, range(P))
     gpu.update(1); orc.update(1)                               # t = 6: actor step for agents 0 (delay 3), 1, 2, 3
-    _compare_state(gpu, orc, range(P), 1e-4, "second step (actor step under the new delay; Adam count continues)")
+    check_step_elementwise(gpu, orc, pairs, before, "second step (actor step under the new delay; Adam count continues)", ties=ties)
+    gpu.set_debug(0)
     assert orc.agents[0].actor_updates == 4 and orc.agents[1].actor_updates == 5
     gpu.update(6); orc.update(6)
-    _compare_state(gpu, orc, range(P), 1e-3, "six more free steps")
+    _compare_state(gpu, orc, range(P), 1e-3, "six more free steps", steps=6)
     with pytest.raises(pp.PopError):
         gpu.copy_agent(0, P, True)
     with pytest.raises(pp.PopError):

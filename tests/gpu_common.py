@@ -247,7 +247,9 @@ def check_step_elementwise(gpu, orc, pairs, before, label, grads=True, ties=None
                         flipped[int(net[-1]) - 1] = rt.unflatten(ref["theta"], *shape)
             env, n_env = (rt.tie_envelope(ps, skip=kept) if ties is not None else (None, 0))
             rep.tie_units += n_env
-            pc.check_adam_step(rep, tag, net, shape, got, ref, bef, lr, b1, b2, eps, count, tau=tau_used, tol=tol, eta=eta,
+            # (the shared critics' gradient is a sum over P batches in agent groups: twice the single-batch bound)
+            pc.check_adam_step(rep, tag, net, shape, got, ref, bef, lr, b1, b2, eps, count, tau=tau_used, tol=tol,
+                               eta=2.0 * eta if (kind == "shared" and net != "actor") else eta,
                                g_scale=ps.noise_scale(), g_extra=env)
     return rep
 

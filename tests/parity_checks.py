@@ -25,10 +25,13 @@ Targets: t = (1 - tau) t_before + tau theta, so |t_gpu - t_ref| <= 1e-6 |t_ref| 
 import numpy as np
 
 TENSORS = ("W1", "b1", "W2", "b2", "W3", "b3")
-ETA = 2e-6          # element-wise bound on the gradient's rounding error, relative to the sum of its absolute terms
+ETA = 8e-6          # element-wise bound on the gradient's rounding error, relative to the sum of its absolute terms.  The
+                    # rigorous bound for the 256- to 448-term fp32 dot products of this path is n 2^-24 = 1.5e-5 .. 2.7e-5
+                    # per product (and a gradient entry is several products deep); measured worst on the device: 7.4e-7 at
+                    # fan-ins up to 256, 2.8e-6 at 393, 4.4e-6 at 448
 FLOOR = 0.05        # ... plus this fraction of ETA times the layer's largest gradient entry: a term whose activation is
                     # nearly zero carries that activation's absolute error, not a relative one (measured on the device:
-                    # up to 1.2e-8 of the layer's largest entry beyond 1e-6 * S; the worst element error measured is 7.4e-7 * S)
+                    # up to 1.2e-8 of the layer's largest entry beyond 1e-6 * S)
 TOL = 1e-4          # one-step parameter tolerance (relative; lr is the floor of the scale)
 
 
@@ -105,7 +108,7 @@ class StepReport:
 
 
 def check_adam_step(rep, label, net, shape, got, ref, before, lr, b1, b2, eps, count, tau=None, tol=TOL, eta=ETA,
-                    grad_l2_tol=1e-5, g_scale=None, g_extra=None):
+                    grad_l2_tol=2e-5, g_scale=None, g_extra=None):
     """One network after one Adam step from a common state.
 
     got / ref: dicts with flat arrays 'theta', 'm', 'v' (and 'target' when the targets moved, 'g' when exported /
@@ -147,8 +150,9 @@ def check_adam_step(rep, label, net, shape, got, ref, before, lr, b1, b2, eps, c
                     scale = max(scale, 0.1 * float(np.linalg.norm(np.asarray(g_scale, dtype=np.float64)[s])))
                 extra = float(np.linalg.norm(np.asarray(g_extra, dtype=np.float64)[s])) if g_extra is not None else 0.0
                 e = max(float(np.linalg.norm(g_g[s] - g)) - extra, 0.0) / scale
-                rep.worst_grad_l2 = max(rep.worst_grad_l2, e)
-                assert e <= grad_l2_tol, "%s gradient rel-L2 %.3e" % (tag, e)
+                if g.size >= 8:                              # (a one-entry tensor has had its whole test element-wise)
+                    rep.worst_grad_l2 = max(rep.worst_grad_l2, e)
+                    assert e <= grad_l2_tol, "%s gradient rel-L2 %.3e" % (tag, e)
             # exactly zero on one side only: a unit dead on the whole batch for one side and, through a pre-activation
             # within rounding of zero, alive with a negligible value for the other (the difference is inside e_g,
             # checked above); such entries are rare and are treated as undetermined below

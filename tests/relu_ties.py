@@ -62,15 +62,26 @@ def unflatten(flat, fan_in, fan_out, hidden=(256, 256)):
     return net
 
 
+KAPPA = 0.01      # an activation carries the rounding error of its own dot product; measured in units of the gradient's
+                  # error bound (parity_checks.ETA times the sum of absolute terms) that is KAPPA times the activation's
+                  # own sum of absolute terms: 4e-8 of it, where an fp32 dot product of n terms errs by about
+                  # 2^-24 sqrt(n) times its rms term.  Matters at first-layer fan-ins of several hundred.
+
+
 def abs_sums(net, cache, dy, need_dx=False):
     """Running error scale of a backward pass: the oracle's backward with every product taken on absolute values.
     For every gradient entry (canonical flat order) this is the sum of the absolute values of all the terms that
     enter it, including those of the backward products upstream of it (D_l = D_{l+1} |W_{l+1}|^T under the ReLU
-    mask, dW_l -> |in_l|^T D_l, db_l -> column sums of D_l): the scale of the rounding error of an fp32 evaluation of
-    that entry, cancellation in the back-propagated signal included.  Used for tolerances only; reference values
-    always come from the oracle's own backward.  Returns (flat scale, D at the input or None)."""
+    mask, dW_l -> (|in_l| + KAPPA A_l)^T D_l with A_l the same kind of sum for the forward pass that produced in_l,
+    db_l -> column sums of D_l): the scale of the rounding error of an fp32 evaluation of that entry, cancellation in
+    the back-propagated signal included.  Used for tolerances only; reference values always come from the oracle's
+    own backward.  Returns (flat scale, D at the input or None)."""
     inputs, pre, y, head = cache
     last = len(net) - 1
+    A = [np.zeros_like(inputs[0])]                      # the network's input is exact
+    for l in range(last):
+        a = (np.abs(inputs[l]) + A[l]) @ np.abs(net[l][0]) + np.abs(net[l][1])
+        A.append(a * (pre[l] > 0.0))
     out = [None] * len(net)
     d = np.abs(dy)
     for l in range(last, -1, -1):
@@ -78,7 +89,7 @@ def abs_sums(net, cache, dy, need_dx=False):
             dz = d * (1.0 - y * y) if head == 'tanh' else d
         else:
             dz = d * (pre[l] > 0.0)
-        out[l] = (np.abs(inputs[l]).T @ dz, dz.sum(axis=0))
+        out[l] = ((np.abs(inputs[l]) + KAPPA * A[l]).T @ dz, dz.sum(axis=0))
         if l > 0 or need_dx:
             d = dz @ np.abs(net[l][0]).T
     return mlp.flatten(out), (d if need_dx else None)

@@ -1,14 +1,13 @@
 """GPU parity at the edges of the supported shapes: the largest and the smallest observation / action sizes of
-each algorithm, buffers shorter than a batch, zero-step calls.  Tolerances as elsewhere: gradients are not compared
-here; parameters and targets per network rel-L2 <= 1e-4 on forced single steps, and <= 2e-3 on the very first step
-from the initial state at large fan-ins (Adam's first update is lr * sign(g): a ReLU pre-activation within fp32
-rounding of zero flips the sign of the smallest gradient entries, see test_gpu_sac.py)."""
+each algorithm, buffers shorter than a batch, zero-step calls.  Tolerances as elsewhere: the first step and three
+forced single steps element by element (gpu_common.check_step_elementwise; at large fan-ins a hidden unit within
+fp32 rounding of its kink is common, and must then be demonstrated as such)."""
 import numpy as np
 import pytest
 
 import paper_2206_08888_amd as pp
 import workloads
-from gpu_common import STATE12, PARAMS6, ensure_built, rel_l2
+from gpu_common import STATE12, PARAMS6, check_step_elementwise, check_tensors_all, ensure_built, rel_l2, snapshot
 from oracle import sac as oracle_sac, td3 as oracle_td3, td3_shared as oracle_shared
 
 pytestmark = pytest.mark.gpu
@@ -44,20 +43,21 @@ def _worst(gpu, orc, P, names):
     return max(rel_l2(gpu.get_params(i, n), orc.get_params(i, n)) for i in range(P) for n in names)
 
 
-def _first_then_forced(gpu, orc, P, nets, state, first_tol, steps=3):
-    gpu.update(1); orc.update(1)
-    e1 = _worst(gpu, orc, P, nets)
-    assert e1 <= first_tol, e1
-    eb = 0.0
-    for _ in range(steps):
-        for i in range(P):
-            for n in state:
-                gpu.set_params(i, n, orc.get_params(i, n))
+def _first_then_forced(gpu, orc, P, state, label, steps=3):
+    """The first step from the initial state and `steps` forced single steps, each element by element."""
+    gpu.set_debug(1)
+    pairs = [(i, i) for i in range(P)]
+    ties, rep = [], None
+    for k in range(1 + steps):
+        if k:
+            for i in range(P):
+                for n in state:
+                    gpu.set_params(i, n, orc.get_params(i, n))
+        before = snapshot(orc, range(P))
         gpu.update(1); orc.update(1)
-        e = _worst(gpu, orc, P, nets)
-        eb = max(eb, e)
-        assert e <= 1e-4, e
-    return e1, eb
+        rep = check_step_elementwise(gpu, orc, pairs, before, "%s, step %d" % (label, k), ties=ties, report=rep)
+    gpu.set_debug(0)
+    return rep, ties
 
 
 @pytest.mark.parametrize("O,A", [(56, 8), (1, 1), (63, 1)])
@@ -66,10 +66,10 @@ def test_td3_at_the_ends_of_its_shape_range(O, A):
     for i in range(3):
         for n in PARAMS6:
             assert np.array_equal(gpu.get_params(i, n), orc.get_params(i, n).astype(np.float32)), (i, n)
-    e1, eb = _first_then_forced(gpu, orc, 3, PARAMS6, STATE12, 1e-4)
+    rep, ties = _first_then_forced(gpu, orc, 3, STATE12, "TD3 obs %d act %d" % (O, A))
     obs = np.random.default_rng(2).standard_normal((3, 37, O)).astype(np.float32)
     assert np.abs(gpu.act(obs) - orc.act(obs.astype(np.float64))).max() <= 1e-5
-    print("TD3 obs %d act %d: first step %.2e, forced steps %.2e" % (O, A, e1, eb))
+    print("TD3 obs %d act %d: %s; ties %s" % (O, A, rep, ties))
     gpu.close()
 
 
@@ -81,12 +81,12 @@ def test_sac_at_the_ends_of_its_shape_range(O, A, P):
     for i in range(P):
         for n in SAC_NETS:
             assert np.array_equal(gpu.get_params(i, n), orc.get_params(i, n).astype(np.float32)), (i, n)
-    e1, eb = _first_then_forced(gpu, orc, P, SAC_NETS, SAC_STATE, 2e-3 if O + A > 64 else 1e-4)
+    rep, ties = _first_then_forced(gpu, orc, P, SAC_STATE, "SAC obs %d act %d P %d" % (O, A, P))
     for i in range(P):
         assert abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(i, "log_alpha")[0])) <= 2e-6
     obs = np.random.default_rng(2).standard_normal((P, 19, O)).astype(np.float32)
     assert np.abs(gpu.act(obs) - orc.act(obs.astype(np.float64))).max() <= (2e-5 if O > 64 else 5e-6)
-    print("SAC obs %d act %d P %d: first step %.2e, forced steps %.2e" % (O, A, P, e1, eb))
+    print("SAC obs %d act %d P %d: %s; ties %s" % (O, A, P, rep, ties))
     gpu.close()
 
 
@@ -107,6 +107,11 @@ def test_buffers_shorter_than_a_batch_and_zero_step_calls(algo):
         assert idx[i].max() < 100
         assert np.array_equal(idx[i].astype(np.int64), orc.agents[i].last["idx"]), i
     assert _worst(gpu, orc, P, nets) <= 1e-4
+    if algo == "shared":
+        check_tensors_all(gpu, orc, [(0, 0)], PARAMS6, 1e-4, "short buffers", steps=2)
+        check_tensors_all(gpu, orc, [(i, i) for i in range(P)], ("actor", "t_actor"), 1e-4, "short buffers", steps=2)
+    else:
+        check_tensors_all(gpu, orc, [(i, i) for i in range(P)], nets, 1e-4, "short buffers", steps=2)
     gpu.close()
 
 
@@ -132,5 +137,6 @@ def test_row_classes_without_a_kernel_are_refused_at_launch(monkeypatch):
     gpu, orc = _pair("td3", 3, 17, 6, 600)
     gpu.update(2); orc.update(2)
     assert _worst(gpu, orc, 3, PARAMS6) <= 1e-4
+    check_tensors_all(gpu, orc, [(i, i) for i in range(3)], PARAMS6, 1e-4, "separate launches", steps=2)
     gpu.close()
 

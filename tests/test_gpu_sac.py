@@ -1,14 +1,15 @@
 """GPU parity of the SAC population step against the CPU oracle (oracle/sac.py), through the
 C boundary, at the shapes the paper measures SAC on (HalfCheetah-v2: obs 17, act 6; Sec. 4.1).
-Tolerances as for TD3: initial parameters bit-exact; parameters and targets relative L2 per
-agent and network <= 1e-4 after one step and <= 1e-3 after 100 steps; log alpha absolute."""
+Tolerances as for TD3 (test_gpu_parity.py): initial parameters bit-exact; single steps from a common state
+element by element (gpu_common.check_step_elementwise; a ReLU unit resolved the other way must be demonstrated as
+such); free-running steps per tensor, relative L2 <= 1e-4 after a few steps and <= 1e-3 after 100; log alpha absolute."""
 import numpy as np
 import pytest
 
 import paper_2206_08888_amd as pp
 import workloads
-from gpu_common import ensure_built, rel_l2
-from oracle import sac as oracle_sac, mlp as oracle_mlp, philox as oracle_philox
+from gpu_common import check_step_elementwise, check_tensors_all, ensure_built, rel_l2, snapshot
+from oracle import sac as oracle_sac
 
 pytestmark = pytest.mark.gpu
 
@@ -54,16 +55,21 @@ def make_sac_pair(P=2, capacity=2000, oracle=True, hps=None, agents=None, obs_di
     return gpu, orc, agents
 
 
-def compare(gpu, orc, agents, tol, label, alpha_tol=2e-6):
-    worst = 0.0
-    for j, i in enumerate(agents):
-        for w in NETS5:
-            e = rel_l2(gpu.get_params(i, w), orc.get_params(j, w))
-            worst = max(worst, e)
-            assert e <= tol, "%s: agent %d %s rel-L2 %.3e > %.1e" % (label, i, w, e, tol)
+def compare(gpu, orc, agents, tol, label, alpha_tol=2e-6, steps=1):
+    """After free-running steps: every network as a whole and tensor by tensor; the temperature absolutely."""
+    pairs = [(i, j) for j, i in enumerate(agents)]
+    worst = check_tensors_all(gpu, orc, pairs, NETS5, tol, label, steps=steps)
+    assert worst <= tol, "%s: worst network rel-L2 %.3e > %.1e" % (label, worst, tol)
+    for i, j in pairs:
         da = abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(j, "log_alpha")[0]))
         assert da <= alpha_tol, "%s: agent %d log_alpha differs by %.3e" % (label, i, da)
-    print("%s: worst parameter rel-L2 %.3e (tol %.1e)" % (label, worst, tol))
+    print("%s: worst parameter rel-L2 %.3e (tol %.1e), every tensor within the same tolerance" % (label, worst, tol))
+
+
+def check_alpha(gpu, orc, agents, tol=2e-6):
+    for j, i in enumerate(agents):
+        da = abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(j, "log_alpha")[0]))
+        assert da <= tol, (i, da)
 
 
 def force(gpu, orc, agents):
@@ -87,15 +93,13 @@ def test_initial_state_is_bit_exact():
 def test_one_step_matches_oracle():
     gpu, orc, agents = make_sac_pair()
     gpu.set_debug(True)
+    before = snapshot(orc, agents)
     gpu.update(1); orc.update(1)
-    for i in agents:
-        for w in ("g_critic1", "g_critic2", "g_actor"):
-            e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
-            assert e <= 1e-5, (i, w, e)
+    ties = []
+    rep = check_step_elementwise(gpu, orc, [(i, i) for i in agents], before, "one SAC step", ties=ties)
+    print("one SAC step: %s; ties %s" % (rep, ties))
     compare(gpu, orc, agents, 1e-4, "one SAC step")
     for i in agents:
-        for w in MOMS:
-            assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 2e-5, (i, w)
         for w in ALPHA3[1:]:
             a, b = float(gpu.get_params(i, w)[0]), float(orc.get_params(i, w)[0])
             assert abs(a - b) <= 1e-5 * max(abs(b), 1e-12) + 1e-12, (i, w, a, b)
@@ -104,19 +108,19 @@ def test_one_step_matches_oracle():
 
 
 def test_forty_forced_single_steps_match_oracle():
-    """The GPU state is set to the oracle's before every step, so each step is judged on its own."""
+    """The GPU state is set to the oracle's before every step, so each step is judged on its own, element by element."""
     gpu, orc, agents = make_sac_pair()
-    worst = 0.0
+    gpu.set_debug(True)
+    pairs = [(i, i) for i in agents]
+    ties, rep = [], None
     for step in range(40):
         force(gpu, orc, agents)
+        before = snapshot(orc, agents)
         gpu.update(1); orc.update(1)
-        for j, i in enumerate(agents):
-            for w in NETS5:
-                e = rel_l2(gpu.get_params(i, w), orc.get_params(j, w))
-                worst = max(worst, e)
-                assert e <= 1e-4, (step, i, w, e)
-            assert abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(j, "log_alpha")[0])) <= 2e-6
-    print("forced SAC steps: worst parameter rel-L2 %.3e" % worst)
+        rep = check_step_elementwise(gpu, orc, pairs, before, "forced SAC step %d" % step, ties=ties, report=rep)
+        check_alpha(gpu, orc, agents)
+    print("40 forced SAC steps: %s; %d network updates behind a ReLU tie: %s" % (rep, len(ties), ties))
+    assert len(ties) <= 12
     gpu.close()
 
 
@@ -126,7 +130,7 @@ def test_hundred_steps_match_oracle():
     drift apart, faster for larger learning rates; single steps are covered by the forced test."""
     gpu, orc, agents = make_sac_pair(hps=sac_hparams(2, config_id=0))
     gpu.update(100); orc.update(100)
-    compare(gpu, orc, agents, 1e-3, "100 SAC steps", alpha_tol=1e-4)
+    compare(gpu, orc, agents, 1e-3, "100 SAC steps", alpha_tol=1e-4, steps=100)
     assert gpu.step_count() == 100
     gpu.close()
 
@@ -155,7 +159,7 @@ def test_mid_size_populations_use_the_wider_chains_and_still_match(P):
     hps = sac_hparams(P)
     gpu, orc, agents = make_sac_pair(P=P, capacity=600, hps=hps, agents=[0, P - 1])
     gpu.update(2); orc.update(2)
-    compare(gpu, orc, agents, 1e-4, "two SAC steps at P = %d" % P)
+    compare(gpu, orc, agents, 1e-4, "two SAC steps at P = %d" % P, steps=2)
     gpu.close()
 
 
@@ -211,82 +215,41 @@ def test_copy_agent_carries_the_temperature():
 WIDE = [(376, 17), (40, 10)]
 
 
-def relu_margin(net, x):
-    """Smallest |pre-activation| of the hidden layers of `net` on the rows of x."""
-    _, cache = oracle_mlp.forward(net, x, 'linear')
-    return min(float(np.abs(z).min()) for z in cache[1][:-1])
-
-
-# fp32 products with a fan-in of a few hundred carry absolute errors of a few 1e-6 at these scales; a hidden unit
-# whose fp64 pre-activation is closer to zero than this may switch sides in fp32, which changes the gradient by
-# about 1/B of one sample's share (1e-3 relative): only such a network may miss the sharp tolerance
-KINK = 8e-6
-
-
 @pytest.mark.parametrize("obs_dim,act_dim", WIDE)
 def test_wide_shapes_one_step_matches_oracle(obs_dim, act_dim):
+    """At a fan-in of 393 some hidden unit usually lies within fp32 rounding of its kink in the very first step
+    (measured: a pre-activation of 4.7e-9); the comparison demands that such a step be the oracle's with exactly
+    that unit resolved the other way, and then holds it to the same element-wise tolerance as any other."""
     gpu, orc, agents = make_sac_pair(capacity=700, obs_dim=obs_dim, act_dim=act_dim)
     for i in agents:
         for w in NETS5:
             assert np.array_equal(gpu.get_params(i, w), orc.get_params(i, w).astype(np.float32)), (i, w)
-    # how close the oracle's ReLUs come to their kinks in this step, per agent and network
-    margin = {}
-    actors = [oracle_mlp.copy_net(ag.actor) for ag in orc.agents]
-    for i, ag in enumerate(orc.agents):
-        idx = oracle_philox.sample_indices(ag.seed, 0, ag.B, ag.buffer.count)
-        s, a = (x.astype(np.float64) for x in ag.buffer.gather(idx)[:2])
-        for k in range(2):
-            margin[i, "critic%d" % (k + 1)] = relu_margin(ag.critic[k], np.concatenate([s, a], axis=1))
     gpu.set_debug(True)
+    before = snapshot(orc, agents)
     gpu.update(1); orc.update(1)
-    for i, ag in enumerate(orc.agents):                 # the actor pass runs through the updated critics
-        idx = ag.last["idx"]
-        s = ag.buffer.gather(idx)[0].astype(np.float64)
-        a_pi = oracle_sac.sample_policy(actors[i], s, ag.last["eps1"])[0]
-        x = np.concatenate([s, a_pi], axis=1)
-        margin[i, "actor"] = min(relu_margin(actors[i], s), relu_margin(ag.critic[0], x), relu_margin(ag.critic[1], x))
-    loose = []
-    for i in agents:
-        for w in ("critic1", "critic2", "actor"):
-            e = rel_l2(gpu.get_params(i, "g_" + w), orc.get_params(i, "g_" + w))
-            sharp = e <= 1e-5
-            if not sharp:                                 # only a ReLU on its kink explains more
-                assert margin[i, w] <= KINK and e <= 2e-2, (i, w, e, margin[i, w])
-                loose.append((i, w, e, margin[i, w]))
-            for mom, mtol in (("m_", 2e-5), ("v_", 4e-5)):
-                e = rel_l2(gpu.get_params(i, mom + w), orc.get_params(i, mom + w))
-                assert e <= (mtol if sharp else 4e-2), (i, mom + w, e)
-    print("networks compared at the loose tolerance (agent, network, error, ReLU margin): %s" % loose)
-    assert len(loose) <= 2, loose                         # the sharp comparison must cover most networks
-    # Adam's first step moves every weight by about lr * sign(g): where the kink flipped the signs of the smallest
-    # gradient entries the parameters differ by 2 lr there
-    kinked = {(i, w) for i, w, _, _ in loose}
-    for i in agents:
-        for w in NETS5:
-            tol = 2e-3 if (i, w.replace("t_", "")) in kinked else 1e-4
-            e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
-            assert e <= tol, (i, w, e, tol)
-        assert abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(i, "log_alpha")[0])) <= 2e-6
+    ties = []
+    rep = check_step_elementwise(gpu, orc, [(i, i) for i in agents], before, "one SAC step at obs %d, act %d" % (obs_dim, act_dim), ties=ties)
+    print("one SAC step at obs %d, act %d: %s; ties %s" % (obs_dim, act_dim, rep, ties))
+    assert len(ties) <= 2, ties                           # the plain comparison must cover most networks
+    check_alpha(gpu, orc, agents)
     gpu.close()
 
 
 @pytest.mark.parametrize("obs_dim,act_dim", WIDE)
 def test_wide_shapes_forced_single_steps_match_oracle(obs_dim, act_dim):
-    """Step 0 is judged by its gradients in the one-step test: Adam's first update is lr * sign(g), which turns a
-    ReLU resolved differently in fp32 (it happens at these fan-ins) into 2 lr on the smallest gradient entries."""
     gpu, orc, agents = make_sac_pair(capacity=700, obs_dim=obs_dim, act_dim=act_dim)
-    worst = 0.0
+    gpu.set_debug(True)
+    pairs = [(i, i) for i in agents]
+    ties, rep = [], None
     for step in range(12):
         force(gpu, orc, agents)
+        before = snapshot(orc, agents)
         gpu.update(1); orc.update(1)
-        for j, i in enumerate(agents):
-            for w in NETS5:
-                e = rel_l2(gpu.get_params(i, w), orc.get_params(j, w))
-                if step > 0:
-                    worst = max(worst, e)
-                assert e <= (2e-3 if step == 0 else 1e-4), (step, i, w, e)
-            assert abs(float(gpu.get_params(i, "log_alpha")[0]) - float(orc.get_params(j, "log_alpha")[0])) <= 2e-6
-    print("forced SAC steps at obs %d, act %d: worst parameter rel-L2 %.3e" % (obs_dim, act_dim, worst))
+        rep = check_step_elementwise(gpu, orc, pairs, before, "forced SAC step %d at obs %d, act %d" % (step, obs_dim, act_dim),
+                                     ties=ties, report=rep)
+        check_alpha(gpu, orc, agents)
+    print("12 forced SAC steps at obs %d, act %d: %s; %d network updates behind a ReLU tie: %s" % (obs_dim, act_dim, rep, len(ties), ties))
+    assert len(ties) <= 8
     gpu.close()
 
 
@@ -296,7 +259,7 @@ def test_wide_shapes_in_a_mid_size_population(obs_dim, act_dim):
     hps = sac_hparams(20, act_dim=act_dim)
     gpu, orc, agents = make_sac_pair(P=20, capacity=400, hps=hps, agents=[0, 19], obs_dim=obs_dim, act_dim=act_dim)
     gpu.update(2); orc.update(2)
-    compare(gpu, orc, agents, 1e-4, "two SAC steps at P = 20, obs %d, act %d" % (obs_dim, act_dim))
+    compare(gpu, orc, agents, 1e-4, "two SAC steps at P = 20, obs %d, act %d" % (obs_dim, act_dim), steps=2)
     gpu.close()
 
 

@@ -1,13 +1,14 @@
 """GPU parity of TD3 with shared critics (Sec. 4.2 of the paper) against oracle/td3_shared.py, through the
-C boundary.  Tolerances as for TD3: initial parameters bit-exact; gradients rel-L2 <= 1e-5, parameters and
-targets <= 1e-4 after one step and <= 1e-3 after 100 steps, per network."""
+C boundary.  Tolerances as for TD3 (test_gpu_parity.py): initial parameters bit-exact; single steps from a common
+state element by element (a ReLU unit resolved the other way must be demonstrated as such); free-running steps per
+tensor, relative L2 <= 1e-4 after a few steps and <= 1e-3 after 100."""
 import numpy as np
 import pytest
 
 import paper_2206_08888_amd as pp
 import workloads
-from gpu_common import ensure_built, rel_l2
-from oracle import mlp as oracle_mlp, philox as oracle_philox, td3_shared as oracle_shared
+from gpu_common import check_step_elementwise, check_tensors_all, ensure_built, rel_l2, snapshot
+from oracle import td3_shared as oracle_shared
 
 pytestmark = pytest.mark.gpu
 
@@ -35,19 +36,13 @@ def make_shared_pair(P=3, capacity=1500, hps=None, oracle=True, config_id=2):
     return gpu, orc
 
 
-def compare(gpu, orc, tol, label):
+def compare(gpu, orc, tol, label, steps=1):
+    """After free-running steps: the one critic pair and every policy, as whole networks and tensor by tensor."""
     P = len(orc.agents)
-    worst = 0.0
-    for w in CRITIC_SIDE:
-        e = rel_l2(gpu.get_params(0, w), orc.get_params(0, w))
-        worst = max(worst, e)
-        assert e <= tol, "%s: %s rel-L2 %.3e > %.1e" % (label, w, e, tol)
-    for i in range(P):
-        for w in ACTOR_SIDE:
-            e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
-            worst = max(worst, e)
-            assert e <= tol, "%s: agent %d %s rel-L2 %.3e > %.1e" % (label, i, w, e, tol)
-    print("%s: worst parameter rel-L2 %.3e (tol %.1e)" % (label, worst, tol))
+    worst = max(check_tensors_all(gpu, orc, [(0, 0)], CRITIC_SIDE, tol, label, steps=steps),
+                check_tensors_all(gpu, orc, [(i, i) for i in range(P)], ACTOR_SIDE, tol, label, steps=steps))
+    assert worst <= tol, "%s: worst network rel-L2 %.3e > %.1e" % (label, worst, tol)
+    print("%s: worst parameter rel-L2 %.3e (tol %.1e), every tensor within the same tolerance" % (label, worst, tol))
 
 
 def force(gpu, orc):
@@ -71,19 +66,12 @@ def test_initial_state_one_critic_pair_from_agent_zero():
 def test_one_step_matches_oracle():
     gpu, orc = make_shared_pair()
     gpu.set_debug(True)
+    before = snapshot(orc, range(3))
     gpu.update(1); orc.update(1)
-    for w in ("g_critic1", "g_critic2"):
-        e = rel_l2(gpu.get_params(1, w), orc.get_params(1, w))
-        assert e <= 1e-5, (w, e)
-    for i in range(3):
-        e = rel_l2(gpu.get_params(i, "g_actor"), orc.get_params(i, "g_actor"))
-        assert e <= 1e-5, (i, e)
+    ties = []
+    rep = check_step_elementwise(gpu, orc, [(i, i) for i in range(3)], before, "one step, shared critics", ties=ties)
+    print("one step, shared critics: %s; ties %s" % (rep, ties))
     compare(gpu, orc, 1e-4, "one step, shared critics")
-    for w in MOMS_C:
-        assert rel_l2(gpu.get_params(0, w), orc.get_params(0, w)) <= 2e-5, w
-    for i in range(3):
-        for w in MOMS_A:
-            assert rel_l2(gpu.get_params(i, w), orc.get_params(i, w)) <= 2e-5, (i, w)
     losses = gpu.debug("losses")
     assert abs(losses[0, 0] - orc.last["critic_loss"]) <= 1e-5 * abs(orc.last["critic_loss"])
     assert np.all(losses[:, 0] == losses[0, 0])             # the population's critic loss, reported for every agent
@@ -95,27 +83,23 @@ def test_one_step_matches_oracle():
 
 def test_thirty_forced_single_steps_match_oracle():
     gpu, orc = make_shared_pair()
-    worst = 0.0
+    gpu.set_debug(True)
+    pairs = [(i, i) for i in range(3)]
+    ties, rep = [], None
     for step in range(30):
         force(gpu, orc)
+        before = snapshot(orc, range(3))
         gpu.update(1); orc.update(1)
-        for w in CRITIC_SIDE:
-            e = rel_l2(gpu.get_params(0, w), orc.get_params(0, w))
-            worst = max(worst, e)
-            assert e <= 1e-4, (step, w, e)
-        for i in range(3):
-            for w in ACTOR_SIDE:
-                e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
-                worst = max(worst, e)
-                assert e <= 1e-4, (step, i, w, e)
-    print("forced steps, shared critics: worst parameter rel-L2 %.3e" % worst)
+        rep = check_step_elementwise(gpu, orc, pairs, before, "forced step %d, shared critics" % step, ties=ties, report=rep)
+    print("30 forced steps, shared critics: %s; %d network updates behind a ReLU tie: %s" % (rep, len(ties), ties))
+    assert len(ties) <= 10
     gpu.close()
 
 
 def test_hundred_steps_match_oracle():
     gpu, orc = make_shared_pair(P=2, hps=workloads.hparams(0, 2), capacity=2000)
     gpu.update(100); orc.update(100)
-    compare(gpu, orc, 1e-3, "100 steps, shared critics")
+    compare(gpu, orc, 1e-3, "100 steps, shared critics", steps=100)
     assert gpu.step_count() == 100
     gpu.close()
 
@@ -135,45 +119,24 @@ def test_population_of_one_equals_plain_td3():
     shared.close(); plain.close()
 
 
-def critic_relu_margin(orc, k, t):
-    """Smallest |hidden pre-activation| of shared critic k over every agent's batch of step t (before the step)."""
-    m = np.inf
-    for ag in orc.agents:
-        idx = oracle_philox.sample_indices(ag.seed, t, ag.B, ag.buffer.count)
-        s, a = (x.astype(np.float64) for x in ag.buffer.gather(idx)[:2])
-        _, cache = oracle_mlp.forward(orc.critic[k], np.concatenate([s, a], axis=1), 'linear')
-        m = min(m, min(float(np.abs(z).min()) for z in cache[1][:-1]))
-    return m
-
-
 def test_agents_in_uneven_groups_match_oracle():
     """P = 27: the critic gradient is summed in 20 groups of one or two agents.  With 3.5 million hidden
-    pre-activations per critic and step, one of them usually lies within fp32 rounding of zero
-    and is resolved differently by the two precisions: that network's gradient may then differ
-    by one sample's share, and Adam's first, sign-like step turns it into 2 lr on the smallest entries."""
+    pre-activations per critic and step, one of them usually lies within fp32 rounding of zero and is resolved
+    differently by the two precisions; the comparison demands that the device's critic gradient then be the oracle's
+    with exactly that unit flipped, and holds the step -- the critics, and every policy behind critic 1 -- to the
+    ordinary element-wise tolerance against the oracle's arithmetic on that gradient."""
     P = 27
     gpu, orc = make_shared_pair(P=P, capacity=500)
-    margin = [critic_relu_margin(orc, k, 0) for k in range(2)]
     gpu.set_debug(True)
+    pairs = [(i, i) for i in range(P)]
+    before = snapshot(orc, range(P))
     gpu.update(1); orc.update(1)
-    kinked = []
-    for k in range(2):
-        w = "critic%d" % (k + 1)
-        e = rel_l2(gpu.get_params(0, "g_" + w), orc.get_params(0, "g_" + w))
-        if e > 1e-5:                                        # only a ReLU on its kink explains more
-            assert margin[k] <= 1e-6 and e <= 2e-2, (w, e, margin[k])
-            kinked.append(w)
-        for name in (w, "t_" + w):
-            e = rel_l2(gpu.get_params(0, name), orc.get_params(0, name))
-            assert e <= (2e-3 if w in kinked else 1e-4), (name, e)
-    print("critics compared at the loose tolerance at step 0: %s (ReLU margins %s)" % (kinked, margin))
-    for i in range(P):                                      # the policies went through critic 1: same allowance
-        for w in ACTOR_SIDE:
-            e = rel_l2(gpu.get_params(i, w), orc.get_params(i, w))
-            assert e <= 2e-3, (i, w, e)
-    force(gpu, orc)                                         # later steps are not sign-like: judged at the sharp tolerance
+    ties = []
+    rep = check_step_elementwise(gpu, orc, pairs, before, "first step at P = %d, shared critics" % P, ties=ties)
+    print("first step at P = %d, shared critics: %s; ties %s" % (P, rep, ties))
+    force(gpu, orc)
     gpu.update(2); orc.update(2)
-    compare(gpu, orc, 1e-4, "two steps from a common state at P = %d, shared critics" % P)
+    compare(gpu, orc, 1e-4, "two steps from a common state at P = %d, shared critics" % P, steps=2)
     gpu.close()
 
 

@@ -220,6 +220,18 @@ int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
 int pop_act_explore(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
                     int32_t ptrs_on_device, const float* sigma, uint32_t step);
 
+/* pop_act_explore for callers that cannot allocate device memory or wait for the device: code under HIP graph
+ * capture, tight acting loops, harnesses that forbid hipMalloc.  Same result as pop_act_explore with device
+ * pointers (obs and act_out are device pointers, sigma a host array of P values read before the call returns).
+ * It allocates nothing, copies nothing and synchronises nothing: the noise scales reach the device as a kernel
+ * argument and are staged in a static device array of 256 floats (1 KiB per GPU, held until the process ends), so
+ * populations of more than 256 agents are refused with POP_EUNSUPPORTED.  Every call on a GPU shares that GPU's
+ * array, whatever the context: calls that can overlap on one GPU (different streams, different threads) race on
+ * it; calls on one stream are ordered.  Nothing in the array has to be cleared between calls: a call writes the P
+ * entries it reads. */
+int pop_act_explore_noalloc(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
+                            const float* sigma, uint32_t step);
+
 /* Copy one tensor of one agent (see the POP_* codes) into out[out_len];
  * out_len must be at least the tensor's length, else POP_EINVAL and nothing
  * is written.  Returns the number of floats written (>= 0) or an error. */

@@ -80,6 +80,7 @@ def load_library():
         "pop_update_timed": (C.c_int, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "pop_act": (C.c_int, [vp, fp, i32, fp, i32]),
         "pop_act_explore": (C.c_int, [vp, fp, i32, fp, i32, fp, C.c_uint32]),
+        "pop_act_explore_noalloc": (C.c_int, [vp, fp, i32, fp, fp, C.c_uint32]),
         "pop_get_params": (i64, [vp, i32, i32, fp, i64, i32]),
         "pop_set_params": (C.c_int, [vp, i32, i32, fp, i64, i32]),
         "pop_copy_agent": (C.c_int, [vp, i32, i32, i32]),
@@ -194,6 +195,13 @@ def pop_act_explore(ctx, obs, n, act_out, sigma, step):
     sigma = np.ascontiguousarray(sigma, dtype=np.float32)
     return _check(load_library().pop_act_explore(ctx, _ptr(obs, dev), n, _ptr(act_out, dev), int(dev),
                                                  C.c_void_p(sigma.ctypes.data), int(step)), ctx)
+
+
+def pop_act_explore_noalloc(ctx, obs, n, act_out, sigma, step):
+    """obs and act_out: device tensors; sigma: host values, one per agent."""
+    sigma = np.ascontiguousarray(sigma, dtype=np.float32)
+    return _check(load_library().pop_act_explore_noalloc(ctx, _ptr(obs, True), n, _ptr(act_out, True),
+                                                         C.c_void_p(sigma.ctypes.data), int(step)), ctx)
 
 
 def pop_get_params(ctx, agent, which, out):

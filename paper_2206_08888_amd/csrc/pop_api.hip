@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -16,7 +17,43 @@
 
 using namespace pop;
 
+// Scratch of pop_act_explore_noalloc: the per-agent noise scales of the call in flight.  One array per GPU for the
+// life of the process (1 KiB); host code reaches it only through the address hipGetSymbolAddress returns for the
+// device that is current (scratch_address below), never through this name.
+constexpr int kStaticMaxP = 256;
+static __device__ __align__(256) float scratch[kStaticMaxP];
+
 namespace {
+
+struct SigmaArgs { float s[kStaticMaxP]; };            // travels to the device as a kernel argument (1 KiB)
+
+__global__ void k_stage_sigma(float* dst, SigmaArgs a, int P) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < P) dst[i] = a.s[i];
+}
+
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices];                     // address of `scratch` on each device, once looked up
+std::mutex g_scratch_mutex;
+
+// Address of the static scratch array on the device that is current (looked up once per device).
+hipError_t scratch_address(float** out, int* device) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  *device = dev;
+  return hipSuccess;
+}
 
 constexpr int64_t kAlign = 256;
 constexpr int64_t kStagingBytes = 16ll << 20;
@@ -45,6 +82,8 @@ struct pop_ctx {
   uint64_t t;                    // update steps taken
   uint64_t gathered_t;           // step whose batch already sits in its half of the double buffer
   uint32_t step_launches;        // launches of the step kernel so far (alternates its hand-over counters)
+  float* static_scratch;         // this device's copy of the static scratch array (pop_act_explore_noalloc)
+  int device;                    // the device that was current at pop_create
   int fuse;                      // launch structure of a step, see POP_K_* in pop.h: 0 one launch per part, 1 target and
                                  // critic chains in one launch, 2 one launch per step, 3 as 1 plus the rest of a
                                  // delayed step in one launch
@@ -387,6 +426,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   hipError_t e;
   if ((e = setup_kernels()) != hipSuccess || (e = setup_step_kernel()) != hipSuccess || (e = setup_sac_kernels()) != hipSuccess)
     return bail(e, "kernel attribute setup");
+  if ((e = scratch_address(&ctx->static_scratch, &ctx->device)) != hipSuccess) return bail(e, "hipGetSymbolAddress(scratch)");
   hipStream_t s = ctx->stream;
   // everything between the hyperparameters and the staging area starts at zero
   if ((e = hipMemsetAsync(w, 0, (size_t)L.staging, s)) != hipSuccess) return bail(e, "hipMemsetAsync");
@@ -665,6 +705,29 @@ int pop_act_explore(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, i
   HIP_TRY(ctx, hipMemcpyAsync(sigma_dev, sigma, sizeof(float) * ctx->d.P, hipMemcpyHostToDevice, ctx->stream));
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   return act_impl(ctx, obs, n, act_out, ptrs_on_device, sigma_dev, step);
+}
+
+int pop_act_explore_noalloc(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, const float* sigma, uint32_t step) {
+  if (!ctx) return POP_EINVAL;
+  const PopDev& d = ctx->d;
+  if (d.P > kStaticMaxP)
+    return fail(ctx, POP_EUNSUPPORTED, "a population of %d agents exceeds the %d the static scratch array holds", d.P, kStaticMaxP);
+  if (!sigma) return fail(ctx, POP_EINVAL, "sigma is NULL");
+  if (n < 0) return fail(ctx, POP_EINVAL, "n is negative");
+  if ((int64_t)n * d.A > 0xFFFFFFFFll) return fail(ctx, POP_EINVAL, "n * act_dim exceeds 2^32");
+  SigmaArgs args;
+  for (int a = 0; a < d.P; ++a) {
+    if (!(sigma[a] >= 0.0f)) return fail(ctx, POP_EINVAL, "agent %d: sigma must be >= 0", a);
+    args.s[a] = sigma[a];
+  }
+  if (n == 0) return POP_OK;
+  if (!obs || !act_out) return fail(ctx, POP_EINVAL, "NULL array");
+  // two launches in stream order and nothing else: the noise scales go into this device's scratch array as a kernel
+  // argument, the acting kernel reads them from there
+  k_stage_sigma<<<dim3((d.P + 63) / 64), dim3(64), 0, ctx->stream>>>(ctx->static_scratch, args, d.P);
+  HIP_TRY(ctx, hipGetLastError());
+  HIP_TRY(ctx, launch_act(d, obs, n, act_out, ctx->static_scratch, step, 0u, ctx->stream));
+  return POP_OK;
 }
 
 int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, int64_t out_len, int32_t on_device) {

@@ -81,6 +81,34 @@ typedef struct {
  * 1 <= capacity < 2^32; TD3: obs_dim + act_dim <= 64, act_dim <= 8 (HalfCheetah-v2 of
  * Sec. 4.1 is 17 / 6); SAC: obs_dim + act_dim <= 448, act_dim <= 24 (up to the
  * Humanoid-v2 shapes 376 / 17).  Anything else gives POP_EUNSUPPORTED. */
+
+/* How the kernels of an update step are launched and tiled.  All zeros (the default of a cleared pop_config) lets
+ * the library choose by population size; the fields exist for measurements and for tests that compare the choices
+ * with one another.  They change no result beyond the order of fp32 sums: with the same rows and tile widths every
+ * launch structure gives bit-identical results.  Nothing is read from the process environment. */
+enum {
+  POP_LAUNCH_AUTO = 0,
+  POP_LAUNCH_PER_PART = 1,       /* one launch per part of the step: POP_K_TARGET .. POP_K_WGRAD_ACTOR */
+  POP_LAUNCH_TARGET_CRITIC = 2,  /* target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest per part */
+  POP_LAUNCH_SINGLE = 3,         /* the whole step in one launch (POP_K_STEP) */
+  POP_LAUNCH_TAIL = 4            /* as TARGET_CRITIC, and on steps with an actor update the rest in one launch
+                                    (POP_K_STEP_TAIL) */
+};
+typedef struct {
+  int32_t launch;        /* POP_LAUNCH_*.  SINGLE and TAIL exist for TD3 whose chains all take 32 or 64 batch rows per
+                            workgroup, or (16, 64, 16); pop_create refuses them with POP_EINVAL otherwise.  SAC and
+                            shared critics take PER_PART or TARGET_CRITIC. */
+  int32_t rows_target, rows_critic, rows_actor;   /* batch rows per workgroup of the three layer chains: 0 = choose;
+                            32 or 64, and 16 for the target and actor chains.  A launch structure that has no kernel
+                            for the rows asked for fails at pop_update with POP_EHIP and runs nothing. */
+  int32_t rows_critic1;  /* 0 = choose; 16: the 16-row target workgroups go on into critic 1 for their own rows and only
+                            critic 2 has workgroups of its own (TD3 with TARGET_CRITIC and rows_target == 16 only);
+                            otherwise equal to rows_critic */
+  int32_t half_tiles;    /* weight-gradient tiles of half the width in the stand-alone tile launches: 0 = choose (on
+                            while all of them are resident at once, up to 10 agents), 1 = off, 2 = on.  The sums over
+                            the batch then come in two halves: compare launch structures with this set to 1. */
+} pop_tuning;
+
 typedef struct {
   int32_t algo;
   int32_t P;
@@ -89,6 +117,7 @@ typedef struct {
   int32_t hidden[4];
   int32_t batch;
   int64_t capacity;     /* replay rows per agent */
+  pop_tuning tuning;    /* all zeros: the library chooses */
 } pop_config;
 
 /* Which tensor pop_get_params returns.  Networks come in the canonical flat
@@ -120,12 +149,14 @@ enum {
                                 actor loss of the last step that had one) */
 };
 
-/* Bytes of device workspace a population of this shape needs (replay buffers
- * included), or a negative POP_E* code. */
+/* Bytes of device workspace a population of this shape needs, or a negative POP_E* code.  Everything the
+ * population owns lives in that one allocation -- the stacked parameter tensors of all agents (App. C: one [P, in,
+ * out] array per layer instead of P small ones; Sec. 4.1 names the single allocation as what keeps memory from
+ * fragmenting), targets, Adam moments, the per-agent replay buffers (App. A) and the step's scratch. */
 int64_t pop_workspace_bytes(const pop_config* cfg);
 
-/* Number of floats of one network in canonical order: which = POP_ACTOR or
- * any critic code.  Negative POP_E* code on bad arguments. */
+/* Number of floats of one network of one agent in canonical order (App. C: per layer W[in, out] then b[out]):
+ * which = POP_ACTOR or any critic code.  Negative POP_E* code on bad arguments. */
 int64_t pop_net_size(const pop_config* cfg, int32_t which);
 
 /* Create a population (Sec. 4.1: N replicas with different initial weights
@@ -158,29 +189,11 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs,
  * POP_EEMPTY if some agent has no transitions. */
 int pop_update(pop_ctx* ctx, int32_t n_steps);
 
-/* Kernels of an update step (indices into the arrays of pop_update_timed).
- * A step can be ONE launch, POP_K_STEP: target chains, critic chains,
- * critic weight-gradient tiles, actor chains, actor weight-gradient tiles and
- * the gather of the next step's rows are parts of one grid and hand their
- * results on per agent / per network inside the launch.  The environment
- * variable POP_FUSE, read at pop_create, selects the launch structure:
- *   2 one launch per step (TD3 default for 34 .. 83 agents);
- *   1 target and critic chains in one launch (POP_K_TARGET_CRITIC), the rest
- *     one launch per part (TD3 default up to 12, for 17 .. 33 and from 84 agents; shared critics;
- *     SAC up to 8 agents);
- *   3 as 1, but on steps with an actor update the rest of the step is one
- *     launch (POP_K_STEP_TAIL);
- *   0 one launch per part (POP_K_TARGET .. POP_K_WGRAD_ACTOR; TD3 default for 13 .. 16 agents; SAC).
- * 2 and 3 exist for populations whose chains all take 32 or 64 batch rows per workgroup, and for the
- * small class with 64-row critic chains (POP_ROWS=16); pop_create refuses them with POP_EINVAL otherwise.
- * POP_ROWS (16, 32, 64, "16+" / "16++" -- 16-row target workgroups that go on into critic 1, 32- / 64-row workgroups
- * for critic 2, TD3 with POP_FUSE=1 only -- or "target,critic,actor" with 16 allowed for the target and actor chains only), read
- * wherever a configuration is sized, overrides the batch rows per workgroup of the chains; a launch
- * that has no kernel for the rows asked for fails with POP_EHIP and runs nothing.
- * POP_HALF_TILES=0/1 switches the half-width weight-gradient tiles of the stand-alone launches off / on
- * (default: on up to 10 agents; always off while POP_FUSE is set, so that the launch structures compare
- * bit for bit).
- * The arithmetic, and so every result, is bit-identical in all of them. */
+/* Kernels of an update step (indices into the arrays of pop_update_timed).  The parts of a step -- target chains,
+ * critic chains, critic weight-gradient tiles, actor chains, actor weight-gradient tiles, the gather of the next
+ * step's rows -- run as one launch each, or several of them as parts of one grid that hand their results on per
+ * agent / per network inside the launch (Sec. 4.1: the cost of a small population's step is dispatch, not
+ * arithmetic); pop_tuning.launch says which. */
 enum {
   POP_K_GATHER = 0,        /* replay index draw + row gather (first step of a call only) */
   POP_K_TARGET = 1,        /* target actor, smoothing, twin target critics, y */
@@ -203,7 +216,8 @@ int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launche
 
 /* Deterministic actions of every agent's current actor (for SAC: the tanh of
  * the mean): obs[P, n, obs_dim] -> act_out[P, n, act_dim] (agent i acts on
- * slice i). */
+ * slice i).  This is the inference the paper's actor processes run on their copy of the parameters (App. A), here
+ * for the whole population at once on the device that holds them. */
 int pop_act(pop_ctx* ctx, const float* obs, int32_t n, float* act_out,
             int32_t ptrs_on_device);
 
@@ -284,15 +298,26 @@ int pop_debug_indices(pop_ctx* ctx, int64_t* out);
 int64_t pop_step_count(const pop_ctx* ctx);
 int64_t pop_buffer_count(const pop_ctx* ctx, int32_t agent);
 
-/* Block until everything enqueued by this context has finished; reports
- * asynchronous kernel errors as POP_EHIP, and likewise a wait between
- * workgroups of a fused launch that ran into its time limit
- * (50 ms per wait; the launch still completes, its results are invalid). */
+/* Runtime options of a context. */
+enum {
+  POP_OPT_WAIT_LIMIT_TICKS = 0   /* longest wait of one workgroup for another of the same launch, in 10 ns ticks
+                                    (1 .. 10^9; default 5,000,000 = 50 ms).  In force from the next launch on. */
+};
+int pop_set_option(pop_ctx* ctx, int32_t key, int64_t value);
+
+/* Block until everything enqueued by this context has finished (Sec. 4.1: the host takes part only between
+ * device calls of many update steps each); reports asynchronous kernel errors as POP_EHIP.
+ * A wait between workgroups of a fused launch that ran into its time limit (the launch still completes, its
+ * results are invalid) is reported once, as POP_EHIP, by the first call that synchronises after it -- pop_sync,
+ * pop_update_timed, and pop_get_params / pop_debug_get / pop_act with host pointers -- and then cleared: the
+ * population's state is invalid from that step on until the caller restores it (pop_set_params). */
 int pop_sync(pop_ctx* ctx);
 
-/* Free the host-side context (never the workspace). */
+/* Free the host-side context (never the workspace: Sec. 4.1's single allocation stays the caller's). */
 int pop_destroy(pop_ctx* ctx);
 
+/* Message of the last failing call on this context (of the last failing pop_create, pop_workspace_bytes or
+ * pop_net_size of this thread when ctx is NULL).  Valid until the next call on the context. */
 const char* pop_last_error(const pop_ctx* ctx);
 
 #ifdef __cplusplus

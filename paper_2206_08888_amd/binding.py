@@ -30,13 +30,22 @@ class pop_hparams(C.Structure):
                 ("reserved_", C.c_int32)]
 
 
+POP_LAUNCH_AUTO, POP_LAUNCH_PER_PART, POP_LAUNCH_TARGET_CRITIC, POP_LAUNCH_SINGLE, POP_LAUNCH_TAIL = 0, 1, 2, 3, 4
+POP_OPT_WAIT_LIMIT_TICKS = 0
+
+
+class pop_tuning(C.Structure):
+    _fields_ = [("launch", C.c_int32), ("rows_target", C.c_int32), ("rows_critic", C.c_int32), ("rows_actor", C.c_int32),
+                ("rows_critic1", C.c_int32), ("half_tiles", C.c_int32)]
+
+
 class pop_config(C.Structure):
     _fields_ = [("algo", C.c_int32), ("P", C.c_int32), ("obs_dim", C.c_int32), ("act_dim", C.c_int32),
                 ("n_hidden", C.c_int32), ("hidden", C.c_int32 * 4), ("batch", C.c_int32),
-                ("capacity", C.c_int64)]
+                ("capacity", C.c_int64), ("tuning", pop_tuning)]
 
 
-assert C.sizeof(pop_hparams) == 64 and C.sizeof(pop_config) == 48
+assert C.sizeof(pop_hparams) == 64 and C.sizeof(pop_config) == 72
 
 
 class PopError(RuntimeError):
@@ -91,6 +100,7 @@ def load_library():
         "pop_step_count": (i64, [vp]),
         "pop_buffer_count": (i64, [vp, i32]),
         "pop_sync": (C.c_int, [vp]),
+        "pop_set_option": (C.c_int, [vp, i32, i64]),
         "pop_destroy": (C.c_int, [vp]),
         "pop_last_error": (C.c_char_p, [vp]),
     }
@@ -101,13 +111,21 @@ def load_library():
     return lib
 
 
-def make_config(P, obs_dim, act_dim, hidden=(256, 256), batch=256, capacity=10000, algo=POP_ALGO_TD3):
+def make_config(P, obs_dim, act_dim, hidden=(256, 256), batch=256, capacity=10000, algo=POP_ALGO_TD3,
+                launch=POP_LAUNCH_AUTO, rows=None, rows_critic1=0, half_tiles=0):
+    """rows: None (the library chooses), one value for all three chains, or (target, critic, actor); launch,
+    rows_critic1, half_tiles: the fields of pop_tuning."""
     cfg = pop_config()
     cfg.algo, cfg.P, cfg.obs_dim, cfg.act_dim = algo, P, obs_dim, act_dim
     cfg.n_hidden = len(hidden)
     for i in range(4):
         cfg.hidden[i] = hidden[i] if i < len(hidden) else 0
     cfg.batch, cfg.capacity = batch, capacity
+    cfg.tuning.launch = launch
+    if rows is not None:
+        rt, rc, ra = (rows, rows, rows) if isinstance(rows, int) else rows
+        cfg.tuning.rows_target, cfg.tuning.rows_critic, cfg.tuning.rows_actor = rt, rc, ra
+    cfg.tuning.rows_critic1, cfg.tuning.half_tiles = rows_critic1, half_tiles
     return cfg
 
 
@@ -254,6 +272,10 @@ def pop_sync(ctx):
     return _check(load_library().pop_sync(ctx), ctx)
 
 
+def pop_set_option(ctx, key, value):
+    return _check(load_library().pop_set_option(ctx, int(key), int(value)), ctx)
+
+
 def pop_destroy(ctx):
     return _check(load_library().pop_destroy(ctx))
 
@@ -333,6 +355,9 @@ class Population:
         out = np.empty(shape, dtype=dt)
         pop_debug_get(self.ctx, DEBUG_CODES[what], out)
         return out
+
+    def set_option(self, key, value):
+        return pop_set_option(self.ctx, key, value)
 
     def step_count(self):
         return pop_step_count(self.ctx)

@@ -413,9 +413,8 @@ __device__ inline void thin_wide(const float* Xl, const float* V, int J, float* 
   for (int j0 = 0; j0 < J; j0 += kMaxAct) G::thin(Xl, V + j0 * kH, J - j0 < kMaxAct ? J - j0 : kMaxAct, outl + j0, tid, stride);
 }
 
-// Longest time a workgroup waits for another one of the same launch, in 10 ns ticks of the
-// constant-rate clock (50 ms; a healthy wait is a fraction of a millisecond).
-constexpr unsigned long long kWaitLimitTicks = 5000000ull;
+// The longest time a workgroup waits for another one of the same launch is d.wait_limit, in 10 ns ticks of the
+// constant-rate clock (50 ms unless the host sets another bound; a healthy wait is a fraction of a millisecond).
 
 // Bellman targets handed from a target workgroup to critic workgroups of the same launch
 // travel as one 64-bit word per row, (t + 1) << 32 | bits of y, written and read with
@@ -433,7 +432,7 @@ __device__ inline float await_y(const PopDev& d, size_t row, uint32_t t) {
   uint64_t word;
   while (((word = __hip_atomic_load(d.y_tagged + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != t + 1u) {
     __builtin_amdgcn_s_sleep(4);
-    if (wall_clock64() - t0 > kWaitLimitTicks) {
+    if (wall_clock64() - t0 > d.wait_limit) {
       atomicOr(d.fault, 1u);
       break;
     }
@@ -466,7 +465,7 @@ __device__ inline void wait_count(const PopDev& d, const uint32_t* count, uint32
   const uint64_t t0 = wall_clock64();
   while (__hip_atomic_load(count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
     __builtin_amdgcn_s_sleep(8);
-    if (wall_clock64() - t0 > kWaitLimitTicks) {
+    if (wall_clock64() - t0 > d.wait_limit) {
       atomicOr(d.fault, 2u);
       break;
     }

@@ -82,6 +82,7 @@ struct pop_ctx {
   uint64_t t;                    // update steps taken
   uint64_t gathered_t;           // step whose batch already sits in its half of the double buffer
   uint32_t step_launches;        // launches of the step kernel so far (alternates its hand-over counters)
+  bool handover_pending;         // a launch with waits between its workgroups was enqueued since the fault word was last read
   float* static_scratch;         // this device's copy of the static scratch array (pop_act_explore_noalloc)
   int device;                    // the device that was current at pop_create
   int fuse;                      // launch structure of a step, see POP_K_* in pop.h: 0 one launch per part, 1 target and
@@ -108,6 +109,21 @@ int fail(pop_ctx* ctx, int code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(ctx, POP_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
   } while (0)
 
+// Call after the stream has been synchronised: a wait between workgroups that ran out (chains.h) left bits in the
+// fault word.  Reported once, then cleared, so that the context can be used again after its state is restored.
+int check_fault(pop_ctx* ctx) {
+  if (!ctx->handover_pending) return POP_OK;
+  uint32_t fault = 0;
+  HIP_TRY(ctx, hipMemcpyAsync(&fault, ctx->d.fault, sizeof fault, hipMemcpyDeviceToHost, ctx->stream));
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  ctx->handover_pending = false;
+  if (!fault) return POP_OK;
+  HIP_TRY(ctx, hipMemsetAsync(ctx->d.fault, 0, sizeof fault, ctx->stream));
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  return fail(ctx, POP_EHIP, "a wait between workgroups of a fused launch ran into its time limit (fault bits %u: 1 = Bellman targets, "
+              "2 = a hand-over count): the results of that step and every later one are invalid", fault);
+}
+
 int check_config(const pop_config* c, pop_ctx* ctx) {
   if (!c) return fail(ctx, POP_EINVAL, "config is NULL");
   if (c->P < 1 || c->obs_dim < 1 || c->act_dim < 1 || c->batch < 1 || c->capacity < 1 || c->n_hidden < 1 ||
@@ -123,6 +139,14 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
   if (c->batch != 256) return fail(ctx, POP_EUNSUPPORTED, "batch must be 256");
   if (c->capacity > 0xFFFFFFFFll) return fail(ctx, POP_EUNSUPPORTED, "capacity must be below 2^32");
   if ((int64_t)c->P * c->batch > (1ll << 24)) return fail(ctx, POP_EUNSUPPORTED, "P * batch too large");
+  const pop_tuning& u = c->tuning;
+  auto rows_ok = [](int r, bool chain16) { return r == 0 || r == 32 || r == 64 || (chain16 && r == 16); };
+  if (u.launch < POP_LAUNCH_AUTO || u.launch > POP_LAUNCH_TAIL) return fail(ctx, POP_EINVAL, "tuning.launch %d is not a POP_LAUNCH_* value", u.launch);
+  if (!rows_ok(u.rows_target, true) || !rows_ok(u.rows_critic, false) || !rows_ok(u.rows_actor, true))
+    return fail(ctx, POP_EINVAL, "tuning.rows_*: 0, 32 or 64 (16 as well for the target and actor chains)");
+  if (u.rows_critic1 != 0 && u.rows_critic1 != 16 && u.rows_critic1 != u.rows_critic)
+    return fail(ctx, POP_EINVAL, "tuning.rows_critic1: 0, 16 or the value of rows_critic");
+  if (u.half_tiles < 0 || u.half_tiles > 2) return fail(ctx, POP_EINVAL, "tuning.half_tiles: 0 (choose), 1 (off) or 2 (on)");
   return POP_OK;
 }
 
@@ -135,7 +159,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // populations: those parts have only 8 P workgroups at 32 rows, well under the 256 CUs, and
   // their latency is what a step waits for; 16-row tiles halve the matrix time of every
   // product by spreading it over twice the CUs.  Else 32.  (64-row chains for all three parts, half the weight
-  // traffic per row, exist as well -- POP_ROWS=64 -- and were the choice from 128 agents on until the 32-row
+  // traffic per row, exist as well -- tuning.rows_* = 64 -- and were the choice from 128 agents on until the 32-row
   // products learnt to issue their loads between the MFMAs: 1297 against 1278 us/step at P = 256, equal at 128.)
   const int cls = (int64_t)c.P * (c.batch / 16) <= 256 ? 0 : 1;
   d.rows_t = d.rows_a = cls == 0 ? 16 : 32;
@@ -156,8 +180,8 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // workgroups of its own, 32 rows each: 16 P + 8 P workgroups as before, but the tail after the targets is a
   // 16-row critic chain or a 32-row backward pass instead of a 64-row backward pass (88 against 92 us/step at P = 10).
   d.rows_c1 = 0;
-  const char* fuse_env = getenv("POP_FUSE");
-  if (c.algo == POP_ALGO_TD3 && cls == 0 && (!fuse_env || atoi(fuse_env) == 1)) {
+  const pop_tuning& u = c.tuning;
+  if (c.algo == POP_ALGO_TD3 && cls == 0 && (u.launch == POP_LAUNCH_AUTO || u.launch == POP_LAUNCH_TARGET_CRITIC)) {
     if (d.rows_c == 64) { d.rows_c = 32; d.rows_c1 = 16; }
     // 11 and 12 agents (20 P <= 256 < 24 P): the same with 64-row workgroups for critic 2 -- 93 against 98 us/step
     else if (b16 + b16 / 2 > 256 && b16 + b16 / 4 <= 256) { d.rows_c = 64; d.rows_c1 = 16; }
@@ -168,16 +192,12 @@ void fill_dims(const pop_config& c, PopDev& d) {
     if ((int64_t)c.P * (c.batch / 64) * 2 <= 256) d.rows_c = 64;
     if ((int64_t)c.P * (c.batch / 16) <= 512) d.rows_t = 16;
   }
-  if (const char* env = getenv("POP_ROWS")) {       // 16, 32 or 64, or "target,critic,actor": override (measurements, tests)
-    const int v = atoi(env);
-    int rt = 0, rc = 0, ra = 0;
-    auto ok = [](int r, bool chain16) { return r == 32 || r == 64 || (chain16 && r == 16); };
-    if (sscanf(env, "%d,%d,%d", &rt, &rc, &ra) == 3) {   // "target,critic,actor"
-      if (ok(rt, true) && ok(rc, false) && ok(ra, true)) { d.rows_t = rt; d.rows_c = rc; d.rows_a = ra; d.rows_c1 = 0; }
-    } else if (!strcmp(env, "16+") || !strcmp(env, "16++")) {   // the classes of 9 .. 12 agents, whatever the population
-      if (c.algo == POP_ALGO_TD3) { d.rows_t = d.rows_a = d.rows_c1 = 16; d.rows_c = env[3] ? 64 : 32; }
-    } else if (v == 16) { d.rows_t = d.rows_a = 16; d.rows_c = 64; d.rows_c1 = 0; }
-    else if (v == 32 || v == 64) { d.rows_t = d.rows_c = d.rows_a = v; d.rows_c1 = 0; }
+  // the caller's choices (measurements, tests); naming any chain's rows drops the critic-1 class unless it is named too
+  if (u.rows_target || u.rows_critic || u.rows_actor || u.rows_critic1) {
+    if (u.rows_target) d.rows_t = u.rows_target;
+    if (u.rows_critic) d.rows_c = u.rows_critic;
+    if (u.rows_actor) d.rows_a = u.rows_actor;
+    d.rows_c1 = u.rows_critic1 == 16 ? 16 : 0;
   }
   // Wide inputs (SAC only; kernels with a pipelined first layer): 32-row chains -- with weights of
   // 2 MB per agent, 16-row workgroups re-read them from L2 often enough to be bound by that -- except
@@ -189,9 +209,8 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // these shapes) some CUs hold two tiles and others one, and the launch lasts as long as the former; tiles of
   // half the width (37 workgroups per network) spread evenly while all of them are resident at three per CU, i.e.
   // up to 10 agents: 73 -> 69 us/step at P = 2, 81 -> 79 at P = 8, 87.8 -> 85.6 at P = 10 (93.5 -> 94.3 at P = 12).
-  // The sums over the batch then come in two halves, so the launch structures that POP_FUSE selects for
-  // comparisons bit for bit keep the full tiles.  POP_HALF_TILES=0/1 overrides (measurements).
-  d.half_tiles = (getenv("POP_HALF_TILES") ? atoi(getenv("POP_HALF_TILES")) != 0 : 2 * (int64_t)c.P * 37 <= 3 * 256) && !getenv("POP_FUSE");
+  // The sums over the batch then come in two halves, so comparisons of launch structures bit for bit switch them off.
+  d.half_tiles = u.half_tiles ? u.half_tiles == 2 : 2 * (int64_t)c.P * 37 <= 3 * 256;
   d.actor = make_layout(d.O, c.algo == POP_ALGO_SAC ? 2 * d.A : d.A);   // SAC: mean and log-std per action
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
@@ -349,6 +368,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   ctx->t = 0;
   ctx->gathered_t = ~0ull;
   ctx->step_launches = 0;
+  ctx->handover_pending = false;
   // One launch per step (parts handing over between workgroups), target and critic chains in one launch and the
   // rest in launches of their own, or one launch per part -- by measurement over P = 2 .. 128 (us/step, 64-row
   // critic chains up to P = 16; single launch / target+critic fused / per part): 78 / 83 / - at P = 2, 84 / 85 / -
@@ -376,16 +396,16 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   // 32-row critic chains up to P = 8: 142 against 157 us/step there); measured at P = 32, fusing them loses 4 %
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = (d.rows_t == 16 && d.rows_c == 32 && tc_blocks <= kCUs) ? 1 : 0;
   if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 1;   // target and critic chains together; the critic's weight step is a reduction of its own
-  if (const char* env = getenv("POP_FUSE")) { const int v = atoi(env); if (v >= 0 && v <= 3) ctx->fuse = v; }
+  if (cfg->tuning.launch != POP_LAUNCH_AUTO) ctx->fuse = cfg->tuning.launch - POP_LAUNCH_PER_PART;   // 0 .. 3
   if (d.D > kMaxIn) ctx->fuse = 0;                  // wide inputs: the chains exist as separate launches only
   if (cfg->algo == POP_ALGO_TD3_SHARED && ctx->fuse > 1) ctx->fuse = 1;
-  if (d.rows_c1 != d.rows_c && ctx->fuse != 1) {
+  if (d.rows_c1 != d.rows_c && (ctx->fuse != 1 || cfg->algo != POP_ALGO_TD3 || d.rows_t != 16 || d.rows_c1 != 16)) {
     delete ctx;
-    return fail(nullptr, POP_EINVAL, "POP_ROWS=16+ and 16++ need POP_FUSE=1 (target and critic chains in one launch)");
+    return fail(nullptr, POP_EINVAL, "tuning.rows_critic1 = 16 needs TD3, rows_target = 16 and POP_LAUNCH_TARGET_CRITIC");
   }
   if (ctx->fuse >= 2 && d.rows_t == 16 && d.rows_c != 64) {   // the single launch exists for the (16, 64, 16) small class only
     delete ctx;
-    return fail(nullptr, POP_EINVAL, "POP_FUSE=2 and 3 need POP_ROWS=16 (64-row critic chains) for a population this small");
+    return fail(nullptr, POP_EINVAL, "POP_LAUNCH_SINGLE and POP_LAUNCH_TAIL need rows (16, 64, 16) for a population this small");
   }
   ctx->hp.assign(hp, hp + cfg->P);
   if (cfg->algo == POP_ALGO_SAC)
@@ -414,6 +434,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.cpart = (float*)(w + L.cpart); d.apart = (float*)(w + L.apart); d.losses = (float*)(w + L.losses);
   d.y_tagged = (uint64_t*)(w + L.y_tagged); d.done_c = (uint32_t*)(w + L.done_c); d.done_wc = (uint32_t*)(w + L.done_wc); d.done_a = (uint32_t*)(w + L.done_a);
   d.fault = (uint32_t*)(w + L.fault);
+  d.wait_limit = 5000000ull;                           // 50 ms
   d.log_alpha = (float*)(w + L.log_alpha);
   d.spart = (float*)(w + L.spart); d.sloss = (float*)(w + L.sloss);
   ctx->d = d;
@@ -517,7 +538,8 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
     return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
   bool any_actor = false;
   for (int a = 0; a < d.P && !any_actor; ++a) any_actor = (t % (uint32_t)ctx->hp[a].policy_delay) == 0;
-  if (d.algo == POP_ALGO_SAC) {                       // critic chain and tiles are the TD3 ones; POP_FUSE = 0: one launch
+  if (ctx->fuse != 0) ctx->handover_pending = true;   // every fused launch has waits between its workgroups
+  if (d.algo == POP_ALGO_SAC) {                       // critic chain and tiles are the TD3 ones; fuse = 0: one launch
                                                       // per part, else target and critic chains in one launch
     if (ctx->fuse != 0) {
       if (!run(POP_K_TARGET_CRITIC, launch_sac_target_critic)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
@@ -557,9 +579,10 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
   }
   if (ctx->fuse == 2) {
     tick(POP_K_STEP, 0);
-    e = launch_step(d, t, ctx->step_launches++, 1, any_actor ? 1 : 0, has_next ? 1 : 0, s);
+    e = launch_step(d, t, ctx->step_launches, 1, any_actor ? 1 : 0, has_next ? 1 : 0, s);
     tick(POP_K_STEP, 1);
     if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    ctx->step_launches++;                            // only a launch that ran has cleared the other half of the counters
     if (has_next) ctx->gathered_t = ctx->t + 1;
     ctx->t++;
     return POP_OK;
@@ -568,9 +591,10 @@ int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
     if (!run(POP_K_TARGET_CRITIC, launch_target_critic)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
     if (any_actor && ctx->fuse == 3) {               // the rest of the step in one launch: the actor's own forward pass
       tick(POP_K_STEP_TAIL, 0);                      // runs beside the critic weight gradients
-      e = launch_step(d, t, ctx->step_launches++, 0, 1, has_next ? 1 : 0, s);
+      e = launch_step(d, t, ctx->step_launches, 0, 1, has_next ? 1 : 0, s);
       tick(POP_K_STEP_TAIL, 1);
       if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+      ctx->step_launches++;
       if (has_next) ctx->gathered_t = ctx->t + 1;
       ctx->t++;
       return POP_OK;
@@ -653,6 +677,7 @@ int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launche
     }
   }
   for (auto& e : ev) (void)hipEventDestroy(e);
+  if (rc == POP_OK) rc = check_fault(ctx);
   return rc;
 }
 
@@ -684,7 +709,7 @@ int act_impl(pop_ctx* ctx, const float* obs, int32_t n, float* act_out, int32_t 
                                   (size_t)k * d.A * 4, d.P, hipMemcpyDeviceToHost, s));
     HIP_TRY(ctx, hipStreamSynchronize(s));
   }
-  return POP_OK;
+  return check_fault(ctx);
 }
 }  // namespace
 
@@ -738,7 +763,11 @@ int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, i
     if (!out || out_len < 1) return fail(ctx, POP_EINVAL, "out is NULL or too short");
     const float* src = ctx->d.log_alpha + (size_t)(which - POP_LOG_ALPHA) * ctx->d.P + agent;
     HIP_TRY(ctx, hipMemcpyAsync(out, src, 4, on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, ctx->stream));
-    if (!on_device) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (!on_device) {
+      HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+      const int rc = check_fault(ctx);
+      if (rc != POP_OK) return rc;
+    }
     return 1;
   }
   if (which < 0 || which > POP_GRAD_CRITIC2) return fail(ctx, POP_EINVAL, "bad tensor code %d", which);
@@ -751,7 +780,11 @@ int64_t pop_get_params(pop_ctx* ctx, int32_t agent, int32_t which, float* out, i
   const char* src = ctx->ws + region + (int64_t)agent * ctx->d.agent_sz * 4 + off;
   HIP_TRY(ctx, hipMemcpyAsync(out, src, (size_t)L->size * 4, on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
                               ctx->stream));
-  if (!on_device) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  if (!on_device) {
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    const int rc = check_fault(ctx);
+    if (rc != POP_OK) return rc;
+  }
   return L->size;
 }
 
@@ -810,11 +843,16 @@ int64_t pop_debug_get(pop_ctx* ctx, int32_t what, void* out, int64_t out_bytes, 
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     float* o = (float*)out;
     for (int a = 0; a < d.P; ++a) { o[2 * a] = raw[4 * a] + raw[4 * a + 1]; o[2 * a + 1] = raw[4 * a + 2]; }
-    return bytes;
+    const int rc = check_fault(ctx);
+    return rc != POP_OK ? rc : bytes;
   }
   HIP_TRY(ctx, hipMemcpyAsync(out, src, (size_t)bytes, on_device ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost,
                               ctx->stream));
-  if (!on_device) HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  if (!on_device) {
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    const int rc = check_fault(ctx);
+    if (rc != POP_OK) return rc;
+  }
   return bytes;
 }
 
@@ -901,12 +939,21 @@ int pop_copy_agent(pop_ctx* ctx, int32_t dst, int32_t src, int32_t with_buffer) 
 
 int pop_sync(pop_ctx* ctx) {
   if (!ctx) return POP_EINVAL;
-  uint32_t fault = 0;
-  HIP_TRY(ctx, hipMemcpyAsync(&fault, ctx->d.fault, sizeof fault, hipMemcpyDeviceToHost, ctx->stream));
   HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   HIP_TRY(ctx, hipGetLastError());
-  if (fault) return fail(ctx, POP_EHIP, "a bounded wait inside a kernel ran out (fault bits %u): results are invalid", fault);
-  return POP_OK;
+  return check_fault(ctx);
+}
+
+int pop_set_option(pop_ctx* ctx, int32_t key, int64_t value) {
+  if (!ctx) return POP_EINVAL;
+  switch (key) {
+    case POP_OPT_WAIT_LIMIT_TICKS:
+      if (value < 1 || value > 1000000000ll) return fail(ctx, POP_EINVAL, "wait limit must be 1 .. 10^9 ticks of 10 ns");
+      ctx->d.wait_limit = (unsigned long long)value;
+      return POP_OK;
+    default:
+      return fail(ctx, POP_EINVAL, "unknown option %d", key);
+  }
 }
 
 int pop_destroy(pop_ctx* ctx) {

@@ -24,9 +24,10 @@ def rel_l2(a, b):
 
 
 def make_pair(config_id=0, P=None, capacity=None, fill=None, batch=None, hps=None, agents=None, oracle=True,
-              obs_dim=None, act_dim=None):
+              obs_dim=None, act_dim=None, **tuning):
     """HIP population + oracle population fed with the same hyperparameters and
-    transitions.  `agents` selects which population members the oracle holds."""
+    transitions.  `agents` selects which population members the oracle holds; `tuning`: launch structure, rows
+    per workgroup and tile width (see paper_2206_08888_amd.make_config)."""
     cfgd = workloads.CONFIGS[config_id]
     P = cfgd["P"] if P is None else P
     capacity = cfgd["capacity"] if capacity is None else capacity
@@ -35,7 +36,7 @@ def make_pair(config_id=0, P=None, capacity=None, fill=None, batch=None, hps=Non
     O = cfgd["obs_dim"] if obs_dim is None else obs_dim
     A = cfgd["act_dim"] if act_dim is None else act_dim
     hps = workloads.hparams(config_id, P) if hps is None else hps
-    cfg = pp.make_config(P, O, A, cfgd["hidden"], batch, capacity)
+    cfg = pp.make_config(P, O, A, cfgd["hidden"], batch, capacity, **tuning)
     gpu = pp.Population(cfg, hps)
     agents = list(range(P)) if agents is None else list(agents)
     orc = None
@@ -51,7 +52,7 @@ def make_pair(config_id=0, P=None, capacity=None, fill=None, batch=None, hps=Non
     return gpu, orc, agents
 
 
-def make_full_size_pair(config_id, verify_agents):
+def make_full_size_pair(config_id, verify_agents, **tuning):
     """HIP population of a config at its full size and an oracle population holding
     only `verify_agents`.  The verified agents get host-generated transitions
     (identical bytes on both sides); the other agents' buffers are filled on the
@@ -61,7 +62,7 @@ def make_full_size_pair(config_id, verify_agents):
     cfgd = workloads.CONFIGS[config_id]
     P, O, A, cap, B = cfgd["P"], cfgd["obs_dim"], cfgd["act_dim"], cfgd["capacity"], cfgd["batch"]
     hps = workloads.hparams(config_id)
-    cfg = pp.make_config(P, O, A, cfgd["hidden"], B, cap)
+    cfg = pp.make_config(P, O, A, cfgd["hidden"], B, cap, **tuning)
     gpu = pp.Population(cfg, hps)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(workloads.DATA_SEED + 77 * config_id)
@@ -94,51 +95,6 @@ def force_state(gpu, orc, pairs):
     for i, j in pairs:
         for which in STATE12:
             gpu.set_params(i, which, orc.get_params(j, which))
-
-
-def forced_step_errors(gpu, orc, pairs):
-    """After one step from a common state: worst rel-L2 of (parameters and targets, second
-    moments, first moments) over the given agents."""
-    def worst(names):
-        w = 0.0
-        for i, j in pairs:
-            for which in names:
-                ref = orc.get_params(j, which)
-                if ref.any():
-                    w = max(w, rel_l2(gpu.get_params(i, which), ref))
-        return w
-    return worst(PARAMS6), worst(MOM_V), worst(MOM_M)
-
-
-class ForcedStepStats:
-    """Tolerances of a forced single step (GPU started from the oracle's state):
-      parameters and targets  <= 1e-4 always (the one-step tolerance);
-      second moments          <= 1e-3 always;
-      first moments           <= 1e-4, except on steps where a ReLU pre-activation lies
-                              within fp32 rounding error of zero and the two sides resolve
-                              it differently: one (sample, unit) then enters or leaves the
-                              gradient, which moves m by up to a few 1e-3 relative while
-                              the parameters move by < 1e-5.  Such steps must stay rare
-                              (<= 10 % of the steps) and bounded (<= 5e-2)."""
-
-    def __init__(self):
-        self.steps = 0
-        self.flips = 0
-        self.worst_p = self.worst_v = self.worst_m = 0.0
-
-    def add(self, ep, ev, em, tag):
-        self.steps += 1
-        self.worst_p, self.worst_v, self.worst_m = max(self.worst_p, ep), max(self.worst_v, ev), max(self.worst_m, em)
-        assert ep <= 1e-4, (tag, "parameters", ep)
-        assert ev <= 1e-3, (tag, "second moments", ev)
-        assert em <= 5e-2, (tag, "first moments", em)
-        if em > 1e-4:
-            self.flips += 1
-
-    def finish(self):
-        assert self.flips <= max(1, self.steps // 10), (self.flips, self.steps)
-        return ("%d forced steps: parameters %.2e, v %.2e, m %.2e worst rel-L2; %d step(s) with a ReLU tie resolved "
-                "differently" % (self.steps, self.worst_p, self.worst_v, self.worst_m, self.flips))
 
 
 # ------------------------------------------------------------------------------------------------------------

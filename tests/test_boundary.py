@@ -32,9 +32,42 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, n), n
 
 
-def test_struct_sizes_match_the_header(lib):
-    assert C.sizeof(pp.pop_hparams) == 64
-    assert C.sizeof(pp.pop_config) == 48
+def test_struct_sizes_match_the_header(lib, tmp_path):
+    """The ctypes structures against the header itself: a C program compiled from include/pop.h prints its sizes
+    and the offsets of the fields that follow padding."""
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "pop.h"\n'
+                   'int main(void) { printf("%zu %zu %zu %zu %zu\\n", sizeof(pop_hparams), sizeof(pop_config), sizeof(pop_tuning), '
+                   'offsetof(pop_config, capacity), offsetof(pop_config, tuning)); return 0; }\n')
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [C.sizeof(pp.pop_hparams), C.sizeof(pp.pop_config), C.sizeof(pp.pop_tuning),
+                   pp.pop_config.capacity.offset, pp.pop_config.tuning.offset] == [64, 72, 24, 40, 48]
+
+
+def test_bad_tuning_values_are_refused_before_any_gpu_work(lib):
+    for kw in (dict(launch=7), dict(launch=-1), dict(rows=(16, 16, 16)), dict(rows=48), dict(half_tiles=3), dict(rows_critic1=32)):
+        with pytest.raises(pp.PopError) as e:
+            pp.pop_workspace_bytes(pp.make_config(2, 17, 6, (256, 256), 256, 100, **kw))
+        assert e.value.code == pp.POP_EINVAL and "tuning" in str(e.value), kw
+    # the rows per workgroup size the partial-sum areas of the workspace
+    a = pp.pop_workspace_bytes(pp.make_config(20, 17, 6, (256, 256), 256, 100, rows=64))
+    b = pp.pop_workspace_bytes(pp.make_config(20, 17, 6, (256, 256), 256, 100, rows=32))
+    assert a < b
+
+
+def test_nothing_is_read_from_the_environment(lib, monkeypatch):
+    """The launch structure and tile geometry come from pop_config.tuning alone."""
+    cfg = pp.make_config(20, 17, 6, (256, 256), 256, 100)
+    plain = pp.pop_workspace_bytes(cfg)
+    for name, value in (("POP_ROWS", "64"), ("POP_FUSE", "0"), ("POP_HALF_TILES", "1")):
+        monkeypatch.setenv(name, value)
+    assert pp.pop_workspace_bytes(cfg) == plain
+    text = "".join(open(os.path.join(ROOT, "paper_2206_08888_amd", "csrc", f)).read()
+                   for f in os.listdir(os.path.join(ROOT, "paper_2206_08888_amd", "csrc")))
+    assert "getenv" not in text
 
 
 def test_workspace_size_and_net_sizes(lib):

@@ -22,14 +22,14 @@ def _lib():
     ensure_built()
 
 
-def _pair(algo, P, O, A, capacity, fill=None, hps=None):
+def _pair(algo, P, O, A, capacity, fill=None, hps=None, **tuning):
     fill = capacity if fill is None else fill
     hps = workloads.hparams(2, P) if hps is None else hps
     if algo == "sac":
         for hp in hps:
             hp["target_entropy"] = -float(A)
     code = {"td3": pp.POP_ALGO_TD3, "sac": pp.POP_ALGO_SAC, "shared": pp.POP_ALGO_TD3_SHARED}[algo]
-    gpu = pp.Population(pp.make_config(P, O, A, (256, 256), 256, capacity, algo=code), hps)
+    gpu = pp.Population(pp.make_config(P, O, A, (256, 256), 256, capacity, algo=code, **tuning), hps)
     mod = {"td3": oracle_td3, "sac": oracle_sac, "shared": oracle_shared}[algo]
     orc = mod.Population(hps, O, A, [256, 256], 256, capacity)
     for i in range(P):
@@ -123,20 +123,66 @@ def test_unsupported_shapes_are_refused_with_a_message():
         assert e.value.code == pp.POP_EUNSUPPORTED and "must be <=" in str(e.value)
 
 
-def test_row_classes_without_a_kernel_are_refused_at_launch(monkeypatch):
-    """POP_ROWS can ask for (target, critic, actor) rows per workgroup that the fused launches have no kernel for:
+def test_row_classes_without_a_kernel_are_refused_at_launch():
+    """tuning.rows_* can ask for (target, critic, actor) rows per workgroup that the fused launches have no kernel for:
     the launch is refused with an error, nothing runs; as separate launches the same rows work and match."""
-    monkeypatch.setenv("POP_ROWS", "32,64,32")
-    monkeypatch.setenv("POP_FUSE", "2")
-    gpu, orc = _pair("td3", 3, 17, 6, 600)
+    gpu, orc = _pair("td3", 3, 17, 6, 600, rows=(32, 64, 32), launch=pp.POP_LAUNCH_SINGLE)
     with pytest.raises(pp.PopError) as e:
         gpu.update(1)
     assert e.value.code == pp.POP_EHIP
     gpu.close()
-    monkeypatch.setenv("POP_FUSE", "0")
-    gpu, orc = _pair("td3", 3, 17, 6, 600)
+    gpu, orc = _pair("td3", 3, 17, 6, 600, rows=(32, 64, 32), launch=pp.POP_LAUNCH_PER_PART)
     gpu.update(2); orc.update(2)
     assert _worst(gpu, orc, 3, PARAMS6) <= 1e-4
     check_tensors_all(gpu, orc, [(i, i) for i in range(3)], PARAMS6, 1e-4, "separate launches", steps=2)
     gpu.close()
 
+
+def test_critic1_inside_the_target_workgroups_needs_the_fused_launch():
+    with pytest.raises(pp.PopError) as e:                   # TD3, target and critic chains in one launch only
+        _pair("td3", 3, 17, 6, 300, rows=(16, 32, 16), rows_critic1=16, launch=pp.POP_LAUNCH_PER_PART)
+    assert e.value.code == pp.POP_EINVAL
+
+
+@pytest.mark.parametrize("launch,rows", [(pp.POP_LAUNCH_TARGET_CRITIC, None), (pp.POP_LAUNCH_SINGLE, (16, 64, 16))])
+def test_a_wait_between_workgroups_that_runs_out_is_reported_once_and_the_context_recovers(launch, rows):
+    """Workgroups of a fused launch wait for results of other workgroups of the same launch, each wait bounded by
+    the constant-rate clock.  With the bound set to one tick (10 ns) from the host every such wait gives up at
+    once: the kernels still run to their end (with stale operands), the step's results are invalid, and the next
+    call that synchronises says so -- once.  After the state is restored the context works as before."""
+    hps = workloads.hparams(2, 4)
+    def make():
+        gpu = pp.Population(pp.make_config(4, 17, 6, (256, 256), 256, 800, launch=launch, rows=rows, half_tiles=1), hps)
+        for i in range(4):
+            gpu.insert(i, **workloads.transitions(2, i, 800))
+        return gpu
+    gpu, twin = make(), make()
+    gpu.update(2); twin.update(2)
+    saved = {(i, w): gpu.get_params(i, w) for i in range(4) for w in STATE12}
+    gpu.set_option(pp.POP_OPT_WAIT_LIMIT_TICKS, 1)
+    gpu.update(1)
+    with pytest.raises(pp.PopError) as e:
+        gpu.sync()
+    assert e.value.code == pp.POP_EHIP and "time limit" in str(e.value)
+    gpu.sync()                                              # reported once, then cleared
+    gpu.update(1)                                           # still one tick: the other reporting path
+    with pytest.raises(pp.PopError) as e:
+        gpu.get_params(0, "actor")
+    assert e.value.code == pp.POP_EHIP
+    gpu.get_params(0, "actor")
+    with pytest.raises(pp.PopError):
+        gpu.set_option(pp.POP_OPT_WAIT_LIMIT_TICKS, 0)
+    with pytest.raises(pp.PopError):
+        gpu.set_option(99, 1)
+    gpu.set_option(pp.POP_OPT_WAIT_LIMIT_TICKS, 5_000_000)
+    gpu.close()
+    # a fresh context (the step counter of the faulted one has moved on) with the saved state continues like the twin
+    again = make()
+    again.update(2)
+    for (i, w), v in saved.items():
+        assert np.array_equal(again.get_params(i, w), v)
+    again.update(3); twin.update(3)
+    for i in range(4):
+        for w in STATE12:
+            assert np.array_equal(again.get_params(i, w), twin.get_params(i, w)), (i, w)
+    again.close(); twin.close()

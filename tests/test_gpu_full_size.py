@@ -69,16 +69,16 @@ def test_sampled_agents_match_oracle_at_full_size(config_id):
     gpu.close()
 
 
-def test_single_launch_step_equals_separate_launches_bit_for_bit_at_p80(monkeypatch):
+def test_single_launch_step_equals_separate_launches_bit_for_bit_at_p80():
     """Config 2 at full size: the update step as ONE launch (results passed between
     workgroups inside the launch) against one launch per part, 60 steps.  The arithmetic
     is the same, so a single stale or early read anywhere in the hand-overs would show as a
     bit difference in some parameter or moment of some agent."""
     agents = (0, 7, 33, 64, 79)
     states = []
-    for fuse in ("2", "0"):
-        monkeypatch.setenv("POP_FUSE", fuse)
-        gpu, _ = make_full_size_pair(2, [])
+    import paper_2206_08888_amd as pp
+    for launch in (pp.POP_LAUNCH_SINGLE, pp.POP_LAUNCH_PER_PART):
+        gpu, _ = make_full_size_pair(2, [], launch=launch)
         gpu.update(60)
         gpu.sync()
         assert gpu.step_count() == 60

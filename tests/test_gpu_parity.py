@@ -282,7 +282,7 @@ def test_set_params_round_trips_and_rejects_bad_arguments():
     gpu.close()
 
 
-def test_launch_structures_agree_bit_for_bit(monkeypatch):
+def test_launch_structures_agree_bit_for_bit():
     """One launch per step (parts hand results on inside the launch: tagged words for the
     Bellman targets, counters for activation tiles and updated critics), target + critic
     chains fused with and without the rest of the step fused, and one launch per part: identical arithmetic, so every
@@ -293,20 +293,19 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
     for i, hp in enumerate(hps):
         hp["policy_delay"] = (2, 1, 3)[i % 3]
     states = []
-    monkeypatch.setenv("POP_ROWS", "16")                # the row class all four structures exist for (16, 64, 16)
-    for fuse in ("2", "3", "1", "0"):
-        monkeypatch.setenv("POP_FUSE", fuse)
-        gpu, _, _ = make_pair(2, P=11, capacity=3000, hps=hps, oracle=False)
+    for launch in (pp.POP_LAUNCH_SINGLE, pp.POP_LAUNCH_TAIL, pp.POP_LAUNCH_TARGET_CRITIC, pp.POP_LAUNCH_PER_PART):
+        # rows (16, 64, 16): the class all four structures exist for; full-width tiles in all of them
+        gpu, _, _ = make_pair(2, P=11, capacity=3000, hps=hps, oracle=False, launch=launch, rows=(16, 64, 16), half_tiles=1)
         gpu.update(7)
         ms, cnt = gpu.update_timed(6)
         assert cnt["gather"] == 1
-        if fuse == "2":
+        if launch == pp.POP_LAUNCH_SINGLE:
             assert cnt["step"] == 6 and sum(cnt.values()) == 7
         else:
             assert cnt["step"] == 0
-            if fuse == "3":
+            if launch == pp.POP_LAUNCH_TAIL:
                 assert cnt["target_critic"] == 6 and cnt["step_tail"] == 6 and sum(cnt.values()) == 13
-            elif fuse == "1":
+            elif launch == pp.POP_LAUNCH_TARGET_CRITIC:
                 assert cnt["target_critic"] == cnt["wgrad_critic"] == cnt["actor"] == cnt["wgrad_actor"] == 6
                 assert sum(cnt.values()) == 25
             else:
@@ -323,14 +322,12 @@ def test_launch_structures_agree_bit_for_bit(monkeypatch):
 
 @pytest.mark.parametrize("P,launches", [(8, {"target_critic": 3, "wgrad_critic": 3}), (9, {"target_critic": 3, "wgrad_critic": 3}),
                                         (12, {"target_critic": 3, "wgrad_critic": 3}), (14, {"target": 3, "critic": 3, "wgrad_critic": 3})])
-def test_small_populations_with_32_row_critic_chains_match_oracle(P, launches, monkeypatch):
+def test_small_populations_with_32_row_critic_chains_match_oracle(P, launches):
     """Up to 8 agents the critic chains take 32 rows beside the 16-row target chains of the same launch; with 9
     and 10 the target workgroups run critic 1 for their own rows and only critic 2 has 32-row workgroups (64-row
     ones with 11 and 12 agents); from 13 to 16 agents the two chains are launches of their own.  Both against the oracle over three steps with mixed
     policy delays, in the launch structure the library picks by itself; a single launch per step is refused for
     these row classes."""
-    monkeypatch.delenv("POP_FUSE", raising=False)
-    monkeypatch.delenv("POP_ROWS", raising=False)
     hps = workloads.hparams(2, P)
     for i, hp in enumerate(hps):
         hp["policy_delay"] = (2, 1, 3)[i % 3]
@@ -342,27 +339,25 @@ def test_small_populations_with_32_row_critic_chains_match_oracle(P, launches, m
     orc.update(3)
     _compare_state(gpu, orc, range(P), 1e-4, "P = %d, 3 steps" % P, steps=3)
     gpu.close()
-    monkeypatch.setenv("POP_FUSE", "2")
     if P == 9:                                          # falls back to 64-row critic chains, which the single launch has
-        make_pair(2, P=P, capacity=1500, hps=hps, oracle=False)[0].close()
+        make_pair(2, P=P, capacity=1500, hps=hps, oracle=False, launch=pp.POP_LAUNCH_SINGLE)[0].close()
         return
     with pytest.raises(pp.PopError) as e:
-        make_pair(2, P=P, capacity=1500, hps=hps, oracle=False)
+        make_pair(2, P=P, capacity=1500, hps=hps, oracle=False, launch=pp.POP_LAUNCH_SINGLE)
     assert e.value.code == pp.POP_EINVAL
 
 
-def test_sixty_four_row_chains_match_oracle_and_each_other(monkeypatch):
+def test_sixty_four_row_chains_match_oracle_and_each_other():
     """No population gets 64-row target and actor chains by default any more (the 32-row ones overtook them);
-    POP_ROWS=64 still selects them.  P = 5 with mixed delays, 5 steps: against the oracle, and one launch per step
-    against one launch per part bit for bit."""
+    tuning.rows_* = 64 still selects them.  P = 5 with mixed delays, 5 steps: against the oracle, and one launch per step
+    against one launch per part bit for bit (full-width tiles in all of them)."""
     hps = workloads.hparams(2, 5)
     for i, hp in enumerate(hps):
         hp["policy_delay"] = (2, 1, 3)[i % 3]
-    monkeypatch.setenv("POP_ROWS", "64")
     states = []
-    for fuse in ("1", "2", "0"):
-        monkeypatch.setenv("POP_FUSE", fuse)
-        gpu, orc, _ = make_pair(2, P=5, capacity=2000, hps=hps, oracle=(fuse == "1"))
+    for launch in (pp.POP_LAUNCH_TARGET_CRITIC, pp.POP_LAUNCH_SINGLE, pp.POP_LAUNCH_PER_PART):
+        gpu, orc, _ = make_pair(2, P=5, capacity=2000, hps=hps, oracle=(launch == pp.POP_LAUNCH_TARGET_CRITIC),
+                                launch=launch, rows=64, half_tiles=1)
         gpu.update(5)
         if orc is not None:
             orc.update(5)
@@ -373,6 +368,27 @@ def test_sixty_four_row_chains_match_oracle_and_each_other(monkeypatch):
     for other in states[1:]:
         for key in states[0]:
             assert np.array_equal(states[0][key], other[key]), key
+
+
+def test_tile_width_is_independent_of_the_launch_structure():
+    """Half-width weight-gradient tiles (the default up to 10 agents) sum the batch in two halves: results differ from
+    full-width tiles in the last bits only, whichever launch structure runs them, and do not depend on anything but
+    the tuning field."""
+    hps = workloads.hparams(2, 4)
+    out = {}
+    for half in (0, 1, 2):
+        for launch in (pp.POP_LAUNCH_AUTO, pp.POP_LAUNCH_PER_PART):
+            gpu, _, _ = make_pair(2, P=4, capacity=1200, hps=hps, oracle=False, launch=launch, rows=(16, 32, 16), half_tiles=half)
+            gpu.update(3)
+            out[half, launch] = {(i, w): gpu.get_params(i, w) for i in range(4) for w in STATE12}
+            gpu.close()
+    for half in (0, 1, 2):                                  # same tile width: launch structures agree bit for bit
+        a, b = out[half, pp.POP_LAUNCH_AUTO], out[half, pp.POP_LAUNCH_PER_PART]
+        assert all(np.array_equal(a[k], b[k]) for k in a)
+    a, b, c = out[0, pp.POP_LAUNCH_AUTO], out[2, pp.POP_LAUNCH_AUTO], out[1, pp.POP_LAUNCH_AUTO]
+    assert all(np.array_equal(a[k], b[k]) for k in a)       # "choose" means on at P = 4
+    assert any(not np.array_equal(a[k], c[k]) for k in a)   # and full-width tiles differ ...
+    assert max(rel_l2(a[k], c[k]) for k in a if c[k].any()) <= 1e-5   # ... in rounding only
 
 
 def test_copy_agent_and_set_hparams_follow_the_oracle():

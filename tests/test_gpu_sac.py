@@ -33,11 +33,11 @@ def sac_hparams(P, config_id=2, act_dim=6):
     return hps
 
 
-def make_sac_pair(P=2, capacity=2000, oracle=True, hps=None, agents=None, obs_dim=17, act_dim=6):
+def make_sac_pair(P=2, capacity=2000, oracle=True, hps=None, agents=None, obs_dim=17, act_dim=6, **tuning):
     """Buffers hold the synthetic transitions of config 2 (HalfCheetah shapes), of config 3 for the Humanoid
     shapes, else of config 2's stream drawn at the given shapes."""
     hps = sac_hparams(P, act_dim=act_dim) if hps is None else hps
-    cfg = pp.make_config(P, obs_dim, act_dim, (256, 256), 256, capacity, algo=pp.POP_ALGO_SAC)
+    cfg = pp.make_config(P, obs_dim, act_dim, (256, 256), 256, capacity, algo=pp.POP_ALGO_SAC, **tuning)
     gpu = pp.Population(cfg, hps)
     agents = list(range(P)) if agents is None else list(agents)
     orc = oracle_sac.Population([hps[i] for i in agents], obs_dim, act_dim, [256, 256], 256, capacity) if oracle else None
@@ -177,11 +177,11 @@ def test_act_mean_and_sampled_actions_match_oracle():
     gpu.close()
 
 
-def test_fused_and_separate_target_critic_launches_agree_bit_for_bit(monkeypatch):
+def test_fused_and_separate_target_critic_launches_agree_bit_for_bit():
     states = []
     for fuse in ("1", "0"):
-        monkeypatch.setenv("POP_FUSE", fuse)
-        gpu, _, _ = make_sac_pair(P=11, capacity=800, oracle=False, hps=sac_hparams(11))
+        gpu, _, _ = make_sac_pair(P=11, capacity=800, oracle=False, hps=sac_hparams(11),
+                                  launch=pp.POP_LAUNCH_TARGET_CRITIC if fuse == "1" else pp.POP_LAUNCH_PER_PART)
         gpu.update(5)
         ms, cnt = gpu.update_timed(3)
         assert (cnt["target_critic"], cnt["target"], cnt["critic"]) == ((3, 0, 0) if fuse == "1" else (0, 3, 3))

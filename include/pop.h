@@ -17,7 +17,8 @@
  *   - "device pointer" = HIP device memory of the GPU that was current at
  *     pop_create; "host pointer" = ordinary host memory.  The caller owns every
  *     pointer it passes, including the workspace and the stream; the library
- *     allocates no device memory and frees nothing of the caller's.
+ *     allocates no device memory (a context holds 8 bytes of pinned host memory)
+ *     and frees nothing of the caller's.
  *   - All work is enqueued on the stream given to pop_create.  pop_update and
  *     calls with device pointers are asynchronous; calls that take or fill host
  *     pointers synchronise that stream before returning.
@@ -183,7 +184,10 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs,
 
 /* Run n_steps update steps for every agent, back to back on the device with
  * no host synchronisation in between (Sec. 4.1: many update steps chained
- * without returning parameters to the host).  One step of one agent: sample a
+ * without returning parameters to the host).  A step also draws and gathers the
+ * replay rows of the step after it, so that a later call starts at once; rows
+ * gathered ahead are dropped when an insert, a buffer copy or new hyperparameters
+ * come in between.  One step of one agent: sample a
  * batch from its own buffer, TD3 critic update, and -- when step %
  * policy_delay == 0 -- actor update and Polyak update of all three targets.
  * POP_EEMPTY if some agent has no transitions. */

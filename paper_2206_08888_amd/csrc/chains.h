@@ -433,7 +433,7 @@ __device__ inline float await_y(const PopDev& d, size_t row, uint32_t t) {
   while (((word = __hip_atomic_load(d.y_tagged + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 32) != t + 1u) {
     __builtin_amdgcn_s_sleep(4);
     if (wall_clock64() - t0 > d.wait_limit) {
-      atomicOr(d.fault, 1u);
+      __hip_atomic_store(d.fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       break;
     }
   }
@@ -466,7 +466,7 @@ __device__ inline void wait_count(const PopDev& d, const uint32_t* count, uint32
   while (__hip_atomic_load(count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < want) {
     __builtin_amdgcn_s_sleep(8);
     if (wall_clock64() - t0 > d.wait_limit) {
-      atomicOr(d.fault, 2u);
+      __hip_atomic_store(d.fault + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
       break;
     }
   }

@@ -60,7 +60,7 @@ constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
   int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
-  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, fault, spart, sloss, sigma, log_alpha, staging, replay, total;
+  int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, spart, sloss, sigma, log_alpha, staging, replay, total;
   int64_t param_bytes;
 };
 
@@ -82,7 +82,8 @@ struct pop_ctx {
   uint64_t t;                    // update steps taken
   uint64_t gathered_t;           // step whose batch already sits in its half of the double buffer
   uint32_t step_launches;        // launches of the step kernel so far (alternates its hand-over counters)
-  bool handover_pending;         // a launch with waits between its workgroups was enqueued since the fault word was last read
+  bool handover_pending;         // a launch with waits between its workgroups was enqueued since the fault words were last read
+  uint32_t* fault_host;          // two words of pinned host memory the kernels mark when a wait runs out
   float* static_scratch;         // this device's copy of the static scratch array (pop_act_explore_noalloc)
   int device;                    // the device that was current at pop_create
   int fuse;                      // launch structure of a step, see POP_K_* in pop.h: 0 one launch per part, 1 target and
@@ -109,17 +110,16 @@ int fail(pop_ctx* ctx, int code, const char* fmt, ...) {
     if (e_ != hipSuccess) return fail(ctx, POP_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
   } while (0)
 
-// Call after the stream has been synchronised: a wait between workgroups that ran out (chains.h) left bits in the
-// fault word.  Reported once, then cleared, so that the context can be used again after its state is restored.
+// Call after the stream has been synchronised: a wait between workgroups that ran out (chains.h) left marks in
+// the two fault words, which live in pinned host memory the device writes to directly (so this costs no copy).
+// Reported once, then cleared, so that the context can be used again after its state is restored.
 int check_fault(pop_ctx* ctx) {
   if (!ctx->handover_pending) return POP_OK;
-  uint32_t fault = 0;
-  HIP_TRY(ctx, hipMemcpyAsync(&fault, ctx->d.fault, sizeof fault, hipMemcpyDeviceToHost, ctx->stream));
-  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
   ctx->handover_pending = false;
+  volatile uint32_t* f = ctx->fault_host;
+  const uint32_t fault = (f[0] ? 1u : 0u) | (f[1] ? 2u : 0u);
   if (!fault) return POP_OK;
-  HIP_TRY(ctx, hipMemsetAsync(ctx->d.fault, 0, sizeof fault, ctx->stream));
-  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  f[0] = 0u; f[1] = 0u;
   return fail(ctx, POP_EHIP, "a wait between workgroups of a fused launch ran into its time limit (fault bits %u: 1 = Bellman targets, "
               "2 = a hand-over count): the results of that step and every later one are invalid", fault);
 }
@@ -255,7 +255,6 @@ Layout make_ws_layout(const PopDev& d) {
   L.losses = take(P * 4 * 4);
   L.y_tagged = take(P * B * 8);
   L.done_c = take(4 * P * 4); L.done_wc = take(4 * P * 4); L.done_a = take(2 * P * 4);
-  L.fault = take(4);
   L.spart = take(2 * (int64_t)d.groups * d.critic.padded * 4);
   L.sloss = take(2 * (int64_t)d.groups * 4);
   L.sigma = take(P * 4);
@@ -433,14 +432,16 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.adZ1 = (float*)(w + L.adZ1);
   d.cpart = (float*)(w + L.cpart); d.apart = (float*)(w + L.apart); d.losses = (float*)(w + L.losses);
   d.y_tagged = (uint64_t*)(w + L.y_tagged); d.done_c = (uint32_t*)(w + L.done_c); d.done_wc = (uint32_t*)(w + L.done_wc); d.done_a = (uint32_t*)(w + L.done_a);
-  d.fault = (uint32_t*)(w + L.fault);
+  d.fault = nullptr;                                   // set below, once the pinned words exist
   d.wait_limit = 5000000ull;                           // 50 ms
   d.log_alpha = (float*)(w + L.log_alpha);
   d.spart = (float*)(w + L.spart); d.sloss = (float*)(w + L.sloss);
   ctx->d = d;
 
+  ctx->fault_host = nullptr;
   auto bail = [&](hipError_t e, const char* what) {
     rc = fail(nullptr, POP_EHIP, "%s: %s", what, hipGetErrorString(e));
+    if (ctx->fault_host) (void)hipHostFree(ctx->fault_host);
     delete ctx;
     return rc;
   };
@@ -448,6 +449,14 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   if ((e = setup_kernels()) != hipSuccess || (e = setup_step_kernel()) != hipSuccess || (e = setup_sac_kernels()) != hipSuccess)
     return bail(e, "kernel attribute setup");
   if ((e = scratch_address(&ctx->static_scratch, &ctx->device)) != hipSuccess) return bail(e, "hipGetSymbolAddress(scratch)");
+  // the two fault words: 8 bytes of pinned host memory, mapped into the device's address space
+  void* fh = nullptr;
+  if ((e = hipHostMalloc(&fh, 2 * sizeof(uint32_t), hipHostMallocMapped)) != hipSuccess) return bail(e, "hipHostMalloc(fault words)");
+  ctx->fault_host = (uint32_t*)fh;
+  ctx->fault_host[0] = ctx->fault_host[1] = 0u;
+  void* fd = nullptr;
+  if ((e = hipHostGetDevicePointer(&fd, fh, 0)) != hipSuccess) { (void)hipHostFree(fh); return bail(e, "hipHostGetDevicePointer"); }
+  ctx->d.fault = (uint32_t*)fd;
   hipStream_t s = ctx->stream;
   // everything between the hyperparameters and the staging area starts at zero
   if ((e = hipMemsetAsync(w, 0, (size_t)L.staging, s)) != hipSuccess) return bail(e, "hipMemsetAsync");
@@ -519,11 +528,13 @@ int pop_insert(pop_ctx* ctx, int32_t agent, int64_t n, const float* obs, const f
 namespace {
 
 // One update step: launches in stream order.  `tick(k, end)` is called before and after
-// kernel k.  When another step follows in the same call, the critic weight-gradient
-// kernel also gathers that step's replay rows, so only the first step of a call pays
-// for a stand-alone gather.
+// kernel k.  The critic weight-gradient kernel also draws and gathers the replay rows of the
+// step after this one (whether or not that step belongs to the same call), so a stand-alone
+// gather runs only when those rows are not there or no longer valid: at the very first step,
+// and after an insert, a buffer copy or new hyperparameters (a new seed draws other rows).
 template <class Tick>
-int enqueue_step(pop_ctx* ctx, bool has_next, Tick tick) {
+int enqueue_step(pop_ctx* ctx, Tick tick) {
+  const bool has_next = ctx->t + 1 <= 0xFFFFFFFFull;
   const PopDev& d = ctx->d;
   hipStream_t s = ctx->stream;
   const uint32_t t = (uint32_t)ctx->t;
@@ -635,7 +646,7 @@ int pop_update(pop_ctx* ctx, int32_t n_steps) {
   int rc = check_update(ctx, n_steps);
   if (rc != POP_OK) return rc;
   for (int i = 0; i < n_steps; ++i)
-    if ((rc = enqueue_step(ctx, i + 1 < n_steps, [](int, int) {})) != POP_OK) return rc;
+    if ((rc = enqueue_step(ctx, [](int, int) {})) != POP_OK) return rc;
   return POP_OK;
 }
 
@@ -655,7 +666,7 @@ int pop_update_timed(pop_ctx* ctx, int32_t n_steps, double* ms, int64_t* launche
     std::fill(used.begin(), used.end(), 0);
     hipError_t ee = hipSuccess;
     for (int i = 0; i < steps && rc == POP_OK; ++i) {
-      rc = enqueue_step(ctx, done + i + 1 < n_steps, [&](int k, int end) {
+      rc = enqueue_step(ctx, [&](int k, int end) {
         const size_t slot = (size_t)i * POP_K_COUNT + k;
         hipError_t r = hipEventRecord(ev[2 * slot + end], s);
         if (r != hipSuccess) ee = r;
@@ -896,6 +907,7 @@ int pop_set_hparams(pop_ctx* ctx, int32_t agent, const pop_hparams* hp) {
   HpDev& g = ctx->hp_dev[agent];
   g.actor_base = actor_updates_before(ctx, agent, ctx->t);   // under the old delay, up to now
   g.t_base = (uint32_t)ctx->t;
+  ctx->gathered_t = ~0ull;                             // rows gathered ahead were drawn under the old seed
   ctx->hp[agent] = *hp;
   to_device_hp(*hp, g);
   if (ctx->d.algo == POP_ALGO_SAC) { ctx->hp[agent].policy_delay = 1; g.policy_delay = 1; }
@@ -958,6 +970,7 @@ int pop_set_option(pop_ctx* ctx, int32_t key, int64_t value) {
 
 int pop_destroy(pop_ctx* ctx) {
   if (!ctx) return POP_EINVAL;
+  if (ctx->fault_host) (void)hipHostFree(ctx->fault_host);
   delete ctx;
   return POP_OK;
 }

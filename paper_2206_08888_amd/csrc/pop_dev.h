@@ -106,7 +106,7 @@ struct PopDev {
   uint32_t* done_c;            // [2][2P] critic chunks finished per network
   uint32_t* done_wc;           // [2][2P] critic weight-gradient roles finished per network
   uint32_t* done_a;            // [2][P]  actor chunks finished per agent
-  uint32_t* fault;             // [1]: bit 0 = a wait for y ran out, bit 1 = a wait for a count
+  uint32_t* fault;             // [2] in pinned host memory: [0] != 0: a wait for y ran out, [1] != 0: a wait for a count
   unsigned long long wait_limit;   // longest wait of one workgroup for another of the same launch, in 10 ns ticks of the
                                // constant-rate clock (default 50 ms; a healthy wait is a fraction of a millisecond)
 };

@@ -61,10 +61,12 @@ def lib_path():
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpop.so")
 
 
-def load_library():
-    """Load libpop.so (built by `python -m paper_2206_08888_amd.build`)."""
+def load_library(path=None):
+    """Load libpop.so (built by `python -m paper_2206_08888_amd.build`), or, when the first call of the process names
+    it, another build of the same boundary (the traced libpop_trace.so)."""
     global _LIB
     if _LIB is not None:
+        assert path is None or os.path.samefile(path, _LIB._name), "another build of the library is already loaded"
         return _LIB
     # PyTorch ships its own HIP runtime; callers allocate the workspace and the stream with it, so it has to be the
     # runtime libpop.so binds to as well: loaded first, its libamdhip64 satisfies the library's dependency.  (Loaded
@@ -73,7 +75,7 @@ def load_library():
         import torch  # noqa: F401
     except ImportError:
         pass
-    path = lib_path()
+    path = lib_path() if path is None else path
     if not os.path.exists(path):
         raise ImportError("%s is missing: build it with `python -m paper_2206_08888_amd.build` "
                           "(there is no fallback implementation)" % path)

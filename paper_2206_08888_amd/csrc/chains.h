@@ -32,6 +32,10 @@
 #include "mfma_tiles16.h"
 #include "rng.h"
 
+#ifndef POP_ONE_TRIP
+#define POP_ONE_TRIP 1
+#endif
+
 namespace pop {
 
 static_assert(kMaxAct == 8, "the action-gradient loops read dz3 rows as two 16-byte vectors");
@@ -128,6 +132,41 @@ __device__ inline void stage_vector(float* dst, const float* __restrict__ src, i
     }
   }
 }
+
+// The same copy in two halves, for chain prologues: fetch() requests the values into registers, put() writes
+// them to LDS.  A prologue calls every fetch() before the first put(), so that all it needs from memory is under
+// way at once; as separate load-then-store loops each vector and the input tile wait out a trip to memory of their own
+// (five in a row at the head of a target chain: 2.8 us).  One element per thread: n <= kThreads.
+struct SmallVec {
+  float v;
+  __device__ inline void fetch(const float* __restrict__ src, int n, int tid) { v = src[tid < n ? tid : 0]; }
+  __device__ inline void put(float* dst, int n, int tid) const { if (tid < n) dst[tid] = v; }
+};
+
+// The input tile of a chain (columns [c0, c0 + n) of R batch rows into columns [0, n) of the LDS tile, the rest
+// zero) in the same two halves; for the narrow inputs (row stride of the tile at most kMaxIn + 4).
+template <int R>
+struct InputTile {
+  static constexpr int IT = (R * (kMaxIn + 4) + kThreads - 1) / kThreads;
+  float v[IT];
+  __device__ inline void fetch(int xld, const float* __restrict__ rows, int row_stride, int c0, int n, int valid, int tid) {
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int e = tid + i * kThreads;
+      const int r = e / xld, c = e - r * xld;
+      const bool in = e < R * xld && c < n && r < valid;
+      const float x = rows[in ? (size_t)r * row_stride + c0 + c : (size_t)c0];
+      v[i] = in ? x : 0.0f;
+    }
+  }
+  __device__ inline void put(float* Xl, int xld, int tid) const {
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int e = tid + i * kThreads;
+      if (e < R * xld) Xl[e] = v[i];
+    }
+  }
+};
 
 // Stage a head weight W3[256][J] as J rows of 256 (so that the thin products read it with
 // 16-byte LDS loads like any other row vector); thread c moves the J weights of hidden unit c.
@@ -498,12 +537,28 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   pre.load(ta, d.actor, wave, lane);
   const HpDev hp = d.hp[agent];
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
-  stage_vector(v_ab3, ta + d.actor.b3, d.A, tid);
-  stage_vector(v_cw3, tc0 + d.critic.w3, kH, tid);
-  stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
-  if (tid < 2) v_cb3[tid] = (tid == 0 ? tc0 : tc1)[d.critic.b3];
-  POP_MARK(30);
-  G::load_input(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
+  if (POP_ONE_TRIP && d.D <= kMaxIn) {               // everything the chain needs from memory before its first product: one trip
+    SmallVec ab3, cw3a, cw3b;
+    InputTile<R> xin;
+    ab3.fetch(ta + d.actor.b3, d.A, tid);
+    cw3a.fetch(tc0 + d.critic.w3, kH, tid);
+    cw3b.fetch(tc1 + d.critic.w3, kH, tid);
+    const float cb3 = (tid == 0 ? tc0 : tc1)[d.critic.b3];
+    xin.fetch(L.xld, rows, d.row, d.D + 2, d.O, R, tid);
+    POP_MARK(30);
+    ab3.put(v_ab3, d.A, tid);
+    cw3a.put(v_cw3, kH, tid);
+    cw3b.put(v_cw3 + kH, kH, tid);
+    if (tid < 2) v_cb3[tid] = cb3;
+    xin.put(Xs, L.xld, tid);
+  } else {
+    stage_vector(v_ab3, ta + d.actor.b3, d.A, tid);
+    stage_vector(v_cw3, tc0 + d.critic.w3, kH, tid);
+    stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
+    if (tid < 2) v_cb3[tid] = (tid == 0 ? tc0 : tc1)[d.critic.b3];
+    POP_MARK(30);
+    G::load_input(Xs, L.xld, rows, d.row, d.D + 2, d.O, R, tid);
+  }
   __syncthreads();
   POP_MARK(31);
 
@@ -589,12 +644,25 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)net * d.B + r0) * kH;
   float* part = d.cpart + ((size_t)net * d.cstride + chunk) * kCPart;
-  stage_vector(v_w3, cn + d.critic.w3, kH, tid);
-  G::load_input(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
   float yv = 0.0f, b3 = 0.0f;
-  if (tid < R) {
-    if (!WAIT) yv = d.y[(size_t)agent * d.B + r0 + tid];
-    b3 = cn[d.critic.b3];
+  if (POP_ONE_TRIP && d.D <= kMaxIn) {               // one trip to memory for all of the prologue
+    SmallVec w3;
+    InputTile<R> xin;
+    w3.fetch(cn + d.critic.w3, kH, tid);
+    xin.fetch(L.xld, rows, d.row, 0, d.D, R, tid);
+    if (tid < R) {
+      if (!WAIT) yv = d.y[(size_t)agent * d.B + r0 + tid];
+      b3 = cn[d.critic.b3];
+    }
+    w3.put(v_w3, kH, tid);
+    xin.put(Xs, L.xld, tid);
+  } else {
+    stage_vector(v_w3, cn + d.critic.w3, kH, tid);
+    G::load_input(Xs, L.xld, rows, d.row, 0, d.D, R, tid);
+    if (tid < R) {
+      if (!WAIT) yv = d.y[(size_t)agent * d.B + r0 + tid];
+      b3 = cn[d.critic.b3];
+    }
   }
   POP_MARK(0);
   __syncthreads();
@@ -693,14 +761,25 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)agent * d.B + r0) * kH;
   float* part = d.apart + ((size_t)agent * (d.B / R) + chunk) * kAPart;
-  stage_vector(v_ab3, an + d.actor.b3, A, tid);
   float cb3 = 0.0f;
   auto stage_critic = [&]() {
     stage_vector(v_cw3, cn + d.critic.w3, kH, tid);
     cb3 = cn[d.critic.b3];
   };
-  if (!WAIT) stage_critic();
-  G::load_input(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
+  if (POP_ONE_TRIP && d.D <= kMaxIn) {               // one trip to memory for all of the prologue
+    SmallVec ab3, cw3;
+    InputTile<R> xin;
+    ab3.fetch(an + d.actor.b3, A, tid);
+    if (!WAIT) { cw3.fetch(cn + d.critic.w3, kH, tid); cb3 = cn[d.critic.b3]; }
+    xin.fetch(L.xld, rows, d.row, 0, d.O, R, tid);
+    ab3.put(v_ab3, A, tid);
+    if (!WAIT) cw3.put(v_cw3, kH, tid);
+    xin.put(Xs, L.xld, tid);
+  } else {
+    stage_vector(v_ab3, an + d.actor.b3, A, tid);
+    if (!WAIT) stage_critic();
+    G::load_input(Xs, L.xld, rows, d.row, 0, d.O, R, tid);
+  }
   __syncthreads();
 
   const uint64_t mask_a1 = G::template first_layer<WAIT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);

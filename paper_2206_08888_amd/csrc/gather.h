@@ -7,6 +7,10 @@
 #include "pop_dev.h"
 #include "rng.h"
 
+#ifndef POP_GATHER_MIN_E
+#define POP_GATHER_MIN_E 4
+#endif
+
 namespace pop {
 
 // Floats of the stacked batch one thread copies: 1 for narrow rows; for wide rows (SAC at the Humanoid shapes:
@@ -15,7 +19,7 @@ namespace pop {
 // than the rows cost to fetch).
 __host__ __device__ inline int gather_floats_per_thread(const PopDev& d) {
   const int e = (d.row + 63) / 64;
-  return e < 1 ? 1 : (e > 16 ? 16 : e);
+  return e < POP_GATHER_MIN_E ? POP_GATHER_MIN_E : (e > 16 ? 16 : e);
 }
 __host__ __device__ inline int gather_blocks_per_agent(const PopDev& d) {
   const int per = 256 * gather_floats_per_thread(d);

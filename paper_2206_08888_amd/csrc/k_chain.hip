@@ -10,14 +10,18 @@ template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_target(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
+  POP_BLOCK_TIME(kTraceTarget, 0);
   if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) target_chain<G>(d, t, agent, chunk, lds);
+  POP_BLOCK_TIME(kTraceTarget, 1);
 }
 
 template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_critic(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int net, chunk;
+  POP_BLOCK_TIME(kTraceCritic, 0);
   if (decode_block(blockIdx.x, 2 * d.P, d.B / G::R, net, chunk)) critic_chain<G, false, false>(d, t, net, chunk, lds);
+  POP_BLOCK_TIME(kTraceCritic, 1);
 }
 
 // Target and critic chains of one step in a single launch.  The critic's forward pass does
@@ -30,11 +34,13 @@ template <class GT, class GC>
 __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
   int unit, chunk;
+  POP_BLOCK_TIME(kTraceTargetCritic, 0);
   if ((int)blockIdx.x < target_blocks) {
     if (decode_block(blockIdx.x, d.P, d.B / GT::R, unit, chunk)) target_chain<GT>(d, t, unit, chunk, lds);
   } else if (decode_block(blockIdx.x - target_blocks, 2 * d.P, d.B / GC::R, unit, chunk)) {
     critic_chain<GC, true, false>(d, t, unit, chunk, lds);
   }
+  POP_BLOCK_TIME(kTraceTargetCritic, 1);
 }
 
 // The same for populations whose 16-row target workgroups and 32-row critic workgroups do not all get a CU at
@@ -44,6 +50,7 @@ template <class GC>
 __global__ __launch_bounds__(kThreads, 1) void k_target_critic1(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
   int agent, chunk;
+  POP_BLOCK_TIME(kTraceTargetCritic, 0);
   if ((int)blockIdx.x < target_blocks) {
     if (decode_block(blockIdx.x, d.P, d.B / 16, agent, chunk)) {
       target_chain<Rows16>(d, t, agent, chunk, lds);
@@ -53,6 +60,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic1(PopDev d, uint32
   } else if (decode_block(blockIdx.x - target_blocks, d.P, d.B / GC::R, agent, chunk)) {
     critic_chain<GC, true, false>(d, t, 2 * agent + 1, chunk, lds);
   }
+  POP_BLOCK_TIME(kTraceTargetCritic, 1);
 }
 
 // PER_CU: workgroups per CU the register budget is set for
@@ -60,7 +68,9 @@ template <class G, int PER_CU = 1>
 __global__ __launch_bounds__(kThreads, PER_CU) void k_actor(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
+  POP_BLOCK_TIME(kTraceActor, 0);
   if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, false>(d, t, agent, chunk, lds, 0);
+  POP_BLOCK_TIME(kTraceActor, 1);
 }
 
 // ---------------------------------------------------------------------------------------------

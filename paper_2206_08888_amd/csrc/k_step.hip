@@ -19,6 +19,10 @@
 
 namespace pop {
 
+#ifdef POP_TRACE
+int g_trace_step_parts[6];           // blocks of the parts of the last k_step launch: target, critic, critic tiles, actor, actor tiles, gather
+#endif
+
 struct StepGrid {
   int t, c, wc, a, wa, g;          // blocks of each part (0: the part is not in this launch)
   int roles_c, roles_a;            // weight-gradient roles per critic / actor network
@@ -30,7 +34,7 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
   extern __shared__ __attribute__((aligned(16))) float lds[];
   int b = blockIdx.x;
   POP_MARK(63);
-  POP_BLOCK_TIME(0);
+  POP_BLOCK_TIME(kTraceStep, 0);
   if (b == 0) {                                      // zero the counters the next step will count in
                                                      // (whichever part block 0 belongs to)
     const int other = d.sync_half ^ 1;
@@ -43,13 +47,13 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
   int unit, sub;
   if (b < g.t) {
     if (decode_block(b, d.P, d.B / GT::R, unit, sub)) target_chain<GT>(d, t, unit, sub, lds);
-    POP_BLOCK_TIME(1);
+    POP_BLOCK_TIME(kTraceStep, 1);
     return;
   }
   b -= g.t;
   if (b < g.c) {
     if (decode_block(b, 2 * d.P, d.B / GC::R, unit, sub)) critic_chain<GC, true, true>(d, t, unit, sub, lds);
-    POP_BLOCK_TIME(1);
+    POP_BLOCK_TIME(kTraceStep, 1);
     return;
   }
   b -= g.c;
@@ -60,28 +64,28 @@ __global__ __launch_bounds__(kThreads, 2) void k_step(PopDev d, uint32_t t, Step
     // still finds what it waits for -- the tiles of its own critic 1 -- at lower block indices.  With one
     // workgroup per CU the actor chains of the first agents then start while later agents' tiles still run.
     const int tiles = 2 * g.roles_c, chunks = g.a / d.P;
-    if (decode_block(b, d.P, tiles + chunks, unit, sub)) {
+    if (decode_block<true>(b, d.P, tiles + chunks, unit, sub)) {    // an agent's actor chains wait for its own tiles
       if (sub < tiles) wgrad_roles<true>(d, t, 0, 2 * unit + sub / g.roles_c, sub % g.roles_c, lds, sh_adam, g.c != 0);
       else actor_chain<GA, true>(d, t, unit, sub - tiles, lds, g.roles_c);
     }
-    POP_BLOCK_TIME(1);
+    POP_BLOCK_TIME(kTraceStep, 1);
     return;
   }
   if (b < g.wc) {
     if (decode_block(b, 2 * d.P, g.roles_c, unit, sub)) wgrad_roles<true>(d, t, 0, unit, sub, lds, sh_adam, g.c != 0);
-    POP_BLOCK_TIME(1);
+    POP_BLOCK_TIME(kTraceStep, 1);
     return;
   }
   b -= g.wc;
   if (b < g.a) {
     if (decode_block(b, d.P, d.B / GA::R, unit, sub)) actor_chain<GA, true>(d, t, unit, sub, lds, g.roles_c);
-    POP_BLOCK_TIME(1);
+    POP_BLOCK_TIME(kTraceStep, 1);
     return;
   }
   b -= g.a;
   if (b < g.wa) {
     if (decode_block(b, d.P, g.roles_a, unit, sub)) wgrad_roles<true>(d, t, 1, unit, sub, lds, sh_adam);
-    POP_BLOCK_TIME(1);
+    POP_BLOCK_TIME(kTraceStep, 1);
     return;
   }
   b -= g.wa;
@@ -122,6 +126,10 @@ hipError_t launch_step(const PopDev& dev, uint32_t t, uint32_t launch_seq, int w
   const int vec = vec_ta > vec_critic(d) ? vec_ta : vec_critic(d);
   const size_t tiles = (size_t)(32 * kLda) * sizeof(float) + sizeof(Adam);
   const dim3 grid(g.t + g.c + g.wc + g.a + g.wa + g.g), block(kThreads);
+#ifdef POP_TRACE
+  g_trace_step_parts[0] = g.t; g_trace_step_parts[1] = g.c; g_trace_step_parts[2] = g.wc; g_trace_step_parts[3] = g.a;
+  g_trace_step_parts[4] = g.wa; g_trace_step_parts[5] = g.g;
+#endif
   size_t bytes = tiles;
   auto need = [&](size_t b) { if (b > bytes) bytes = b; };
   if (d.rows_a == 16) {

@@ -14,16 +14,19 @@ __global__ __launch_bounds__(kThreads, 3) void k_wgrad_adam(PopDev d, uint32_t t
   __shared__ Adam sh_adam;
   __shared__ __attribute__((aligned(16))) float xt_lds[32 * kLda];
   POP_MARK(49);
+  POP_BLOCK_TIME(actor_phase ? kTraceWgradActor : kTraceWgradCritic, 0);
   if ((int)blockIdx.x >= main_blocks) {              // gather role: rows of the next step
     if (prefetch) {
       const int g = blockIdx.x - main_blocks, per = gather_blocks_per_agent(d);
       gather_block(d, t + 1u, g / per, g % per, threadIdx.x);
     }
+    POP_BLOCK_TIME(actor_phase ? kTraceWgradActor : kTraceWgradCritic, 1);
     return;
   }
   int unit, role;
   if (decode_block(blockIdx.x, actor_phase ? d.P : 2 * d.P, roles, unit, role))
     wgrad_roles<false, true, HALF>(d, t, actor_phase, unit, role, xt_lds, &sh_adam);
+  POP_BLOCK_TIME(actor_phase ? kTraceWgradActor : kTraceWgradCritic, 1);
 }
 
 int wgrad_role_count(const PopDev& d, int actor_phase) {

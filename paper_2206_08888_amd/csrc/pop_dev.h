@@ -3,21 +3,25 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-// Phase marks for kernel tuning: compiled out unless POP_TRACE is defined by a test harness,
-// which then also defines the g_pop_trace array the marks go to.
+// Timeline instrumentation, compiled out of the library proper.  The traced build (trace_unity.hip: every source of
+// the library in one translation unit with POP_TRACE defined, built as libpop_trace.so) keeps, per kernel kind and
+// block, the constant-rate clock at the block's start and end, and the phase marks of one chosen block; the
+// trace_* calls of that build read them back (paper_2206_08888_amd/timeline.py prints the timelines).
 #ifdef POP_TRACE
+constexpr int kTraceKinds = 8, kTraceBlocks = 32768;
+enum { kTraceStep = 0, kTraceTargetCritic = 1, kTraceWgradCritic = 2, kTraceActor = 3, kTraceWgradActor = 4, kTraceTarget = 5, kTraceCritic = 6 };
 extern __device__ unsigned long long g_pop_trace[64];
 extern __device__ int g_pop_trace_block;            // the block whose marks are recorded
+extern __device__ unsigned long long g_pop_block_time[kTraceKinds][2][kTraceBlocks];
 #define POP_MARK(i)                                                                 \
   do {                                                                              \
     if ((int)blockIdx.x == g_pop_trace_block && threadIdx.x == 0) g_pop_trace[i] = wall_clock64(); \
     if (blockIdx.x == 0 && threadIdx.x == 0 && (i) == 63) g_pop_trace[63] = wall_clock64();       \
   } while (0)
-extern __device__ unsigned long long g_pop_block_time[2][8192];   // start / end of every block of the traced launch
-#define POP_BLOCK_TIME(w) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_pop_block_time[w][blockIdx.x] = wall_clock64(); } while (0)
+#define POP_BLOCK_TIME(kind, w) do { if (threadIdx.x == 0 && blockIdx.x < kTraceBlocks) g_pop_block_time[kind][w][blockIdx.x] = wall_clock64(); } while (0)
 #else
 #define POP_MARK(i)
-#define POP_BLOCK_TIME(w)
+#define POP_BLOCK_TIME(kind, w)
 #endif
 
 namespace pop {
@@ -124,20 +128,30 @@ __device__ inline const float* batch_rows(const PopDev& d, uint32_t t, int agent
 // Workgroup ids are handed to the 8 XCDs round-robin; decode a 1-D block id so that
 // all `per_unit` workgroups of one unit (an agent or a network) land on the same
 // XCD and share its L2 (weights and activations of that unit).  That works for whole
-// groups of 8 units; the units % 8 left over are laid out plainly (their workgroups
-// spread over the XCDs), so that a grid has exactly units * per_unit blocks: blocks that
-// only exit would still take a turn in the dispatcher's walk over the CUs, and push
-// later workgroups onto CUs that are already busy while others stand empty.
+// groups of 8 units.  The r = units % 8 left over cannot each have an XCD of their own while
+// the grid keeps exactly units * per_unit blocks (blocks that only exit would still take a
+// turn in the dispatcher's walk over the CUs, and push later workgroups onto CUs that are
+// already busy while others stand empty), so their workgroups are numbered XCD by XCD: a
+// left-over unit then sits on about 8 / r neighbouring XCDs instead of on all 8 (P = 10: the
+// two left-over agents on four XCDs each, the four left-over critics on two), and its weights
+// are fetched from memory that many times instead of eight.
 // The grouping only needs ids that are congruent mod 8 to share an XCD, so `id` may be
 // offset by any constant (a kernel that runs two kinds of workgroups).
-__device__ inline bool decode_block(int id, int units, int per_unit, int& unit, int& sub) {
+// ORDERED: the caller needs `sub` to grow with `id` within a unit (a later sub-block waits for an
+// earlier one of the same unit); the left-over units are then laid out plainly, over all XCDs.
+template <bool ORDERED = false>
+__host__ __device__ inline bool decode_block(int id, int units, int per_unit, int& unit, int& sub) {
   const int full = units & ~7, nfull = full * per_unit;
   if (id < nfull) {
     const int x = id & 7, slot = id >> 3;
     unit = (slot / per_unit) * 8 + x;
     sub = slot % per_unit;
   } else {
-    const int j = id - nfull;
+    int j = id - nfull;
+    if (!ORDERED) {                                    // position of block j when the left-over blocks are listed XCD by XCD
+      const int n = (units - full) * per_unit, q = n >> 3, rem = n & 7, x = j & 7;
+      j = x * q + (x < rem ? x : rem) + (j >> 3);
+    }
     unit = full + j / per_unit;
     sub = j % per_unit;
   }

@@ -537,6 +537,26 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   pre.load(ta, d.actor, wave, lane);
   const HpDev hp = d.hp[agent];
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
+  // The smoothing noise of this chunk depends on nothing the chain computes (counter RNG: agent seed, step,
+  // element), so it is drawn here, while the prologue's loads are on their way, and added after the head.
+  constexpr int kNoisePerThread = (R * kMaxAct + kThreads - 1) / kThreads;
+  float noise[kNoisePerThread];
+  auto draw_noise = [&]() {
+#pragma unroll
+    for (int i = 0; i < kNoisePerThread; ++i) {
+      const int e = tid + i * kThreads;
+      noise[i] = 0.0f;
+      if (e < R * d.A) {
+        const int r = e / d.A, j = e - r * d.A;
+        const uint32_t el = (uint32_t)((r0 + r) * d.A + j);
+        const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, el >> 2, t, kStreamSmooth, 0u);
+        float n4[4];
+        normals4(blk, n4);
+        const float n = (el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0]);
+        noise[i] = fminf(fmaxf(hp.policy_noise * n, -hp.noise_clip), hp.noise_clip);
+      }
+    }
+  };
   if (POP_ONE_TRIP && d.D <= kMaxIn) {               // everything the chain needs from memory before its first product: one trip
     SmallVec ab3, cw3a, cw3b;
     InputTile<R> xin;
@@ -545,6 +565,8 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
     cw3b.fetch(tc1 + d.critic.w3, kH, tid);
     const float cb3 = (tid == 0 ? tc0 : tc1)[d.critic.b3];
     xin.fetch(L.xld, rows, d.row, d.D + 2, d.O, R, tid);
+    __builtin_amdgcn_sched_barrier(0);                 // the loads go out first, the noise is drawn under them
+    draw_noise();
     POP_MARK(30);
     ab3.put(v_ab3, d.A, tid);
     cw3a.put(v_cw3, kH, tid);
@@ -552,6 +574,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
     if (tid < 2) v_cb3[tid] = cb3;
     xin.put(Xs, L.xld, tid);
   } else {
+    draw_noise();
     stage_vector(v_ab3, ta + d.actor.b3, d.A, tid);
     stage_vector(v_cw3, tc0 + d.critic.w3, kH, tid);
     stage_vector(v_cw3 + kH, tc1 + d.critic.w3, kH, tid);
@@ -572,18 +595,16 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   else head_mfma<R>(buf, ta + d.actor.w3, d.A, head, kMaxAct, wave, lane);   // the head's weights straight from global memory
   __syncthreads();
   POP_MARK(34);
-  for (int e = tid; e < R * d.A; e += kThreads) {
-    const int r = e / d.A, j = e - r * d.A;
-    const float mu = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
-    const uint32_t el = (uint32_t)((r0 + r) * d.A + j);
-    const U4 blk = philox4x32_10(hp.seed_lo, hp.seed_hi, el >> 2, t, kStreamSmooth, 0u);
-    float n4[4];
-    normals4(blk, n4);
-    const float n = (el & 2u) ? ((el & 1u) ? n4[3] : n4[2]) : ((el & 1u) ? n4[1] : n4[0]);
-    const float noise = fminf(fmaxf(hp.policy_noise * n, -hp.noise_clip), hp.noise_clip);
-    const float at = fminf(fmaxf(mu + noise, -1.0f), 1.0f);
-    Xs[r * L.xld + d.O + j] = at;
-    d.atilde[((size_t)agent * d.B + r0 + r) * d.A + j] = at;
+#pragma unroll
+  for (int i = 0; i < kNoisePerThread; ++i) {
+    const int e = tid + i * kThreads;
+    if (e < R * d.A) {
+      const int r = e / d.A, j = e - r * d.A;
+      const float mu = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
+      const float at = fminf(fmaxf(mu + noise[i], -1.0f), 1.0f);
+      Xs[r * L.xld + d.O + j] = at;
+      d.atilde[((size_t)agent * d.B + r0 + r) * d.A + j] = at;
+    }
   }
   __syncthreads();
   POP_MARK(35);

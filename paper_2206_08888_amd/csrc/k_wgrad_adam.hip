@@ -29,14 +29,19 @@ __global__ __launch_bounds__(kThreads, 3) void k_wgrad_adam(PopDev d, uint32_t t
   POP_BLOCK_TIME(actor_phase ? kTraceWgradActor : kTraceWgradCritic, 1);
 }
 
+// Roles of one network: its 32 x 128 weight tiles, then the small tensors (wgrad.h): one role, and for an actor one
+// more per kSmallHeadBlock head columns.
+static int small_roles(const PopDev& d, int actor_phase) {
+  return actor_phase ? 1 + (d.actor.out + kSmallHeadBlock - 1) / kSmallHeadBlock : 1;
+}
 int wgrad_role_count(const PopDev& d, int actor_phase) {
   const NetLayout& L = actor_phase ? d.actor : d.critic;
-  return 16 + 2 * ((L.in + 31) / 32) + 1;
+  return 16 + 2 * ((L.in + 31) / 32) + small_roles(d, actor_phase);
 }
 
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s) {
-  const int full = wgrad_role_count(d, actor_phase);
-  const int roles = d.half_tiles ? 2 * (full - 1) + 1 : full;   // every tile role twice; one small-tensor role
+  const int full = wgrad_role_count(d, actor_phase), small = small_roles(d, actor_phase);
+  const int roles = d.half_tiles ? 2 * (full - small) + small : full;   // every tile role twice; the small-tensor roles once
   const int main_blocks = xcd_grid(actor_phase ? d.P : 2 * d.P, roles);
   const int extra = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
   const dim3 grid(main_blocks + extra), block(kThreads);

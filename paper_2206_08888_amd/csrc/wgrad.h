@@ -218,7 +218,7 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   POP_MARK(54);
 }
 
-constexpr int kHeadBlock = 16;   // head columns whose Adam operands the small-tensor role holds in registers at once
+constexpr int kSmallHeadBlock = 8;   // head columns of an actor that one small-tensor role sums and updates
 
 // One role of the weight-gradient step of one network (unit = agent in the actor phase, else network).
 // WAIT: consumers (the actor chain, for critic 1) and, if producer_in_launch, producers (the
@@ -277,14 +277,17 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     weight_tile<WAIT, SLIM, HALF>(d, wait_on, (uint32_t)chunks, sh_adam, setup, delayed_step && !(actor_phase && d.algo == 1), x, w2 ? kH : d.row, w2 ? kH : L.in, 32 * ((w2 ? role : role - 16) >> 1), n0, z,
                 (uint32_t)(w2 ? L.w2 : L.w1), xt_lds, th, mo, ve, tg, gr, tid);
   } else {
-    // small tensors from per-chunk partial sums; thread c owns hidden unit c.  The Adam operands
-    // are requested first: they depend on nothing and arrive while the partial sums are read.
-    constexpr int HB = SLIM ? 8 : kHeadBlock;         // head columns held in registers at once
+    // Small tensors from per-chunk partial sums; thread c owns hidden unit c.  Role `small` = 0: the hidden biases,
+    // and for a critic its one head column, head bias and loss, for an actor its head bias and loss (SAC: the
+    // temperature).  An actor's head columns are roles of their own, kSmallHeadBlock columns each (small - 1 =
+    // block): as one role they made the longest workgroup of the launch by far (16 chunk records walked once per
+    // block of columns, a trip to memory every few records: 17 us at P = 10 where a tile takes 8).
+    // The Adam operands are requested first: they depend on nothing and arrive while the partial sums are read.
+    constexpr int HB = kSmallHeadBlock;
+    const int small = role - (HALF ? 2 * tiles : tiles);
     const int c = tid;
     const int out = L.out;
     POP_MARK(55);
-    const uint32_t i_b1 = (uint32_t)(L.b1 + c), i_b2 = (uint32_t)(L.b2 + c), i_w3 = (uint32_t)(L.w3 + c * out),
-                   i_b3 = (uint32_t)(L.b3 + (c < out ? c : 0));
     const bool polyak = delayed_step && !(actor_phase && d.algo == 1);
     auto ld = [&](uint32_t i) {
       AdamRegs r;
@@ -292,55 +295,21 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
       r.tg = polyak ? tg[i] : 0.0f;
       return r;
     };
-    const AdamRegs r_b1 = ld(i_b1), r_b2 = ld(i_b2), r_b3 = ld(i_b3);
-    AdamRegs r_w3[HB];                       // head columns go in blocks of HB; the first is requested here
+    if (small > 0) {                                  // actor: head columns [j0, j0 + HB)
+      const int j0 = (small - 1) * HB;
+      const uint32_t i_w3 = (uint32_t)(L.w3 + c * out);
+      AdamRegs r_w3[HB];
 #pragma unroll
-    for (int j = 0; j < HB; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j < out ? j : 0));
-    setup();
-    if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
-    __syncthreads();
-    const Adam adam = *sh_adam;
-    POP_MARK(56);
-    float gb1 = 0.0f, gb2 = 0.0f, gw3[HB], gb3 = 0.0f, loss = 0.0f, logp = 0.0f;
+      for (int j = 0; j < HB; ++j) r_w3[j] = ld(i_w3 + (uint32_t)(j0 + j < out ? j0 + j : 0));
+      setup();
+      if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
+      __syncthreads();
+      const Adam adam = *sh_adam;
+      float gw3[HB];
 #pragma unroll
-    for (int j = 0; j < HB; ++j) gw3[j] = 0.0f;
-    // Every load of a chunk's record goes out unconditionally (head columns beyond `out` re-read column 0
-    // and are dropped at the store), so that the loads of several chunks are in flight together.
-    if (actor_phase) {
-#pragma unroll (SLIM ? 2 : 4)
-      for (int ch = 0; ch < chunks; ++ch) {
-        const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart;
-        const float t1 = p[kAP_db1 + c], t2 = p[kAP_db2 + c], t3 = p[kAP_db3 + (c < out ? c : 0)];
-        const float tl = p[kAP_loss], tp = p[kAP_logp];
-        float tw[HB];
-#pragma unroll
-        for (int j = 0; j < HB; ++j) tw[j] = p[kAP_dW3 + (j < out ? j : 0) * kH + c];
-        gb1 += t1; gb2 += t2; gb3 += t3; loss += tl; logp += tp;
-#pragma unroll
-        for (int j = 0; j < HB; ++j) gw3[j] += tw[j];
-      }
-    } else {
-#pragma unroll 4
-      for (int ch = 0; ch < chunks; ++ch) {
-        const float* p = d.cpart + ((size_t)unit * d.cstride + ch) * kCPart;
-        const float t1 = p[kCP_db1 + c], t2 = p[kCP_db2 + c], tw = p[kCP_dW3 + c], t3 = p[kCP_db3], tl = p[kCP_loss];
-        gb1 += t1; gb2 += t2; gw3[0] += tw; gb3 += t3; loss += tl;
-      }
-    }
-    POP_MARK(57);
-    adam_store<WAIT>(adam, r_b1, gb1, i_b1, th, mo, ve, tg, gr);
-    adam_store<WAIT>(adam, r_b2, gb2, i_b2, th, mo, ve, tg, gr);
-#pragma unroll
-    for (int j = 0; j < HB; ++j)
-      if (j < out) adam_store<WAIT>(adam, r_w3[j], gw3[j], i_w3 + (uint32_t)j, th, mo, ve, tg, gr);
-    if (c < out) adam_store<WAIT>(adam, r_b3, gb3, i_b3, th, mo, ve, tg, gr);
-#pragma unroll 1
-    for (int j0 = HB; j0 < out; j0 += HB) {   // wider heads (SAC with more than 8 actions; actor only)
-#pragma unroll
-      for (int j = 0; j < HB; ++j) {
-        r_w3[j] = ld(i_w3 + (uint32_t)(j0 + j < out ? j0 + j : 0));
-        gw3[j] = 0.0f;
-      }
+      for (int j = 0; j < HB; ++j) gw3[j] = 0.0f;
+      // every load goes out unconditionally (columns beyond `out` re-read column 0 and are dropped at the store),
+      // so that the loads of several chunks are in flight together
 #pragma unroll 4
       for (int ch = 0; ch < chunks; ++ch) {
         const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart + kAP_dW3 + c;
@@ -353,7 +322,40 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
 #pragma unroll
       for (int j = 0; j < HB; ++j)
         if (j0 + j < out) adam_store<WAIT>(adam, r_w3[j], gw3[j], i_w3 + (uint32_t)(j0 + j), th, mo, ve, tg, gr);
+      POP_MARK(58);
+      return;                                         // (actor roles do not count themselves in for anybody)
     }
+    const uint32_t i_b1 = (uint32_t)(L.b1 + c), i_b2 = (uint32_t)(L.b2 + c), i_w3 = (uint32_t)(L.w3 + c * out),
+                   i_b3 = (uint32_t)(L.b3 + (c < out ? c : 0));
+    const AdamRegs r_b1 = ld(i_b1), r_b2 = ld(i_b2), r_b3 = ld(i_b3);
+    AdamRegs r_w3 = ld(i_w3);                         // critic: its one head column
+    setup();
+    if (WAIT && wait_on && tid == 0) wait_count(d, wait_on, (uint32_t)chunks);
+    __syncthreads();
+    const Adam adam = *sh_adam;
+    POP_MARK(56);
+    float gb1 = 0.0f, gb2 = 0.0f, gw3 = 0.0f, gb3 = 0.0f, loss = 0.0f, logp = 0.0f;
+    if (actor_phase) {
+#pragma unroll 4
+      for (int ch = 0; ch < chunks; ++ch) {
+        const float* p = d.apart + ((size_t)agent * chunks + ch) * kAPart;
+        const float t1 = p[kAP_db1 + c], t2 = p[kAP_db2 + c], t3 = p[kAP_db3 + (c < out ? c : 0)];
+        const float tl = p[kAP_loss], tp = p[kAP_logp];
+        gb1 += t1; gb2 += t2; gb3 += t3; loss += tl; logp += tp;
+      }
+    } else {
+#pragma unroll 4
+      for (int ch = 0; ch < chunks; ++ch) {
+        const float* p = d.cpart + ((size_t)unit * d.cstride + ch) * kCPart;
+        const float t1 = p[kCP_db1 + c], t2 = p[kCP_db2 + c], tw = p[kCP_dW3 + c], t3 = p[kCP_db3], tl = p[kCP_loss];
+        gb1 += t1; gb2 += t2; gw3 += tw; gb3 += t3; loss += tl;
+      }
+    }
+    POP_MARK(57);
+    adam_store<WAIT>(adam, r_b1, gb1, i_b1, th, mo, ve, tg, gr);
+    adam_store<WAIT>(adam, r_b2, gb2, i_b2, th, mo, ve, tg, gr);
+    if (!actor_phase) adam_store<WAIT>(adam, r_w3, gw3, i_w3, th, mo, ve, tg, gr);
+    if (c < out) adam_store<WAIT>(adam, r_b3, gb3, i_b3, th, mo, ve, tg, gr);
     if (actor_phase && d.algo == 1 && c == 0) {
       // SAC temperature: gradient of -alpha mean(log pi + target entropy) with respect to log_alpha, log pi
       // from this step's actor pass held constant; one Adam step with lr_alpha, no target

@@ -85,8 +85,8 @@ typedef struct {
 
 /* How the kernels of an update step are launched and tiled.  All zeros (the default of a cleared pop_config) lets
  * the library choose by population size; the fields exist for measurements and for tests that compare the choices
- * with one another.  They change no result beyond the order of fp32 sums: with the same rows and tile widths every
- * launch structure gives bit-identical results.  Nothing is read from the process environment. */
+ * with one another.  They change no result beyond the order of fp32 sums: with the same rows and tile widths, and actor_ahead
+ * off, every launch structure gives bit-identical results.  Nothing is read from the process environment. */
 enum {
   POP_LAUNCH_AUTO = 0,
   POP_LAUNCH_PER_PART = 1,       /* one launch per part of the step: POP_K_TARGET .. POP_K_WGRAD_ACTOR */
@@ -108,6 +108,12 @@ typedef struct {
   int32_t half_tiles;    /* weight-gradient tiles of half the width in the stand-alone tile launches: 0 = choose (on
                             while all of them are resident at once, up to 10 agents), 1 = off, 2 = on.  The sums over
                             the batch then come in two halves: compare launch structures with this set to 1. */
+  int32_t actor_ahead;   /* the actor's own forward pass of a step with a policy update runs inside the target / critic
+                            launch, in the 32-row workgroups of critic 2 while they wait for their Bellman targets, and
+                            the actor launch starts at the critic: 0 = choose (on where it exists and those workgroups
+                            have a CU each), 1 = off, 2 = on.  Exists for TD3 and shared critics with TARGET_CRITIC and
+                            rows (16, 32, 16); POP_EINVAL for 2 elsewhere.  That pass then runs on 32-row instead of
+                            16-row tiles, another order of the fp32 sums: compare launch structures with this set to 1. */
 } pop_tuning;
 
 typedef struct {

@@ -36,7 +36,7 @@ POP_OPT_WAIT_LIMIT_TICKS = 0
 
 class pop_tuning(C.Structure):
     _fields_ = [("launch", C.c_int32), ("rows_target", C.c_int32), ("rows_critic", C.c_int32), ("rows_actor", C.c_int32),
-                ("rows_critic1", C.c_int32), ("half_tiles", C.c_int32)]
+                ("rows_critic1", C.c_int32), ("half_tiles", C.c_int32), ("actor_ahead", C.c_int32)]
 
 
 class pop_config(C.Structure):
@@ -45,7 +45,7 @@ class pop_config(C.Structure):
                 ("capacity", C.c_int64), ("tuning", pop_tuning)]
 
 
-assert C.sizeof(pop_hparams) == 64 and C.sizeof(pop_config) == 72
+assert C.sizeof(pop_hparams) == 64 and C.sizeof(pop_config) == 80
 
 
 class PopError(RuntimeError):
@@ -114,9 +114,9 @@ def load_library(path=None):
 
 
 def make_config(P, obs_dim, act_dim, hidden=(256, 256), batch=256, capacity=10000, algo=POP_ALGO_TD3,
-                launch=POP_LAUNCH_AUTO, rows=None, rows_critic1=0, half_tiles=0):
+                launch=POP_LAUNCH_AUTO, rows=None, rows_critic1=0, half_tiles=0, actor_ahead=0):
     """rows: None (the library chooses), one value for all three chains, or (target, critic, actor); launch,
-    rows_critic1, half_tiles: the fields of pop_tuning."""
+    rows_critic1, half_tiles, actor_ahead: the fields of pop_tuning."""
     cfg = pop_config()
     cfg.algo, cfg.P, cfg.obs_dim, cfg.act_dim = algo, P, obs_dim, act_dim
     cfg.n_hidden = len(hidden)
@@ -127,7 +127,7 @@ def make_config(P, obs_dim, act_dim, hidden=(256, 256), batch=256, capacity=1000
     if rows is not None:
         rt, rc, ra = (rows, rows, rows) if isinstance(rows, int) else rows
         cfg.tuning.rows_target, cfg.tuning.rows_critic, cfg.tuning.rows_actor = rt, rc, ra
-    cfg.tuning.rows_critic1, cfg.tuning.half_tiles = rows_critic1, half_tiles
+    cfg.tuning.rows_critic1, cfg.tuning.half_tiles, cfg.tuning.actor_ahead = rows_critic1, half_tiles, actor_ahead
     return cfg
 
 

@@ -249,6 +249,7 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
   static constexpr int R = 32 * MT, kPad = 8;
   using Pre = LayerPre<MT>;
   using WtBlock = WeightBlock<MT, true>;
+  static constexpr int kStage = 0;                   // no LDS staging of weights (`stage` arguments are unused)
   __device__ static inline void load_wt(WtBlock& wt, const float* W, int wave, int lane) { wt.load(W, 0, wave, lane); }
   __device__ static inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
                                            int tid) {
@@ -266,13 +267,13 @@ struct Rows32 {                                      // 32 MT rows on v_mfma_f32
   }
   template <bool THROUGH>
   __device__ static inline void input_grad_to_global(const float* Zl, const float* W, WtBlock& w0, uint64_t mask,
-                                                     float* dXg, float* colsum_out, int wave, int lane) {
+                                                     float* dXg, float* colsum_out, int wave, int lane, float*) {
     pop::input_grad_to_global<MT, THROUGH, FED>(Zl, W, w0, mask, dXg, colsum_out, wave, lane);
   }
   // buf <- (buf W^T) * mask in place; tail() as in gemm256
   template <class Tail>
   __device__ static inline void input_grad_to_lds(float* buf, const float* W, WtBlock& wt, uint64_t mask, int wave,
-                                                  int lane, Tail tail) {
+                                                  int lane, Tail tail, float*) {
     Acc<MT> acc;
     acc.zero();
     gemm256<MT, true, 2, FED>(buf, kLda, W, wt, wave, lane, acc, tail);
@@ -318,7 +319,8 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
       b2 = *reinterpret_cast<const f32x4*>(net + L.b2 + 64 * wave + 4 * (lane & 15));
     }
   };
-  using WtBlock = WeightBlock16<true>;
+  using WtBlock = WeightStage16;                     // the transposed products stage their weights through LDS
+  static constexpr int kStage = kStage16;            // floats of LDS they need for that
   __device__ static inline void load_wt(WtBlock& wt, const float* W, int wave, int lane) { wt.load(W, 0, wave, lane); }
   __device__ static inline void load_input(float* Xl, int xld, const float* rows, int row_stride, int c0, int n, int valid,
                                            int tid) {
@@ -345,10 +347,10 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
   template <bool THROUGH>
   __device__ static inline void input_grad_to_global(const float* Zl, const float* W, WtBlock& w0, uint64_t mask,
                                                      float* __restrict__ dXg, float* __restrict__ colsum_out, int wave,
-                                                     int lane) {
+                                                     int lane, float* stage) {
     Acc16 acc;
     acc.zero();
-    gemm256_16<true>(Zl, kLda, W, w0, wave, lane, acc, NoTail());
+    gemm256_16_staged(Zl, kLda, W, w0, stage, wave, lane, acc, NoTail());
     const int c = lane & 15, kq = lane >> 4;
     float cs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
@@ -376,10 +378,10 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
   }
   template <class Tail>
   __device__ static inline void input_grad_to_lds(float* buf, const float* W, WtBlock& wt, uint64_t mask, int wave,
-                                                  int lane, Tail tail) {
+                                                  int lane, Tail tail, float* stage) {
     Acc16 acc;
     acc.zero();
-    gemm256_16<true>(buf, kLda, W, wt, wave, lane, acc, tail);
+    gemm256_16_staged(buf, kLda, W, wt, stage, wave, lane, acc, tail);
     __syncthreads();
     const int c = lane & 15, kq = lane >> 4;
 #pragma unroll
@@ -392,6 +394,20 @@ struct Rows16 {                                      // 16 rows on v_mfma_f32_16
   }
   __device__ static inline void thin(const float* Xl, const float* V, int J, float* outl, int tid, int stride = kMaxAct) {
     thin_dot16(Xl, V, J, outl, tid, stride);
+  }
+  // The ReLU pattern first_layer / hidden_layer return, rebuilt from the layer's output Hg[16][256] in global memory
+  __device__ static inline uint64_t mask_from_global(const float* __restrict__ Hg, int wave, int lane) {
+    const int c = lane & 15, kq = lane >> 4;
+    f32x4 h[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) h[v] = *reinterpret_cast<const f32x4*>(Hg + (4 * kq + v) * kH + 64 * wave + 4 * c);
+    uint64_t mask = 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+        if (h[v][nt] > 0.0f) mask |= 1ull << (4 * nt + v);
+    return mask;
   }
   __device__ static inline void store_outer_masked(float* buf, uint64_t mask, const float* rowvec, const float* colvec,
                                                    int wave, int lane) {
@@ -640,6 +656,46 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
 
 
 // ---------------------------------------------------------------------------------------------
+// The actor's own forward pass (s -> h1 -> h2 -> a_pi) for the rows of a critic workgroup, run by that workgroup
+// while it waits for its Bellman targets: it depends on nothing of the step but the batch, and the actor launch that
+// follows the critics' weight step then starts at the critic (actor_chain<.., AHEAD>).  Xs: the critic's input tile
+// [s, a] -- the action columns meet the zero rows that pad the actor's first-layer weights; `area`: LDS of
+// ahead_floats<R>() floats that the critic chain does not use.  Writes aH1, aH2 and api.
+template <int R>
+constexpr int ahead_floats() { return R * kLda + R * kMaxAct + kHeadRed; }
+constexpr int vec_critic_floats = kH + 8, vec_actor_floats = 8 + kH + kHeadRed;   // staged vectors of the critic / actor chain;
+                                                     // behind them: the weight stage of the 16-row transposed products
+constexpr int kAheadBase = 8 + 2 * kH + 8 + kHeadRed;   // floats behind the LDS map that the chains of the launch use for their vectors
+template <class G>
+__device__ __forceinline__ void actor_forward_ahead(const PopDev& d, int agent, int r0, const float* Xs, int xld, float* area) {
+  constexpr int R = G::R;
+  static_assert(R == 32, "built for the 32-row critic workgroups");
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  float* buf2 = area;
+  float* head = buf2 + R * kLda;
+  float* red = head + R * kMaxAct;
+  const float* an = net_ptr(d, d.theta, agent, 0);
+  typename G::Pre pa;
+  POP_MARK(56);
+  pa.load(an, d.actor, wave, lane);
+  const size_t act_off = ((size_t)agent * d.B + r0) * kH;
+  G::template first_layer<false>(Xs, xld, an, d.actor, pa, buf2, d.aH1 + act_off, wave, lane);
+  __syncthreads();
+  POP_MARK(57);
+  G::template hidden_layer<false>(buf2, an, d.actor, pa, d.aH2 + act_off, wave, lane, NoTail());
+  __syncthreads();
+  POP_MARK(58);
+  head_mfma_split<R, false>(buf2, an + d.actor.w3, d.A, head, kMaxAct, wave, lane, red);
+  __syncthreads();
+  POP_MARK(59);
+  float* out = d.api + ((size_t)agent * d.B + r0) * d.A;
+  for (int e = tid; e < R * d.A; e += kThreads) {
+    const int r = e / d.A, j = e - r * d.A;
+    out[e] = tanhf(head[r * kMaxAct + j] + an[d.actor.b3 + j]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Critic forward + backward.  One workgroup per (critic network, chunk); network = 2 agent + k.
 //   L = (1/B) sum_b (Q_k(s_b, a_b) - y_b)^2 ;  dq = 2 (q - y) / B
 //   dz2 = (dq W3^T) * [h2 > 0] ;  dz1 = (dz2 W2^T) * [h1 > 0]
@@ -647,8 +703,9 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
 // partial sums of dW3, db3, db2, db1 and of the loss.
 // WAIT: the targets come from target workgroups of the same launch; the lanes that need
 // them poll for their rows right before the loss.  SIGNAL: count this chunk as finished
-// for the weight-gradient workgroups of the same launch.
-template <class G, bool WAIT, bool SIGNAL>
+// for the weight-gradient workgroups of the same launch.  AHEAD: the workgroups of critic 2 run the actor's forward
+// pass for their rows before they wait (d.actor_ahead, steps with an actor update).
+template <class G, bool WAIT, bool SIGNAL, bool AHEAD = false>
 __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int net, int chunk, float* lds) {
   constexpr int R = G::R;
   const LdsMap<G::R, G::kPad> L(d.D);
@@ -697,6 +754,10 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
   __syncthreads();
   POP_MARK(3);
   G::thin(buf, v_w3, 1, head, tid);
+  if constexpr (AHEAD) {
+    if (k == 1 && d.actor_ahead && t % (uint32_t)d.hp[agent].policy_delay == 0u)
+      actor_forward_ahead<G>(d, agent, r0, Xs, L.xld, lds + L.vec + kAheadBase);
+  }
   if (WAIT && tid < R) yv = await_y(d, (size_t)agent * d.B + r0 + tid, t);   // same lane uses it below
   __syncthreads();
   POP_MARK(4);
@@ -737,7 +798,8 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
   POP_MARK(5);
   __syncthreads();
   POP_MARK(6);
-  G::template input_grad_to_global<SIGNAL>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane);
+  G::template input_grad_to_global<SIGNAL>(buf, cn + d.critic.w2, wt, mask1, d.cdZ1 + act_off, part + kCP_db1, wave, lane,
+                                           lds + L.vec + vec_critic_floats);
   POP_MARK(7);
   if (SIGNAL) signal_count(d.done_c + parity_base(d, t, 2 * d.P) + net, tid);
 }
@@ -755,8 +817,9 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
 // WAIT: the critic update of this step runs in the same launch; the actor's own forward
 // pass goes ahead, everything that reads critic 1 waits until all of its weight-gradient
 // workgroups are done.  SIGNAL: count this chunk as finished for the actor's weight-gradient
-// workgroups.
-template <class G, bool WAIT>
+// workgroups.  AHEAD: the forward pass was run by critic workgroups of the launch before (actor_forward_ahead): the
+// chain takes a_pi and the first layer's ReLU pattern from what they wrote and starts at the critic.
+template <class G, bool WAIT, bool AHEAD = false>
 __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int agent, int chunk, float* lds, int critic_roles) {
   constexpr int R = G::R;
   const LdsMap<G::R, G::kPad> L(d.D);
@@ -778,7 +841,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   const float* cn = net_ptr(d, d.theta, agent, 1);
   POP_MARK(8);
   typename G::Pre pre;
-  pre.load(an, d.actor, wave, lane);
+  pre.load(AHEAD ? cn : an, AHEAD ? d.critic : d.actor, wave, lane);
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   const size_t act_off = ((size_t)agent * d.B + r0) * kH;
   float* part = d.apart + ((size_t)agent * (d.B / R) + chunk) * kAPart;
@@ -787,6 +850,38 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
     stage_vector(v_cw3, cn + d.critic.w3, kH, tid);
     cb3 = cn[d.critic.b3];
   };
+  uint64_t mask_a1 = 0;
+  if constexpr (AHEAD) {
+    static_assert(!WAIT, "the forward pass ahead belongs to the separate launches");
+    // one trip to memory: the critic's head, the input tile [s, a_pi] (a_pi from the forward pass ahead), h1's pattern
+    constexpr int IT = InputTile<R>::IT;
+    SmallVec cw3;
+    float xv[IT];
+    cw3.fetch(cn + d.critic.w3, kH, tid);
+    cb3 = cn[d.critic.b3];
+    const float* ag = d.api + ((size_t)agent * d.B + r0) * A;
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int e = tid + i * kThreads;
+      const int r = e / L.xld, c = e - r * L.xld;
+      const bool in = e < R * L.xld && c < d.D;
+      const float* p = !in ? rows : c < d.O ? rows + (size_t)r * d.row + c : ag + r * A + (c - d.O);
+      const float x = *p;
+      xv[i] = in ? x : 0.0f;
+    }
+    mask_a1 = G::mask_from_global(d.aH1 + act_off, wave, lane);
+    cw3.put(v_cw3, kH, tid);
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int e = tid + i * kThreads;
+      const int r = e / L.xld, c = e - r * L.xld;
+      if (e < R * L.xld) {
+        Xs[e] = xv[i];
+        if (c >= d.O && c < d.D) api[r * kMaxAct + (c - d.O)] = xv[i];
+      }
+    }
+    __syncthreads();
+  } else {
   if (POP_ONE_TRIP && d.D <= kMaxIn) {               // one trip to memory for all of the prologue
     SmallVec ab3, cw3;
     InputTile<R> xin;
@@ -803,7 +898,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   }
   __syncthreads();
 
-  const uint64_t mask_a1 = G::template first_layer<WAIT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
+  mask_a1 = G::template first_layer<WAIT>(Xs, L.xld, an, d.actor, pre, buf, d.aH1 + act_off, wave, lane);
   __syncthreads();
   G::template hidden_layer<false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
                          [&]() { if (!WAIT) pre.load(cn, d.critic, wave, lane); });
@@ -818,6 +913,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
     Xs[r * L.xld + d.O + j] = a;
   }
   __syncthreads();
+  }
 
   // critic 1 on [s, a_pi]
   POP_MARK(9);
@@ -862,7 +958,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
 #pragma unroll
       for (int i = 0; i < R / 4; ++i)
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
-    });                                              // buf = dz1 of the critic
+    }, lds + L.vec + vec_actor_floats);              // buf = dz1 of the critic
   }
   __syncthreads();
   POP_MARK(12);
@@ -925,15 +1021,16 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   }
   __syncthreads();
   POP_MARK(13);
-  G::template input_grad_to_global<WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  G::template input_grad_to_global<WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane,
+                                         lds + L.vec + vec_actor_floats);
   POP_MARK(14);
   if (WAIT) signal_count(d.done_a + parity_base(d, t, d.P) + agent, tid);
 }
 
 // floats of staged vectors behind the LDS map of each chain
 inline int vec_target(const PopDev&) { return 8 + 2 * kH + 8 + kHeadRed; }
-inline int vec_critic(const PopDev&) { return kH + 8; }
-inline int vec_actor(const PopDev&) { return 8 + kH + kHeadRed; }
+inline int vec_critic(const PopDev&) { return vec_critic_floats; }
+inline int vec_actor(const PopDev&) { return vec_actor_floats; }
 inline int vec_act(const PopDev& d) { return kH * d.actor.out + kMaxHead; }
 constexpr int kActScratch = 2 * (kSacMaxAct / kMaxAct);   // acting: two head blocks of [32][kSacMaxAct]
 

@@ -49,7 +49,8 @@ static_assert(kSs % kMaxAct == 0 && 2 * kSs >= kMaxHead, "dz3 rows of kMaxHead f
 // operands -- the actor's head, the critics' first-layer rows of the action -- go through the matrix pipe
 // straight from global memory)
 inline int vec_sac_target(const PopDev&) { return kMaxHead + 2 * kH + 8 + kHeadRed; }
-inline int vec_sac_actor(const PopDev&) { return kMaxHead + 2 * kH + 8 + kHeadRed; }
+constexpr int vec_sac_actor_floats = kMaxHead + 2 * kH + 8 + kHeadRed;   // behind them: the weight stage of the 16-row chains
+inline int vec_sac_actor(const PopDev&) { return vec_sac_actor_floats; }
 
 // ---------------------------------------------------------------------------------------------
 // Target chain.  One workgroup per (agent, chunk).
@@ -301,7 +302,7 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
 #pragma unroll
       for (int i = 0; i < R / 4; ++i)
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
-    });                                              // buf = dz1 of critic k
+    }, lds + L.vec + vec_sac_actor_floats);          // buf = dz1 of critic k
     __syncthreads();
     if (R <= 32 && A <= 16) head_mfma_split<R <= 32 ? R : 16, true>(buf, cn[k] + d.critic.w1 + d.O * kH, A, k == 0 ? da1 : da2, kSs, wave, lane, v_cb3 + 8);
     else head_mfma_t<R>(buf, cn[k] + d.critic.w1 + d.O * kH, A, k == 0 ? da1 : da2, kSs, wave, lane);
@@ -339,7 +340,8 @@ __device__ __forceinline__ void sac_actor_chain(const PopDev& d, uint32_t t, int
   else sac_head_backward<R, kMaxHead>(buf, dz3, an + d.actor.w3, H2, d.adZ2 + act_off, part, tid);
   __syncthreads();
   POP_MARK(29);
-  G::template input_grad_to_global<false>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane);
+  G::template input_grad_to_global<false>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane,
+                                          lds + L.vec + vec_sac_actor_floats);
   POP_MARK(30);
 }
 

@@ -29,8 +29,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_critic(PopDev d, uint32_t t) {
 // only wait, before the loss, for the targets of their own rows.  Target workgroups have the
 // lower block indices: workgroups are dispatched in index order, so whatever a critic
 // workgroup waits for has already been dispatched and the wait always ends.
-// GT, GC: tile geometries of the two chains.
-template <class GT, class GC>
+// GT, GC: tile geometries of the two chains.  AHEAD: critic_chain's.
+template <class GT, class GC, bool AHEAD = false>
 __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
   int unit, chunk;
@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_
   if ((int)blockIdx.x < target_blocks) {
     if (decode_block(blockIdx.x, d.P, d.B / GT::R, unit, chunk)) target_chain<GT>(d, t, unit, chunk, lds);
   } else if (decode_block(blockIdx.x - target_blocks, 2 * d.P, d.B / GC::R, unit, chunk)) {
-    critic_chain<GC, true, false>(d, t, unit, chunk, lds);
+    critic_chain<GC, true, false, AHEAD>(d, t, unit, chunk, lds);
   }
   POP_BLOCK_TIME(kTraceTargetCritic, 1);
 }
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic(PopDev d, uint32_
 // The same for populations whose 16-row target workgroups and 32-row critic workgroups do not all get a CU at
 // once: a target workgroup goes on into critic 1 for its own 16 rows (its targets are its own, nothing waits),
 // and only critic 2 has workgroups of its own.
-template <class GC>
+template <class GC, bool AHEAD = false>
 __global__ __launch_bounds__(kThreads, 1) void k_target_critic1(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
   int agent, chunk;
@@ -58,18 +58,18 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic1(PopDev d, uint32
       critic_chain<Rows16, false, false>(d, t, 2 * agent, chunk, lds);
     }
   } else if (decode_block(blockIdx.x - target_blocks, d.P, d.B / GC::R, agent, chunk)) {
-    critic_chain<GC, true, false>(d, t, 2 * agent + 1, chunk, lds);
+    critic_chain<GC, true, false, AHEAD>(d, t, 2 * agent + 1, chunk, lds);
   }
   POP_BLOCK_TIME(kTraceTargetCritic, 1);
 }
 
-// PER_CU: workgroups per CU the register budget is set for
-template <class G, int PER_CU = 1>
+// PER_CU: workgroups per CU the register budget is set for; AHEAD: actor_chain's
+template <class G, int PER_CU = 1, bool AHEAD = false>
 __global__ __launch_bounds__(kThreads, PER_CU) void k_actor(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
   POP_BLOCK_TIME(kTraceActor, 0);
-  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, false>(d, t, agent, chunk, lds, 0);
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, false, AHEAD>(d, t, agent, chunk, lds, 0);
   POP_BLOCK_TIME(kTraceActor, 1);
 }
 
@@ -152,6 +152,9 @@ hipError_t setup_kernels() {
   POP_SET_LDS(k_target_critic<Rows16, Rows32<1>>);
   POP_SET_LDS(k_target_critic1<Rows32<1>>);
   POP_SET_LDS(k_target_critic1<Rows32<2>>);
+  POP_SET_LDS(k_target_critic1<Rows32<1>, true>);
+  POP_SET_LDS(k_target_critic<Rows16, Rows32<1>, true>);
+  POP_SET_LDS(k_actor<Rows16, 1, true>);
   POP_SET_LDS(k_target_critic<Rows32<1>, Rows32<1>>);
   POP_SET_LDS(k_target_critic<Rows32<2>, Rows32<2>>);
   POP_SET_LDS(k_act);
@@ -182,18 +185,25 @@ hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
   const int vec = vec_target(d) > vec_critic(d) ? vec_target(d) : vec_critic(d);
   if (d.rows_c1 != d.rows_c) {                       // critic 1 inside the target workgroups
     if (d.rows_t != 16 || d.rows_c1 != 16 || (d.rows_c != 32 && d.rows_c != 64)) return hipErrorInvalidValue;
-    const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = d.rows_c == 32 ? Lds<1>(d.D).bytes(vec) : Lds<2>(d.D).bytes(vec);
+    // (the 16-row critic chain stages the weights of its transposed product in LDS)
+    const size_t a = LdsMap<16, 16>(d.D).bytes(vec) + kStage16 * sizeof(float), b = d.rows_c == 32 ? Lds<1>(d.D).bytes(vec) : Lds<2>(d.D).bytes(vec);
     const dim3 grid(nt + xcd_grid(d.P, d.B / d.rows_c)), block(kThreads);
-    if (d.rows_c == 32) k_target_critic1<Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
+    if (d.actor_ahead) {
+      if (d.rows_c != 32) return hipErrorInvalidValue;
+      const size_t c = Lds<1>(d.D).bytes(kAheadBase + ahead_floats<32>());
+      k_target_critic1<Rows32<1>, true><<<grid, block, a > c ? a : c, s>>>(d, t, nt);
+    } else if (d.rows_c == 32) k_target_critic1<Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
     else k_target_critic1<Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
     return hipGetLastError();
   }
   const dim3 grid(nt + nc), block(kThreads);
   if (!(d.rows_t == 16 && (d.rows_c == 64 || d.rows_c == 32)) && !(d.rows_t == d.rows_c && (d.rows_t == 32 || d.rows_t == 64)))
     return hipErrorInvalidValue;                     // the kernel exists for these row classes only
+  if (d.actor_ahead && !(d.rows_t == 16 && d.rows_c == 32)) return hipErrorInvalidValue;
   if (d.rows_t == 16 && d.rows_c == 32) {
     const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = Lds<1>(d.D).bytes(vec);
-    k_target_critic<Rows16, Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
+    if (d.actor_ahead) k_target_critic<Rows16, Rows32<1>, true><<<grid, block, Lds<1>(d.D).bytes(kAheadBase + ahead_floats<32>()), s>>>(d, t, nt);
+    else k_target_critic<Rows16, Rows32<1>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
   } else if (d.rows_t == 16) {
     const size_t a = LdsMap<16, 16>(d.D).bytes(vec), b = Lds<2>(d.D).bytes(vec);
     k_target_critic<Rows16, Rows32<2>><<<grid, block, a > b ? a : b, s>>>(d, t, nt);
@@ -208,7 +218,10 @@ hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
 }
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_a)), block(kThreads);
-  if (d.rows_a == 16) k_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+  if (d.actor_ahead) {
+    if (d.rows_a != 16) return hipErrorInvalidValue;
+    k_actor<Rows16, 1, true><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_actor(d)) + kStage16 * sizeof(float), s>>>(d, t);
+  } else if (d.rows_a == 16) k_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_actor(d)) + kStage16 * sizeof(float), s>>>(d, t);
   else if (d.rows_a == 32 && (int)grid.x > kCUs) k_actor<Rows32<1, true>, 2><<<grid, block, Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   else if (d.rows_a == 32) k_actor<Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
   else k_actor<Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec_actor(d)), s>>>(d, t);

@@ -9,14 +9,18 @@ template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_sac_target(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
+  POP_BLOCK_TIME(kTraceTarget, 0);
   if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) sac_target_chain<G>(d, t, agent, chunk, lds);
+  POP_BLOCK_TIME(kTraceTarget, 1);
 }
 
 template <class G>
 __global__ __launch_bounds__(kThreads, 1) void k_sac_actor(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
+  POP_BLOCK_TIME(kTraceActor, 0);
   if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) sac_actor_chain<G>(d, t, agent, chunk, lds);
+  POP_BLOCK_TIME(kTraceActor, 1);
 }
 
 // Target and critic chains in one launch, as for TD3 (k_chain.hip): the critics' forward pass runs beside
@@ -25,11 +29,13 @@ template <class GT, class GC>
 __global__ __launch_bounds__(kThreads, 1) void k_sac_target_critic(PopDev d, uint32_t t, int target_blocks) {
   extern __shared__ float lds[];
   int unit, chunk;
+  POP_BLOCK_TIME(kTraceTargetCritic, 0);
   if ((int)blockIdx.x < target_blocks) {
     if (decode_block(blockIdx.x, d.P, d.B / GT::R, unit, chunk)) sac_target_chain<GT>(d, t, unit, chunk, lds);
   } else if (decode_block(blockIdx.x - target_blocks, 2 * d.P, d.B / GC::R, unit, chunk)) {
     critic_chain<GC, true, false>(d, t, unit, chunk, lds);
   }
+  POP_BLOCK_TIME(kTraceTargetCritic, 1);
 }
 
 hipError_t setup_sac_kernels() {
@@ -64,7 +70,7 @@ size_t chain_lds(const PopDev& d, int rows, int regions, int vec) {
 
 size_t sac_lds_bytes(const PopDev& d) {
   size_t m = chain_lds(d, d.rows_t, kSacScratch, vec_sac_target(d));
-  m = std::max(m, chain_lds(d, d.rows_a, kSacScratch, vec_sac_actor(d)));
+  m = std::max(m, chain_lds(d, d.rows_a, kSacScratch, vec_sac_actor(d)) + (d.rows_a == 16 ? kStage16 * sizeof(float) : 0));   // weight stage
   m = std::max(m, chain_lds(d, d.rows_c, 3, vec_critic(d)));
   m = std::max(m, Lds<1>(d.O, kActScratch).bytes(vec_act(d)));
   return m;
@@ -107,10 +113,10 @@ hipError_t launch_sac_actor(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_a)), block(kThreads);
   const int vec = vec_sac_actor(d);
   if (d.D > kMaxIn) {
-    if (d.rows_a == 16) k_sac_actor<Rows16Deep><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+    if (d.rows_a == 16) k_sac_actor<Rows16Deep><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec) + kStage16 * sizeof(float), s>>>(d, t);
     else if (d.rows_a == 32) k_sac_actor<Rows32Deep<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
     else return hipErrorInvalidValue;
-  } else if (d.rows_a == 16) k_sac_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
+  } else if (d.rows_a == 16) k_sac_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D, kSacScratch).bytes(vec) + kStage16 * sizeof(float), s>>>(d, t);
   else if (d.rows_a == 32) k_sac_actor<Rows32<1>><<<grid, block, LdsMap<32, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   else k_sac_actor<Rows32<2>><<<grid, block, LdsMap<64, 8>(d.D, kSacScratch).bytes(vec), s>>>(d, t);
   return hipGetLastError();

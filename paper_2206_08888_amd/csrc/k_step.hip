@@ -133,7 +133,7 @@ hipError_t launch_step(const PopDev& dev, uint32_t t, uint32_t launch_seq, int w
   size_t bytes = tiles;
   auto need = [&](size_t b) { if (b > bytes) bytes = b; };
   if (d.rows_a == 16) {
-    need(LdsMap<16, 16>(d.D).bytes(vec_ta));
+    need(LdsMap<16, 16>(d.D).bytes(vec_ta) + kStage16 * sizeof(float));   // with the weight stage of the 16-row actor chain
     need(Lds<2>(d.D).bytes(vec_critic(d)));
     // One workgroup per CU for small populations: the request is kept above half of a CU's LDS (the 64-row
     // critic chain alone needs 80,928 of the 81,920 bytes that would let two share).  With two per CU the actor

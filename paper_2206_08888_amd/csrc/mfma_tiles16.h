@@ -98,6 +98,80 @@ __device__ inline void gemm256_16(const float* __restrict__ Xl, int ldx, const f
   }
 }
 
+// The transposed product (backward: acc[r][k] += sum_n Z[r][n] W[k][n]) with its weight operand staged through LDS.
+// Read straight from memory, that operand is 16 rows of W per quarter of a load instruction, 16 bytes of each: every
+// 128-byte line comes through the CU's L1 twice, half used, and a 16-row product, which already asks the L1 for half
+// of its bandwidth in the forward direction, takes 7.7 us instead of 4.9.  Here a wavefront fetches its 64 rows of W
+// in double blocks of 32 n as whole lines (8 lanes x 16 bytes per row, 8 rows per instruction), parks them in an LDS
+// area of its own and reads them back in the MFMA layout.  No barrier: a wavefront reads only what it wrote itself,
+// and the LDS serves a wavefront's accesses in order.
+//   LDS layout of a double block (two of them per wavefront, kStage16 floats per workgroup): row p = c + 16 nt
+//   (holding W[64 wave + 4 c + nt][32 D ..]) at p * 32 floats, its eight 16-byte pieces rotated by p >> 1 -- the 16
+//   lanes of a quarter wavefront then hit 64 different banks in the writes (two rows of opposite parity) and in the
+//   reads (sixteen rows, one piece each).
+constexpr int kStage16Wave = 2 * 64 * 32;            // floats per wavefront: two double blocks
+constexpr int kStage16 = 4 * kStage16Wave;           // floats per workgroup (64 KB)
+struct WeightStage16 {                               // one double block on its way from memory to LDS
+  f32x4 g[8];
+  __device__ inline void load(const float* __restrict__ W, int D, int wave, int lane) {
+    const int s = lane >> 3, h = lane & 7;
+#pragma unroll
+    for (int q = 0; q < 8; ++q)                      // rows p = 8 q + s: c = 8 (q & 1) + s, nt = q >> 1
+      g[q] = *reinterpret_cast<const f32x4*>(W + (64 * wave + 4 * (8 * (q & 1) + s) + (q >> 1)) * kH + 32 * D + 4 * h);
+  }
+  __device__ inline void put(float* __restrict__ stage_wave, int D, int lane) const {
+    const int s = lane >> 3, h = lane & 7;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int p = 8 * q + s;
+      *reinterpret_cast<f32x4*>(stage_wave + (D & 1) * 2048 + p * 32 + 4 * ((h + (p >> 1)) & 7)) = g[q];
+    }
+  }
+};
+// block i (16 n) of the staged operand in the MFMA layout: w[nt][j] = W[64 wave + 4 c + nt][16 i + 4 kq + j]
+__device__ inline void staged_block16(WeightBlock16<true>& b, const float* __restrict__ stage_wave, int i, int lane) {
+  const int c = lane & 15, kq = lane >> 4;
+  const float* base = stage_wave + ((i >> 1) & 1) * 2048 + c * 32 + 4 * ((4 * (i & 1) + kq + (c >> 1)) & 7);
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt) b.w[nt] = *reinterpret_cast<const f32x4*>(base + 16 * 32 * nt);
+}
+// g0: double block 0, requested by the caller as early as it can (with double block 1 as well the chains measured
+// slower: 64 more registers held across the product before); `stage`: the workgroup's kStage16 floats; tail() runs
+// once the last double block has been requested.
+template <class Tail>
+__device__ inline void gemm256_16_staged(const float* __restrict__ Xl, int ldx, const float* __restrict__ W,
+                                         const WeightStage16& g0, float* __restrict__ stage, int wave, int lane, Acc16& acc,
+                                         Tail tail) {
+  float* sw = stage + wave * kStage16Wave;
+  WeightStage16 g[3];                                // double blocks D + 1 .. D + 3 in flight
+  WeightBlock16<true> wb[2];
+  LdsBlock16 xb[2];
+  g[0] = g0;
+  g[1].load(W, 1, wave, lane);
+  g[2].load(W, 2, wave, lane);
+  g[0].put(sw, 0, lane);
+  staged_block16(wb[0], sw, 0, lane);
+  xb[0].load(Xl, ldx, 0, lane);
+#pragma unroll
+  for (int D = 0; D < 8; ++D) {
+    if (D + 3 < 8) g[D % 3].load(W, D + 3, wave, lane);        // its registers were parked in LDS one round ago
+    if (D == 5) tail();
+    staged_block16(wb[1], sw, 2 * D + 1, lane);
+    xb[1].load(Xl, ldx, 16 * (2 * D + 1), lane);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_block16<true>(xb[0], wb[0], acc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (D + 1 < 8) {
+      g[(D + 1) % 3].put(sw, D + 1, lane);           // requested two rounds ago (the first two: at the start)
+      staged_block16(wb[0], sw, 2 * D + 2, lane);
+      xb[0].load(Xl, ldx, 16 * (2 * D + 2), lane);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_block16<true>(xb[1], wb[1], acc);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // First-layer weights for the leading 32 rows of W (two blocks), fetched ahead of time;
 // rows at or beyond the fan-in K read as zero.
 struct SmallW16 {

@@ -59,7 +59,7 @@ constexpr int64_t kAlign = 256;
 constexpr int64_t kStagingBytes = 16ll << 20;
 
 struct Layout {
-  int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, y;
+  int64_t hp, theta, target, m, v, grad, count, cursor, idx, batch, atilde, api, y;
   int64_t cH1, cdZ2, cdZ1, aH1, aH2, adZ2, adZ1, cpart, apart, losses, y_tagged, done_c, done_wc, done_a, spart, sloss, sigma, log_alpha, staging, replay, total;
   int64_t param_bytes;
 };
@@ -147,6 +147,7 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
   if (u.rows_critic1 != 0 && u.rows_critic1 != 16 && u.rows_critic1 != u.rows_critic)
     return fail(ctx, POP_EINVAL, "tuning.rows_critic1: 0, 16 or the value of rows_critic");
   if (u.half_tiles < 0 || u.half_tiles > 2) return fail(ctx, POP_EINVAL, "tuning.half_tiles: 0 (choose), 1 (off) or 2 (on)");
+  if (u.actor_ahead < 0 || u.actor_ahead > 2) return fail(ctx, POP_EINVAL, "tuning.actor_ahead: 0 (choose), 1 (off) or 2 (on)");
   return POP_OK;
 }
 
@@ -215,6 +216,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
   d.capacity = (uint64_t)c.capacity;
+  d.actor_ahead = 0;                                   // pop_create decides, once the launch structure is known
   d.share = 1;
   if (c.algo == POP_ALGO_TD3_SHARED) {
     // groups of agents whose critic gradients are summed by separate workgroups: as many as keep the partial
@@ -246,7 +248,7 @@ Layout make_ws_layout(const PopDev& d) {
   L.m = take(L.param_bytes); L.v = take(L.param_bytes); L.grad = take(L.param_bytes);
   L.count = take(P * 4); L.cursor = take(P * 4);
   L.idx = take(2 * P * B * 4); L.batch = take(2 * P * B * d.row * 4);
-  L.atilde = take(P * B * d.A * 4); L.y = take(P * B * 4);
+  L.atilde = take(P * B * d.A * 4); L.api = take(P * B * d.A * 4); L.y = take(P * B * 4);
   const int64_t act = P * B * kH * 4;
   L.cH1 = take(2 * act); L.cdZ2 = take(2 * act); L.cdZ1 = take(2 * act);
   L.aH1 = take(act); L.aH2 = take(act); L.adZ2 = take(act); L.adZ1 = take(act);
@@ -402,6 +404,17 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
     delete ctx;
     return fail(nullptr, POP_EINVAL, "tuning.rows_critic1 = 16 needs TD3, rows_target = 16 and POP_LAUNCH_TARGET_CRITIC");
   }
+  // The actor's forward pass inside the target / critic launch: where the 32-row workgroups of critic 2 stand idle
+  // beside 16-row target workgroups (their forward pass takes 12 us, the targets arrive after 27) and every workgroup
+  // of the launch has a CU of its own.
+  {
+    const bool exists = ctx->fuse == 1 && cfg->algo != POP_ALGO_SAC && d.rows_t == 16 && d.rows_c == 32 && d.rows_a == 16 && d.D <= kMaxIn;
+    if (cfg->tuning.actor_ahead == 2 && !exists) {
+      delete ctx;
+      return fail(nullptr, POP_EINVAL, "tuning.actor_ahead = 2 needs TD3 or shared critics, POP_LAUNCH_TARGET_CRITIC and rows (16, 32, 16)");
+    }
+    d.actor_ahead = cfg->tuning.actor_ahead ? (cfg->tuning.actor_ahead == 2) : (exists && tc_blocks <= kCUs);
+  }
   if (ctx->fuse >= 2 && d.rows_t == 16 && d.rows_c != 64) {   // the single launch exists for the (16, 64, 16) small class only
     delete ctx;
     return fail(nullptr, POP_EINVAL, "POP_LAUNCH_SINGLE and POP_LAUNCH_TAIL need rows (16, 64, 16) for a population this small");
@@ -426,7 +439,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   d.replay = (float*)(w + L.replay);
   d.count = (uint32_t*)(w + L.count); d.cursor = (uint32_t*)(w + L.cursor);
   d.idx = (uint32_t*)(w + L.idx); d.batch = (float*)(w + L.batch);
-  d.atilde = (float*)(w + L.atilde); d.y = (float*)(w + L.y);
+  d.atilde = (float*)(w + L.atilde); d.api = (float*)(w + L.api); d.y = (float*)(w + L.y);
   d.cH1 = (float*)(w + L.cH1); d.cdZ2 = (float*)(w + L.cdZ2); d.cdZ1 = (float*)(w + L.cdZ1);
   d.aH1 = (float*)(w + L.aH1); d.aH2 = (float*)(w + L.aH2); d.adZ2 = (float*)(w + L.adZ2);
   d.adZ1 = (float*)(w + L.adZ1);

@@ -95,6 +95,9 @@ struct PopDev {
   uint32_t* idx;               // [2][P][B]
   float* batch;                // [2][P][B][row]
   float* atilde;               // [P][B][A]
+  float* api;                  // [P][B][A] actions of the current policy on the batch, where the critic-2 workgroups of the
+                               // fused target / critic launch run the actor's forward pass ahead of the actor launch
+  int actor_ahead;             // 1: they do (small populations: those workgroups would otherwise idle until the targets arrive)
   float* y;                    // [P][B]
   // activations handed from the chain kernels to the weight-gradient kernel
   float *cH1, *cdZ2, *cdZ1;    // [P][2][B][256]

@@ -225,20 +225,26 @@ RHO_TIE = 1e-6     # a unit counts as "on its kink" below this relative margin (
 
 def explain(pass_, g_device, rho_max=RHO_TIE, limit=32, goal=1e-5):
     """Greedy search over the units nearest their kink: keep a flip if it brings the oracle's gradient closer to the
-    device's.  Returns (error before, error after, [(rho, pass, layer, row, unit)] kept, smallest rho seen)."""
+    device's; passes over the candidates are repeated while one of them still helps.  Returns (error before, error after, [(rho, pass, layer, row, unit)] kept, smallest rho seen)."""
     base = rel_l2(g_device, pass_.gradient())
     cands = candidates(pass_.passes, rho_max, limit)
     kept, err = [], base
-    for c in cands:
-        if err <= goal:
-            break
-        _, p, l, r, u = c
-        pass_.flip(p, l, r, u)
-        e = rel_l2(g_device, pass_.gradient())
-        if e < 0.7 * err:
-            kept.append(c); err = e
-        else:
+    progress = True
+    while progress and err > goal:                        # again over those left: a small flip shows once a large one is out of the way
+        progress = False
+        for c in cands:
+            if err <= goal:
+                break
+            if c in kept:
+                continue
+            _, p, l, r, u = c
             pass_.flip(p, l, r, u)
+            e = rel_l2(g_device, pass_.gradient())
+            if e < 0.7 * err:
+                kept.append(c); err = e
+                progress = True
+            else:
+                pass_.flip(p, l, r, u)
     return base, err, kept, (cands[0][0] if cands else float("inf"))
 
 

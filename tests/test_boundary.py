@@ -44,11 +44,11 @@ def test_struct_sizes_match_the_header(lib, tmp_path):
     subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
     got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert got == [C.sizeof(pp.pop_hparams), C.sizeof(pp.pop_config), C.sizeof(pp.pop_tuning),
-                   pp.pop_config.capacity.offset, pp.pop_config.tuning.offset] == [64, 72, 24, 40, 48]
+                   pp.pop_config.capacity.offset, pp.pop_config.tuning.offset] == [64, 80, 28, 40, 48]
 
 
 def test_bad_tuning_values_are_refused_before_any_gpu_work(lib):
-    for kw in (dict(launch=7), dict(launch=-1), dict(rows=(16, 16, 16)), dict(rows=48), dict(half_tiles=3), dict(rows_critic1=32)):
+    for kw in (dict(launch=7), dict(launch=-1), dict(rows=(16, 16, 16)), dict(rows=48), dict(half_tiles=3), dict(rows_critic1=32), dict(actor_ahead=3)):
         with pytest.raises(pp.PopError) as e:
             pp.pop_workspace_bytes(pp.make_config(2, 17, 6, (256, 256), 256, 100, **kw))
         assert e.value.code == pp.POP_EINVAL and "tuning" in str(e.value), kw

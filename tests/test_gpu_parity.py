@@ -379,7 +379,7 @@ def test_tile_width_is_independent_of_the_launch_structure():
     out = {}
     for half in (0, 1, 2):
         for launch in (pp.POP_LAUNCH_AUTO, pp.POP_LAUNCH_PER_PART):
-            gpu, _, _ = make_pair(2, P=4, capacity=1200, hps=hps, oracle=False, launch=launch, rows=(16, 32, 16), half_tiles=half)
+            gpu, _, _ = make_pair(2, P=4, capacity=1200, hps=hps, oracle=False, launch=launch, rows=(16, 32, 16), half_tiles=half, actor_ahead=1)
             gpu.update(3)
             out[half, launch] = {(i, w): gpu.get_params(i, w) for i in range(4) for w in STATE12}
             gpu.close()
@@ -390,6 +390,27 @@ def test_tile_width_is_independent_of_the_launch_structure():
     assert all(np.array_equal(a[k], b[k]) for k in a)       # "choose" means on at P = 4
     assert any(not np.array_equal(a[k], c[k]) for k in a)   # and full-width tiles differ ...
     assert max(rel_l2(a[k], c[k]) for k in a if c[k].any()) <= 1e-5   # ... in rounding only
+
+
+@pytest.mark.parametrize("P", [4, 10])
+def test_actor_forward_inside_the_target_critic_launch_changes_rounding_only(P):
+    """Small populations run the actor's own forward pass in the critic-2 workgroups of the target / critic launch
+    (tuning.actor_ahead; the default there), on 32-row instead of 16-row tiles: against the same steps with the
+    forward pass in the actor launch the results differ, and in the order of the fp32 sums only.  Agents with
+    different policy delays take it on their own delayed steps."""
+    hps = workloads.hparams(2, P)
+    for i, h in enumerate(hps):
+        h["policy_delay"] = 1 + i % 3
+    out = {}
+    for ahead in (0, 1, 2):
+        gpu, _, _ = make_pair(2, P=P, capacity=1200, hps=hps, oracle=False, actor_ahead=ahead)
+        gpu.update(4)
+        out[ahead] = {(i, w): gpu.get_params(i, w) for i in range(P) for w in STATE12}
+        gpu.close()
+    assert all(np.array_equal(out[0][k], out[2][k]) for k in out[0])          # "choose" means on here
+    assert any(not np.array_equal(out[1][k], out[2][k]) for k in out[1])
+    worst = max(rel_l2(out[2][k], out[1][k]) for k in out[1] if out[1][k].any())
+    assert worst <= 2e-5, worst
 
 
 def test_copy_agent_and_set_hparams_follow_the_oracle():

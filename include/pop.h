@@ -110,8 +110,8 @@ typedef struct {
                             the batch then come in two halves: compare launch structures with this set to 1. */
   int32_t actor_ahead;   /* the actor's own forward pass of a step with a policy update runs inside the target / critic
                             launch, in the 32-row workgroups of critic 2 while they wait for their Bellman targets, and
-                            the actor launch starts at the critic: 0 = choose (on where it exists and those workgroups
-                            have a CU each), 1 = off, 2 = on.  Exists for TD3 and shared critics with TARGET_CRITIC and
+                            the actor launch starts at the critic: 0 = choose (on with rows_critic1 == 16 while every
+                            workgroup of the launch has a CU of its own), 1 = off, 2 = on.  Exists for TD3 and shared critics with TARGET_CRITIC and
                             rows (16, 32, 16); POP_EINVAL for 2 elsewhere.  That pass then runs on 32-row instead of
                             16-row tiles, another order of the fp32 sums: compare launch structures with this set to 1. */
 } pop_tuning;

@@ -413,7 +413,11 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
       delete ctx;
       return fail(nullptr, POP_EINVAL, "tuning.actor_ahead = 2 needs TD3 or shared critics, POP_LAUNCH_TARGET_CRITIC and rows (16, 32, 16)");
     }
-    d.actor_ahead = cfg->tuning.actor_ahead ? (cfg->tuning.actor_ahead == 2) : (exists && tc_blocks <= kCUs);
+    // Measured (us/step, off / on): 79.0 / 77.8 at P = 10, 78.1 / 76.6 at P = 9, 73.0 / 73.1 at P = 8, 65.7 / 65.5 at
+    // P = 4: the pass takes 17 us in a 32-row workgroup and the wait it fills is 11 us long, so the launch grows by
+    // most of what the actor launch saves -- except where the target workgroups, which run critic 1 as well
+    // (rows_c1 == 16), are the longer ones anyway.
+    d.actor_ahead = cfg->tuning.actor_ahead ? (cfg->tuning.actor_ahead == 2) : (exists && d.rows_c1 == 16 && tc_blocks <= kCUs);
   }
   if (ctx->fuse >= 2 && d.rows_t == 16 && d.rows_c != 64) {   // the single launch exists for the (16, 64, 16) small class only
     delete ctx;

@@ -395,7 +395,7 @@ def test_tile_width_is_independent_of_the_launch_structure():
 @pytest.mark.parametrize("P", [4, 10])
 def test_actor_forward_inside_the_target_critic_launch_changes_rounding_only(P):
     """Small populations run the actor's own forward pass in the critic-2 workgroups of the target / critic launch
-    (tuning.actor_ahead; the default there), on 32-row instead of 16-row tiles: against the same steps with the
+    (tuning.actor_ahead; the default at 9 and 10 agents), on 32-row instead of 16-row tiles: against the same steps with the
     forward pass in the actor launch the results differ, and in the order of the fp32 sums only.  Agents with
     different policy delays take it on their own delayed steps."""
     hps = workloads.hparams(2, P)
@@ -407,7 +407,8 @@ def test_actor_forward_inside_the_target_critic_launch_changes_rounding_only(P):
         gpu.update(4)
         out[ahead] = {(i, w): gpu.get_params(i, w) for i in range(P) for w in STATE12}
         gpu.close()
-    assert all(np.array_equal(out[0][k], out[2][k]) for k in out[0])          # "choose" means on here
+    chosen = 2 if P == 10 else 1                              # "choose": on where the target workgroups run critic 1
+    assert all(np.array_equal(out[0][k], out[chosen][k]) for k in out[0])
     assert any(not np.array_equal(out[1][k], out[2][k]) for k in out[1])
     worst = max(rel_l2(out[2][k], out[1][k]) for k in out[1] if out[1][k].any())
     assert worst <= 2e-5, worst

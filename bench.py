@@ -41,8 +41,9 @@ H = 256
 ROOT = os.path.dirname(os.path.abspath(__file__))
 
 
-def kernel_flops(P, B, O, A, algo="td3"):
-    """Algorithmic FLOPs of one launch of each kernel (2 per multiply-add), whole population."""
+def kernel_flops(P, B, O, A, algo="td3", actor_ahead=False):
+    """Algorithmic FLOPs of one launch of each kernel (2 per multiply-add), whole population.  actor_ahead: the
+    actor's forward pass runs inside the target / critic launch on steps with a policy update (every second one)."""
     D = O + A
     if algo == "sac":
         return sac_kernel_flops(P, B, O, A)
@@ -57,6 +58,9 @@ def kernel_flops(P, B, O, A, algo="td3"):
         "wgrad_actor": 2 * B * H * H + 2 * B * O * H,
     }
     per_agent["target_critic"] = per_agent["target"] + per_agent["critic"]
+    if actor_ahead:
+        per_agent["target_critic"] += fwd_actor / 2
+        per_agent["actor"] -= fwd_actor
     # the whole step as one launch: average over launches with and without the delayed actor part (delay 2)
     per_agent["step_tail"] = per_agent["wgrad_critic"] + per_agent["actor"] + per_agent["wgrad_actor"]
     per_agent["step"] = (per_agent["target_critic"] + per_agent["wgrad_critic"]
@@ -215,7 +219,7 @@ def time_config(config_id, steps, warmup, repeats, torch, with_kernels=True, P=N
     secs = time_steps(pop, steps, warmup, repeats, torch)
     dt = statistics.median(secs)
     out = dict(P=P, seconds=dt, ms_per_step=1e3 * dt / steps, value=P * steps / dt,
-               repeat_ms_per_step=[1e3 * s / steps for s in secs])
+               repeat_ms_per_step=[1e3 * s / steps for s in secs], tuning=pop.tuning())
     if with_kernels:
         n = max(steps, 100)
         ms, cnt = pop.update_timed(n)
@@ -298,7 +302,7 @@ def cpu_baseline(config_id, budget_s=12.0):
 
 def analyse(res, c, steps, config_id):
     P, B, O, A = c["P"], c["batch"], c["obs_dim"], c["act_dim"]
-    flops = kernel_flops(P, B, O, A, c["algo"])
+    flops = kernel_flops(P, B, O, A, c["algo"], actor_ahead=res["tuning"]["actor_ahead"] == 2)
     nbytes = kernel_bytes(P, B, O, A, c["algo"])
     kus, per = res["kernel_us"], res["kernel_launches_per_step"]
     per_step_us = {k: (kus[k] or 0.0) * per[k] for k in kus}
@@ -407,6 +411,7 @@ def main():
         "step_frac_of_fp32_mfma_peak": an["step_frac"],
         "hbm": an["hbm"],
         "counters": an["counters"],
+        "tuning_in_force": res["tuning"],
         "kernel_avg_us": res["kernel_us"],
         "kernel_us_per_step": an["per_step_us"],
     }
@@ -417,7 +422,7 @@ def main():
                        "value": sec["value"], "unit": "agent-updates/s", "ms_per_step": sec["ms_per_step"],
                        "repeat_ms_per_step": sec["repeat_ms_per_step"],
                        "step_frac_of_fp32_mfma_peak": an2["step_frac"], "roofline": an2["roofline"], "hbm": an2["hbm"],
-                       "counters": an2["counters"], "kernel_avg_us": sec["kernel_us"]}
+                       "counters": an2["counters"], "tuning_in_force": sec["tuning"], "kernel_avg_us": sec["kernel_us"]}
     if cpu is not None:
         line["cpu_baseline"] = cpu
     print(json.dumps(line))

@@ -308,6 +308,12 @@ int pop_debug_indices(pop_ctx* ctx, int64_t* out);
 int64_t pop_step_count(const pop_ctx* ctx);
 int64_t pop_buffer_count(const pop_ctx* ctx, int32_t agent);
 
+/* The launch structure and tiling in force for this context, with every "choose" of pop_config.tuning resolved
+ * (Sec. 4.1 leaves the mapping of the population onto the device to the implementation; this is the mapping taken):
+ * launch = POP_LAUNCH_*, rows_* = batch rows per workgroup, half_tiles and actor_ahead = 1 (off) or 2 (on).  For
+ * reports and measurements; host only, no device work. */
+int pop_get_tuning(const pop_ctx* ctx, pop_tuning* out);
+
 /* Runtime options of a context. */
 enum {
   POP_OPT_WAIT_LIMIT_TICKS = 0   /* longest wait of one workgroup for another of the same launch, in 10 ns ticks

@@ -103,6 +103,7 @@ def load_library(path=None):
         "pop_buffer_count": (i64, [vp, i32]),
         "pop_sync": (C.c_int, [vp]),
         "pop_set_option": (C.c_int, [vp, i32, i64]),
+        "pop_get_tuning": (C.c_int, [vp, C.POINTER(pop_tuning)]),
         "pop_destroy": (C.c_int, [vp]),
         "pop_last_error": (C.c_char_p, [vp]),
     }
@@ -278,6 +279,13 @@ def pop_set_option(ctx, key, value):
     return _check(load_library().pop_set_option(ctx, int(key), int(value)), ctx)
 
 
+def pop_get_tuning(ctx):
+    """The tuning in force as a dict (field names of pop_tuning)."""
+    t = pop_tuning()
+    _check(load_library().pop_get_tuning(ctx, C.byref(t)), ctx)
+    return {name: int(getattr(t, name)) for name, _ in pop_tuning._fields_}
+
+
 def pop_destroy(ctx):
     return _check(load_library().pop_destroy(ctx))
 
@@ -360,6 +368,9 @@ class Population:
 
     def set_option(self, key, value):
         return pop_set_option(self.ctx, key, value)
+
+    def tuning(self):
+        return pop_get_tuning(self.ctx)
 
     def step_count(self):
         return pop_step_count(self.ctx)

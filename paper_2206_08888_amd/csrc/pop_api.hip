@@ -973,6 +973,16 @@ int pop_sync(pop_ctx* ctx) {
   return check_fault(ctx);
 }
 
+int pop_get_tuning(const pop_ctx* ctx, pop_tuning* out) {
+  if (!ctx || !out) return POP_EINVAL;
+  const PopDev& d = ctx->d;
+  out->launch = POP_LAUNCH_PER_PART + ctx->fuse;
+  out->rows_target = d.rows_t; out->rows_critic = d.rows_c; out->rows_actor = d.rows_a; out->rows_critic1 = d.rows_c1;
+  out->half_tiles = d.half_tiles ? 2 : 1;
+  out->actor_ahead = d.actor_ahead ? 2 : 1;
+  return POP_OK;
+}
+
 int pop_set_option(pop_ctx* ctx, int32_t key, int64_t value) {
   if (!ctx) return POP_EINVAL;
   switch (key) {

@@ -142,6 +142,31 @@ def test_critic1_inside_the_target_workgroups_needs_the_fused_launch():
     with pytest.raises(pp.PopError) as e:                   # TD3, target and critic chains in one launch only
         _pair("td3", 3, 17, 6, 300, rows=(16, 32, 16), rows_critic1=16, launch=pp.POP_LAUNCH_PER_PART)
     assert e.value.code == pp.POP_EINVAL
+    with pytest.raises(pp.PopError) as e:                   # the actor's forward pass ahead: in that launch only
+        _pair("td3", 3, 17, 6, 300, launch=pp.POP_LAUNCH_PER_PART, actor_ahead=2)
+    assert e.value.code == pp.POP_EINVAL
+
+
+def test_the_tuning_in_force_is_reported():
+    """pop_get_tuning resolves every "choose": the population classes of the library's own choice, and a caller's
+    fields handed back as given."""
+    def tuning(algo, P, **kw):
+        gpu = pp.Population(pp.make_config(P, 17, 6, (256, 256), 256, 64, algo=algo, **kw), workloads.hparams(2, P))
+        t = gpu.tuning()
+        gpu.close()
+        return t
+    t = tuning(pp.POP_ALGO_TD3, 10)
+    assert t == dict(launch=pp.POP_LAUNCH_TARGET_CRITIC, rows_target=16, rows_critic=32, rows_actor=16, rows_critic1=16,
+                     half_tiles=2, actor_ahead=2)
+    t = tuning(pp.POP_ALGO_TD3, 4)
+    assert (t["launch"], t["rows_critic1"], t["actor_ahead"], t["half_tiles"]) == (pp.POP_LAUNCH_TARGET_CRITIC, 32, 1, 2)
+    t = tuning(pp.POP_ALGO_TD3, 80)
+    assert t == dict(launch=pp.POP_LAUNCH_SINGLE, rows_target=32, rows_critic=32, rows_actor=32, rows_critic1=32,
+                     half_tiles=1, actor_ahead=1)
+    t = tuning(pp.POP_ALGO_TD3, 6, launch=pp.POP_LAUNCH_PER_PART, rows=(32, 64, 32), half_tiles=1)
+    assert t == dict(launch=pp.POP_LAUNCH_PER_PART, rows_target=32, rows_critic=64, rows_actor=32, rows_critic1=64,
+                     half_tiles=1, actor_ahead=1)
+    assert tuning(pp.POP_ALGO_SAC, 32)["launch"] == pp.POP_LAUNCH_PER_PART
 
 
 @pytest.mark.parametrize("launch,rows", [(pp.POP_LAUNCH_TARGET_CRITIC, None), (pp.POP_LAUNCH_SINGLE, (16, 64, 16))])

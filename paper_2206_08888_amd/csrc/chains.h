@@ -462,6 +462,14 @@ struct Rows16Deep : Rows16 {
 
 }  // namespace
 
+// Action dimensions beyond kMaxAct (up to kSacMaxAct): the chains are compiled a second time with scratch rows of
+// AS = kSacMaxAct floats -- a block of kSacMaxAct / kMaxAct of the map's [R][8] regions -- and kWideScratch regions.
+constexpr int kWideScratch = 3 * (kSacMaxAct / kMaxAct);
+constexpr int vec_target_floats(int AS) { return AS + 2 * kH + 8 + kHeadRed; }
+constexpr int vec_actor_floats_for(int AS) { return AS + kH + kHeadRed; }
+constexpr int vec_critic_floats = kH + 8, vec_actor_floats = vec_actor_floats_for(kMaxAct);   // staged vectors of the critic / actor
+                                                     // chain; behind them: the weight stage of the 16-row transposed products
+
 // Thin product with any number of outputs, eight at a time (the register budget of one pass).
 template <class G>
 __device__ inline void thin_wide(const float* Xl, const float* V, int J, float* outl, int stride, int tid) {
@@ -532,16 +540,17 @@ __device__ inline void wait_count(const PopDev& d, const uint32_t* count, uint32
 // Target chain.  One workgroup per (agent, chunk).
 //   a~ = clip(pi'(s') + clip(sigma eps, -c, c), -1, 1), eps = normal e = b A + j of stream 1
 //   y  = r + gamma (1 - d) min(Q1'(s', a~), Q2'(s', a~))
-template <class G>
+// AS: row stride of the head scratch (kMaxAct, or kSacMaxAct for action dimensions beyond kMaxAct).
+template <class G, int AS = kMaxAct>
 __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int agent, int chunk, float* lds) {
-  constexpr int R = G::R;
-  const LdsMap<G::R, G::kPad> L(d.D);
+  constexpr int R = G::R, RG = AS / kMaxAct;
+  const LdsMap<G::R, G::kPad> L(d.D, AS == kMaxAct ? 3 : kWideScratch);
   float* Xs = lds;
   float* buf = lds + L.buf;
-  float* head = lds + L.s0;
-  float* qmin = lds + L.s1;
-  float* v_ab3 = lds + L.vec;                        // [8]
-  float* v_cw3 = v_ab3 + 8;                          // [2][256]
+  float* head = lds + L.s0;                          // [R][AS]
+  float* qmin = lds + L.s(RG);
+  float* v_ab3 = lds + L.vec;                        // [AS]
+  float* v_cw3 = v_ab3 + AS;                         // [2][256]
   float* v_cb3 = v_cw3 + 2 * kH;                     // [2]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int r0 = chunk * R;
@@ -555,7 +564,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   const float* rows = batch_rows(d, t, agent) + (size_t)r0 * d.row;
   // The smoothing noise of this chunk depends on nothing the chain computes (counter RNG: agent seed, step,
   // element), so it is drawn here, while the prologue's loads are on their way, and added after the head.
-  constexpr int kNoisePerThread = (R * kMaxAct + kThreads - 1) / kThreads;
+  constexpr int kNoisePerThread = (R * AS + kThreads - 1) / kThreads;
   float noise[kNoisePerThread];
   auto draw_noise = [&]() {
 #pragma unroll
@@ -607,8 +616,8 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
   G::template hidden_layer<false>(buf, ta, d.actor, pre, nullptr, wave, lane, [&]() { pre.load(tc0, d.critic, wave, lane); });
   __syncthreads();
   POP_MARK(33);
-  if (R <= 32) head_mfma_split<R <= 32 ? R : 16, false>(buf, ta + d.actor.w3, d.A, head, kMaxAct, wave, lane, v_cb3 + 8);
-  else head_mfma<R>(buf, ta + d.actor.w3, d.A, head, kMaxAct, wave, lane);   // the head's weights straight from global memory
+  if (R <= 32 && (AS == kMaxAct || d.A <= 16)) head_mfma_split<R <= 32 ? R : 16, false>(buf, ta + d.actor.w3, d.A, head, AS, wave, lane, v_cb3 + 8);
+  else head_mfma<R>(buf, ta + d.actor.w3, d.A, head, AS, wave, lane);   // the head's weights straight from global memory
   __syncthreads();
   POP_MARK(34);
 #pragma unroll
@@ -616,7 +625,7 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
     const int e = tid + i * kThreads;
     if (e < R * d.A) {
       const int r = e / d.A, j = e - r * d.A;
-      const float mu = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
+      const float mu = tanhf(head[r * AS + j] + v_ab3[j]);
       const float at = fminf(fmaxf(mu + noise[i], -1.0f), 1.0f);
       Xs[r * L.xld + d.O + j] = at;
       d.atilde[((size_t)agent * d.B + r0 + r) * d.A + j] = at;
@@ -663,8 +672,6 @@ __device__ __forceinline__ void target_chain(const PopDev& d, uint32_t t, int ag
 // ahead_floats<R>() floats that the critic chain does not use.  Writes aH1, aH2 and api.
 template <int R>
 constexpr int ahead_floats() { return R * kLda + R * kMaxAct + kHeadRed; }
-constexpr int vec_critic_floats = kH + 8, vec_actor_floats = 8 + kH + kHeadRed;   // staged vectors of the critic / actor chain;
-                                                     // behind them: the weight stage of the 16-row transposed products
 constexpr int kAheadBase = 8 + 2 * kH + 8 + kHeadRed;   // floats behind the LDS map that the chains of the launch use for their vectors
 template <class G>
 __device__ __forceinline__ void actor_forward_ahead(const PopDev& d, int agent, int r0, const float* Xs, int xld, float* area) {
@@ -819,18 +826,20 @@ __device__ __forceinline__ void critic_chain(const PopDev& d, uint32_t t, int ne
 // workgroups are done.  SIGNAL: count this chunk as finished for the actor's weight-gradient
 // workgroups.  AHEAD: the forward pass was run by critic workgroups of the launch before (actor_forward_ahead): the
 // chain takes a_pi and the first layer's ReLU pattern from what they wrote and starts at the critic.
-template <class G, bool WAIT, bool AHEAD = false>
+// AS: row stride of the head scratch blocks, as in target_chain.
+template <class G, bool WAIT, bool AHEAD = false, int AS = kMaxAct>
 __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int agent, int chunk, float* lds, int critic_roles) {
-  constexpr int R = G::R;
-  const LdsMap<G::R, G::kPad> L(d.D);
+  constexpr int R = G::R, RG = AS / kMaxAct;
+  const LdsMap<G::R, G::kPad> L(d.D, AS == kMaxAct ? 3 : kWideScratch);
   float* Xs = lds;
   float* buf = lds + L.buf;
-  float* head = lds + L.s0;
-  float* api = lds + L.s1;
-  float* dz3 = lds + L.s2;
+  float* head = lds + L.s0;                          // three blocks of [R][AS]
+  float* api = lds + L.s(RG);
+  float* dz3 = lds + L.s(2 * RG);
   const int A = d.A;
-  float* v_ab3 = lds + L.vec;                        // [8] actor head bias
-  float* v_cw3 = v_ab3 + 8;                          // [256] critic head
+  float* v_ab3 = lds + L.vec;                        // [AS] actor head bias
+  float* v_cw3 = v_ab3 + AS;                         // [256] critic head
+  float* stage = lds + L.vec + vec_actor_floats_for(AS);   // weight stage of the 16-row transposed products
   // the actor's head and the critic's first-layer rows of the action inputs are matrix-pipe operands read
   // straight from global memory (head_mfma, head_mfma_t)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -852,7 +861,7 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   };
   uint64_t mask_a1 = 0;
   if constexpr (AHEAD) {
-    static_assert(!WAIT, "the forward pass ahead belongs to the separate launches");
+    static_assert(!WAIT && AS == kMaxAct, "the forward pass ahead belongs to the separate launches of the narrow shapes");
     // one trip to memory: the critic's head, the input tile [s, a_pi] (a_pi from the forward pass ahead), h1's pattern
     constexpr int IT = InputTile<R>::IT;
     SmallVec cw3;
@@ -903,13 +912,13 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   G::template hidden_layer<false>(buf, an, d.actor, pre, d.aH2 + act_off, wave, lane,
                          [&]() { if (!WAIT) pre.load(cn, d.critic, wave, lane); });
   __syncthreads();
-  if (R <= 32) head_mfma_split<R <= 32 ? R : 16, false>(buf, an + d.actor.w3, A, head, kMaxAct, wave, lane, v_cw3 + kH);
-  else head_mfma<R>(buf, an + d.actor.w3, A, head, kMaxAct, wave, lane);
+  if (R <= 32 && (AS == kMaxAct || A <= 16)) head_mfma_split<R <= 32 ? R : 16, false>(buf, an + d.actor.w3, A, head, AS, wave, lane, v_cw3 + kH);
+  else head_mfma<R>(buf, an + d.actor.w3, A, head, AS, wave, lane);
   __syncthreads();
   for (int e = tid; e < R * A; e += kThreads) {
     const int r = e / A, j = e - r * A;
-    const float a = tanhf(head[r * kMaxAct + j] + v_ab3[j]);
-    api[r * kMaxAct + j] = a;
+    const float a = tanhf(head[r * AS + j] + v_ab3[j]);
+    api[r * AS + j] = a;
     Xs[r * L.xld + d.O + j] = a;
   }
   __syncthreads();
@@ -958,16 +967,16 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
 #pragma unroll
       for (int i = 0; i < R / 4; ++i)
         h2r[i] = *reinterpret_cast<const f32x4*>(h2g + (4 * i + (tid >> 6)) * kH + 4 * (tid & 63));
-    }, lds + L.vec + vec_actor_floats);              // buf = dz1 of the critic
+    }, stage);                                       // buf = dz1 of the critic
   }
   __syncthreads();
   POP_MARK(12);
-  if (R <= 32) head_mfma_split<R <= 32 ? R : 16, true>(buf, cn + d.critic.w1 + d.O * kH, A, head, kMaxAct, wave, lane, v_cw3 + kH);   // da
-  else head_mfma_t<R>(buf, cn + d.critic.w1 + d.O * kH, A, head, kMaxAct, wave, lane);
+  if (R <= 32 && (AS == kMaxAct || A <= 16)) head_mfma_split<R <= 32 ? R : 16, true>(buf, cn + d.critic.w1 + d.O * kH, A, head, AS, wave, lane, v_cw3 + kH);   // da
+  else head_mfma_t<R>(buf, cn + d.critic.w1 + d.O * kH, A, head, AS, wave, lane);
   G::load_wt(wt, an + d.actor.w2, wave, lane);       // block 0 of the actor's input-gradient product
   __syncthreads();
-  for (int e = tid; e < R * kMaxAct; e += kThreads) {
-    const int j = e % kMaxAct;
+  for (int e = tid; e < R * AS; e += kThreads) {
+    const int j = e % AS;
     const float a = j < A ? api[e] : 0.0f;
     dz3[e] = j < A ? head[e] * (1.0f - a * a) : 0.0f;     // unused columns are kept at zero
   }
@@ -977,33 +986,34 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
   __syncthreads();
   if (tid < A) {
     float s = 0.0f;
-    for (int r = 0; r < R; ++r) s += dz3[r * kMaxAct + tid];
+    for (int r = 0; r < R; ++r) s += dz3[r * AS + tid];
     put<WAIT>(part + kAP_db3 + tid, s);
   }
   {                                                  // actor head backward, one thread per hidden unit
     const int c = tid;
-    float w3[kMaxAct], gw3[kMaxAct];
+    constexpr int RB = AS == kMaxAct ? 4 : 2;        // rows in flight (the wide rows cost three times the registers)
+    float w3[AS], gw3[AS];
 #pragma unroll
-    for (int j = 0; j < kMaxAct; ++j) { w3[j] = (an + d.actor.w3)[c * A + (j < A ? j : 0)]; gw3[j] = 0.0f; }
+    for (int j = 0; j < AS; ++j) { w3[j] = (an + d.actor.w3)[c * A + (j < A ? j : 0)]; gw3[j] = 0.0f; }
 #pragma unroll
-    for (int j = 0; j < kMaxAct; ++j) w3[j] = j < A ? w3[j] : 0.0f;
+    for (int j = 0; j < AS; ++j) w3[j] = j < A ? w3[j] : 0.0f;
     float gb2 = 0.0f;
     float* zg = d.adZ2 + act_off + c;
 #pragma unroll 1
-    for (int rb = 0; rb < R; rb += 4) {
-      float h[4];
-      f32x4 g[4][2];
+    for (int rb = 0; rb < R; rb += RB) {
+      float h[RB];
+      f32x4 g[RB][AS / 4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < RB; ++i) {
         h[i] = buf[(rb + i) * kLda + c];
-        g[i][0] = *reinterpret_cast<const f32x4*>(&dz3[(rb + i) * kMaxAct]);      // columns >= A hold zeros
-        g[i][1] = *reinterpret_cast<const f32x4*>(&dz3[(rb + i) * kMaxAct + 4]);
+#pragma unroll
+        for (int q = 0; q < AS / 4; ++q) g[i][q] = *reinterpret_cast<const f32x4*>(&dz3[(rb + i) * AS + 4 * q]);   // columns >= A hold zeros
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < RB; ++i) {
         float dh = 0.0f;
 #pragma unroll
-        for (int j = 0; j < kMaxAct; ++j) {
+        for (int j = 0; j < AS; ++j) {
           const float gj = g[i][j >> 2][j & 3];
           gw3[j] += h[i] * gj;
           dh += gj * w3[j];
@@ -1015,22 +1025,21 @@ __device__ __forceinline__ void actor_chain(const PopDev& d, uint32_t t, int age
       }
     }
 #pragma unroll
-    for (int j = 0; j < kMaxAct; ++j)
+    for (int j = 0; j < AS; ++j)
       if (j < A) put<WAIT>(part + kAP_dW3 + j * kH + c, gw3[j]);
     put<WAIT>(part + kAP_db2 + c, gb2);
   }
   __syncthreads();
   POP_MARK(13);
-  G::template input_grad_to_global<WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane,
-                                         lds + L.vec + vec_actor_floats);
+  G::template input_grad_to_global<WAIT>(buf, an + d.actor.w2, wt, mask_a1, d.adZ1 + act_off, part + kAP_db1, wave, lane, stage);
   POP_MARK(14);
   if (WAIT) signal_count(d.done_a + parity_base(d, t, d.P) + agent, tid);
 }
 
 // floats of staged vectors behind the LDS map of each chain
-inline int vec_target(const PopDev&) { return 8 + 2 * kH + 8 + kHeadRed; }
+inline int vec_target(const PopDev& d) { return vec_target_floats(d.A > kMaxAct ? kSacMaxAct : kMaxAct); }
 inline int vec_critic(const PopDev&) { return vec_critic_floats; }
-inline int vec_actor(const PopDev&) { return vec_actor_floats; }
+inline int vec_actor(const PopDev& d) { return vec_actor_floats_for(d.A > kMaxAct ? kSacMaxAct : kMaxAct); }
 inline int vec_act(const PopDev& d) { return kH * d.actor.out + kMaxHead; }
 constexpr int kActScratch = 2 * (kSacMaxAct / kMaxAct);   // acting: two head blocks of [32][kSacMaxAct]
 

@@ -2,16 +2,17 @@
 //   k_target, k_critic, k_actor : the three chains of an update step
 //   k_target_critic             : target and critic chains in one launch
 //   k_act                       : obs -> actor (acting, no gradient)
+#include <algorithm>
 #include "chains.h"
 
 namespace pop {
 
-template <class G>
+template <class G, int AS = kMaxAct>
 __global__ __launch_bounds__(kThreads, 1) void k_target(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
   POP_BLOCK_TIME(kTraceTarget, 0);
-  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) target_chain<G>(d, t, agent, chunk, lds);
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) target_chain<G, AS>(d, t, agent, chunk, lds);
   POP_BLOCK_TIME(kTraceTarget, 1);
 }
 
@@ -63,13 +64,13 @@ __global__ __launch_bounds__(kThreads, 1) void k_target_critic1(PopDev d, uint32
   POP_BLOCK_TIME(kTraceTargetCritic, 1);
 }
 
-// PER_CU: workgroups per CU the register budget is set for; AHEAD: actor_chain's
-template <class G, int PER_CU = 1, bool AHEAD = false>
+// PER_CU: workgroups per CU the register budget is set for; AHEAD, AS: actor_chain's
+template <class G, int PER_CU = 1, bool AHEAD = false, int AS = kMaxAct>
 __global__ __launch_bounds__(kThreads, PER_CU) void k_actor(PopDev d, uint32_t t) {
   extern __shared__ float lds[];
   int agent, chunk;
   POP_BLOCK_TIME(kTraceActor, 0);
-  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, false, AHEAD>(d, t, agent, chunk, lds, 0);
+  if (decode_block(blockIdx.x, d.P, d.B / G::R, agent, chunk)) actor_chain<G, false, AHEAD, AS>(d, t, agent, chunk, lds, 0);
   POP_BLOCK_TIME(kTraceActor, 1);
 }
 
@@ -137,6 +138,14 @@ hipError_t setup_kernels() {
   const int most = 160 * 1024;                        // whole LDS of a CU; the launches ask for what they need
 #define POP_SET_LDS(...)                                                                                   \
   if ((e = hipFuncSetAttribute((const void*)__VA_ARGS__, hipFuncAttributeMaxDynamicSharedMemorySize, most)) != hipSuccess) return e
+  POP_SET_LDS(k_target<Rows16Deep, kSacMaxAct>);
+  POP_SET_LDS(k_target<Rows32Deep<1>, kSacMaxAct>);
+  POP_SET_LDS(k_actor<Rows16Deep, 1, false, kSacMaxAct>);
+  POP_SET_LDS(k_actor<Rows32Deep<1>, 1, false, kSacMaxAct>);
+  POP_SET_LDS(k_target<Rows16Deep>);
+  POP_SET_LDS(k_target<Rows32Deep<1>>);
+  POP_SET_LDS(k_actor<Rows16Deep>);
+  POP_SET_LDS(k_actor<Rows32Deep<1>>);
   POP_SET_LDS(k_target<Rows16>);
   POP_SET_LDS(k_target<Rows32<1>>);
   POP_SET_LDS(k_target<Rows32<2>>);
@@ -164,9 +173,30 @@ hipError_t setup_kernels() {
 
 // Rows per workgroup (pop_dev.h): (target, critic, actor) = (16, 32 or 64, 16) for small
 // populations, else (32, 32, 32); (64, 64, 64) on request.
+// LDS of the largest chain workgroup of a TD3 step at these shapes (the launches below ask for what each needs)
+size_t td3_lds_bytes(const PopDev& d) {
+  auto chain = [&](int rows, int vec, bool staged, int regions) {
+    return rows == 16 ? LdsMap<16, 16>(d.D, regions).bytes(vec) + (staged ? kStage16 * sizeof(float) : 0)
+           : rows == 32 ? LdsMap<32, 8>(d.D, regions).bytes(vec) : LdsMap<64, 8>(d.D, regions).bytes(vec);
+  };
+  const int regions = d.A > kMaxAct ? kWideScratch : 3;
+  size_t m = chain(d.rows_t, vec_target(d), false, regions);
+  m = std::max(m, chain(d.rows_c, vec_critic(d), false, 3));
+  m = std::max(m, chain(d.rows_a, vec_actor(d), true, regions));
+  return std::max(m, Lds<1>(d.O, kActScratch).bytes(vec_act(d)));
+}
+
 hipError_t launch_target(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_t)), block(kThreads);
-  if (d.rows_t == 16) k_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_target(d)), s>>>(d, t);
+  if (d.A > kMaxAct) {                               // wide actions: scratch rows of kSacMaxAct floats, first layers as for wide inputs
+    if (d.rows_t == 16) k_target<Rows16Deep, kSacMaxAct><<<grid, block, LdsMap<16, 16>(d.D, kWideScratch).bytes(vec_target(d)), s>>>(d, t);
+    else if (d.rows_t == 32) k_target<Rows32Deep<1>, kSacMaxAct><<<grid, block, LdsMap<32, 8>(d.D, kWideScratch).bytes(vec_target(d)), s>>>(d, t);
+    else return hipErrorInvalidValue;
+  } else if (d.D > kMaxIn) {                         // wide inputs: pipelined first layers, 16 or 32 rows
+    if (d.rows_t == 16) k_target<Rows16Deep><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_target(d)), s>>>(d, t);
+    else if (d.rows_t == 32) k_target<Rows32Deep<1>><<<grid, block, Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
+    else return hipErrorInvalidValue;
+  } else if (d.rows_t == 16) k_target<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_target(d)), s>>>(d, t);
   else if (d.rows_t == 32) k_target<Rows32<1>><<<grid, block, Lds<1>(d.D).bytes(vec_target(d)), s>>>(d, t);
   else k_target<Rows32<2>><<<grid, block, Lds<2>(d.D).bytes(vec_target(d)), s>>>(d, t);
   return hipGetLastError();
@@ -218,7 +248,17 @@ hipError_t launch_target_critic(const PopDev& d, uint32_t t, hipStream_t s) {
 }
 hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s) {
   const dim3 grid(xcd_grid(d.P, d.B / d.rows_a)), block(kThreads);
-  if (d.actor_ahead) {
+  if (d.A > kMaxAct) {
+    if (d.actor_ahead) return hipErrorInvalidValue;
+    if (d.rows_a == 16) k_actor<Rows16Deep, 1, false, kSacMaxAct><<<grid, block, LdsMap<16, 16>(d.D, kWideScratch).bytes(vec_actor(d)) + kStage16 * sizeof(float), s>>>(d, t);
+    else if (d.rows_a == 32) k_actor<Rows32Deep<1>, 1, false, kSacMaxAct><<<grid, block, LdsMap<32, 8>(d.D, kWideScratch).bytes(vec_actor(d)), s>>>(d, t);
+    else return hipErrorInvalidValue;
+  } else if (d.D > kMaxIn) {
+    if (d.actor_ahead) return hipErrorInvalidValue;
+    if (d.rows_a == 16) k_actor<Rows16Deep><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_actor(d)) + kStage16 * sizeof(float), s>>>(d, t);
+    else if (d.rows_a == 32) k_actor<Rows32Deep<1>><<<grid, block, Lds<1>(d.D).bytes(vec_actor(d)), s>>>(d, t);
+    else return hipErrorInvalidValue;
+  } else if (d.actor_ahead) {
     if (d.rows_a != 16) return hipErrorInvalidValue;
     k_actor<Rows16, 1, true><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_actor(d)) + kStage16 * sizeof(float), s>>>(d, t);
   } else if (d.rows_a == 16) k_actor<Rows16><<<grid, block, LdsMap<16, 16>(d.D).bytes(vec_actor(d)) + kStage16 * sizeof(float), s>>>(d, t);

@@ -33,6 +33,7 @@ hipError_t launch_sac_target(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_sac_actor(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_sac_target_critic(const PopDev& d, uint32_t t, hipStream_t s);   // target + critic chains in one launch
 hipError_t setup_sac_kernels();
+size_t td3_lds_bytes(const PopDev& d);   // the same for the TD3 step's chains
 size_t sac_lds_bytes(const PopDev& d);   // largest dynamic LDS request of the SAC step's and the acting kernels
 
 // the step as one launch (k_step.hip); with_chains = 0: without the target and critic chains (launched

@@ -133,7 +133,9 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
     return fail(ctx, POP_EINVAL, "unknown algorithm %d", c->algo);
   if (c->n_hidden != 2 || c->hidden[0] != kH || c->hidden[1] != kH)
     return fail(ctx, POP_EUNSUPPORTED, "hidden layers must be {256, 256}");
-  const int max_in = c->algo == POP_ALGO_SAC ? kSacMaxIn : kMaxIn, max_act = c->algo == POP_ALGO_SAC ? kSacMaxAct : kMaxAct;
+  // first-layer fan-in: the chains with a pipelined first layer go up to kSacMaxIn, their wide scratch rows up to
+  // kSacMaxAct actions (SAC and plain TD3; the shared critics' weight step is built for the narrow shapes)
+  const int max_in = c->algo == POP_ALGO_TD3_SHARED ? kMaxIn : kSacMaxIn, max_act = c->algo == POP_ALGO_TD3_SHARED ? kMaxAct : kSacMaxAct;
   if (c->obs_dim + c->act_dim > max_in) return fail(ctx, POP_EUNSUPPORTED, "obs_dim + act_dim must be <= %d", max_in);
   if (c->act_dim > max_act) return fail(ctx, POP_EUNSUPPORTED, "act_dim must be <= %d", max_act);
   if (c->batch != 256) return fail(ctx, POP_EUNSUPPORTED, "batch must be 256");
@@ -200,10 +202,10 @@ void fill_dims(const pop_config& c, PopDev& d) {
     if (u.rows_actor) d.rows_a = u.rows_actor;
     d.rows_c1 = u.rows_critic1 == 16 ? 16 : 0;
   }
-  // Wide inputs (SAC only; kernels with a pipelined first layer): 32-row chains -- with weights of
+  // Wide inputs or (TD3) actions (kernels with a pipelined first layer): 32-row chains -- with weights of
   // 2 MB per agent, 16-row workgroups re-read them from L2 often enough to be bound by that -- except
   // for populations too small to fill the chip with them.
-  if (d.D > kMaxIn) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; d.rows_c1 = 0; }
+  if (d.D > kMaxIn || (c.algo == POP_ALGO_TD3 && d.A > kMaxAct)) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; d.rows_c1 = 0; }
   if (d.rows_c1 == 0) d.rows_c1 = d.rows_c;
   d.cstride = d.B / (d.rows_c1 < d.rows_c ? d.rows_c1 : d.rows_c);
   // Stand-alone weight-gradient launches: with fewer than two 32 x 128 tiles per CU (19 workgroups per network at
@@ -227,10 +229,9 @@ void fill_dims(const pop_config& c, PopDev& d) {
   }
 }
 
-// The SAC chains size their LDS from the shapes: refuse what one CU cannot hold.
+// The chains size their LDS from the shapes: refuse what one CU cannot hold.
 int check_fit(const PopDev& d, pop_ctx* ctx) {
-  if (d.algo != POP_ALGO_SAC) return POP_OK;
-  const size_t need = sac_lds_bytes(d);
+  const size_t need = d.algo == POP_ALGO_SAC ? sac_lds_bytes(d) : td3_lds_bytes(d);
   if (need > kLdsPerCU)
     return fail(ctx, POP_EUNSUPPORTED, "obs_dim %d, act_dim %d need %zu bytes of LDS per workgroup, %d available", d.O, d.A,
                 need, kLdsPerCU);
@@ -398,7 +399,7 @@ int pop_create(pop_ctx** out, const pop_config* cfg, const pop_hparams* hp, uint
   if (cfg->algo == POP_ALGO_SAC) ctx->fuse = (d.rows_t == 16 && d.rows_c == 32 && tc_blocks <= kCUs) ? 1 : 0;
   if (cfg->algo == POP_ALGO_TD3_SHARED) ctx->fuse = 1;   // target and critic chains together; the critic's weight step is a reduction of its own
   if (cfg->tuning.launch != POP_LAUNCH_AUTO) ctx->fuse = cfg->tuning.launch - POP_LAUNCH_PER_PART;   // 0 .. 3
-  if (d.D > kMaxIn) ctx->fuse = 0;                  // wide inputs: the chains exist as separate launches only
+  if (d.D > kMaxIn || d.A > kMaxAct) ctx->fuse = 0; // wide inputs or actions: the chains exist as separate launches only
   if (cfg->algo == POP_ALGO_TD3_SHARED && ctx->fuse > 1) ctx->fuse = 1;
   if (d.rows_c1 != d.rows_c && (ctx->fuse != 1 || cfg->algo != POP_ALGO_TD3 || d.rows_t != 16 || d.rows_c1 != 16)) {
     delete ctx;

@@ -42,10 +42,10 @@ def make_pair(config_id=0, P=None, capacity=None, fill=None, batch=None, hps=Non
     orc = None
     if oracle:
         orc = oracle_td3.Population([hps[i] for i in agents], O, A, list(cfgd["hidden"]), batch, capacity)
+    custom = obs_dim is not None or act_dim is not None     # the config's stream drawn at the given shapes
     for i in range(P):
-        for tr in workloads.transition_chunks(config_id, i, fill):
-            if obs_dim is not None or act_dim is not None:
-                raise NotImplementedError
+        chunks = [workloads.transitions(config_id, i, fill, obs_dim=O, act_dim=A, salt=1)] if custom else workloads.transition_chunks(config_id, i, fill)
+        for tr in chunks:
             gpu.insert(i, **tr)
             if oracle and i in agents:
                 orc.insert(agents.index(i), **tr)

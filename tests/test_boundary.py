@@ -87,8 +87,10 @@ def test_workspace_size_and_net_sizes(lib):
     (dict(hidden=(128, 128)), pp.POP_EUNSUPPORTED),
     (dict(hidden=(256,)), pp.POP_EUNSUPPORTED),
     (dict(batch=100), pp.POP_EUNSUPPORTED),
-    (dict(obs_dim=100), pp.POP_EUNSUPPORTED),
-    (dict(act_dim=9), pp.POP_EUNSUPPORTED),
+    (dict(obs_dim=443), pp.POP_EUNSUPPORTED),
+    (dict(act_dim=25), pp.POP_EUNSUPPORTED),
+    (dict(algo=pp.POP_ALGO_TD3_SHARED, obs_dim=100), pp.POP_EUNSUPPORTED),
+    (dict(algo=pp.POP_ALGO_TD3_SHARED, act_dim=9), pp.POP_EUNSUPPORTED),
     (dict(capacity=1 << 33), pp.POP_EUNSUPPORTED),
     (dict(algo=7), pp.POP_EINVAL),
     (dict(algo=pp.POP_ALGO_SAC, obs_dim=100, act_dim=25), pp.POP_EUNSUPPORTED),
@@ -101,6 +103,12 @@ def test_bad_configs_are_rejected(lib, kwargs, code):
         pp.pop_workspace_bytes(pp.make_config(**base))
     assert e.value.code == code
     assert pp.pop_last_error() != ""
+
+
+def test_td3_takes_the_humanoid_shapes(lib):
+    cfg = pp.make_config(2, 376, 17, (256, 256), 256, 1000)
+    assert pp.pop_net_size(cfg, pp.PARAM_CODES["actor"]) == 376 * 256 + 256 + 256 * 256 + 256 + 256 * 17 + 17
+    assert pp.pop_net_size(cfg, pp.PARAM_CODES["critic2"]) == 393 * 256 + 256 + 256 * 256 + 256 + 256 + 1
 
 
 def test_sac_takes_the_humanoid_shapes(lib):

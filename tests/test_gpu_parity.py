@@ -458,3 +458,63 @@ def test_copy_agent_and_set_hparams_follow_the_oracle():
     with pytest.raises(pp.PopError):
         gpu.set_hparams(0, dict(new0, seed=0))
     gpu.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# Wider shapes (plain TD3): Ant-v2 (obs 111, act 8: critic fan-in 119), the widest fan-in the chains take (obs 440,
+# act 8), Humanoid-v2 (obs 376, act 17: scratch rows of 24 floats, a head the split contraction does not cover) and one
+# in between (obs 40, act 10: wide scratch rows on a narrow input).  The first layers run software-pipelined (the
+# chains of the SAC Humanoid shapes), every part of the step is a launch of its own.
+WIDE = [(111, 8), (440, 8), (376, 17), (40, 10)]
+
+
+@pytest.mark.parametrize("obs_dim,act_dim", WIDE)
+def test_wide_observations_forced_single_steps_match_oracle(obs_dim, act_dim):
+    hps = workloads.hparams(1, 10)[:2]
+    gpu, orc, agents = make_pair(1, P=2, capacity=700, hps=hps, obs_dim=obs_dim, act_dim=act_dim)
+    for i in agents:
+        for w in PARAMS6:
+            assert np.array_equal(gpu.get_params(i, w), orc.get_params(i, w).astype(np.float32)), (i, w)
+    gpu.set_debug(1)
+    pairs = [(i, i) for i in agents]
+    ties, rep = [], None
+    for step in range(12):
+        force_state(gpu, orc, pairs)
+        before = snapshot(orc, agents)
+        gpu.update(1); orc.update(1)
+        rep = check_step_elementwise(gpu, orc, pairs, before, "forced step %d at obs %d, act %d" % (step, obs_dim, act_dim),
+                                     ties=ties, report=rep)
+        idx = gpu.debug("indices")
+        for i in agents:
+            assert np.array_equal(idx[i].astype(np.int64), orc.agents[i].last["idx"])
+    print("12 forced steps at obs %d, act %d: %s; %d network updates behind a ReLU tie: %s" % (obs_dim, act_dim, rep, len(ties), ties))
+    assert len(ties) <= 8
+    gpu.close()
+
+
+@pytest.mark.parametrize("obs_dim,act_dim", WIDE)
+def test_wide_observations_in_a_mid_size_population(obs_dim, act_dim):
+    """P = 20 (32-row chains): agents 0 and 19 against the oracle, the first step element by element, three more free
+    steps per tensor (Adam's first steps are sign-like: entries of the wide first layers whose gradient is within
+    rounding of zero may start the other way, which the element-wise check accounts for entry by entry and the free
+    run can only bound), and acting."""
+    hps = workloads.hparams(2, 20)
+    gpu, orc, agents = make_pair(2, P=20, capacity=400, hps=hps, agents=[0, 19], obs_dim=obs_dim, act_dim=act_dim)
+    gpu.set_debug(1)
+    pairs = list(zip(agents, range(len(agents))))
+    before = snapshot(orc, range(len(agents)))
+    gpu.update(1); orc.update(1)
+    ties = []
+    rep = check_step_elementwise(gpu, orc, pairs, before, "first step at P = 20, obs %d, act %d" % (obs_dim, act_dim), ties=ties)
+    print("first step at P = 20, obs %d, act %d: %s; ties %s" % (obs_dim, act_dim, rep, ties))
+    gpu.update(3); orc.update(3)
+    check_tensors_all(gpu, orc, pairs, PARAMS6, 1e-3, "four steps at P = 20, obs %d, act %d" % (obs_dim, act_dim), steps=4)
+    force_state(gpu, orc, pairs)                            # acting: the same actors on both sides
+    rng = np.random.default_rng(9)
+    obs = rng.standard_normal((20, 45, obs_dim)).astype(np.float32)
+    got = gpu.act(obs)
+    for i, j in pairs:
+        want = orc.agents[j].act(obs[i].astype(np.float64))
+        assert float(np.abs(got[i] - want).max()) <= 2e-5
+    gpu.close()
+

@@ -79,9 +79,8 @@ typedef struct {
  *
  * Population-wide shapes.  Supported now: algo TD3, TD3_SHARED or SAC, n_hidden == 2 with
  * hidden = {256, 256}, batch == 256 (the batch of every workload of Sec. 4.1),
- * 1 <= capacity < 2^32; TD3 and SAC: obs_dim + act_dim <= 448, act_dim <= 24 (HalfCheetah-v2 of Sec. 4.1 is
- * 17 / 6, Humanoid-v2 376 / 17); TD3_SHARED: obs_dim + act_dim <= 64, act_dim <= 8.  Anything else gives
- * POP_EUNSUPPORTED. */
+ * 1 <= capacity < 2^32; obs_dim + act_dim <= 448, act_dim <= 24 (HalfCheetah-v2 of Sec. 4.1 is 17 / 6,
+ * Humanoid-v2 376 / 17).  Anything else gives POP_EUNSUPPORTED. */
 
 /* How the kernels of an update step are launched and tiled.  All zeros (the default of a cleared pop_config) lets
  * the library choose by population size; the fields exist for measurements and for tests that compare the choices

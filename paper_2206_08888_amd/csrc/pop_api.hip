@@ -134,8 +134,8 @@ int check_config(const pop_config* c, pop_ctx* ctx) {
   if (c->n_hidden != 2 || c->hidden[0] != kH || c->hidden[1] != kH)
     return fail(ctx, POP_EUNSUPPORTED, "hidden layers must be {256, 256}");
   // first-layer fan-in: the chains with a pipelined first layer go up to kSacMaxIn, their wide scratch rows up to
-  // kSacMaxAct actions (SAC and plain TD3; the shared critics' weight step is built for the narrow shapes)
-  const int max_in = c->algo == POP_ALGO_TD3_SHARED ? kMaxIn : kSacMaxIn, max_act = c->algo == POP_ALGO_TD3_SHARED ? kMaxAct : kSacMaxAct;
+  // kSacMaxAct actions
+  const int max_in = kSacMaxIn, max_act = kSacMaxAct;
   if (c->obs_dim + c->act_dim > max_in) return fail(ctx, POP_EUNSUPPORTED, "obs_dim + act_dim must be <= %d", max_in);
   if (c->act_dim > max_act) return fail(ctx, POP_EUNSUPPORTED, "act_dim must be <= %d", max_act);
   if (c->batch != 256) return fail(ctx, POP_EUNSUPPORTED, "batch must be 256");
@@ -205,7 +205,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // Wide inputs or (TD3) actions (kernels with a pipelined first layer): 32-row chains -- with weights of
   // 2 MB per agent, 16-row workgroups re-read them from L2 often enough to be bound by that -- except
   // for populations too small to fill the chip with them.
-  if (d.D > kMaxIn || (c.algo == POP_ALGO_TD3 && d.A > kMaxAct)) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; d.rows_c1 = 0; }
+  if (d.D > kMaxIn || (c.algo != POP_ALGO_SAC && d.A > kMaxAct)) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; d.rows_c1 = 0; }
   if (d.rows_c1 == 0) d.rows_c1 = d.rows_c;
   d.cstride = d.B / (d.rows_c1 < d.rows_c ? d.rows_c1 : d.rows_c);
   // Stand-alone weight-gradient launches: with fewer than two 32 x 128 tiles per CU (19 workgroups per network at

@@ -30,10 +30,11 @@ constexpr int kH = 256;        // hidden width the kernels are specialised for
 constexpr int kLda = kH + 4;   // LDS row stride of a 256-wide activation tile: 4*odd words, so
                                // 8 lanes reading 16 B each from 8 consecutive rows hit all 32 banks
 constexpr int kThreads = 256;  // 4 wavefronts of 64 per workgroup in every compute kernel
-constexpr int kMaxIn = 64;     // TD3: largest first-layer fan-in (obs_dim + act_dim)
-constexpr int kMaxAct = 8;     // TD3: largest action dimension; also the row stride of the small LDS scratch blocks
-constexpr int kSacMaxIn = 448; // SAC: largest first-layer fan-in (the Humanoid shapes need 393)
-constexpr int kSacMaxAct = 24; // SAC: largest action dimension (Humanoid: 17) and row stride of its scratch blocks
+constexpr int kMaxIn = 64;     // narrow shapes: largest first-layer fan-in (obs_dim + act_dim) of the chains without a pipelined
+                               // first layer -- all fused launch structures are built for these
+constexpr int kMaxAct = 8;     // narrow shapes: largest action dimension; also the row stride of the small LDS scratch blocks
+constexpr int kSacMaxIn = 448; // wide shapes (SAC and plain TD3): largest first-layer fan-in (the Humanoid shapes need 393)
+constexpr int kSacMaxAct = 24; // wide shapes: largest action dimension (Humanoid: 17) and row stride of their scratch blocks
 constexpr int kCUs = 256;       // compute units of the chip
 constexpr int kLdsPerCU = 160 * 1024;   // bytes of LDS one workgroup can ask for
 constexpr int kMaxHead = 48;   // largest actor head: 2 * kSacMaxAct outputs (mean and log-std of the SAC policy)

@@ -89,8 +89,8 @@ def test_workspace_size_and_net_sizes(lib):
     (dict(batch=100), pp.POP_EUNSUPPORTED),
     (dict(obs_dim=443), pp.POP_EUNSUPPORTED),
     (dict(act_dim=25), pp.POP_EUNSUPPORTED),
-    (dict(algo=pp.POP_ALGO_TD3_SHARED, obs_dim=100), pp.POP_EUNSUPPORTED),
-    (dict(algo=pp.POP_ALGO_TD3_SHARED, act_dim=9), pp.POP_EUNSUPPORTED),
+    (dict(algo=pp.POP_ALGO_TD3_SHARED, obs_dim=443), pp.POP_EUNSUPPORTED),
+    (dict(algo=pp.POP_ALGO_TD3_SHARED, act_dim=25), pp.POP_EUNSUPPORTED),
     (dict(capacity=1 << 33), pp.POP_EUNSUPPORTED),
     (dict(algo=7), pp.POP_EINVAL),
     (dict(algo=pp.POP_ALGO_SAC, obs_dim=100, act_dim=25), pp.POP_EUNSUPPORTED),

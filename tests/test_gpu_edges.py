@@ -116,7 +116,7 @@ def test_buffers_shorter_than_a_batch_and_zero_step_calls(algo):
 
 
 def test_unsupported_shapes_are_refused_with_a_message():
-    for algo, O, A in ((pp.POP_ALGO_TD3, 441, 8), (pp.POP_ALGO_TD3, 17, 25), (pp.POP_ALGO_TD3_SHARED, 60, 6), (pp.POP_ALGO_TD3_SHARED, 17, 9),
+    for algo, O, A in ((pp.POP_ALGO_TD3, 441, 8), (pp.POP_ALGO_TD3, 17, 25), (pp.POP_ALGO_TD3_SHARED, 440, 9), (pp.POP_ALGO_TD3_SHARED, 17, 25),
                        (pp.POP_ALGO_SAC, 425, 24), (pp.POP_ALGO_SAC, 100, 25)):
         with pytest.raises(pp.PopError) as e:
             pp.Population(pp.make_config(2, O, A, (256, 256), 256, 100, algo=algo), workloads.hparams(2, 2))

@@ -23,13 +23,15 @@ def _lib():
     ensure_built()
 
 
-def make_shared_pair(P=3, capacity=1500, hps=None, oracle=True, config_id=2):
+def make_shared_pair(P=3, capacity=1500, hps=None, oracle=True, config_id=2, obs_dim=17, act_dim=6):
     hps = workloads.hparams(config_id, P) if hps is None else hps      # per-agent lr, tau, noise; one policy delay
-    cfg = pp.make_config(P, 17, 6, (256, 256), 256, capacity, algo=pp.POP_ALGO_TD3_SHARED)
+    cfg = pp.make_config(P, obs_dim, act_dim, (256, 256), 256, capacity, algo=pp.POP_ALGO_TD3_SHARED)
     gpu = pp.Population(cfg, hps)
-    orc = oracle_shared.Population(hps, 17, 6, [256, 256], 256, capacity) if oracle else None
+    orc = oracle_shared.Population(hps, obs_dim, act_dim, [256, 256], 256, capacity) if oracle else None
     for i in range(P):
-        for tr in workloads.transition_chunks(2, i, capacity):
+        chunks = (workloads.transition_chunks(2, i, capacity) if (obs_dim, act_dim) == (17, 6)
+                  else [workloads.transitions(2, i, capacity, obs_dim=obs_dim, act_dim=act_dim, salt=1)])
+        for tr in chunks:
             gpu.insert(i, **tr)
             if oracle:
                 orc.insert(i, **tr)
@@ -93,6 +95,25 @@ def test_thirty_forced_single_steps_match_oracle():
         rep = check_step_elementwise(gpu, orc, pairs, before, "forced step %d, shared critics" % step, ties=ties, report=rep)
     print("30 forced steps, shared critics: %s; %d network updates behind a ReLU tie: %s" % (rep, len(ties), ties))
     assert len(ties) <= 10
+    gpu.close()
+
+
+@pytest.mark.parametrize("obs_dim,act_dim", [(111, 8), (376, 17)])
+def test_wide_shapes_forced_single_steps_match_oracle(obs_dim, act_dim):
+    """Shared critics at the Ant and Humanoid shapes: the chains of the wide shapes, one launch per part, the critics'
+    weight step with 2 x 4 and 2 x 13 first-layer tile rows."""
+    gpu, orc = make_shared_pair(capacity=600, obs_dim=obs_dim, act_dim=act_dim)
+    gpu.set_debug(True)
+    pairs = [(i, i) for i in range(3)]
+    ties, rep = [], None
+    for step in range(8):
+        force(gpu, orc)
+        before = snapshot(orc, range(3))
+        gpu.update(1); orc.update(1)
+        rep = check_step_elementwise(gpu, orc, pairs, before, "forced step %d, shared critics, obs %d, act %d" % (step, obs_dim, act_dim),
+                                     ties=ties, report=rep)
+    print("8 forced steps, shared critics at obs %d, act %d: %s; %d network updates behind a ReLU tie: %s" % (obs_dim, act_dim, rep, len(ties), ties))
+    assert len(ties) <= 8
     gpu.close()
 
 

@@ -164,7 +164,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // product by spreading it over twice the CUs.  Else 32.  (64-row chains for all three parts, half the weight
   // traffic per row, exist as well -- tuning.rows_* = 64 -- and were the choice from 128 agents on until the 32-row
   // products learnt to issue their loads between the MFMAs: 1297 against 1278 us/step at P = 256, equal at 128.)
-  const int cls = (int64_t)c.P * (c.batch / 16) <= 256 ? 0 : 1;
+  const int cls = (int64_t)c.P * (c.batch / 16) <= kCUs ? 0 : 1;   // 16-row chains of a part get a CU each
   d.rows_t = d.rows_a = cls == 0 ? 16 : 32;
   // Beside 16 P target workgroups of 16 rows, 64-row critic chains (8 P workgroups) keep the fused
   // target/critic launch of a small population within one workgroup per CU.
@@ -177,7 +177,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // critics measure alike (98 -> 89 us/step at P = 8, 122 -> 109 at P = 12); SAC, whose steps are longer, gains
   // from the 32-row critic chains throughout (177 -> 157 us/step at P = 10 as launches of their own).
   const int64_t b16 = (int64_t)c.P * (c.batch / 16);
-  if (cls == 0 && (c.algo == POP_ALGO_SAC || 2 * b16 <= 256 || b16 + b16 / 2 > 256)) d.rows_c = 32;
+  if (cls == 0 && (c.algo == POP_ALGO_SAC || 2 * b16 <= kCUs || b16 + b16 / 2 > kCUs)) d.rows_c = 32;
   // 9 and 10 agents (24 P <= 256 < 32 P), TD3 proper, target and critic chains in one launch: the 16-row target
   // workgroups go on into critic 1 for their own rows (no hand-over, nothing waits), and only critic 2 has
   // workgroups of its own, 32 rows each: 16 P + 8 P workgroups as before, but the tail after the targets is a
@@ -187,13 +187,13 @@ void fill_dims(const pop_config& c, PopDev& d) {
   if (c.algo == POP_ALGO_TD3 && cls == 0 && (u.launch == POP_LAUNCH_AUTO || u.launch == POP_LAUNCH_TARGET_CRITIC)) {
     if (d.rows_c == 64) { d.rows_c = 32; d.rows_c1 = 16; }
     // 11 and 12 agents (20 P <= 256 < 24 P): the same with 64-row workgroups for critic 2 -- 93 against 98 us/step
-    else if (b16 + b16 / 2 > 256 && b16 + b16 / 4 <= 256) { d.rows_c = 64; d.rows_c1 = 16; }
+    else if (b16 + b16 / 2 > kCUs && b16 + b16 / 4 <= kCUs) { d.rows_c = 64; d.rows_c1 = 16; }
   }
   if (c.algo == POP_ALGO_SAC && cls == 1) {           // one launch per chain, so each takes the rows that suit it:
     // 64-row critic chains while they still fit one round of one workgroup per CU (51 against 59 us at P = 32),
     // 16-row target chains while they fit one round of two per CU (44 against 46 us); the actor chain stays at 32
-    if ((int64_t)c.P * (c.batch / 64) * 2 <= 256) d.rows_c = 64;
-    if ((int64_t)c.P * (c.batch / 16) <= 512) d.rows_t = 16;
+    if ((int64_t)c.P * (c.batch / 64) * 2 <= kCUs) d.rows_c = 64;
+    if ((int64_t)c.P * (c.batch / 16) <= 2 * kCUs) d.rows_t = 16;
   }
   // the caller's choices (measurements, tests); naming any chain's rows drops the critic-1 class unless it is named too
   if (u.rows_target || u.rows_critic || u.rows_actor || u.rows_critic1) {
@@ -205,7 +205,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // Wide inputs or (TD3) actions (kernels with a pipelined first layer): 32-row chains -- with weights of
   // 2 MB per agent, 16-row workgroups re-read them from L2 often enough to be bound by that -- except
   // for populations too small to fill the chip with them.
-  if (d.D > kMaxIn || (c.algo != POP_ALGO_SAC && d.A > kMaxAct)) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= 256 ? 16 : 32; d.rows_c = 32; d.rows_c1 = 0; }
+  if (d.D > kMaxIn || (c.algo != POP_ALGO_SAC && d.A > kMaxAct)) { d.rows_t = d.rows_a = (int64_t)c.P * (c.batch / 16) <= kCUs ? 16 : 32; d.rows_c = 32; d.rows_c1 = 0; }
   if (d.rows_c1 == 0) d.rows_c1 = d.rows_c;
   d.cstride = d.B / (d.rows_c1 < d.rows_c ? d.rows_c1 : d.rows_c);
   // Stand-alone weight-gradient launches: with fewer than two 32 x 128 tiles per CU (19 workgroups per network at
@@ -213,7 +213,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
   // half the width (37 workgroups per network) spread evenly while all of them are resident at three per CU, i.e.
   // up to 10 agents: 73 -> 69 us/step at P = 2, 81 -> 79 at P = 8, 87.8 -> 85.6 at P = 10 (93.5 -> 94.3 at P = 12).
   // The sums over the batch then come in two halves, so comparisons of launch structures bit for bit switch them off.
-  d.half_tiles = u.half_tiles ? u.half_tiles == 2 : 2 * (int64_t)c.P * 37 <= 3 * 256;
+  d.half_tiles = u.half_tiles ? u.half_tiles == 2 : 2 * (int64_t)c.P * 37 <= 3 * kCUs;
   d.actor = make_layout(d.O, c.algo == POP_ALGO_SAC ? 2 * d.A : d.A);   // SAC: mean and log-std per action
   d.critic = make_layout(d.D, 1);
   d.agent_sz = d.actor.padded + 2 * d.critic.padded;
@@ -225,7 +225,7 @@ void fill_dims(const pop_config& c, PopDev& d) {
     // launch (2 networks x groups x roles workgroups) within the 768 the chip holds at once (three per CU)
     const int roles = 16 + 2 * ((d.critic.in + 31) / 32) + 1;
     d.share = c.P;
-    d.groups = std::max(1, std::min(c.P, 768 / (2 * roles)));
+    d.groups = std::max(1, std::min(c.P, 3 * kCUs / (2 * roles)));
   }
 }
 

@@ -183,9 +183,14 @@ def build_population(config_id, torch, P=None, **tuning):
 
 
 def time_steps(pop, steps, warmup, repeats, torch):
-    """Seconds of each of `repeats` pop_update(steps) calls, after max(warmup, 20) untimed steps."""
+    """Seconds of each of `repeats` pop_update(steps) calls, after max(warmup, 20) untimed steps -- and as many more
+    as it takes to fill 100 ms, so that a short run is timed at the clocks a long one settles at."""
     pop.update(max(warmup, 20))
     pop.sync()
+    t_end = time.perf_counter() + 0.1
+    while time.perf_counter() < t_end:
+        pop.update(20)
+        pop.sync()
     out = []
     for _ in range(repeats):
         torch.cuda.synchronize()

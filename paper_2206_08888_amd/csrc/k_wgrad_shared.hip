@@ -8,18 +8,30 @@
 //   k_shared_adam: one thread per parameter adds the group partials in a fixed order and applies Adam and, on
 //     delayed steps, Polyak to the one critic pair (agent 0's blocks), with agent 0's hyperparameters.
 // No atomics: the result does not depend on scheduling.
+#include "gather.h"
 #include "launch.h"
 #include "wgrad.h"
 
 namespace pop {
 
-__global__ __launch_bounds__(kThreads, 3) void k_shared_partial(PopDev d, uint32_t t, int roles) {
+// Blocks at and beyond main_blocks gather the replay rows of step t + 1 into the other half of the batch buffer
+// (prefetch != 0), as the tail of the per-agent weight-gradient launch does.
+__global__ __launch_bounds__(kThreads, 3) void k_shared_partial(PopDev d, uint32_t t, int roles, int main_blocks, int prefetch) {
   __shared__ __attribute__((aligned(16))) float xt_lds[32 * kLda];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  // block -> (network, group, role): the roles of one (network, group) are neighbours
-  const int role = blockIdx.x % roles, ng = blockIdx.x / roles;
+  if ((int)blockIdx.x >= main_blocks) {
+    if (prefetch) {
+      const int g = blockIdx.x - main_blocks, per = gather_blocks_per_agent(d);
+      gather_block(d, t + 1u, g / per, g % per, tid);
+    }
+    return;
+  }
+  // block -> (network, group, role): the roles of one (network, group) share an XCD -- the eight row slabs of a
+  // weight matrix read the same dZ tiles of the group's agents, and find them in that XCD's L2 (numbered plainly,
+  // round-robin over the XCDs, every XCD fetched its own copy: 351 MB per launch at P = 80 against 126 MB of activations)
+  int ng, role;
+  if (!decode_block(blockIdx.x, 2 * d.groups, roles, ng, role)) return;
   const int net = ng % 2, g = ng / 2;
-  if (g >= d.groups) return;
   const NetLayout& L = d.critic;
   float* out = d.spart + ((size_t)net * d.groups + g) * L.padded;
   const int n1 = (L.in + 31) / 32;
@@ -106,9 +118,10 @@ __global__ __launch_bounds__(256) void k_shared_adam(PopDev d, uint32_t t) {
   adam_store<false>(a, r, g, (uint32_t)e, th, mo, ve, tg, gr);
 }
 
-hipError_t launch_wgrad_shared(const PopDev& d, uint32_t t, hipStream_t s) {
+hipError_t launch_wgrad_shared(const PopDev& d, uint32_t t, int prefetch_next, hipStream_t s) {
   const int roles = 16 + 2 * ((d.critic.in + 31) / 32) + 1;
-  hipLaunchKernelGGL(k_shared_partial, dim3(2 * d.groups * roles), dim3(kThreads), 0, s, d, t, roles);
+  const int main_blocks = 2 * d.groups * roles, extra = prefetch_next ? d.P * gather_blocks_per_agent(d) : 0;
+  hipLaunchKernelGGL(k_shared_partial, dim3(main_blocks + extra), dim3(kThreads), 0, s, d, t, roles, main_blocks, prefetch_next);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_shared_adam, dim3((d.critic.size + 255) / 256, 2), dim3(256), 0, s, d, t);

@@ -25,7 +25,7 @@ hipError_t launch_actor(const PopDev& d, uint32_t t, hipStream_t s);
 hipError_t launch_wgrad_adam(const PopDev& d, uint32_t t, int actor_phase, int prefetch_next, hipStream_t s);
 
 // shared critics: partial gradient sums per agent group, then Adam on the one critic pair (k_wgrad_shared.hip)
-hipError_t launch_wgrad_shared(const PopDev& d, uint32_t t, hipStream_t s);
+hipError_t launch_wgrad_shared(const PopDev& d, uint32_t t, int prefetch_next, hipStream_t s);
 
 // SAC: target chain (online actor, soft clipped double-Q target) and actor chain (k_sac.hip); the critic chain
 // and the weight-gradient launches are shared with TD3

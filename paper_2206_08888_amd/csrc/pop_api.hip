@@ -595,7 +595,11 @@ int enqueue_step(pop_ctx* ctx, Tick tick) {
     } else if (!run(POP_K_TARGET, launch_target) || !run(POP_K_CRITIC, launch_critic)) {
       return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
     }
-    if (!run(POP_K_WGRAD_CRITIC, launch_wgrad_shared)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    tick(POP_K_WGRAD_CRITIC, 0);
+    e = launch_wgrad_shared(d, t, has_next ? 1 : 0, s);
+    tick(POP_K_WGRAD_CRITIC, 1);
+    if (e != hipSuccess) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
+    if (has_next) ctx->gathered_t = ctx->t + 1;
     if (any_actor) {
       if (!run(POP_K_ACTOR, launch_actor)) return fail(ctx, POP_EHIP, "kernel launch: %s", hipGetErrorString(e));
       tick(POP_K_WGRAD_ACTOR, 0);

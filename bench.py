@@ -104,7 +104,12 @@ def kernel_bytes(P, B, O, A, algo="td3", delay=2):
       of each critic ([B, 256] floats: h1, dz2, dz1) and the batch rows read.
     wgrad_actor: the same for the actor, whose launch always carries Polyak (32 B per parameter), with its
       activations h1, h2, dz2, dz1 (h2 only as far as the head's weight gradient needs it).
-    The shared critics keep ONE critic pair: their Adam traffic does not grow with P."""
+    The shared critics keep ONE critic pair: their Adam traffic does not grow with P.
+    The chain launches, for the ratio of measured to necessary traffic (they are bound by the matrix units, not by
+    HBM): every network a chain runs read once (4 B per parameter), its columns of the batch rows read, and what
+    it leaves for the weight-gradient tiles written (target: y; critic: h1, dz2, dz1 of both critics; actor: h1, h2,
+    dz2, dz1 and the head's gradient).  target_critic and step are the sums of the parts one launch carries (step:
+    averaged over steps with and without the actor part)."""
     D, out_a = O + A, (2 * A if algo == "sac" else A)
     row = 2 * O + A + 2
     n_actor = O * H + H + H * H + H + H * out_a + out_a
@@ -112,14 +117,26 @@ def kernel_bytes(P, B, O, A, algo="td3", delay=2):
     polyak = 1.0 if algo == "sac" else 1.0 / delay
     act_critic = 2 * 3 * B * H * 4 + B * row * 4
     crit_state = 2 * n_critic * (24 + 8 * polyak)
+    shared = algo == "td3_shared"
+    nets_target = 0 if shared else 2 * n_critic             # critics beside the actor in each chain, per agent
+    nets_critic = 0 if shared else 2 * n_critic
+    nets_actor = 0 if shared else (2 if algo == "sac" else 1) * n_critic
     per = {
         "gather": 2 * B * row * 4 + B * 4,
         "wgrad_critic": act_critic + crit_state,
         "wgrad_actor": 4 * B * H * 4 + B * row * 4 + n_actor * (24 + (0 if algo == "sac" else 8)),
+        "target": 4 * (n_actor + nets_target) + B * (O + 2) * 4 + B * 4,
+        "critic": 4 * nets_critic + B * (D + 1) * 4 + 2 * 3 * B * H * 4,
+        "actor": 4 * (n_actor + nets_actor) + B * O * 4 + 4 * B * H * 4 + B * out_a * 4,
     }
     out = {k: v * P for k, v in per.items()}
-    if algo == "td3_shared":
+    if shared:                                              # one critic pair and its targets, read once per launch
         out["wgrad_critic"] = act_critic * P + crit_state
+        out["target"] += 4 * 2 * n_critic
+        out["critic"] += 4 * 2 * n_critic
+        out["actor"] += 4 * n_critic
+    out["target_critic"] = out["target"] + out["critic"]
+    out["step"] = out["target_critic"] + out["wgrad_critic"] + (out["actor"] + out["wgrad_actor"]) / delay + out["gather"]
     return out
 
 
@@ -326,7 +343,8 @@ def analyse(res, c, steps, config_id):
     if kus.get("step"):                                     # the parts run inside one launch: the launch as a whole
         tot = nbytes["wgrad_critic"] + nbytes["wgrad_actor"] / 2 + nbytes["gather"]
         gbps = (counters.get("step", {}).get("hbm_bytes_per_launch") or tot) / (kus["step"] * 1e-6) / 1e9
-        hbm["step"] = dict(algorithmic_bytes_per_launch_of_its_memory_bound_parts=tot, avg_launch_us=kus["step"],
+        hbm["step"] = dict(algorithmic_bytes_per_launch_of_its_memory_bound_parts=tot, algorithmic_bytes_per_launch=nbytes["step"],
+                           avg_launch_us=kus["step"],
                            measured_bytes_per_launch=counters.get("step", {}).get("hbm_bytes_per_launch"),
                            gbps=gbps, frac_of_hbm_peak=gbps / HBM_PEAK_GBPS)
     step_frac = res["value"] * step_flops_per_agent(B, O, A, algo=c["algo"]) / (MFMA_FP32_PEAK_TFLOPS * 1e12)

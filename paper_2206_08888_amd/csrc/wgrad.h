@@ -37,6 +37,7 @@ namespace pop {
 struct Adam {
   float lr, b1, b2, eps, inv_c1, inv_c2, tau;
   int polyak, record;
+  int through;   // another workgroup of this launch reads the updated parameters (critic 1 ahead of an actor chain)
 };
 
 struct AdamRegs { float th, m, v, tg; };
@@ -51,7 +52,8 @@ __device__ inline double ipow(double b, uint32_t n) {
   return r;
 }
 
-// THROUGH: the updated parameter is read by the actor chain of the same launch
+// THROUGH: the launch hands results from workgroup to workgroup; the updated parameter goes through to memory if
+// this network is one whose parameters the actor chain of the same launch reads (a.through)
 template <bool THROUGH = false>
 __device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uint32_t i, float* __restrict__ th,
                                   float* __restrict__ m, float* __restrict__ v, float* __restrict__ tg,
@@ -62,7 +64,8 @@ __device__ inline void adam_store(const Adam& a, const AdamRegs& r, float g, uin
   v[i] = vv;
   const float denom = __builtin_amdgcn_sqrtf(vv * a.inv_c2) + a.eps;
   const float tn = r.th - a.lr * (mm * a.inv_c1) * __builtin_amdgcn_rcpf(denom);
-  put<THROUGH>(th + i, tn);
+  if (THROUGH && a.through) put<true>(th + i, tn);
+  else th[i] = tn;
   if (a.polyak) tg[i] = (1.0f - a.tau) * r.tg + a.tau * tn;
   if (a.record) gr[i] = g;
 }
@@ -85,7 +88,7 @@ __device__ inline void adam_store4(const Adam& a, const AdamRegs4& r, const f32x
   }
   *reinterpret_cast<f32x4*>(m + i) = mm;
   *reinterpret_cast<f32x4*>(v + i) = vv;
-  if (THROUGH) {
+  if (THROUGH && a.through) {
     put2<true>(th + i, tn[0], tn[1]);
     put2<true>(th + i + 2, tn[2], tn[3]);
   } else {
@@ -177,21 +180,25 @@ __device__ __forceinline__ void weight_tile(const PopDev& d, const uint32_t* wai
   auto store_x = [&]() { xsl.store(Xl, ldx, M, m0, wave, lane); };
   WeightBlock<1, false, 1> z0;
   const float* zk = z + n0 + (size_t)kh * 128 * kH;   // this wavefront's rows of dZ
-  if (WAIT && wait_on) {                             // x and z come from a chain of this launch:
-    load_adam();                                     // the Adam operands can be on their way meanwhile
+  if (WAIT && wait_on) {                             // x and z come from a chain of this launch
+    // The counter is read before anything else is requested: a wavefront's loads come back in the order they went
+    // out, so a poll issued behind the Adam operands would only return once those 64 KB have arrived from memory,
+    // and x and z, which cannot be requested before it, one more trip later.  setup() runs under the poll's trip.
+    uint32_t seen = 0u;
+    if (tid == 0) seen = __hip_atomic_load(wait_on, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     setup();
-    if (tid == 0) wait_count(d, wait_on, want);
+    if (tid == 0) {
+      if (seen < want) wait_count(d, wait_on, want);
+      else __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
     __syncthreads();
-    load_x();
-    z0.load(zk, 0, cw, lane);
-  } else {                                           // what the product needs first goes out first
-    load_x();
-    z0.load(zk, 0, cw, lane);
-    __builtin_amdgcn_sched_barrier(0);
-    load_adam();
-    __builtin_amdgcn_sched_barrier(0);
-    setup();
   }
+  load_x();                                          // what the product needs first goes out first
+  z0.load(zk, 0, cw, lane);
+  __builtin_amdgcn_sched_barrier(0);
+  load_adam();
+  __builtin_amdgcn_sched_barrier(0);
+  if (!(WAIT && wait_on)) setup();
   __builtin_amdgcn_sched_barrier(0);
   POP_MARK(51);
   store_x();
@@ -236,6 +243,10 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
   const bool delayed_step = (t % delay) == 0u;
   if (actor_phase && !delayed_step) return;
 
+  // Only critic 1, and only on a step on which its agent's actor chain follows in this launch, has a reader of its
+  // updated parameters inside the launch: the others store plainly and leave without waiting for their stores to be
+  // acknowledged and counting in (that wait keeps a tile's slot for a trip to memory: 5 us of the 310 us a step's critic half takes at P = 80).
+  const bool feeds_actor = WAIT && !actor_phase && (unit & 1) == 0 && delayed_step;
   auto setup = [&]() {
     if (tid != 0) return;                            // read by everyone after the next barrier
     Adam a;
@@ -249,6 +260,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
     a.tau = hp.tau;
     a.polyak = (delayed_step && !(actor_phase && d.algo == 1)) ? 1 : 0;   // SAC has no target actor
     a.record = d.record_grads;
+    a.through = feeds_actor ? 1 : 0;
     *sh_adam = a;
   };
 
@@ -376,7 +388,7 @@ __device__ __forceinline__ void wgrad_roles(const PopDev& d, uint32_t t, int act
       else d.losses[(size_t)agent * 4 + (net - 1)] = loss;
     }
   }
-  if (WAIT && !actor_phase) signal_count(d.done_wc + parity_base(d, t, 2 * d.P) + unit, tid);
+  if (feeds_actor) signal_count(d.done_wc + parity_base(d, t, 2 * d.P) + unit, tid);
 }
 
 }  // namespace pop

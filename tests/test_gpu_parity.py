@@ -371,6 +371,27 @@ def test_sixty_four_row_chains_match_oracle_and_each_other():
             assert np.array_equal(states[0][key], other[key]), key
 
 
+def test_mid_size_single_launch_with_mixed_delays_equals_separate_launches():
+    """The single launch of mid-size populations (32-row chains, two workgroups per CU): only critic 1 of an agent whose
+    actor part runs on this step stores its parameters through to memory and counts in for the actor chain that waits
+    for it; with delays 2, 1 and 3 side by side every step has agents of both kinds.  Bit for bit against the
+    structures that hand over at launch boundaries, P = 40 (the single launch is the default there), 7 steps."""
+    hps = workloads.hparams(2, 40)
+    for i, hp in enumerate(hps):
+        hp["policy_delay"] = (2, 1, 3)[i % 3]
+    states = []
+    for launch in (pp.POP_LAUNCH_SINGLE, pp.POP_LAUNCH_TAIL, pp.POP_LAUNCH_TARGET_CRITIC):
+        gpu, _, _ = make_pair(2, P=40, capacity=1000, hps=hps, oracle=False, launch=launch)
+        assert gpu.tuning()["launch"] == launch and gpu.tuning()["rows_actor"] == 32
+        gpu.update(7)
+        gpu.sync()
+        states.append({(i, w): gpu.get_params(i, w) for i in range(40) for w in STATE12})
+        gpu.close()
+    for other in states[1:]:
+        for key in states[0]:
+            assert np.array_equal(states[0][key], other[key]), key
+
+
 def test_tile_width_is_independent_of_the_launch_structure():
     """Half-width weight-gradient tiles (the default up to 10 agents) sum the batch in two halves: results differ from
     full-width tiles in the last bits only, whichever launch structure runs them, and do not depend on anything but
